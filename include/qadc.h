@@ -1,0 +1,165 @@
+/*
+ * qadc.h -- C ABI of the Quick ADC hot path for AMD MI355X (gfx950).
+ *
+ * Quick ADC (Andre, Kermarrec, Le Scouarnec, ICMR'17): nearest-neighbour search
+ * over product-quantization codes with m sub-quantizers of 16 centroids each
+ * (4-bit components), per-query lookup tables whose float distances are
+ * quantized to 8-bit integers, saturating integer sums and top-R selection.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every array argument is a CALLER-OWNED DEVICE pointer (HBM), dense, in the
+ *    row-major shape written beside it.  The library keeps no pointer after a
+ *    call returns and frees nothing of the caller's.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue kernels on it and return without synchronizing; outputs are
+ *    valid once the stream has reached that point.
+ *  - Scratch memory comes from the caller: `workspace` (device, 256-byte
+ *    aligned) of at least qadc_workspace_bytes(...) bytes.  The library never
+ *    allocates device memory.  Calls that share a workspace must be ordered
+ *    on one stream.
+ *  - Return value: QADC_OK, or a negative error.  On QADC_EINVAL / QADC_ENOMEM
+ *    nothing was enqueued and the outputs are untouched.  qadc_last_error()
+ *    gives a thread-local message for the last failing call.
+ *  - Standard code layout (Fig. 2a of the paper): code i is m/2 consecutive
+ *    bytes; byte j holds component 2j in its low nibble and component 2j+1 in
+ *    its high nibble (the 0x0f mask and the 4-bit shift of Alg. 2).  8-bit
+ *    codes (ksub = 256) are m consecutive bytes.
+ *  - Top-R outputs: row q holds the R best of query q, ascending under the
+ *    total order (distance, index) -- lowest index first among equal
+ *    distances.  When fewer than R codes exist the tail is padded with index
+ *    0xFFFFFFFF and distance `nbins` (u8) or +inf (f32).
+ */
+#ifndef QADC_H
+#define QADC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QADC_OK       0
+#define QADC_EINVAL  (-1)  /* bad argument: null pointer, unsupported m / ksub / R / n ... */
+#define QADC_ENOMEM  (-2)  /* workspace too small */
+#define QADC_EHIP    (-3)  /* a HIP runtime call failed */
+
+#define QADC_MAX_R     1024  /* largest R accepted by the scans */
+#define QADC_MAX_INIT  8192  /* largest n_init accepted by qadc_quantize_luts */
+
+/* qmin_mode of qadc_quantize_luts */
+#define QADC_QMIN_PER_TABLE 0 /* bias_j = min of table j; range starts at sum_j bias_j */
+#define QADC_QMIN_GLOBAL    1 /* bias_j = min over all tables (Section 3.3, literal)  */
+
+/* variant of qadc_scan_topk */
+#define QADC_U8_4BIT    0 /* Alg. 2: 4-bit codes, uint8 tables, saturating sums      */
+#define QADC_F32_4BIT   1 /* Alg. 1: 4-bit codes, float tables, float32 sums         */
+#define QADC_F32_8BIT   2 /* Alg. 1: 8-bit codes (ksub = 256), float tables          */
+
+/* which call a workspace is for (qadc_workspace_bytes) */
+#define QADC_WS_SCAN_TOPK 0
+#define QADC_WS_QUANTIZE  1
+
+/*
+ * Tables step, Eq. (1) of the paper:
+ *     luts[q][j][i] = || y'_q^j - codebooks[j][i] ||^2 ,  y'_q = queries[q] - base[q]
+ * for j < m sub-spaces of d/m dimensions and i < ksub centroids.  Differences and
+ * their squares are summed in float64 (no norm expansion) and rounded once to float32.
+ *   codebooks [m][ksub][d/m] f32   ksub in {16, 256}; d % m == 0
+ *   queries   [nq][d] f32
+ *   base      [nq][d] f32 or NULL   (NULL: exhaustive search, y' = y;  else the
+ *             centroid of the probed cell, Section 2.3 "Index")
+ *   luts      [nq][m][ksub] f32     (output)
+ */
+int qadc_build_luts(const float *codebooks, int d, int m, int ksub,
+                    const float *queries, const float *base, int nq,
+                    float *luts, void *stream);
+
+/*
+ * Quantization of the tables, Section 3.3.  For each query q:
+ *   qmax   = the min(R, n_init)-th smallest float ADC distance (Eq. (2), float32,
+ *            increasing j) of the n_init codes `init_codes`, or qmax_in[q] when
+ *            init_codes is NULL;
+ *   bias_j = min_i,g luts[q][g][j][i]  (PER_TABLE)  or  min over all j too (GLOBAL);
+ *   qmin   = sum_j bias_j in increasing j (PER_TABLE)  or  the global minimum (GLOBAL);
+ *   delta  = (qmax - qmin) / nbins, replaced by 1 when not > 0;
+ *   qluts[q][g][j][i] = min(nbins, floor(max(0, luts[q][g][j][i] - bias_j) / delta))
+ * all in float32 with a correctly rounded division.
+ *   luts       [nq][ngroup][m][16] f32   ngroup table sets per query share one
+ *              quantizer (1 for exhaustive search; one per probed cell otherwise)
+ *   init_codes [n_init][m/2] u8, standard layout, scanned with table set 0 of each
+ *              query; nullable.  n_init <= QADC_MAX_INIT.
+ *   qmax_in    [nq] f32, read only when init_codes is NULL (then required)
+ *   nbins      1..255: number of bins n; also the saturation value (255 for
+ *              unsigned bytes, 127 for the paper's signed bytes)
+ *   qluts      [nq][ngroup][m][16] u8    (output)
+ *   bias       [nq][m] f32               (output, nullable)
+ *   delta      [nq] f32                  (output, nullable)
+ *   qmax_out   [nq] f32                  (output, nullable)
+ */
+int qadc_quantize_luts(const float *luts, int nq, int ngroup, int m,
+                       const uint8_t *init_codes, int64_t n_init, const float *qmax_in,
+                       int R, int nbins, int qmin_mode,
+                       uint8_t *qluts, float *bias, float *delta, float *qmax_out,
+                       void *stream);
+
+/*
+ * Scan step + top-R (Alg. 1 / Alg. 2).  For every query q and code i < n:
+ *   QADC_U8_4BIT   dist = min(nbins, sum_j luts_u8[q][j][c_i[j]])   (equal to the chain of
+ *                  saturating adds of Alg. 2, entries being non-negative)
+ *   QADC_F32_4BIT  dist = sum_j luts_f32[q][j][c_i[j]], float32, increasing j (Eq. (2))
+ *   QADC_F32_8BIT  same with one byte per component and 256-entry tables
+ * and the R smallest (dist, i) are written in ascending order.
+ *   codes    [n][m/2] u8 (4-bit variants) or [n][m] u8 (8-bit), standard layout
+ *   m        4-bit variants: 8, 16, 32 or 64;  8-bit variant: 4, 8, 16 or 32
+ *   luts     [nq][m][16] u8, [nq][m][16] f32 or [nq][m][256] f32 by variant
+ *   nbins    saturation value of the u8 variant (1..255); ignored otherwise
+ *   R        1..QADC_MAX_R
+ *   out_idx  [nq][R] u32   position i of the code in `codes`
+ *   out_dist [nq][R] u8 or f32 by variant
+ *   workspace  >= qadc_workspace_bytes(QADC_WS_SCAN_TOPK, n, m, nq, R)
+ */
+int qadc_scan_topk(int variant, const void *codes, int64_t n, int m,
+                   const void *luts, int nq, int R, int nbins,
+                   uint32_t *out_idx, void *out_dist,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Database side, Section 2.1: enc(x) = (i_0 .. i_{m-1}), i_j = index of the centroid of
+ * sub-quantizer j closest to sub-vector x^j (float32 distances from the differences,
+ * ties to the lowest index), written in the standard layout.  Not on the query
+ * path; it exists to build large databases directly in HBM.
+ *   codebooks [m][ksub][d/m] f32, ksub in {16, 256} (m even when ksub == 16)
+ *   x         [n][d] f32
+ *   codes     [n][m/2] u8 (ksub 16) or [n][m] u8 (ksub 256)   (output)
+ */
+int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *x, int64_t n,
+                   uint8_t *codes, void *stream);
+
+/*
+ * Per-kernel timing for benchmarks (the paper reports Index / Tables / Scan times
+ * separately, Section 4.3).  While enabled, the library brackets the kernels named
+ * below with HIP events on the caller's stream; qadc_profile_read waits for the
+ * recorded events and returns the summed duration and the number of launches since
+ * profiling was enabled.  Process-wide state, not thread-safe; host pointers.
+ */
+#define QADC_PROF_SCAN   0  /* code-streaming kernel of qadc_scan_topk */
+#define QADC_PROF_MERGE  1  /* cross-workgroup top-R kernel of qadc_scan_topk */
+#define QADC_PROF_COUNT  2
+int qadc_profile_enable(int on);
+int qadc_profile_read(int which, double *total_ms, int64_t *launches);
+
+/* Bytes of workspace a call needs (0 when it needs none, or on bad arguments). */
+size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R);
+
+/* Message of the last failing call on this thread ("" when none). */
+const char *qadc_last_error(void);
+
+/* Library version string. */
+const char *qadc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QADC_H */

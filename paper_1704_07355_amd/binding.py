@@ -1,0 +1,182 @@
+"""Thin ctypes binding of libqadc.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/qadc.h) and
+takes torch tensors that live on the GPU; torch is used for device memory and
+for the current HIP stream, nothing else.  There is no fallback: if the HIP
+library is missing or a call fails, an exception is raised.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libqadc.so")
+
+QADC_OK, QADC_EINVAL, QADC_ENOMEM, QADC_EHIP = 0, -1, -2, -3
+QADC_MAX_R = 1024
+QADC_MAX_INIT = 8192
+QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
+QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
+QADC_WS_SCAN_TOPK, QADC_WS_QUANTIZE = 0, 1
+QADC_PROF_SCAN, QADC_PROF_MERGE = 0, 1
+
+EXPORTS = (
+    "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_pq_encode",
+    "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes",
+    "qadc_last_error", "qadc_version",
+)
+
+_lib = None
+
+
+class QadcError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"qadc error {code}: {msg}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libqadc.so (built in-tree by paper_1704_07355_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            raise ImportError(f"{_SO} not found: run `python -m paper_1704_07355_amd.build` first")
+        L = ctypes.CDLL(_SO)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+        L.qadc_build_luts.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, vp]
+        L.qadc_build_luts.restype = i32
+        L.qadc_quantize_luts.argtypes = [vp, i32, i32, i32, vp, i64, vp, i32, i32, i32,
+                                         vp, vp, vp, vp, vp]
+        L.qadc_quantize_luts.restype = i32
+        L.qadc_scan_topk.argtypes = [i32, vp, i64, i32, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.qadc_scan_topk.restype = i32
+        L.qadc_pq_encode.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp]
+        L.qadc_pq_encode.restype = i32
+        L.qadc_profile_enable.argtypes = [i32]
+        L.qadc_profile_enable.restype = i32
+        L.qadc_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        L.qadc_profile_read.restype = i32
+        L.qadc_workspace_bytes.argtypes = [i32, i64, i32, i32, i32]
+        L.qadc_workspace_bytes.restype = sz
+        L.qadc_last_error.restype = ctypes.c_char_p
+        L.qadc_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensor must be a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int):
+    if rc != QADC_OK:
+        raise QadcError(rc, lib().qadc_last_error().decode())
+
+
+def qadc_version() -> str:
+    return lib().qadc_version().decode()
+
+
+def qadc_last_error() -> str:
+    return lib().qadc_last_error().decode()
+
+
+def qadc_workspace_bytes(call: int, n: int, m: int, nq: int, R: int) -> int:
+    return int(lib().qadc_workspace_bytes(call, n, m, nq, R))
+
+
+def qadc_build_luts(codebooks, queries, base=None, out=None):
+    """codebooks f32 [m][ksub][dsub], queries f32 [nq][d], base f32 [nq][d] | None -> f32 [nq][m][ksub]."""
+    m, ksub, dsub = codebooks.shape
+    nq, d = queries.shape
+    if out is None:
+        out = torch.empty((nq, m, ksub), dtype=torch.float32, device=queries.device)
+    _check(lib().qadc_build_luts(_ptr(codebooks, torch.float32), d, m, ksub,
+                                 _ptr(queries, torch.float32), _ptr(base, torch.float32), nq,
+                                 _ptr(out, torch.float32), _stream()))
+    return out
+
+
+def qadc_quantize_luts(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_TABLE, qmax_in=None):
+    """luts f32 [nq][m][16] or [nq][ngroup][m][16]; init_codes u8 [n_init][m/2] | None.
+
+    Returns (qluts u8 like luts, bias f32 [nq][m], delta f32 [nq], qmax f32 [nq]).
+    """
+    if luts.dim() == 3:
+        nq, m, k = luts.shape
+        ngroup = 1
+    else:
+        nq, ngroup, m, k = luts.shape
+    if k != 16:
+        raise ValueError("quantized tables need 16-entry (4-bit) tables")
+    dev = luts.device
+    qluts = torch.empty(luts.shape, dtype=torch.uint8, device=dev)
+    bias = torch.empty((nq, m), dtype=torch.float32, device=dev)
+    delta = torch.empty((nq,), dtype=torch.float32, device=dev)
+    qmax = torch.empty((nq,), dtype=torch.float32, device=dev)
+    n_init = 0 if init_codes is None else init_codes.shape[0]
+    _check(lib().qadc_quantize_luts(_ptr(luts, torch.float32), nq, ngroup, m,
+                                    _ptr(init_codes, torch.uint8), n_init,
+                                    _ptr(qmax_in, torch.float32), R, nbins, qmin_mode,
+                                    _ptr(qluts), _ptr(bias), _ptr(delta), _ptr(qmax), _stream()))
+    return qluts, bias, delta, qmax
+
+
+def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=None, out_dist=None,
+                   n=None):
+    """codes u8 [n][row]; luts [nq][m][ksub] (u8 or f32 by variant) -> (idx i64-viewable u32 [nq][R], dist)."""
+    nq, m, ksub = luts.shape
+    if n is None:
+        n = codes.shape[0]
+    dev = luts.device
+    want = torch.uint8 if variant == QADC_U8_4BIT else torch.float32
+    if luts.dtype != want:
+        raise ValueError(f"variant {variant} needs {want} tables")
+    if out_idx is None:
+        out_idx = torch.empty((nq, R), dtype=torch.int32, device=dev)  # bit pattern of uint32
+    if out_dist is None:
+        out_dist = torch.empty((nq, R), dtype=want, device=dev)
+    need = qadc_workspace_bytes(QADC_WS_SCAN_TOPK, n, m, nq, R)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=dev)
+    _check(lib().qadc_scan_topk(variant, _ptr(codes, torch.uint8), n, m, _ptr(luts), nq, R, nbins,
+                                _ptr(out_idx), _ptr(out_dist), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream()))
+    return out_idx, out_dist
+
+
+def qadc_pq_encode(codebooks, x, out=None):
+    """codebooks f32 [m][ksub][dsub], x f32 [n][d] -> codes u8 [n][m/2] (ksub 16) or [n][m] (ksub 256)."""
+    m, ksub, dsub = codebooks.shape
+    n, d = x.shape
+    row = m // 2 if ksub == 16 else m
+    if out is None:
+        out = torch.empty((n, row), dtype=torch.uint8, device=x.device)
+    _check(lib().qadc_pq_encode(_ptr(codebooks, torch.float32), d, m, ksub, _ptr(x, torch.float32),
+                                n, _ptr(out, torch.uint8), _stream()))
+    return out
+
+
+def qadc_profile_enable(on: bool) -> None:
+    _check(lib().qadc_profile_enable(1 if on else 0))
+
+
+def qadc_profile_read(which: int):
+    """-> (total milliseconds, launches) of the named kernel since profiling was enabled."""
+    ms, cnt = ctypes.c_double(0), ctypes.c_int64(0)
+    _check(lib().qadc_profile_read(which, ctypes.byref(ms), ctypes.byref(cnt)))
+    return ms.value, cnt.value

@@ -1,0 +1,92 @@
+// extern "C" boundary of the library: argument checks and dispatch only.
+// Every step of the path runs in the kernels of the other translation units.
+
+#include "qadc_common.h"
+#include "qadc_profile.h"
+
+namespace qadc {
+
+char *err_buf()
+{
+    static thread_local char buf[512] = "";
+    return buf;
+}
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(err_buf(), 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int build_luts(const float *, int, int, int, const float *, const float *, int, float *, hipStream_t);
+int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
+                  int, uint8_t *, float *, float *, float *, hipStream_t);
+int scan_topk_u8(const uint8_t *, int64_t, int, const uint8_t *, int, int, int, uint32_t *,
+                 uint8_t *, void *, size_t, hipStream_t);
+size_t scan_topk_u8_workspace(int64_t, int, int, int);
+int pq_encode(const float *, int, int, int, const float *, int64_t, uint8_t *, hipStream_t);
+
+}  // namespace qadc
+
+extern "C" {
+
+int qadc_build_luts(const float *codebooks, int d, int m, int ksub, const float *queries,
+                    const float *base, int nq, float *luts, void *stream)
+{
+    return qadc::build_luts(codebooks, d, m, ksub, queries, base, nq, luts, (hipStream_t)stream);
+}
+
+int qadc_quantize_luts(const float *luts, int nq, int ngroup, int m, const uint8_t *init_codes,
+                       int64_t n_init, const float *qmax_in, int R, int nbins, int qmin_mode,
+                       uint8_t *qluts, float *bias, float *delta, float *qmax_out, void *stream)
+{
+    return qadc::quantize_luts(luts, nq, ngroup, m, init_codes, n_init, qmax_in, R, nbins,
+                               qmin_mode, qluts, bias, delta, qmax_out, (hipStream_t)stream);
+}
+
+int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void *luts, int nq,
+                   int R, int nbins, uint32_t *out_idx, void *out_dist, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    if (!luts || !out_idx || !out_dist || (!codes && n > 0))
+        return qadc::fail(QADC_EINVAL, "qadc_scan_topk: null pointer");
+    if (nq == 0) return QADC_OK;
+    switch (variant) {
+    case QADC_U8_4BIT:
+        return qadc::scan_topk_u8((const uint8_t *)codes, n, m, (const uint8_t *)luts, nq, R, nbins,
+                                  out_idx, (uint8_t *)out_dist, workspace, workspace_bytes,
+                                  (hipStream_t)stream);
+    default:
+        return qadc::fail(QADC_EINVAL, "qadc_scan_topk: unknown variant %d", variant);
+    }
+}
+
+int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *x, int64_t n,
+                   uint8_t *codes, void *stream)
+{
+    return qadc::pq_encode(codebooks, d, m, ksub, x, n, codes, (hipStream_t)stream);
+}
+
+int qadc_profile_enable(int on) { return qadc::profile_enable(on); }
+
+int qadc_profile_read(int which, double *total_ms, int64_t *launches)
+{
+    return qadc::profile_read(which, total_ms, launches);
+}
+
+size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)
+{
+    switch (call) {
+    case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(n, m, nq, R);
+    default: return 0;
+    }
+}
+
+const char *qadc_last_error(void) { return qadc::err_buf(); }
+
+const char *qadc_version(void) { return "qadc-gfx950 0.1"; }
+
+}  // extern "C"

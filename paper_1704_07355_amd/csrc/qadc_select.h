@@ -1,0 +1,72 @@
+// Workgroup-level exact selection: the r-th smallest key of a list by radix
+// select (one 256-bin histogram pass per key byte, most significant first).
+// Keys are unsigned integers whose order is the wanted order; for the scans a
+// key is (distance << index_bits) | index, so the r-th smallest key is the r-th
+// neighbour under the total order (distance, index) and keys are unique.
+#pragma once
+
+#include "qadc_common.h"
+
+namespace qadc {
+
+struct SelectScratch {
+    unsigned hist[256];
+    unsigned bin;
+    unsigned need;
+};
+
+// Scan of a 256-bin histogram by the first wave: finds the bin holding the
+// `need`-th smallest element (1-based) and the rank of that element inside the bin.
+__device__ __forceinline__ void select_bin(SelectScratch *sc, unsigned need)
+{
+    if (threadIdx.x < WAVE) {
+        const int l = lane_id();
+        unsigned h0 = sc->hist[4 * l + 0], h1 = sc->hist[4 * l + 1];
+        unsigned h2 = sc->hist[4 * l + 2], h3 = sc->hist[4 * l + 3];
+        unsigned tot = h0 + h1 + h2 + h3;
+        unsigned inc = tot;
+#pragma unroll
+        for (int d = 1; d < WAVE; d <<= 1) {
+            unsigned up = __shfl_up(inc, d);
+            if (l >= d) inc += up;
+        }
+        unsigned excl = inc - tot;
+        unsigned h[4] = {h0, h1, h2, h3};
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (excl < need && need <= excl + h[b]) {
+                sc->bin = 4 * l + b;
+                sc->need = need - excl;
+            }
+            excl += h[b];
+        }
+    }
+}
+
+// The `need`-th smallest (1-based, need <= cnt) of keys[0..cnt).  `keys` may be
+// in LDS or in global memory.  Every thread of the workgroup must call this with
+// the same arguments; every thread gets the result.  NBYTES = number of key
+// bytes that can be non-zero.
+template <typename K, int NBYTES>
+__device__ K block_radix_select(const K *keys, unsigned cnt, unsigned need, SelectScratch *sc)
+{
+    K prefix = 0, mask = 0;
+    for (int shift = (NBYTES - 1) * 8; shift >= 0; shift -= 8) {
+        for (unsigned i = threadIdx.x; i < 256; i += blockDim.x) sc->hist[i] = 0;
+        __syncthreads();
+        for (unsigned i = threadIdx.x; i < cnt; i += blockDim.x) {
+            K k = keys[i];
+            if ((k & mask) == prefix) atomicAdd(&sc->hist[(unsigned)(k >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        select_bin(sc, need);
+        __syncthreads();
+        need = sc->need;
+        prefix |= (K)sc->bin << shift;
+        mask |= (K)255 << shift;
+        __syncthreads();
+    }
+    return prefix;
+}
+
+}  // namespace qadc

@@ -1,0 +1,283 @@
+"""GPU parity: every C-ABI call against the CPU oracle on the same seeded inputs."""
+
+import os
+
+import numpy as np
+import pytest
+
+from gpu_common import config1, to_gpu, idx_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def Q():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1704_07355_amd as Q
+    Q.lib()
+    return Q
+
+
+@pytest.fixture(scope="module")
+def O():
+    from oracle import qadc_oracle as O
+    return O
+
+
+def oracle_topk(codes, qlut, R, nbins=255):
+    from oracle import cref
+    i, d = cref.scan_topk_u8(codes, qlut[None], R, nbins)
+    return i[0], d[0]
+
+
+def gpu_topk(Q, codes_gpu, qluts, R, nbins=255, n=None):
+    import torch
+    idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes_gpu, to_gpu(qluts), R, nbins, n=n)
+    torch.cuda.synchronize()
+    return idx_np(idx), dist.cpu().numpy()
+
+
+# ------------------------------------------------------------------ tables
+
+@pytest.mark.parametrize("with_base", [False, True])
+def test_build_luts_matches_oracle(Q, O, with_base):
+    c = config1()
+    base = c["base"][:len(c["queries"])] if with_base else None
+    want = O.build_luts(c["codebooks"], c["queries"], base)
+    got = Q.qadc_build_luts(to_gpu(c["codebooks"]), to_gpu(c["queries"]),
+                            to_gpu(base) if with_base else None).cpu().numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-4, atol=0)
+
+
+def test_build_luts_8bit_tables(Q, O):
+    rng = np.random.default_rng(0)
+    cb = rng.normal(scale=30, size=(8, 256, 12)).astype(np.float32)
+    y = rng.normal(scale=30, size=(5, 96)).astype(np.float32)
+    got = Q.qadc_build_luts(to_gpu(cb), to_gpu(y)).cpu().numpy()
+    np.testing.assert_allclose(got, O.build_luts(cb, y), rtol=1e-4)
+
+
+@pytest.mark.parametrize("nbins", [255, 127])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_quantize_luts_matches_oracle(Q, O, nbins, mode):
+    c = config1()
+    cb, codes, queries = c["codebooks"], c["codes"], c["queries"]
+    R, init = 100, 200
+    # (a) the whole GPU chain: float tables within 1e-4, quantized entries within +-1
+    luts = Q.qadc_build_luts(to_gpu(cb), to_gpu(queries))
+    ql, bias, delta, qmax = Q.qadc_quantize_luts(luts, to_gpu(codes[:init]), R, nbins, mode)
+    ql, bias, delta, qmax = (t.cpu().numpy() for t in (ql, bias, delta, qmax))
+    for iq in range(len(queries)):
+        t = O.quick_adc_tables(cb, queries[iq], codes, init, R, nbins, mode)
+        np.testing.assert_allclose(qmax[iq], t["qmax"], rtol=1e-4)
+        np.testing.assert_allclose(bias[iq], t["bias"], rtol=1e-4)
+        np.testing.assert_allclose(delta[iq], t["delta"], rtol=1e-4)
+        assert np.abs(ql[iq].astype(int) - t["qlut"].astype(int)).max() <= 1
+        assert ql[iq].max() <= nbins
+    # (b) identical float tables in -> identical float32 arithmetic -> identical bytes out
+    o_luts = O.build_luts(cb, queries)
+    ql, bias, delta, qmax = Q.qadc_quantize_luts(to_gpu(o_luts), to_gpu(codes[:init]), R, nbins, mode)
+    ql, bias, delta, qmax = (t.cpu().numpy() for t in (ql, bias, delta, qmax))
+    for iq in range(len(queries)):
+        t = O.quick_adc_tables(cb, queries[iq], codes, init, R, nbins, mode, lut=o_luts[iq])
+        assert qmax[iq] == t["qmax"] and delta[iq] == t["delta"]
+        assert np.array_equal(bias[iq], t["bias"])
+        assert np.array_equal(ql[iq], t["qlut"])
+
+
+def test_quantize_edge_cases(Q, O):
+    c = config1()
+    cb, codes, queries = c["codebooks"], c["codes"], c["queries"][:3]
+    o_luts = O.build_luts(cb, queries)
+    # init smaller than R, init = 1, init larger than usual
+    for init, R in [(50, 100), (1, 100), (1000, 100), (8192, 1000), (200, 1)]:
+        ql, bias, delta, qmax = Q.qadc_quantize_luts(to_gpu(o_luts), to_gpu(codes[:init]), R)
+        for iq in range(len(queries)):
+            t = O.quick_adc_tables(cb, queries[iq], codes, init, R, lut=o_luts[iq])
+            assert qmax[iq].item() == t["qmax"], (init, R)
+            assert np.array_equal(ql[iq].cpu().numpy(), t["qlut"])
+    # qmax given instead of init codes; degenerate delta (qmax <= qmin)
+    import torch
+    for qm in (1e9, 0.0):
+        qmax_in = torch.full((len(queries),), qm, dtype=torch.float32, device="cuda:0")
+        ql, bias, delta, qmax = Q.qadc_quantize_luts(to_gpu(o_luts), None, 100, qmax_in=qmax_in)
+        for iq in range(len(queries)):
+            b, dl = O.quantizer_params(o_luts[iq], np.float32(qm), 255, 0)
+            assert delta[iq].item() == dl
+            assert np.array_equal(ql[iq].cpu().numpy(), O.quantize_luts(o_luts[iq], b, dl, 255))
+    # several table sets per query share one quantizer
+    rng = np.random.default_rng(1)
+    luts = rng.uniform(5, 3000, size=(4, 6, 16, 16)).astype(np.float32)
+    qmax_in = to_gpu(np.array([20000, 30000, 1000, 50000], dtype=np.float32))
+    for mode in (0, 1):
+        ql, bias, delta, _ = Q.qadc_quantize_luts(to_gpu(luts), None, 100, 255, mode, qmax_in=qmax_in)
+        for iq in range(4):
+            b, dl = O.quantizer_params(luts[iq], qmax_in[iq].item(), 255, mode)
+            assert np.array_equal(bias[iq].cpu().numpy(), b) and delta[iq].item() == dl
+            want = np.stack([O.quantize_luts(l, b, dl, 255) for l in luts[iq]])
+            assert np.array_equal(ql[iq].cpu().numpy(), want)
+
+
+def test_bad_arguments_are_errors(Q):
+    import torch
+    c = config1()
+    codes = to_gpu(c["codes"][:1000])
+    ql = torch.zeros((1, 16, 16), dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(Q.QadcError) as e:
+        Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes, ql, 5000)
+    assert e.value.code == Q.QADC_EINVAL
+    with pytest.raises(Q.QadcError) as e:
+        Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes, ql, 100,
+                         workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.code == Q.QADC_ENOMEM
+    with pytest.raises(Q.QadcError):
+        Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes, ql, 100, nbins=300)
+    luts = torch.zeros((1, 16, 16), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(Q.QadcError):
+        Q.qadc_quantize_luts(luts, None, 100)  # neither init codes nor qmax
+
+
+# -------------------------------------------------------------------- scan
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("nbins", [255, 127])
+def test_scan_topk_config1_bit_exact(Q, O, nbins, mode):
+    """Config 1: N=100k, 16 queries, oracle-quantized tables in -> identical indices and sums out."""
+    c = config1()
+    cb, codes, queries = c["codebooks"], c["codes"], c["queries"]
+    R = 100
+    qluts = np.stack([O.quick_adc_tables(cb, y, codes, 200, R, nbins, mode)["qlut"] for y in queries])
+    gi, gd = gpu_topk(Q, to_gpu(codes), qluts, R, nbins)
+    for iq in range(len(queries)):
+        wi, wd = oracle_topk(codes, qluts[iq], R, nbins)
+        assert np.array_equal(gi[iq], wi), f"query {iq}"
+        assert np.array_equal(gd[iq], wd), f"query {iq}"
+
+
+def test_full_chain_config1(Q, O):
+    """GPU tables -> GPU quantization -> GPU scan; the oracle replays the integer part on the GPU's tables."""
+    c = config1()
+    cb, codes, queries = c["codebooks"], c["codes"], c["queries"]
+    R, init = 100, 200
+    g_codes = to_gpu(codes)
+    luts = Q.qadc_build_luts(to_gpu(cb), to_gpu(queries))
+    ql, _, _, _ = Q.qadc_quantize_luts(luts, g_codes[:init], R)
+    import torch
+    idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, g_codes, ql, R)
+    torch.cuda.synchronize()
+    h_ql = ql.cpu().numpy()
+    fidx = []
+    for iq in range(len(queries)):
+        wi, wd = oracle_topk(codes, h_ql[iq], R)
+        assert np.array_equal(idx_np(idx)[iq], wi) and np.array_equal(dist[iq].cpu().numpy(), wd)
+        fi, _ = O.adc_search(cb, queries[iq], O.unpack_nibbles(codes), R)
+        fidx.append(fi)
+    # Section 4.2: quantized tables barely change what float ADC returns (ordering check only)
+    assert O.overlap_at_r(idx_np(idx), np.stack(fidx)) > 0.6
+
+
+@pytest.mark.parametrize("m", [8, 16, 32, 64])
+@pytest.mark.parametrize("n", [0, 1, 99, 100, 4097, 100_003])
+def test_scan_topk_shapes_and_ragged_tails(Q, m, n):
+    rng = np.random.default_rng(m * 1000003 + n)
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    qluts = rng.integers(0, 40, size=(3, m, 16)).astype(np.uint8)
+    R = 100
+    g = to_gpu(codes) if n else to_gpu(np.zeros((1, m // 2), dtype=np.uint8))
+    gi, gd = gpu_topk(Q, g, qluts, R, n=n)
+    for iq in range(3):
+        wi, wd = oracle_topk(codes, qluts[iq], R)
+        assert np.array_equal(gi[iq], wi), (m, n, iq)
+        assert np.array_equal(gd[iq], wd), (m, n, iq)
+
+
+@pytest.mark.parametrize("kind", ["zeros", "saturated", "binary", "wide", "one_hot_far"])
+@pytest.mark.parametrize("R", [1, 100, 1024])
+def test_scan_topk_ties_and_saturation(Q, kind, R):
+    """Degenerate tables: every sum equal, every sum saturated, two-valued sums, sums that overflow a byte."""
+    rng = np.random.default_rng(42)
+    n, m = 50_021, 16
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    codes[1000:1200] = codes[7]  # duplicate codes: equal sums at distinct indices
+    if kind == "zeros":
+        ql = np.zeros((m, 16), dtype=np.uint8)
+    elif kind == "saturated":
+        ql = np.full((m, 16), 255, dtype=np.uint8)
+    elif kind == "binary":
+        ql = rng.integers(0, 2, size=(m, 16)).astype(np.uint8)
+    elif kind == "wide":
+        ql = rng.integers(0, 256, size=(m, 16)).astype(np.uint8)
+    else:
+        ql = np.full((m, 16), 200, dtype=np.uint8)
+        ql[:, 3] = 0
+    gi, gd = gpu_topk(Q, to_gpu(codes), ql[None], R)
+    wi, wd = oracle_topk(codes, ql, R)
+    assert np.array_equal(gi[0], wi) and np.array_equal(gd[0], wd)
+
+
+def test_scan_topk_adversarial_order(Q):
+    """Sums strictly decreasing with the index: every code beats all earlier ones."""
+    n, m = 70_000, 16
+    codes = np.zeros((n, m // 2), dtype=np.uint8)
+    lvl = (np.arange(n)[::-1] * 240 // n).astype(np.int64)  # 239 .. 0
+    # component 0 carries lvl % 16, component 1 carries lvl // 16
+    codes[:, 0] = (lvl % 16) | ((lvl // 16) << 4)
+    ql = np.zeros((m, 16), dtype=np.uint8)
+    ql[0] = np.arange(16)
+    ql[1] = np.arange(16) * 16
+    gi, gd = gpu_topk(Q, to_gpu(codes), ql[None], 100)
+    wi, wd = oracle_topk(codes, ql, 100)
+    assert np.array_equal(gi[0], wi) and np.array_equal(gd[0], wd)
+
+
+def test_scan_topk_is_deterministic_and_launch_shape_free(Q, O):
+    c = config1()
+    codes, cb = c["codes"], c["codebooks"]
+    qlut = O.quick_adc_tables(cb, c["queries"][0], codes, 200, 100)["qlut"]
+    g = to_gpu(codes)
+    ref = gpu_topk(Q, g, qlut[None], 100)
+    saved = {k: os.environ.get(k) for k in ("QADC_SCAN_NT", "QADC_SCAN_WGS")}
+    try:
+        for nt, wgs in [("512", "1"), ("512", "7"), ("1024", "256"), ("1024", "3"), ("512", "2048")]:
+            os.environ["QADC_SCAN_NT"], os.environ["QADC_SCAN_WGS"] = nt, wgs
+            for _ in range(2):
+                got = gpu_topk(Q, g, qlut[None], 100)
+                assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1]), (nt, wgs)
+    finally:
+        for k, v in saved.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+    wi, wd = oracle_topk(codes, qlut, 100)
+    assert np.array_equal(ref[0][0], wi) and np.array_equal(ref[1][0], wd)
+
+
+# ------------------------------------------------------------------ encode
+
+@pytest.mark.parametrize("shape", [(128, 16, 16), (128, 32, 16), (96, 8, 256), (96, 16, 16)])
+def test_pq_encode_matches_oracle(Q, O, shape):
+    """GPU encode (float32 distances) against the oracle (float64): identical except where the two
+    best centroids are closer than float32 rounding can tell apart."""
+    from oracle import cref
+    from workloads import MixtureSpec, mixture_vectors, SEED_BASE, SEED_TRAIN
+    d, m, k = shape
+    spec = MixtureSpec(d=d)
+    x = mixture_vectors(spec, SEED_BASE, 0, 20_011)
+    rng = np.random.default_rng(d + m + k)
+    train = mixture_vectors(spec, SEED_TRAIN, 0, 4000)
+    rows = rng.permutation(4000)[:k]
+    dsub = d // m
+    cb = np.stack([train[rows, j * dsub:(j + 1) * dsub] for j in range(m)]).astype(np.float32)
+    x[:k] = train[rows]  # vectors that sit exactly on centroids
+    want = cref.pq_encode(x, cb)
+    got = Q.qadc_pq_encode(to_gpu(cb), to_gpu(x)).cpu().numpy()
+    assert got.shape == want.shape
+    wc = O.unpack_nibbles(want) if k == 16 else want
+    gc = O.unpack_nibbles(got) if k == 16 else got
+    bad = np.argwhere(wc != gc)
+    assert len(bad) < 1e-4 * wc.size
+    for r, j in bad:
+        dist = O.sq_l2(x[r:r + 1, j * dsub:(j + 1) * dsub], cb[j])[0]
+        assert abs(dist[wc[r, j]] - dist[gc[r, j]]) <= 1e-5 * dist[wc[r, j]]
