@@ -96,7 +96,7 @@ def main():
     bufs = [codes[b * n:(b + 1) * n] for b in range(args.buffers)]
 
     ws_bytes = Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, n, m, 1, R)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    ws = Q.qadc_workspace_init(torch.empty(ws_bytes, dtype=torch.uint8, device=dev))
     luts = torch.empty((1, m, 16), dtype=torch.float32, device=dev)
     out_idx = torch.empty((1, R), dtype=torch.int32, device=dev)
     out_dist = torch.empty((1, R), dtype=torch.uint8, device=dev)
@@ -133,6 +133,7 @@ def main():
         torch.cuda.synchronize()
         ms_scan, launches = Q.qadc_profile_read(Q.QADC_PROF_SCAN)
         ms_merge, _ = Q.qadc_profile_read(Q.QADC_PROF_MERGE)
+        ms_seed, _ = Q.qadc_profile_read(Q.QADC_PROF_SEED)
         Q.qadc_profile_enable(False)
         avg_ms = ms_scan / max(1, launches)
         achieved = n * row / (avg_ms * 1e-3) / 1e9
@@ -141,7 +142,8 @@ def main():
                     "traffic": None, "avg_kernel_us": round(avg_ms * 1e3, 2),
                     "bytes_per_launch": n * row, "launches_timed": launches}
         scan_only = {"scan_kernel_us": round(avg_ms * 1e3, 2),
-                     "merge_kernel_us": round(ms_merge / max(1, launches) * 1e3, 2)}
+                     "merge_kernel_us": round(ms_merge / max(1, launches) * 1e3, 2),
+                     "seed_kernel_us": round(ms_seed / max(1, launches) * 1e3, 2)}
 
     # CPU oracle (plain C twin, one query per thread) on a bounded sample: same codes, same tables.
     cpu = None

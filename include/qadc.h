@@ -16,8 +16,10 @@
  *    valid once the stream has reached that point.
  *  - Scratch memory comes from the caller: `workspace` (device, 256-byte
  *    aligned) of at least qadc_workspace_bytes(...) bytes.  The library never
- *    allocates device memory.  Calls that share a workspace must be ordered
- *    on one stream.
+ *    allocates device memory.  A workspace holds control words that every call
+ *    expects to be zero and leaves zero: clear it ONCE with qadc_workspace_init
+ *    before its first use (and again after a call on it failed or was aborted).
+ *    Calls that share a workspace must be ordered on one stream.
  *  - Return value: QADC_OK, or a negative error.  On QADC_EINVAL / QADC_ENOMEM
  *    nothing was enqueued and the outputs are untouched.  qadc_last_error()
  *    gives a thread-local message for the last failing call.
@@ -146,12 +148,20 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
  */
 #define QADC_PROF_SCAN   0  /* code-streaming kernel of qadc_scan_topk */
 #define QADC_PROF_MERGE  1  /* cross-workgroup top-R kernel of qadc_scan_topk */
-#define QADC_PROF_COUNT  2
+#define QADC_PROF_SEED   2  /* sampling kernel of qadc_scan_topk (large databases only) */
+#define QADC_PROF_COUNT  3
 int qadc_profile_enable(int on);
 int qadc_profile_read(int which, double *total_ms, int64_t *launches);
 
 /* Bytes of workspace a call needs (0 when it needs none, or on bad arguments). */
 size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R);
+
+/*
+ * Clears a workspace (asynchronous memset on `stream`).  Required once before the
+ * first call that uses the workspace; every call leaves the workspace ready for the
+ * next one.  Do not record it into a HIP graph: clear the workspace before capture.
+ */
+int qadc_workspace_init(void *workspace, size_t bytes, void *stream);
 
 /* Message of the last failing call on this thread ("" when none). */
 const char *qadc_last_error(void);

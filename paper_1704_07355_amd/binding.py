@@ -22,11 +22,11 @@ QADC_MAX_INIT = 8192
 QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
 QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
 QADC_WS_SCAN_TOPK, QADC_WS_QUANTIZE = 0, 1
-QADC_PROF_SCAN, QADC_PROF_MERGE = 0, 1
+QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED = 0, 1, 2
 
 EXPORTS = (
     "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_pq_encode",
-    "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes",
+    "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version",
 )
 
@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.qadc_profile_read.restype = i32
         L.qadc_workspace_bytes.argtypes = [i32, i64, i32, i32, i32]
         L.qadc_workspace_bytes.restype = sz
+        L.qadc_workspace_init.argtypes = [vp, sz, vp]
+        L.qadc_workspace_init.restype = i32
         L.qadc_last_error.restype = ctypes.c_char_p
         L.qadc_version.restype = ctypes.c_char_p
         _lib = L
@@ -97,6 +99,13 @@ def qadc_last_error() -> str:
 
 def qadc_workspace_bytes(call: int, n: int, m: int, nq: int, R: int) -> int:
     return int(lib().qadc_workspace_bytes(call, n, m, nq, R))
+
+
+def qadc_workspace_init(workspace):
+    """Clears a workspace tensor before its first use; returns it."""
+    _check(lib().qadc_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream()))
+    return workspace
 
 
 def qadc_build_luts(codebooks, queries, base=None, out=None):
@@ -152,7 +161,7 @@ def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=N
         out_dist = torch.empty((nq, R), dtype=want, device=dev)
     need = qadc_workspace_bytes(QADC_WS_SCAN_TOPK, n, m, nq, R)
     if workspace is None:
-        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=dev)
+        workspace = qadc_workspace_init(torch.empty((max(need, 256),), dtype=torch.uint8, device=dev))
     _check(lib().qadc_scan_topk(variant, _ptr(codes, torch.uint8), n, m, _ptr(luts), nq, R, nbins,
                                 _ptr(out_idx), _ptr(out_dist), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream()))

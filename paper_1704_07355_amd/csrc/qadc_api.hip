@@ -28,6 +28,7 @@ int scan_topk_u8(const uint8_t *, int64_t, int, const uint8_t *, int, int, int, 
                  uint8_t *, void *, size_t, hipStream_t);
 size_t scan_topk_u8_workspace(int64_t, int, int, int);
 int pq_encode(const float *, int, int, int, const float *, int64_t, uint8_t *, hipStream_t);
+int workspace_init(void *, size_t, hipStream_t);
 
 }  // namespace qadc
 
@@ -83,6 +84,11 @@ size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)
     case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(n, m, nq, R);
     default: return 0;
     }
+}
+
+int qadc_workspace_init(void *workspace, size_t bytes, void *stream)
+{
+    return qadc::workspace_init(workspace, bytes, (hipStream_t)stream);
 }
 
 const char *qadc_last_error(void) { return qadc::err_buf(); }

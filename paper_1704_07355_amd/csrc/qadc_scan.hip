@@ -1,18 +1,29 @@
-// Scan step + top-R of Quick ADC on gfx950 (Alg. 2 of the paper; Alg. 1 for the
-// float variants lives in qadc_scan_f32.hip).
+// Scan step + top-R of Quick ADC on gfx950 (Alg. 2 of the paper).
 //
 // Data flow of one query:
-//   codes (HBM, standard layout, streamed once, 16 B per lane per load)
+//   codes (HBM, standard layout, streamed once, 16 B per lane per load, next tile
+//   prefetched into registers while the current one is processed)
 //     -> per code: one LDS lookup per code BYTE in a 256-entry "pair table"
 //        ptab[jb][v] = min(cap, q[2jb][v & 15] + q[2jb+1][v >> 4]), summed and
 //        clamped once at `cap`.  Entries are non-negative, so this equals the
 //        chain of saturating adds of Alg. 2 (mask 0x0f, lookup, add, shift).
-//     -> key = sum << 24 | (index inside the workgroup's chunk); keys below the
-//        workgroup's running threshold are appended to an LDS candidate list
-//        (one atomic per wavefront), which is cut back to its R smallest keys
-//        by an exact radix select whenever it fills up.
-//     -> every workgroup writes its R best as 64-bit keys sum << 32 | index;
-//        a second kernel selects and orders the R best of all of them.
+//     -> key = sum << 24 | (index inside the workgroup's chunk).
+//   Selection never stores more than a few hundred keys per workgroup:
+//     * the first ("seed") tile of a workgroup is histogrammed by sum; the bin
+//       tau_w holding its R-th smallest sum bounds the R-th smallest sum of the
+//       chunk, and only keys with sum <= tau_w are appended to the workgroup's LDS
+//       candidate list (one LDS atomic per wavefront);
+//     * the seed counts of bins <= tau_w are also added to a grid-wide histogram
+//       (16 replicas, fire-and-forget atomics).  At its end a workgroup sums the
+//       replicas: the bin where the running count reaches R bounds the R-th
+//       smallest sum of the WHOLE database, whatever part of the other
+//       workgroups' counts has arrived, and the workgroup reports only the
+//       candidates at or below it (a handful);
+//     * should a candidate list fill up (adversarial order, massive ties), it is
+//       cut back to its R smallest keys by an exact radix select, so the result
+//       never depends on the thresholds being good, only the speed does.
+//   A second, single-workgroup kernel orders the R smallest of the reported keys
+//   (sum << 32 | index) and clears the control block for the next call.
 // The total order (sum, index) is carried by the integer keys, so the result
 // does not depend on how the grid is cut or on the order waves run in.
 
@@ -23,11 +34,19 @@ namespace qadc {
 
 constexpr int SCAN_VEC = 2;               // 16-byte loads per thread and tile
 constexpr int SCAN_SLACK = QADC_MAX_R;    // candidate slots beyond one tile
-constexpr uint64_t PAD_KEY = ~0ull;
+constexpr int GH_REP = 8;                 // replicas of the grid-wide histogram
+constexpr unsigned NO_KEY = 0xffffffffu;
+
+// Per-query control block in the workspace, followed by counts[G] (keys reported by each
+// workgroup) and lists[G][R] (the keys).  Block and counts must be all zero when the scan
+// kernel starts; the merge kernel leaves every word the call wrote zeroed again.
+struct alignas(256) ScanHeader {
+    unsigned ghist[GH_REP][256];  // sums of the best codes of every seed tile
+};
 
 template <int B, int NT>
 struct ScanCfg {
-    static constexpr int CPV = (B <= 16) ? 16 / B : 1;            // codes per thread-load
+    static constexpr int CPV = (B <= 16) ? 16 / B : 1;            // codes per 16-byte load
     static constexpr int CPT = (B <= 16) ? SCAN_VEC * CPV : 1;    // codes per thread and tile
     static constexpr int TILE = NT * CPT;
     static constexpr int CAP = TILE + SCAN_SLACK;
@@ -37,12 +56,49 @@ struct ScanShared {
     SelectScratch sel;
     unsigned ccnt;     // append counter of a compaction
     unsigned tcnt[3];  // append counters of the tiles, used in rotation
+    unsigned tau;      // threshold bin published by wave 0
 };
 
 __device__ __forceinline__ unsigned byte_of(const uint4 &v, int k)
 {
     const unsigned w = (k < 4) ? v.x : (k < 8) ? v.y : (k < 12) ? v.z : v.w;
     return (w >> (8 * (k & 3))) & 0xffu;
+}
+
+// Keys with sum <= tau are exactly the keys below this limit.
+__device__ __forceinline__ unsigned limit_of_bin(unsigned tau)
+{
+    return tau >= 255u ? NO_KEY : ((tau + 1u) << 24);
+}
+
+// Called by one whole wave; h[b] is the count of bin NB*lane+b.  Returns, in every lane,
+// the smallest bin whose inclusive running count reaches `need`, or 64*NB when none does.
+template <int NB>
+__device__ __forceinline__ unsigned wave_threshold_bin(const unsigned (&h)[NB], unsigned need,
+                                                       unsigned *total = nullptr)
+{
+    const int l = lane_id();
+    unsigned tot = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) tot += h[b];
+    unsigned inc = tot;
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        const unsigned up = __shfl_up(inc, d);
+        if (l >= d) inc += up;
+    }
+    if (total) *total = __shfl(inc, WAVE - 1);
+    const unsigned long long m = __ballot(inc >= need);
+    if (m == 0) return (unsigned)(WAVE * NB);
+    const int first = __ffsll((long long)m) - 1;
+    unsigned run = inc - tot, bin = (unsigned)(NB * l + NB - 1);
+    bool found = false;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        run += h[b];
+        if (!found && run >= need) { bin = (unsigned)(NB * l + b); found = true; }
+    }
+    return __shfl(bin, first);
 }
 
 // Cuts keys[0..cnt) back to its `keep` smallest keys (cnt > keep) and returns
@@ -56,7 +112,7 @@ __device__ unsigned compact_candidates(unsigned *keys, unsigned cnt, unsigned ke
 #pragma unroll
     for (int t = 0; t < PER; ++t) {
         unsigned i = threadIdx.x + t * NT;
-        mine[t] = (i < cnt) ? keys[i] : 0xffffffffu;
+        mine[t] = (i < cnt) ? keys[i] : NO_KEY;
     }
     if (threadIdx.x == 0) sh->ccnt = 0;
     __syncthreads();
@@ -71,10 +127,147 @@ __device__ unsigned compact_candidates(unsigned *keys, unsigned cnt, unsigned ke
     return kth;
 }
 
+// The two 16-byte loads of one thread for the tile starting at code t0.
 template <int B, int NT>
-__global__ __launch_bounds__(NT) void scan_u8_kernel(
-    const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap,
-    int R, int64_t chunk, uint64_t *__restrict__ part)
+__device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int64_t t0, int64_t c1,
+                                          uint4 (&w)[2], int (&nc)[2])
+{
+    const int tid = threadIdx.x;
+    if constexpr (B <= 16) {
+        constexpr int CPV = 16 / B;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            const int64_t base = t0 + ((int64_t)v * NT + tid) * CPV;
+            w[v] = make_uint4(0, 0, 0, 0);
+            nc[v] = 0;
+            if (base + CPV <= c1) {
+                w[v] = *reinterpret_cast<const uint4 *>(codes + base * B);
+                nc[v] = CPV;
+            } else if (base < c1) {  // ragged end of the database: byte loads, no read past the end
+                nc[v] = (int)(c1 - base);
+                unsigned tmp[4] = {0, 0, 0, 0};
+                for (int k = 0; k < nc[v] * B; ++k)
+                    tmp[k >> 2] |= (unsigned)codes[base * B + k] << (8 * (k & 3));
+                w[v] = make_uint4(tmp[0], tmp[1], tmp[2], tmp[3]);
+            }
+        }
+    } else {
+        const int64_t i = t0 + tid;
+        w[0] = w[1] = make_uint4(0, 0, 0, 0);
+        nc[0] = nc[1] = 0;
+        if (i < c1) {
+            w[0] = *reinterpret_cast<const uint4 *>(codes + i * B);
+            w[1] = *reinterpret_cast<const uint4 *>(codes + i * B + 16);
+            nc[0] = 1;
+        }
+    }
+}
+
+// Lookups, sum, clamp, key = sum << 24 | index inside the chunk (NO_KEY where no code).
+template <int B, int NT>
+__device__ __forceinline__ void tile_keys(const uint4 (&w)[2], const int (&nc)[2], unsigned rel0,
+                                          const uint8_t *ptab, unsigned cap,
+                                          unsigned (&k)[ScanCfg<B, NT>::CPT])
+{
+    const int tid = threadIdx.x;
+    if constexpr (B <= 16) {
+        constexpr int CPV = 16 / B;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+#pragma unroll
+            for (int c = 0; c < CPV; ++c) {
+                unsigned s = 0;
+#pragma unroll
+                for (int jb = 0; jb < B; ++jb) s += ptab[jb * 256 + byte_of(w[v], c * B + jb)];
+                s = min(s, cap);
+                const unsigned li = rel0 + (unsigned)((v * NT + tid) * CPV + c);
+                k[v * CPV + c] = (c < nc[v]) ? ((s << 24) | li) : NO_KEY;
+            }
+        }
+    } else {
+        unsigned s = 0;
+#pragma unroll
+        for (int jb = 0; jb < 16; ++jb) s += ptab[jb * 256 + byte_of(w[0], jb)];
+#pragma unroll
+        for (int jb = 0; jb < 16; ++jb) s += ptab[(16 + jb) * 256 + byte_of(w[1], jb)];
+        s = min(s, cap);
+        k[0] = nc[0] ? ((s << 24) | (rel0 + (unsigned)tid)) : NO_KEY;
+    }
+}
+
+// Pair tables of one query in LDS: ptab[jb][v] = min(cap, q[2jb][v & 15] + q[2jb+1][v >> 4]).
+template <int B, int NT>
+__device__ __forceinline__ void build_pair_tables(const uint8_t *__restrict__ qlut, unsigned cap,
+                                                  uint8_t *ptab)
+{
+    for (int e = threadIdx.x; e < B * 256; e += NT) {
+        const int jb = e >> 8, v = e & 255;
+        const unsigned s = (unsigned)qlut[(2 * jb) * 16 + (v & 15)] +
+                           (unsigned)qlut[(2 * jb + 1) * 16 + (v >> 4)];
+        ptab[e] = (uint8_t)min(s, cap);
+    }
+}
+
+// Seed kernel: a sample of the database (one tile per workgroup, tiles spread evenly) is
+// scanned and histogrammed by sum.  Each workgroup adds the counts of its lowest bins (its
+// best `flush_need` codes, never beyond its own R-th) to the query's grid-wide histogram.
+// The bin where that histogram's running count reaches R bounds the R-th smallest sum of
+// the whole database from above: the scan kernel only keeps keys at or below it.
+template <int B>
+__global__ __launch_bounds__(1024) void seed_u8_kernel(
+    const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
+    int R, unsigned flush_need, int64_t seed_stride, char *__restrict__ ws, size_t ws_stride)
+{
+    constexpr int NT = 1024;
+    using C = ScanCfg<B, NT>;
+    __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
+    __shared__ unsigned hist[256];
+
+    const int tid = threadIdx.x;
+    const int q = blockIdx.y;
+    const int g = blockIdx.x;
+    const unsigned cap = (unsigned)cap_i;
+    const int64_t c0 = (int64_t)g * seed_stride;
+    const int64_t c1 = min(n, c0 + C::TILE);
+    if (c0 >= c1) return;
+
+    uint4 w[2];
+    int nc[2];
+    tile_load<B, NT>(codes, c0, c1, w, nc);
+    build_pair_tables<B, NT>(qluts + (size_t)q * (2 * B) * 16, cap, ptab);
+    for (int e = tid; e < 256; e += NT) hist[e] = 0;
+    __syncthreads();
+
+    unsigned k[C::CPT];
+    tile_keys<B, NT>(w, nc, 0u, ptab, cap, k);
+#pragma unroll
+    for (int c = 0; c < C::CPT; ++c)
+        if ((k[c] >> 24) < cap) atomicAdd(&hist[k[c] >> 24], 1u);  // NO_KEY has sum 255 >= cap
+    __syncthreads();
+    if (tid < WAVE) {
+        unsigned h[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) h[b] = hist[4 * tid + b];
+        const unsigned f = min(wave_threshold_bin<4>(h, (unsigned)R),
+                               wave_threshold_bin<4>(h, flush_need));
+        ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+        unsigned *ghist = hdr->ghist[g % GH_REP];
+        // lane l reports bins l, l+64, ...: the low bins of a workgroup travel as ONE request
+        for (unsigned b0 = 0; b0 <= f && b0 < 256u; b0 += WAVE) {  // uniform
+            const unsigned bin = b0 + tid;
+            const unsigned c = hist[bin];
+            if (bin <= f && bin < cap && c)
+                __hip_atomic_fetch_add(&ghist[bin], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Scan kernel: workgroup g streams codes [g*chunk, (g+1)*chunk) of query blockIdx.y.
+template <int B, int NT>
+__global__ __launch_bounds__(NT, 8) void scan_u8_kernel(
+    const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
+    int R, int64_t chunk, int has_seed, char *__restrict__ ws, size_t ws_stride,
+    size_t counts_off, size_t lists_off)
 {
     using C = ScanCfg<B, NT>;
     __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
@@ -84,21 +277,45 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     const int tid = threadIdx.x;
     const int q = blockIdx.y;
     const int g = blockIdx.x;
-    const int G = gridDim.x;
-    const uint8_t *qlut = qluts + (size_t)q * (2 * B) * 16;
-
-    for (int e = tid; e < B * 256; e += NT) {
-        const int jb = e >> 8, v = e & 255;
-        unsigned s = (unsigned)qlut[(2 * jb) * 16 + (v & 15)] + (unsigned)qlut[(2 * jb + 1) * 16 + (v >> 4)];
-        ptab[e] = (uint8_t)min(s, (unsigned)cap);
-    }
-    if (tid == 0) sh.tcnt[0] = 0;
-    __syncthreads();
+    const unsigned cap = (unsigned)cap_i;
+    const ScanHeader *hdr = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride);
 
     const int64_t c0 = (int64_t)g * chunk;
     const int64_t c1 = min(n, c0 + chunk);
-    unsigned thr = 0xffffffffu;  // keys >= thr cannot be among the R best of this chunk
-    unsigned have = 0;           // candidates in keys[] before the current tile (uniform)
+    if (c0 >= c1) return;  // uniform: nothing to scan, nothing to report
+
+    uint4 w[2], wn[2];
+    int nc[2], ncn[2];
+    tile_load<B, NT>(codes, c0, c1, w, nc);
+
+    // Grid-wide bound left by the seed kernel: the bin where the running count of the summed
+    // replicas reaches R, or 256.
+    if (tid < WAVE) {
+        unsigned t = 256, carry = 0;
+        for (unsigned b0 = 0; b0 < 256 && has_seed; b0 += 128) {  // uniform
+            const unsigned bin = b0 + 2u * tid;
+            unsigned h[2] = {0, 0};
+#pragma unroll
+            for (int r = 0; r < GH_REP; ++r) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(&hdr->ghist[r][bin]);
+                h[0] += v.x;
+                h[1] += v.y;
+            }
+            unsigned tot;
+            const unsigned hit = wave_threshold_bin<2>(h, (unsigned)R - carry, &tot);
+            if (hit < 128u) { t = b0 + hit; break; }
+            carry += tot;  // still below R
+        }
+        if (tid == 0) sh.tau = t;
+    }
+    build_pair_tables<B, NT>(qluts + (size_t)q * (2 * B) * 16, cap, ptab);
+    for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
+    if (tid == 0) sh.tcnt[0] = 0;
+    __syncthreads();
+
+    const bool seeded = sh.tau < 256u;  // uniform
+    unsigned lim = seeded ? limit_of_bin(sh.tau) : NO_KEY;  // keys >= lim cannot be among the R best
+    unsigned have = 0;  // candidates in keys[] before the current tile (uniform)
     int rot = 0;
 
     // One barrier per tile: the tile's appends go through counter tcnt[rot]; after the
@@ -108,75 +325,61 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
         unsigned *ctr = &sh.tcnt[rot];
         const int nxt = (rot == 2) ? 0 : rot + 1;
         if (tid == 0) sh.tcnt[nxt] = 0;
-        if constexpr (B <= 16) {
+        const bool more = t0 + C::TILE < c1;
+        if (more) tile_load<B, NT>(codes, t0 + C::TILE, c1, wn, ncn);
+
+        unsigned k[C::CPT];
+        tile_keys<B, NT>(w, nc, (unsigned)(t0 - c0), ptab, cap, k);
+
+        if (t0 == c0 && !seeded) {
+            // No grid-wide bound (small database): bound the chunk by its own first tile.
+            // Histogram of the tile's unsaturated sums -> the bin holding its R-th smallest.
 #pragma unroll
-            for (int v = 0; v < SCAN_VEC; ++v) {
-                const int64_t base = t0 + ((int64_t)v * NT + tid) * C::CPV;
-                uint4 w = make_uint4(0, 0, 0, 0);
-                int nc = 0;
-                if (base + C::CPV <= c1) {
-                    w = *reinterpret_cast<const uint4 *>(codes + base * B);
-                    nc = C::CPV;
-                } else if (base < c1) {
-                    nc = (int)(c1 - base);
-                    unsigned tmp[4] = {0, 0, 0, 0};
-                    for (int k = 0; k < nc * B; ++k)
-                        tmp[k >> 2] |= (unsigned)codes[base * B + k] << (8 * (k & 3));
-                    w = make_uint4(tmp[0], tmp[1], tmp[2], tmp[3]);
-                }
+            for (int c = 0; c < C::CPT; ++c)
+                if ((k[c] >> 24) < cap) atomicAdd(&sh.sel.hist[k[c] >> 24], 1u);
+            __syncthreads();
+            if (tid < WAVE) {
+                unsigned h[4];
 #pragma unroll
-                for (int c = 0; c < C::CPV; ++c) {
-                    unsigned s = 0;
-#pragma unroll
-                    for (int jb = 0; jb < B; ++jb) s += ptab[jb * 256 + byte_of(w, c * B + jb)];
-                    s = min(s, (unsigned)cap);
-                    const unsigned key = (s << 24) | (unsigned)(base + c - c0);
-                    const bool pass = (c < nc) && (key < thr);
-                    const unsigned slot = have + wave_append_slot(pass, ctr);
-                    if (pass) keys[slot] = key;
-                }
+                for (int b = 0; b < 4; ++b) h[b] = sh.sel.hist[4 * tid + b];
+                const unsigned t = wave_threshold_bin<4>(h, (unsigned)R);
+                if (tid == 0) sh.tau = min(t, cap);
             }
-        } else {  // B == 32: one code per thread and tile, two 16-byte loads
-            const int64_t i = t0 + tid;
-            bool pass = false;
-            unsigned key = 0;
-            if (i < c1) {
-                const uint4 w0 = *reinterpret_cast<const uint4 *>(codes + i * B);
-                const uint4 w1 = *reinterpret_cast<const uint4 *>(codes + i * B + 16);
-                unsigned s = 0;
+            __syncthreads();
+            lim = limit_of_bin(sh.tau);
+        }
+
 #pragma unroll
-                for (int jb = 0; jb < 16; ++jb) s += ptab[jb * 256 + byte_of(w0, jb)];
-#pragma unroll
-                for (int jb = 0; jb < 16; ++jb) s += ptab[(16 + jb) * 256 + byte_of(w1, jb)];
-                s = min(s, (unsigned)cap);
-                key = (s << 24) | (unsigned)(i - c0);
-                pass = key < thr;
-            }
+        for (int c = 0; c < C::CPT; ++c) {
+            const bool pass = k[c] < lim;
             const unsigned slot = have + wave_append_slot(pass, ctr);
-            if (pass) keys[slot] = key;
+            if (pass) keys[slot] = k[c];
         }
         __syncthreads();
         have += *ctr;
         rot = nxt;
         if (have > (unsigned)SCAN_SLACK) {  // the next tile might not fit: keep the R best
-            thr = compact_candidates<NT, C::CAP>(keys, have, (unsigned)R, &sh);
+            const unsigned kth = compact_candidates<NT, C::CAP>(keys, have, (unsigned)R, &sh);
+            lim = min(lim, kth + 1u);  // keys are unique: later ones must be below the R-th kept
             have = (unsigned)R;
+        }
+        if (more) {
+            w[0] = wn[0]; w[1] = wn[1];
+            nc[0] = ncn[0]; nc[1] = ncn[1];
         }
     }
 
-    unsigned cnt = have;
-    if (cnt > (unsigned)R) {
-        compact_candidates<NT, C::CAP>(keys, cnt, (unsigned)R, &sh);
-        cnt = (unsigned)R;
+    if (have > (unsigned)R) {
+        compact_candidates<NT, C::CAP>(keys, have, (unsigned)R, &sh);
+        have = (unsigned)R;
     }
-    uint64_t *dst = part + ((size_t)q * G + g) * R;
-    for (int i = tid; i < R; i += NT) {
-        uint64_t k = PAD_KEY;
-        if ((unsigned)i < cnt) {
-            const unsigned key = keys[i];
-            k = ((uint64_t)(key >> 24) << 32) | (uint64_t)(c0 + (key & 0xffffffu));
-        }
-        dst[i] = k;
+    if (have == 0) return;  // counts[g] stays zero
+    unsigned *counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + counts_off);
+    uint64_t *dst = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + lists_off) + (size_t)g * R;
+    if (tid == 0) counts[g] = have;
+    for (unsigned i = tid; i < have; i += NT) {
+        const unsigned key = keys[i];
+        dst[i] = ((uint64_t)(key >> 24) << 32) | (uint64_t)(c0 + (key & 0xffffffu));
     }
 }
 
@@ -185,88 +388,77 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
 constexpr int MERGE_NT = 1024;
 constexpr int MERGE_CAP = 4096;
 
-// R best of `total` 64-bit keys (dist << 32 | index; PAD_KEY = absent), ordered.
+// R best of the keys reported by the G workgroups of each query (64-bit keys
+// dist << 32 | index, at most R per workgroup), ordered; then everything the call wrote
+// in the workspace is cleared.  KBYTES = significant key bytes (5 for u8 distances).
 // DistT = uint8_t: the distance is the key's bits 32..39; float: bits 32..63.
 template <typename DistT, int KBYTES>
 __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
-    const uint64_t *__restrict__ part, unsigned total, unsigned need, int R, DistT pad_dist,
-    uint32_t *__restrict__ out_idx, DistT *__restrict__ out_dist)
+    char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off, int G,
+    unsigned need, int R, DistT pad_dist, uint32_t *__restrict__ out_idx,
+    DistT *__restrict__ out_dist)
 {
-    // need = min(R, number of codes scanned): at least that many real keys are in `part`.
+    // need = min(R, number of codes scanned): at least that many keys were reported.
     __shared__ uint64_t lkeys[MERGE_CAP];
     __shared__ SelectScratch sc;
     __shared__ unsigned lcnt;
 
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
-    const uint64_t *src = part + (size_t)q * total;
-    constexpr uint64_t KMASK = (KBYTES == 8) ? ~0ull : ((1ull << (8 * (KBYTES & 7))) - 1);
-    if (need == 0) {
-        for (unsigned i = tid; i < (unsigned)R; i += MERGE_NT) {
-            out_idx[(size_t)q * R + i] = 0xffffffffu;
-            out_dist[(size_t)q * R + i] = pad_dist;
-        }
-        return;
-    }
+    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+    unsigned *counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + counts_off);
+    uint64_t *lists = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + lists_off);
 
-    // first pass over the most significant byte: the bin of the R-th key
-    for (int i = tid; i < 256; i += MERGE_NT) sc.hist[i] = 0;
+    // every reported key, spread over the threads by workgroup
+    auto each_key = [&](auto f) {
+        for (int g = tid; g < G; g += MERGE_NT) {
+            const unsigned c = min(counts[g], (unsigned)R);
+            for (unsigned i = 0; i < c; ++i) f(lists[(size_t)g * R + i]);
+        }
+    };
+
     if (tid == 0) lcnt = 0;
     __syncthreads();
-    constexpr int TOP = (KBYTES - 1) * 8;
-    for (unsigned i = tid; i < total; i += MERGE_NT)
-        atomicAdd(&sc.hist[(unsigned)((src[i] & KMASK) >> TOP) & 255u], 1u);
+    each_key([&](uint64_t k) {
+        const unsigned slot = atomicAdd(&lcnt, 1u);
+        if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
+    });
     __syncthreads();
-    select_bin(&sc, need);
-    __syncthreads();
-    const unsigned bin = sc.bin;
-    const unsigned upto = (need - sc.need) + sc.hist[bin];  // keys whose top byte <= bin
-    __syncthreads();
+    const unsigned total = lcnt;
+    need = min(need, total);
+    const bool in_lds = total <= (unsigned)MERGE_CAP;
 
-    uint64_t kth;
-    const bool in_lds = upto <= (unsigned)MERGE_CAP;
-    if (in_lds) {
-        for (unsigned i0 = 0; i0 < total; i0 += MERGE_NT) {
-            const unsigned i = i0 + tid;
-            uint64_t k = (i < total) ? (src[i] & KMASK) : ~0ull;
-            const bool ok = (i < total) && ((unsigned)(k >> TOP) & 255u) <= bin;
-            const unsigned slot = wave_append_slot(ok, &lcnt);
-            if (ok) lkeys[slot] = k;
-        }
-        __syncthreads();
-        kth = block_radix_select<uint64_t, KBYTES>(lkeys, upto, need, &sc);
-    } else {
-        kth = block_radix_select<uint64_t, KBYTES>(src, total, need, &sc) & KMASK;
-        // PAD_KEY masked to KBYTES still compares above every real key
+    uint64_t kth = 0;
+    if (need > 0) {
+        if (in_lds) kth = block_radix_select<uint64_t, KBYTES>(lkeys, total, need, &sc);
+        else kth = block_radix_select_each<uint64_t, KBYTES>(each_key, need, &sc);
     }
     __syncthreads();
 
-    // gather the `need` keys <= kth into lkeys[0..need) (reusing the list), then order by rank
+    // gather the `need` keys <= kth into lkeys[0..need), then order them by rank
     uint64_t mine[MERGE_CAP / MERGE_NT];
     if (in_lds) {
 #pragma unroll
         for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
             const unsigned i = tid + t * MERGE_NT;
-            mine[t] = (i < upto) ? lkeys[i] : ~0ull;
+            mine[t] = (i < total) ? lkeys[i] : ~0ull;
         }
     }
     if (tid == 0) lcnt = 0;
     __syncthreads();
-    if (in_lds) {
+    if (need > 0) {
+        if (in_lds) {
 #pragma unroll
-        for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
-            const unsigned i = tid + t * MERGE_NT;
-            const bool ok = (i < upto) && mine[t] <= kth;
-            const unsigned slot = wave_append_slot(ok, &lcnt);
-            if (ok) lkeys[slot] = mine[t];
-        }
-    } else {
-        for (unsigned i0 = 0; i0 < total; i0 += MERGE_NT) {
-            const unsigned i = i0 + tid;
-            const uint64_t k = (i < total) ? (src[i] & KMASK) : ~0ull;
-            const bool ok = (i < total) && k <= kth;
-            const unsigned slot = wave_append_slot(ok, &lcnt);
-            if (ok) lkeys[slot] = k;
+            for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
+                const unsigned i = tid + t * MERGE_NT;
+                const bool ok = (i < total) && mine[t] <= kth;
+                const unsigned slot = wave_append_slot(ok, &lcnt);
+                if (ok) lkeys[slot] = mine[t];
+            }
+        } else {
+            each_key([&](uint64_t k) {
+                if (k <= kth) lkeys[atomicAdd(&lcnt, 1u)] = k;  // exactly `need` keys: they are unique
+            });
         }
     }
     __syncthreads();
@@ -279,23 +471,35 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
             const uint64_t k = lkeys[i];
             unsigned rank = 0;
             for (unsigned j = 0; j < need; ++j) rank += (lkeys[j] < k) ? 1u : 0u;
-            const uint32_t idx = (uint32_t)k;
             DistT d;
             if constexpr (sizeof(DistT) == 1) d = (DistT)((k >> 32) & 0xff);
             else d = __uint_as_float((unsigned)(k >> 32));
-            if (idx == 0xffffffffu) d = pad_dist;  // a padding key was selected (fewer than R codes)
-            out_idx[(size_t)q * R + rank] = idx;
+            out_idx[(size_t)q * R + rank] = (uint32_t)k;
             out_dist[(size_t)q * R + rank] = d;
         }
     }
+
+    // Leave every word this call wrote in the workspace zero again, so that the next call
+    // finds clean control blocks wherever its own layout puts them.
+    __syncthreads();
+    for (int g = tid; g < G; g += MERGE_NT) {
+        const unsigned c = min(counts[g], (unsigned)R);
+        for (unsigned i = 0; i < c; ++i) lists[(size_t)g * R + i] = 0;
+        counts[g] = 0;
+    }
+    unsigned *z = &hdr->ghist[0][0];
+    for (int i = tid; i < GH_REP * 256; i += MERGE_NT) z[i] = 0;
 }
 
 // ---------------------------------------------------------------- host
 
 struct ScanPlan {
-    int B, NT, tile, G, qbatch;
+    int B, NT, G, qbatch;
     int64_t chunk;
-    size_t ws_bytes;
+    int seed_wgs;         // 0: no seed kernel
+    int64_t seed_stride;  // codes between the sampled tiles
+    unsigned flush_need;
+    size_t counts_off, lists_off, stride, ws_bytes;
 };
 
 static int env_int(const char *name, int dflt)
@@ -310,47 +514,94 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
     if (!(m == 8 || m == 16 || m == 32 || m == 64)) return false;
     if (n < 0 || n > 0xfffffffell || nq < 1 || R < 1 || R > QADC_MAX_R) return false;
     p->B = m / 2;
-    p->NT = env_int("QADC_SCAN_NT", 512) == 1024 ? 1024 : 512;
+    const int nt = env_int("QADC_SCAN_NT", 1024);
+    p->NT = (nt == 256 || nt == 512) ? nt : 1024;
     const int cpt = (p->B <= 16) ? SCAN_VEC * (16 / p->B) : 1;
-    p->tile = p->NT * cpt;
-    const int64_t tiles = n > 0 ? ceil_div(n, p->tile) : 1;
-    int64_t G = env_int("QADC_SCAN_WGS", p->NT == 1024 ? 256 : 512);
+    const int tile = p->NT * cpt;
+    // chunks start on 16-code boundaries (16-byte aligned for every code size) and stay
+    // below 2^24 codes, the range of the index bits of a candidate key
+    int64_t G = env_int("QADC_SCAN_WGS", 512);
     if (G < 1) G = 1;
-    if (G > tiles) G = tiles;
-    const int64_t max_chunk = ((1ll << 24) - 1) / p->tile * p->tile;
-    int64_t chunk = ceil_div(tiles, G) * p->tile;
+    const int64_t max_chunk = (1ll << 24) - 16;
+    int64_t chunk = n > 0 ? ceil_div(ceil_div(n, G), 16) * 16 : 16;
+    if (chunk < tile) chunk = tile;  // no point in splitting below one tile
     if (chunk > max_chunk) chunk = max_chunk;
     p->chunk = chunk;
     p->G = (int)(n > 0 ? ceil_div(n, chunk) : 1);
-    const size_t per_query = (size_t)p->G * R * sizeof(uint64_t);
-    int64_t qb = (int64_t)((256ull << 20) / per_query);
+    // Seed kernel: worth its launch once the database is many tiles long.  It samples up to
+    // SEED_WGS tiles of 1024-thread workgroups, spread evenly; each reports a few times its
+    // share of R codes to the grid-wide histogram.
+    const int seed_tile = 1024 * cpt;
+    const int64_t seed_tiles = n / seed_tile;
+    p->seed_wgs = 0;
+    p->seed_stride = 0;
+    p->flush_need = 16;
+    if (seed_tiles >= env_int("QADC_SEED_MIN_TILES", 64)) {
+        int64_t S = env_int("QADC_SEED_WGS", 256);
+        if (S > seed_tiles / 4) S = seed_tiles / 4;
+        if (S < 1) S = 1;
+        p->seed_wgs = (int)S;
+        p->seed_stride = (n / S) / 16 * 16;
+        int64_t fl = ceil_div(4ll * R, S);
+        if (fl < 16) fl = 16;
+        if (fl > R) fl = R;
+        p->flush_need = (unsigned)fl;
+    }
+    p->counts_off = sizeof(ScanHeader);
+    p->lists_off = p->counts_off + align_up((size_t)p->G * sizeof(unsigned), 256);
+    p->stride = p->lists_off + align_up((size_t)p->G * R * sizeof(uint64_t), 256);
+    int64_t qb = (int64_t)((256ull << 20) / p->stride);
     if (qb < 1) qb = 1;
     if (qb > nq) qb = nq;
     if (qb > 65535) qb = 65535;
     p->qbatch = (int)qb;
-    p->ws_bytes = align_up(per_query * (size_t)qb, 256);
+    p->ws_bytes = p->stride * (size_t)qb;
     return true;
 }
 
 template <int B, int NT>
 static void launch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, const uint8_t *qluts,
-                           int nq, int cap, int R, uint64_t *part, hipStream_t st)
+                           int nq, int cap, int R, char *ws, hipStream_t st)
 {
     dim3 grid(p.G, nq);
     hipLaunchKernelGGL((scan_u8_kernel<B, NT>), grid, dim3(NT), 0, st, codes, n, qluts, cap, R,
-                       p.chunk, part);
+                       p.chunk, p.seed_wgs > 0 ? 1 : 0, ws, p.stride, p.counts_off, p.lists_off);
+}
+
+static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
+                             const uint8_t *qluts, int nq, int cap, int R, char *ws, hipStream_t st)
+{
+    dim3 grid(p.seed_wgs, nq);
+    switch (p.B) {
+    case 4:
+        hipLaunchKernelGGL(seed_u8_kernel<4>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+                           p.flush_need, p.seed_stride, ws, p.stride);
+        break;
+    case 8:
+        hipLaunchKernelGGL(seed_u8_kernel<8>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+                           p.flush_need, p.seed_stride, ws, p.stride);
+        break;
+    case 16:
+        hipLaunchKernelGGL(seed_u8_kernel<16>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+                           p.flush_need, p.seed_stride, ws, p.stride);
+        break;
+    default:
+        hipLaunchKernelGGL(seed_u8_kernel<32>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+                           p.flush_need, p.seed_stride, ws, p.stride);
+        break;
+    }
 }
 
 template <int NT>
 static void dispatch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
-                             const uint8_t *qluts, int nq, int cap, int R, uint64_t *part,
+                             const uint8_t *qluts, int nq, int cap, int R, char *ws,
                              hipStream_t st)
 {
     switch (p.B) {
-    case 4: launch_scan_u8<4, NT>(p, codes, n, qluts, nq, cap, R, part, st); break;
-    case 8: launch_scan_u8<8, NT>(p, codes, n, qluts, nq, cap, R, part, st); break;
-    case 16: launch_scan_u8<16, NT>(p, codes, n, qluts, nq, cap, R, part, st); break;
-    default: launch_scan_u8<32, NT>(p, codes, n, qluts, nq, cap, R, part, st); break;
+    case 4: launch_scan_u8<4, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
+    case 8: launch_scan_u8<8, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
+    case 16: launch_scan_u8<16, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
+    default: launch_scan_u8<32, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
     }
 }
 
@@ -366,18 +617,26 @@ int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, i
     if (((uintptr_t)codes & 15) != 0) return fail(QADC_EINVAL, "qadc_scan_topk: codes must be 16-byte aligned");
     if (workspace_bytes < p.ws_bytes || !workspace)
         return fail(QADC_ENOMEM, "qadc_scan_topk: workspace %zu < %zu bytes", workspace_bytes, p.ws_bytes);
-    uint64_t *part = (uint64_t *)workspace;
+    if (((uintptr_t)workspace & 255) != 0)
+        return fail(QADC_EINVAL, "qadc_scan_topk: workspace must be 256-byte aligned");
+    char *ws = (char *)workspace;
     for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
         const int nb = min(p.qbatch, nq - q0);
         const uint8_t *ql = qluts + (size_t)q0 * m * 16;
+        if (p.seed_wgs > 0) {
+            prof_begin(QADC_PROF_SEED, st);
+            dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
+            prof_end(QADC_PROF_SEED, st);
+        }
         prof_begin(QADC_PROF_SCAN, st);
-        if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, ql, nb, nbins, R, part, st);
-        else dispatch_scan_u8<512>(p, codes, n, ql, nb, nbins, R, part, st);
+        if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, ql, nb, nbins, R, ws, st);
+        else if (p.NT == 512) dispatch_scan_u8<512>(p, codes, n, ql, nb, nbins, R, ws, st);
+        else dispatch_scan_u8<256>(p, codes, n, ql, nb, nbins, R, ws, st);
         prof_end(QADC_PROF_SCAN, st);
         prof_begin(QADC_PROF_MERGE, st);
-        hipLaunchKernelGGL((merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, part,
-                           (unsigned)(p.G * R), (unsigned)min((int64_t)R, n), R, (uint8_t)nbins, out_idx + (size_t)q0 * R,
-                           out_dist + (size_t)q0 * R);
+        hipLaunchKernelGGL((merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
+                           p.stride, p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n),
+                           R, (uint8_t)nbins, out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
         prof_end(QADC_PROF_MERGE, st);
     }
     QADC_HIP_TRY(hipGetLastError());
@@ -389,6 +648,13 @@ size_t scan_topk_u8_workspace(int64_t n, int m, int nq, int R)
     ScanPlan p;
     if (!make_scan_plan(QADC_U8_4BIT, n, m, nq, R, &p)) return 0;
     return p.ws_bytes;
+}
+
+int workspace_init(void *workspace, size_t bytes, hipStream_t st)
+{
+    if (!workspace && bytes) return fail(QADC_EINVAL, "qadc_workspace_init: null workspace");
+    if (bytes) QADC_HIP_TRY(hipMemsetAsync(workspace, 0, bytes, st));
+    return QADC_OK;
 }
 
 }  // namespace qadc

@@ -43,21 +43,21 @@ __device__ __forceinline__ void select_bin(SelectScratch *sc, unsigned need)
     }
 }
 
-// The `need`-th smallest (1-based, need <= cnt) of keys[0..cnt).  `keys` may be
-// in LDS or in global memory.  Every thread of the workgroup must call this with
-// the same arguments; every thread gets the result.  NBYTES = number of key
-// bytes that can be non-zero.
-template <typename K, int NBYTES>
-__device__ K block_radix_select(const K *keys, unsigned cnt, unsigned need, SelectScratch *sc)
+// The `need`-th smallest (1-based) of the keys enumerated by `each`, a callable that the
+// whole workgroup calls as each(f) and that invokes f(key) once per key, spread over the
+// threads in any way.  At least `need` keys must exist.  Every thread of the workgroup must
+// call this with the same arguments; every thread gets the result.  NBYTES = number of
+// low key bytes that can be non-zero.
+template <typename K, int NBYTES, typename Each>
+__device__ K block_radix_select_each(Each each, unsigned need, SelectScratch *sc)
 {
     K prefix = 0, mask = 0;
     for (int shift = (NBYTES - 1) * 8; shift >= 0; shift -= 8) {
         for (unsigned i = threadIdx.x; i < 256; i += blockDim.x) sc->hist[i] = 0;
         __syncthreads();
-        for (unsigned i = threadIdx.x; i < cnt; i += blockDim.x) {
-            K k = keys[i];
+        each([&](K k) {
             if ((k & mask) == prefix) atomicAdd(&sc->hist[(unsigned)(k >> shift) & 255u], 1u);
-        }
+        });
         __syncthreads();
         select_bin(sc, need);
         __syncthreads();
@@ -67,6 +67,17 @@ __device__ K block_radix_select(const K *keys, unsigned cnt, unsigned need, Sele
         __syncthreads();
     }
     return prefix;
+}
+
+// Same over a flat array keys[0..cnt) in LDS or global memory (need <= cnt).
+template <typename K, int NBYTES>
+__device__ K block_radix_select(const K *keys, unsigned cnt, unsigned need, SelectScratch *sc)
+{
+    return block_radix_select_each<K, NBYTES>(
+        [&](auto f) {
+            for (unsigned i = threadIdx.x; i < cnt; i += blockDim.x) f(keys[i]);
+        },
+        need, sc);
 }
 
 }  // namespace qadc

@@ -239,7 +239,8 @@ def test_scan_topk_is_deterministic_and_launch_shape_free(Q, O):
     ref = gpu_topk(Q, g, qlut[None], 100)
     saved = {k: os.environ.get(k) for k in ("QADC_SCAN_NT", "QADC_SCAN_WGS")}
     try:
-        for nt, wgs in [("512", "1"), ("512", "7"), ("1024", "256"), ("1024", "3"), ("512", "2048")]:
+        for nt, wgs in [("256", "1"), ("512", "7"), ("1024", "256"), ("1024", "3"), ("256", "4096"),
+                        ("512", "1024")]:
             os.environ["QADC_SCAN_NT"], os.environ["QADC_SCAN_WGS"] = nt, wgs
             for _ in range(2):
                 got = gpu_topk(Q, g, qlut[None], 100)
@@ -281,3 +282,27 @@ def test_pq_encode_matches_oracle(Q, O, shape):
     for r, j in bad:
         dist = O.sq_l2(x[r:r + 1, j * dsub:(j + 1) * dsub], cb[j])[0]
         assert abs(dist[wc[r, j]] - dist[gc[r, j]]) <= 1e-5 * dist[wc[r, j]]
+
+
+def test_workspace_is_left_clean_between_calls(Q, O):
+    """One workspace, cleared once, then reused by calls of different sizes and tables."""
+    import torch
+    c = config1()
+    codes, cb = c["codes"], c["codebooks"]
+    g = to_gpu(codes)
+    R = 100
+    nbytes = Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, len(codes), 16, 4, R)
+    ws = torch.full((nbytes,), 0xAB, dtype=torch.uint8, device="cuda:0")  # dirty on purpose
+    Q.qadc_workspace_init(ws)
+    rng = np.random.default_rng(8)
+    for it, (n, nq) in enumerate([(100_000, 4), (5_000, 1), (100_000, 2), (77, 3), (60_001, 4)]):
+        if it % 2 == 0:
+            ql = np.stack([O.quick_adc_tables(cb, y, codes, 200, R)["qlut"] for y in c["queries"][:nq]])
+        else:
+            ql = rng.integers(0, 30, size=(nq, 16, 16)).astype(np.uint8)
+        idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, g, to_gpu(ql), R, workspace=ws, n=n)
+        torch.cuda.synchronize()
+        for iq in range(nq):
+            wi, wd = oracle_topk(codes[:n], ql[iq], R)
+            assert np.array_equal(idx_np(idx)[iq], wi), (it, iq)
+            assert np.array_equal(dist[iq].cpu().numpy(), wd), (it, iq)
