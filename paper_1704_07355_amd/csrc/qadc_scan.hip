@@ -34,7 +34,7 @@ namespace qadc {
 
 constexpr int SCAN_VEC = 2;               // 16-byte loads per thread and tile
 constexpr int SCAN_SLACK = QADC_MAX_R;    // candidate slots beyond one tile
-constexpr int GH_REP = 8;                 // replicas of the grid-wide histogram
+constexpr int GH_REP = 2;                 // replicas of the grid-wide histogram
 constexpr unsigned NO_KEY = 0xffffffffu;
 
 // Per-query control block in the workspace, followed by counts[G] (keys reported by each
@@ -57,6 +57,7 @@ struct ScanShared {
     unsigned ccnt;     // append counter of a compaction
     unsigned tcnt[3];  // append counters of the tiles, used in rotation
     unsigned tau;      // threshold bin published by wave 0
+    unsigned fcnt;     // append counter of the barrier-free pass (may run past the list's end)
 };
 
 __device__ __forceinline__ unsigned byte_of(const uint4 &v, int k)
@@ -127,13 +128,37 @@ __device__ unsigned compact_candidates(unsigned *keys, unsigned cnt, unsigned ke
     return kth;
 }
 
-// The two 16-byte loads of one thread for the tile starting at code t0.
-template <int B, int NT>
+// 16-byte streaming load: the codes are read once per query, so they are fetched with the
+// non-temporal hint and do not displace the tables and candidate lists from the caches.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const uint8_t *p)
+{
+    const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// The two 16-byte loads of one thread for the tile starting at code t0.  FULL: the whole
+// tile lies inside the database (t0 + TILE <= c1), no bounds to check.
+template <int B, int NT, bool FULL = false>
 __device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int64_t t0, int64_t c1,
                                           uint4 (&w)[2], int (&nc)[2])
 {
     const int tid = threadIdx.x;
-    if constexpr (B <= 16) {
+    if constexpr (FULL) {
+        if constexpr (B <= 16) {
+            constexpr int CPV = 16 / B;
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                w[v] = stream_load16(codes + (t0 + ((int64_t)v * NT + tid) * CPV) * B);
+                nc[v] = CPV;
+            }
+        } else {
+            w[0] = stream_load16(codes + (t0 + tid) * B);
+            w[1] = stream_load16(codes + (t0 + tid) * B + 16);
+            nc[0] = 1;
+            nc[1] = 0;
+        }
+    } else if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
 #pragma unroll
         for (int v = 0; v < 2; ++v) {
@@ -141,7 +166,7 @@ __device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int
             w[v] = make_uint4(0, 0, 0, 0);
             nc[v] = 0;
             if (base + CPV <= c1) {
-                w[v] = *reinterpret_cast<const uint4 *>(codes + base * B);
+                w[v] = stream_load16(codes + base * B);
                 nc[v] = CPV;
             } else if (base < c1) {  // ragged end of the database: byte loads, no read past the end
                 nc[v] = (int)(c1 - base);
@@ -156,15 +181,24 @@ __device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int
         w[0] = w[1] = make_uint4(0, 0, 0, 0);
         nc[0] = nc[1] = 0;
         if (i < c1) {
-            w[0] = *reinterpret_cast<const uint4 *>(codes + i * B);
-            w[1] = *reinterpret_cast<const uint4 *>(codes + i * B + 16);
+            w[0] = stream_load16(codes + i * B);
+            w[1] = stream_load16(codes + i * B + 16);
             nc[0] = 1;
         }
     }
 }
 
-// Lookups, sum, clamp, key = sum << 24 | index inside the chunk (NO_KEY where no code).
-template <int B, int NT>
+// One pair-table entry, known to the compiler as a byte value.
+__device__ __forceinline__ unsigned pair_entry(const uint8_t *ptab, int jb, unsigned v)
+{
+    const unsigned e = ptab[jb * 256 + v];
+    __builtin_assume(e < 256u);
+    return e;
+}
+
+// Lookups, sum, clamp, key = sum << 24 | index among the workgroup's codes (NO_KEY where no
+// code; FULL: every slot of the tile holds a code).
+template <int B, int NT, bool FULL = false>
 __device__ __forceinline__ void tile_keys(const uint4 (&w)[2], const int (&nc)[2], unsigned rel0,
                                           const uint8_t *ptab, unsigned cap,
                                           unsigned (&k)[ScanCfg<B, NT>::CPT])
@@ -174,24 +208,25 @@ __device__ __forceinline__ void tile_keys(const uint4 (&w)[2], const int (&nc)[2
         constexpr int CPV = 16 / B;
 #pragma unroll
         for (int v = 0; v < 2; ++v) {
+            const unsigned li0 = rel0 + (unsigned)((v * NT + tid) * CPV);
 #pragma unroll
             for (int c = 0; c < CPV; ++c) {
                 unsigned s = 0;
 #pragma unroll
-                for (int jb = 0; jb < B; ++jb) s += ptab[jb * 256 + byte_of(w[v], c * B + jb)];
+                for (int jb = 0; jb < B; ++jb) s += pair_entry(ptab, jb, byte_of(w[v], c * B + jb));
                 s = min(s, cap);
-                const unsigned li = rel0 + (unsigned)((v * NT + tid) * CPV + c);
-                k[v * CPV + c] = (c < nc[v]) ? ((s << 24) | li) : NO_KEY;
+                const unsigned key = (s << 24) | (li0 + c);
+                k[v * CPV + c] = (FULL || c < nc[v]) ? key : NO_KEY;
             }
         }
     } else {
         unsigned s = 0;
 #pragma unroll
-        for (int jb = 0; jb < 16; ++jb) s += ptab[jb * 256 + byte_of(w[0], jb)];
+        for (int jb = 0; jb < 16; ++jb) s += pair_entry(ptab, jb, byte_of(w[0], jb));
 #pragma unroll
-        for (int jb = 0; jb < 16; ++jb) s += ptab[(16 + jb) * 256 + byte_of(w[1], jb)];
+        for (int jb = 0; jb < 16; ++jb) s += pair_entry(ptab, 16 + jb, byte_of(w[1], jb));
         s = min(s, cap);
-        k[0] = nc[0] ? ((s << 24) | (rel0 + (unsigned)tid)) : NO_KEY;
+        k[0] = (FULL || nc[0]) ? ((s << 24) | (rel0 + (unsigned)tid)) : NO_KEY;
     }
 }
 
@@ -262,34 +297,49 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
     }
 }
 
-// Scan kernel: workgroup g streams codes [g*chunk, (g+1)*chunk) of query blockIdx.y.
+// Scan kernel.  The database is cut into tiles of TILE codes; workgroup g of G takes tiles
+// g, g+G, g+2G, ... so that at any moment the grid reads one contiguous window of HBM.
+// A candidate key is sum << 24 | (it * TILE + offset in tile), `it` counting the workgroup's
+// own tiles: inside a workgroup that order is the order of the global indices.
+//
+// With a grid-wide bound from the seed kernel the pass is barrier-free: keys at or below
+// the bound (a handful per workgroup) are appended to the LDS list with one atomic per
+// wavefront.  If the list ever overflows, or when there is no bound (small databases),
+// the workgroup runs the careful pass instead: one barrier per tile, the first tile
+// histogrammed for a bound of its own, the list cut back to its R smallest keys by an exact
+// radix select whenever it fills up -- so the result never depends on the bound being
+// good, only the speed does.
 template <int B, int NT>
-__global__ __launch_bounds__(NT, 8) void scan_u8_kernel(
+__global__ __launch_bounds__(NT) void scan_u8_kernel(
     const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, int64_t chunk, int has_seed, char *__restrict__ ws, size_t ws_stride,
-    size_t counts_off, size_t lists_off)
+    int R, int has_seed, char *__restrict__ ws, size_t ws_stride, size_t counts_off,
+    size_t lists_off)
 {
     using C = ScanCfg<B, NT>;
     __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
+    __shared__ __attribute__((aligned(16))) uint8_t qlut_s[2 * B * 16];
     __shared__ unsigned keys[C::CAP];
     __shared__ ScanShared sh;
 
     const int tid = threadIdx.x;
     const int q = blockIdx.y;
     const int g = blockIdx.x;
+    const int64_t G = gridDim.x;
     const unsigned cap = (unsigned)cap_i;
     const ScanHeader *hdr = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride);
+    if ((int64_t)g * C::TILE >= n) return;  // uniform: no tile for this workgroup
 
-    const int64_t c0 = (int64_t)g * chunk;
-    const int64_t c1 = min(n, c0 + chunk);
-    if (c0 >= c1) return;  // uniform: nothing to scan, nothing to report
+    uint4 w[2];
+    int nc[2];
+    tile_load<B, NT>(codes, (int64_t)g * C::TILE, n, w, nc);  // first tile: in flight during set-up
 
-    uint4 w[2], wn[2];
-    int nc[2], ncn[2];
-    tile_load<B, NT>(codes, c0, c1, w, nc);
-
-    // Grid-wide bound left by the seed kernel: the bin where the running count of the summed
-    // replicas reaches R, or 256.
+    // quantized tables -> LDS, and the grid-wide bound left by the seed kernel: the bin where
+    // the running count of the summed replicas reaches R, or 256.
+    {
+        const uint8_t *qlut = qluts + (size_t)q * (2 * B) * 16;
+        for (int e = tid; e < 2 * B * 4; e += NT)
+            reinterpret_cast<unsigned *>(qlut_s)[e] = reinterpret_cast<const unsigned *>(qlut)[e];
+    }
     if (tid < WAVE) {
         unsigned t = 256, carry = 0;
         for (unsigned b0 = 0; b0 < 256 && has_seed; b0 += 128) {  // uniform
@@ -306,66 +356,95 @@ __global__ __launch_bounds__(NT, 8) void scan_u8_kernel(
             if (hit < 128u) { t = b0 + hit; break; }
             carry += tot;  // still below R
         }
-        if (tid == 0) sh.tau = t;
+        if (tid == 0) { sh.tau = t; sh.fcnt = 0; sh.tcnt[0] = 0; }
     }
-    build_pair_tables<B, NT>(qluts + (size_t)q * (2 * B) * 16, cap, ptab);
     for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
-    if (tid == 0) sh.tcnt[0] = 0;
+    __syncthreads();
+    for (int e = tid; e < B * 256; e += NT) {
+        const int jb = e >> 8, v = e & 255;
+        const unsigned s = (unsigned)qlut_s[(2 * jb) * 16 + (v & 15)] +
+                           (unsigned)qlut_s[(2 * jb + 1) * 16 + (v >> 4)];
+        ptab[e] = (uint8_t)min(s, cap);
+    }
     __syncthreads();
 
     const bool seeded = sh.tau < 256u;  // uniform
     unsigned lim = seeded ? limit_of_bin(sh.tau) : NO_KEY;  // keys >= lim cannot be among the R best
-    unsigned have = 0;  // candidates in keys[] before the current tile (uniform)
-    int rot = 0;
+    unsigned have = 0;  // candidates in keys[] (uniform)
+    bool careful = !seeded;
 
-    // One barrier per tile: the tile's appends go through counter tcnt[rot]; after the
-    // barrier everybody adds its final value to `have`.  The counter of the next tile
-    // is cleared one tile ahead, when no wave can still be reading or bumping it.
-    for (int64_t t0 = c0; t0 < c1; t0 += C::TILE) {
-        unsigned *ctr = &sh.tcnt[rot];
-        const int nxt = (rot == 2) ? 0 : rot + 1;
-        if (tid == 0) sh.tcnt[nxt] = 0;
-        const bool more = t0 + C::TILE < c1;
-        if (more) tile_load<B, NT>(codes, t0 + C::TILE, c1, wn, ncn);
-
-        unsigned k[C::CPT];
-        tile_keys<B, NT>(w, nc, (unsigned)(t0 - c0), ptab, cap, k);
-
-        if (t0 == c0 && !seeded) {
-            // No grid-wide bound (small database): bound the chunk by its own first tile.
-            // Histogram of the tile's unsaturated sums -> the bin holding its R-th smallest.
-#pragma unroll
-            for (int c = 0; c < C::CPT; ++c)
-                if ((k[c] >> 24) < cap) atomicAdd(&sh.sel.hist[k[c] >> 24], 1u);
-            __syncthreads();
-            if (tid < WAVE) {
-                unsigned h[4];
-#pragma unroll
-                for (int b = 0; b < 4; ++b) h[b] = sh.sel.hist[4 * tid + b];
-                const unsigned t = wave_threshold_bin<4>(h, (unsigned)R);
-                if (tid == 0) sh.tau = min(t, cap);
+    if (seeded) {
+        // barrier-free pass
+        unsigned rel = 0;
+        for (int64_t t0 = (int64_t)g * C::TILE; t0 < n; t0 += G * C::TILE, rel += C::TILE) {
+            unsigned k[C::CPT];
+            if (t0 + C::TILE <= n) {  // uniform: a whole tile, no bounds to check
+                if (rel) tile_load<B, NT, true>(codes, t0, n, w, nc);
+                tile_keys<B, NT, true>(w, nc, rel, ptab, cap, k);
+            } else {
+                if (rel) tile_load<B, NT>(codes, t0, n, w, nc);
+                tile_keys<B, NT>(w, nc, rel, ptab, cap, k);
             }
-            __syncthreads();
-            lim = limit_of_bin(sh.tau);
-        }
-
 #pragma unroll
-        for (int c = 0; c < C::CPT; ++c) {
-            const bool pass = k[c] < lim;
-            const unsigned slot = have + wave_append_slot(pass, ctr);
-            if (pass) keys[slot] = k[c];
+            for (int c = 0; c < C::CPT; ++c) {
+                const bool pass = k[c] < lim;
+                const unsigned slot = wave_append_slot(pass, &sh.fcnt);
+                if (pass && slot < (unsigned)C::CAP) keys[slot] = k[c];
+            }
         }
         __syncthreads();
-        have += *ctr;
-        rot = nxt;
-        if (have > (unsigned)SCAN_SLACK) {  // the next tile might not fit: keep the R best
-            const unsigned kth = compact_candidates<NT, C::CAP>(keys, have, (unsigned)R, &sh);
-            lim = min(lim, kth + 1u);  // keys are unique: later ones must be below the R-th kept
-            have = (unsigned)R;
-        }
-        if (more) {
-            w[0] = wn[0]; w[1] = wn[1];
-            nc[0] = ncn[0]; nc[1] = ncn[1];
+        have = sh.fcnt;
+        careful = have > (unsigned)C::CAP;  // keys were dropped: start over, carefully
+        if (careful) tile_load<B, NT>(codes, (int64_t)g * C::TILE, n, w, nc);
+    }
+
+    if (careful) {
+        // One barrier per tile: the tile's appends go through counter tcnt[rot]; after the
+        // barrier everybody adds its final value to `have`.  The counter of the next tile
+        // is cleared one tile ahead, when no wave can still be reading or bumping it.
+        have = 0;
+        int rot = 0;
+        unsigned rel = 0;
+        for (int64_t t0 = (int64_t)g * C::TILE; t0 < n; t0 += G * C::TILE, rel += C::TILE) {
+            unsigned *ctr = &sh.tcnt[rot];
+            const int nxt = (rot == 2) ? 0 : rot + 1;
+            if (tid == 0) sh.tcnt[nxt] = 0;
+            if (rel) tile_load<B, NT>(codes, t0, n, w, nc);
+            unsigned k[C::CPT];
+            tile_keys<B, NT>(w, nc, rel, ptab, cap, k);
+
+            if (rel == 0 && !seeded) {
+                // No grid-wide bound: bound the workgroup's share by its own first tile.
+                // Histogram of the tile's unsaturated sums -> the bin of its R-th smallest.
+#pragma unroll
+                for (int c = 0; c < C::CPT; ++c)
+                    if ((k[c] >> 24) < cap) atomicAdd(&sh.sel.hist[k[c] >> 24], 1u);
+                __syncthreads();
+                if (tid < WAVE) {
+                    unsigned h[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) h[b] = sh.sel.hist[4 * tid + b];
+                    const unsigned t = wave_threshold_bin<4>(h, (unsigned)R);
+                    if (tid == 0) sh.tau = min(t, cap);
+                }
+                __syncthreads();
+                lim = limit_of_bin(sh.tau);
+            }
+
+#pragma unroll
+            for (int c = 0; c < C::CPT; ++c) {
+                const bool pass = k[c] < lim;
+                const unsigned slot = have + wave_append_slot(pass, ctr);
+                if (pass) keys[slot] = k[c];
+            }
+            __syncthreads();
+            have += *ctr;
+            rot = nxt;
+            if (have > (unsigned)SCAN_SLACK) {  // the next tile might not fit: keep the R best
+                const unsigned kth = compact_candidates<NT, C::CAP>(keys, have, (unsigned)R, &sh);
+                lim = min(lim, kth + 1u);  // keys are unique: later ones must be below the R-th kept
+                have = (unsigned)R;
+            }
         }
     }
 
@@ -379,7 +458,9 @@ __global__ __launch_bounds__(NT, 8) void scan_u8_kernel(
     if (tid == 0) counts[g] = have;
     for (unsigned i = tid; i < have; i += NT) {
         const unsigned key = keys[i];
-        dst[i] = ((uint64_t)(key >> 24) << 32) | (uint64_t)(c0 + (key & 0xffffffu));
+        const uint64_t rel = key & 0xffffffu;
+        const uint64_t idx = ((rel / C::TILE) * (uint64_t)G + (uint64_t)g) * C::TILE + rel % C::TILE;
+        dst[i] = ((uint64_t)(key >> 24) << 32) | idx;
     }
 }
 
@@ -514,20 +595,20 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
     if (!(m == 8 || m == 16 || m == 32 || m == 64)) return false;
     if (n < 0 || n > 0xfffffffell || nq < 1 || R < 1 || R > QADC_MAX_R) return false;
     p->B = m / 2;
-    const int nt = env_int("QADC_SCAN_NT", 1024);
-    p->NT = (nt == 256 || nt == 512) ? nt : 1024;
+    const int nt = env_int("QADC_SCAN_NT", 256);
+    p->NT = (nt == 1024 || nt == 512) ? nt : 256;
     const int cpt = (p->B <= 16) ? SCAN_VEC * (16 / p->B) : 1;
     const int tile = p->NT * cpt;
-    // chunks start on 16-code boundaries (16-byte aligned for every code size) and stay
-    // below 2^24 codes, the range of the index bits of a candidate key
-    int64_t G = env_int("QADC_SCAN_WGS", 512);
+    const int64_t tiles = n > 0 ? ceil_div(n, tile) : 1;
+    // every workgroup takes tiles g, g+G, ...; its tiles must number below 2^24 / tile, the
+    // range of the index bits of a candidate key
+    int64_t G = env_int("QADC_SCAN_WGS", 2048);
     if (G < 1) G = 1;
-    const int64_t max_chunk = (1ll << 24) - 16;
-    int64_t chunk = n > 0 ? ceil_div(ceil_div(n, G), 16) * 16 : 16;
-    if (chunk < tile) chunk = tile;  // no point in splitting below one tile
-    if (chunk > max_chunk) chunk = max_chunk;
-    p->chunk = chunk;
-    p->G = (int)(n > 0 ? ceil_div(n, chunk) : 1);
+    if (G > tiles) G = tiles;
+    const int64_t max_tiles_per_wg = ((1ll << 24) - 1) / tile;
+    if (ceil_div(tiles, G) > max_tiles_per_wg) G = ceil_div(tiles, max_tiles_per_wg);
+    p->G = (int)G;
+    p->chunk = 0;
     // Seed kernel: worth its launch once the database is many tiles long.  It samples up to
     // SEED_WGS tiles of 1024-thread workgroups, spread evenly; each reports a few times its
     // share of R codes to the grid-wide histogram.
@@ -565,7 +646,7 @@ static void launch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, c
 {
     dim3 grid(p.G, nq);
     hipLaunchKernelGGL((scan_u8_kernel<B, NT>), grid, dim3(NT), 0, st, codes, n, qluts, cap, R,
-                       p.chunk, p.seed_wgs > 0 ? 1 : 0, ws, p.stride, p.counts_off, p.lists_off);
+                       p.seed_wgs > 0 ? 1 : 0, ws, p.stride, p.counts_off, p.lists_off);
 }
 
 static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
@@ -615,6 +696,7 @@ int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, i
                     (long long)n, m, nq, R);
     if (nbins < 1 || nbins > 255) return fail(QADC_EINVAL, "qadc_scan_topk: nbins=%d not in 1..255", nbins);
     if (((uintptr_t)codes & 15) != 0) return fail(QADC_EINVAL, "qadc_scan_topk: codes must be 16-byte aligned");
+    if (((uintptr_t)qluts & 3) != 0) return fail(QADC_EINVAL, "qadc_scan_topk: luts must be 4-byte aligned");
     if (workspace_bytes < p.ws_bytes || !workspace)
         return fail(QADC_ENOMEM, "qadc_scan_topk: workspace %zu < %zu bytes", workspace_bytes, p.ws_bytes);
     if (((uintptr_t)workspace & 255) != 0)

@@ -306,3 +306,36 @@ def test_workspace_is_left_clean_between_calls(Q, O):
             wi, wd = oracle_topk(codes[:n], ql[iq], R)
             assert np.array_equal(idx_np(idx)[iq], wi), (it, iq)
             assert np.array_equal(dist[iq].cpu().numpy(), wd), (it, iq)
+
+
+@pytest.mark.parametrize("kind", ["mixture", "zeros", "decreasing", "binary", "global_offset"])
+def test_scan_topk_large_enough_for_the_seed_kernel(Q, O, kind):
+    """Databases long enough for the sampling kernel: good bound, useless bound (every code ties:
+    the barrier-free pass overflows and the careful pass takes over), adversarial order."""
+    rng = np.random.default_rng(77)
+    n, m, R = 700_003, 16, 100
+    if kind == "mixture":
+        c = config1()
+        reps = -(-n // len(c["codes"]))
+        codes = np.tile(c["codes"], (reps, 1))[:n].copy()
+        codes[::7] = rng.integers(0, 256, size=codes[::7].shape, dtype=np.uint8)
+        ql = O.quick_adc_tables(c["codebooks"], c["queries"][3], codes, 200, R)["qlut"]
+    elif kind == "zeros":
+        codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+        ql = np.zeros((m, 16), dtype=np.uint8)
+    elif kind == "binary":
+        codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+        ql = rng.integers(0, 2, size=(m, 16)).astype(np.uint8)
+    elif kind == "global_offset":  # every sum >= 16 * 9: the low bins of the histogram stay empty
+        codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+        ql = (9 + rng.integers(0, 6, size=(m, 16))).astype(np.uint8)
+    else:
+        codes = np.zeros((n, m // 2), dtype=np.uint8)
+        lvl = (np.arange(n)[::-1] * 240 // n).astype(np.int64)
+        codes[:, 0] = (lvl % 16) | ((lvl // 16) << 4)
+        ql = np.zeros((m, 16), dtype=np.uint8)
+        ql[0] = np.arange(16)
+        ql[1] = np.arange(16) * 16
+    gi, gd = gpu_topk(Q, to_gpu(codes), ql[None], R)
+    wi, wd = oracle_topk(codes, ql, R)
+    assert np.array_equal(gi[0], wi) and np.array_equal(gd[0], wd)
