@@ -60,8 +60,9 @@ extern "C" {
 #define QADC_F32_8BIT   2 /* Alg. 1: 8-bit codes (ksub = 256), float tables          */
 
 /* which call a workspace is for (qadc_workspace_bytes) */
-#define QADC_WS_SCAN_TOPK 0
-#define QADC_WS_QUANTIZE  1
+#define QADC_WS_SCAN_TOPK      0 /* qadc_scan_topk, variant QADC_U8_4BIT  */
+#define QADC_WS_SCAN_F32_4BIT  1 /* qadc_scan_topk, variant QADC_F32_4BIT */
+#define QADC_WS_SCAN_F32_8BIT  2 /* qadc_scan_topk, variant QADC_F32_8BIT */
 
 /*
  * Tables step, Eq. (1) of the paper:
@@ -115,12 +116,14 @@ int qadc_quantize_luts(const float *luts, int nq, int ngroup, int m,
  * and the R smallest (dist, i) are written in ascending order.
  *   codes    [n][m/2] u8 (4-bit variants) or [n][m] u8 (8-bit), standard layout
  *   m        4-bit variants: 8, 16, 32 or 64;  8-bit variant: 4, 8, 16 or 32
- *   luts     [nq][m][16] u8, [nq][m][16] f32 or [nq][m][256] f32 by variant
+ *   luts     [nq][m][16] u8, [nq][m][16] f32 or [nq][m][256] f32 by variant (4-byte aligned;
+ *            float tables are expected non-negative, as squared distances are)
  *   nbins    saturation value of the u8 variant (1..255); ignored otherwise
  *   R        1..QADC_MAX_R
  *   out_idx  [nq][R] u32   position i of the code in `codes`
  *   out_dist [nq][R] u8 or f32 by variant
- *   workspace  >= qadc_workspace_bytes(QADC_WS_SCAN_TOPK, n, m, nq, R)
+ *   workspace  >= qadc_workspace_bytes(QADC_WS_SCAN_TOPK | _F32_4BIT | _F32_8BIT, n, m, nq, R),
+ *              by variant; the largest of the three serves every variant
  */
 int qadc_scan_topk(int variant, const void *codes, int64_t n, int m,
                    const void *luts, int nq, int R, int nbins,

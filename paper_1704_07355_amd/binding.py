@@ -21,7 +21,7 @@ QADC_MAX_R = 1024
 QADC_MAX_INIT = 8192
 QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
 QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
-QADC_WS_SCAN_TOPK, QADC_WS_QUANTIZE = 0, 1
+QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT = 0, 1, 2
 QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED = 0, 1, 2
 
 EXPORTS = (
@@ -159,7 +159,8 @@ def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=N
         out_idx = torch.empty((nq, R), dtype=torch.int32, device=dev)  # bit pattern of uint32
     if out_dist is None:
         out_dist = torch.empty((nq, R), dtype=want, device=dev)
-    need = qadc_workspace_bytes(QADC_WS_SCAN_TOPK, n, m, nq, R)
+    need = qadc_workspace_bytes({QADC_U8_4BIT: QADC_WS_SCAN_TOPK, QADC_F32_4BIT: QADC_WS_SCAN_F32_4BIT,
+                                 QADC_F32_8BIT: QADC_WS_SCAN_F32_8BIT}[variant], n, m, nq, R)
     if workspace is None:
         workspace = qadc_workspace_init(torch.empty((max(need, 256),), dtype=torch.uint8, device=dev))
     _check(lib().qadc_scan_topk(variant, _ptr(codes, torch.uint8), n, m, _ptr(luts), nq, R, nbins,

@@ -27,6 +27,9 @@ int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const 
 int scan_topk_u8(const uint8_t *, int64_t, int, const uint8_t *, int, int, int, uint32_t *,
                  uint8_t *, void *, size_t, hipStream_t);
 size_t scan_topk_u8_workspace(int64_t, int, int, int);
+int scan_topk_f32(int, const uint8_t *, int64_t, int, const float *, int, int, uint32_t *, float *,
+                  void *, size_t, hipStream_t);
+size_t scan_topk_f32_workspace(int, int64_t, int, int, int);
 int pq_encode(const float *, int, int, int, const float *, int64_t, uint8_t *, hipStream_t);
 int workspace_init(void *, size_t, hipStream_t);
 
@@ -60,6 +63,11 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void 
         return qadc::scan_topk_u8((const uint8_t *)codes, n, m, (const uint8_t *)luts, nq, R, nbins,
                                   out_idx, (uint8_t *)out_dist, workspace, workspace_bytes,
                                   (hipStream_t)stream);
+    case QADC_F32_4BIT:
+    case QADC_F32_8BIT:
+        return qadc::scan_topk_f32(variant, (const uint8_t *)codes, n, m, (const float *)luts, nq, R,
+                                   out_idx, (float *)out_dist, workspace, workspace_bytes,
+                                   (hipStream_t)stream);
     default:
         return qadc::fail(QADC_EINVAL, "qadc_scan_topk: unknown variant %d", variant);
     }
@@ -82,6 +90,8 @@ size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)
 {
     switch (call) {
     case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(n, m, nq, R);
+    case QADC_WS_SCAN_F32_4BIT: return qadc::scan_topk_f32_workspace(QADC_F32_4BIT, n, m, nq, R);
+    case QADC_WS_SCAN_F32_8BIT: return qadc::scan_topk_f32_workspace(QADC_F32_8BIT, n, m, nq, R);
     default: return 0;
     }
 }

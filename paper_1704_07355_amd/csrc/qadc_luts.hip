@@ -2,7 +2,7 @@
 // (Section 3.3) on gfx950.  Both are tiny next to the scan: one workgroup per
 // query, everything staged in LDS.
 
-#include "qadc_select.h"
+#include "qadc_scan_common.h"
 
 namespace qadc {
 
@@ -55,17 +55,6 @@ int build_luts(const float *codebooks, int d, int m, int ksub, const float *quer
 
 constexpr int QUANT_NT = 256;
 constexpr int QUANT_MAX_M = 64;
-
-// Order-preserving map float -> unsigned (any sign), and back.
-__device__ __forceinline__ unsigned f2ord(float f)
-{
-    const unsigned b = __float_as_uint(f);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-__device__ __forceinline__ float ord2f(unsigned o)
-{
-    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
-}
 
 __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
     const float *__restrict__ luts, int ngroup, int m, const uint8_t *__restrict__ init_codes,

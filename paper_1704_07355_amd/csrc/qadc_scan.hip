@@ -27,30 +27,9 @@
 // The total order (sum, index) is carried by the integer keys, so the result
 // does not depend on how the grid is cut or on the order waves run in.
 
-#include "qadc_select.h"
-#include "qadc_profile.h"
+#include "qadc_scan_common.h"
 
 namespace qadc {
-
-constexpr int SCAN_VEC = 2;               // 16-byte loads per thread and tile
-constexpr int SCAN_SLACK = QADC_MAX_R;    // candidate slots beyond one tile
-constexpr int GH_REP = 2;                 // replicas of the grid-wide histogram
-constexpr unsigned NO_KEY = 0xffffffffu;
-
-// Per-query control block in the workspace, followed by counts[G] (keys reported by each
-// workgroup) and lists[G][R] (the keys).  Block and counts must be all zero when the scan
-// kernel starts; the merge kernel leaves every word the call wrote zeroed again.
-struct alignas(256) ScanHeader {
-    unsigned ghist[GH_REP][256];  // sums of the best codes of every seed tile
-};
-
-template <int B, int NT>
-struct ScanCfg {
-    static constexpr int CPV = (B <= 16) ? 16 / B : 1;            // codes per 16-byte load
-    static constexpr int CPT = (B <= 16) ? SCAN_VEC * CPV : 1;    // codes per thread and tile
-    static constexpr int TILE = NT * CPT;
-    static constexpr int CAP = TILE + SCAN_SLACK;
-};
 
 struct ScanShared {
     SelectScratch sel;
@@ -59,12 +38,6 @@ struct ScanShared {
     unsigned tau;      // threshold bin published by wave 0
     unsigned fcnt;     // append counter of the barrier-free pass (may run past the list's end)
 };
-
-__device__ __forceinline__ unsigned byte_of(const uint4 &v, int k)
-{
-    const unsigned w = (k < 4) ? v.x : (k < 8) ? v.y : (k < 12) ? v.z : v.w;
-    return (w >> (8 * (k & 3))) & 0xffu;
-}
 
 // Keys with sum <= tau are exactly the keys below this limit.
 __device__ __forceinline__ unsigned limit_of_bin(unsigned tau)
@@ -102,93 +75,6 @@ __device__ __forceinline__ unsigned wave_threshold_bin(const unsigned (&h)[NB], 
     return __shfl(bin, first);
 }
 
-// Cuts keys[0..cnt) back to its `keep` smallest keys (cnt > keep) and returns
-// the largest key kept.  Called by every thread of the workgroup.
-template <int NT, int CAP>
-__device__ unsigned compact_candidates(unsigned *keys, unsigned cnt, unsigned keep, ScanShared *sh)
-{
-    const unsigned kth = block_radix_select<unsigned, 4>(keys, cnt, keep, &sh->sel);
-    constexpr int PER = (CAP + NT - 1) / NT;
-    unsigned mine[PER];
-#pragma unroll
-    for (int t = 0; t < PER; ++t) {
-        unsigned i = threadIdx.x + t * NT;
-        mine[t] = (i < cnt) ? keys[i] : NO_KEY;
-    }
-    if (threadIdx.x == 0) sh->ccnt = 0;
-    __syncthreads();
-#pragma unroll
-    for (int t = 0; t < PER; ++t) {
-        unsigned i = threadIdx.x + t * NT;
-        bool ok = (i < cnt) && (mine[t] <= kth);
-        unsigned slot = wave_append_slot(ok, &sh->ccnt);
-        if (ok) keys[slot] = mine[t];
-    }
-    __syncthreads();
-    return kth;
-}
-
-// 16-byte streaming load: the codes are read once per query, so they are fetched with the
-// non-temporal hint and do not displace the tables and candidate lists from the caches.
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 stream_load16(const uint8_t *p)
-{
-    const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
-// The two 16-byte loads of one thread for the tile starting at code t0.  FULL: the whole
-// tile lies inside the database (t0 + TILE <= c1), no bounds to check.
-template <int B, int NT, bool FULL = false>
-__device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int64_t t0, int64_t c1,
-                                          uint4 (&w)[2], int (&nc)[2])
-{
-    const int tid = threadIdx.x;
-    if constexpr (FULL) {
-        if constexpr (B <= 16) {
-            constexpr int CPV = 16 / B;
-#pragma unroll
-            for (int v = 0; v < 2; ++v) {
-                w[v] = stream_load16(codes + (t0 + ((int64_t)v * NT + tid) * CPV) * B);
-                nc[v] = CPV;
-            }
-        } else {
-            w[0] = stream_load16(codes + (t0 + tid) * B);
-            w[1] = stream_load16(codes + (t0 + tid) * B + 16);
-            nc[0] = 1;
-            nc[1] = 0;
-        }
-    } else if constexpr (B <= 16) {
-        constexpr int CPV = 16 / B;
-#pragma unroll
-        for (int v = 0; v < 2; ++v) {
-            const int64_t base = t0 + ((int64_t)v * NT + tid) * CPV;
-            w[v] = make_uint4(0, 0, 0, 0);
-            nc[v] = 0;
-            if (base + CPV <= c1) {
-                w[v] = stream_load16(codes + base * B);
-                nc[v] = CPV;
-            } else if (base < c1) {  // ragged end of the database: byte loads, no read past the end
-                nc[v] = (int)(c1 - base);
-                unsigned tmp[4] = {0, 0, 0, 0};
-                for (int k = 0; k < nc[v] * B; ++k)
-                    tmp[k >> 2] |= (unsigned)codes[base * B + k] << (8 * (k & 3));
-                w[v] = make_uint4(tmp[0], tmp[1], tmp[2], tmp[3]);
-            }
-        }
-    } else {
-        const int64_t i = t0 + tid;
-        w[0] = w[1] = make_uint4(0, 0, 0, 0);
-        nc[0] = nc[1] = 0;
-        if (i < c1) {
-            w[0] = stream_load16(codes + i * B);
-            w[1] = stream_load16(codes + i * B + 16);
-            nc[0] = 1;
-        }
-    }
-}
-
-// One pair-table entry, known to the compiler as a byte value.
 __device__ __forceinline__ unsigned pair_entry(const uint8_t *ptab, int jb, unsigned v)
 {
     const unsigned e = ptab[jb * 256 + v];
@@ -441,7 +327,7 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
             have += *ctr;
             rot = nxt;
             if (have > (unsigned)SCAN_SLACK) {  // the next tile might not fit: keep the R best
-                const unsigned kth = compact_candidates<NT, C::CAP>(keys, have, (unsigned)R, &sh);
+                const unsigned kth = compact_candidates<unsigned, 4, NT, C::CAP>(keys, have, (unsigned)R, &sh.sel, &sh.ccnt);
                 lim = min(lim, kth + 1u);  // keys are unique: later ones must be below the R-th kept
                 have = (unsigned)R;
             }
@@ -449,7 +335,7 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     }
 
     if (have > (unsigned)R) {
-        compact_candidates<NT, C::CAP>(keys, have, (unsigned)R, &sh);
+        compact_candidates<unsigned, 4, NT, C::CAP>(keys, have, (unsigned)R, &sh.sel, &sh.ccnt);
         have = (unsigned)R;
     }
     if (have == 0) return;  // counts[g] stays zero
@@ -464,114 +350,6 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     }
 }
 
-// ---------------------------------------------------------------- merge
-
-constexpr int MERGE_NT = 1024;
-constexpr int MERGE_CAP = 4096;
-
-// R best of the keys reported by the G workgroups of each query (64-bit keys
-// dist << 32 | index, at most R per workgroup), ordered; then everything the call wrote
-// in the workspace is cleared.  KBYTES = significant key bytes (5 for u8 distances).
-// DistT = uint8_t: the distance is the key's bits 32..39; float: bits 32..63.
-template <typename DistT, int KBYTES>
-__global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
-    char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off, int G,
-    unsigned need, int R, DistT pad_dist, uint32_t *__restrict__ out_idx,
-    DistT *__restrict__ out_dist)
-{
-    // need = min(R, number of codes scanned): at least that many keys were reported.
-    __shared__ uint64_t lkeys[MERGE_CAP];
-    __shared__ SelectScratch sc;
-    __shared__ unsigned lcnt;
-
-    const int tid = threadIdx.x;
-    const int q = blockIdx.x;
-    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
-    unsigned *counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + counts_off);
-    uint64_t *lists = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + lists_off);
-
-    // every reported key, spread over the threads by workgroup
-    auto each_key = [&](auto f) {
-        for (int g = tid; g < G; g += MERGE_NT) {
-            const unsigned c = min(counts[g], (unsigned)R);
-            for (unsigned i = 0; i < c; ++i) f(lists[(size_t)g * R + i]);
-        }
-    };
-
-    if (tid == 0) lcnt = 0;
-    __syncthreads();
-    each_key([&](uint64_t k) {
-        const unsigned slot = atomicAdd(&lcnt, 1u);
-        if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
-    });
-    __syncthreads();
-    const unsigned total = lcnt;
-    need = min(need, total);
-    const bool in_lds = total <= (unsigned)MERGE_CAP;
-
-    uint64_t kth = 0;
-    if (need > 0) {
-        if (in_lds) kth = block_radix_select<uint64_t, KBYTES>(lkeys, total, need, &sc);
-        else kth = block_radix_select_each<uint64_t, KBYTES>(each_key, need, &sc);
-    }
-    __syncthreads();
-
-    // gather the `need` keys <= kth into lkeys[0..need), then order them by rank
-    uint64_t mine[MERGE_CAP / MERGE_NT];
-    if (in_lds) {
-#pragma unroll
-        for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
-            const unsigned i = tid + t * MERGE_NT;
-            mine[t] = (i < total) ? lkeys[i] : ~0ull;
-        }
-    }
-    if (tid == 0) lcnt = 0;
-    __syncthreads();
-    if (need > 0) {
-        if (in_lds) {
-#pragma unroll
-            for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
-                const unsigned i = tid + t * MERGE_NT;
-                const bool ok = (i < total) && mine[t] <= kth;
-                const unsigned slot = wave_append_slot(ok, &lcnt);
-                if (ok) lkeys[slot] = mine[t];
-            }
-        } else {
-            each_key([&](uint64_t k) {
-                if (k <= kth) lkeys[atomicAdd(&lcnt, 1u)] = k;  // exactly `need` keys: they are unique
-            });
-        }
-    }
-    __syncthreads();
-
-    for (unsigned i = tid; i < (unsigned)R; i += MERGE_NT) {
-        if (i >= need) {
-            out_idx[(size_t)q * R + i] = 0xffffffffu;
-            out_dist[(size_t)q * R + i] = pad_dist;
-        } else {
-            const uint64_t k = lkeys[i];
-            unsigned rank = 0;
-            for (unsigned j = 0; j < need; ++j) rank += (lkeys[j] < k) ? 1u : 0u;
-            DistT d;
-            if constexpr (sizeof(DistT) == 1) d = (DistT)((k >> 32) & 0xff);
-            else d = __uint_as_float((unsigned)(k >> 32));
-            out_idx[(size_t)q * R + rank] = (uint32_t)k;
-            out_dist[(size_t)q * R + rank] = d;
-        }
-    }
-
-    // Leave every word this call wrote in the workspace zero again, so that the next call
-    // finds clean control blocks wherever its own layout puts them.
-    __syncthreads();
-    for (int g = tid; g < G; g += MERGE_NT) {
-        const unsigned c = min(counts[g], (unsigned)R);
-        for (unsigned i = 0; i < c; ++i) lists[(size_t)g * R + i] = 0;
-        counts[g] = 0;
-    }
-    unsigned *z = &hdr->ghist[0][0];
-    for (int i = tid; i < GH_REP * 256; i += MERGE_NT) z[i] = 0;
-}
-
 // ---------------------------------------------------------------- host
 
 struct ScanPlan {
@@ -582,12 +360,6 @@ struct ScanPlan {
     unsigned flush_need;
     size_t counts_off, lists_off, stride, ws_bytes;
 };
-
-static int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    return (s && *s) ? atoi(s) : dflt;
-}
 
 static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPlan *p)
 {
@@ -628,15 +400,12 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
         if (fl > R) fl = R;
         p->flush_need = (unsigned)fl;
     }
-    p->counts_off = sizeof(ScanHeader);
-    p->lists_off = p->counts_off + align_up((size_t)p->G * sizeof(unsigned), 256);
-    p->stride = p->lists_off + align_up((size_t)p->G * R * sizeof(uint64_t), 256);
-    int64_t qb = (int64_t)((256ull << 20) / p->stride);
-    if (qb < 1) qb = 1;
-    if (qb > nq) qb = nq;
-    if (qb > 65535) qb = 65535;
-    p->qbatch = (int)qb;
-    p->ws_bytes = p->stride * (size_t)qb;
+    const ScanLayout l = scan_layout(p->G, R);
+    p->counts_off = l.counts_off;
+    p->lists_off = l.lists_off;
+    p->stride = l.stride;
+    p->qbatch = scan_query_batch(p->stride, nq);
+    p->ws_bytes = p->stride * (size_t)p->qbatch;
     return true;
 }
 

@@ -339,3 +339,64 @@ def test_scan_topk_large_enough_for_the_seed_kernel(Q, O, kind):
     gi, gd = gpu_topk(Q, to_gpu(codes), ql[None], R)
     wi, wd = oracle_topk(codes, ql, R)
     assert np.array_equal(gi[0], wi) and np.array_equal(gd[0], wd)
+
+
+# ------------------------------------------------------- float ADC (Alg. 1)
+
+def gpu_topk_f32(Q, variant, codes_gpu, luts, R, n=None):
+    import torch
+    idx, dist = Q.qadc_scan_topk(variant, codes_gpu, to_gpu(luts), R, n=n)
+    torch.cuda.synchronize()
+    return idx_np(idx), dist.cpu().numpy()
+
+
+def test_float_adc_scan_config1_bit_exact(Q, O):
+    """Alg. 1 on 4-bit codes: float32 sums in increasing j on both sides -> identical bits."""
+    from oracle import cref
+    c = config1()
+    luts = O.build_luts(c["codebooks"], c["queries"])
+    gi, gd = gpu_topk_f32(Q, Q.QADC_F32_4BIT, to_gpu(c["codes"]), luts, 100)
+    wi, wd = cref.scan_topk_f32(c["codes"], luts, 100)
+    assert np.array_equal(gi, wi)
+    assert np.array_equal(gd.view(np.uint32), wd.view(np.uint32))
+
+
+def test_float_adc_scan_8bit_codes(Q, O):
+    """Config-5-shaped baseline: d=96, m=8 x 256 centroids, float tables of 8 KiB."""
+    from oracle import cref
+    from workloads import MixtureSpec, mixture_vectors, SEED_BASE, SEED_TRAIN, SEED_QUERY
+    spec = MixtureSpec(d=96)
+    train = mixture_vectors(spec, SEED_TRAIN, 0, 3000)
+    rows = np.random.default_rng(0).permutation(3000)[:256]
+    cb = np.stack([O.kmeans_lloyd(train[:, j * 12:(j + 1) * 12], rows, 2)[0] for j in range(8)])
+    base = mixture_vectors(spec, SEED_BASE, 0, 60_007)
+    codes = cref.pq_encode(base, cb)
+    queries = mixture_vectors(spec, SEED_QUERY, 0, 5)
+    luts = O.build_luts(cb, queries)
+    assert luts.shape == (5, 8, 256)
+    g_luts = Q.qadc_build_luts(to_gpu(cb), to_gpu(queries)).cpu().numpy()
+    np.testing.assert_allclose(g_luts, luts, rtol=1e-4)
+    gi, gd = gpu_topk_f32(Q, Q.QADC_F32_8BIT, to_gpu(codes), luts, 100)
+    wi, wd = cref.scan_topk_f32(codes, luts, 100)
+    assert np.array_equal(gi, wi)
+    assert np.array_equal(gd.view(np.uint32), wd.view(np.uint32))
+
+
+@pytest.mark.parametrize("variant_m", [("4", 8), ("4", 16), ("4", 32), ("4", 64),
+                                       ("8", 4), ("8", 8), ("8", 16), ("8", 32)])
+@pytest.mark.parametrize("n", [0, 37, 2049, 30_011])
+def test_float_adc_scan_shapes(Q, variant_m, n):
+    from oracle import cref
+    bits, m = variant_m
+    k = 16 if bits == "4" else 256
+    variant = Q.QADC_F32_4BIT if bits == "4" else Q.QADC_F32_8BIT
+    row = m // 2 if k == 16 else m
+    rng = np.random.default_rng(m * 131 + n + k)
+    codes = rng.integers(0, 256, size=(n, row), dtype=np.uint8)
+    luts = rng.uniform(0, 1000, size=(2, m, k)).astype(np.float32)
+    luts[1] = np.floor(luts[1] / 250)  # few distinct values: many exact ties
+    g = to_gpu(codes) if n else to_gpu(np.zeros((1, row), dtype=np.uint8))
+    gi, gd = gpu_topk_f32(Q, variant, g, luts, 64, n=n)
+    wi, wd = cref.scan_topk_f32(codes, luts, 64)
+    assert np.array_equal(gi, wi), (bits, m, n)
+    assert np.array_equal(gd.view(np.uint32), wd.view(np.uint32)), (bits, m, n)
