@@ -131,6 +131,49 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m,
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Inverted index (Section 2.2): K cells around the coarse centroids; the codes of the
+ * RESIDUALS x - centroid of a cell's vectors are stored contiguously (one inverted list per
+ * cell, cell c holding storage positions list_off[c] .. list_off[c+1]-1), with the vector
+ * id of every position.  The struct itself lives in HOST memory; its pointers are device
+ * pointers.
+ */
+typedef struct qadc_ivf_index {
+    const float *coarse;      /* [K][d] f32 coarse centroids                         */
+    const int64_t *list_off;  /* [K+1] i64, list_off[0] = 0, list_off[K] = n         */
+    const uint8_t *codes;     /* [n][m/2] u8, standard layout, in list order, 16-byte aligned */
+    const uint32_t *ids;      /* [n] u32 vector id of each storage position          */
+    const float *codebooks;   /* [m][16][d/m] f32 product quantizer of the residuals */
+    int d, m, K;
+    int64_t n;
+} qadc_ivf_index;
+
+/*
+ * Non-exhaustive Quick ADC search, Section 2.3 with the tables quantized as in Section 3.3.
+ * For each query: Index (the nprobe closest cells by squared distance to the coarse
+ * centroids, float32, closest first, ties to the lowest cell id; or the cells given in
+ * probes_in), Tables (Eq. (1) on the residual y - centroid, one set of m tables per cell),
+ * qmax (the min(R, n_walk)-th smallest float ADC distance of the first n_walk = min(init,
+ * codes in the probed lists) codes met walking the lists in probe order, each with its own
+ * cell's tables), ONE quantizer for the query shared by its nprobe table sets (as
+ * qadc_quantize_luts with ngroup = nprobe), Scan of every code of every probed list with
+ * saturating sums, and the R smallest under the order (sum, storage position).
+ *   queries    [nq][d] f32
+ *   nprobe     1..256 (the paper's `ma`); init 1..QADC_MAX_INIT; nbins 1..255; R 1..QADC_MAX_R
+ *   probes_in  [nq][nprobe] i32 or NULL; a negative entry is an unused slot
+ *   out_ids    [nq][R] u32   ids[position] of the neighbours (0xFFFFFFFF padding)
+ *   out_dist   [nq][R] u8    their quantized sums (nbins padding)
+ *   dbg_probes [nq][nprobe] i32 or NULL: the cells scanned      (output, for replay/tests)
+ *   dbg_qluts  [nq][nprobe][m][16] u8 or NULL: the tables used  (output, for replay/tests)
+ *   workspace  >= qadc_ivf_workspace_bytes(ix, nq, nprobe, R), cleared once as above
+ */
+int qadc_ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprobe, int R,
+                    int init, int nbins, int qmin_mode, const int32_t *probes_in,
+                    uint32_t *out_ids, uint8_t *out_dist, int32_t *dbg_probes, uint8_t *dbg_qluts,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+size_t qadc_ivf_workspace_bytes(const qadc_ivf_index *ix, int nq, int nprobe, int R);
+
+/*
  * Database side, Section 2.1: enc(x) = (i_0 .. i_{m-1}), i_j = index of the centroid of
  * sub-quantizer j closest to sub-vector x^j (float32 distances from the differences,
  * ties to the lowest index), written in the standard layout.  Not on the query
@@ -152,7 +195,9 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
 #define QADC_PROF_SCAN   0  /* code-streaming kernel of qadc_scan_topk */
 #define QADC_PROF_MERGE  1  /* cross-workgroup top-R kernel of qadc_scan_topk */
 #define QADC_PROF_SEED   2  /* sampling kernel of qadc_scan_topk (large databases only) */
-#define QADC_PROF_COUNT  3
+#define QADC_PROF_IVF_INDEX  3  /* Index step of qadc_ivf_search (coarse distances, cell choice) */
+#define QADC_PROF_IVF_TABLES 4  /* Tables step of qadc_ivf_search (tables, qmax, quantization)   */
+#define QADC_PROF_COUNT  5
 int qadc_profile_enable(int on);
 int qadc_profile_read(int which, double *total_ms, int64_t *launches);
 

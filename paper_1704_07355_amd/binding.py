@@ -22,15 +22,23 @@ QADC_MAX_INIT = 8192
 QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
 QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
 QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT = 0, 1, 2
-QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED = 0, 1, 2
+QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES = 0, 1, 2, 3, 4
 
 EXPORTS = (
-    "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_pq_encode",
+    "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_ivf_search",
+    "qadc_ivf_workspace_bytes", "qadc_pq_encode",
     "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version",
 )
 
 _lib = None
+
+
+class qadc_ivf_index(ctypes.Structure):
+    """Mirror of the C struct: device pointers + shapes (include/qadc.h)."""
+    _fields_ = [("coarse", ctypes.c_void_p), ("list_off", ctypes.c_void_p), ("codes", ctypes.c_void_p),
+                ("ids", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("d", ctypes.c_int),
+                ("m", ctypes.c_int), ("K", ctypes.c_int), ("n", ctypes.c_int64)]
 
 
 class QadcError(RuntimeError):
@@ -54,6 +62,11 @@ def lib() -> ctypes.CDLL:
         L.qadc_quantize_luts.restype = i32
         L.qadc_scan_topk.argtypes = [i32, vp, i64, i32, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.qadc_scan_topk.restype = i32
+        L.qadc_ivf_search.argtypes = [ctypes.POINTER(qadc_ivf_index), vp, i32, i32, i32, i32, i32, i32,
+                                      vp, vp, vp, vp, vp, vp, sz, vp]
+        L.qadc_ivf_search.restype = i32
+        L.qadc_ivf_workspace_bytes.argtypes = [ctypes.POINTER(qadc_ivf_index), i32, i32, i32]
+        L.qadc_ivf_workspace_bytes.restype = sz
         L.qadc_pq_encode.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp]
         L.qadc_pq_encode.restype = i32
         L.qadc_profile_enable.argtypes = [i32]
@@ -190,3 +203,44 @@ def qadc_profile_read(which: int):
     ms, cnt = ctypes.c_double(0), ctypes.c_int64(0)
     _check(lib().qadc_profile_read(which, ctypes.byref(ms), ctypes.byref(cnt)))
     return ms.value, cnt.value
+
+
+class IvfIndex:
+    """Holds the tensors of an inverted index on the GPU and the C struct that points at them."""
+
+    def __init__(self, coarse, list_off, codes, ids, codebooks):
+        K, d = coarse.shape
+        m = codebooks.shape[0]
+        assert codebooks.shape[1] == 16 and codes.shape[1] == m // 2
+        assert list_off.dtype == torch.int64 and list_off.numel() == K + 1
+        assert ids.dtype == torch.int32 or ids.dtype == torch.uint32
+        self.tensors = (coarse, list_off, codes, ids, codebooks)  # keep alive
+        self.c = qadc_ivf_index(_ptr(coarse, torch.float32).value, _ptr(list_off).value,
+                                _ptr(codes, torch.uint8).value, _ptr(ids).value,
+                                _ptr(codebooks, torch.float32).value, d, m, K, codes.shape[0])
+        self.d, self.m, self.K, self.n = d, m, K, codes.shape[0]
+
+
+def qadc_ivf_workspace_bytes(index: IvfIndex, nq: int, nprobe: int, R: int) -> int:
+    return int(lib().qadc_ivf_workspace_bytes(ctypes.byref(index.c), nq, nprobe, R))
+
+
+def qadc_ivf_search(index: IvfIndex, queries, nprobe, R, init, nbins=255,
+                    qmin_mode=QADC_QMIN_PER_TABLE, probes_in=None, workspace=None, debug=False):
+    """-> (ids i32-bits-of-u32 [nq][R], dist u8 [nq][R][, probes i32 [nq][nprobe], qluts u8 [nq][nprobe][m][16]])."""
+    nq = queries.shape[0]
+    dev = queries.device
+    out_ids = torch.empty((nq, R), dtype=torch.int32, device=dev)
+    out_dist = torch.empty((nq, R), dtype=torch.uint8, device=dev)
+    dbg_p = torch.empty((nq, nprobe), dtype=torch.int32, device=dev) if debug else None
+    dbg_q = torch.empty((nq, nprobe, index.m, 16), dtype=torch.uint8, device=dev) if debug else None
+    need = qadc_ivf_workspace_bytes(index, nq, nprobe, R)
+    if workspace is None:
+        workspace = qadc_workspace_init(torch.empty((max(need, 256),), dtype=torch.uint8, device=dev))
+    _check(lib().qadc_ivf_search(ctypes.byref(index.c), _ptr(queries, torch.float32), nq, nprobe, R, init,
+                                 nbins, qmin_mode, _ptr(probes_in, torch.int32), _ptr(out_ids),
+                                 _ptr(out_dist), _ptr(dbg_p), _ptr(dbg_q), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream()))
+    if debug:
+        return out_ids, out_dist, dbg_p, dbg_q
+    return out_ids, out_dist

@@ -32,6 +32,9 @@ int scan_topk_f32(int, const uint8_t *, int64_t, int, const float *, int, int, u
 size_t scan_topk_f32_workspace(int, int64_t, int, int, int);
 int pq_encode(const float *, int, int, int, const float *, int64_t, uint8_t *, hipStream_t);
 int workspace_init(void *, size_t, hipStream_t);
+int ivf_search(const qadc_ivf_index *, const float *, int, int, int, int, int, int, const int32_t *,
+               uint32_t *, uint8_t *, int32_t *, uint8_t *, void *, size_t, hipStream_t);
+size_t ivf_workspace_bytes(const qadc_ivf_index *, int, int, int);
 
 }  // namespace qadc
 
@@ -71,6 +74,21 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void 
     default:
         return qadc::fail(QADC_EINVAL, "qadc_scan_topk: unknown variant %d", variant);
     }
+}
+
+int qadc_ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprobe, int R,
+                    int init, int nbins, int qmin_mode, const int32_t *probes_in,
+                    uint32_t *out_ids, uint8_t *out_dist, int32_t *dbg_probes, uint8_t *dbg_qluts,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    return qadc::ivf_search(ix, queries, nq, nprobe, R, init, nbins, qmin_mode, probes_in, out_ids,
+                            out_dist, dbg_probes, dbg_qluts, workspace, workspace_bytes,
+                            (hipStream_t)stream);
+}
+
+size_t qadc_ivf_workspace_bytes(const qadc_ivf_index *ix, int nq, int nprobe, int R)
+{
+    return qadc::ivf_workspace_bytes(ix, nq, nprobe, R);
 }
 
 int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *x, int64_t n,

@@ -1,0 +1,516 @@
+// Non-exhaustive search (Sections 2.2 and 2.3 of the paper) with Quick ADC on gfx950:
+//   Index   squared distances of the query to the K coarse centroids, the nprobe closest cells
+//   Tables  one set of m float tables per probed cell, on the residual y - centroid (Eq. (1))
+//   qmax    float ADC of the first `init` codes met walking the probed lists in probe order
+//           (Section 3.3), then ONE 8-bit quantizer per query shared by all its cells, so
+//           that quantized sums of different cells compare
+//   Scan    every code of every probed list: pair-table lookups, clamped sum (Alg. 2),
+//           key = sum << 32 | storage position; R smallest keys per query; ids[position]
+// Inverted lists are skewed (a few lists hold millions of codes, most a few thousand), so a
+// query's lists are cut into units of at most IVF_UNIT codes and dealt round-robin to the
+// W workgroups of the query.
+
+#include "qadc_scan_common.h"
+
+namespace qadc {
+
+constexpr int IVF_MAX_NPROBE = 256;
+constexpr int IVF_QT = 32;       // queries per workgroup of the coarse-distance kernel
+constexpr int IVF_NT = 256;      // threads of the scan workgroups
+constexpr int IVF_UNIT_TILES = 8;
+
+// ------------------------------------------------------------------ Index
+
+// dist[q][c] = sum_t (y[q][t] - coarse[c][t])^2, float32, t increasing.  One thread per
+// centroid, IVF_QT queries per workgroup held in LDS (broadcast reads).
+__global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
+    const float *__restrict__ coarse, int K, int d, const float *__restrict__ queries, int nq,
+    float *__restrict__ dist)
+{
+    extern __shared__ float yq[];  // [IVF_QT][d]
+    const int q0 = blockIdx.y * IVF_QT;
+    const int nqt = min(IVF_QT, nq - q0);
+    for (int e = threadIdx.x; e < IVF_QT * d; e += blockDim.x) {
+        const int qq = e / d;
+        yq[e] = (qq < nqt) ? queries[(size_t)(q0 + qq) * d + (e - qq * d)] : 0.0f;
+    }
+    __syncthreads();
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= K) return;
+    float acc[IVF_QT];
+#pragma unroll
+    for (int qq = 0; qq < IVF_QT; ++qq) acc[qq] = 0.0f;
+    const float *cv = coarse + (size_t)c * d;
+    for (int t = 0; t < d; ++t) {
+        const float x = cv[t];
+#pragma unroll
+        for (int qq = 0; qq < IVF_QT; ++qq) {
+            const float df = yq[qq * d + t] - x;
+            acc[qq] += df * df;
+        }
+    }
+    for (int qq = 0; qq < nqt; ++qq) dist[(size_t)(q0 + qq) * K + c] = acc[qq];
+}
+
+// probes[q][0..nprobe) = the nprobe closest cells, closest first, ties to the lowest cell id.
+__global__ __launch_bounds__(1024) void ivf_select_probes_kernel(
+    const float *__restrict__ dist, int K, int nprobe, int32_t *__restrict__ probes)
+{
+    __shared__ SelectScratch sc;
+    __shared__ uint64_t sel[IVF_MAX_NPROBE];
+    __shared__ unsigned cnt;
+    const int q = blockIdx.x;
+    const float *dq = dist + (size_t)q * K;
+    auto each = [&](auto f) {
+        for (int c = threadIdx.x; c < K; c += blockDim.x)
+            f(((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c);
+    };
+    const unsigned need = (unsigned)min(nprobe, K);
+    const uint64_t kth = block_radix_select_each<uint64_t, 8>(each, need, &sc);
+    if (threadIdx.x == 0) cnt = 0;
+    __syncthreads();
+    each([&](uint64_t k) {
+        if (k <= kth) sel[atomicAdd(&cnt, 1u)] = k;  // exactly `need` keys: they are unique
+    });
+    __syncthreads();
+    for (unsigned i = threadIdx.x; i < (unsigned)nprobe; i += blockDim.x) {
+        if (i >= need) {
+            probes[(size_t)q * nprobe + i] = -1;
+        } else {
+            const uint64_t k = sel[i];
+            unsigned rank = 0;
+            for (unsigned j = 0; j < need; ++j) rank += (sel[j] < k) ? 1u : 0u;
+            probes[(size_t)q * nprobe + rank] = (int32_t)(unsigned)k;
+        }
+    }
+}
+
+// ----------------------------------------------------------------- Tables
+
+// luts[q][p][j][i] = || (y_q - coarse[probes[q][p]])^j - C^j[i] ||^2, float64 inside, one
+// rounding to float32 (same arithmetic as the exhaustive tables kernel).  Unused probe slots
+// (cell id < 0) get +inf tables: nothing of them is ever scanned.
+__global__ __launch_bounds__(256) void ivf_build_luts_kernel(
+    const float *__restrict__ codebooks, int d, int m, const float *__restrict__ queries,
+    const float *__restrict__ coarse, const int32_t *__restrict__ probes, int nprobe,
+    float *__restrict__ luts)
+{
+    extern __shared__ double yr[];  // [d]
+    const int p = blockIdx.x, q = blockIdx.y;
+    const int cell = probes[(size_t)q * nprobe + p];
+    const int dsub = d / m;
+    const int entries = m * 16;
+    float *out = luts + ((size_t)q * nprobe + p) * entries;
+    if (cell < 0) {
+        for (int e = threadIdx.x; e < entries; e += blockDim.x) out[e] = __builtin_inff();
+        return;
+    }
+    for (int t = threadIdx.x; t < d; t += blockDim.x)
+        yr[t] = (double)queries[(size_t)q * d + t] - (double)coarse[(size_t)cell * d + t];
+    __syncthreads();
+    for (int e = threadIdx.x; e < entries; e += blockDim.x) {
+        const int j = e >> 4;
+        const float *c = codebooks + (size_t)e * dsub;
+        const double *y = yr + j * dsub;
+        double acc = 0.0;
+        for (int t = 0; t < dsub; ++t) {
+            const double df = y[t] - (double)c[t];
+            acc += df * df;
+        }
+        out[e] = (float)acc;
+    }
+}
+
+// ------------------------------------------------------------------- qmax
+
+// qmax[q] = min(R, n_walk)-th smallest float ADC distance (Eq. (2), float32, increasing j)
+// of the first n_walk = min(init, codes in the probed lists) codes met walking the lists in
+// probe order, each code with the tables of its own cell; 0 when the lists are empty.
+__global__ __launch_bounds__(256) void ivf_qmax_kernel(
+    const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int m,
+    const int32_t *__restrict__ probes, int nprobe, const float *__restrict__ luts, int init, int R,
+    float *__restrict__ qmax)
+{
+    __shared__ unsigned cand[QADC_MAX_INIT];
+    __shared__ long long start[IVF_MAX_NPROBE + 1];  // codes before probe p in the walk
+    __shared__ long long lo[IVF_MAX_NPROBE];
+    __shared__ SelectScratch sc;
+    const int q = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int B = m / 2;
+    if (tid == 0) {
+        long long run = 0;
+        for (int p = 0; p < nprobe; ++p) {
+            const int cell = probes[(size_t)q * nprobe + p];
+            start[p] = run;
+            lo[p] = cell >= 0 ? list_off[cell] : 0;
+            run += cell >= 0 ? (list_off[cell + 1] - list_off[cell]) : 0;
+        }
+        start[nprobe] = run;
+    }
+    __syncthreads();
+    const long long total = start[nprobe];
+    const int n_walk = (int)min((long long)init, total);
+    if (n_walk == 0) {  // uniform
+        if (tid == 0) qmax[q] = 0.0f;
+        return;
+    }
+    for (int i = tid; i < n_walk; i += blockDim.x) {
+        int p = 0;
+        while (start[p + 1] <= i) ++p;  // lists are few; the walk is short
+        const uint8_t *c = codes + (size_t)(lo[p] + (i - start[p])) * B;
+        const float *lut = luts + ((size_t)q * nprobe + p) * m * 16;
+        float acc = 0.0f;
+        for (int jb = 0; jb < B; ++jb) {
+            const unsigned comps = c[jb];
+            acc = acc + lut[(2 * jb) * 16 + (comps & 15u)];
+            acc = acc + lut[(2 * jb + 1) * 16 + (comps >> 4)];
+        }
+        cand[i] = f2ord(acc);
+    }
+    __syncthreads();
+    const unsigned need = (unsigned)min(R, n_walk);
+    const unsigned kth = block_radix_select<unsigned, 4>(cand, (unsigned)n_walk, need, &sc);
+    if (tid == 0) qmax[q] = ord2f(kth);
+}
+
+// ------------------------------------------------------------------- Scan
+
+struct IvfShared {
+    SelectScratch sel;
+    unsigned ccnt;
+    unsigned tcnt[3];
+    unsigned tau;
+    long long ustart[IVF_MAX_NPROBE + 1];  // units before probe p
+    long long a0[IVF_MAX_NPROBE];          // list start rounded down to 16 codes
+    long long lo[IVF_MAX_NPROBE];
+    long long hi[IVF_MAX_NPROBE];
+};
+
+template <int B>
+__global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
+    const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int64_t n_total,
+    const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
+    int R, char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off)
+{
+    constexpr int NT = IVF_NT;
+    using C = ScanCfg<B, NT>;
+    constexpr long long UNIT = (long long)IVF_UNIT_TILES * C::TILE;
+    __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
+    __shared__ uint64_t keys[C::CAP];
+    __shared__ IvfShared sh;
+
+    const int tid = threadIdx.x;
+    const int q = blockIdx.y;
+    const int g = blockIdx.x;
+    const int W = gridDim.x;
+    const unsigned cap = (unsigned)cap_i;
+
+    if (tid == 0) {
+        long long run = 0;
+        for (int p = 0; p < nprobe; ++p) {
+            const int cell = probes[(size_t)q * nprobe + p];
+            long long l = 0, h = 0;
+            if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
+            const long long a = l / 16 * 16;
+            sh.ustart[p] = run;
+            sh.lo[p] = l;
+            sh.hi[p] = h;
+            sh.a0[p] = a;
+            run += (h > l) ? (h - a + UNIT - 1) / UNIT : 0;
+        }
+        sh.ustart[nprobe] = run;
+        sh.tcnt[0] = 0;
+    }
+    for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
+    __syncthreads();
+    const long long units = sh.ustart[nprobe];
+
+    uint64_t lim = ~0ull;  // keys >= lim cannot be among the R best of this workgroup's codes
+    unsigned have = 0;
+    int rot = 0;
+    int cur_p = -1;
+    bool first_tile = true;
+
+    for (long long u = g; u < units; u += W) {  // uniform
+        int p = 0;
+        {   // the probe this unit belongs to (binary search, same result in every thread)
+            int lo_p = 0, hi_p = nprobe;
+            while (hi_p - lo_p > 1) {
+                const int mid = (lo_p + hi_p) >> 1;
+                if (sh.ustart[mid] <= u) lo_p = mid; else hi_p = mid;
+            }
+            p = lo_p;
+        }
+        if (p != cur_p) {
+            __syncthreads();  // nobody still reads the previous pair tables
+            {
+                const uint8_t *qlut = qluts + ((size_t)q * nprobe + p) * (2 * B) * 16;
+                for (int e = tid; e < B * 256; e += NT) {
+                    const int jb = e >> 8, v = e & 255;
+                    const unsigned s = (unsigned)qlut[(2 * jb) * 16 + (v & 15)] +
+                                       (unsigned)qlut[(2 * jb + 1) * 16 + (v >> 4)];
+                    ptab[e] = (uint8_t)min(s, cap);
+                }
+            }
+            __syncthreads();
+            cur_p = p;
+        }
+        const long long lo = sh.lo[p], hi = sh.hi[p];
+        const long long u0 = sh.a0[p] + (u - sh.ustart[p]) * UNIT;
+        const long long u1 = min(hi, u0 + UNIT);
+        for (long long t0 = u0; t0 < u1; t0 += C::TILE) {
+            unsigned *ctr = &sh.tcnt[rot];
+            const int nxt = (rot == 2) ? 0 : rot + 1;
+            if (tid == 0) sh.tcnt[nxt] = 0;
+            uint4 w[2];
+            int nc[2];
+            tile_load<B, NT>(codes, t0, n_total, w, nc);  // may reach into the neighbouring lists
+            uint64_t k[C::CPT];
+            if constexpr (B <= 16) {
+                constexpr int CPV = 16 / B;
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+#pragma unroll
+                    for (int c = 0; c < CPV; ++c) {
+                        unsigned s = 0;
+#pragma unroll
+                        for (int jb = 0; jb < B; ++jb) s += ptab[jb * 256 + byte_of(w[v], c * B + jb)];
+                        s = min(s, cap);
+                        const long long pos = t0 + (long long)((v * NT + tid) * CPV + c);
+                        const bool valid = (c < nc[v]) && pos >= lo && pos < u1;
+                        k[v * CPV + c] = valid ? (((uint64_t)s << 32) | (uint64_t)pos) : ~0ull;
+                    }
+                }
+            } else {
+                unsigned s = 0;
+#pragma unroll
+                for (int jb = 0; jb < 32; ++jb) s += ptab[jb * 256 + byte_of(w[jb >> 4], jb & 15)];
+                s = min(s, cap);
+                const long long pos = t0 + tid;
+                const bool valid = nc[0] && pos >= lo && pos < u1;
+                k[0] = valid ? (((uint64_t)s << 32) | (uint64_t)pos) : ~0ull;
+            }
+
+            if (first_tile) {
+                // bound the workgroup's share by its own first tile: the bin of the R-th
+                // smallest unsaturated sum (keys above it cannot be among the R best)
+#pragma unroll
+                for (int c = 0; c < C::CPT; ++c)
+                    if (k[c] != ~0ull && (unsigned)(k[c] >> 32) < cap)
+                        atomicAdd(&sh.sel.hist[(unsigned)(k[c] >> 32)], 1u);
+                __syncthreads();
+                if (tid < WAVE) {
+                    const int l = tid;
+                    unsigned h0 = sh.sel.hist[4 * l], h1 = sh.sel.hist[4 * l + 1];
+                    unsigned h2 = sh.sel.hist[4 * l + 2], h3 = sh.sel.hist[4 * l + 3];
+                    const unsigned tot = h0 + h1 + h2 + h3;
+                    unsigned inc = tot;
+#pragma unroll
+                    for (int dd = 1; dd < WAVE; dd <<= 1) {
+                        const unsigned up = __shfl_up(inc, dd);
+                        if (l >= dd) inc += up;
+                    }
+                    const unsigned long long mm = __ballot(inc >= (unsigned)R);
+                    unsigned t = cap;
+                    if (mm) {
+                        const int fl = __ffsll((long long)mm) - 1;
+                        unsigned run = inc - tot, bin = 4u * l + 3u;
+                        const unsigned hh[4] = {h0, h1, h2, h3};
+                        bool found = false;
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            run += hh[b];
+                            if (!found && run >= (unsigned)R) { bin = 4u * l + b; found = true; }
+                        }
+                        t = __shfl(bin, fl);
+                    }
+                    if (tid == 0) sh.tau = min(t, cap);
+                }
+                __syncthreads();
+                lim = ((uint64_t)sh.tau + 1ull) << 32;
+                first_tile = false;
+            }
+
+#pragma unroll
+            for (int c = 0; c < C::CPT; ++c) {
+                const bool pass = k[c] < lim;
+                const unsigned slot = have + wave_append_slot(pass, ctr);
+                if (pass) keys[slot] = k[c];
+            }
+            __syncthreads();
+            have += *ctr;
+            rot = nxt;
+            if (have > (unsigned)SCAN_SLACK) {
+                const uint64_t kth = compact_candidates<uint64_t, 5, NT, C::CAP>(
+                    keys, have, (unsigned)R, &sh.sel, &sh.ccnt);
+                lim = min(lim, kth + 1ull);
+                have = (unsigned)R;
+            }
+        }
+    }
+
+    if (have > (unsigned)R) {
+        compact_candidates<uint64_t, 5, NT, C::CAP>(keys, have, (unsigned)R, &sh.sel, &sh.ccnt);
+        have = (unsigned)R;
+    }
+    if (have == 0) return;
+    unsigned *counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + counts_off);
+    uint64_t *dst = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + lists_off) + (size_t)g * R;
+    if (tid == 0) counts[g] = have;
+    for (unsigned i = tid; i < have; i += NT) dst[i] = keys[i];
+}
+
+// out_ids[q][r] = ids[position] for the positions the merge kernel wrote (in place).
+__global__ void ivf_gather_ids_kernel(const uint32_t *__restrict__ ids, uint32_t *__restrict__ out,
+                                      int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < total) {
+        const uint32_t pos = out[i];
+        if (pos != 0xffffffffu) out[i] = ids[pos];
+    }
+}
+
+// ------------------------------------------------------------------- host
+
+int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
+                  int, uint8_t *, float *, float *, float *, hipStream_t);
+
+struct IvfPlan {
+    int qb, W;
+    ScanLayout l;
+    size_t off_dist, off_probes, off_luts, off_qluts, off_qmax, off_scan, bytes;
+};
+
+static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, IvfPlan *p)
+{
+    if (!ix || nq < 1 || nprobe < 1 || nprobe > IVF_MAX_NPROBE || R < 1 || R > QADC_MAX_R) return false;
+    if (!(ix->m == 8 || ix->m == 16 || ix->m == 32 || ix->m == 64)) return false;
+    if (ix->d < ix->m || ix->d % ix->m || ix->K < 1 || ix->n < 0 || ix->n > 0xfffffffell) return false;
+    p->W = env_int("QADC_IVF_WGS", 64);
+    if (p->W < 1) p->W = 1;
+    p->l = scan_layout(p->W, R);
+    const size_t per_q = align_up((size_t)ix->K * 4, 256) + align_up((size_t)nprobe * 4, 256) +
+                         align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
+                         align_up((size_t)nprobe * ix->m * 16, 256) + 256 + p->l.stride;
+    int64_t qb = (int64_t)((512ull << 20) / per_q);
+    if (qb < 1) qb = 1;
+    if (qb > nq) qb = nq;
+    if (qb > 4096) qb = 4096;
+    p->qb = (int)qb;
+    size_t o = 0;
+    p->off_dist = o;   o += align_up((size_t)qb * ix->K * 4, 256);
+    p->off_probes = o; o += align_up((size_t)qb * nprobe * 4, 256);
+    p->off_luts = o;   o += align_up((size_t)qb * nprobe * ix->m * 16 * 4, 256);
+    p->off_qluts = o;  o += align_up((size_t)qb * nprobe * ix->m * 16, 256);
+    p->off_qmax = o;   o += align_up((size_t)qb * 4, 256);
+    p->off_scan = o;   o += p->l.stride * (size_t)qb;
+    p->bytes = o;
+    return true;
+}
+
+size_t ivf_workspace_bytes(const qadc_ivf_index *ix, int nq, int nprobe, int R)
+{
+    IvfPlan p;
+    if (!make_ivf_plan(ix, nq, nprobe, R, &p)) return 0;
+    return p.bytes;
+}
+
+int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprobe, int R, int init,
+               int nbins, int qmin_mode, const int32_t *probes_in, uint32_t *out_ids,
+               uint8_t *out_dist, int32_t *dbg_probes, uint8_t *dbg_qluts, void *workspace,
+               size_t workspace_bytes, hipStream_t st)
+{
+    IvfPlan p;
+    if (!ix || !queries || !out_ids || !out_dist)
+        return fail(QADC_EINVAL, "qadc_ivf_search: null pointer");
+    if (nq == 0) return QADC_OK;
+    if (!make_ivf_plan(ix, nq, nprobe, R, &p))
+        return fail(QADC_EINVAL, "qadc_ivf_search: unsupported nq=%d nprobe=%d R=%d d=%d m=%d K=%d", nq,
+                    nprobe, R, ix->d, ix->m, ix->K);
+    if (!ix->coarse || !ix->list_off || !ix->codes || !ix->ids || !ix->codebooks)
+        return fail(QADC_EINVAL, "qadc_ivf_search: index has a null pointer");
+    if (init < 1 || init > QADC_MAX_INIT || nbins < 1 || nbins > 255)
+        return fail(QADC_EINVAL, "qadc_ivf_search: init=%d nbins=%d", init, nbins);
+    if (((uintptr_t)ix->codes & 15) != 0)
+        return fail(QADC_EINVAL, "qadc_ivf_search: codes must be 16-byte aligned");
+    if (!workspace || workspace_bytes < p.bytes)
+        return fail(QADC_ENOMEM, "qadc_ivf_search: workspace %zu < %zu bytes", workspace_bytes, p.bytes);
+    if (((uintptr_t)workspace & 255) != 0)
+        return fail(QADC_EINVAL, "qadc_ivf_search: workspace must be 256-byte aligned");
+    const int d = ix->d, m = ix->m, K = ix->K;
+    if ((size_t)IVF_QT * d * sizeof(float) > 48 * 1024)
+        return fail(QADC_EINVAL, "qadc_ivf_search: d=%d too large", d);
+    char *ws = (char *)workspace;
+    float *dist = (float *)(ws + p.off_dist);
+    int32_t *probes = (int32_t *)(ws + p.off_probes);
+    float *luts = (float *)(ws + p.off_luts);
+    uint8_t *qluts = (uint8_t *)(ws + p.off_qluts);
+    float *qmax = (float *)(ws + p.off_qmax);
+    char *scan_ws = ws + p.off_scan;
+
+    for (int q0 = 0; q0 < nq; q0 += p.qb) {
+        const int nb = min(p.qb, nq - q0);
+        const float *yq = queries + (size_t)q0 * d;
+        // Index
+        prof_begin(QADC_PROF_IVF_INDEX, st);
+        if (probes_in) {
+            QADC_HIP_TRY(hipMemcpyAsync(probes, probes_in + (size_t)q0 * nprobe,
+                                        (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        } else {
+            dim3 grid((unsigned)ceil_div(K, 256), (unsigned)ceil_div(nb, IVF_QT));
+            hipLaunchKernelGGL(ivf_coarse_dist_kernel, grid, dim3(256), (size_t)IVF_QT * d * sizeof(float),
+                               st, ix->coarse, K, d, yq, nb, dist);
+            hipLaunchKernelGGL(ivf_select_probes_kernel, dim3(nb), dim3(1024), 0, st, dist, K, nprobe,
+                               probes);
+        }
+        prof_end(QADC_PROF_IVF_INDEX, st);
+        // Tables
+        prof_begin(QADC_PROF_IVF_TABLES, st);
+        hipLaunchKernelGGL(ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256), (size_t)d * sizeof(double),
+                           st, ix->codebooks, d, m, yq, ix->coarse, probes, nprobe, luts);
+        hipLaunchKernelGGL(ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes, m, probes,
+                           nprobe, luts, init, R, qmax);
+        int rc = quantize_luts(luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
+                               nullptr, nullptr, st);
+        if (rc != QADC_OK) return rc;
+        prof_end(QADC_PROF_IVF_TABLES, st);
+        // Scan
+        prof_begin(QADC_PROF_SCAN, st);
+        dim3 grid(p.W, nb);
+#define QADC_IVF_CASE(B_)                                                                              \
+    case B_:                                                                                          \
+        hipLaunchKernelGGL(ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes, ix->n, \
+                           probes, nprobe, qluts, nbins, R, scan_ws, p.l.stride, p.l.counts_off,      \
+                           p.l.lists_off);                                                            \
+        break;
+        switch (m / 2) {
+            QADC_IVF_CASE(4)
+            QADC_IVF_CASE(8)
+            QADC_IVF_CASE(16)
+            QADC_IVF_CASE(32)
+        }
+#undef QADC_IVF_CASE
+        prof_end(QADC_PROF_SCAN, st);
+        prof_begin(QADC_PROF_MERGE, st);
+        uint32_t *oi = out_ids + (size_t)q0 * R;
+        hipLaunchKernelGGL((merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, scan_ws,
+                           p.l.stride, p.l.counts_off, p.l.lists_off, p.W, (unsigned)R, R, (uint8_t)nbins,
+                           oi, out_dist + (size_t)q0 * R);
+        const int64_t total = (int64_t)nb * R;
+        hipLaunchKernelGGL(ivf_gather_ids_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, st,
+                           ix->ids, oi, total);
+        prof_end(QADC_PROF_MERGE, st);
+        if (dbg_probes)
+            QADC_HIP_TRY(hipMemcpyAsync(dbg_probes + (size_t)q0 * nprobe, probes,
+                                        (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        if (dbg_qluts)
+            QADC_HIP_TRY(hipMemcpyAsync(dbg_qluts + (size_t)q0 * nprobe * m * 16, qluts,
+                                        (size_t)nb * nprobe * m * 16, hipMemcpyDeviceToDevice, st));
+    }
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+}  // namespace qadc

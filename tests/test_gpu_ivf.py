@@ -1,0 +1,129 @@
+"""GPU parity of qadc_ivf_search against the CPU oracle's non-exhaustive search."""
+
+import numpy as np
+import pytest
+
+from gpu_common import to_gpu, idx_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def Q():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1704_07355_amd as Q
+    Q.lib()
+    return Q
+
+
+@pytest.fixture(scope="module")
+def O():
+    from oracle import qadc_oracle as O
+    return O
+
+
+def build_ivf(O, n=60_000, K=48, d=64, m=16, seed=0, zipf=True):
+    """Small inverted index with Zipf-skewed lists: vectors around K seeded centres, residual codes."""
+    from oracle import cref
+    from workloads import zipf_list_sizes
+    rng = np.random.default_rng(seed)
+    coarse = rng.uniform(0, 255, size=(K, d)).astype(np.float32)
+    sizes = zipf_list_sizes(n, K, 0.8, seed) if zipf else np.full(K, n // K)
+    cell = np.repeat(np.arange(K), sizes)
+    rng.shuffle(cell)
+    x = (coarse[cell] + rng.normal(scale=18, size=(len(cell), d))).astype(np.float32)
+    dsub = d // m
+    resid_sample = (x[:4000] - coarse[cell[:4000]]).astype(np.float32)
+    rows = rng.permutation(4000)[:16]
+    cb = np.stack([O.kmeans_lloyd(resid_sample[:, j * dsub:(j + 1) * dsub], rows, 3)[0] for j in range(m)])
+    # assign + encode residuals with the plain-C twin (same steps as O.ivf_build)
+    assign = O.ivf_assign(x, coarse)
+    order = np.argsort(assign, kind="stable")
+    resid = (x[order] - coarse[assign[order]]).astype(np.float32)
+    codes = cref.pq_encode(resid, cb)
+    list_off = np.zeros(K + 1, dtype=np.int64)
+    np.cumsum(np.bincount(assign, minlength=K), out=list_off[1:])
+    index = dict(list_off=list_off, codes=codes, ids=order.astype(np.uint32))
+    return coarse, cb, x, index
+
+
+def gpu_index(Q, coarse, cb, index):
+    return Q.IvfIndex(to_gpu(coarse), to_gpu(index["list_off"]), to_gpu(index["codes"]),
+                      to_gpu(index["ids"].view(np.int32)), to_gpu(cb))
+
+
+@pytest.mark.parametrize("m", [16, 32])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_ivf_search_matches_oracle(Q, O, m, mode):
+    import torch
+    coarse, cb, x, index = build_ivf(O, m=m, seed=m)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(5)
+    queries = (x[rng.integers(0, len(x), size=12)] + rng.normal(scale=6, size=(12, x.shape[1]))).astype(np.float32)
+    nprobe, R, init = 8, 100, 300
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, R, init, 255, mode, debug=True)
+    torch.cuda.synchronize()
+    ids, dist, probes, qluts = idx_np(ids), dist.cpu().numpy(), probes.cpu().numpy(), qluts.cpu().numpy()
+    for iq in range(len(queries)):
+        full = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R, 255, mode)
+        # Index step: same cells in the same order (float32 vs float64 distances: allow a swap of
+        # cells whose distances agree to 1e-5)
+        dq = O.sq_l2(queries[iq][None], coarse)[0]
+        if not np.array_equal(probes[iq], full["probes"]):
+            np.testing.assert_allclose(dq[probes[iq]], dq[full["probes"]], rtol=1e-5)
+        # Tables + quantizer: entries within one step of the oracle's
+        if np.array_equal(probes[iq], full["probes"]):
+            assert np.abs(qluts[iq].astype(int) - full["qluts"].astype(int)).max() <= 1
+        # integer part replayed by the oracle on the GPU's own cells and tables: bit-exact
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R, 255, mode,
+                                     probes=probes[iq], qluts=qluts[iq])
+        assert np.array_equal(ids[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq], rep["dist"]), iq
+
+
+def test_ivf_search_given_probes_and_edge_lists(Q, O):
+    """Cells given by the caller, including empty lists, an unused slot and a single huge list."""
+    import torch
+    coarse, cb, x, index = build_ivf(O, n=40_000, K=20, seed=3)
+    # empty two lists by moving their boundaries: rebuild offsets with zero-size cells
+    gix = gpu_index(Q, coarse, cb, index)
+    sizes = np.diff(index["list_off"])
+    big = int(np.argmax(sizes))
+    small = int(np.argmin(sizes))
+    probes_in = np.array([[big, small, 3, -1], [small, 5, big, 7], [big, -1, -1, -1]], dtype=np.int32)
+    queries = x[[10, 2000, 30000]] + 1.5
+    R, init = 150, 200
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries.astype(np.float32)), 4, R, init,
+                                                 probes_in=to_gpu(probes_in), debug=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(probes.cpu().numpy(), probes_in)
+    for iq in range(3):
+        cells = probes_in[iq][probes_in[iq] >= 0]
+        ql = qluts[iq].cpu().numpy()[:len(cells)]
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq].astype(np.float32), len(cells), init, R,
+                                     probes=cells, qluts=ql)
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]) and np.array_equal(dist[iq].cpu().numpy(), rep["dist"])
+        # and the GPU's tables are the oracle's within one step
+        full = O.ivf_quick_adc_search(index, coarse, cb, queries[iq].astype(np.float32), len(cells), init, R,
+                                      probes=cells)
+        assert np.abs(ql.astype(int) - full["qluts"].astype(int)).max() <= 1
+
+
+def test_ivf_all_cells_equals_flat_scan_of_the_lists(Q, O):
+    """nprobe = K: every stored code is scanned exactly once, with its own cell's tables."""
+    import torch
+    coarse, cb, x, index = build_ivf(O, n=30_000, K=9, seed=9)
+    gix = gpu_index(Q, coarse, cb, index)
+    y = x[123:124].copy()
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(y), 9, 100, 500, debug=True)
+    torch.cuda.synchronize()
+    probes, qluts = probes.cpu().numpy()[0], qluts.cpu().numpy()[0]
+    assert sorted(probes.tolist()) == list(range(9))
+    sums = np.empty(len(x), dtype=np.uint8)
+    for t, p in enumerate(probes):
+        lo, hi = index["list_off"][p], index["list_off"][p + 1]
+        sums[lo:hi] = O.scan_saturating(qluts[t], index["codes"][lo:hi])
+    pos, d = O.top_r(sums, 100, pad_dist=255)
+    assert np.array_equal(idx_np(ids)[0], index["ids"][pos]) and np.array_equal(dist[0].cpu().numpy(), d)
+    assert 123 in idx_np(ids)[0]
