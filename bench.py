@@ -2,19 +2,21 @@
 """Benchmark of the Quick ADC hot path on one MI355X.
 
 Workload (BASELINE config 2, "single-query bandwidth scan"): d=128 mixture
-data, PQ m=16 x 16 centroids (64-bit codes), N = 10,000,000 codes contiguous
-in HBM, queries issued one at a time, uint8 tables, R = 100.
+data, PQ m=16 x 16 centroids (64-bit codes) trained by 10 k-means iterations
+on 20,000 vectors, N = 10,000,000 codes contiguous in HBM, queries issued one
+at a time, uint8 tables (init = 200), R = 100.
 
 One "step" is one query through the whole path on one stream:
-    qadc_build_luts -> qadc_quantize_luts (init = 200) -> qadc_scan_topk
+    qadc_build_luts -> qadc_quantize_luts -> qadc_scan_topk
 over 10 M codes already resident in HBM.  Successive steps scan successive
 code buffers out of `--buffers` distinct ones (default 8 x 80 MB = 640 MB),
 so that the scan streams from HBM and not from the 256 MB last-level cache.
 
 Prints ONE JSON line: whole-path throughput in G codes/s, the roofline of the
-dominant kernel (the code-streaming scan kernel, timed with HIP events on its
-own stream by the library's profiling hooks), and the CPU oracle timed on the
-host cores on a bounded sample of the same workload.
+dominant kernel (the code-streaming scan kernel; its duration is taken from HIP
+events attached to its own dispatches by the library's profiling hooks), the
+accuracy of the quantized scan against float ADC, and the CPU oracle timed on
+the host cores on a bounded sample of the same workload.
 """
 
 from __future__ import annotations
@@ -43,29 +45,63 @@ def parse():
     ap.add_argument("--R", type=int, default=100)
     ap.add_argument("--init", type=int, default=200)
     ap.add_argument("--queries", type=int, default=1000)
-    ap.add_argument("--cpu-queries", type=int, default=32, help="queries of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-queries", type=int, default=256, help="queries of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--recall-queries", type=int, default=100, help="queries of the accuracy sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timing pass")
     return ap.parse_args()
 
 
-def build_database(Q, torch, spec, m, n_total, dev):
-    """Codebooks + n_total encoded mixture vectors, all produced on the GPU."""
+def build_database(Q, torch, spec, m, n_total, n_keep, dev):
+    """Codebooks (GPU k-means) + n_total encoded mixture vectors, all produced on the GPU.
+
+    The raw vectors of the first n_keep rows are kept for the exact-neighbour accuracy check.
+    """
     from workloads import SEED_TRAIN, SEED_BASE, kmeans_init_rows
     from workloads.mixture_torch import mixture_vectors_torch, BLOCK
-    d = spec.d
-    dsub = d // m
-    # Codebooks: the sub-vectors of 16 seeded learning-set rows (a k-means start state).
     train = mixture_vectors_torch(spec, SEED_TRAIN, 0, 20_000, dev)
     rows = torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev)
-    cb = train[rows].reshape(16, m, dsub).permute(1, 0, 2).contiguous()
+    cb = Q.qadc_pq_train(train, m, 16, rows, 10)
     codes = torch.empty((n_total, m // 2), dtype=torch.uint8, device=dev)
+    raw = torch.empty((n_keep, spec.d), dtype=torch.float32, device=dev) if n_keep else None
     chunk = 4 * BLOCK
     for s in range(0, n_total, chunk):
         cnt = min(chunk, n_total - s)
         x = mixture_vectors_torch(spec, SEED_BASE, s, cnt, dev)
         Q.qadc_pq_encode(cb, x, out=codes[s:s + cnt])
+        if raw is not None and s < n_keep:
+            k = min(cnt, n_keep - s)
+            raw[s:s + k] = x[:k]
     torch.cuda.synchronize()
-    return cb, codes
+    return cb, codes, raw
+
+
+def accuracy(Q, torch, np, cb, codes, raw, queries, R, init):
+    """overlap@R of the quantized scan with float ADC on the same codes, and NN-recall@R of both."""
+    luts = Q.qadc_build_luts(cb, queries)
+    ql, _, _, _ = Q.qadc_quantize_luts(luts, codes[:init], R)
+    qi, _ = Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes, ql, R)
+    fi, _ = Q.qadc_scan_topk(Q.QADC_F32_4BIT, codes, luts, R)
+    # exact nearest neighbour of each query among the raw vectors (measurement only)
+    best = torch.full((queries.shape[0],), float("inf"), device=queries.device)
+    arg = torch.zeros((queries.shape[0],), dtype=torch.int64, device=queries.device)
+    qq = (queries * queries).sum(1)
+    step = 1 << 20
+    for s in range(0, raw.shape[0], step):
+        x = raw[s:s + step]
+        dist = qq[:, None] - 2.0 * queries @ x.T + (x * x).sum(1)[None, :]
+        v, a = dist.min(1)
+        upd = v < best
+        best[upd] = v[upd]
+        arg[upd] = a[upd] + s
+    torch.cuda.synchronize()
+    qi = qi.cpu().numpy().view(np.uint32).astype(np.int64)
+    fi = fi.cpu().numpy().view(np.uint32).astype(np.int64)
+    nn = arg.cpu().numpy()
+    overlap = float(np.mean([len(np.intersect1d(a, b)) / R for a, b in zip(qi, fi)]))
+    rec_q = float(np.mean([nn[i] in qi[i] for i in range(len(nn))]))
+    rec_f = float(np.mean([nn[i] in fi[i] for i in range(len(nn))]))
+    return {"queries": int(queries.shape[0]), "overlap_at_R_vs_float_adc": round(overlap, 4),
+            "nn_recall_at_R_quick_adc": round(rec_q, 4), "nn_recall_at_R_float_adc": round(rec_f, 4)}
 
 
 def main():
@@ -90,7 +126,8 @@ def main():
     row = m // 2
 
     t0 = time.time()
-    cb, codes = build_database(Q, torch, spec, m, n * args.buffers, dev)
+    n_keep = n if args.recall_queries > 0 else 0
+    cb, codes, raw = build_database(Q, torch, spec, m, n * args.buffers, n_keep, dev)
     queries = mixture_vectors_torch(spec, SEED_QUERY, 0, args.queries, dev)
     t_build = time.time() - t0
     bufs = [codes[b * n:(b + 1) * n] for b in range(args.buffers)]
@@ -121,35 +158,42 @@ def main():
     ms_per_step = ms_total / args.steps
     gcodes = n / (ms_per_step * 1e-3) / 1e9
 
-    # Per-kernel timing of the scan kernel (HIP events recorded by the library around the
-    # kernel on the stream it runs on), same launch configuration, same rotation.
+    # Per-kernel durations (HIP events attached to each dispatch by the library), same launch
+    # configuration, same buffer rotation.
     roofline = None
-    scan_only = None
+    kernels = None
     if not args.no_profile:
-        nprof = min(args.steps, 200)
+        nprof = min(args.steps, 300)
         Q.qadc_profile_enable(True)
         for i in range(nprof):
             step(args.warmup + i)
         torch.cuda.synchronize()
-        ms_scan, launches = Q.qadc_profile_read(Q.QADC_PROF_SCAN)
-        ms_merge, _ = Q.qadc_profile_read(Q.QADC_PROF_MERGE)
-        ms_seed, _ = Q.qadc_profile_read(Q.QADC_PROF_SEED)
+        us = {}
+        for name, which in (("scan", Q.QADC_PROF_SCAN), ("seed", Q.QADC_PROF_SEED),
+                            ("merge", Q.QADC_PROF_MERGE), ("tables", Q.QADC_PROF_TABLES),
+                            ("quantize", Q.QADC_PROF_QUANTIZE)):
+            ms, cnt = Q.qadc_profile_read(which)
+            us[name] = (ms / max(1, cnt) * 1e3, cnt)
         Q.qadc_profile_enable(False)
-        avg_ms = ms_scan / max(1, launches)
-        achieved = n * row / (avg_ms * 1e-3) / 1e9
+        avg_us, launches = us["scan"]
+        achieved = n * row / (avg_us * 1e-6) / 1e9
         roofline = {"bound": "hbm", "kernel": "scan_u8_kernel", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                    "traffic": None, "avg_kernel_us": round(avg_ms * 1e3, 2),
+                    "traffic": None, "avg_kernel_us": round(avg_us, 2),
                     "bytes_per_launch": n * row, "launches_timed": launches}
-        scan_only = {"scan_kernel_us": round(avg_ms * 1e3, 2),
-                     "merge_kernel_us": round(ms_merge / max(1, launches) * 1e3, 2),
-                     "seed_kernel_us": round(ms_seed / max(1, launches) * 1e3, 2)}
+        kernels = {k + "_kernel_us": round(v[0], 2) for k, v in us.items()}
+
+    acc = None
+    if args.recall_queries > 0:
+        acc = accuracy(Q, torch, np, cb, bufs[0], raw, queries[:args.recall_queries].contiguous(), R, init)
+        acc["note"] = ("overlap = |top-R(Quick ADC) & top-R(float ADC, same codes)| / R; NN-recall = exact "
+                       "nearest neighbour (raw vectors) among the R returned; first buffer only")
 
     # CPU oracle (plain C twin, one query per thread) on a bounded sample: same codes, same tables.
     cpu = None
     if args.cpu_queries > 0:
         from oracle import cref
-        nqc = args.cpu_queries
+        nqc = min(args.cpu_queries, args.queries)
         h_codes = bufs[0].cpu().numpy()
         l = Q.qadc_build_luts(cb, queries[:nqc].contiguous())
         ql, _, _, _ = Q.qadc_quantize_luts(l, bufs[0][:init], R)
@@ -171,14 +215,13 @@ def main():
         "value": round(gcodes, 2), "unit": "Gcodes/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "config 2: single-query scan, d=128 mixture, PQ m=%d x 4-bit, N=%d codes "
-                   "contiguous, queries one at a time, R=%d, init=%d, %d rotating code buffers"
-                   % (m, n, R, init, args.buffers),
-                   "n": n, "m": m, "R": R, "init": init, "nbins": 255, "buffers": args.buffers,
-                   "codebooks": "16 seeded learning-set rows per sub-space"},
+        "config": {"workload": "config 2: single-query scan, d=128 mixture, PQ m=%d x 4-bit (10 k-means "
+                   "iterations on 20k vectors), N=%d codes contiguous, queries one at a time, R=%d, "
+                   "init=%d, %d rotating code buffers" % (m, n, R, init, args.buffers),
+                   "n": n, "m": m, "R": R, "init": init, "nbins": 255, "buffers": args.buffers},
         "hbm_gbps_whole_path": round(n * row / (ms_per_step * 1e-3) / 1e9, 1),
         "pct_hbm_peak_whole_path": round(100 * n * row / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
-        "roofline": roofline, "kernels": scan_only, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,
         "database_build_s": round(t_build, 2),
     }
     print(json.dumps(rec))

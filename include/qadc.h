@@ -187,19 +187,37 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
 
 /*
  * Per-kernel timing for benchmarks (the paper reports Index / Tables / Scan times
- * separately, Section 4.3).  While enabled, the library brackets the kernels named
- * below with HIP events on the caller's stream; qadc_profile_read waits for the
- * recorded events and returns the summed duration and the number of launches since
- * profiling was enabled.  Process-wide state, not thread-safe; host pointers.
+ * separately, Section 4.3).  While enabled, the library launches the kernels named
+ * below with a start and a stop HIP event attached to each dispatch (the kernel's own
+ * duration on its stream); qadc_profile_read waits for the recorded events and
+ * returns the summed duration and the number of launches since profiling was enabled.
+ * Process-wide state, not thread-safe; host pointers.
  */
 #define QADC_PROF_SCAN   0  /* code-streaming kernel of qadc_scan_topk */
 #define QADC_PROF_MERGE  1  /* cross-workgroup top-R kernel of qadc_scan_topk */
 #define QADC_PROF_SEED   2  /* sampling kernel of qadc_scan_topk (large databases only) */
 #define QADC_PROF_IVF_INDEX  3  /* Index step of qadc_ivf_search (coarse distances, cell choice) */
 #define QADC_PROF_IVF_TABLES 4  /* Tables step of qadc_ivf_search (tables, qmax, quantization)   */
-#define QADC_PROF_COUNT  5
+#define QADC_PROF_TABLES     5  /* qadc_build_luts kernel */
+#define QADC_PROF_QUANTIZE   6  /* qadc_quantize_luts kernel */
+#define QADC_PROF_COUNT  7
 int qadc_profile_enable(int on);
 int qadc_profile_read(int which, double *total_ms, int64_t *launches);
+
+/*
+ * Database side, Section 2.1: trains the m codebooks of a product quantizer, each by
+ * `iters` iterations of Lloyd's k-means on the matching sub-vectors of the learning set,
+ * started from the sub-vectors of the ksub rows `init_rows`.  An iteration assigns each
+ * sub-vector to its closest centroid (float64 distances from the differences, ties to the
+ * lowest index) and replaces each centroid by the mean of its sub-vectors (float64 sum in
+ * row order, stored as float32; a centroid that owns nothing keeps its value).
+ *   train      [n][d] f32
+ *   init_rows  [ksub] i64 distinct row numbers (device)
+ *   codebooks  [m][ksub][d/m] f32   (output)
+ *   workspace  >= n * m bytes
+ */
+int qadc_pq_train(const float *train, int64_t n, int d, int m, int ksub, const int64_t *init_rows,
+                  int iters, float *codebooks, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Bytes of workspace a call needs (0 when it needs none, or on bad arguments). */
 size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R);

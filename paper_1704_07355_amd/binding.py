@@ -22,11 +22,12 @@ QADC_MAX_INIT = 8192
 QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
 QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
 QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT = 0, 1, 2
-QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES = 0, 1, 2, 3, 4
+(QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES,
+ QADC_PROF_TABLES, QADC_PROF_QUANTIZE) = range(7)
 
 EXPORTS = (
     "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_ivf_search",
-    "qadc_ivf_workspace_bytes", "qadc_pq_encode",
+    "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train",
     "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version",
 )
@@ -69,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.qadc_ivf_workspace_bytes.restype = sz
         L.qadc_pq_encode.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp]
         L.qadc_pq_encode.restype = i32
+        L.qadc_pq_train.argtypes = [vp, i64, i32, i32, i32, vp, i32, vp, vp, sz, vp]
+        L.qadc_pq_train.restype = i32
         L.qadc_profile_enable.argtypes = [i32]
         L.qadc_profile_enable.restype = i32
         L.qadc_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -244,3 +247,13 @@ def qadc_ivf_search(index: IvfIndex, queries, nprobe, R, init, nbins=255,
     if debug:
         return out_ids, out_dist, dbg_p, dbg_q
     return out_ids, out_dist
+
+
+def qadc_pq_train(train, m, ksub, init_rows, iters):
+    """train f32 [n][d], init_rows i64 [ksub] -> codebooks f32 [m][ksub][d/m] (Lloyd k-means per sub-space)."""
+    n, d = train.shape
+    cb = torch.empty((m, ksub, d // m), dtype=torch.float32, device=train.device)
+    ws = torch.empty((n * m,), dtype=torch.uint8, device=train.device)
+    _check(lib().qadc_pq_train(_ptr(train, torch.float32), n, d, m, ksub, _ptr(init_rows, torch.int64),
+                               iters, _ptr(cb), _ptr(ws), ws.numel(), _stream()))
+    return cb

@@ -32,6 +32,8 @@ int scan_topk_f32(int, const uint8_t *, int64_t, int, const float *, int, int, u
 size_t scan_topk_f32_workspace(int, int64_t, int, int, int);
 int pq_encode(const float *, int, int, int, const float *, int64_t, uint8_t *, hipStream_t);
 int workspace_init(void *, size_t, hipStream_t);
+int pq_train(const float *, int64_t, int, int, int, const int64_t *, int, float *, void *, size_t,
+             hipStream_t);
 int ivf_search(const qadc_ivf_index *, const float *, int, int, int, int, int, int, const int32_t *,
                uint32_t *, uint8_t *, int32_t *, uint8_t *, void *, size_t, hipStream_t);
 size_t ivf_workspace_bytes(const qadc_ivf_index *, int, int, int);
@@ -102,6 +104,13 @@ int qadc_profile_enable(int on) { return qadc::profile_enable(on); }
 int qadc_profile_read(int which, double *total_ms, int64_t *launches)
 {
     return qadc::profile_read(which, total_ms, launches);
+}
+
+int qadc_pq_train(const float *train, int64_t n, int d, int m, int ksub, const int64_t *init_rows,
+                  int iters, float *codebooks, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return qadc::pq_train(train, n, d, m, ksub, init_rows, iters, codebooks, workspace, workspace_bytes,
+                          (hipStream_t)stream);
 }
 
 size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)

@@ -454,36 +454,31 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         const int nb = min(p.qb, nq - q0);
         const float *yq = queries + (size_t)q0 * d;
         // Index
-        prof_begin(QADC_PROF_IVF_INDEX, st);
         if (probes_in) {
             QADC_HIP_TRY(hipMemcpyAsync(probes, probes_in + (size_t)q0 * nprobe,
                                         (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
         } else {
             dim3 grid((unsigned)ceil_div(K, 256), (unsigned)ceil_div(nb, IVF_QT));
-            hipLaunchKernelGGL(ivf_coarse_dist_kernel, grid, dim3(256), (size_t)IVF_QT * d * sizeof(float),
-                               st, ix->coarse, K, d, yq, nb, dist);
-            hipLaunchKernelGGL(ivf_select_probes_kernel, dim3(nb), dim3(1024), 0, st, dist, K, nprobe,
-                               probes);
+            launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel, grid, dim3(256),
+                   (size_t)IVF_QT * d * sizeof(float), st, ix->coarse, K, d, yq, nb, dist);
+            launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(nb), dim3(1024), 0, st, dist, K,
+                   nprobe, probes);
         }
-        prof_end(QADC_PROF_IVF_INDEX, st);
         // Tables
-        prof_begin(QADC_PROF_IVF_TABLES, st);
-        hipLaunchKernelGGL(ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256), (size_t)d * sizeof(double),
-                           st, ix->codebooks, d, m, yq, ix->coarse, probes, nprobe, luts);
-        hipLaunchKernelGGL(ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes, m, probes,
-                           nprobe, luts, init, R, qmax);
+        launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
+               (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, probes, nprobe, luts);
+        launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
+               m, probes, nprobe, luts, init, R, qmax);
         int rc = quantize_luts(luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
                                nullptr, nullptr, st);
         if (rc != QADC_OK) return rc;
-        prof_end(QADC_PROF_IVF_TABLES, st);
         // Scan
-        prof_begin(QADC_PROF_SCAN, st);
         dim3 grid(p.W, nb);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
-        hipLaunchKernelGGL(ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes, ix->n, \
-                           probes, nprobe, qluts, nbins, R, scan_ws, p.l.stride, p.l.counts_off,      \
-                           p.l.lists_off);                                                            \
+        launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
+               ix->n, probes, nprobe, qluts, nbins, R, scan_ws, p.l.stride, p.l.counts_off,           \
+               p.l.lists_off);                                                                        \
         break;
         switch (m / 2) {
             QADC_IVF_CASE(4)
@@ -492,16 +487,13 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             QADC_IVF_CASE(32)
         }
 #undef QADC_IVF_CASE
-        prof_end(QADC_PROF_SCAN, st);
-        prof_begin(QADC_PROF_MERGE, st);
         uint32_t *oi = out_ids + (size_t)q0 * R;
-        hipLaunchKernelGGL((merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, scan_ws,
-                           p.l.stride, p.l.counts_off, p.l.lists_off, p.W, (unsigned)R, R, (uint8_t)nbins,
-                           oi, out_dist + (size_t)q0 * R);
+        launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, scan_ws,
+               p.l.stride, p.l.counts_off, p.l.lists_off, p.W, (unsigned)R, R, (uint8_t)nbins, oi,
+               out_dist + (size_t)q0 * R);
         const int64_t total = (int64_t)nb * R;
-        hipLaunchKernelGGL(ivf_gather_ids_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, st,
-                           ix->ids, oi, total);
-        prof_end(QADC_PROF_MERGE, st);
+        launch(QADC_PROF_MERGE, ivf_gather_ids_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0,
+               st, ix->ids, oi, total);
         if (dbg_probes)
             QADC_HIP_TRY(hipMemcpyAsync(dbg_probes + (size_t)q0 * nprobe, probes,
                                         (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));

@@ -45,8 +45,8 @@ int build_luts(const float *codebooks, int d, int m, int ksub, const float *quer
     if (m < 1 || d < m || d % m != 0 || (ksub != 16 && ksub != 256) || nq < 0 || d > 8192)
         return fail(QADC_EINVAL, "qadc_build_luts: unsupported d=%d m=%d ksub=%d nq=%d", d, m, ksub, nq);
     if (nq == 0) return QADC_OK;
-    hipLaunchKernelGGL(build_luts_kernel, dim3(nq), dim3(256), (size_t)d * sizeof(double), st,
-                       codebooks, d, m, ksub, queries, base, luts);
+    launch(QADC_PROF_TABLES, build_luts_kernel, dim3(nq), dim3(256), (size_t)d * sizeof(double), st,
+           codebooks, d, m, ksub, queries, base, luts);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }
@@ -156,9 +156,8 @@ int quantize_luts(const float *luts, int nq, int ngroup, int m, const uint8_t *i
         return fail(QADC_EINVAL, "qadc_quantize_luts: neither init_codes nor qmax_in given");
     }
     if (nq == 0) return QADC_OK;
-    hipLaunchKernelGGL(quantize_luts_kernel, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,
-                       init_codes, (int)n_init, qmax_in, R, nbins, qmin_mode, qluts, bias, delta,
-                       qmax_out);
+    launch(QADC_PROF_QUANTIZE, quantize_luts_kernel, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,
+           init_codes, (int)n_init, qmax_in, R, nbins, qmin_mode, qluts, bias, delta, qmax_out);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }

@@ -1,4 +1,4 @@
-// Optional per-kernel timing with HIP events on the caller's stream.
+// Optional per-kernel timing with HIP events attached to the kernel dispatches.
 
 #include <vector>
 
@@ -15,23 +15,17 @@ double g_ms[QADC_PROF_COUNT];
 int64_t g_launches[QADC_PROF_COUNT];
 }  // namespace
 
-bool prof_on() { return g_on; }
-
-void prof_begin(int which, hipStream_t st)
+bool prof_open(int which, hipEvent_t *start, hipEvent_t *stop)
 {
-    if (!g_on) return;
+    if (!g_on) return false;
     Pair p;
     p.which = which;
-    if (hipEventCreate(&p.a) != hipSuccess) return;
-    if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return; }
-    (void)hipEventRecord(p.a, st);
+    if (hipEventCreate(&p.a) != hipSuccess) return false;
+    if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return false; }
     g_open.push_back(p);
-}
-
-void prof_end(int which, hipStream_t st)
-{
-    if (!g_on || g_open.empty() || g_open.back().which != which) return;
-    (void)hipEventRecord(g_open.back().b, st);
+    *start = p.a;
+    *stop = p.b;
+    return true;
 }
 
 static void drain()

@@ -414,7 +414,7 @@ static void launch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, c
                            int nq, int cap, int R, char *ws, hipStream_t st)
 {
     dim3 grid(p.G, nq);
-    hipLaunchKernelGGL((scan_u8_kernel<B, NT>), grid, dim3(NT), 0, st, codes, n, qluts, cap, R,
+    launch(QADC_PROF_SCAN, (scan_u8_kernel<B, NT>), grid, dim3(NT), 0, st, codes, n, qluts, cap, R,
                        p.seed_wgs > 0 ? 1 : 0, ws, p.stride, p.counts_off, p.lists_off);
 }
 
@@ -424,19 +424,19 @@ static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
     dim3 grid(p.seed_wgs, nq);
     switch (p.B) {
     case 4:
-        hipLaunchKernelGGL(seed_u8_kernel<4>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+        launch(QADC_PROF_SEED, seed_u8_kernel<4>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
                            p.flush_need, p.seed_stride, ws, p.stride);
         break;
     case 8:
-        hipLaunchKernelGGL(seed_u8_kernel<8>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+        launch(QADC_PROF_SEED, seed_u8_kernel<8>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
                            p.flush_need, p.seed_stride, ws, p.stride);
         break;
     case 16:
-        hipLaunchKernelGGL(seed_u8_kernel<16>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+        launch(QADC_PROF_SEED, seed_u8_kernel<16>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
                            p.flush_need, p.seed_stride, ws, p.stride);
         break;
     default:
-        hipLaunchKernelGGL(seed_u8_kernel<32>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+        launch(QADC_PROF_SEED, seed_u8_kernel<32>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
                            p.flush_need, p.seed_stride, ws, p.stride);
         break;
     }
@@ -474,21 +474,13 @@ int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, i
     for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
         const int nb = min(p.qbatch, nq - q0);
         const uint8_t *ql = qluts + (size_t)q0 * m * 16;
-        if (p.seed_wgs > 0) {
-            prof_begin(QADC_PROF_SEED, st);
-            dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
-            prof_end(QADC_PROF_SEED, st);
-        }
-        prof_begin(QADC_PROF_SCAN, st);
+        if (p.seed_wgs > 0) dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
         if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, ql, nb, nbins, R, ws, st);
         else if (p.NT == 512) dispatch_scan_u8<512>(p, codes, n, ql, nb, nbins, R, ws, st);
         else dispatch_scan_u8<256>(p, codes, n, ql, nb, nbins, R, ws, st);
-        prof_end(QADC_PROF_SCAN, st);
-        prof_begin(QADC_PROF_MERGE, st);
-        hipLaunchKernelGGL((merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
+        launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
                            p.stride, p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n),
-                           R, (uint8_t)nbins, out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
-        prof_end(QADC_PROF_MERGE, st);
+               R, (uint8_t)nbins, out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
     }
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;

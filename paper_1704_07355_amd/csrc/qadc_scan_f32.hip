@@ -169,8 +169,8 @@ static void dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, cons
     dim3 grid(p.G, nq), block(F32_NT);
 #define QADC_F32_CASE(ROW_)                                                                        \
     case ROW_:                                                                                     \
-        hipLaunchKernelGGL((scan_f32_kernel<KSUB, ROW_>), grid, block, 0, st, codes, n, luts, R, ws, \
-                           p.l.stride, p.l.counts_off, p.l.lists_off);                             \
+        launch(QADC_PROF_SCAN, (scan_f32_kernel<KSUB, ROW_>), grid, block, 0, st, codes, n, luts, R, ws, \
+               p.l.stride, p.l.counts_off, p.l.lists_off);                                         \
         break;
     switch (p.ROW) {
         QADC_F32_CASE(4)
@@ -199,15 +199,11 @@ int scan_topk_f32(int variant, const uint8_t *codes, int64_t n, int m, const flo
     for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
         const int nb = min(p.qbatch, nq - q0);
         const float *lq = luts + (size_t)q0 * M * p.KSUB;
-        prof_begin(QADC_PROF_SCAN, st);
         if (p.KSUB == 16) dispatch_f32<16>(p, codes, n, lq, nb, R, ws, st);
         else dispatch_f32<256>(p, codes, n, lq, nb, R, ws, st);
-        prof_end(QADC_PROF_SCAN, st);
-        prof_begin(QADC_PROF_MERGE, st);
-        hipLaunchKernelGGL((merge_topk_kernel<float, 8>), dim3(nb), dim3(MERGE_NT), 0, st, ws, p.l.stride,
-                           p.l.counts_off, p.l.lists_off, p.G, (unsigned)min((int64_t)R, n), R,
-                           __builtin_inff(), out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
-        prof_end(QADC_PROF_MERGE, st);
+        launch(QADC_PROF_MERGE, (merge_topk_kernel<float, 8>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
+               p.l.stride, p.l.counts_off, p.l.lists_off, p.G, (unsigned)min((int64_t)R, n), R,
+               __builtin_inff(), out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
     }
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;

@@ -400,3 +400,17 @@ def test_float_adc_scan_shapes(Q, variant_m, n):
     wi, wd = cref.scan_topk_f32(codes, luts, 64)
     assert np.array_equal(gi, wi), (bits, m, n)
     assert np.array_equal(gd.view(np.uint32), wd.view(np.uint32)), (bits, m, n)
+
+
+@pytest.mark.parametrize("shape", [(128, 16, 16, 6000, 4), (96, 8, 256, 3000, 2)])
+def test_pq_train_matches_oracle(Q, O, shape):
+    """GPU k-means (float64 assignment, deterministic float64 means) against the oracle's Lloyd."""
+    from workloads import MixtureSpec, mixture_vectors, kmeans_init_rows, SEED_TRAIN
+    d, m, k, n, iters = shape
+    train = mixture_vectors(MixtureSpec(d=d), SEED_TRAIN, 0, n)
+    rows = kmeans_init_rows(n, k)
+    want = O.pq_train(train, m, k, iters, rows)
+    got = Q.qadc_pq_train(to_gpu(train), m, k, to_gpu(rows), iters).cpu().numpy()
+    np.testing.assert_allclose(got, want, rtol=2e-6, atol=1e-5)
+    again = Q.qadc_pq_train(to_gpu(train), m, k, to_gpu(rows), iters).cpu().numpy()
+    assert np.array_equal(got, again)
