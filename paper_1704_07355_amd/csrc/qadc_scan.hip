@@ -159,6 +159,11 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
     for (int e = tid; e < 256; e += NT) hist[e] = 0;
     __syncthreads();
 
+    if (g == 0) {  // the scan kernel takes the pair tables from here instead of rebuilding them
+        ScanHeader *hdr0 = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+        for (int e = tid; e < B * 64; e += NT)
+            reinterpret_cast<unsigned *>(hdr0->ptab)[e] = reinterpret_cast<const unsigned *>(ptab)[e];
+    }
     unsigned k[C::CPT];
     tile_keys<B, NT>(w, nc, 0u, ptab, cap, k);
 #pragma unroll
@@ -219,13 +224,8 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     int nc[2];
     tile_load<B, NT>(codes, (int64_t)g * C::TILE, n, w, nc);  // first tile: in flight during set-up
 
-    // quantized tables -> LDS, and the grid-wide bound left by the seed kernel: the bin where
-    // the running count of the summed replicas reaches R, or 256.
-    {
-        const uint8_t *qlut = qluts + (size_t)q * (2 * B) * 16;
-        for (int e = tid; e < 2 * B * 4; e += NT)
-            reinterpret_cast<unsigned *>(qlut_s)[e] = reinterpret_cast<const unsigned *>(qlut)[e];
-    }
+    // The grid-wide bound left by the seed kernel: the bin where the running count of the
+    // summed replicas reaches R, or 256.  Pair tables: those of the seed kernel, or built here.
     if (tid < WAVE) {
         unsigned t = 256, carry = 0;
         for (unsigned b0 = 0; b0 < 256 && has_seed; b0 += 128) {  // uniform
@@ -245,12 +245,20 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
         if (tid == 0) { sh.tau = t; sh.fcnt = 0; sh.tcnt[0] = 0; }
     }
     for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
-    __syncthreads();
-    for (int e = tid; e < B * 256; e += NT) {
-        const int jb = e >> 8, v = e & 255;
-        const unsigned s = (unsigned)qlut_s[(2 * jb) * 16 + (v & 15)] +
-                           (unsigned)qlut_s[(2 * jb + 1) * 16 + (v >> 4)];
-        ptab[e] = (uint8_t)min(s, cap);
+    if (has_seed) {
+        for (int e = tid; e < B * 16; e += NT)
+            reinterpret_cast<uint4 *>(ptab)[e] = reinterpret_cast<const uint4 *>(hdr->ptab)[e];
+    } else {
+        const uint8_t *qlut = qluts + (size_t)q * (2 * B) * 16;
+        for (int e = tid; e < 2 * B * 4; e += NT)
+            reinterpret_cast<unsigned *>(qlut_s)[e] = reinterpret_cast<const unsigned *>(qlut)[e];
+        __syncthreads();
+        for (int e = tid; e < B * 256; e += NT) {
+            const int jb = e >> 8, v = e & 255;
+            const unsigned s = (unsigned)qlut_s[(2 * jb) * 16 + (v & 15)] +
+                               (unsigned)qlut_s[(2 * jb + 1) * 16 + (v >> 4)];
+            ptab[e] = (uint8_t)min(s, cap);
+        }
     }
     __syncthreads();
 

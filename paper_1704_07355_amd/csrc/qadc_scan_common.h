@@ -19,6 +19,7 @@ constexpr unsigned NO_KEY = 0xffffffffu;
 // kernel starts; the merge kernel leaves every word the call wrote zeroed again.
 struct alignas(256) ScanHeader {
     unsigned ghist[GH_REP][256];  // sums of the best codes of every seed tile
+    uint8_t ptab[32 * 256];       // the query's pair tables, left by the seed kernel for the scan
 };
 
 template <int B, int NT>
@@ -139,12 +140,18 @@ __device__ __forceinline__ float ord2f(unsigned o)
 // ---------------------------------------------------------------- merge
 
 constexpr int MERGE_NT = 1024;
-constexpr int MERGE_CAP = 4096;
+constexpr int MERGE_CAP = 4096;   // keys staged in LDS
+constexpr int MERGE_WG_PER_THREAD = 8;
 
 // R best of the keys reported by the G workgroups of each query (64-bit keys
 // dist << 32 | index, at most R per workgroup), ordered; then everything the call wrote
 // in the workspace is cleared.  KBYTES = significant key bytes (5 for u8 distances).
-// DistT = uint8_t: the distance is the key's bits 32..39; float: bits 32..63.
+// DistT = uint8_t: the distance is the key's bits 32..39; float: bits 32..63 (ordered image).
+//
+// Usual case (a few hundred keys in all): one histogram pass over the most significant key
+// byte finds the bin of the R-th key; the keys up to that bin are ranked against each other
+// by counting, which selects and orders in one step.  Massive ties fall back to the full
+// radix select.
 template <typename DistT, int KBYTES>
 __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off, int G,
@@ -153,14 +160,16 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
 {
     // need = min(R, number of codes scanned): at least that many keys were reported.
     __shared__ uint64_t lkeys[MERGE_CAP];
+    __shared__ uint64_t cand[MERGE_NT];
     __shared__ SelectScratch sc;
-    __shared__ unsigned lcnt;
+    __shared__ unsigned lcnt, ccnt;
 
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
     ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
     unsigned *counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + counts_off);
     uint64_t *lists = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + lists_off);
+    constexpr int TOP = (KBYTES - 1) * 8;
 
     // every reported key, spread over the threads by workgroup
     auto each_key = [&](auto f) {
@@ -170,36 +179,91 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         }
     };
 
-    if (tid == 0) lcnt = 0;
+    // Gather.  Counts and the first key of every region are fetched together (most regions
+    // hold zero or one key), further keys in a second round.
+    if (tid == 0) { lcnt = 0; ccnt = 0; }
+    for (int i = tid; i < 256; i += MERGE_NT) sc.hist[i] = 0;
     __syncthreads();
-    each_key([&](uint64_t k) {
-        const unsigned slot = atomicAdd(&lcnt, 1u);
-        if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
-    });
+    unsigned mycnt[MERGE_WG_PER_THREAD];
+#pragma unroll
+    for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
+        const int g = tid + t * MERGE_NT;
+        mycnt[t] = 0;
+        if (g < G) {
+            const unsigned c = min(counts[g], (unsigned)R);
+            const uint64_t k0 = lists[(size_t)g * R];
+            mycnt[t] = c;
+            for (unsigned i = 0; i < c; ++i) {
+                const uint64_t k = i ? lists[(size_t)g * R + i] : k0;
+                const unsigned slot = atomicAdd(&lcnt, 1u);
+                if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
+                atomicAdd(&sc.hist[(unsigned)(k >> TOP) & 255u], 1u);
+            }
+        }
+    }
+    for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {  // very wide grids
+        const unsigned c = min(counts[g], (unsigned)R);
+        for (unsigned i = 0; i < c; ++i) {
+            const uint64_t k = lists[(size_t)g * R + i];
+            const unsigned slot = atomicAdd(&lcnt, 1u);
+            if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
+            atomicAdd(&sc.hist[(unsigned)(k >> TOP) & 255u], 1u);
+        }
+    }
     __syncthreads();
     const unsigned total = lcnt;
     need = min(need, total);
     const bool in_lds = total <= (unsigned)MERGE_CAP;
 
-    uint64_t kth = 0;
-    if (need > 0) {
+    bool done = false;
+    if (need > 0 && in_lds) {
+        // bin of the need-th key by its most significant byte, and the keys up to that bin
+        select_bin(&sc, need);
+        __syncthreads();
+        const unsigned bin = sc.bin;
+        for (unsigned i = tid; i < total; i += MERGE_NT) {
+            const uint64_t k = lkeys[i];
+            if (((unsigned)(k >> TOP) & 255u) <= bin) {
+                const unsigned slot = atomicAdd(&ccnt, 1u);
+                if (slot < (unsigned)MERGE_NT) cand[slot] = k;
+            }
+        }
+        __syncthreads();
+        const unsigned nc = ccnt;
+        if (nc <= (unsigned)MERGE_NT) {  // uniform: rank the candidates against each other
+            if ((unsigned)tid < nc) {
+                const uint64_t k = cand[tid];
+                unsigned rank = 0;
+                for (unsigned j = 0; j < nc; ++j) rank += (cand[j] < k) ? 1u : 0u;
+                if (rank < need) {
+                    DistT d;
+                    if constexpr (sizeof(DistT) == 1) d = (DistT)((k >> 32) & 0xff);
+                    else d = ord2f((unsigned)(k >> 32));
+                    out_idx[(size_t)q * R + rank] = (uint32_t)k;
+                    out_dist[(size_t)q * R + rank] = d;
+                }
+            }
+            done = true;
+        }
+        __syncthreads();
+    }
+
+    if (need > 0 && !done) {
+        // full radix select, then order the winners by rank
+        uint64_t kth;
         if (in_lds) kth = block_radix_select<uint64_t, KBYTES>(lkeys, total, need, &sc);
         else kth = block_radix_select_each<uint64_t, KBYTES>(each_key, need, &sc);
-    }
-    __syncthreads();
-
-    // gather the `need` keys <= kth into lkeys[0..need), then order them by rank
-    uint64_t mine[MERGE_CAP / MERGE_NT];
-    if (in_lds) {
+        __syncthreads();
+        uint64_t mine[MERGE_CAP / MERGE_NT];
+        if (in_lds) {
 #pragma unroll
-        for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
-            const unsigned i = tid + t * MERGE_NT;
-            mine[t] = (i < total) ? lkeys[i] : ~0ull;
+            for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
+                const unsigned i = tid + t * MERGE_NT;
+                mine[t] = (i < total) ? lkeys[i] : ~0ull;
+            }
         }
-    }
-    if (tid == 0) lcnt = 0;
-    __syncthreads();
-    if (need > 0) {
+        if (tid == 0) lcnt = 0;
+        __syncthreads();
         if (in_lds) {
 #pragma unroll
             for (int t = 0; t < MERGE_CAP / MERGE_NT; ++t) {
@@ -213,14 +277,8 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
                 if (k <= kth) lkeys[atomicAdd(&lcnt, 1u)] = k;  // exactly `need` keys: they are unique
             });
         }
-    }
-    __syncthreads();
-
-    for (unsigned i = tid; i < (unsigned)R; i += MERGE_NT) {
-        if (i >= need) {
-            out_idx[(size_t)q * R + i] = 0xffffffffu;
-            out_dist[(size_t)q * R + i] = pad_dist;
-        } else {
+        __syncthreads();
+        for (unsigned i = tid; i < need; i += MERGE_NT) {
             const uint64_t k = lkeys[i];
             unsigned rank = 0;
             for (unsigned j = 0; j < need; ++j) rank += (lkeys[j] < k) ? 1u : 0u;
@@ -231,17 +289,28 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
             out_dist[(size_t)q * R + rank] = d;
         }
     }
+    for (unsigned i = need + tid; i < (unsigned)R; i += MERGE_NT) {
+        out_idx[(size_t)q * R + i] = 0xffffffffu;
+        out_dist[(size_t)q * R + i] = pad_dist;
+    }
 
     // Leave every word this call wrote in the workspace zero again, so that the next call
     // finds clean control blocks wherever its own layout puts them.
-    __syncthreads();
-    for (int g = tid; g < G; g += MERGE_NT) {
+#pragma unroll
+    for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
+        const int g = tid + t * MERGE_NT;
+        if (g < G && mycnt[t]) {
+            for (unsigned i = 0; i < mycnt[t]; ++i) lists[(size_t)g * R + i] = 0;
+            counts[g] = 0;
+        }
+    }
+    for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {
         const unsigned c = min(counts[g], (unsigned)R);
         for (unsigned i = 0; i < c; ++i) lists[(size_t)g * R + i] = 0;
-        counts[g] = 0;
+        if (c) counts[g] = 0;
     }
-    unsigned *z = &hdr->ghist[0][0];
-    for (int i = tid; i < GH_REP * 256; i += MERGE_NT) z[i] = 0;
+    unsigned *z = reinterpret_cast<unsigned *>(hdr);
+    for (int i = tid; i < (int)(sizeof(ScanHeader) / 4); i += MERGE_NT) z[i] = 0;
 }
 
 // Workspace layout of one scan call: per query a ScanHeader, counts[G], lists[G][R].
