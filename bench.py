@@ -6,8 +6,9 @@ data, PQ m=16 x 16 centroids (64-bit codes) trained by 10 k-means iterations
 on 20,000 vectors, N = 10,000,000 codes contiguous in HBM, queries issued one
 at a time, uint8 tables (init = 200), R = 100.
 
-One "step" is one query through the whole path on one stream:
-    qadc_build_luts -> qadc_quantize_luts -> qadc_scan_topk
+One "step" is one query through the whole path on one stream -- Tables, quantization
+of the tables, scan, top-R -- by qadc_search (or, with --separate-calls, by
+qadc_build_luts -> qadc_quantize_luts -> qadc_scan_topk: same arithmetic, more launches)
 over 10 M codes already resident in HBM.  Successive steps scan successive
 code buffers out of `--buffers` distinct ones (default 8 x 80 MB = 640 MB),
 so that the scan streams from HBM and not from the 256 MB last-level cache.
@@ -48,6 +49,8 @@ def parse():
     ap.add_argument("--cpu-queries", type=int, default=256, help="queries of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--recall-queries", type=int, default=100, help="queries of the accuracy sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timing pass")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
     return ap.parse_args()
 
 
@@ -132,7 +135,7 @@ def main():
     t_build = time.time() - t0
     bufs = [codes[b * n:(b + 1) * n] for b in range(args.buffers)]
 
-    ws_bytes = Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, n, m, 1, R)
+    ws_bytes = Q.qadc_workspace_bytes(Q.QADC_WS_SEARCH, n, m, 1, R)
     ws = Q.qadc_workspace_init(torch.empty(ws_bytes, dtype=torch.uint8, device=dev))
     luts = torch.empty((1, m, 16), dtype=torch.float32, device=dev)
     out_idx = torch.empty((1, R), dtype=torch.int32, device=dev)
@@ -141,9 +144,13 @@ def main():
     def step(i):
         qi = i % args.queries
         buf = bufs[i % args.buffers]
-        Q.qadc_build_luts(cb, queries[qi:qi + 1], out=luts)
-        ql, _, _, _ = Q.qadc_quantize_luts(luts, buf[:init], R)
-        Q.qadc_scan_topk(Q.QADC_U8_4BIT, buf, ql, R, workspace=ws, out_idx=out_idx, out_dist=out_dist)
+        if args.separate_calls:
+            Q.qadc_build_luts(cb, queries[qi:qi + 1], out=luts)
+            ql, _, _, _ = Q.qadc_quantize_luts(luts, buf[:init], R)
+            Q.qadc_scan_topk(Q.QADC_U8_4BIT, buf, ql, R, workspace=ws, out_idx=out_idx, out_dist=out_dist)
+        else:
+            Q.qadc_search(cb, queries[qi:qi + 1], buf, R, init, workspace=ws, out_idx=out_idx,
+                          out_dist=out_dist)
 
     for i in range(args.warmup):
         step(i)
@@ -171,7 +178,7 @@ def main():
         us = {}
         for name, which in (("scan", Q.QADC_PROF_SCAN), ("seed", Q.QADC_PROF_SEED),
                             ("merge", Q.QADC_PROF_MERGE), ("tables", Q.QADC_PROF_TABLES),
-                            ("quantize", Q.QADC_PROF_QUANTIZE)):
+                            ("quantize", Q.QADC_PROF_QUANTIZE), ("prepare", Q.QADC_PROF_PREPARE)):
             ms, cnt = Q.qadc_profile_read(which)
             us[name] = (ms / max(1, cnt) * 1e3, cnt)
         Q.qadc_profile_enable(False)
@@ -181,7 +188,7 @@ def main():
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                     "traffic": None, "avg_kernel_us": round(avg_us, 2),
                     "bytes_per_launch": n * row, "launches_timed": launches}
-        kernels = {k + "_kernel_us": round(v[0], 2) for k, v in us.items()}
+        kernels = {k + "_kernel_us": round(v[0], 2) for k, v in us.items() if v[1]}
 
     acc = None
     if args.recall_queries > 0:
@@ -218,7 +225,8 @@ def main():
         "config": {"workload": "config 2: single-query scan, d=128 mixture, PQ m=%d x 4-bit (10 k-means "
                    "iterations on 20k vectors), N=%d codes contiguous, queries one at a time, R=%d, "
                    "init=%d, %d rotating code buffers" % (m, n, R, init, args.buffers),
-                   "n": n, "m": m, "R": R, "init": init, "nbins": 255, "buffers": args.buffers},
+                   "n": n, "m": m, "R": R, "init": init, "nbins": 255, "buffers": args.buffers,
+                   "entry": "build_luts+quantize_luts+scan_topk" if args.separate_calls else "qadc_search"},
         "hbm_gbps_whole_path": round(n * row / (ms_per_step * 1e-3) / 1e9, 1),
         "pct_hbm_peak_whole_path": round(100 * n * row / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
         "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,

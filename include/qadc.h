@@ -63,6 +63,7 @@ extern "C" {
 #define QADC_WS_SCAN_TOPK      0 /* qadc_scan_topk, variant QADC_U8_4BIT  */
 #define QADC_WS_SCAN_F32_4BIT  1 /* qadc_scan_topk, variant QADC_F32_4BIT */
 #define QADC_WS_SCAN_F32_8BIT  2 /* qadc_scan_topk, variant QADC_F32_8BIT */
+#define QADC_WS_SEARCH         3 /* qadc_search */
 
 /*
  * Tables step, Eq. (1) of the paper:
@@ -129,6 +130,22 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m,
                    const void *luts, int nq, int R, int nbins,
                    uint32_t *out_idx, void *out_dist,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Exhaustive Quick ADC search in one call: Tables (Eq. (1)), quantization of the tables
+ * (Section 3.3, qmax from the first min(init, n) codes of `codes`), scan with saturating sums
+ * and top-R (Alg. 2) -- the same arithmetic, operation for operation, as qadc_build_luts +
+ * qadc_quantize_luts(ngroup = 1) + qadc_scan_topk(QADC_U8_4BIT), in fewer kernel launches:
+ * for large databases the tables are recomputed inside the kernel that samples the codes.
+ *   codebooks [m][16][d/m] f32;  queries [nq][d] f32;  codes [n][m/2] u8 (n >= 1)
+ *   out_idx [nq][R] u32, out_dist [nq][R] u8 as qadc_scan_topk
+ *   qluts_out [nq][m][16] u8 or NULL: the quantized tables used (output, for replay/tests)
+ *   workspace >= qadc_workspace_bytes(QADC_WS_SEARCH, n, m, nq, R), cleared once as above
+ */
+int qadc_search(const float *codebooks, int d, int m, const float *queries, int nq,
+                const uint8_t *codes, int64_t n, int R, int init, int nbins, int qmin_mode,
+                uint32_t *out_idx, uint8_t *out_dist, uint8_t *qluts_out,
+                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Inverted index (Section 2.2): K cells around the coarse centroids; the codes of the
@@ -200,7 +217,8 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
 #define QADC_PROF_IVF_TABLES 4  /* Tables step of qadc_ivf_search (tables, qmax, quantization)   */
 #define QADC_PROF_TABLES     5  /* qadc_build_luts kernel */
 #define QADC_PROF_QUANTIZE   6  /* qadc_quantize_luts kernel */
-#define QADC_PROF_COUNT  7
+#define QADC_PROF_PREPARE    7  /* tables + quantizer + sampling kernel of qadc_search */
+#define QADC_PROF_COUNT  8
 int qadc_profile_enable(int on);
 int qadc_profile_read(int which, double *total_ms, int64_t *launches);
 

@@ -21,12 +21,12 @@ QADC_MAX_R = 1024
 QADC_MAX_INIT = 8192
 QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
 QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
-QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT = 0, 1, 2
+QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT, QADC_WS_SEARCH = 0, 1, 2, 3
 (QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES,
- QADC_PROF_TABLES, QADC_PROF_QUANTIZE) = range(7)
+ QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE) = range(8)
 
 EXPORTS = (
-    "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_ivf_search",
+    "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
     "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train",
     "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version",
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.qadc_quantize_luts.restype = i32
         L.qadc_scan_topk.argtypes = [i32, vp, i64, i32, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.qadc_scan_topk.restype = i32
+        L.qadc_search.argtypes = [vp, i32, i32, vp, i32, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.qadc_search.restype = i32
         L.qadc_ivf_search.argtypes = [ctypes.POINTER(qadc_ivf_index), vp, i32, i32, i32, i32, i32, i32,
                                       vp, vp, vp, vp, vp, vp, sz, vp]
         L.qadc_ivf_search.restype = i32
@@ -257,3 +259,25 @@ def qadc_pq_train(train, m, ksub, init_rows, iters):
     _check(lib().qadc_pq_train(_ptr(train, torch.float32), n, d, m, ksub, _ptr(init_rows, torch.int64),
                                iters, _ptr(cb), _ptr(ws), ws.numel(), _stream()))
     return cb
+
+
+def qadc_search(codebooks, queries, codes, R, init, nbins=255, qmin_mode=QADC_QMIN_PER_TABLE,
+                workspace=None, out_idx=None, out_dist=None, qluts_out=None, n=None):
+    """Whole exhaustive Quick ADC query path in one call -> (idx u32-bits [nq][R], dist u8 [nq][R])."""
+    m, ksub, dsub = codebooks.shape
+    nq, d = queries.shape
+    if n is None:
+        n = codes.shape[0]
+    dev = queries.device
+    if out_idx is None:
+        out_idx = torch.empty((nq, R), dtype=torch.int32, device=dev)
+    if out_dist is None:
+        out_dist = torch.empty((nq, R), dtype=torch.uint8, device=dev)
+    if workspace is None:
+        need = qadc_workspace_bytes(QADC_WS_SEARCH, n, m, nq, R)
+        workspace = qadc_workspace_init(torch.empty((max(need, 256),), dtype=torch.uint8, device=dev))
+    _check(lib().qadc_search(_ptr(codebooks, torch.float32), d, m, _ptr(queries, torch.float32), nq,
+                             _ptr(codes, torch.uint8), n, R, init, nbins, qmin_mode, _ptr(out_idx),
+                             _ptr(out_dist), _ptr(qluts_out, torch.uint8), _ptr(workspace),
+                             workspace.numel() * workspace.element_size(), _stream()))
+    return out_idx, out_dist

@@ -27,6 +27,9 @@ int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const 
 int scan_topk_u8(const uint8_t *, int64_t, int, const uint8_t *, int, int, int, uint32_t *,
                  uint8_t *, void *, size_t, hipStream_t);
 size_t scan_topk_u8_workspace(int64_t, int, int, int);
+int search_u8(const float *, int, int, const float *, int, const uint8_t *, int64_t, int, int, int, int,
+              uint32_t *, uint8_t *, uint8_t *, void *, size_t, hipStream_t);
+size_t search_workspace(int64_t, int, int, int);
 int scan_topk_f32(int, const uint8_t *, int64_t, int, const float *, int, int, uint32_t *, float *,
                   void *, size_t, hipStream_t);
 size_t scan_topk_f32_workspace(int, int64_t, int, int, int);
@@ -78,6 +81,15 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void 
     }
 }
 
+int qadc_search(const float *codebooks, int d, int m, const float *queries, int nq,
+                const uint8_t *codes, int64_t n, int R, int init, int nbins, int qmin_mode,
+                uint32_t *out_idx, uint8_t *out_dist, uint8_t *qluts_out, void *workspace,
+                size_t workspace_bytes, void *stream)
+{
+    return qadc::search_u8(codebooks, d, m, queries, nq, codes, n, R, init, nbins, qmin_mode, out_idx,
+                           out_dist, qluts_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
 int qadc_ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprobe, int R,
                     int init, int nbins, int qmin_mode, const int32_t *probes_in,
                     uint32_t *out_ids, uint8_t *out_dist, int32_t *dbg_probes, uint8_t *dbg_qluts,
@@ -119,6 +131,7 @@ size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)
     case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(n, m, nq, R);
     case QADC_WS_SCAN_F32_4BIT: return qadc::scan_topk_f32_workspace(QADC_F32_4BIT, n, m, nq, R);
     case QADC_WS_SCAN_F32_8BIT: return qadc::scan_topk_f32_workspace(QADC_F32_8BIT, n, m, nq, R);
+    case QADC_WS_SEARCH: return qadc::search_workspace(n, m, nq, R);
     default: return 0;
     }
 }

@@ -188,6 +188,221 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
     }
 }
 
+// Prepare kernel of qadc_search: Tables (Eq. (1)), the init scan and the quantizer of
+// Section 3.3, the pair tables and the seed sample of the scan, all in one launch.  Every
+// workgroup recomputes the query's (tiny) tables for itself -- 16 x d subtractions and
+// multiplies and `init` float ADC sums -- so that nothing has to travel between workgroups
+// before the sample can be scanned; workgroup 0 writes the tables out.  The arithmetic is
+// the one of build_luts_kernel and quantize_luts_kernel, operation for operation.
+constexpr int PREP_MAX_D = 2048;
+
+template <int B>
+__global__ __launch_bounds__(1024) void prepare_u8_kernel(
+    const float *__restrict__ codebooks, int d, const float *__restrict__ queries,
+    const uint8_t *__restrict__ codes, int64_t n, int n_init, int R, int nbins, int qmin_mode,
+    unsigned flush_need, int64_t seed_stride, float *__restrict__ luts_out,
+    uint8_t *__restrict__ qluts_out, float *__restrict__ bias_out, float *__restrict__ delta_out,
+    float *__restrict__ qmax_out, char *__restrict__ ws, size_t ws_stride)
+{
+    constexpr int NT = 1024;
+    constexpr int M = 2 * B;
+    using C = ScanCfg<B, NT>;
+    __shared__ double yq[PREP_MAX_D];
+    __shared__ float lut[M * 16];
+    __shared__ __attribute__((aligned(16))) unsigned cand[QADC_MAX_INIT];
+    __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
+    __shared__ __attribute__((aligned(16))) uint8_t qlut_s[M * 16];
+    __shared__ float bias[M];
+    __shared__ SelectScratch sc;
+    __shared__ unsigned qmax_ord;
+    __shared__ float delta_s;
+
+    const int tid = threadIdx.x;
+    const int q = blockIdx.y;
+    const int g = blockIdx.x;
+    const unsigned cap = (unsigned)nbins;
+    const int dsub = d / M;
+    const int64_t c0 = (int64_t)g * seed_stride;
+    const int64_t c1 = min(n, c0 + C::TILE);
+
+    // Every global load the set-up needs is issued here, before the first wait: the sample
+    // tile, the query, this thread's centroid (one table entry per thread) and init code.
+    uint4 w[2];
+    int nc[2] = {0, 0};
+    if (c0 < c1) tile_load<B, NT>(codes, c0, c1, w, nc);
+    constexpr int DREG = 16;  // sub-space dimensions held in registers
+    float cv[DREG];
+    const bool cv_regs = dsub <= DREG;  // uniform
+    if (cv_regs && tid < M * 16) {
+        const float *c = codebooks + (size_t)tid * dsub;
+#pragma unroll
+        for (int t = 0; t < DREG; ++t) cv[t] = (t < dsub) ? c[t] : 0.0f;
+    }
+    unsigned cw[B / 4];
+    if (tid < n_init) {
+        const unsigned *c = reinterpret_cast<const unsigned *>(codes + (size_t)tid * B);
+#pragma unroll
+        for (int k = 0; k < B / 4; ++k) cw[k] = c[k];
+    }
+    for (int t = tid; t < d; t += NT) yq[t] = (double)queries[(size_t)q * d + t];
+    __syncthreads();
+
+    // Tables, Eq. (1): float64 differences and sums, one rounding
+    if (tid < M * 16) {
+        const int j = tid >> 4;
+        const double *y = yq + j * dsub;
+        double acc = 0.0;
+        if (cv_regs) {
+#pragma unroll
+            for (int t = 0; t < DREG; ++t) {
+                if (t < dsub) {
+                    const double df = y[t] - (double)cv[t];
+                    acc += df * df;
+                }
+            }
+        } else {
+            const float *c = codebooks + (size_t)tid * dsub;
+            for (int t = 0; t < dsub; ++t) {
+                const double df = y[t] - (double)c[t];
+                acc += df * df;
+            }
+        }
+        lut[tid] = (float)acc;
+    }
+    for (int e = tid; e < 256; e += NT) sc.hist[e] = 0;  // rank counters / histogram, used below
+    __syncthreads();
+
+    // qmax: the min(R, n_init)-th smallest float ADC distance (float32, increasing j) of the init codes
+    for (int i = tid; i < n_init; i += NT) {
+        float acc = 0.0f;
+        if (i == tid) {
+#pragma unroll
+            for (int jb = 0; jb < B; ++jb) {
+                const unsigned comps = (cw[jb >> 2] >> (8 * (jb & 3))) & 0xffu;
+                acc = acc + lut[(2 * jb) * 16 + (comps & 15u)];
+                acc = acc + lut[(2 * jb + 1) * 16 + (comps >> 4)];
+            }
+        } else {
+            const uint8_t *c = codes + (size_t)i * B;
+            for (int jb = 0; jb < B; ++jb) {
+                const unsigned comps = c[jb];
+                acc = acc + lut[(2 * jb) * 16 + (comps & 15u)];
+                acc = acc + lut[(2 * jb + 1) * 16 + (comps >> 4)];
+            }
+        }
+        cand[i] = f2ord(acc);
+    }
+    __syncthreads();
+    const unsigned need = (unsigned)min(R, n_init);
+    if (n_init <= 256) {
+        // uniform: rank by counting.  Thread (i, part) compares candidate i = tid & 255 with
+        // candidates 64*part .. 64*part+63, fetched four at a time; unused slots hold the
+        // largest value and never count.
+        if (tid >= n_init && tid < 256) cand[tid] = 0xffffffffu;
+        __syncthreads();
+        const int i = tid & 255, part = tid >> 8;
+        const unsigned mine = cand[i];
+        unsigned rank = 0;
+        const uint4 *c4 = reinterpret_cast<const uint4 *>(cand) + part * 16;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint4 o = c4[v];
+            const int j = part * 64 + v * 4;
+            rank += (o.x < mine || (o.x == mine && j + 0 < i)) ? 1u : 0u;
+            rank += (o.y < mine || (o.y == mine && j + 1 < i)) ? 1u : 0u;
+            rank += (o.z < mine || (o.z == mine && j + 2 < i)) ? 1u : 0u;
+            rank += (o.w < mine || (o.w == mine && j + 3 < i)) ? 1u : 0u;
+        }
+        if (i < n_init) atomicAdd(&sc.hist[i], rank);
+        __syncthreads();
+        if (tid < n_init && sc.hist[tid] == need - 1) qmax_ord = cand[tid];
+        __syncthreads();
+        if (tid < 256) sc.hist[tid] = 0;
+    } else {
+        const unsigned kth = block_radix_select<unsigned, 4>(cand, (unsigned)n_init, need, &sc);
+        if (tid == 0) qmax_ord = kth;
+        __syncthreads();
+        for (int e = tid; e < 256; e += NT) sc.hist[e] = 0;
+    }
+    __syncthreads();
+
+    // quantizer of Section 3.3
+    if (tid < M) {
+        float b = lut[tid * 16];
+        for (int i = 1; i < 16; ++i) b = fminf(b, lut[tid * 16 + i]);
+        bias[tid] = b;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const float qmax = ord2f(qmax_ord);
+        float qmin;
+        if (qmin_mode == QADC_QMIN_GLOBAL) {
+            qmin = bias[0];
+            for (int j = 1; j < M; ++j) qmin = fminf(qmin, bias[j]);
+            for (int j = 0; j < M; ++j) bias[j] = qmin;
+        } else {
+            qmin = 0.0f;
+            for (int j = 0; j < M; ++j) qmin = qmin + bias[j];
+        }
+        float delta = __fdiv_rn(qmax - qmin, (float)nbins);
+        if (!(delta > 0.0f)) delta = 1.0f;
+        delta_s = delta;
+        if (g == 0) {
+            if (delta_out) delta_out[q] = delta;
+            if (qmax_out) qmax_out[q] = qmax;
+        }
+    }
+    __syncthreads();
+    if (tid < M * 16) {
+        const float off = fmaxf(0.0f, lut[tid] - bias[tid >> 4]);
+        const float t = floorf(__fdiv_rn(off, delta_s));
+        const uint8_t qv = (t < (float)nbins) ? (uint8_t)t : (uint8_t)nbins;
+        qlut_s[tid] = qv;
+        if (g == 0) {
+            if (qluts_out) qluts_out[(size_t)q * M * 16 + tid] = qv;
+            if (luts_out) luts_out[(size_t)q * M * 16 + tid] = lut[tid];
+            if (bias_out && (tid & 15) == 0) bias_out[(size_t)q * M + (tid >> 4)] = bias[tid >> 4];
+        }
+    }
+    __syncthreads();
+
+    // pair tables, handed to the scan kernel by workgroup 0
+    for (int e = tid; e < B * 256; e += NT) {
+        const int jb = e >> 8, v = e & 255;
+        const unsigned s = (unsigned)qlut_s[(2 * jb) * 16 + (v & 15)] +
+                           (unsigned)qlut_s[(2 * jb + 1) * 16 + (v >> 4)];
+        ptab[e] = (uint8_t)min(s, cap);
+    }
+    __syncthreads();
+    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+    if (g == 0)
+        for (int e = tid; e < B * 64; e += NT)
+            reinterpret_cast<unsigned *>(hdr->ptab)[e] = reinterpret_cast<const unsigned *>(ptab)[e];
+    if (c0 >= c1) return;  // uniform: no sample tile for this workgroup
+
+    // seed sample, as in seed_u8_kernel
+    unsigned k[C::CPT];
+    tile_keys<B, NT>(w, nc, 0u, ptab, cap, k);
+#pragma unroll
+    for (int c = 0; c < C::CPT; ++c)
+        if ((k[c] >> 24) < cap) atomicAdd(&sc.hist[k[c] >> 24], 1u);
+    __syncthreads();
+    if (tid < WAVE) {
+        unsigned h[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) h[b] = sc.hist[4 * tid + b];
+        const unsigned f = min(wave_threshold_bin<4>(h, (unsigned)R),
+                               wave_threshold_bin<4>(h, flush_need));
+        unsigned *ghist = hdr->ghist[g % GH_REP];
+        for (unsigned b0 = 0; b0 <= f && b0 < 256u; b0 += WAVE) {  // uniform
+            const unsigned bin = b0 + tid;
+            const unsigned c = sc.hist[bin];
+            if (bin <= f && bin < cap && c)
+                __hip_atomic_fetch_add(&ghist[bin], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 // Scan kernel.  The database is cut into tiles of TILE codes; workgroup g of G takes tiles
 // g, g+G, g+2G, ... so that at any moment the grid reads one contiguous window of HBM.
 // A candidate key is sum << 24 | (it * TILE + offset in tile), `it` counting the workgroup's
@@ -489,6 +704,88 @@ int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, i
         launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
                            p.stride, p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n),
                R, (uint8_t)nbins, out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
+    }
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+int build_luts(const float *, int, int, int, const float *, const float *, int, float *, hipStream_t);
+int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
+                  int, uint8_t *, float *, float *, float *, hipStream_t);
+
+// Workspace of qadc_search: the scan workspace, then float tables and quantized tables of a batch.
+static size_t search_extra_bytes(int m, int qbatch)
+{
+    return align_up((size_t)qbatch * m * 16 * sizeof(float), 256) + align_up((size_t)qbatch * m * 16, 256);
+}
+
+size_t search_workspace(int64_t n, int m, int nq, int R)
+{
+    ScanPlan p;
+    if (!make_scan_plan(QADC_U8_4BIT, n, m, nq, R, &p)) return 0;
+    return p.ws_bytes + search_extra_bytes(m, p.qbatch);
+}
+
+int search_u8(const float *codebooks, int d, int m, const float *queries, int nq, const uint8_t *codes,
+              int64_t n, int R, int init, int nbins, int qmin_mode, uint32_t *out_idx,
+              uint8_t *out_dist, uint8_t *qluts_out, void *workspace, size_t workspace_bytes,
+              hipStream_t st)
+{
+    ScanPlan p;
+    if (!codebooks || !queries || !out_idx || !out_dist || (!codes && n > 0))
+        return fail(QADC_EINVAL, "qadc_search: null pointer");
+    if (nq == 0) return QADC_OK;
+    if (!make_scan_plan(QADC_U8_4BIT, n, m, nq, R, &p) || d < m || d % m != 0 || d > PREP_MAX_D)
+        return fail(QADC_EINVAL, "qadc_search: unsupported n=%lld d=%d m=%d nq=%d R=%d", (long long)n, d, m,
+                    nq, R);
+    if (nbins < 1 || nbins > 255 || init < 1 || init > QADC_MAX_INIT || n < 1)
+        return fail(QADC_EINVAL, "qadc_search: nbins=%d init=%d n=%lld", nbins, init, (long long)n);
+    if (qmin_mode != QADC_QMIN_PER_TABLE && qmin_mode != QADC_QMIN_GLOBAL)
+        return fail(QADC_EINVAL, "qadc_search: qmin_mode=%d", qmin_mode);
+    if (((uintptr_t)codes & 15) != 0) return fail(QADC_EINVAL, "qadc_search: codes must be 16-byte aligned");
+    const size_t need = p.ws_bytes + search_extra_bytes(m, p.qbatch);
+    if (!workspace || workspace_bytes < need)
+        return fail(QADC_ENOMEM, "qadc_search: workspace %zu < %zu bytes", workspace_bytes, need);
+    if (((uintptr_t)workspace & 255) != 0)
+        return fail(QADC_EINVAL, "qadc_search: workspace must be 256-byte aligned");
+    char *ws = (char *)workspace;
+    float *luts = (float *)(ws + p.ws_bytes);
+    uint8_t *qluts = (uint8_t *)(ws + p.ws_bytes + align_up((size_t)p.qbatch * m * 16 * sizeof(float), 256));
+    const int n_init = (int)min((int64_t)init, n);
+    for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
+        const int nb = min(p.qbatch, nq - q0);
+        const float *yq = queries + (size_t)q0 * d;
+        uint8_t *ql_out = qluts_out ? qluts_out + (size_t)q0 * m * 16 : nullptr;
+        if (p.seed_wgs > 0) {
+            dim3 grid(p.seed_wgs, nb);
+#define QADC_PREP_CASE(B_)                                                                            \
+    case B_:                                                                                         \
+        launch(QADC_PROF_PREPARE, prepare_u8_kernel<B_>, grid, dim3(1024), 0, st, codebooks, d, yq, codes, \
+               n, n_init, R, nbins, qmin_mode, p.flush_need, p.seed_stride, (float *)nullptr, ql_out, \
+               (float *)nullptr, (float *)nullptr, (float *)nullptr, ws, p.stride);                  \
+        break;
+            switch (p.B) {
+                QADC_PREP_CASE(4)
+                QADC_PREP_CASE(8)
+                QADC_PREP_CASE(16)
+                QADC_PREP_CASE(32)
+            }
+#undef QADC_PREP_CASE
+        } else {  // small database: separate tables and quantizer kernels, the scan seeds itself
+            int rc = build_luts(codebooks, d, m, 16, yq, nullptr, nb, luts, st);
+            if (rc != QADC_OK) return rc;
+            rc = quantize_luts(luts, nb, 1, m, codes, n_init, nullptr, R, nbins, qmin_mode, qluts, nullptr,
+                               nullptr, nullptr, st);
+            if (rc != QADC_OK) return rc;
+            if (ql_out)
+                QADC_HIP_TRY(hipMemcpyAsync(ql_out, qluts, (size_t)nb * m * 16, hipMemcpyDeviceToDevice, st));
+        }
+        if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, qluts, nb, nbins, R, ws, st);
+        else if (p.NT == 512) dispatch_scan_u8<512>(p, codes, n, qluts, nb, nbins, R, ws, st);
+        else dispatch_scan_u8<256>(p, codes, n, qluts, nb, nbins, R, ws, st);
+        launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
+               p.stride, p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n), R, (uint8_t)nbins,
+               out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
     }
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;

@@ -414,3 +414,61 @@ def test_pq_train_matches_oracle(Q, O, shape):
     np.testing.assert_allclose(got, want, rtol=2e-6, atol=1e-5)
     again = Q.qadc_pq_train(to_gpu(train), m, k, to_gpu(rows), iters).cpu().numpy()
     assert np.array_equal(got, again)
+
+
+# ------------------------------------------------------------- qadc_search
+
+@pytest.mark.parametrize("n", [100_000, 700_003])
+@pytest.mark.parametrize("mode_nbins", [(0, 255), (1, 255), (0, 127)])
+def test_search_equals_the_three_call_chain_and_the_oracle(Q, O, n, mode_nbins):
+    """qadc_search = build_luts + quantize_luts + scan_topk, bit for bit (small databases take the
+    separate kernels, large ones the fused prepare kernel), and the oracle replays its integer part."""
+    import torch
+    mode, nbins = mode_nbins
+    c = config1()
+    cb, queries = c["codebooks"], c["queries"][:6]
+    reps = -(-n // len(c["codes"]))
+    codes = np.tile(c["codes"], (reps, 1))[:n].copy()
+    if reps > 1:
+        rng = np.random.default_rng(n)
+        codes[100_000:] ^= rng.integers(0, 256, size=codes[100_000:].shape, dtype=np.uint8) & 0x11
+    R, init = 100, 200
+    g_codes, g_cb, g_q = to_gpu(codes), to_gpu(cb), to_gpu(queries)
+    ql_out = torch.empty((len(queries), 16, 16), dtype=torch.uint8, device="cuda:0")
+    si, sd = Q.qadc_search(g_cb, g_q, g_codes, R, init, nbins, mode, qluts_out=ql_out)
+    luts = Q.qadc_build_luts(g_cb, g_q)
+    ql, _, _, _ = Q.qadc_quantize_luts(luts, g_codes[:init], R, nbins, mode)
+    ci, cd = Q.qadc_scan_topk(Q.QADC_U8_4BIT, g_codes, ql, R, nbins)
+    torch.cuda.synchronize()
+    assert torch.equal(ql_out, ql)
+    assert torch.equal(si, ci) and torch.equal(sd, cd)
+    h_ql = ql_out.cpu().numpy()
+    for iq in range(len(queries)):
+        wi, wd = oracle_topk(codes, h_ql[iq], R, nbins)
+        assert np.array_equal(idx_np(si)[iq], wi) and np.array_equal(sd[iq].cpu().numpy(), wd)
+        t = O.quick_adc_tables(cb, queries[iq], codes, init, R, nbins, mode)
+        assert np.abs(h_ql[iq].astype(int) - t["qlut"].astype(int)).max() <= 1
+
+
+def test_search_large_init_and_other_code_sizes(Q, O):
+    """init above 1024 (radix select instead of rank counting) and m = 8 / 32 in the fused kernel."""
+    import torch
+    from workloads import MixtureSpec, mixture_vectors, SEED_QUERY
+    rng = np.random.default_rng(31)
+    for m, init in [(8, 1500), (32, 1000), (16, 3000)]:
+        d = 128
+        cb = rng.uniform(0, 255, size=(m, 16, d // m)).astype(np.float32)
+        n = 600_011
+        codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+        queries = mixture_vectors(MixtureSpec(d=d), SEED_QUERY, 0, 3)
+        g_codes, g_cb, g_q = to_gpu(codes), to_gpu(cb), to_gpu(queries)
+        ql_out = torch.empty((3, m, 16), dtype=torch.uint8, device="cuda:0")
+        si, sd = Q.qadc_search(g_cb, g_q, g_codes, 100, init, qluts_out=ql_out)
+        luts = Q.qadc_build_luts(g_cb, g_q)
+        ql, _, _, _ = Q.qadc_quantize_luts(luts, g_codes[:init], 100)
+        torch.cuda.synchronize()
+        assert torch.equal(ql_out, ql), (m, init)
+        h_ql = ql_out.cpu().numpy()
+        for iq in range(3):
+            wi, wd = oracle_topk(codes, h_ql[iq], 100)
+            assert np.array_equal(idx_np(si)[iq], wi) and np.array_equal(sd[iq].cpu().numpy(), wd), (m, init)
