@@ -28,6 +28,7 @@
 // does not depend on how the grid is cut or on the order waves run in.
 
 #include "qadc_scan_common.h"
+#include "qadc_scan_tiled.h"
 
 namespace qadc {
 
@@ -39,42 +40,7 @@ struct ScanShared {
     unsigned fcnt;     // append counter of the barrier-free pass (may run past the list's end)
 };
 
-// Keys with sum <= tau are exactly the keys below this limit.
-__device__ __forceinline__ unsigned limit_of_bin(unsigned tau)
-{
-    return tau >= 255u ? NO_KEY : ((tau + 1u) << 24);
-}
-
-// Called by one whole wave; h[b] is the count of bin NB*lane+b.  Returns, in every lane,
-// the smallest bin whose inclusive running count reaches `need`, or 64*NB when none does.
-template <int NB>
-__device__ __forceinline__ unsigned wave_threshold_bin(const unsigned (&h)[NB], unsigned need,
-                                                       unsigned *total = nullptr)
-{
-    const int l = lane_id();
-    unsigned tot = 0;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) tot += h[b];
-    unsigned inc = tot;
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        const unsigned up = __shfl_up(inc, d);
-        if (l >= d) inc += up;
-    }
-    if (total) *total = __shfl(inc, WAVE - 1);
-    const unsigned long long m = __ballot(inc >= need);
-    if (m == 0) return (unsigned)(WAVE * NB);
-    const int first = __ffsll((long long)m) - 1;
-    unsigned run = inc - tot, bin = (unsigned)(NB * l + NB - 1);
-    bool found = false;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        run += h[b];
-        if (!found && run >= need) { bin = (unsigned)(NB * l + b); found = true; }
-    }
-    return __shfl(bin, first);
-}
-
+// One pair-table entry, known to the compiler as a byte value.
 __device__ __forceinline__ unsigned pair_entry(const uint8_t *ptab, int jb, unsigned v)
 {
     const unsigned e = ptab[jb * 256 + v];
@@ -419,7 +385,7 @@ template <int B, int NT>
 __global__ __launch_bounds__(NT) void scan_u8_kernel(
     const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
     int R, int has_seed, char *__restrict__ ws, size_t ws_stride, size_t counts_off,
-    size_t lists_off)
+    size_t lists_off, const unsigned *__restrict__ redo_flags)
 {
     using C = ScanCfg<B, NT>;
     __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
@@ -434,6 +400,7 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     const unsigned cap = (unsigned)cap_i;
     const ScanHeader *hdr = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride);
     if ((int64_t)g * C::TILE >= n) return;  // uniform: no tile for this workgroup
+    if (redo_flags && redo_flags[q] == 0) return;  // uniform: only the queries the tiled scan gave up on
 
     uint4 w[2];
     int nc[2];
@@ -577,6 +544,9 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
 
 struct ScanPlan {
     int B, NT, G, qbatch;
+    bool tiled;           // batches go through the query-tiled kernel
+    TiledPlan t;
+    size_t countsA_off, listsA_off, taus_off, flags_off;
     int64_t chunk;
     int seed_wgs;         // 0: no seed kernel
     int64_t seed_stride;  // codes between the sampled tiles
@@ -613,7 +583,12 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
     p->seed_stride = 0;
     p->flush_need = 16;
     if (seed_tiles >= env_int("QADC_SEED_MIN_TILES", 64)) {
-        int64_t S = env_int("QADC_SEED_WGS", 256);
+        int64_t S = env_int("QADC_SEED_WGS", 0);
+        if (S <= 0) {  // about 1/40 of the database, between 256 and 1024 tiles
+            S = seed_tiles / 40;
+            if (S < 256) S = 256;
+            if (S > 1024) S = 1024;
+        }
         if (S > seed_tiles / 4) S = seed_tiles / 4;
         if (S < 1) S = 1;
         p->seed_wgs = (int)S;
@@ -623,22 +598,36 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
         if (fl > R) fl = R;
         p->flush_need = (unsigned)fl;
     }
+    p->tiled = p->seed_wgs > 0 && nq >= TILED_MIN_Q && env_int("QADC_TILED", 1) != 0 &&
+               make_tiled_plan(n, m, nq, &p->t);
+    if (p->tiled && p->G > 256) p->G = 256;  // the single-query kernel only redoes rare queries
     const ScanLayout l = scan_layout(p->G, R);
     p->counts_off = l.counts_off;
     p->lists_off = l.lists_off;
     p->stride = l.stride;
+    p->countsA_off = p->listsA_off = p->taus_off = p->flags_off = 0;
+    if (p->tiled) {
+        p->countsA_off = p->stride;
+        p->listsA_off = p->countsA_off + align_up((size_t)p->t.GC * sizeof(unsigned), 256);
+        p->stride = p->listsA_off + align_up((size_t)p->t.GC * TILED_LCAP * sizeof(uint64_t), 256);
+    }
     p->qbatch = scan_query_batch(p->stride, nq);
     p->ws_bytes = p->stride * (size_t)p->qbatch;
+    if (p->tiled) {
+        p->taus_off = p->ws_bytes;
+        p->flags_off = p->taus_off + align_up((size_t)p->qbatch * sizeof(unsigned), 256);
+        p->ws_bytes = p->flags_off + align_up((size_t)p->qbatch * sizeof(unsigned), 256);
+    }
     return true;
 }
 
 template <int B, int NT>
 static void launch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, const uint8_t *qluts,
-                           int nq, int cap, int R, char *ws, hipStream_t st)
+                           int nq, int cap, int R, char *ws, const unsigned *redo_flags, hipStream_t st)
 {
     dim3 grid(p.G, nq);
     launch(QADC_PROF_SCAN, (scan_u8_kernel<B, NT>), grid, dim3(NT), 0, st, codes, n, qluts, cap, R,
-                       p.seed_wgs > 0 ? 1 : 0, ws, p.stride, p.counts_off, p.lists_off);
+                       p.seed_wgs > 0 ? 1 : 0, ws, p.stride, p.counts_off, p.lists_off, redo_flags);
 }
 
 static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
@@ -668,14 +657,36 @@ static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
 template <int NT>
 static void dispatch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
                              const uint8_t *qluts, int nq, int cap, int R, char *ws,
-                             hipStream_t st)
+                             const unsigned *redo_flags, hipStream_t st)
 {
     switch (p.B) {
-    case 4: launch_scan_u8<4, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
-    case 8: launch_scan_u8<8, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
-    case 16: launch_scan_u8<16, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
-    default: launch_scan_u8<32, NT>(p, codes, n, qluts, nq, cap, R, ws, st); break;
+    case 4: launch_scan_u8<4, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
+    case 8: launch_scan_u8<8, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
+    case 16: launch_scan_u8<16, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
+    default: launch_scan_u8<32, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
     }
+}
+
+// Scan + merge of one batch whose control blocks are ready (seed/prepare kernel done or not needed).
+static int scan_and_merge_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, const uint8_t *qluts,
+                             int nb, int nbins, int R, char *ws, uint32_t *out_idx, uint8_t *out_dist,
+                             hipStream_t st)
+{
+    unsigned *flags = nullptr;
+    if (p.tiled && nb >= TILED_MIN_Q) {
+        unsigned *taus = reinterpret_cast<unsigned *>(ws + p.taus_off);
+        flags = reinterpret_cast<unsigned *>(ws + p.flags_off);
+        const int rc = run_tiled_scan(p.t, codes, n, nb, nbins, R, taus, ws, p.stride, p.countsA_off,
+                                      p.listsA_off, flags, st);
+        if (rc != QADC_OK) return rc;
+    }
+    if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);
+    else if (p.NT == 512) dispatch_scan_u8<512>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);
+    else dispatch_scan_u8<256>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);
+    launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws, p.stride,
+           p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n), R, (uint8_t)nbins, out_idx,
+           out_dist, p.countsA_off, p.listsA_off, flags ? p.t.GC : 0, (int)TILED_LCAP, flags);
+    return QADC_OK;
 }
 
 int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, int nq, int R,
@@ -698,12 +709,9 @@ int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, i
         const int nb = min(p.qbatch, nq - q0);
         const uint8_t *ql = qluts + (size_t)q0 * m * 16;
         if (p.seed_wgs > 0) dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
-        if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, ql, nb, nbins, R, ws, st);
-        else if (p.NT == 512) dispatch_scan_u8<512>(p, codes, n, ql, nb, nbins, R, ws, st);
-        else dispatch_scan_u8<256>(p, codes, n, ql, nb, nbins, R, ws, st);
-        launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
-                           p.stride, p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n),
-               R, (uint8_t)nbins, out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
+        const int rc = scan_and_merge_u8(p, codes, n, ql, nb, nbins, R, ws, out_idx + (size_t)q0 * R,
+                                         out_dist + (size_t)q0 * R, st);
+        if (rc != QADC_OK) return rc;
     }
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
@@ -780,12 +788,9 @@ int search_u8(const float *codebooks, int d, int m, const float *queries, int nq
             if (ql_out)
                 QADC_HIP_TRY(hipMemcpyAsync(ql_out, qluts, (size_t)nb * m * 16, hipMemcpyDeviceToDevice, st));
         }
-        if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, qluts, nb, nbins, R, ws, st);
-        else if (p.NT == 512) dispatch_scan_u8<512>(p, codes, n, qluts, nb, nbins, R, ws, st);
-        else dispatch_scan_u8<256>(p, codes, n, qluts, nb, nbins, R, ws, st);
-        launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
-               p.stride, p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n), R, (uint8_t)nbins,
-               out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R);
+        const int rc = scan_and_merge_u8(p, codes, n, qluts, nb, nbins, R, ws, out_idx + (size_t)q0 * R,
+                                         out_dist + (size_t)q0 * R, st);
+        if (rc != QADC_OK) return rc;
     }
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;

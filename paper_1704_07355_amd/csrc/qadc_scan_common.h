@@ -36,6 +36,42 @@ __device__ __forceinline__ unsigned byte_of(const uint4 &v, int k)
     return (w >> (8 * (k & 3))) & 0xffu;
 }
 
+// Keys with sum <= tau are exactly the keys below this limit.
+__device__ __forceinline__ unsigned limit_of_bin(unsigned tau)
+{
+    return tau >= 255u ? NO_KEY : ((tau + 1u) << 24);
+}
+
+// Called by one whole wave; h[b] is the count of bin NB*lane+b.  Returns, in every lane,
+// the smallest bin whose inclusive running count reaches `need`, or 64*NB when none does.
+template <int NB>
+__device__ __forceinline__ unsigned wave_threshold_bin(const unsigned (&h)[NB], unsigned need,
+                                                       unsigned *total = nullptr)
+{
+    const int l = lane_id();
+    unsigned tot = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) tot += h[b];
+    unsigned inc = tot;
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        const unsigned up = __shfl_up(inc, d);
+        if (l >= d) inc += up;
+    }
+    if (total) *total = __shfl(inc, WAVE - 1);
+    const unsigned long long m = __ballot(inc >= need);
+    if (m == 0) return (unsigned)(WAVE * NB);
+    const int first = __ffsll((long long)m) - 1;
+    unsigned run = inc - tot, bin = (unsigned)(NB * l + NB - 1);
+    bool found = false;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        run += h[b];
+        if (!found && run >= need) { bin = (unsigned)(NB * l + b); found = true; }
+    }
+    return __shfl(bin, first);
+}
+
 // Cuts keys[0..cnt) back to its `keep` smallest keys (cnt > keep) and returns the largest
 // key kept.  K = key type, NBYTES = key bytes that can be non-zero.  Called by every thread
 // of the workgroup; `ccnt` is an LDS counter of the workgroup.
@@ -152,11 +188,16 @@ constexpr int MERGE_WG_PER_THREAD = 8;
 // byte finds the bin of the R-th key; the keys up to that bin are ranked against each other
 // by counting, which selects and orders in one step.  Massive ties fall back to the full
 // radix select.
+// Two report regions may exist per query: region B (G workgroups, up to R keys each) written
+// by the single-query kernels, and region A (GA workgroups, up to pitchA keys each) written
+// by the query-tiled kernel.  flags[q] != 0 says that region A of query q is incomplete and
+// region B holds the result; without flags only region B exists.
 template <typename DistT, int KBYTES>
 __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off, int G,
     unsigned need, int R, DistT pad_dist, uint32_t *__restrict__ out_idx,
-    DistT *__restrict__ out_dist)
+    DistT *__restrict__ out_dist, size_t countsA_off, size_t listsA_off, int GA, int pitchA,
+    unsigned *__restrict__ flags)
 {
     // need = min(R, number of codes scanned): at least that many keys were reported.
     __shared__ uint64_t lkeys[MERGE_CAP];
@@ -169,13 +210,21 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
     unsigned *counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + counts_off);
     uint64_t *lists = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + lists_off);
+    int pitch = R;
+    const bool redone = flags && flags[q] != 0;  // uniform
+    if (flags && !redone) {                      // the tiled kernel's report is the result
+        counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + countsA_off);
+        lists = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + listsA_off);
+        G = GA;
+        pitch = pitchA;
+    }
     constexpr int TOP = (KBYTES - 1) * 8;
 
     // every reported key, spread over the threads by workgroup
     auto each_key = [&](auto f) {
         for (int g = tid; g < G; g += MERGE_NT) {
-            const unsigned c = min(counts[g], (unsigned)R);
-            for (unsigned i = 0; i < c; ++i) f(lists[(size_t)g * R + i]);
+            const unsigned c = min(counts[g], (unsigned)pitch);
+            for (unsigned i = 0; i < c; ++i) f(lists[(size_t)g * pitch + i]);
         }
     };
 
@@ -190,11 +239,11 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         const int g = tid + t * MERGE_NT;
         mycnt[t] = 0;
         if (g < G) {
-            const unsigned c = min(counts[g], (unsigned)R);
-            const uint64_t k0 = lists[(size_t)g * R];
+            const unsigned c = min(counts[g], (unsigned)pitch);
+            const uint64_t k0 = lists[(size_t)g * pitch];
             mycnt[t] = c;
             for (unsigned i = 0; i < c; ++i) {
-                const uint64_t k = i ? lists[(size_t)g * R + i] : k0;
+                const uint64_t k = i ? lists[(size_t)g * pitch + i] : k0;
                 const unsigned slot = atomicAdd(&lcnt, 1u);
                 if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
                 atomicAdd(&sc.hist[(unsigned)(k >> TOP) & 255u], 1u);
@@ -202,9 +251,9 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         }
     }
     for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {  // very wide grids
-        const unsigned c = min(counts[g], (unsigned)R);
+        const unsigned c = min(counts[g], (unsigned)pitch);
         for (unsigned i = 0; i < c; ++i) {
-            const uint64_t k = lists[(size_t)g * R + i];
+            const uint64_t k = lists[(size_t)g * pitch + i];
             const unsigned slot = atomicAdd(&lcnt, 1u);
             if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
             atomicAdd(&sc.hist[(unsigned)(k >> TOP) & 255u], 1u);
@@ -300,14 +349,24 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
         const int g = tid + t * MERGE_NT;
         if (g < G && mycnt[t]) {
-            for (unsigned i = 0; i < mycnt[t]; ++i) lists[(size_t)g * R + i] = 0;
+            for (unsigned i = 0; i < mycnt[t]; ++i) lists[(size_t)g * pitch + i] = 0;
             counts[g] = 0;
         }
     }
     for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {
-        const unsigned c = min(counts[g], (unsigned)R);
-        for (unsigned i = 0; i < c; ++i) lists[(size_t)g * R + i] = 0;
+        const unsigned c = min(counts[g], (unsigned)pitch);
+        for (unsigned i = 0; i < c; ++i) lists[(size_t)g * pitch + i] = 0;
         if (c) counts[g] = 0;
+    }
+    if (redone) {  // the abandoned report of the tiled kernel
+        unsigned *ca = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + countsA_off);
+        uint64_t *la = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + listsA_off);
+        for (int g = tid; g < GA; g += MERGE_NT) {
+            const unsigned c = min(ca[g], (unsigned)pitchA);
+            for (unsigned i = 0; i < c; ++i) la[(size_t)g * pitchA + i] = 0;
+            if (c) ca[g] = 0;
+        }
+        if (tid == 0) flags[q] = 0;
     }
     unsigned *z = reinterpret_cast<unsigned *>(hdr);
     for (int i = tid; i < (int)(sizeof(ScanHeader) / 4); i += MERGE_NT) z[i] = 0;

@@ -1,0 +1,29 @@
+// Interface of the query-tiled scan (qadc_scan_tiled.hip) towards the scan driver.
+#pragma once
+
+#include "qadc_common.h"
+
+namespace qadc {
+
+constexpr int TILED_Q = 8;             // queries per workgroup
+constexpr int TILED_NT = 256;          // threads per workgroup
+constexpr int TILED_LCAP = 64;         // keys a workgroup can report per query
+constexpr int TILED_MAX_CHUNKS = 1024; // database chunks per query
+constexpr int TILED_MIN_Q = 8;         // smallest batch worth tiling
+
+struct TiledPlan {
+    int B, GC;
+    int64_t chunk;
+    size_t lds_bytes;
+};
+
+bool make_tiled_plan(int64_t n, int m, int nq, TiledPlan *t);
+
+// tau kernel + tiled scan kernel for `nq` queries whose control blocks (histogram, pair
+// tables) were filled by the seed/prepare kernel.  Region A of query q: counts at
+// ws + q*ws_stride + countsA_off ([GC] u32), lists at + listsA_off ([GC][TILED_LCAP] u64).
+int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, int cap, int R,
+                   unsigned *taus, char *ws, size_t ws_stride, size_t countsA_off, size_t listsA_off,
+                   unsigned *flags, hipStream_t st);
+
+}  // namespace qadc

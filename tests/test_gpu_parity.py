@@ -472,3 +472,47 @@ def test_search_large_init_and_other_code_sizes(Q, O):
         for iq in range(3):
             wi, wd = oracle_topk(codes, h_ql[iq], 100)
             assert np.array_equal(idx_np(si)[iq], wi) and np.array_equal(sd[iq].cpu().numpy(), wd), (m, init)
+
+
+# ----------------------------------------------------- query-tiled scan
+
+@pytest.mark.parametrize("m", [8, 16, 32, 64])
+def test_scan_topk_query_batches_share_code_reads(Q, O, m):
+    """Batches of >= 8 queries on a long database go through the query-tiled kernel (8 queries per
+    workgroup); queries whose bound is useless (all sums tie) fall back to the single-query kernel."""
+    rng = np.random.default_rng(m)
+    n, R, nq = 500_009, 100, 21
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    codes[::5] = codes[3]  # duplicates: ties at distinct indices
+    qluts = rng.integers(0, 1 + 255 // m, size=(nq, m, 16)).astype(np.uint8)
+    qluts[4] = 0                                   # every sum ties: redo path
+    qluts[9] = rng.integers(0, 2, size=(m, 16))    # two-valued entries: heavy ties
+    qluts[13] = 255                                # everything saturates
+    qluts[17, :, :8] = 0                           # many zero sums
+    gi, gd = gpu_topk(Q, to_gpu(codes), qluts, R)
+    for iq in range(nq):
+        wi, wd = oracle_topk(codes, qluts[iq], R)
+        assert np.array_equal(gi[iq], wi), (m, iq)
+        assert np.array_equal(gd[iq], wd), (m, iq)
+
+
+def test_search_batch_config1_shaped(Q, O):
+    """qadc_search on a batch of 16 mixture queries over a long database (fused prepare kernel +
+    query-tiled scan) against the oracle's replay of the integer part and its own tables."""
+    import torch
+    c = config1()
+    n = 800_000
+    reps = -(-n // len(c["codes"]))
+    rng = np.random.default_rng(3)
+    codes = np.tile(c["codes"], (reps, 1))[:n].copy()
+    codes[100_000:] ^= rng.integers(0, 256, size=codes[100_000:].shape, dtype=np.uint8) & 0x33
+    ql_out = torch.empty((16, 16, 16), dtype=torch.uint8, device="cuda:0")
+    si, sd = Q.qadc_search(to_gpu(c["codebooks"]), to_gpu(c["queries"]), to_gpu(codes), 100, 200,
+                           qluts_out=ql_out)
+    torch.cuda.synchronize()
+    h_ql = ql_out.cpu().numpy()
+    for iq in range(16):
+        t = O.quick_adc_tables(c["codebooks"], c["queries"][iq], codes, 200, 100)
+        assert np.abs(h_ql[iq].astype(int) - t["qlut"].astype(int)).max() <= 1
+        wi, wd = oracle_topk(codes, h_ql[iq], 100)
+        assert np.array_equal(idx_np(si)[iq], wi) and np.array_equal(sd[iq].cpu().numpy(), wd)
