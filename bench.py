@@ -38,20 +38,30 @@ HBM_PEAK_GBPS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--n", type=int, default=10_000_000, help="codes per query scan")
+    ap.add_argument("--workload", choices=["scan", "batched"], default="scan",
+                    help="scan: config 2, one query at a time (default); batched: config 3, query batches "
+                         "over 128-bit codes")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--n", type=int, default=None, help="codes per query scan")
+    ap.add_argument("--batch", type=int, default=256, help="queries per step of the batched workload")
     ap.add_argument("--buffers", type=int, default=8, help="distinct code buffers rotated over")
-    ap.add_argument("--m", type=int, default=16)
+    ap.add_argument("--m", type=int, default=None)
     ap.add_argument("--R", type=int, default=100)
-    ap.add_argument("--init", type=int, default=200)
+    ap.add_argument("--init", type=int, default=None)
     ap.add_argument("--queries", type=int, default=1000)
     ap.add_argument("--cpu-queries", type=int, default=256, help="queries of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--recall-queries", type=int, default=100, help="queries of the accuracy sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timing pass")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
-    return ap.parse_args()
+    args = ap.parse_args()
+    dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200),
+            "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000)}[args.workload]
+    for k, v in dflt.items():
+        if getattr(args, k) is None:
+            setattr(args, k, v)
+    return args
 
 
 def build_database(Q, torch, spec, m, n_total, n_keep, dev):
@@ -107,12 +117,103 @@ def accuracy(Q, torch, np, cb, codes, raw, queries, R, init):
             "nn_recall_at_R_quick_adc": round(rec_q, 4), "nn_recall_at_R_float_adc": round(rec_f, 4)}
 
 
+ALU_PEAK_TLOOKUPS = 157.3  # 256 CUs x 64 lanes x 2.4 GHz x 4 byte lanes per 32-bit lane-op
+
+
+def run_batched(args):
+    """Config 3: batches of queries over 128-bit codes; a step = one batch through qadc_search."""
+    import numpy as np
+    import torch
+    import paper_1704_07355_amd as Q
+    from workloads import MixtureSpec, SEED_QUERY
+    from workloads.mixture_torch import mixture_vectors_torch
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    spec = MixtureSpec(d=128)
+    m, n, R, init, nb = args.m, args.n, args.R, args.init, args.batch
+    t0 = time.time()
+    cb, codes, _ = build_database(Q, torch, spec, m, n, 0, dev)
+    nq_total = nb * (args.steps + args.warmup)
+    queries = mixture_vectors_torch(spec, SEED_QUERY, 0, nq_total, dev)
+    t_build = time.time() - t0
+    ws = Q.qadc_workspace_init(torch.empty(Q.qadc_workspace_bytes(Q.QADC_WS_SEARCH, n, m, nb, R),
+                                           dtype=torch.uint8, device=dev))
+    out_idx = torch.empty((nb, R), dtype=torch.int32, device=dev)
+    out_dist = torch.empty((nb, R), dtype=torch.uint8, device=dev)
+    ql_out = torch.empty((nb, m, 16), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        Q.qadc_search(cb, queries[i * nb:(i + 1) * nb], codes, R, init, workspace=ws, out_idx=out_idx,
+                      out_dist=out_dist, qluts_out=ql_out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    pairs = n * nb / (ms_per_step * 1e-3)
+
+    roofline = kernels = None
+    if not args.no_profile:
+        Q.qadc_profile_enable(True)
+        step(args.warmup + args.steps - 1)
+        torch.cuda.synchronize()
+        ms_scan, launches = Q.qadc_profile_read(Q.QADC_PROF_SCAN)
+        ms_prep = sum(Q.qadc_profile_read(w)[0] for w in (Q.QADC_PROF_PREPARE, Q.QADC_PROF_TABLES,
+                                                          Q.QADC_PROF_QUANTIZE))
+        ms_seed, _ = Q.qadc_profile_read(Q.QADC_PROF_SEED)
+        ms_merge, _ = Q.qadc_profile_read(Q.QADC_PROF_MERGE)
+        Q.qadc_profile_enable(False)
+        ach = n * nb * m / (ms_scan * 1e-3) / 1e12
+        roofline = {"bound": "alu", "kernel": "scan_u8_tiled_kernel (+ redo launch)", "achieved": round(ach, 2),
+                    "peak": ALU_PEAK_TLOOKUPS, "unit": "T lookup-adds/s", "frac": round(ach / ALU_PEAK_TLOOKUPS, 4),
+                    "traffic": None, "scan_ms": round(ms_scan, 3), "launches_timed": launches}
+        kernels = {"scan_ms": round(ms_scan, 3), "tables_quantize_ms": round(ms_prep, 3),
+                   "seed_tau_ms": round(ms_seed, 3), "merge_ms": round(ms_merge, 3)}
+
+    cpu = None
+    if args.cpu_queries > 0:
+        from oracle import cref
+        nqc = min(8, nb)
+        h_codes = codes.cpu().numpy()
+        h_ql = ql_out[:nqc].cpu().numpy()
+        gi, gd = out_idx[:nqc].cpu().numpy().view(np.uint32), out_dist[:nqc].cpu().numpy()
+        t0 = time.time()
+        ci, cd = cref.scan_topk_u8(h_codes, h_ql, R)
+        dt = time.time() - t0
+        cpu = {"value": round(nqc * n / dt / 1e9, 4), "unit": "G pairs/s", "cores": cref.num_threads(),
+               "kind": "oracle", "sample": "%d queries of the last batch x %d codes, one query per thread"
+               % (nqc, n), "seconds": round(dt, 2),
+               "gpu_matches_oracle": bool(np.array_equal(gi, ci) and np.array_equal(gd, cd))}
+
+    print(json.dumps({
+        "metric": "G (code, query) pairs scanned/s (query-batched 4-bit Quick ADC scan, whole path per batch)",
+        "value": round(pairs / 1e9, 1), "unit": "Gpairs/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "config 3: d=128 mixture, PQ m=%d x 4-bit, N=%d codes, batches of %d queries "
+                   "through qadc_search (8 queries share each code read in a workgroup), R=%d, init=%d"
+                   % (m, n, nb, R, init), "n": n, "m": m, "R": R, "init": init, "batch": nb},
+        "gcodes_per_s_per_query": round(pairs / nb / 1e9, 2),
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
               "(no collectives, no sharding in this library)" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    if args.workload == "batched":
+        import paper_1704_07355_amd as Q
+        Q.lib()
+        return run_batched(args)
 
     import numpy as np
     import torch

@@ -764,7 +764,8 @@ int search_u8(const float *codebooks, int d, int m, const float *queries, int nq
         const int nb = min(p.qbatch, nq - q0);
         const float *yq = queries + (size_t)q0 * d;
         uint8_t *ql_out = qluts_out ? qluts_out + (size_t)q0 * m * 16 : nullptr;
-        if (p.seed_wgs > 0) {
+        if (p.seed_wgs > 0 && nb < TILED_MIN_Q) {
+            // few queries: one launch; every sampling workgroup recomputes the tables it needs
             dim3 grid(p.seed_wgs, nb);
 #define QADC_PREP_CASE(B_)                                                                            \
     case B_:                                                                                         \
@@ -779,7 +780,9 @@ int search_u8(const float *codebooks, int d, int m, const float *queries, int nq
                 QADC_PREP_CASE(32)
             }
 #undef QADC_PREP_CASE
-        } else {  // small database: separate tables and quantizer kernels, the scan seeds itself
+        } else {
+            // a batch, or a small database: tables and quantizer once per query by their own
+            // kernels, then the sampling kernel (large databases) or a self-seeding scan
             int rc = build_luts(codebooks, d, m, 16, yq, nullptr, nb, luts, st);
             if (rc != QADC_OK) return rc;
             rc = quantize_luts(luts, nb, 1, m, codes, n_init, nullptr, R, nbins, qmin_mode, qluts, nullptr,
@@ -787,6 +790,7 @@ int search_u8(const float *codebooks, int d, int m, const float *queries, int nq
             if (rc != QADC_OK) return rc;
             if (ql_out)
                 QADC_HIP_TRY(hipMemcpyAsync(ql_out, qluts, (size_t)nb * m * 16, hipMemcpyDeviceToDevice, st));
+            if (p.seed_wgs > 0) dispatch_seed_u8(p, codes, n, qluts, nb, nbins, R, ws, st);
         }
         const int rc = scan_and_merge_u8(p, codes, n, qluts, nb, nbins, R, ws, out_idx + (size_t)q0 * R,
                                          out_dist + (size_t)q0 * R, st);

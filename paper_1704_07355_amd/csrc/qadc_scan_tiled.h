@@ -6,7 +6,7 @@
 namespace qadc {
 
 constexpr int TILED_Q = 8;             // queries per workgroup
-constexpr int TILED_NT = 256;          // threads per workgroup
+constexpr int TILED_NT = 512;          // threads per workgroup
 constexpr int TILED_LCAP = 64;         // keys a workgroup can report per query
 constexpr int TILED_MAX_CHUNKS = 1024; // database chunks per query
 constexpr int TILED_MIN_Q = 8;         // smallest batch worth tiling
