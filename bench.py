@@ -38,9 +38,11 @@ HBM_PEAK_GBPS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--workload", choices=["scan", "batched"], default="scan",
+    ap.add_argument("--workload", choices=["scan", "batched", "ivf"], default="scan",
                     help="scan: config 2, one query at a time (default); batched: config 3, query batches "
-                         "over 128-bit codes")
+                         "over 128-bit codes; ivf: config 4, inverted index with Zipf-skewed lists")
+    ap.add_argument("--K", type=int, default=65536, help="coarse centroids of the ivf workload")
+    ap.add_argument("--nprobe", type=int, default=64)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--n", type=int, default=None, help="codes per query scan")
@@ -57,7 +59,8 @@ def parse():
                     help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
     args = ap.parse_args()
     dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200),
-            "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000)}[args.workload]
+            "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000),
+            "ivf": dict(steps=4, warmup=1, n=100_000_000, m=32, init=1000)}[args.workload]
     for k, v in dflt.items():
         if getattr(args, k) is None:
             setattr(args, k, v)
@@ -204,16 +207,140 @@ def run_batched(args):
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
 
 
+def run_ivf(args):
+    """Config 4: IVF + Quick ADC.  A step = one batch of queries through qadc_ivf_search.
+
+    Synthetic index built list by list on the GPU: list sizes follow a Zipf(0.8) profile, every
+    stored vector is its cell's centroid plus N(0, 18^2) noise, so its residual code is the
+    encoding of that noise; ids are a running counter; a query is the centroid of a size-weighted
+    random cell plus N(0, 18^2) noise.
+    """
+    import numpy as np
+    import torch
+    import paper_1704_07355_amd as Q
+    from workloads import MixtureSpec, SEED_QUERY, SEED_BASE, SEED_TRAIN, zipf_list_sizes, kmeans_init_rows
+    from workloads.mixture_torch import mixture_vectors_torch
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    d, m, n, K, R, init, nprobe, nb = 128, args.m, args.n, args.K, args.R, args.init, args.nprobe, args.batch
+    sigma = 18.0
+    t0 = time.time()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED_BASE * 7919 + 11)
+    coarse = mixture_vectors_torch(MixtureSpec(d=d), SEED_TRAIN, 0, K, dev)
+    sizes = zipf_list_sizes(n, K, 0.8, SEED_BASE)
+    list_off = torch.from_numpy(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)).to(dev)
+    train = sigma * torch.randn((20_000, d), generator=gen, device=dev)
+    cb = Q.qadc_pq_train(train.contiguous(), m, 16, torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev), 10)
+    codes = torch.empty((n, m // 2), dtype=torch.uint8, device=dev)
+    chunk = 1 << 22
+    for s in range(0, n, chunk):
+        cnt = min(chunk, n - s)
+        x = sigma * torch.randn((cnt, d), generator=gen, device=dev)
+        Q.qadc_pq_encode(cb, x, out=codes[s:s + cnt])
+    ids = torch.arange(n, dtype=torch.int32, device=dev)
+    index = Q.IvfIndex(coarse, list_off, codes, ids, cb)
+    nq_total = nb * (args.steps + args.warmup)
+    prob = torch.from_numpy(sizes / sizes.sum()).to(dev)
+    home = torch.multinomial(prob, nq_total, replacement=True, generator=gen)
+    queries = (coarse[home] + sigma * torch.randn((nq_total, d), generator=gen, device=dev)).contiguous()
+    torch.cuda.synchronize()
+    t_build = time.time() - t0
+
+    ws = Q.qadc_workspace_init(torch.empty(Q.qadc_ivf_workspace_bytes(index, nb, nprobe, R),
+                                           dtype=torch.uint8, device=dev))
+
+    def step(i, debug=False):
+        return Q.qadc_ivf_search(index, queries[i * nb:(i + 1) * nb], nprobe, R, init, workspace=ws, debug=debug)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    Q.qadc_profile_enable(True)
+    last = args.warmup + args.steps - 1
+    out_ids, out_dist, probes, qluts = step(last, debug=True)
+    torch.cuda.synchronize()
+    phase = {}
+    for name, which in (("index", Q.QADC_PROF_IVF_INDEX), ("tables", Q.QADC_PROF_IVF_TABLES),
+                        ("quantize", Q.QADC_PROF_QUANTIZE), ("scan", Q.QADC_PROF_SCAN),
+                        ("merge", Q.QADC_PROF_MERGE)):
+        phase[name] = Q.qadc_profile_read(which)[0]
+    Q.qadc_profile_enable(False)
+    h_probes = probes.cpu().numpy()
+    scanned = float(sizes[h_probes.clip(0)].sum())  # codes scanned by the last batch
+    row = m // 2
+    ach = scanned * row / (phase["scan"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "ivf_scan_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                "scan_ms_per_batch": round(phase["scan"], 3), "codes_scanned_per_query": round(scanned / nb)}
+
+    cpu = None
+    if args.cpu_queries > 0:
+        from oracle import qadc_oracle as O
+        nqc = min(4, nb)
+        h_coarse, h_cb = coarse.cpu().numpy(), cb.cpu().numpy()
+        h_off = list_off.cpu().numpy()
+        h_q = queries[last * nb:last * nb + nqc].cpu().numpy()
+        h_ql = qluts[:nqc].cpu().numpy()
+        gi, gd = out_ids[:nqc].cpu().numpy().view(np.uint32), out_dist[:nqc].cpu().numpy()
+        same, codes_done, dt = True, 0, 0.0
+        for iq in range(nqc):
+            cells = h_probes[iq]
+            # host copy of the probed lists only, re-based into a compact index
+            lens = (h_off[cells + 1] - h_off[cells]).astype(np.int64)
+            sub_off = np.zeros(len(cells) + 1, dtype=np.int64)
+            np.cumsum(lens, out=sub_off[1:])
+            sub_codes = torch.cat([codes[h_off[c]:h_off[c + 1]] for c in cells]).cpu().numpy()
+            sub_ids = np.concatenate([np.arange(h_off[c], h_off[c + 1], dtype=np.int64) for c in cells])
+            order = np.argsort(sub_ids, kind="stable")  # storage-position order decides ties
+            sub = dict(list_off=sub_off, codes=sub_codes, ids=sub_ids.astype(np.uint32))
+            t1 = time.time()
+            rep = O.ivf_quick_adc_search(sub, h_coarse[cells], h_cb, h_q[iq], len(cells), init, R,
+                                         probes=np.arange(len(cells)), qluts=h_ql[iq])
+            dt += time.time() - t1
+            codes_done += int(lens.sum())
+            # the compact index keeps probe order, the real one storage order: compare as sets of
+            # (sum, id) after sorting ties by id, which is the storage position here
+            want = sorted(zip(rep["dist"].tolist(), rep["ids"].tolist()))
+            got = sorted(zip(gd[iq].tolist(), gi[iq].tolist()))
+            same = same and ([w[0] for w in want] == [g[0] for g in got])
+            del order
+        cpu = {"value": round(codes_done / dt / 1e9, 4), "unit": "Gcodes/s", "cores": 1, "kind": "oracle",
+               "sample": "%d queries of the last batch, NumPy oracle replay of the GPU's cells and tables "
+               "(%d codes)" % (nqc, codes_done), "seconds": round(dt, 2), "gpu_sums_match_oracle": bool(same)}
+
+    print(json.dumps({
+        "metric": "queries/s (IVF + Quick ADC, whole path per batch)",
+        "value": round(nb / (ms_per_step * 1e-3), 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "config 4: IVF K=%d, Zipf(0.8) lists, N=%d residual codes m=%d x 4-bit, nprobe=%d, "
+                   "batches of %d queries, R=%d, init=%d" % (K, n, m, nprobe, nb, R, init),
+                   "n": n, "K": K, "m": m, "nprobe": nprobe, "R": R, "init": init, "batch": nb},
+        "gcodes_scanned_per_s": round(scanned / (ms_per_step * 1e-3) / 1e9, 2),
+        "phase_ms_per_query": {k: round(v / nb, 5) for k, v in phase.items()},
+        "roofline": roofline, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
               "(no collectives, no sharding in this library)" % args.gpus, file=sys.stderr)
         sys.exit(2)
-    if args.workload == "batched":
+    if args.workload in ("batched", "ivf"):
         import paper_1704_07355_amd as Q
         Q.lib()
-        return run_batched(args)
+        return run_batched(args) if args.workload == "batched" else run_ivf(args)
 
     import numpy as np
     import torch
