@@ -224,7 +224,15 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     auto each_key = [&](auto f) {
         for (int g = tid; g < G; g += MERGE_NT) {
             const unsigned c = min(counts[g], (unsigned)pitch);
-            for (unsigned i = 0; i < c; ++i) f(lists[(size_t)g * pitch + i]);
+            const uint64_t *l = lists + (size_t)g * pitch;
+            for (unsigned i = 0; i < c; i += 8) {  // eight loads in flight before the first use
+                uint64_t k[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) k[u] = (i + u < c) ? l[i + u] : 0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (i + u < c) f(k[u]);
+            }
         }
     };
 

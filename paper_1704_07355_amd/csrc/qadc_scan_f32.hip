@@ -14,18 +14,207 @@
 namespace qadc {
 
 constexpr int F32_NT = 512;
+constexpr int F32_RANGE_CODES = 1024;  // codes looked at to place the bins of the bound
 
 struct F32Shared {
     SelectScratch sel;
     unsigned ccnt;
     unsigned tcnt[3];
+    unsigned tau;
+    unsigned fcnt;
 };
 
-// KSUB = 16: ROW = m/2 bytes per code, two components per byte; KSUB = 256: ROW = m bytes.
+// Bins for the grid-wide bound: a monotone map of the float distance onto 0..255, uniform
+// between `lo` (the smallest sum the tables allow) and the R-th smallest distance of the
+// first codes -- the range Section 3.3 of the paper gives the quantized tables.  Monotone,
+// so "bin <= tau" never drops a code that beats one it keeps; the exact order is decided on
+// the float keys afterwards.
+struct F32Range {
+    float lo, scale;
+};
+
+__device__ __forceinline__ unsigned f32_bin(float d, F32Range r)
+{
+    const float t = fmaxf(0.0f, d - r.lo) * r.scale;
+    return (unsigned)fminf(t, 255.0f);
+}
+
+// Float tables of one query -> LDS.
+template <int KSUB, int ROW, int NT>
+__device__ __forceinline__ void load_float_tables(const float *__restrict__ lq, float *lut)
+{
+    constexpr int M = (KSUB == 16) ? 2 * ROW : ROW;
+    for (int e = threadIdx.x; e < M * KSUB; e += NT) lut[e] = lq[e];
+}
+
+// Eq. (2) for the codes of one thread's tile slot: float32 sums in increasing j.
+template <int KSUB, int ROW, int NT>
+__device__ __forceinline__ void tile_dists(const uint4 (&w)[2], const float *lut,
+                                           float (&d)[ScanCfg<ROW, NT>::CPT])
+{
+    if constexpr (ROW <= 16) {
+        constexpr int CPV = 16 / ROW;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+#pragma unroll
+            for (int c = 0; c < CPV; ++c) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int jb = 0; jb < ROW; ++jb) {
+                    const unsigned b = byte_of(w[v], c * ROW + jb);
+                    if constexpr (KSUB == 16) {
+                        acc = acc + lut[(2 * jb) * 16 + (b & 15u)];
+                        acc = acc + lut[(2 * jb + 1) * 16 + (b >> 4)];
+                    } else {
+                        acc = acc + lut[jb * 256 + b];
+                    }
+                }
+                d[v * CPV + c] = acc;
+            }
+        }
+    } else {
+        float acc = 0.0f;
+#pragma unroll
+        for (int jb = 0; jb < 32; ++jb) {
+            const unsigned b = byte_of(w[jb >> 4], jb & 15);
+            if constexpr (KSUB == 16) {
+                acc = acc + lut[(2 * jb) * 16 + (b & 15u)];
+                acc = acc + lut[(2 * jb + 1) * 16 + (b >> 4)];
+            } else {
+                acc = acc + lut[jb * 256 + b];
+            }
+        }
+        d[0] = acc;
+    }
+}
+
+template <int ROW, int NT>
+__device__ __forceinline__ bool slot_valid(const int (&nc)[2], int slot)
+{
+    if constexpr (ROW <= 16) return (slot % (16 / ROW)) < nc[slot / (16 / ROW)];
+    else return nc[0] != 0;
+}
+
+template <int ROW, int NT>
+__device__ __forceinline__ unsigned slot_index(int slot)
+{
+    if constexpr (ROW <= 16) {
+        constexpr int CPV = 16 / ROW;
+        return (unsigned)(((slot / CPV) * NT + threadIdx.x) * CPV + slot % CPV);
+    } else {
+        return threadIdx.x;
+    }
+}
+
+// Range kernel: one workgroup per query; lo = sum_j min_i D^j[i] (float32, increasing j),
+// hi = the min(R, n0)-th smallest distance of the first n0 codes; scale = 255 / (hi - lo).
+template <int KSUB, int ROW>
+__global__ __launch_bounds__(F32_NT) void f32_range_kernel(
+    const uint8_t *__restrict__ codes, int n0, const float *__restrict__ luts, int R,
+    F32Range *__restrict__ ranges)
+{
+    constexpr int NT = F32_NT;
+    constexpr int M = (KSUB == 16) ? 2 * ROW : ROW;
+    __shared__ float lut[M * KSUB];
+    __shared__ unsigned cand[F32_RANGE_CODES];
+    __shared__ float tmin[M];
+    __shared__ SelectScratch sc;
+    const int tid = threadIdx.x;
+    const int q = blockIdx.x;
+    load_float_tables<KSUB, ROW, NT>(luts + (size_t)q * M * KSUB, lut);
+    __syncthreads();
+    if (tid < M) {
+        float b = lut[tid * KSUB];
+        for (int i = 1; i < KSUB; ++i) b = fminf(b, lut[tid * KSUB + i]);
+        tmin[tid] = b;
+    }
+    for (int i = tid; i < n0; i += NT) {
+        const uint8_t *c = codes + (size_t)i * ROW;
+        float acc = 0.0f;
+        for (int jb = 0; jb < ROW; ++jb) {
+            const unsigned b = c[jb];
+            if constexpr (KSUB == 16) {
+                acc = acc + lut[(2 * jb) * 16 + (b & 15u)];
+                acc = acc + lut[(2 * jb + 1) * 16 + (b >> 4)];
+            } else {
+                acc = acc + lut[jb * 256 + b];
+            }
+        }
+        cand[i] = f2ord(acc);
+    }
+    __syncthreads();
+    const unsigned kth = block_radix_select<unsigned, 4>(cand, (unsigned)n0, (unsigned)min(R, n0), &sc);
+    if (tid == 0) {
+        float lo = 0.0f;
+        for (int j = 0; j < M; ++j) lo = lo + tmin[j];
+        const float hi = ord2f(kth);
+        F32Range r;
+        r.lo = lo;
+        r.scale = (hi > lo) ? 255.0f / (hi - lo) : 0.0f;
+        ranges[q] = r;
+    }
+}
+
+// Seed kernel of the float scan: a sample of tiles is binned and the lowest bins of each
+// workgroup are added to the query's grid-wide histogram, exactly as in the quantized scan.
+template <int KSUB, int ROW>
+__global__ __launch_bounds__(F32_NT) void seed_f32_kernel(
+    const uint8_t *__restrict__ codes, int64_t n, const float *__restrict__ luts,
+    const F32Range *__restrict__ ranges, int R, unsigned flush_need, int64_t seed_stride,
+    char *__restrict__ ws, size_t ws_stride)
+{
+    constexpr int NT = F32_NT;
+    using C = ScanCfg<ROW, NT>;
+    constexpr int M = (KSUB == 16) ? 2 * ROW : ROW;
+    __shared__ float lut[M * KSUB];
+    __shared__ unsigned hist[256];
+    const int tid = threadIdx.x;
+    const int q = blockIdx.y;
+    const int g = blockIdx.x;
+    const int64_t c0 = (int64_t)g * seed_stride;
+    const int64_t c1 = min(n, c0 + C::TILE);
+    if (c0 >= c1) return;
+    uint4 w[2];
+    int nc[2];
+    tile_load<ROW, NT>(codes, c0, c1, w, nc);
+    load_float_tables<KSUB, ROW, NT>(luts + (size_t)q * M * KSUB, lut);
+    for (int e = tid; e < 256; e += NT) hist[e] = 0;
+    const F32Range r = ranges[q];
+    __syncthreads();
+    float d[C::CPT];
+    tile_dists<KSUB, ROW, NT>(w, lut, d);
+#pragma unroll
+    for (int c = 0; c < C::CPT; ++c) {
+        const unsigned bin = f32_bin(d[c], r);
+        if (slot_valid<ROW, NT>(nc, c) && bin < 255u) atomicAdd(&hist[bin], 1u);
+    }
+    __syncthreads();
+    if (tid < WAVE) {
+        unsigned h[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) h[b] = hist[4 * tid + b];
+        const unsigned f = min(wave_threshold_bin<4>(h, (unsigned)R), wave_threshold_bin<4>(h, flush_need));
+        ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+        unsigned *ghist = hdr->ghist[g % GH_REP];
+        for (unsigned b0 = 0; b0 <= f && b0 < 256u; b0 += WAVE) {  // uniform
+            const unsigned bin = b0 + tid;
+            const unsigned c = hist[bin];
+            if (bin <= f && bin < 255u && c)
+                __hip_atomic_fetch_add(&ghist[bin], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Scan kernel.  KSUB = 16: ROW = m/2 bytes per code, two components per byte; KSUB = 256:
+// ROW = m bytes.  Workgroup g takes tiles g, g+G, ...  With a grid-wide bound the pass is
+// barrier-free (keys whose bin is at or below the bound are appended to the LDS list); on
+// overflow, or without a bound, the careful pass runs: one barrier per tile, the list cut
+// back to its R smallest keys by an exact radix select whenever it fills.
 template <int KSUB, int ROW>
 __global__ __launch_bounds__(F32_NT) void scan_f32_kernel(
-    const uint8_t *__restrict__ codes, int64_t n, const float *__restrict__ luts, int R,
-    char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off)
+    const uint8_t *__restrict__ codes, int64_t n, const float *__restrict__ luts,
+    const F32Range *__restrict__ ranges, int has_seed, int R, char *__restrict__ ws,
+    size_t ws_stride, size_t counts_off, size_t lists_off)
 {
     constexpr int NT = F32_NT;
     using C = ScanCfg<ROW, NT>;
@@ -39,75 +228,87 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_kernel(
     const int g = blockIdx.x;
     const int64_t G = gridDim.x;
     if ((int64_t)g * C::TILE >= n) return;  // uniform
+    const ScanHeader *hdr = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride);
 
-    const float *lq = luts + (size_t)q * M * KSUB;
-    for (int e = tid; e < M * KSUB; e += NT) lut[e] = lq[e];
-    if (tid == 0) sh.tcnt[0] = 0;
+    if (tid < WAVE) {
+        unsigned t = 256, carry = 0;
+        for (unsigned b0 = 0; b0 < 256 && has_seed; b0 += 128) {  // uniform
+            const unsigned bin = b0 + 2u * tid;
+            unsigned h[2] = {0, 0};
+#pragma unroll
+            for (int r = 0; r < GH_REP; ++r) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(&hdr->ghist[r][bin]);
+                h[0] += v.x;
+                h[1] += v.y;
+            }
+            unsigned tot;
+            const unsigned hit = wave_threshold_bin<2>(h, (unsigned)R - carry, &tot);
+            if (hit < 128u) { t = b0 + hit; break; }
+            carry += tot;
+        }
+        if (tid == 0) { sh.tau = t; sh.fcnt = 0; sh.tcnt[0] = 0; }
+    }
+    load_float_tables<KSUB, ROW, NT>(luts + (size_t)q * M * KSUB, lut);
     __syncthreads();
 
-    uint64_t lim = ~0ull;  // keys >= lim cannot be among the R best of this workgroup's codes
+    const bool seeded = sh.tau < 255u;  // uniform (bin 255 is never counted)
     unsigned have = 0;
-    int rot = 0;
-    unsigned rel = 0;
-    for (int64_t t0 = (int64_t)g * C::TILE; t0 < n; t0 += G * C::TILE, rel += C::TILE) {
-        unsigned *ctr = &sh.tcnt[rot];
-        const int nxt = (rot == 2) ? 0 : rot + 1;
-        if (tid == 0) sh.tcnt[nxt] = 0;
-        uint4 w[2];
-        int nc[2];
-        tile_load<ROW, NT>(codes, t0, n, w, nc);
-
-        uint64_t k[C::CPT];
-        if constexpr (ROW <= 16) {
-            constexpr int CPV = 16 / ROW;
+    bool careful = !seeded;
+    if (seeded) {
+        const unsigned tau = sh.tau;
+        const F32Range r = ranges[q];
+        unsigned rel = 0;
+        for (int64_t t0 = (int64_t)g * C::TILE; t0 < n; t0 += G * C::TILE, rel += C::TILE) {
+            uint4 w[2];
+            int nc[2];
+            tile_load<ROW, NT>(codes, t0, n, w, nc);
+            float d[C::CPT];
+            tile_dists<KSUB, ROW, NT>(w, lut, d);
 #pragma unroll
-            for (int v = 0; v < 2; ++v) {
-#pragma unroll
-                for (int c = 0; c < CPV; ++c) {
-                    float acc = 0.0f;
-#pragma unroll
-                    for (int jb = 0; jb < ROW; ++jb) {
-                        const unsigned b = byte_of(w[v], c * ROW + jb);
-                        if constexpr (KSUB == 16) {
-                            acc = acc + lut[(2 * jb) * 16 + (b & 15u)];
-                            acc = acc + lut[(2 * jb + 1) * 16 + (b >> 4)];
-                        } else {
-                            acc = acc + lut[jb * 256 + b];
-                        }
-                    }
-                    const unsigned li = rel + (unsigned)((v * NT + tid) * CPV + c);
-                    k[v * CPV + c] = (c < nc[v]) ? (((uint64_t)f2ord(acc) << 32) | li) : ~0ull;
-                }
+            for (int c = 0; c < C::CPT; ++c) {
+                const bool pass = slot_valid<ROW, NT>(nc, c) && f32_bin(d[c], r) <= tau;
+                const unsigned slot = wave_append_slot(pass, &sh.fcnt);
+                if (pass && slot < (unsigned)C::CAP)
+                    keys[slot] = ((uint64_t)f2ord(d[c]) << 32) | (rel + slot_index<ROW, NT>(c));
             }
-        } else {
-            float acc = 0.0f;
-#pragma unroll
-            for (int jb = 0; jb < 32; ++jb) {
-                const unsigned b = byte_of(w[jb >> 4], jb & 15);
-                if constexpr (KSUB == 16) {
-                    acc = acc + lut[(2 * jb) * 16 + (b & 15u)];
-                    acc = acc + lut[(2 * jb + 1) * 16 + (b >> 4)];
-                } else {
-                    acc = acc + lut[jb * 256 + b];
-                }
-            }
-            k[0] = nc[0] ? (((uint64_t)f2ord(acc) << 32) | (rel + (unsigned)tid)) : ~0ull;
-        }
-
-#pragma unroll
-        for (int c = 0; c < C::CPT; ++c) {
-            const bool pass = k[c] < lim;
-            const unsigned slot = have + wave_append_slot(pass, ctr);
-            if (pass) keys[slot] = k[c];
         }
         __syncthreads();
-        have += *ctr;
-        rot = nxt;
-        if (have > (unsigned)SCAN_SLACK) {
-            const uint64_t kth = compact_candidates<uint64_t, 8, NT, C::CAP>(keys, have, (unsigned)R,
-                                                                              &sh.sel, &sh.ccnt);
-            lim = min(lim, kth + 1ull);
-            have = (unsigned)R;
+        have = sh.fcnt;
+        careful = have > (unsigned)C::CAP;  // keys were dropped: start over, carefully
+    }
+
+    if (careful) {
+        uint64_t lim = ~0ull;  // keys >= lim cannot be among the R best of this workgroup's codes
+        have = 0;
+        int rot = 0;
+        unsigned rel = 0;
+        for (int64_t t0 = (int64_t)g * C::TILE; t0 < n; t0 += G * C::TILE, rel += C::TILE) {
+            unsigned *ctr = &sh.tcnt[rot];
+            const int nxt = (rot == 2) ? 0 : rot + 1;
+            if (tid == 0) sh.tcnt[nxt] = 0;
+            uint4 w[2];
+            int nc[2];
+            tile_load<ROW, NT>(codes, t0, n, w, nc);
+            float d[C::CPT];
+            tile_dists<KSUB, ROW, NT>(w, lut, d);
+#pragma unroll
+            for (int c = 0; c < C::CPT; ++c) {
+                const uint64_t key = slot_valid<ROW, NT>(nc, c)
+                                         ? (((uint64_t)f2ord(d[c]) << 32) | (rel + slot_index<ROW, NT>(c)))
+                                         : ~0ull;
+                const bool pass = key < lim;
+                const unsigned slot = have + wave_append_slot(pass, ctr);
+                if (pass) keys[slot] = key;
+            }
+            __syncthreads();
+            have += *ctr;
+            rot = nxt;
+            if (have > (unsigned)SCAN_SLACK) {
+                const uint64_t kth = compact_candidates<uint64_t, 8, NT, C::CAP>(keys, have, (unsigned)R,
+                                                                                  &sh.sel, &sh.ccnt);
+                lim = min(lim, kth + 1ull);
+                have = (unsigned)R;
+            }
         }
     }
 
@@ -129,8 +330,11 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_kernel(
 
 struct F32Plan {
     int ROW, KSUB, G, qbatch;
+    int seed_wgs;
+    int64_t seed_stride;
+    unsigned flush_need;
     ScanLayout l;
-    size_t ws_bytes;
+    size_t ranges_off, ws_bytes;
 };
 
 static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan *p)
@@ -150,15 +354,32 @@ static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan 
     const int cpt = (p->ROW <= 16) ? SCAN_VEC * (16 / p->ROW) : 1;
     const int tile = F32_NT * cpt;
     const int64_t tiles = n > 0 ? ceil_div(n, tile) : 1;
-    int64_t G = env_int("QADC_SCAN_F32_WGS", 512);
+    int64_t G = env_int("QADC_SCAN_F32_WGS", 1024);
     if (G < 1) G = 1;
     if (G > tiles) G = tiles;
     const int64_t max_tiles_per_wg = 0xffffffffll / tile;
     if (ceil_div(tiles, G) > max_tiles_per_wg) G = ceil_div(tiles, max_tiles_per_wg);
     p->G = (int)G;
+    // sample for the grid-wide bound, as in the quantized scan
+    p->seed_wgs = 0;
+    p->seed_stride = 0;
+    p->flush_need = 16;
+    if (tiles >= env_int("QADC_SEED_MIN_TILES", 64) * 2) {
+        int64_t S = tiles / 40;
+        if (S < 256) S = 256;
+        if (S > 1024) S = 1024;
+        if (S > tiles / 4) S = tiles / 4;
+        p->seed_wgs = (int)S;
+        p->seed_stride = (n / S) / 16 * 16;
+        int64_t fl = ceil_div(4ll * R, S);
+        if (fl < 16) fl = 16;
+        if (fl > R) fl = R;
+        p->flush_need = (unsigned)fl;
+    }
     p->l = scan_layout(p->G, R);
     p->qbatch = scan_query_batch(p->l.stride, nq);
-    p->ws_bytes = p->l.stride * (size_t)p->qbatch;
+    p->ranges_off = p->l.stride * (size_t)p->qbatch;
+    p->ws_bytes = p->ranges_off + align_up((size_t)p->qbatch * sizeof(F32Range), 256);
     return true;
 }
 
@@ -167,10 +388,19 @@ static void dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, cons
                          int R, char *ws, hipStream_t st)
 {
     dim3 grid(p.G, nq), block(F32_NT);
-#define QADC_F32_CASE(ROW_)                                                                        \
-    case ROW_:                                                                                     \
-        launch(QADC_PROF_SCAN, (scan_f32_kernel<KSUB, ROW_>), grid, block, 0, st, codes, n, luts, R, ws, \
-               p.l.stride, p.l.counts_off, p.l.lists_off);                                         \
+    F32Range *ranges = reinterpret_cast<F32Range *>(ws + p.ranges_off);
+    const int n0 = (int)min((int64_t)F32_RANGE_CODES, n);
+#define QADC_F32_CASE(ROW_)                                                                          \
+    case ROW_:                                                                                       \
+        if (p.seed_wgs > 0) {                                                                        \
+            launch(QADC_PROF_SEED, (f32_range_kernel<KSUB, ROW_>), dim3(nq), block, 0, st, codes, n0, luts, R, \
+                   ranges);                                                                          \
+            launch(QADC_PROF_SEED, (seed_f32_kernel<KSUB, ROW_>), dim3(p.seed_wgs, nq), block, 0, st, codes, n, \
+                   luts, (const F32Range *)ranges, R, p.flush_need, p.seed_stride, ws, p.l.stride);   \
+        }                                                                                            \
+        launch(QADC_PROF_SCAN, (scan_f32_kernel<KSUB, ROW_>), grid, block, 0, st, codes, n, luts,     \
+               (const F32Range *)ranges, p.seed_wgs > 0 ? 1 : 0, R, ws, p.l.stride, p.l.counts_off,   \
+               p.l.lists_off);                                                                       \
         break;
     switch (p.ROW) {
         QADC_F32_CASE(4)

@@ -402,6 +402,44 @@ def test_float_adc_scan_shapes(Q, variant_m, n):
     assert np.array_equal(gd.view(np.uint32), wd.view(np.uint32)), (bits, m, n)
 
 
+@pytest.mark.parametrize("bits", ["4", "8"])
+@pytest.mark.parametrize("kind", ["mixture", "constant", "far_head", "decreasing", "ties"])
+def test_float_adc_scan_large_enough_for_the_seed_kernel(Q, O, bits, kind):
+    """Float scan with the sampled bound: a good bound, a bound with no resolution (every distance
+    equal), a bound placed by an unrepresentative head (the barrier-free pass overflows and the
+    careful pass takes over), decreasing distances, and many exact ties at the R-th place."""
+    from oracle import cref
+    rng = np.random.default_rng(5 + len(kind))
+    n, R = 700_003, 100
+    m, k = (16, 16) if bits == "4" else (8, 256)
+    row = m // 2 if k == 16 else m
+    variant = Q.QADC_F32_4BIT if bits == "4" else Q.QADC_F32_8BIT
+    codes = rng.integers(0, 256, size=(n, row), dtype=np.uint8)
+    if kind == "mixture":
+        luts = rng.gamma(2.0, 50.0, size=(2, m, k)).astype(np.float32)
+    elif kind == "constant":
+        luts = np.full((2, m, k), 3.25, dtype=np.float32)
+    elif kind == "far_head":
+        luts = rng.uniform(0, 100, size=(2, m, k)).astype(np.float32)
+        luts[:, 0, :] += np.linspace(0, 5000, k, dtype=np.float32)
+        hi = 255 if k == 256 else 0xff
+        codes[:1024, 0] = hi   # the head only holds the largest entry of table 0 (and 1)
+        codes[1024:, 0] = 0
+    elif kind == "decreasing":
+        luts = np.zeros((2, m, k), dtype=np.float32)
+        luts[:, 0, :] = np.arange(k, dtype=np.float32) * (1.0 if k == 256 else 16.0)
+        if k == 16:
+            luts[:, 1, :] = np.arange(k, dtype=np.float32)
+        codes[:] = 0
+        codes[:, 0] = (np.arange(n)[::-1] * 250 // n).astype(np.uint8)
+    else:
+        luts = rng.integers(0, 3, size=(2, m, k)).astype(np.float32)
+    gi, gd = gpu_topk_f32(Q, variant, to_gpu(codes), luts, R)
+    wi, wd = cref.scan_topk_f32(codes, luts, R)
+    assert np.array_equal(gi, wi), (bits, kind)
+    assert np.array_equal(gd.view(np.uint32), wd.view(np.uint32)), (bits, kind)
+
+
 @pytest.mark.parametrize("shape", [(128, 16, 16, 6000, 4), (96, 8, 256, 3000, 2)])
 def test_pq_train_matches_oracle(Q, O, shape):
     """GPU k-means (float64 assignment, deterministic float64 means) against the oracle's Lloyd."""
