@@ -38,9 +38,10 @@ HBM_PEAK_GBPS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--workload", choices=["scan", "batched", "ivf"], default="scan",
+    ap.add_argument("--workload", choices=["scan", "batched", "ivf", "compare"], default="scan",
                     help="scan: config 2, one query at a time (default); batched: config 3, query batches "
-                         "over 128-bit codes; ivf: config 4, inverted index with Zipf-skewed lists")
+                         "over 128-bit codes; ivf: config 4, inverted index with Zipf-skewed lists; "
+                         "compare: config 5, 8-bit PQ with float tables against Quick ADC on the same vectors")
     ap.add_argument("--K", type=int, default=65536, help="coarse centroids of the ivf workload")
     ap.add_argument("--nprobe", type=int, default=64)
     ap.add_argument("--steps", type=int, default=None)
@@ -60,7 +61,8 @@ def parse():
     args = ap.parse_args()
     dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200),
             "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000),
-            "ivf": dict(steps=4, warmup=1, n=100_000_000, m=32, init=1000)}[args.workload]
+            "ivf": dict(steps=4, warmup=1, n=100_000_000, m=32, init=1000),
+            "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200)}[args.workload]
     for k, v in dflt.items():
         if getattr(args, k) is None:
             setattr(args, k, v)
@@ -331,16 +333,174 @@ def run_ivf(args):
         "roofline": roofline, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
 
 
+def run_compare(args):
+    """Config 5: the same d=96 vectors under 8-bit PQ (m=8 x 256, float32 tables, Alg. 1) and under
+    Quick ADC (m=16 x 16, uint8 tables, Alg. 2), both 64-bit codes, both one query at a time
+    through the same scan API.  A step = one query through both paths; `value` is Quick ADC's rate.
+    """
+    import numpy as np
+    import torch
+    import paper_1704_07355_amd as Q
+    from workloads import MixtureSpec, SEED_QUERY, SEED_TRAIN, SEED_BASE, kmeans_init_rows
+    from workloads.mixture_torch import mixture_vectors_torch, BLOCK
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    spec = MixtureSpec(d=96)
+    n, R, init = args.n, args.R, args.init
+    t0 = time.time()
+    train = mixture_vectors_torch(spec, SEED_TRAIN, 0, 20_000, dev)
+    cb8 = Q.qadc_pq_train(train, 8, 256, torch.from_numpy(kmeans_init_rows(20_000, 256)).to(dev), 10)
+    cb4 = Q.qadc_pq_train(train, 16, 16, torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev), 10)
+    codes8 = torch.empty((n, 8), dtype=torch.uint8, device=dev)
+    codes4 = torch.empty((n, 8), dtype=torch.uint8, device=dev)
+    keep = args.recall_queries > 0
+    raw = torch.empty((n, spec.d), dtype=torch.float32, device=dev) if keep else None
+    chunk = 4 * BLOCK
+    for s in range(0, n, chunk):
+        cnt = min(chunk, n - s)
+        x = mixture_vectors_torch(spec, SEED_BASE, s, cnt, dev)
+        Q.qadc_pq_encode(cb8, x, out=codes8[s:s + cnt])
+        Q.qadc_pq_encode(cb4, x, out=codes4[s:s + cnt])
+        if keep:
+            raw[s:s + cnt] = x
+    queries = mixture_vectors_torch(spec, SEED_QUERY, 0, args.queries, dev)
+    torch.cuda.synchronize()
+    t_build = time.time() - t0
+
+    ws4 = Q.qadc_workspace_init(torch.empty(Q.qadc_workspace_bytes(Q.QADC_WS_SEARCH, n, 16, 1, R),
+                                            dtype=torch.uint8, device=dev))
+    ws8 = Q.qadc_workspace_init(torch.empty(Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_F32_8BIT, n, 8, 1, R),
+                                            dtype=torch.uint8, device=dev))
+    luts8 = torch.empty((1, 8, 256), dtype=torch.float32, device=dev)
+    idx4 = torch.empty((1, R), dtype=torch.int32, device=dev)
+    dist4 = torch.empty((1, R), dtype=torch.uint8, device=dev)
+    idx8 = torch.empty((1, R), dtype=torch.int32, device=dev)
+    dist8 = torch.empty((1, R), dtype=torch.float32, device=dev)
+
+    def quick(i):
+        qi = i % args.queries
+        Q.qadc_search(cb4, queries[qi:qi + 1], codes4, R, init, workspace=ws4, out_idx=idx4, out_dist=dist4)
+
+    def pq8(i):
+        qi = i % args.queries
+        Q.qadc_build_luts(cb8, queries[qi:qi + 1], out=luts8)
+        Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, luts8, R, workspace=ws8, out_idx=idx8, out_dist=dist8)
+
+    def timed(fn):
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            fn(args.warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    ms4 = timed(quick)
+    ms8 = timed(pq8)
+
+    roofline = kernels = None
+    if not args.no_profile:
+        nprof = min(args.steps, 200)
+        per = {}
+        for name, fn in (("quick_adc", quick), ("pq8_float", pq8)):
+            Q.qadc_profile_enable(True)
+            for i in range(nprof):
+                fn(i)
+            torch.cuda.synchronize()
+            per[name] = {}
+            for k, which in (("scan", Q.QADC_PROF_SCAN), ("seed", Q.QADC_PROF_SEED), ("merge", Q.QADC_PROF_MERGE),
+                             ("tables", Q.QADC_PROF_TABLES), ("prepare", Q.QADC_PROF_PREPARE)):
+                ms, cnt = Q.qadc_profile_read(which)
+                if cnt:
+                    per[name][k + "_us_per_query"] = round(ms / nprof * 1e3, 2)
+            Q.qadc_profile_enable(False)
+        kernels = per
+        us = per["quick_adc"]["scan_us_per_query"]
+        ach = n * 8 / (us * 1e-6) / 1e9
+        us8 = per["pq8_float"]["scan_us_per_query"]
+        roofline = {"bound": "hbm", "kernel": "scan_u8_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "avg_kernel_us": us, "bytes_per_launch": n * 8, "launches_timed": nprof,
+                    "pq8_float_scan_kernel": {"avg_kernel_us": us8,
+                                              "achieved": round(n * 8 / (us8 * 1e-6) / 1e9, 1),
+                                              "frac": round(n * 8 / (us8 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}}
+
+    acc = None
+    if keep:
+        nq = min(args.recall_queries, args.queries)
+        qs = queries[:nq].contiguous()
+        i4, _ = Q.qadc_search(cb4, qs, codes4, R, init)
+        f4, _ = Q.qadc_scan_topk(Q.QADC_F32_4BIT, codes4, Q.qadc_build_luts(cb4, qs), R)
+        i8, _ = Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, Q.qadc_build_luts(cb8, qs), R)
+        best = torch.full((nq,), float("inf"), device=dev)
+        arg = torch.zeros((nq,), dtype=torch.int64, device=dev)
+        qq = (qs * qs).sum(1)
+        for s in range(0, n, 1 << 20):
+            x = raw[s:s + (1 << 20)]
+            dist = qq[:, None] - 2.0 * qs @ x.T + (x * x).sum(1)[None, :]
+            v, a = dist.min(1)
+            upd = v < best
+            best[upd] = v[upd]
+            arg[upd] = a[upd] + s
+        torch.cuda.synchronize()
+        nn = arg.cpu().numpy()
+        h = {k: v.cpu().numpy().view(np.uint32).astype(np.int64) for k, v in (("q", i4), ("f4", f4), ("f8", i8))}
+        rec = {k: float(np.mean([nn[i] in h[k][i] for i in range(nq)])) for k in h}
+        ov = float(np.mean([len(np.intersect1d(a, b)) / R for a, b in zip(h["q"], h["f4"])]))
+        acc = {"queries": nq, "nn_recall_at_R_quick_adc": round(rec["q"], 4),
+               "nn_recall_at_R_float_adc_4bit_codes": round(rec["f4"], 4),
+               "nn_recall_at_R_pq8_float": round(rec["f8"], 4),
+               "overlap_at_R_quick_vs_float_adc_same_codes": round(ov, 4),
+               "note": "NN-recall = exact nearest neighbour (raw vectors) among the R returned, the paper's "
+                       "Recall@R; the mixture's within-component neighbours are isotropic noise, so every 64-bit "
+                       "code sits near chance here -- the overlap with float ADC is the meaningful figure"}
+
+    cpu = None
+    if args.cpu_queries > 0:
+        from oracle import cref
+        nqc = min(32, args.queries)
+        h_codes = codes4.cpu().numpy()
+        ql = torch.empty((nqc, 16, 16), dtype=torch.uint8, device=dev)
+        gi, gd = Q.qadc_search(cb4, queries[:nqc].contiguous(), codes4, R, init, qluts_out=ql)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        ci, cd = cref.scan_topk_u8(h_codes, ql.cpu().numpy(), R)
+        dt = time.time() - t0
+        cpu = {"value": round(nqc * n / dt / 1e9, 4), "unit": "Gcodes/s", "cores": cref.num_threads(),
+               "kind": "oracle", "sample": "%d Quick ADC queries x %d codes, one query per thread" % (nqc, n),
+               "seconds": round(dt, 2),
+               "gpu_matches_oracle": bool(np.array_equal(gi.cpu().numpy().view(np.uint32), ci)
+                                          and np.array_equal(gd.cpu().numpy(), cd))}
+
+    print(json.dumps({
+        "metric": "G PQ codes scanned/s (Quick ADC m=16 x 4-bit, whole path per query) with the 8-bit PQ "
+                  "float-table scan of the same vectors beside it",
+        "value": round(n / (ms4 * 1e-3) / 1e9, 2), "unit": "Gcodes/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms4, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "config 5: d=96 mixture, N=%d vectors as PQ m=8 x 256 (float32 tables) and as "
+                   "PQ m=16 x 16 (Quick ADC, uint8 tables), 64-bit codes both, queries one at a time, R=%d, "
+                   "init=%d" % (n, R, init), "n": n, "R": R, "init": init},
+        "pq8_float": {"ms_per_query": round(ms8, 5), "gcodes_per_s": round(n / (ms8 * 1e-3) / 1e9, 2)},
+        "speedup_quick_adc_over_pq8_float": round(ms8 / ms4, 3),
+        "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,
+        "database_build_s": round(t_build, 2)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
               "(no collectives, no sharding in this library)" % args.gpus, file=sys.stderr)
         sys.exit(2)
-    if args.workload in ("batched", "ivf"):
+    if args.workload in ("batched", "ivf", "compare"):
         import paper_1704_07355_amd as Q
         Q.lib()
-        return run_batched(args) if args.workload == "batched" else run_ivf(args)
+        return {"batched": run_batched, "ivf": run_ivf, "compare": run_compare}[args.workload](args)
 
     import numpy as np
     import torch
