@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--cpu-queries", type=int, default=256, help="queries of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--recall-queries", type=int, default=100, help="queries of the accuracy sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timing pass")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="scan workload: also run this many plain device copies of one code buffer (untimed), so "
+                         "that a counter run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
     args = ap.parse_args()
@@ -539,6 +542,13 @@ def main():
         else:
             Q.qadc_search(cb, queries[qi:qi + 1], buf, R, init, workspace=ws, out_idx=out_idx,
                           out_dist=out_dist)
+
+    if args.copy_calibration > 0:
+        dst = torch.empty_like(bufs[0])
+        for i in range(args.copy_calibration):
+            dst.copy_(bufs[i % args.buffers])  # reads n*row bytes, writes n*row bytes
+        torch.cuda.synchronize()
+        del dst
 
     for i in range(args.warmup):
         step(i)
