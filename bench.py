@@ -53,7 +53,7 @@ def parse():
     ap.add_argument("--R", type=int, default=100)
     ap.add_argument("--init", type=int, default=None)
     ap.add_argument("--queries", type=int, default=1000)
-    ap.add_argument("--cpu-queries", type=int, default=256, help="queries of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-queries", type=int, default=2048, help="queries of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--recall-queries", type=int, default=100, help="queries of the accuracy sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timing pass")
     ap.add_argument("--copy-calibration", type=int, default=0,
@@ -125,6 +125,11 @@ def accuracy(Q, torch, np, cb, codes, raw, queries, R, init):
             "nn_recall_at_R_quick_adc": round(rec_q, 4), "nn_recall_at_R_float_adc": round(rec_f, 4)}
 
 
+# HBM bytes per scan_u8_kernel launch from the FETCH_SIZE / WRITE_SIZE counter runs summarized in
+# profiles/scan_u8_config2_hbm_traffic.md (scaled by a plain copy of known size); valid for the
+# workload it was measured on only: (n, m) -> (bytes read, bytes written).
+SCAN_TRAFFIC = {(10_000_000, 16): (39150.9 * 1.9994 * 1024, 53.1 * 1.0 * 1024)}
+
 ALU_PEAK_TLOOKUPS = 157.3  # 256 CUs x 64 lanes x 2.4 GHz x 4 byte lanes per 32-bit lane-op
 
 
@@ -188,7 +193,7 @@ def run_batched(args):
     cpu = None
     if args.cpu_queries > 0:
         from oracle import cref
-        nqc = min(8, nb)
+        nqc = min(64, nb)
         h_codes = codes.cpu().numpy()
         h_ql = ql_out[:nqc].cpu().numpy()
         gi, gd = out_idx[:nqc].cpu().numpy().view(np.uint32), out_dist[:nqc].cpu().numpy()
@@ -291,7 +296,7 @@ def run_ivf(args):
     cpu = None
     if args.cpu_queries > 0:
         from oracle import qadc_oracle as O
-        nqc = min(4, nb)
+        nqc = min(100, nb)
         h_coarse, h_cb = coarse.cpu().numpy(), cb.cpu().numpy()
         h_off = list_off.cpu().numpy()
         h_q = queries[last * nb:last * nb + nqc].cpu().numpy()
@@ -465,7 +470,7 @@ def run_compare(args):
     cpu = None
     if args.cpu_queries > 0:
         from oracle import cref
-        nqc = min(32, args.queries)
+        nqc = min(256, args.queries)
         h_codes = codes4.cpu().numpy()
         ql = torch.empty((nqc, 16, 16), dtype=torch.uint8, device=dev)
         gi, gd = Q.qadc_search(cb4, queries[:nqc].contiguous(), codes4, R, init, qluts_out=ql)
@@ -582,9 +587,13 @@ def main():
         Q.qadc_profile_enable(False)
         avg_us, launches = us["scan"]
         achieved = n * row / (avg_us * 1e-6) / 1e9
+        tr = SCAN_TRAFFIC.get((n, m))
         roofline = {"bound": "hbm", "kernel": "scan_u8_kernel", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                    "traffic": None, "avg_kernel_us": round(avg_us, 2),
+                    "traffic": int(tr[0] + tr[1]) if tr else None,
+                    "traffic_source": "profiles/scan_u8_config2_hbm_traffic.md (rocprofv3 --pmc, bytes per "
+                                      "launch, read %d + written %d)" % (tr[0], tr[1]) if tr else None,
+                    "avg_kernel_us": round(avg_us, 2),
                     "bytes_per_launch": n * row, "launches_timed": launches}
         kernels = {k + "_kernel_us": round(v[0], 2) for k, v in us.items() if v[1]}
 
@@ -598,9 +607,9 @@ def main():
     cpu = None
     if args.cpu_queries > 0:
         from oracle import cref
-        nqc = min(args.cpu_queries, args.queries)
+        nqc = args.cpu_queries
         h_codes = bufs[0].cpu().numpy()
-        l = Q.qadc_build_luts(cb, queries[:nqc].contiguous())
+        l = Q.qadc_build_luts(cb, mixture_vectors_torch(spec, SEED_QUERY, 0, nqc, dev))
         ql, _, _, _ = Q.qadc_quantize_luts(l, bufs[0][:init], R)
         gi, gd = Q.qadc_scan_topk(Q.QADC_U8_4BIT, bufs[0], ql, R)
         torch.cuda.synchronize()

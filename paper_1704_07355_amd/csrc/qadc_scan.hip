@@ -82,6 +82,46 @@ __device__ __forceinline__ void tile_keys(const uint4 (&w)[2], const int (&nc)[2
     }
 }
 
+// Unclamped sums of a whole tile (every slot holds a code), for the pass that only keeps
+// sums at or below a bound smaller than the saturation value.
+template <int B, int NT>
+__device__ __forceinline__ void tile_sums(const uint4 (&w)[2], const uint8_t *ptab,
+                                          unsigned (&sm)[ScanCfg<B, NT>::CPT])
+{
+    if constexpr (B <= 16) {
+        constexpr int CPV = 16 / B;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+#pragma unroll
+            for (int c = 0; c < CPV; ++c) {
+                unsigned s = 0;
+#pragma unroll
+                for (int jb = 0; jb < B; ++jb) s += pair_entry(ptab, jb, byte_of(w[v], c * B + jb));
+                sm[v * CPV + c] = s;
+            }
+        }
+    } else {
+        unsigned s = 0;
+#pragma unroll
+        for (int jb = 0; jb < 16; ++jb) s += pair_entry(ptab, jb, byte_of(w[0], jb));
+#pragma unroll
+        for (int jb = 0; jb < 16; ++jb) s += pair_entry(ptab, 16 + jb, byte_of(w[1], jb));
+        sm[0] = s;
+    }
+}
+
+// Index of slot c of this thread inside a tile (the layout tile_load and tile_keys use).
+template <int B, int NT>
+__device__ __forceinline__ unsigned tile_slot_index(int c)
+{
+    if constexpr (B <= 16) {
+        constexpr int CPV = 16 / B;
+        return (unsigned)(((c / CPV) * NT + (int)threadIdx.x) * CPV + c % CPV);
+    } else {
+        return threadIdx.x;
+    }
+}
+
 // Pair tables of one query in LDS: ptab[jb][v] = min(cap, q[2jb][v & 15] + q[2jb+1][v >> 4]).
 template <int B, int NT>
 __device__ __forceinline__ void build_pair_tables(const uint8_t *__restrict__ qlut, unsigned cap,
@@ -95,15 +135,17 @@ __device__ __forceinline__ void build_pair_tables(const uint8_t *__restrict__ ql
     }
 }
 
-// Seed kernel: a sample of the database (one tile per workgroup, tiles spread evenly) is
-// scanned and histogrammed by sum.  Each workgroup adds the counts of its lowest bins (its
-// best `flush_need` codes, never beyond its own R-th) to the query's grid-wide histogram.
-// The bin where that histogram's running count reaches R bounds the R-th smallest sum of
-// the whole database from above: the scan kernel only keeps keys at or below it.
+// Seed kernel: a sample of the database (`tiles_per_wg` tiles per workgroup, all tiles spread
+// evenly) is scanned and histogrammed by sum.  Each workgroup adds the counts of its lowest
+// bins (its best `flush_need` codes, never beyond its own R-th) to the query's grid-wide
+// histogram.  The bin where that histogram's running count reaches R bounds the R-th
+// smallest sum of the whole database from above: the scan kernel only keeps keys at or
+// below it.
 template <int B>
 __global__ __launch_bounds__(1024) void seed_u8_kernel(
     const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, unsigned flush_need, int64_t seed_stride, char *__restrict__ ws, size_t ws_stride)
+    int R, unsigned flush_need, int64_t seed_stride, int tiles_per_wg, char *__restrict__ ws,
+    size_t ws_stride)
 {
     constexpr int NT = 1024;
     using C = ScanCfg<B, NT>;
@@ -114,13 +156,12 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
     const int q = blockIdx.y;
     const int g = blockIdx.x;
     const unsigned cap = (unsigned)cap_i;
-    const int64_t c0 = (int64_t)g * seed_stride;
-    const int64_t c1 = min(n, c0 + C::TILE);
-    if (c0 >= c1) return;
+    int64_t c0 = (int64_t)g * tiles_per_wg * seed_stride;
+    if (c0 >= n) return;
 
     uint4 w[2];
     int nc[2];
-    tile_load<B, NT>(codes, c0, c1, w, nc);
+    tile_load<B, NT>(codes, c0, min(n, c0 + C::TILE), w, nc);
     build_pair_tables<B, NT>(qluts + (size_t)q * (2 * B) * 16, cap, ptab);
     for (int e = tid; e < 256; e += NT) hist[e] = 0;
     __syncthreads();
@@ -130,11 +171,14 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
         for (int e = tid; e < B * 64; e += NT)
             reinterpret_cast<unsigned *>(hdr0->ptab)[e] = reinterpret_cast<const unsigned *>(ptab)[e];
     }
-    unsigned k[C::CPT];
-    tile_keys<B, NT>(w, nc, 0u, ptab, cap, k);
+    for (int t = 0; t < tiles_per_wg && c0 < n; ++t, c0 += seed_stride) {  // uniform
+        if (t) tile_load<B, NT>(codes, c0, min(n, c0 + C::TILE), w, nc);
+        unsigned k[C::CPT];
+        tile_keys<B, NT>(w, nc, 0u, ptab, cap, k);
 #pragma unroll
-    for (int c = 0; c < C::CPT; ++c)
-        if ((k[c] >> 24) < cap) atomicAdd(&hist[k[c] >> 24], 1u);  // NO_KEY has sum 255 >= cap
+        for (int c = 0; c < C::CPT; ++c)
+            if ((k[c] >> 24) < cap) atomicAdd(&hist[k[c] >> 24], 1u);  // NO_KEY has sum 255 >= cap
+    }
     __syncthreads();
     if (tid < WAVE) {
         unsigned h[4];
@@ -402,22 +446,43 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     if ((int64_t)g * C::TILE >= n) return;  // uniform: no tile for this workgroup
     if (redo_flags && redo_flags[q] == 0) return;  // uniform: only the queries the tiled scan gave up on
 
+    // Loads are returned in the order they were issued: the small ones the set-up waits for
+    // (the seed kernel's pair tables and the low half of its histogram) go first, the first
+    // tile of codes after them, so that set-up runs while the tile is in flight.
+    constexpr int PPT = (B * 16 + NT - 1) / NT;  // 16-byte pieces of the pair tables per thread
+    uint4 pt[PPT];
+    uint2 gh[GH_REP];
+    if (has_seed) {
+#pragma unroll
+        for (int t = 0; t < PPT; ++t)
+            if (tid + t * NT < B * 16) pt[t] = reinterpret_cast<const uint4 *>(hdr->ptab)[tid + t * NT];
+        if (tid < WAVE) {
+#pragma unroll
+            for (int r = 0; r < GH_REP; ++r) gh[r] = *reinterpret_cast<const uint2 *>(&hdr->ghist[r][2 * tid]);
+        }
+        asm volatile("" ::: "memory");
+    }
     uint4 w[2];
     int nc[2];
-    tile_load<B, NT>(codes, (int64_t)g * C::TILE, n, w, nc);  // first tile: in flight during set-up
+    tile_load<B, NT>(codes, (int64_t)g * C::TILE, n, w, nc);
+    asm volatile("" ::: "memory");
 
     // The grid-wide bound left by the seed kernel: the bin where the running count of the
     // summed replicas reaches R, or 256.  Pair tables: those of the seed kernel, or built here.
     if (tid < WAVE) {
         unsigned t = 256, carry = 0;
         for (unsigned b0 = 0; b0 < 256 && has_seed; b0 += 128) {  // uniform
-            const unsigned bin = b0 + 2u * tid;
             unsigned h[2] = {0, 0};
+            if (b0 == 0) {
 #pragma unroll
-            for (int r = 0; r < GH_REP; ++r) {
-                const uint2 v = *reinterpret_cast<const uint2 *>(&hdr->ghist[r][bin]);
-                h[0] += v.x;
-                h[1] += v.y;
+                for (int r = 0; r < GH_REP; ++r) { h[0] += gh[r].x; h[1] += gh[r].y; }
+            } else {
+#pragma unroll
+                for (int r = 0; r < GH_REP; ++r) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(&hdr->ghist[r][b0 + 2u * tid]);
+                    h[0] += v.x;
+                    h[1] += v.y;
+                }
             }
             unsigned tot;
             const unsigned hit = wave_threshold_bin<2>(h, (unsigned)R - carry, &tot);
@@ -428,8 +493,9 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     }
     for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
     if (has_seed) {
-        for (int e = tid; e < B * 16; e += NT)
-            reinterpret_cast<uint4 *>(ptab)[e] = reinterpret_cast<const uint4 *>(hdr->ptab)[e];
+#pragma unroll
+        for (int t = 0; t < PPT; ++t)
+            if (tid + t * NT < B * 16) reinterpret_cast<uint4 *>(ptab)[tid + t * NT] = pt[t];
     } else {
         const uint8_t *qlut = qluts + (size_t)q * (2 * B) * 16;
         for (int e = tid; e < 2 * B * 4; e += NT)
@@ -450,22 +516,38 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     bool careful = !seeded;
 
     if (seeded) {
-        // barrier-free pass
+        // Barrier-free pass.  The bound is below the saturation value (the seed histogram only
+        // counts unsaturated sums), so a sum that passes needs no clamp; whole tiles are tested
+        // with one comparison per thread and the append code runs only in waves with a hit.
+        const unsigned tau = sh.tau;
         unsigned rel = 0;
         for (int64_t t0 = (int64_t)g * C::TILE; t0 < n; t0 += G * C::TILE, rel += C::TILE) {
-            unsigned k[C::CPT];
             if (t0 + C::TILE <= n) {  // uniform: a whole tile, no bounds to check
                 if (rel) tile_load<B, NT, true>(codes, t0, n, w, nc);
-                tile_keys<B, NT, true>(w, nc, rel, ptab, cap, k);
+                unsigned sm[C::CPT];
+                tile_sums<B, NT>(w, ptab, sm);
+                unsigned best = sm[0];
+#pragma unroll
+                for (int c = 1; c < C::CPT; ++c) best = min(best, sm[c]);
+                if (__ballot(best <= tau) != 0ull) {
+#pragma unroll
+                    for (int c = 0; c < C::CPT; ++c) {
+                        const bool pass = sm[c] <= tau;
+                        const unsigned slot = wave_append_slot(pass, &sh.fcnt);
+                        if (pass && slot < (unsigned)C::CAP)
+                            keys[slot] = (sm[c] << 24) | (rel + tile_slot_index<B, NT>(c));
+                    }
+                }
             } else {
                 if (rel) tile_load<B, NT>(codes, t0, n, w, nc);
+                unsigned k[C::CPT];
                 tile_keys<B, NT>(w, nc, rel, ptab, cap, k);
-            }
 #pragma unroll
-            for (int c = 0; c < C::CPT; ++c) {
-                const bool pass = k[c] < lim;
-                const unsigned slot = wave_append_slot(pass, &sh.fcnt);
-                if (pass && slot < (unsigned)C::CAP) keys[slot] = k[c];
+                for (int c = 0; c < C::CPT; ++c) {
+                    const bool pass = k[c] < lim;
+                    const unsigned slot = wave_append_slot(pass, &sh.fcnt);
+                    if (pass && slot < (unsigned)C::CAP) keys[slot] = k[c];
+                }
             }
         }
         __syncthreads();
@@ -633,23 +715,26 @@ static void launch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, c
 static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
                              const uint8_t *qluts, int nq, int cap, int R, char *ws, hipStream_t st)
 {
-    dim3 grid(p.seed_wgs, nq);
+    // batches: several tiles per workgroup, so that building the pair tables pays
+    const int tpw = (nq >= TILED_MIN_Q) ? 8 : 1;
+    dim3 grid((unsigned)ceil_div(p.seed_wgs, tpw), nq);
+    const unsigned flush = (unsigned)min((int64_t)R, (int64_t)p.flush_need * tpw);
     switch (p.B) {
     case 4:
         launch(QADC_PROF_SEED, seed_u8_kernel<4>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           p.flush_need, p.seed_stride, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride);
         break;
     case 8:
         launch(QADC_PROF_SEED, seed_u8_kernel<8>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           p.flush_need, p.seed_stride, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride);
         break;
     case 16:
         launch(QADC_PROF_SEED, seed_u8_kernel<16>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           p.flush_need, p.seed_stride, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride);
         break;
     default:
         launch(QADC_PROF_SEED, seed_u8_kernel<32>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           p.flush_need, p.seed_stride, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride);
         break;
     }
 }

@@ -6,7 +6,9 @@
 namespace qadc {
 
 constexpr int TILED_Q = 8;             // queries per workgroup
-constexpr int TILED_NT = 512;          // threads per workgroup
+// threads per workgroup: with m = 64 (B = 32) one workgroup's tables fill 128 KiB of the LDS,
+// so that workgroup is made twice as large to keep enough wavefronts on the CU
+constexpr int tiled_nt(int B) { return B >= 32 ? 1024 : 512; }
 constexpr int TILED_LCAP = 64;         // keys a workgroup can report per query
 constexpr int TILED_MAX_CHUNKS = 1024; // database chunks per query
 constexpr int TILED_MIN_Q = 8;         // smallest batch worth tiling

@@ -19,6 +19,19 @@
 
 namespace qadc {
 
+// Two 16-bit lanes per register: saturating a - b, and min.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pk_sub_sat_u16(unsigned a, unsigned b)
+{
+    const u16x2 r = __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
+    return __builtin_bit_cast(unsigned, r);
+}
+__device__ __forceinline__ unsigned pk_min_u16(unsigned a, unsigned b)
+{
+    const u16x2 r = __builtin_elementwise_min(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
+    return __builtin_bit_cast(unsigned, r);
+}
+
 // tau[q] = bin where the running count of query q's histogram reaches R, or 256.
 __global__ __launch_bounds__(256) void scan_tau_kernel(const char *__restrict__ ws, size_t ws_stride,
                                                        int nq, int R, unsigned *__restrict__ taus)
@@ -46,12 +59,12 @@ __global__ __launch_bounds__(256) void scan_tau_kernel(const char *__restrict__ 
 }
 
 template <int B>
-__global__ __launch_bounds__(TILED_NT) void scan_u8_tiled_kernel(
+__global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled_kernel(
     const uint8_t *__restrict__ codes, int64_t n, int64_t chunk, int nq, int cap_i,
     const unsigned *__restrict__ taus, const char *__restrict__ ws, size_t ws_stride,
     size_t countsA_off, size_t listsA_off, unsigned *__restrict__ flags)
 {
-    constexpr int NT = TILED_NT;
+    constexpr int NT = tiled_nt(B);
     using C = ScanCfg<B, NT>;
     extern __shared__ uint4 tab[];  // [B * 256] entries of eight 16-bit pair sums
     __shared__ unsigned keys[TILED_Q][TILED_LCAP];
@@ -75,7 +88,7 @@ __global__ __launch_bounds__(TILED_NT) void scan_u8_tiled_kernel(
 #pragma unroll
         for (int k = 0; k < TILED_Q; ++k) {
             const int q = q0 + k;
-            v[k] = 0;
+            v[k] = 1;  // no query in this slot: sums stay above its bound of "nothing passes"
             if (q < nq) v[k] = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ptab[e];
         }
         tab[e] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
@@ -92,6 +105,12 @@ __global__ __launch_bounds__(TILED_NT) void scan_u8_tiled_kernel(
             thr[k] = (t >= cap) ? 0xffff : (int)t;
         }
     }
+    // thr + 1 of two queries per register (saturating at 0xffff, which no sum reaches; 0 where
+    // there is no query): lane k of (acc -sat- thr1) is zero exactly when query k's sum passes.
+    unsigned thr1[TILED_Q / 2];
+#pragma unroll
+    for (int i = 0; i < TILED_Q / 2; ++i)
+        thr1[i] = (unsigned)min(thr[2 * i] + 1, 0xffff) | ((unsigned)min(thr[2 * i + 1] + 1, 0xffff) << 16);
     __syncthreads();
 
     unsigned rel = 0;
@@ -119,13 +138,19 @@ __global__ __launch_bounds__(TILED_NT) void scan_u8_tiled_kernel(
                 }
                 const bool valid = (B <= 16) ? (c < nc[v]) : (nc[0] != 0);
                 const unsigned li = rel + (unsigned)((B <= 16) ? (v * NT + tid) * CPV + c : tid);
-                const unsigned acc[4] = {a0, a1, a2, a3};
+                // does any of the eight sums pass?  (rare: the append code is skipped otherwise)
+                const unsigned z = pk_min_u16(pk_min_u16(pk_sub_sat_u16(a0, thr1[0]), pk_sub_sat_u16(a1, thr1[1])),
+                                              pk_min_u16(pk_sub_sat_u16(a2, thr1[2]), pk_sub_sat_u16(a3, thr1[3])));
+                const bool any = valid && min(z & 0xffffu, z >> 16) == 0u;
+                if (__ballot(any) != 0ull) {
+                    const unsigned acc[4] = {a0, a1, a2, a3};
 #pragma unroll
-                for (int k = 0; k < TILED_Q; ++k) {
-                    const unsigned s = (k & 1) ? (acc[k >> 1] >> 16) : (acc[k >> 1] & 0xffffu);
-                    const bool pass = valid && (int)s <= thr[k];
-                    const unsigned slot = wave_append_slot(pass, &cnt[k]);
-                    if (pass && slot < (unsigned)TILED_LCAP) keys[k][slot] = (min(s, cap) << 24) | li;
+                    for (int k = 0; k < TILED_Q; ++k) {
+                        const unsigned s = (k & 1) ? (acc[k >> 1] >> 16) : (acc[k >> 1] & 0xffffu);
+                        const bool pass = valid && (int)s <= thr[k];
+                        const unsigned slot = wave_append_slot(pass, &cnt[k]);
+                        if (pass && slot < (unsigned)TILED_LCAP) keys[k][slot] = (min(s, cap) << 24) | li;
+                    }
                 }
             }
         }
@@ -157,7 +182,7 @@ bool make_tiled_plan(int64_t n, int m, int nq, TiledPlan *t)
 {
     t->B = m / 2;
     const int cpt = (t->B <= 16) ? SCAN_VEC * (16 / t->B) : 1;
-    const int tile = TILED_NT * cpt;
+    const int tile = tiled_nt(t->B) * cpt;
     // chunks: at most TILED_MAX_CHUNKS per query, at least 64 tiles long, a multiple of the tile,
     // below 2^24 codes (index bits of a key)
     int64_t chunk = ceil_div(ceil_div(n, TILED_MAX_CHUNKS), tile) * tile;
@@ -182,7 +207,7 @@ static int launch_tiled(const TiledPlan &t, const uint8_t *codes, int64_t n, int
         attr_set = true;
     }
     dim3 grid((unsigned)ceil_div(nq, TILED_Q), (unsigned)t.GC);
-    launch(QADC_PROF_SCAN, scan_u8_tiled_kernel<B>, grid, dim3(TILED_NT), t.lds_bytes, st, codes, n, t.chunk,
+    launch(QADC_PROF_SCAN, scan_u8_tiled_kernel<B>, grid, dim3(tiled_nt(B)), t.lds_bytes, st, codes, n, t.chunk,
            nq, cap, taus, (const char *)ws, ws_stride, countsA_off, listsA_off, flags);
     return QADC_OK;
 }
