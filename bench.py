@@ -64,7 +64,7 @@ def parse():
     args = ap.parse_args()
     dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200),
             "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000),
-            "ivf": dict(steps=4, warmup=1, n=100_000_000, m=32, init=1000),
+            "ivf": dict(steps=4, warmup=1, n=1_000_000_000, m=32, init=1000),
             "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200)}[args.workload]
     for k, v in dflt.items():
         if getattr(args, k) is None:
@@ -281,8 +281,8 @@ def run_ivf(args):
     torch.cuda.synchronize()
     phase = {}
     for name, which in (("index", Q.QADC_PROF_IVF_INDEX), ("tables", Q.QADC_PROF_IVF_TABLES),
-                        ("quantize", Q.QADC_PROF_QUANTIZE), ("scan", Q.QADC_PROF_SCAN),
-                        ("merge", Q.QADC_PROF_MERGE)):
+                        ("quantize", Q.QADC_PROF_QUANTIZE), ("seed", Q.QADC_PROF_SEED),
+                        ("scan", Q.QADC_PROF_SCAN), ("merge", Q.QADC_PROF_MERGE)):
         phase[name] = Q.qadc_profile_read(which)[0]
     Q.qadc_profile_enable(False)
     h_probes = probes.cpu().numpy()
@@ -296,7 +296,7 @@ def run_ivf(args):
     cpu = None
     if args.cpu_queries > 0:
         from oracle import qadc_oracle as O
-        nqc = min(100, nb)
+        nqc = min(32, nb)
         h_coarse, h_cb = coarse.cpu().numpy(), cb.cpu().numpy()
         h_off = list_off.cpu().numpy()
         h_q = queries[last * nb:last * nb + nqc].cpu().numpy()

@@ -53,27 +53,73 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
 }
 
 // probes[q][0..nprobe) = the nprobe closest cells, closest first, ties to the lowest cell id.
-__global__ __launch_bounds__(1024) void ivf_select_probes_kernel(
+// Keys are order(dist) << 32 | cell (unique).  Thread t looks at cells t, t + NT, ...  The
+// need-th smallest of the threads' minima, T, bounds the need-th smallest key of the whole
+// row from above (need threads each hold a key <= T), and only those need threads can hold
+// keys <= T: at most need * ceil(K / NT) candidates, normally about `need` of them.  A second
+// pass over the row gathers the candidates in LDS, where the exact selection runs.  A
+// candidate list that does not fit takes the radix select over the whole row instead.
+constexpr int IVF_SEL_NT = 1024;
+constexpr int IVF_SEL_CAP = 4096;
+
+__global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
     const float *__restrict__ dist, int K, int nprobe, int32_t *__restrict__ probes)
 {
+    constexpr int NT = IVF_SEL_NT;
     __shared__ SelectScratch sc;
-    __shared__ uint64_t sel[IVF_MAX_NPROBE];
+    __shared__ uint64_t cand[IVF_SEL_CAP];  // thread minima first, then the candidates
     __shared__ unsigned cnt;
+    const int tid = threadIdx.x;
     const int q = blockIdx.x;
     const float *dq = dist + (size_t)q * K;
-    auto each = [&](auto f) {
-        for (int c = threadIdx.x; c < K; c += blockDim.x)
-            f(((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c);
-    };
     const unsigned need = (unsigned)min(nprobe, K);
-    const uint64_t kth = block_radix_select_each<uint64_t, 8>(each, need, &sc);
-    if (threadIdx.x == 0) cnt = 0;
+
+    // this thread's smallest key: smallest value, lowest cell among equals (cells grow with c)
+    uint64_t mine = ~0ull;
+    for (int c = tid; c < K; c += NT) {
+        const uint64_t k = ((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c;
+        mine = min(mine, k);
+    }
+    const int nmin = min(K, NT);  // threads that hold at least one key
+    if (tid < nmin) cand[tid] = mine;
+    if (tid == 0) cnt = 0;
     __syncthreads();
-    each([&](uint64_t k) {
-        if (k <= kth) sel[atomicAdd(&cnt, 1u)] = k;  // exactly `need` keys: they are unique
-    });
+    const uint64_t T = block_radix_select<uint64_t, 8>(cand, (unsigned)nmin, need, &sc);
+    __syncthreads();  // everybody has T; the minima may be overwritten
+    if (mine <= T) {  // only these threads can hold candidates
+        for (int c = tid; c < K; c += NT) {
+            const uint64_t k = ((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c;
+            if (k <= T) {
+                const unsigned slot = atomicAdd(&cnt, 1u);
+                if (slot < (unsigned)IVF_SEL_CAP) cand[slot] = k;
+            }
+        }
+    }
     __syncthreads();
-    for (unsigned i = threadIdx.x; i < (unsigned)nprobe; i += blockDim.x) {
+    const unsigned ncand = cnt;
+    const bool in_lds = ncand <= (unsigned)IVF_SEL_CAP;
+    __syncthreads();
+
+    auto each_row = [&](auto f) {
+        for (int c = tid; c < K; c += NT) f(((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c);
+    };
+    uint64_t kth;
+    if (in_lds) kth = block_radix_select<uint64_t, 8>(cand, ncand, need, &sc);
+    else kth = block_radix_select_each<uint64_t, 8>(each_row, need, &sc);
+    // the winners (exactly `need`: keys are unique), ordered by rank
+    __shared__ uint64_t sel[IVF_MAX_NPROBE];
+    if (tid == 0) cnt = 0;
+    __syncthreads();
+    if (in_lds) {
+        for (unsigned i = tid; i < ncand; i += NT)
+            if (cand[i] <= kth) sel[atomicAdd(&cnt, 1u)] = cand[i];
+    } else {
+        each_row([&](uint64_t k) {
+            if (k <= kth) sel[atomicAdd(&cnt, 1u)] = k;
+        });
+    }
+    __syncthreads();
+    for (unsigned i = tid; i < (unsigned)nprobe; i += NT) {
         if (i >= need) {
             probes[(size_t)q * nprobe + i] = -1;
         } else {
@@ -138,15 +184,30 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     const int q = blockIdx.x;
     const int tid = threadIdx.x;
     const int B = m / 2;
-    if (tid == 0) {
-        long long run = 0;
-        for (int p = 0; p < nprobe; ++p) {
-            const int cell = probes[(size_t)q * nprobe + p];
-            start[p] = run;
-            lo[p] = cell >= 0 ? list_off[cell] : 0;
-            run += cell >= 0 ? (list_off[cell + 1] - list_off[cell]) : 0;
+    // list lengths one thread per probe, exclusive prefix sum
+    __shared__ unsigned long long wsum[256 / WAVE];
+    unsigned long long len = 0;
+    if (tid < nprobe) {
+        const int cell = probes[(size_t)q * nprobe + tid];
+        long long l = 0, h = 0;
+        if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
+        lo[tid] = l;
+        len = (unsigned long long)(h - l);
+    }
+    {
+        const int l = lane_id();
+        unsigned long long inc = len;
+#pragma unroll
+        for (int dd = 1; dd < WAVE; dd <<= 1) {
+            const unsigned long long up = __shfl_up(inc, dd);
+            if (l >= dd) inc += up;
         }
-        start[nprobe] = run;
+        if (l == WAVE - 1) wsum[tid / WAVE] = inc;
+        __syncthreads();
+        unsigned long long before = 0;
+        for (int wv = 0; wv < tid / WAVE; ++wv) before += wsum[wv];
+        if (tid < nprobe) start[tid] = (long long)(before + inc - len);
+        if (tid == nprobe - 1) start[nprobe] = (long long)(before + inc);
     }
     __syncthreads();
     const long long total = start[nprobe];
@@ -174,6 +235,78 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     if (tid == 0) qmax[q] = ord2f(kth);
 }
 
+// ------------------------------------------------------------------- Seed
+//
+// A bound for the scan: the quantized sums (Alg. 2) of a sample of the query's codes -- the
+// first `per_list` codes of every probed list -- are histogrammed by one workgroup per query;
+// the bin where the running count reaches R bounds the query's R-th smallest sum from above.
+// It is left in the first word of the query's control block as bound + 1 (0: no bound).
+// The sample uses the 16-entry tables directly (two lookups per code byte): building pair
+// tables for every cell would cost more than the sample itself.
+constexpr int IVF_SEED_NT = 1024;
+constexpr int IVF_SEED_PCH = 32;  // probed cells whose tables are in LDS at a time
+
+template <int B>
+__global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
+    const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes,
+    const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
+    int R, int per_list, char *__restrict__ ws, size_t ws_stride)
+{
+    constexpr int NT = IVF_SEED_NT;
+    constexpr int TAB = 2 * B * 16;  // bytes of one cell's quantized tables
+    __shared__ __attribute__((aligned(16))) uint8_t tab[IVF_SEED_PCH * TAB];
+    __shared__ long long lo[IVF_MAX_NPROBE];
+    __shared__ int len[IVF_MAX_NPROBE];
+    __shared__ unsigned hist[256];
+    const int tid = threadIdx.x;
+    const int q = blockIdx.x;
+    const unsigned cap = (unsigned)cap_i;
+    if (tid < nprobe) {
+        const int cell = probes[(size_t)q * nprobe + tid];
+        long long l = 0, h = 0;
+        if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
+        lo[tid] = l;
+        len[tid] = (int)min((long long)per_list, h - l);
+    }
+    for (int e = tid; e < 256; e += NT) hist[e] = 0;
+    for (int p0 = 0; p0 < nprobe; p0 += IVF_SEED_PCH) {  // uniform
+        const int np = min(IVF_SEED_PCH, nprobe - p0);
+        __syncthreads();  // geometry and histogram ready; nobody still reads the previous tables
+        const unsigned *src = reinterpret_cast<const unsigned *>(qluts + ((size_t)q * nprobe + p0) * TAB);
+        for (int e = tid; e < np * (TAB / 4); e += NT) reinterpret_cast<unsigned *>(tab)[e] = src[e];
+        __syncthreads();
+        for (int i = tid; i < np * per_list; i += NT) {
+            const int pp = i / per_list, c = i - pp * per_list;
+            if (c >= len[p0 + pp]) continue;
+            const unsigned *cw = reinterpret_cast<const unsigned *>(codes + (size_t)(lo[p0 + pp] + c) * B);
+            const uint8_t *t = tab + pp * TAB;
+            unsigned sum = 0;
+#pragma unroll
+            for (int k = 0; k < B / 4; ++k) {
+                const unsigned x = cw[k];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const unsigned v = (x >> (8 * b)) & 0xffu;
+                    const int jb = 4 * k + b;
+                    sum += (unsigned)t[(2 * jb) * 16 + (v & 15u)] + (unsigned)t[(2 * jb + 1) * 16 + (v >> 4)];
+                }
+            }
+            if (sum < cap) atomicAdd(&hist[sum], 1u);  // saturated sums carry no information
+        }
+    }
+    __syncthreads();
+    if (tid < WAVE) {
+        unsigned h[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) h[b] = hist[4 * tid + b];
+        const unsigned t = wave_threshold_bin<4>(h, (unsigned)R);
+        if (tid == 0) {
+            ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+            hdr->ghist[0][0] = (t < 256u) ? t + 1u : 0u;
+        }
+    }
+}
+
 // ------------------------------------------------------------------- Scan
 
 struct IvfShared {
@@ -181,6 +314,8 @@ struct IvfShared {
     unsigned ccnt;
     unsigned tcnt[3];
     unsigned tau;
+    unsigned fcnt;                         // append counter of the barrier-free pass
+    unsigned long long wsum[IVF_NT / WAVE];  // unit counts of the wavefronts (prefix sum)
     long long ustart[IVF_MAX_NPROBE + 1];  // units before probe p
     long long a0[IVF_MAX_NPROBE];          // list start rounded down to 16 codes
     long long lo[IVF_MAX_NPROBE];
@@ -197,6 +332,7 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     using C = ScanCfg<B, NT>;
     constexpr long long UNIT = (long long)IVF_UNIT_TILES * C::TILE;
     __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
+    __shared__ __attribute__((aligned(16))) uint8_t qlut_s[2 * B * 16];
     __shared__ uint64_t keys[C::CAP];
     __shared__ IvfShared sh;
 
@@ -205,22 +341,38 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     const int g = blockIdx.x;
     const int W = gridDim.x;
     const unsigned cap = (unsigned)cap_i;
+    // bound + 1 left by the seed kernel (uniform load), 0 when there is none
+    const unsigned tau1 = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ghist[0][0];
 
-    if (tid == 0) {
-        long long run = 0;
-        for (int p = 0; p < nprobe; ++p) {
-            const int cell = probes[(size_t)q * nprobe + p];
-            long long l = 0, h = 0;
-            if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
-            const long long a = l / 16 * 16;
-            sh.ustart[p] = run;
-            sh.lo[p] = l;
-            sh.hi[p] = h;
-            sh.a0[p] = a;
-            run += (h > l) ? (h - a + UNIT - 1) / UNIT : 0;
+    // Geometry of the probed lists, one thread per probe, then an exclusive prefix sum of the
+    // unit counts.
+    static_assert(IVF_MAX_NPROBE <= NT, "one thread per probe");
+    unsigned long long my_units = 0;
+    if (tid < nprobe) {
+        const int cell = probes[(size_t)q * nprobe + tid];
+        long long l = 0, h = 0;
+        if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
+        const long long a = l / 16 * 16;
+        sh.lo[tid] = l;
+        sh.hi[tid] = h;
+        sh.a0[tid] = a;
+        my_units = (h > l) ? (unsigned long long)((h - a + UNIT - 1) / UNIT) : 0ull;
+    }
+    {
+        const int l = lane_id();
+        unsigned long long inc = my_units;
+#pragma unroll
+        for (int dd = 1; dd < WAVE; dd <<= 1) {
+            const unsigned long long up = __shfl_up(inc, dd);
+            if (l >= dd) inc += up;
         }
-        sh.ustart[nprobe] = run;
-        sh.tcnt[0] = 0;
+        if (l == WAVE - 1) sh.wsum[tid / WAVE] = inc;
+        __syncthreads();
+        unsigned long long before = 0;
+        for (int wv = 0; wv < tid / WAVE; ++wv) before += sh.wsum[wv];
+        if (tid < nprobe) sh.ustart[tid] = (long long)(before + inc - my_units);
+        if (tid == nprobe - 1) sh.ustart[nprobe] = (long long)(before + inc);
+        if (tid == 0) { sh.tcnt[0] = 0; sh.fcnt = 0; }
     }
     for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
     __syncthreads();
@@ -231,31 +383,110 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     int rot = 0;
     int cur_p = -1;
     bool first_tile = true;
+    const long long ub = units * g / W, ue = units * (g + 1) / W;
 
-    for (long long u = g; u < units; u += W) {  // uniform
-        int p = 0;
-        {   // the probe this unit belongs to (binary search, same result in every thread)
-            int lo_p = 0, hi_p = nprobe;
-            while (hi_p - lo_p > 1) {
-                const int mid = (lo_p + hi_p) >> 1;
-                if (sh.ustart[mid] <= u) lo_p = mid; else hi_p = mid;
-            }
-            p = lo_p;
+    // probe of unit u (binary search, same result in every thread)
+    auto probe_of = [&](long long u) {
+        int lo_p = 0, hi_p = nprobe;
+        while (hi_p - lo_p > 1) {
+            const int mid = (lo_p + hi_p) >> 1;
+            if (sh.ustart[mid] <= u) lo_p = mid; else hi_p = mid;
         }
-        if (p != cur_p) {
-            __syncthreads();  // nobody still reads the previous pair tables
-            {
-                const uint8_t *qlut = qluts + ((size_t)q * nprobe + p) * (2 * B) * 16;
-                for (int e = tid; e < B * 256; e += NT) {
-                    const int jb = e >> 8, v = e & 255;
-                    const unsigned s = (unsigned)qlut[(2 * jb) * 16 + (v & 15)] +
-                                       (unsigned)qlut[(2 * jb + 1) * 16 + (v >> 4)];
-                    ptab[e] = (uint8_t)min(s, cap);
+        return lo_p;
+    };
+    // pair tables of probe p (called by the whole workgroup)
+    auto load_tables = [&](int p) {
+        __syncthreads();  // nobody still reads the previous pair tables
+        const uint8_t *qlut = qluts + ((size_t)q * nprobe + p) * (2 * B) * 16;
+        for (int e = tid; e < 2 * B * 4; e += NT)
+            reinterpret_cast<unsigned *>(qlut_s)[e] = reinterpret_cast<const unsigned *>(qlut)[e];
+        __syncthreads();
+        for (int e = tid; e < B * 256; e += NT) {
+            const int jb = e >> 8, v = e & 255;
+            const unsigned s = (unsigned)qlut_s[(2 * jb) * 16 + (v & 15)] +
+                               (unsigned)qlut_s[(2 * jb + 1) * 16 + (v >> 4)];
+            ptab[e] = (uint8_t)min(s, cap);
+        }
+        __syncthreads();
+    };
+
+    // With a bound: no barrier inside a unit.  The bound is below the saturation value, so a
+    // sum that passes needs no clamp; the append code only runs in waves with a hit.  After
+    // each unit the list is looked at: the nearest cells hold most of a query's candidates, so
+    // the workgroups that scan them cut their list back to its R smallest keys (which tightens
+    // their own bound) whenever it grows.  Should the list overflow inside a unit, everything
+    // is redone by the careful pass below.
+    bool careful = true;
+    if (tau1 != 0u) {
+        careful = false;
+        lim = (uint64_t)tau1 << 32;  // keys with sum <= bound
+        for (long long u = ub; u < ue; ++u) {  // uniform
+            const int p = probe_of(u);
+            if (p != cur_p) { load_tables(p); cur_p = p; }
+            const long long lo = sh.lo[p], hi = sh.hi[p];
+            const long long u0 = sh.a0[p] + (u - sh.ustart[p]) * UNIT;
+            const long long u1 = min(hi, u0 + UNIT);
+            for (long long t0 = u0; t0 < u1; t0 += C::TILE) {
+                uint4 w[2];
+                int nc[2];
+                tile_load<B, NT>(codes, t0, n_total, w, nc);
+                uint64_t k[C::CPT];
+                if constexpr (B <= 16) {
+                    constexpr int CPV = 16 / B;
+#pragma unroll
+                    for (int v = 0; v < 2; ++v) {
+#pragma unroll
+                        for (int c = 0; c < CPV; ++c) {
+                            unsigned s = 0;
+#pragma unroll
+                            for (int jb = 0; jb < B; ++jb) s += ptab[jb * 256 + byte_of(w[v], c * B + jb)];
+                            const long long pos = t0 + (long long)((v * NT + tid) * CPV + c);
+                            const bool valid = (c < nc[v]) && pos >= lo && pos < u1;
+                            k[v * CPV + c] = valid ? (((uint64_t)s << 32) | (uint64_t)pos) : ~0ull;
+                        }
+                    }
+                } else {
+                    unsigned s = 0;
+#pragma unroll
+                    for (int jb = 0; jb < 32; ++jb) s += ptab[jb * 256 + byte_of(w[jb >> 4], jb & 15)];
+                    const long long pos = t0 + tid;
+                    const bool valid = nc[0] && pos >= lo && pos < u1;
+                    k[0] = valid ? (((uint64_t)s << 32) | (uint64_t)pos) : ~0ull;
+                }
+                uint64_t best = k[0];
+#pragma unroll
+                for (int c = 1; c < C::CPT; ++c) best = min(best, k[c]);
+                if (__ballot(best < lim) != 0ull) {
+#pragma unroll
+                    for (int c = 0; c < C::CPT; ++c) {
+                        const bool pass = k[c] < lim;
+                        const unsigned slot = wave_append_slot(pass, &sh.fcnt);
+                        if (pass && slot < (unsigned)C::CAP) keys[slot] = k[c];
+                    }
                 }
             }
             __syncthreads();
-            cur_p = p;
+            have = sh.fcnt;
+            __syncthreads();  // everybody has read the count before the next unit bumps it
+            if (have > (unsigned)C::CAP) { careful = true; break; }  // uniform: keys were dropped
+            if (have > (unsigned)SCAN_SLACK / 2) {
+                const uint64_t kth = compact_candidates<uint64_t, 5, NT, C::CAP>(
+                    keys, have, (unsigned)R, &sh.sel, &sh.ccnt);
+                lim = min(lim, kth + 1ull);
+                have = (unsigned)R;
+                if (tid == 0) sh.fcnt = (unsigned)R;
+                __syncthreads();
+            }
         }
+        if (careful) { have = 0; cur_p = -1; lim = ~0ull; }
+    }
+
+    // Careful pass.  Workgroup g takes a contiguous range of the query's units: consecutive
+    // units mostly belong to the same list, so the pair tables are rebuilt only when the list
+    // changes.
+    for (long long u = ub; careful && u < ue; ++u) {  // uniform
+        const int p = probe_of(u);
+        if (p != cur_p) { load_tables(p); cur_p = p; }
         const long long lo = sh.lo[p], hi = sh.hi[p];
         const long long u0 = sh.a0[p] + (u - sh.ustart[p]) * UNIT;
         const long long u1 = min(hi, u0 + UNIT);
@@ -332,11 +563,16 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
                 first_tile = false;
             }
 
+            uint64_t best = k[0];
 #pragma unroll
-            for (int c = 0; c < C::CPT; ++c) {
-                const bool pass = k[c] < lim;
-                const unsigned slot = have + wave_append_slot(pass, ctr);
-                if (pass) keys[slot] = k[c];
+            for (int c = 1; c < C::CPT; ++c) best = min(best, k[c]);
+            if (__ballot(best < lim) != 0ull) {  // the append code only runs in waves with a hit
+#pragma unroll
+                for (int c = 0; c < C::CPT; ++c) {
+                    const bool pass = k[c] < lim;
+                    const unsigned slot = have + wave_append_slot(pass, ctr);
+                    if (pass) keys[slot] = k[c];
+                }
             }
             __syncthreads();
             have += *ctr;
@@ -379,6 +615,7 @@ int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const 
 
 struct IvfPlan {
     int qb, W;
+    int seed_per_list;  // codes sampled per probed list for the bound of the scan (0: no seed kernel)
     ScanLayout l;
     size_t off_dist, off_probes, off_luts, off_qluts, off_qmax, off_scan, bytes;
 };
@@ -390,6 +627,11 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     if (ix->d < ix->m || ix->d % ix->m || ix->K < 1 || ix->n < 0 || ix->n > 0xfffffffell) return false;
     p->W = env_int("QADC_IVF_WGS", 64);
     if (p->W < 1) p->W = 1;
+    // about 1/16 of an average list, between 64 and 1024 codes
+    int64_t spl = ix->n / ix->K / 16;
+    if (spl < 64) spl = 64;
+    if (spl > 1024) spl = 1024;
+    p->seed_per_list = env_int("QADC_IVF_SEED", 1) ? (int)spl : 0;
     p->l = scan_layout(p->W, R);
     const size_t per_q = align_up((size_t)ix->K * 4, 256) + align_up((size_t)nprobe * 4, 256) +
                          align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
@@ -461,7 +703,7 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             dim3 grid((unsigned)ceil_div(K, 256), (unsigned)ceil_div(nb, IVF_QT));
             launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel, grid, dim3(256),
                    (size_t)IVF_QT * d * sizeof(float), st, ix->coarse, K, d, yq, nb, dist);
-            launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(nb), dim3(1024), 0, st, dist, K,
+            launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(nb), dim3(IVF_SEL_NT), 0, st, dist, K,
                    nprobe, probes);
         }
         // Tables
@@ -476,6 +718,9 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         dim3 grid(p.W, nb);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
+        if (p.seed_per_list > 0)                                                                      \
+            launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb), dim3(IVF_SEED_NT), 0, st, ix->list_off,  \
+                   ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws, p.l.stride);  \
         launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
                ix->n, probes, nprobe, qluts, nbins, R, scan_ws, p.l.stride, p.l.counts_off,           \
                p.l.lists_off);                                                                        \

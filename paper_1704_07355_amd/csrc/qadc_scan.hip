@@ -235,11 +235,14 @@ __global__ __launch_bounds__(1024) void prepare_u8_kernel(
     const int64_t c0 = (int64_t)g * seed_stride;
     const int64_t c1 = min(n, c0 + C::TILE);
 
-    // Every global load the set-up needs is issued here, before the first wait: the sample
-    // tile, the query, this thread's centroid (one table entry per thread) and init code.
-    uint4 w[2];
-    int nc[2] = {0, 0};
-    if (c0 < c1) tile_load<B, NT>(codes, c0, c1, w, nc);
+    // Every global load the set-up needs is issued here, before the first wait.  Loads come
+    // back in the order they were issued, so the small ones the tables wait for go first: the
+    // query, this thread's centroid (one table entry per thread) and init code; the sample
+    // tile (32 KiB per workgroup) follows and is in flight during the whole set-up.
+    static_assert(PREP_MAX_D <= 2 * NT, "two query components per thread");
+    float yv[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) yv[t] = (tid + t * NT < d) ? queries[(size_t)q * d + tid + t * NT] : 0.0f;
     constexpr int DREG = 16;  // sub-space dimensions held in registers
     float cv[DREG];
     const bool cv_regs = dsub <= DREG;  // uniform
@@ -254,7 +257,14 @@ __global__ __launch_bounds__(1024) void prepare_u8_kernel(
 #pragma unroll
         for (int k = 0; k < B / 4; ++k) cw[k] = c[k];
     }
-    for (int t = tid; t < d; t += NT) yq[t] = (double)queries[(size_t)q * d + t];
+    asm volatile("" ::: "memory");
+    uint4 w[2];
+    int nc[2] = {0, 0};
+    if (c0 < c1) tile_load<B, NT>(codes, c0, c1, w, nc);
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        if (tid + t * NT < d) yq[tid + t * NT] = (double)yv[t];
     __syncthreads();
 
     // Tables, Eq. (1): float64 differences and sums, one rounding

@@ -127,3 +127,71 @@ def test_ivf_all_cells_equals_flat_scan_of_the_lists(Q, O):
     pos, d = O.top_r(sums, 100, pad_dist=255)
     assert np.array_equal(idx_np(ids)[0], index["ids"][pos]) and np.array_equal(dist[0].cpu().numpy(), d)
     assert 123 in idx_np(ids)[0]
+
+
+@pytest.mark.parametrize("seed_kernel", ["1", "0"])
+def test_ivf_scan_with_and_without_the_sampled_bound(Q, O, seed_kernel, monkeypatch):
+    """The sampled bound only prunes: with it (barrier-free pass) and without it (careful pass)
+    the result is the oracle's.  Larger lists, so that workgroups walk several tiles."""
+    import torch
+    monkeypatch.setenv("QADC_IVF_SEED", seed_kernel)
+    coarse, cb, x, index = build_ivf(O, n=400_000, K=12, m=32, seed=21)
+    gix = gpu_index(Q, coarse, cb, index)
+    queries = (x[[7, 90_000, 399_999]] + 2.0).astype(np.float32)
+    nprobe, R, init = 6, 100, 1000
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    for iq in range(len(queries)):
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
+
+
+def test_ivf_bound_without_resolution_falls_back(Q, O):
+    """Every stored code identical: all sums tie, the sampled bound lets everything through, the
+    barrier-free list overflows and the careful pass decides by storage position."""
+    import torch
+    coarse, cb, x, index = build_ivf(O, n=120_000, K=6, m=16, seed=4)
+    index = dict(index)
+    index["codes"] = np.full_like(index["codes"], 0x21)
+    gix = gpu_index(Q, coarse, cb, index)
+    queries = x[[5, 60_000]].astype(np.float32)
+    nprobe, R, init = 3, 100, 200
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    for iq in range(len(queries)):
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
+
+
+def test_ivf_probe_selection_many_cells_with_exact_ties(Q, O):
+    """Index step with more cells than selection threads and every centroid stored twice: equal
+    distances are ordered by cell id, a pair cut by the nprobe boundary keeps its lower id."""
+    import torch
+    rng = np.random.default_rng(17)
+    K, d, m, nprobe = 3000, 32, 8, 65
+    coarse = rng.uniform(0, 255, size=(K, d)).astype(np.float32)
+    coarse[K // 2:] = coarse[:K // 2]
+    cb = rng.uniform(-20, 20, size=(m, 16, d // m)).astype(np.float32)
+    list_off = np.arange(K + 1, dtype=np.int64) * 2
+    codes = rng.integers(0, 256, size=(2 * K, m // 2), dtype=np.uint8)
+    index = dict(list_off=list_off, codes=codes, ids=np.arange(2 * K, dtype=np.uint32))
+    gix = gpu_index(Q, coarse, cb, index)
+    queries = rng.uniform(0, 255, size=(5, d)).astype(np.float32)
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, 50, 100, debug=True)
+    torch.cuda.synchronize()
+    probes = probes.cpu().numpy()
+    for iq in range(len(queries)):
+        want = O.ivf_probes(queries[iq], coarse, nprobe)
+        got = probes[iq]
+        if not np.array_equal(got, want):
+            dq = O.sq_l2(queries[iq][None], coarse)[0]
+            np.testing.assert_allclose(dq[got], dq[want], rtol=1e-5)
+        assert len(set(got.tolist())) == nprobe
+        where = {int(c): i for i, c in enumerate(got)}
+        for c, i in where.items():
+            if c >= K // 2:   # the twin with the lower id comes right before
+                assert where.get(c - K // 2) == i - 1, (iq, c)
