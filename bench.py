@@ -217,6 +217,32 @@ def run_batched(args):
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
 
 
+def build_ivf_index(Q, torch, np, n, K, m, n_queries, dev, d=128, sigma=18.0):
+    """Synthetic inverted index on the GPU (see run_ivf) -> (IvfIndex, list sizes, queries)."""
+    from workloads import MixtureSpec, SEED_BASE, SEED_TRAIN, zipf_list_sizes, kmeans_init_rows
+    from workloads.mixture_torch import mixture_vectors_torch
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED_BASE * 7919 + 11)
+    coarse = mixture_vectors_torch(MixtureSpec(d=d), SEED_TRAIN, 0, K, dev)
+    sizes = zipf_list_sizes(n, K, 0.8, SEED_BASE)
+    list_off = torch.from_numpy(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)).to(dev)
+    train = sigma * torch.randn((20_000, d), generator=gen, device=dev)
+    cb = Q.qadc_pq_train(train.contiguous(), m, 16, torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev), 10)
+    codes = torch.empty((n, m // 2), dtype=torch.uint8, device=dev)
+    chunk = 1 << 22
+    for s in range(0, n, chunk):
+        cnt = min(chunk, n - s)
+        x = sigma * torch.randn((cnt, d), generator=gen, device=dev)
+        Q.qadc_pq_encode(cb, x, out=codes[s:s + cnt])
+    ids = torch.arange(n, dtype=torch.int32, device=dev)
+    index = Q.IvfIndex(coarse, list_off, codes, ids, cb)
+    prob = torch.from_numpy(sizes / sizes.sum()).to(dev)
+    home = torch.multinomial(prob, n_queries, replacement=True, generator=gen)
+    queries = (coarse[home] + sigma * torch.randn((n_queries, d), generator=gen, device=dev)).contiguous()
+    torch.cuda.synchronize()
+    return index, sizes, queries
+
+
 def run_ivf(args):
     """Config 4: IVF + Quick ADC.  A step = one batch of queries through qadc_ivf_search.
 
@@ -233,29 +259,11 @@ def run_ivf(args):
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    d, m, n, K, R, init, nprobe, nb = 128, args.m, args.n, args.K, args.R, args.init, args.nprobe, args.batch
-    sigma = 18.0
+    m, n, K, R, init, nprobe, nb = args.m, args.n, args.K, args.R, args.init, args.nprobe, args.batch
     t0 = time.time()
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(SEED_BASE * 7919 + 11)
-    coarse = mixture_vectors_torch(MixtureSpec(d=d), SEED_TRAIN, 0, K, dev)
-    sizes = zipf_list_sizes(n, K, 0.8, SEED_BASE)
-    list_off = torch.from_numpy(np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)).to(dev)
-    train = sigma * torch.randn((20_000, d), generator=gen, device=dev)
-    cb = Q.qadc_pq_train(train.contiguous(), m, 16, torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev), 10)
-    codes = torch.empty((n, m // 2), dtype=torch.uint8, device=dev)
-    chunk = 1 << 22
-    for s in range(0, n, chunk):
-        cnt = min(chunk, n - s)
-        x = sigma * torch.randn((cnt, d), generator=gen, device=dev)
-        Q.qadc_pq_encode(cb, x, out=codes[s:s + cnt])
-    ids = torch.arange(n, dtype=torch.int32, device=dev)
-    index = Q.IvfIndex(coarse, list_off, codes, ids, cb)
     nq_total = nb * (args.steps + args.warmup)
-    prob = torch.from_numpy(sizes / sizes.sum()).to(dev)
-    home = torch.multinomial(prob, nq_total, replacement=True, generator=gen)
-    queries = (coarse[home] + sigma * torch.randn((nq_total, d), generator=gen, device=dev)).contiguous()
-    torch.cuda.synchronize()
+    index, sizes, queries = build_ivf_index(Q, torch, np, n, K, m, nq_total, dev)
+    coarse, list_off, codes, _, cb = index.tensors
     t_build = time.time() - t0
 
     ws = Q.qadc_workspace_init(torch.empty(Q.qadc_ivf_workspace_bytes(index, nb, nprobe, R),
