@@ -733,9 +733,10 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         }
 #undef QADC_IVF_CASE
         uint32_t *oi = out_ids + (size_t)q0 * R;
-        launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, scan_ws,
-               p.l.stride, p.l.counts_off, p.l.lists_off, p.W, (unsigned)R, R, (uint8_t)nbins, oi,
-               out_dist + (size_t)q0 * R, (size_t)0, (size_t)0, 0, 0, (unsigned *)nullptr);
+        rc = launch_merge<uint8_t, 5>(nb, st, scan_ws, p.l.stride, p.l.counts_off, p.l.lists_off, p.W,
+                                      (unsigned)R, R, (uint8_t)nbins, oi, out_dist + (size_t)q0 * R, (size_t)0,
+                                      (size_t)0, 0, 0, (unsigned *)nullptr);
+        if (rc != QADC_OK) return rc;
         const int64_t total = (int64_t)nb * R;
         launch(QADC_PROF_MERGE, ivf_gather_ids_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0,
                st, ix->ids, oi, total);

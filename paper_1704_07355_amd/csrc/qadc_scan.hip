@@ -778,10 +778,9 @@ static int scan_and_merge_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
     if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);
     else if (p.NT == 512) dispatch_scan_u8<512>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);
     else dispatch_scan_u8<256>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);
-    launch(QADC_PROF_MERGE, (merge_topk_kernel<uint8_t, 5>), dim3(nb), dim3(MERGE_NT), 0, st, ws, p.stride,
-           p.counts_off, p.lists_off, p.G, (unsigned)min((int64_t)R, n), R, (uint8_t)nbins, out_idx,
-           out_dist, p.countsA_off, p.listsA_off, flags ? p.t.GC : 0, (int)TILED_LCAP, flags);
-    return QADC_OK;
+    return launch_merge<uint8_t, 5>(nb, st, ws, p.stride, p.counts_off, p.lists_off, p.G,
+                                    (unsigned)min((int64_t)R, n), R, (uint8_t)nbins, out_idx, out_dist,
+                                    p.countsA_off, p.listsA_off, flags ? p.t.GC : 0, (int)TILED_LCAP, flags);
 }
 
 int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, int nq, int R,

@@ -176,7 +176,7 @@ __device__ __forceinline__ float ord2f(unsigned o)
 // ---------------------------------------------------------------- merge
 
 constexpr int MERGE_NT = 1024;
-constexpr int MERGE_CAP = 4096;   // keys staged in LDS
+constexpr int MERGE_CAP = 6144;   // keys staged in LDS
 constexpr int MERGE_WG_PER_THREAD = 8;
 
 // R best of the keys reported by the G workgroups of each query (64-bit keys
@@ -184,10 +184,10 @@ constexpr int MERGE_WG_PER_THREAD = 8;
 // in the workspace is cleared.  KBYTES = significant key bytes (5 for u8 distances).
 // DistT = uint8_t: the distance is the key's bits 32..39; float: bits 32..63 (ordered image).
 //
-// Usual case (a few hundred keys in all): one histogram pass over the most significant key
-// byte finds the bin of the R-th key; the keys up to that bin are ranked against each other
-// by counting, which selects and orders in one step.  Massive ties fall back to the full
-// radix select.
+// Usual case (a few hundred to a few thousand keys in all): the keys are gathered in LDS; one
+// histogram pass over the eight most significant bits in which they differ at all finds the
+// bin of the R-th key; the keys up to that bin are ranked against each other by counting,
+// which selects and orders in one step.  Massive ties fall back to the full radix select.
 // Two report regions may exist per query: region B (G workgroups, up to R keys each) written
 // by the single-query kernels, and region A (GA workgroups, up to pitchA keys each) written
 // by the query-tiled kernel.  flags[q] != 0 says that region A of query q is incomplete and
@@ -204,6 +204,7 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     __shared__ uint64_t cand[MERGE_NT];
     __shared__ SelectScratch sc;
     __shared__ unsigned lcnt, ccnt;
+    __shared__ unsigned long long all_or, all_and;
 
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
@@ -218,8 +219,6 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         G = GA;
         pitch = pitchA;
     }
-    constexpr int TOP = (KBYTES - 1) * 8;
-
     // every reported key, spread over the threads by workgroup
     auto each_key = [&](auto f) {
         for (int g = tid; g < G; g += MERGE_NT) {
@@ -236,41 +235,71 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         }
     };
 
-    // Gather.  Counts and the first key of every region are fetched together (most regions
-    // hold zero or one key), further keys in a second round.
-    if (tid == 0) { lcnt = 0; ccnt = 0; }
+    // Gather, region by region.
+    if (tid == 0) { lcnt = 0; ccnt = 0; all_or = 0ull; all_and = ~0ull; }
     for (int i = tid; i < 256; i += MERGE_NT) sc.hist[i] = 0;
     __syncthreads();
+    // Histogram bits.  Integer distances: the distance byte itself, counted while gathering.
+    // Float distances: the eight most significant bits in which the keys differ at all (the
+    // bits above them agree), found from the OR and the AND of all keys, counted afterwards.
+    constexpr bool ADAPT = sizeof(DistT) != 1;
+    unsigned long long my_or = 0ull, my_and = ~0ull;
+    auto take = [&](uint64_t k) {
+        const unsigned slot = atomicAdd(&lcnt, 1u);
+        if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
+        if constexpr (ADAPT) {
+            my_or |= k;
+            my_and &= k;
+        } else {
+            atomicAdd(&sc.hist[(unsigned)(k >> 32) & 255u], 1u);
+        }
+    };
     unsigned mycnt[MERGE_WG_PER_THREAD];
 #pragma unroll
     for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
         const int g = tid + t * MERGE_NT;
         mycnt[t] = 0;
         if (g < G) {
+            // count and first key fetched together: most regions hold zero or one key
             const unsigned c = min(counts[g], (unsigned)pitch);
-            const uint64_t k0 = lists[(size_t)g * pitch];
+            const uint64_t *l = lists + (size_t)g * pitch;
+            const uint64_t k0 = l[0];
             mycnt[t] = c;
-            for (unsigned i = 0; i < c; ++i) {
-                const uint64_t k = i ? lists[(size_t)g * pitch + i] : k0;
-                const unsigned slot = atomicAdd(&lcnt, 1u);
-                if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
-                atomicAdd(&sc.hist[(unsigned)(k >> TOP) & 255u], 1u);
+            if (c) take(k0);
+            for (unsigned i = 1; i < c; i += 4) {  // four loads in flight
+                uint64_t k[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) k[u] = (i + u < c) ? l[i + u] : 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i + u < c) take(k[u]);
             }
         }
     }
     for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {  // very wide grids
         const unsigned c = min(counts[g], (unsigned)pitch);
-        for (unsigned i = 0; i < c; ++i) {
-            const uint64_t k = lists[(size_t)g * pitch + i];
-            const unsigned slot = atomicAdd(&lcnt, 1u);
-            if (slot < (unsigned)MERGE_CAP) lkeys[slot] = k;
-            atomicAdd(&sc.hist[(unsigned)(k >> TOP) & 255u], 1u);
+        for (unsigned i = 0; i < c; ++i) take(lists[(size_t)g * pitch + i]);
+    }
+    if constexpr (ADAPT) {
+        if (my_or != 0ull || my_and != ~0ull) {
+            atomicOr(&all_or, my_or);
+            atomicAnd(&all_and, my_and);
         }
     }
     __syncthreads();
     const unsigned total = lcnt;
     need = min(need, total);
     const bool in_lds = total <= (unsigned)MERGE_CAP;
+    int TOP = 32;
+    if constexpr (ADAPT) {
+        const unsigned long long diff = all_or ^ all_and;
+        const int top = diff ? 63 - __clzll((long long)diff) : 7;
+        TOP = top > 7 ? top - 7 : 0;
+        if (in_lds)
+            for (unsigned i = tid; i < total; i += MERGE_NT)
+                atomicAdd(&sc.hist[(unsigned)(lkeys[i] >> TOP) & 255u], 1u);
+        __syncthreads();
+    }
 
     bool done = false;
     if (need > 0 && in_lds) {
@@ -378,6 +407,15 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     }
     unsigned *z = reinterpret_cast<unsigned *>(hdr);
     for (int i = tid; i < (int)(sizeof(ScanHeader) / 4); i += MERGE_NT) z[i] = 0;
+}
+
+// One merge workgroup per query.
+template <typename DistT, int KBYTES, typename... Args>
+inline int launch_merge(int nq, hipStream_t st, Args... args)
+{
+    launch(QADC_PROF_MERGE, (merge_topk_kernel<DistT, KBYTES>), dim3(nq), dim3(MERGE_NT), 0, st,
+           args...);
+    return QADC_OK;
 }
 
 // Workspace layout of one scan call: per query a ScanHeader, counts[G], lists[G][R].

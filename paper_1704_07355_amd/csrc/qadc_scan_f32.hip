@@ -431,10 +431,11 @@ int scan_topk_f32(int variant, const uint8_t *codes, int64_t n, int m, const flo
         const float *lq = luts + (size_t)q0 * M * p.KSUB;
         if (p.KSUB == 16) dispatch_f32<16>(p, codes, n, lq, nb, R, ws, st);
         else dispatch_f32<256>(p, codes, n, lq, nb, R, ws, st);
-        launch(QADC_PROF_MERGE, (merge_topk_kernel<float, 8>), dim3(nb), dim3(MERGE_NT), 0, st, ws,
-               p.l.stride, p.l.counts_off, p.l.lists_off, p.G, (unsigned)min((int64_t)R, n), R,
-               __builtin_inff(), out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R, (size_t)0, (size_t)0, 0,
-               0, (unsigned *)nullptr);
+        const int rc = launch_merge<float, 8>(nb, st, ws, p.l.stride, p.l.counts_off, p.l.lists_off, p.G,
+                                              (unsigned)min((int64_t)R, n), R, __builtin_inff(),
+                                              out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R, (size_t)0,
+                                              (size_t)0, 0, 0, (unsigned *)nullptr);
+        if (rc != QADC_OK) return rc;
     }
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
