@@ -264,12 +264,19 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_kernel(
             tile_load<ROW, NT>(codes, t0, n, w, nc);
             float d[C::CPT];
             tile_dists<KSUB, ROW, NT>(w, lut, d);
+            bool pass[C::CPT], any = false;
 #pragma unroll
             for (int c = 0; c < C::CPT; ++c) {
-                const bool pass = slot_valid<ROW, NT>(nc, c) && f32_bin(d[c], r) <= tau;
-                const unsigned slot = wave_append_slot(pass, &sh.fcnt);
-                if (pass && slot < (unsigned)C::CAP)
-                    keys[slot] = ((uint64_t)f2ord(d[c]) << 32) | (rel + slot_index<ROW, NT>(c));
+                pass[c] = slot_valid<ROW, NT>(nc, c) && f32_bin(d[c], r) <= tau;
+                any = any || pass[c];
+            }
+            if (__ballot(any) != 0ull) {  // the append code only runs in waves with a hit
+#pragma unroll
+                for (int c = 0; c < C::CPT; ++c) {
+                    const unsigned slot = wave_append_slot(pass[c], &sh.fcnt);
+                    if (pass[c] && slot < (unsigned)C::CAP)
+                        keys[slot] = ((uint64_t)f2ord(d[c]) << 32) | (rel + slot_index<ROW, NT>(c));
+                }
             }
         }
         __syncthreads();
