@@ -128,7 +128,7 @@ def accuracy(Q, torch, np, cb, codes, raw, queries, R, init):
 # HBM bytes per scan_u8_kernel launch from the FETCH_SIZE / WRITE_SIZE counter runs summarized in
 # profiles/scan_u8_config2_hbm_traffic.md (scaled by a plain copy of known size); valid for the
 # workload it was measured on only: (n, m) -> (bytes read, bytes written).
-SCAN_TRAFFIC = {(10_000_000, 16): (39150.9 * 1.9994 * 1024, 53.1 * 1.0 * 1024)}
+SCAN_TRAFFIC = {(10_000_000, 16): (39141.8 * 1.9994 * 1024, 53.1 * 1.0 * 1024)}
 
 ALU_PEAK_TLOOKUPS = 157.3  # 256 CUs x 64 lanes x 2.4 GHz x 4 byte lanes per 32-bit lane-op
 
