@@ -1,31 +1,29 @@
-// Scan step + top-R of Quick ADC on gfx950 (Alg. 2 of the paper).
+// Scan step + top-R of Quick ADC on gfx950 (Alg. 2 of the paper), one query per launch row.
 //
 // Data flow of one query:
-//   codes (HBM, standard layout, streamed once, 16 B per lane per load, next tile
-//   prefetched into registers while the current one is processed)
+//   codes (HBM, standard layout, streamed once, 16 B per lane per load; workgroup g of G takes
+//   tiles g, g+G, ...)
 //     -> per code: one LDS lookup per code BYTE in a 256-entry "pair table"
-//        ptab[jb][v] = min(cap, q[2jb][v & 15] + q[2jb+1][v >> 4]), summed and
-//        clamped once at `cap`.  Entries are non-negative, so this equals the
-//        chain of saturating adds of Alg. 2 (mask 0x0f, lookup, add, shift).
-//     -> key = sum << 24 | (index inside the workgroup's chunk).
+//        ptab[jb][v] = min(cap, q[2jb][v & 15] + q[2jb+1][v >> 4]), summed and clamped once at
+//        `cap`.  Entries are non-negative, so this equals the chain of saturating adds of
+//        Alg. 2 (mask 0x0f, lookup, add, shift).
+//     -> key = sum << 24 | (index among the workgroup's own codes).
 //   Selection never stores more than a few hundred keys per workgroup:
-//     * the first ("seed") tile of a workgroup is histogrammed by sum; the bin
-//       tau_w holding its R-th smallest sum bounds the R-th smallest sum of the
-//       chunk, and only keys with sum <= tau_w are appended to the workgroup's LDS
-//       candidate list (one LDS atomic per wavefront);
-//     * the seed counts of bins <= tau_w are also added to a grid-wide histogram
-//       (16 replicas, fire-and-forget atomics).  At its end a workgroup sums the
-//       replicas: the bin where the running count reaches R bounds the R-th
-//       smallest sum of the WHOLE database, whatever part of the other
-//       workgroups' counts has arrived, and the workgroup reports only the
-//       candidates at or below it (a handful);
-//     * should a candidate list fill up (adversarial order, massive ties), it is
-//       cut back to its R smallest keys by an exact radix select, so the result
-//       never depends on the thresholds being good, only the speed does.
-//   A second, single-workgroup kernel orders the R smallest of the reported keys
-//   (sum << 32 | index) and clears the control block for the next call.
-// The total order (sum, index) is carried by the integer keys, so the result
-// does not depend on how the grid is cut or on the order waves run in.
+//     * a seed step (seed_u8_kernel, or the fused prepare_u8_kernel of qadc_search) scans a
+//       sample of tiles spread over the database and adds the lowest bins of each sample
+//       tile's sum histogram to a per-query histogram in the workspace; the bin where its
+//       running count reaches R bounds the R-th smallest sum of the WHOLE database;
+//     * the scan kernel reads that bound once and keeps only keys at or below it in an LDS
+//       list (one LDS atomic per wavefront with a hit, no barrier in the streaming loop);
+//     * without a bound (small databases), or should the list overflow (adversarial order,
+//       massive ties), the workgroup runs a careful pass: one barrier per tile, a bound from
+//       its own first tile, the list cut back to its R smallest keys by an exact radix select
+//       whenever it fills -- so the result never depends on a bound being good, only the
+//       speed does.
+//   merge_topk_kernel (one workgroup per query) orders the R smallest of the reported keys
+//   (sum << 32 | index) and clears whatever the call wrote in the workspace.
+// The total order (sum, index) is carried by the integer keys, so the result does not depend
+// on how the grid is cut or on the order waves run in.
 
 #include "qadc_scan_common.h"
 #include "qadc_scan_tiled.h"

@@ -5,9 +5,11 @@
 // This is the reference the quantized scan is compared against (recall, speed).  The float
 // tables of the query sit in LDS (1 KiB for 16x4, 8 KiB for 8x8: the sizes of the paper's
 // Table 1); codes are streamed as in the quantized scan.  A candidate key is
-// order(distance) << 32 | index among the workgroup's codes; each workgroup keeps an LDS
-// list that is cut back to its R smallest keys by an exact radix select whenever it fills,
-// and reports at most R keys; the merge kernel orders the R smallest of all of them.
+// order(distance) << 32 | index among the workgroup's codes.  Large databases get a bound as
+// the quantized scan does, on a monotone 8-bit image of the distance (range kernel + seed
+// kernel), and a barrier-free pass; otherwise, or on overflow, each workgroup keeps an LDS
+// list that is cut back to its R smallest keys by an exact radix select whenever it fills.
+// A workgroup reports at most R keys; the merge kernel orders the R smallest of all of them.
 
 #include "qadc_scan_common.h"
 
