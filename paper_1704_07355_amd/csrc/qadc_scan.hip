@@ -314,28 +314,24 @@ __global__ __launch_bounds__(1024) void prepare_u8_kernel(
     const unsigned need = (unsigned)min(R, n_init);
     if (n_init <= 256) {
         // uniform: select by counting.  Thread (i, part) compares candidate i = tid & 255 with
-        // candidates 64*part .. 64*part+63, fetched four at a time, and counts how many are
-        // smaller and how many are smaller or equal; unused slots hold the largest value.  Only
-        // the VALUE of the need-th smallest is wanted: it is the value v with
-        // #(< v) < need <= #(<= v), whichever of its holders reports it.
+        // candidates 64*part .. 64*part+63, fetched four at a time, and counts the smaller ones;
+        // unused slots hold the largest value.  Only the VALUE of the need-th smallest is
+        // wanted: it is the largest candidate with fewer than `need` smaller ones.
         if (tid >= n_init && tid < 256) cand[tid] = 0xffffffffu;
+        if (tid == 0) qmax_ord = 0u;
         __syncthreads();
         const int i = tid & 255, part = tid >> 8;
         const unsigned mine = cand[i];
-        unsigned lt = 0, le = 0;
+        unsigned lt = 0;
         const uint4 *c4 = reinterpret_cast<const uint4 *>(cand) + part * 16;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const uint4 o = c4[v];
             lt += (o.x < mine) + (o.y < mine) + (o.z < mine) + (o.w < mine);
-            le += (o.x <= mine) + (o.y <= mine) + (o.z <= mine) + (o.w <= mine);
         }
-        if (i < n_init) atomicAdd(&sc.hist[i], lt | (le << 16));  // both counts fit 16 bits
+        if (i < n_init) atomicAdd(&sc.hist[i], lt);
         __syncthreads();
-        if (tid < n_init) {
-            const unsigned both = sc.hist[tid];
-            if ((both & 0xffffu) < need && need <= (both >> 16)) qmax_ord = cand[tid];
-        }
+        if (tid < n_init && sc.hist[tid] < need) atomicMax(&qmax_ord, cand[tid]);
         __syncthreads();
         if (tid < 256) sc.hist[tid] = 0;
     } else {
