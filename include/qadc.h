@@ -27,6 +27,10 @@
  *    bytes; byte j holds component 2j in its low nibble and component 2j+1 in
  *    its high nibble (the 0x0f mask and the 4-bit shift of Alg. 2).  8-bit
  *    codes (ksub = 256) are m consecutive bytes.
+ *  - Environment variables named QADC_* (QADC_SCAN_WGS, QADC_SCAN_NT, QADC_TILED,
+ *    QADC_SEED_MIN_TILES, QADC_SEED_WGS, QADC_SCAN_F32_WGS, QADC_IVF_WGS, QADC_IVF_SEED)
+ *    change launch shapes and whether a sampled bound is used -- never a result.
+ *    They are read at every call and exist for tuning and for tests.
  *  - Top-R outputs: row q holds the R best of query q, ascending under the
  *    total order (distance, index) -- lowest index first among equal
  *    distances.  When fewer than R codes exist the tail is padded with index
@@ -212,7 +216,7 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
  */
 #define QADC_PROF_SCAN   0  /* code-streaming kernel of qadc_scan_topk */
 #define QADC_PROF_MERGE  1  /* cross-workgroup top-R kernel of qadc_scan_topk */
-#define QADC_PROF_SEED   2  /* sampling kernel of qadc_scan_topk (large databases only) */
+#define QADC_PROF_SEED   2  /* kernels that sample the codes for the bound of a scan (large inputs only) */
 #define QADC_PROF_IVF_INDEX  3  /* Index step of qadc_ivf_search (coarse distances, cell choice) */
 #define QADC_PROF_IVF_TABLES 4  /* Tables step of qadc_ivf_search (tables, qmax, quantization)   */
 #define QADC_PROF_TABLES     5  /* qadc_build_luts kernel */
