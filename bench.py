@@ -184,7 +184,7 @@ def run_batched(args):
         ms_merge, _ = Q.qadc_profile_read(Q.QADC_PROF_MERGE)
         Q.qadc_profile_enable(False)
         ach = n * nb * m / (ms_scan * 1e-3) / 1e12
-        roofline = {"bound": "alu", "kernel": "scan_u8_tiled_kernel (+ redo launch)", "achieved": round(ach, 2),
+        roofline = {"bound": "alu", "kernel": "scan_u8_tiled16_kernel (+ 16-bit-lane and redo launches)", "achieved": round(ach, 2),
                     "peak": ALU_PEAK_TLOOKUPS, "unit": "T lookup-adds/s", "frac": round(ach / ALU_PEAK_TLOOKUPS, 4),
                     "traffic": None, "scan_ms": round(ms_scan, 3), "launches_timed": launches}
         kernels = {"scan_ms": round(ms_scan, 3), "tables_quantize_ms": round(ms_prep, 3),
@@ -211,7 +211,7 @@ def run_batched(args):
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": "config 3: d=128 mixture, PQ m=%d x 4-bit, N=%d codes, batches of %d queries "
-                   "through qadc_search (8 queries share each code read in a workgroup), R=%d, init=%d"
+                   "through qadc_search (16 queries share each code read in a workgroup), R=%d, init=%d"
                    % (m, n, nb, R, init), "n": n, "m": m, "R": R, "init": init, "batch": nb},
         "gcodes_per_s_per_query": round(pairs / nb / 1e9, 2),
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))

@@ -9,6 +9,9 @@
 // 32 bytes x 255 < 65536), i.e. 8 lookup-adds per LDS access.  The clamp at `cap` is applied
 // when a sum is kept.
 //
+// Groups of sixteen queries whose bounds are all small take a denser form of the same idea
+// (scan_u8_tiled16_kernel: byte lanes, sixteen queries per LDS read).
+//
 // Selection: each query's grid-wide bound (from the seed kernel's histogram) is known
 // before the scan starts; sums at or below it are appended to small per-query LDS lists.  A
 // list that overflows marks its query for the single-query kernel, which redoes that query
@@ -58,6 +61,36 @@ __global__ __launch_bounds__(256) void scan_tau_kernel(const char *__restrict__ 
     if (l == 0) taus[q] = t;
 }
 
+// Workgroup id -> (query group, database chunk).  Workgroups are handed to the 8 XCDs in turn,
+// each XCD with an L2 of its own: XCD x = id % 8 takes the chunks congruent to x, and all query
+// groups of a chunk follow each other in its share of the ids, so that the chunk is fetched
+// from HBM once and every XCD gets the same mix of groups, whichever of them are active.
+__device__ __forceinline__ void tiled_group_and_chunk(int ngroups, int &grp, int &chunk)
+{
+    const unsigned id = blockIdx.x;
+    const unsigned slot = id >> 3;
+    grp = (int)(slot % (unsigned)ngroups);
+    chunk = (int)((slot / (unsigned)ngroups) * 8u + (id & 7u));
+}
+
+constexpr int TILED16_GP = 2;                       // code bytes summed in byte lanes
+constexpr unsigned TILED16_CL = 255 / TILED16_GP;   // entries are clamped to this
+
+// Which kernel scans a group of 16 queries is decided by the largest bound in the group (see the
+// byte-lane kernel below).
+__device__ __forceinline__ unsigned tiled_group_bound(const unsigned *__restrict__ taus, int q0, int nq)
+{
+    unsigned t = 0;
+    for (int k = 0; k < 16; ++k)
+        if (q0 + k < nq) t = max(t, taus[q0 + k]);
+    return t;
+}
+// true: byte lanes (scan_u8_tiled16_kernel);  false: 16-bit lanes (scan_u8_tiled_kernel)
+__device__ __forceinline__ bool tiled_group_in_bytes(unsigned bound, unsigned cl)
+{
+    return bound < cl;
+}
+
 template <int B>
 __global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled_kernel(
     const uint8_t *__restrict__ codes, int64_t n, int64_t chunk, int nq, int cap_i,
@@ -71,12 +104,15 @@ __global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled_kernel(
     __shared__ unsigned cnt[TILED_Q];
 
     const int tid = threadIdx.x;
-    const int q0 = blockIdx.x * TILED_Q;
-    const int gc = blockIdx.y;
+    int grp, gc;
+    tiled_group_and_chunk((nq + TILED_Q - 1) / TILED_Q, grp, gc);
+    const int q0 = grp * TILED_Q;
     const unsigned cap = (unsigned)cap_i;
     const int64_t c0 = (int64_t)gc * chunk;
     const int64_t c1 = min(n, c0 + chunk);
     if (c0 >= c1) return;
+    // uniform: groups of 16 queries whose bounds are small are scanned by the byte-lane kernels
+    if (tiled_group_in_bytes(tiled_group_bound(taus, q0 / 16 * 16, nq), TILED16_CL)) return;
 
     uint4 w[2];
     int nc[2];
@@ -178,6 +214,146 @@ __global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled_kernel(
     }
 }
 
+// Byte-lane form for sixteen queries.  When every bound of a group of 16 queries is below
+// CL = 255 / GP, a sum can only pass if each of its table entries is at most the bound, so the
+// entries may be clamped to CL without changing which sums pass or their values.  Clamped
+// entries of GP consecutive code bytes then add up inside the four byte lanes of a register
+// without a carry (GP * CL <= 255): a 16-byte LDS entry serves 16 queries, and the widening
+// to 16-bit lanes is paid once per GP code bytes.  GP = 2 is used (bounds <= 126; GP = 4 needs
+// bounds <= 62 and measures no faster: the kernel is bound by LDS bank conflicts of the
+// 16-byte reads, not by the adds).  Groups with a larger bound are left to the 16-bit kernel
+// above.  Both kernels are launched over the whole batch; a workgroup whose group belongs to
+// the other kernel exits at once.
+template <int B, int GP>
+__global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled16_kernel(
+    const uint8_t *__restrict__ codes, int64_t n, int64_t chunk, int nq,
+    const unsigned *__restrict__ taus, const char *__restrict__ ws, size_t ws_stride,
+    size_t countsA_off, size_t listsA_off, unsigned *__restrict__ flags)
+{
+    constexpr int NT = tiled_nt(B);
+    constexpr int TQ = 16;
+    constexpr unsigned CL = 255 / GP;
+    using C = ScanCfg<B, NT>;
+    extern __shared__ uint4 tab[];  // [B * 256] entries of sixteen clamped pair sums
+    __shared__ unsigned keys[TQ][TILED_LCAP];
+    __shared__ unsigned cnt[TQ];
+
+    const int tid = threadIdx.x;
+    int grp, gc;
+    tiled_group_and_chunk((nq + TQ - 1) / TQ, grp, gc);
+    const int q0 = grp * TQ;
+    const int64_t c0 = (int64_t)gc * chunk;
+    const int64_t c1 = min(n, c0 + chunk);
+    if (c0 >= c1) return;
+    static_assert(CL == TILED16_CL, "the two kernels must agree on who scans a group");
+    if (!tiled_group_in_bytes(tiled_group_bound(taus, q0, nq), CL)) return;  // uniform
+
+    uint4 w[2];
+    int nc[2];
+    tile_load<B, NT>(codes, c0, c1, w, nc);
+
+    // interleave the sixteen queries' clamped pair tables; a missing query gets CL everywhere
+    for (int e = tid; e < B * 256; e += NT) {
+        unsigned d[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < TQ; ++k) {
+            const int q = q0 + k;
+            unsigned v = CL;
+            if (q < nq) v = min(CL, (unsigned)reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ptab[e]);
+            d[k >> 2] |= v << (8 * (k & 3));
+        }
+        tab[e] = make_uint4(d[0], d[1], d[2], d[3]);
+    }
+    if (tid < TQ) cnt[tid] = 0;
+    // Query k of the group lives in byte (k & 3) of entry dword (k >> 2), and after widening in
+    // 16-bit lane ((k >> 1) & 1) of accumulator 2 * (k >> 2) + (k & 1).  bound + 1 per lane
+    // (0 where there is no query): lane of (acc -sat- thr1) is zero exactly when the sum passes.
+    unsigned thr[TQ];
+    unsigned thr1[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) thr1[i] = 0;
+#pragma unroll
+    for (int k = 0; k < TQ; ++k) {
+        const int q = q0 + k;
+        thr[k] = 0xffffffffu;  // no query
+        if (q < nq) {
+            thr[k] = taus[q];
+            thr1[2 * (k >> 2) + (k & 1)] |= (thr[k] + 1u) << (16 * ((k >> 1) & 1));
+        }
+    }
+    __syncthreads();
+
+    unsigned rel = 0;
+    for (int64_t t0 = c0; t0 < c1; t0 += C::TILE, rel += C::TILE) {
+        if (rel) tile_load<B, NT>(codes, t0, c1, w, nc);
+        constexpr int CPV = (B <= 16) ? 16 / B : 1;
+        constexpr int NV = (B <= 16) ? 2 : 1;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+#pragma unroll
+            for (int c = 0; c < CPV; ++c) {
+                unsigned a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int j0 = 0; j0 < B; j0 += GP) {
+                    uint4 e = make_uint4(0, 0, 0, 0);
+#pragma unroll
+                    for (int j = 0; j < GP; ++j) {
+                        const int jb = j0 + j;
+                        unsigned byte;
+                        if constexpr (B <= 16) byte = byte_of(w[v], c * B + jb);
+                        else byte = byte_of(w[jb >> 4], jb & 15);
+                        const uint4 f = tab[jb * 256 + byte];
+                        e.x += f.x; e.y += f.y; e.z += f.z; e.w += f.w;  // byte lanes: GP * CL <= 255
+                    }
+                    const unsigned ed[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        a[2 * d] += __builtin_amdgcn_perm(0u, ed[d], 0x0c020c00u);      // bytes 0, 2
+                        a[2 * d + 1] += __builtin_amdgcn_perm(0u, ed[d], 0x0c030c01u);  // bytes 1, 3
+                    }
+                }
+                const bool valid = (B <= 16) ? (c < nc[v]) : (nc[0] != 0);
+                const unsigned li = rel + (unsigned)((B <= 16) ? (v * NT + tid) * CPV + c : tid);
+                unsigned z = pk_sub_sat_u16(a[0], thr1[0]);
+#pragma unroll
+                for (int i = 1; i < 8; ++i) z = pk_min_u16(z, pk_sub_sat_u16(a[i], thr1[i]));
+                const bool any = valid && min(z & 0xffffu, z >> 16) == 0u;
+                if (__ballot(any) != 0ull) {
+#pragma unroll
+                    for (int k = 0; k < TQ; ++k) {
+                        const unsigned acc = a[2 * (k >> 2) + (k & 1)];
+                        const unsigned sum = ((k >> 1) & 1) ? (acc >> 16) : (acc & 0xffffu);
+                        const bool pass = valid && thr[k] != 0xffffffffu && sum <= thr[k];
+                        const unsigned slot = wave_append_slot(pass, &cnt[k]);
+                        if (pass && slot < (unsigned)TILED_LCAP) keys[k][slot] = (sum << 24) | li;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+#pragma unroll 1
+    for (int k = 0; k < TQ; ++k) {
+        const int q = q0 + k;
+        if (q >= nq) break;
+        const unsigned c = cnt[k];
+        if (c == 0) continue;
+        if (c > (unsigned)TILED_LCAP) {  // keys were dropped: this query is redone on its own
+            if (tid == 0) flags[q] = 1u;
+            continue;
+        }
+        char *base = const_cast<char *>(ws) + (size_t)q * ws_stride;
+        unsigned *counts = reinterpret_cast<unsigned *>(base + countsA_off);
+        uint64_t *dst = reinterpret_cast<uint64_t *>(base + listsA_off) + (size_t)gc * TILED_LCAP;
+        if (tid == 0) counts[gc] = c;
+        for (unsigned i = tid; i < c; i += NT) {
+            const unsigned key = keys[k][i];
+            dst[i] = ((uint64_t)(key >> 24) << 32) | (uint64_t)(c0 + (key & 0xffffffu));
+        }
+    }
+}
+
 bool make_tiled_plan(int64_t n, int m, int nq, TiledPlan *t)
 {
     t->B = m / 2;
@@ -204,9 +380,16 @@ static int launch_tiled(const TiledPlan &t, const uint8_t *codes, int64_t n, int
     if (!attr_set) {
         QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_u8_tiled_kernel<B>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes));
+        QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_u8_tiled16_kernel<B, TILED16_GP>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes));
         attr_set = true;
     }
-    dim3 grid((unsigned)ceil_div(nq, TILED_Q), (unsigned)t.GC);
+    // every group of 16 queries is scanned by exactly one of the two kernels
+    const unsigned gc8 = (unsigned)ceil_div(t.GC, 8) * 8u;  // chunk slots, eight at a time
+    dim3 grid16((unsigned)ceil_div(nq, 16) * gc8);
+    launch(QADC_PROF_SCAN, (scan_u8_tiled16_kernel<B, TILED16_GP>), grid16, dim3(tiled_nt(B)), t.lds_bytes, st, codes, n,
+           t.chunk, nq, taus, (const char *)ws, ws_stride, countsA_off, listsA_off, flags);
+    dim3 grid((unsigned)ceil_div(nq, TILED_Q) * gc8);
     launch(QADC_PROF_SCAN, scan_u8_tiled_kernel<B>, grid, dim3(tiled_nt(B)), t.lds_bytes, st, codes, n, t.chunk,
            nq, cap, taus, (const char *)ws, ws_stride, countsA_off, listsA_off, flags);
     return QADC_OK;

@@ -534,6 +534,35 @@ def test_scan_topk_query_batches_share_code_reads(Q, O, m):
         assert np.array_equal(gd[iq], wd), (m, iq)
 
 
+@pytest.mark.parametrize("m", [8, 16, 32, 64])
+def test_scan_topk_query_groups_by_bound(Q, O, m):
+    """Groups of 16 queries are scanned by one of two kernels according to the largest bound in
+    the group (byte lanes for bounds up to 126, else 16-bit lanes): a batch with groups of each
+    kind, bounds right at the limit, mixed groups and a partial last group."""
+    rng = np.random.default_rng(100 + m)
+    n, R = 300_007, 100
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    groups = []
+    for base in (0, 60, 62, 63, 100, 126, 127, 200):   # smallest possible sum of each query
+        ql = rng.integers(0, 3, size=(m, 16)).astype(np.uint8)
+        ql[0] += base                                   # every sum of this query is >= base
+        groups.append(ql)
+    qluts = []
+    for gsel in ([0, 0, 1, 1], [2, 2, 3, 3], [4, 4, 5, 5], [6, 7, 7, 6], [0, 3, 5, 7]):
+        for i in range(16 if len(qluts) < 64 else 5):
+            qluts.append(groups[gsel[i % 4]].copy())
+    qluts = np.stack(qluts)                             # 64 + 5 queries
+    gi, gd = gpu_topk(Q, to_gpu(codes), qluts, R)
+    checked = {}
+    for iq in range(len(qluts)):
+        key = qluts[iq].tobytes()
+        if key not in checked:
+            checked[key] = oracle_topk(codes, qluts[iq], R)
+        wi, wd = checked[key]
+        assert np.array_equal(gi[iq], wi), (m, iq)
+        assert np.array_equal(gd[iq], wd), (m, iq)
+
+
 def test_search_batch_config1_shaped(Q, O):
     """qadc_search on a batch of 16 mixture queries over a long database (fused prepare kernel +
     query-tiled scan) against the oracle's replay of the integer part and its own tables."""
