@@ -59,6 +59,9 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="scan workload: also run this many plain device copies of one code buffer (untimed), so "
                          "that a counter run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="scan workload: also time the same steps dealt round-robin to this many HIP streams "
+                         "(each with a workspace of its own), reported beside the single-stream value; 1 = skip")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
     args = ap.parse_args()
@@ -576,6 +579,35 @@ def main():
     ms_per_step = ms_total / args.steps
     gcodes = n / (ms_per_step * 1e-3) / 1e9
 
+    # The same steps with queries in flight on several streams (independent queries, one call each,
+    # a workspace per stream): the small kernels of one query overlap the scan of another.
+    multi = None
+    if args.streams > 1 and not args.separate_calls:
+        ns = args.streams
+        streams = [torch.cuda.Stream(device=dev) for _ in range(ns)]
+        wss = [Q.qadc_workspace_init(torch.empty(ws_bytes, dtype=torch.uint8, device=dev)) for _ in range(ns)]
+        oi = [torch.empty((1, R), dtype=torch.int32, device=dev) for _ in range(ns)]
+        od = [torch.empty((1, R), dtype=torch.uint8, device=dev) for _ in range(ns)]
+        torch.cuda.synchronize()
+
+        def mstep(i):
+            k = i % ns
+            with torch.cuda.stream(streams[k]):
+                Q.qadc_search(cb, queries[i % args.queries:i % args.queries + 1], bufs[i % args.buffers], R, init,
+                              workspace=wss[k], out_idx=oi[k], out_dist=od[k])
+
+        for i in range(args.warmup):
+            mstep(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            mstep(args.warmup + i)
+        torch.cuda.synchronize()
+        ms_multi = (time.perf_counter() - t0) * 1e3 / args.steps
+        multi = {"streams": ns, "ms_per_step": round(ms_multi, 5),
+                 "gcodes_per_s": round(n / (ms_multi * 1e-3) / 1e9, 2),
+                 "note": "same calls, queries dealt round-robin to the streams; host wall clock"}
+
     # Per-kernel durations (HIP events attached to each dispatch by the library), same launch
     # configuration, same buffer rotation.
     roofline = None
@@ -644,6 +676,7 @@ def main():
                    "entry": "build_luts+quantize_luts+scan_topk" if args.separate_calls else "qadc_search"},
         "hbm_gbps_whole_path": round(n * row / (ms_per_step * 1e-3) / 1e9, 1),
         "pct_hbm_peak_whole_path": round(100 * n * row / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+        "multi_stream": multi,
         "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,
         "database_build_s": round(t_build, 2),
     }
