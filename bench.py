@@ -421,6 +421,28 @@ def run_compare(args):
     ms4 = timed(quick)
     ms8 = timed(pq8)
 
+    # the same comparison on batches of 256 queries (one call each): Quick ADC shares code reads
+    # between queries (query-tiled kernels), the float scan has no such form here
+    nbq = min(256, args.queries)
+    qb = queries[:nbq].contiguous()
+    luts8b = Q.qadc_build_luts(cb8, qb)
+
+    def timed_batch(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    ms4b = timed_batch(lambda: Q.qadc_search(cb4, qb, codes4, R, init))
+    ms8b = timed_batch(lambda: Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, luts8b, R))
+    batched = {"queries": nbq, "quick_adc_ms": round(ms4b, 3), "pq8_float_ms": round(ms8b, 3),
+               "quick_adc_gpairs_per_s": round(n * nbq / (ms4b * 1e-3) / 1e9, 1),
+               "pq8_float_gpairs_per_s": round(n * nbq / (ms8b * 1e-3) / 1e9, 1),
+               "speedup_quick_adc_over_pq8_float": round(ms8b / ms4b, 2)}
+
     roofline = kernels = None
     if not args.no_profile:
         nprof = min(args.steps, 200)
@@ -506,6 +528,7 @@ def run_compare(args):
                    "init=%d" % (n, R, init), "n": n, "R": R, "init": init},
         "pq8_float": {"ms_per_query": round(ms8, 5), "gcodes_per_s": round(n / (ms8 * 1e-3) / 1e9, 2)},
         "speedup_quick_adc_over_pq8_float": round(ms8 / ms4, 3),
+        "batches_of_256": batched,
         "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,
         "database_build_s": round(t_build, 2)}))
 
@@ -636,6 +659,15 @@ def main():
                     "avg_kernel_us": round(avg_us, 2),
                     "bytes_per_launch": n * row, "launches_timed": launches}
         kernels = {k + "_kernel_us": round(v[0], 2) for k, v in us.items() if v[1]}
+        # the same scan on ONE buffer every query: 80 MB stay in the 256 MB last-level cache
+        Q.qadc_profile_enable(True)
+        for i in range(100):
+            Q.qadc_search(cb, queries[i % args.queries:i % args.queries + 1], bufs[0], R, init, workspace=ws,
+                          out_idx=out_idx, out_dist=out_dist)
+        torch.cuda.synchronize()
+        ms, cnt = Q.qadc_profile_read(Q.QADC_PROF_SCAN)
+        Q.qadc_profile_enable(False)
+        kernels["scan_kernel_us_same_buffer_every_query"] = round(ms / max(1, cnt) * 1e3, 2)
 
     acc = None
     if args.recall_queries > 0:
