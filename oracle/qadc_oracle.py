@@ -7,7 +7,8 @@ Everything here follows the paper (Andre, Kermarrec, Le Scouarnec, "Accelerated
 Nearest Neighbor Search with Quick ADC", ICMR'17) step by step in plain NumPy,
 slow and unblocked, so that it can be checked against the text by eye:
 
-  Section 2.1          vector / product quantizers, codes of m*b bits
+  Section 2.1          vector / product quantizers, codes of m*b bits; optimized product
+                       quantizers opq(x) = pq(R x), R orthonormal
   Section 2.2          inverted index, residual encoding
   Section 2.3, Alg. 1  Index / Tables / Scan, Eq. (1) tables, Eq. (2) ADC
   Section 3.2, Fig. 2  two 4-bit components per byte, low nibble = even one
@@ -49,7 +50,11 @@ against min(n, sum); the bound  B + Delta*s <= adc < B + Delta*(s+m)  for
 unsaturated sums; stable-argsort and brute-force top-R; the table sizes
 printed in the paper's Table 1.  Recall figures of the paper need its datasets
 and are unpinned (ordering checks only).  k-means is pinned only by
-non-increasing distortion and recovery of well-separated clusters.
+non-increasing distortion and recovery of well-separated clusters.  The OPQ
+trainer is pinned by the orthonormality of R, by a distortion that does not grow
+from round to round, and by data that a known rotation makes separable per
+sub-space (it must get close to the distortion reached with that rotation);
+opq_rotate by permutation and block-rotation matrices worked by hand.
 """
 
 from __future__ import annotations
@@ -135,6 +140,61 @@ def pq_decode(comps: np.ndarray, codebooks: np.ndarray) -> np.ndarray:
     """pq(x): concatenation of the selected centroids, float32 [n][d]."""
     m = codebooks.shape[0]
     return np.concatenate([codebooks[j][comps[:, j]] for j in range(m)], axis=1)
+
+
+def opq_rotate(rot: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """y = R x for every row x (Section 2.1, opq(x) = pq(R x)): float64 products and sums,
+    one rounding to float32.  rot float32 [d][d], x float32 [n][d] -> float32 [n][d]."""
+    return (np.asarray(x, dtype=np.float64) @ np.asarray(rot, dtype=np.float64).T).astype(np.float32)
+
+
+def kmeans_refine(x: np.ndarray, centroids: np.ndarray, iters: int):
+    """`iters` Lloyd iterations (as kmeans_lloyd) started from the given centroids."""
+    x = np.asarray(x, dtype=np.float32)
+    c = np.asarray(centroids, dtype=np.float32).copy()
+    for _ in range(iters):
+        a = np.argmin(sq_l2(x, c), axis=1)
+        for i in range(len(c)):
+            own = x[a == i]
+            if len(own):
+                c[i] = own.astype(np.float64).sum(axis=0) / len(own)
+    return c
+
+
+def pq_distortion(x: np.ndarray, codebooks: np.ndarray) -> float:
+    """Mean squared distance between the rows of x and their reproductions pq(x)."""
+    y = pq_decode(pq_encode(x, codebooks), codebooks)
+    return float(((np.asarray(x, dtype=np.float64) - y) ** 2).sum(axis=1).mean())
+
+
+def opq_train(train: np.ndarray, m: int, k: int, outer: int, inner: int, init_rows: np.ndarray):
+    """Optimized product quantizer (Section 2.1): an orthonormal R (R^T R = I) and the codebooks
+    of pq, so that opq(x) = pq(R x).  The paper takes R from the cited OPQ method; this is
+    its non-parametric form written out: starting from R = I and a product quantizer of the
+    unrotated data, alternate
+      (1) codebooks: `inner` Lloyd iterations per sub-space on the rotated learning set R x,
+          continued from the current codebooks;
+      (2) rotation: with Y the reproductions pq(R x) of the learning set, the orthonormal R
+          minimising sum ||R x - y||^2, i.e. the orthogonal Procrustes solution
+          R = V U^T for the SVD  X^T Y = U S V^T.
+    Neither step increases the distortion sum ||R x - pq(R x)||^2.
+    Returns (R float32 [d][d], codebooks float32 [m][k][d/m], distortion after each round).
+    """
+    x = np.asarray(train, dtype=np.float32)
+    n, d = x.shape
+    dsub = d // m
+    rot = np.eye(d, dtype=np.float64)
+    cb = pq_train(x, m, k, inner, init_rows)
+    history = []
+    for _ in range(outer):
+        xr = (x.astype(np.float64) @ rot.T).astype(np.float32)
+        for j in range(m):
+            cb[j] = kmeans_refine(xr[:, j * dsub:(j + 1) * dsub], cb[j], inner)
+        y = pq_decode(pq_encode(xr, cb), cb).astype(np.float64)
+        history.append(float(((xr.astype(np.float64) - y) ** 2).sum(axis=1).mean()))
+        u, _, vt = np.linalg.svd(x.astype(np.float64).T @ y)
+        rot = (u @ vt).T
+    return rot.astype(np.float32), cb, history
 
 
 def code_bits(m: int, k: int) -> int:

@@ -391,3 +391,55 @@ def test_ivf_probes_and_all_cells():
     assert np.array_equal(res["ids"], ix["ids"][pos])
     # the query's own vector (distance ~ quantization error) is found
     assert 77 in res["ids"]
+
+
+# ------------------------------------------------------------------ optimized product quantizer
+
+def test_opq_rotate_against_hand_worked_matrices():
+    """y = R x (Section 2.1): a permutation matrix permutes components, a plane rotation by 90
+    degrees maps (a, b) to (-b, a), the identity changes nothing."""
+    from oracle import qadc_oracle as O
+    x = np.array([[1.0, 2.0, 3.0, 4.0], [-5.0, 0.5, 7.0, 8.0]], dtype=np.float32)
+    assert np.array_equal(O.opq_rotate(np.eye(4, dtype=np.float32), x), x)
+    perm = np.zeros((4, 4), dtype=np.float32)
+    perm[0, 2] = perm[1, 0] = perm[2, 3] = perm[3, 1] = 1.0     # y0 = x2, y1 = x0, y2 = x3, y3 = x1
+    assert np.array_equal(O.opq_rotate(perm, x), x[:, [2, 0, 3, 1]])
+    quarter = np.eye(4, dtype=np.float32)
+    quarter[:2, :2] = [[0.0, -1.0], [1.0, 0.0]]
+    assert np.array_equal(O.opq_rotate(quarter, x), np.stack([-x[:, 1], x[:, 0], x[:, 2], x[:, 3]], axis=1))
+
+
+def test_opq_train_is_orthonormal_monotone_and_finds_a_hidden_rotation():
+    """Data made of two independent 2-d cluster sets (one per sub-space) and then rotated by a
+    known orthonormal Q: a plain product quantizer on the rotated data mixes the sub-spaces and
+    pays for it; OPQ must return an orthonormal R, never increase its distortion from round to
+    round, and end far below the plain product quantizer."""
+    from oracle import qadc_oracle as O
+    rng = np.random.default_rng(42)
+    n, k = 3000, 16
+    grid = np.array([[a, b] for a in range(4) for b in range(4)], dtype=np.float64) * 10.0
+    parts = [grid[rng.integers(0, 16, size=n)] + rng.normal(scale=0.3, size=(n, 2)) for _ in range(2)]
+    clean = np.concatenate(parts, axis=1)
+    q, _ = np.linalg.qr(rng.normal(size=(4, 4)))
+    mixed = (clean @ q.T).astype(np.float32)
+    rows = rng.permutation(n)[:k]
+    plain = O.pq_distortion(mixed, O.pq_train(mixed, 2, k, 8, rows))
+    ideal = O.pq_distortion(clean.astype(np.float32), O.pq_train(clean.astype(np.float32), 2, k, 8, rows))
+    rot, cb, hist = O.opq_train(mixed, 2, k, 12, 4, rows)
+    np.testing.assert_allclose(rot.astype(np.float64).T @ rot.astype(np.float64), np.eye(4), atol=1e-5)
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(hist, hist[1:]))
+    got = O.pq_distortion(O.opq_rotate(rot, mixed), cb)
+    assert got <= hist[0] * (1 + 1e-6)
+    assert plain > 1.5 * ideal          # the hidden rotation matters on this data
+    assert got < 0.5 * plain            # and OPQ undoes most of the damage
+
+
+def test_opq_with_identity_rotation_is_the_product_quantizer():
+    """outer = 0 rounds: R = I and the codebooks of pq_train."""
+    from oracle import qadc_oracle as O
+    rng = np.random.default_rng(1)
+    x = rng.normal(size=(500, 8)).astype(np.float32)
+    rows = np.arange(16)
+    rot, cb, hist = O.opq_train(x, 4, 16, 0, 3, rows)
+    assert np.array_equal(rot, np.eye(8, dtype=np.float32)) and hist == []
+    assert np.array_equal(cb, O.pq_train(x, 4, 16, 3, rows))
