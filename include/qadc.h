@@ -207,6 +207,18 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
                    uint8_t *codes, void *stream);
 
 /*
+ * Rotation of an optimized product quantizer, Section 2.1: opq(x) = pq(R x), R^T R = I.
+ *     y[i][r] = sum_t rot[r][t] * x[i][t]
+ * with products and sums in float64 in increasing t and one rounding to float32.  At query time
+ * it precedes the Tables step (its cost belongs to that step, Section 4.3): rotate the queries,
+ * then call qadc_build_luts / qadc_search / qadc_ivf_search with the rotated queries and the
+ * codebooks trained on rotated data.  The same call rotates database vectors before
+ * qadc_pq_encode.  The library does not check that rot is orthonormal.
+ *   rot [d][d] f32;  x [n][d] f32;  y [n][d] f32 (output; must not overlap x)
+ */
+int qadc_rotate(const float *rot, int d, const float *x, int64_t n, float *y, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (the paper reports Index / Tables / Scan times
  * separately, Section 4.3).  While enabled, the library launches the kernels named
  * below with a start and a stop HIP event attached to each dispatch (the kernel's own
@@ -222,7 +234,8 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
 #define QADC_PROF_TABLES     5  /* qadc_build_luts kernel */
 #define QADC_PROF_QUANTIZE   6  /* qadc_quantize_luts kernel */
 #define QADC_PROF_PREPARE    7  /* tables + quantizer + sampling kernel of qadc_search */
-#define QADC_PROF_COUNT  8
+#define QADC_PROF_ROTATE     8  /* qadc_rotate kernel */
+#define QADC_PROF_COUNT  9
 int qadc_profile_enable(int on);
 int qadc_profile_read(int which, double *total_ms, int64_t *launches);
 

@@ -23,11 +23,11 @@ QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
 QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
 QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT, QADC_WS_SEARCH = 0, 1, 2, 3
 (QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES,
- QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE) = range(8)
+ QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE, QADC_PROF_ROTATE) = range(9)
 
 EXPORTS = (
     "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
-    "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train",
+    "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train", "qadc_rotate",
     "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version",
 )
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.qadc_ivf_workspace_bytes.restype = sz
         L.qadc_pq_encode.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp]
         L.qadc_pq_encode.restype = i32
+        L.qadc_rotate.argtypes = [vp, i32, vp, i64, vp, vp]
+        L.qadc_rotate.restype = i32
         L.qadc_pq_train.argtypes = [vp, i64, i32, i32, i32, vp, i32, vp, vp, sz, vp]
         L.qadc_pq_train.restype = i32
         L.qadc_profile_enable.argtypes = [i32]
@@ -196,6 +198,17 @@ def qadc_pq_encode(codebooks, x, out=None):
         out = torch.empty((n, row), dtype=torch.uint8, device=x.device)
     _check(lib().qadc_pq_encode(_ptr(codebooks, torch.float32), d, m, ksub, _ptr(x, torch.float32),
                                 n, _ptr(out, torch.uint8), _stream()))
+    return out
+
+
+def qadc_rotate(rot, x, out=None):
+    """rot f32 [d][d], x f32 [n][d] -> y f32 [n][d], y[i] = rot @ x[i]."""
+    n, d = x.shape
+    assert rot.shape == (d, d)
+    if out is None:
+        out = torch.empty((n, d), dtype=torch.float32, device=x.device)
+    _check(lib().qadc_rotate(_ptr(rot, torch.float32), d, _ptr(x, torch.float32), n, _ptr(out, torch.float32),
+                             _stream()))
     return out
 
 

@@ -34,6 +34,7 @@ int scan_topk_f32(int, const uint8_t *, int64_t, int, const float *, int, int, u
                   void *, size_t, hipStream_t);
 size_t scan_topk_f32_workspace(int, int64_t, int, int, int);
 int pq_encode(const float *, int, int, int, const float *, int64_t, uint8_t *, hipStream_t);
+int rotate(const float *, int, const float *, int64_t, float *, hipStream_t);
 int workspace_init(void *, size_t, hipStream_t);
 int pq_train(const float *, int64_t, int, int, int, const int64_t *, int, float *, void *, size_t,
              hipStream_t);
@@ -109,6 +110,11 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
                    uint8_t *codes, void *stream)
 {
     return qadc::pq_encode(codebooks, d, m, ksub, x, n, codes, (hipStream_t)stream);
+}
+
+int qadc_rotate(const float *rot, int d, const float *x, int64_t n, float *y, void *stream)
+{
+    return qadc::rotate(rot, d, x, n, y, (hipStream_t)stream);
 }
 
 int qadc_profile_enable(int on) { return qadc::profile_enable(on); }
