@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--streams", type=int, default=2,
                     help="scan workload: also time the same steps dealt round-robin to this many HIP streams "
                          "(each with a workspace of its own), reported beside the single-stream value; 1 = skip")
+    ap.add_argument("--opq", type=int, default=0, metavar="ROUNDS",
+                    help="scan workload: train an optimized product quantizer with this many rounds; database "
+                         "vectors are rotated before encoding and every query by qadc_rotate before qadc_search")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
     args = ap.parse_args()
@@ -75,33 +78,60 @@ def parse():
     return args
 
 
-def build_database(Q, torch, spec, m, n_total, n_keep, dev):
+def train_opq(Q, torch, train, m, rows, rounds, iters=10):
+    """Optimized product quantizer on the GPU (bench support): `rounds` times { codebooks by k-means on
+    the rotated learning set; rotation by orthogonal Procrustes between the learning set and its
+    reproductions }, then the codebooks of the final rotation.  -> (rot [d][d], codebooks)."""
+    n, d = train.shape
+    dsub = d // m
+    rot = torch.eye(d, dtype=torch.float32, device=train.device)
+    for _ in range(rounds):
+        xr = Q.qadc_rotate(rot, train)
+        cb = Q.qadc_pq_train(xr, m, 16, rows, iters)
+        codes = Q.qadc_pq_encode(cb, xr).long()
+        comps = torch.stack([codes & 15, codes >> 4], dim=2).reshape(n, m)     # component j of every row
+        y = torch.cat([cb[j][comps[:, j]] for j in range(m)], dim=1)            # reproductions pq(R x)
+        u, _, vt = torch.linalg.svd(train.double().T @ y.double())
+        rot = (u @ vt).T.float().contiguous()
+    xr = Q.qadc_rotate(rot, train)
+    return rot, Q.qadc_pq_train(xr, m, 16, rows, iters)
+
+
+def build_database(Q, torch, spec, m, n_total, n_keep, dev, opq_rounds=0):
     """Codebooks (GPU k-means) + n_total encoded mixture vectors, all produced on the GPU.
 
     The raw vectors of the first n_keep rows are kept for the exact-neighbour accuracy check.
+    With opq_rounds > 0 the quantizer is an optimized product quantizer: the vectors are rotated
+    before encoding and the rotation is returned as a fourth value.
     """
     from workloads import SEED_TRAIN, SEED_BASE, kmeans_init_rows
     from workloads.mixture_torch import mixture_vectors_torch, BLOCK
     train = mixture_vectors_torch(spec, SEED_TRAIN, 0, 20_000, dev)
     rows = torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev)
-    cb = Q.qadc_pq_train(train, m, 16, rows, 10)
+    rot = None
+    if opq_rounds > 0:
+        rot, cb = train_opq(Q, torch, train, m, rows, opq_rounds)
+    else:
+        cb = Q.qadc_pq_train(train, m, 16, rows, 10)
     codes = torch.empty((n_total, m // 2), dtype=torch.uint8, device=dev)
     raw = torch.empty((n_keep, spec.d), dtype=torch.float32, device=dev) if n_keep else None
     chunk = 4 * BLOCK
     for s in range(0, n_total, chunk):
         cnt = min(chunk, n_total - s)
         x = mixture_vectors_torch(spec, SEED_BASE, s, cnt, dev)
-        Q.qadc_pq_encode(cb, x, out=codes[s:s + cnt])
+        Q.qadc_pq_encode(cb, Q.qadc_rotate(rot, x) if rot is not None else x, out=codes[s:s + cnt])
         if raw is not None and s < n_keep:
             k = min(cnt, n_keep - s)
             raw[s:s + k] = x[:k]
     torch.cuda.synchronize()
+    if opq_rounds > 0:
+        return cb, codes, raw, rot
     return cb, codes, raw
 
 
-def accuracy(Q, torch, np, cb, codes, raw, queries, R, init):
+def accuracy(Q, torch, np, cb, codes, raw, queries, R, init, rot=None):
     """overlap@R of the quantized scan with float ADC on the same codes, and NN-recall@R of both."""
-    luts = Q.qadc_build_luts(cb, queries)
+    luts = Q.qadc_build_luts(cb, Q.qadc_rotate(rot, queries) if rot is not None else queries)
     ql, _, _, _ = Q.qadc_quantize_luts(luts, codes[:init], R)
     qi, _ = Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes, ql, R)
     fi, _ = Q.qadc_scan_topk(Q.QADC_F32_4BIT, codes, luts, R)
@@ -560,8 +590,13 @@ def main():
 
     t0 = time.time()
     n_keep = n if args.recall_queries > 0 else 0
-    cb, codes, raw = build_database(Q, torch, spec, m, n * args.buffers, n_keep, dev)
+    rot = None
+    if args.opq > 0:
+        cb, codes, raw, rot = build_database(Q, torch, spec, m, n * args.buffers, n_keep, dev, args.opq)
+    else:
+        cb, codes, raw = build_database(Q, torch, spec, m, n * args.buffers, n_keep, dev)
     queries = mixture_vectors_torch(spec, SEED_QUERY, 0, args.queries, dev)
+    yrot = torch.empty((1, spec.d), dtype=torch.float32, device=dev)
     t_build = time.time() - t0
     bufs = [codes[b * n:(b + 1) * n] for b in range(args.buffers)]
 
@@ -578,6 +613,9 @@ def main():
             Q.qadc_build_luts(cb, queries[qi:qi + 1], out=luts)
             ql, _, _, _ = Q.qadc_quantize_luts(luts, buf[:init], R)
             Q.qadc_scan_topk(Q.QADC_U8_4BIT, buf, ql, R, workspace=ws, out_idx=out_idx, out_dist=out_dist)
+        elif rot is not None:
+            Q.qadc_rotate(rot, queries[qi:qi + 1], out=yrot)
+            Q.qadc_search(cb, yrot, buf, R, init, workspace=ws, out_idx=out_idx, out_dist=out_dist)
         else:
             Q.qadc_search(cb, queries[qi:qi + 1], buf, R, init, workspace=ws, out_idx=out_idx,
                           out_dist=out_dist)
@@ -605,7 +643,7 @@ def main():
     # The same steps with queries in flight on several streams (independent queries, one call each,
     # a workspace per stream): the small kernels of one query overlap the scan of another.
     multi = None
-    if args.streams > 1 and not args.separate_calls:
+    if args.streams > 1 and not args.separate_calls and rot is None:
         ns = args.streams
         streams = [torch.cuda.Stream(device=dev) for _ in range(ns)]
         wss = [Q.qadc_workspace_init(torch.empty(ws_bytes, dtype=torch.uint8, device=dev)) for _ in range(ns)]
@@ -644,7 +682,8 @@ def main():
         us = {}
         for name, which in (("scan", Q.QADC_PROF_SCAN), ("seed", Q.QADC_PROF_SEED),
                             ("merge", Q.QADC_PROF_MERGE), ("tables", Q.QADC_PROF_TABLES),
-                            ("quantize", Q.QADC_PROF_QUANTIZE), ("prepare", Q.QADC_PROF_PREPARE)):
+                            ("quantize", Q.QADC_PROF_QUANTIZE), ("prepare", Q.QADC_PROF_PREPARE),
+                            ("rotate", Q.QADC_PROF_ROTATE)):
             ms, cnt = Q.qadc_profile_read(which)
             us[name] = (ms / max(1, cnt) * 1e3, cnt)
         Q.qadc_profile_enable(False)
@@ -671,7 +710,7 @@ def main():
 
     acc = None
     if args.recall_queries > 0:
-        acc = accuracy(Q, torch, np, cb, bufs[0], raw, queries[:args.recall_queries].contiguous(), R, init)
+        acc = accuracy(Q, torch, np, cb, bufs[0], raw, queries[:args.recall_queries].contiguous(), R, init, rot)
         acc["note"] = ("overlap = |top-R(Quick ADC) & top-R(float ADC, same codes)| / R; NN-recall = exact "
                        "nearest neighbour (raw vectors) among the R returned; first buffer only")
 
@@ -681,7 +720,8 @@ def main():
         from oracle import cref
         nqc = args.cpu_queries
         h_codes = bufs[0].cpu().numpy()
-        l = Q.qadc_build_luts(cb, mixture_vectors_torch(spec, SEED_QUERY, 0, nqc, dev))
+        cq = mixture_vectors_torch(spec, SEED_QUERY, 0, nqc, dev)
+        l = Q.qadc_build_luts(cb, Q.qadc_rotate(rot, cq) if rot is not None else cq)
         ql, _, _, _ = Q.qadc_quantize_luts(l, bufs[0][:init], R)
         gi, gd = Q.qadc_scan_topk(Q.QADC_U8_4BIT, bufs[0], ql, R)
         torch.cuda.synchronize()
@@ -705,7 +745,9 @@ def main():
                    "iterations on 20k vectors), N=%d codes contiguous, queries one at a time, R=%d, "
                    "init=%d, %d rotating code buffers" % (m, n, R, init, args.buffers),
                    "n": n, "m": m, "R": R, "init": init, "nbins": 255, "buffers": args.buffers,
-                   "entry": "build_luts+quantize_luts+scan_topk" if args.separate_calls else "qadc_search"},
+                   "entry": "build_luts+quantize_luts+scan_topk" if args.separate_calls else
+                   ("qadc_rotate+qadc_search (optimized product quantizer, %d rounds)" % args.opq if rot is not None
+                    else "qadc_search")},
         "hbm_gbps_whole_path": round(n * row / (ms_per_step * 1e-3) / 1e9, 1),
         "pct_hbm_peak_whole_path": round(100 * n * row / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
         "multi_stream": multi,

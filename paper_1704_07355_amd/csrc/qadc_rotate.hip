@@ -5,8 +5,11 @@
 // the Tables step (Section 4.3 counts it there); the same kernel rotates the database vectors
 // before they are encoded.
 //
-// A small blocked matrix product on the vector ALU: a workgroup of 256 threads computes a tile of
-// 64 vectors x 64 outputs, 16 components of t at a time through LDS, 4 x 4 outputs per thread.
+// Many vectors (database side, query batches): a small blocked matrix product on the vector ALU; a
+// workgroup of 256 threads computes a tile of 64 vectors x 64 outputs, 16 components of t at a
+// time through LDS, 4 x 4 outputs per thread.  A few vectors (queries one at a time): one
+// wavefront per output, the lanes split t and their partial sums are added by a butterfly, so
+// that a query's rotation is one round trip to memory instead of d / 16 of them.
 
 #include "qadc_common.h"
 #include "qadc_profile.h"
@@ -73,12 +76,39 @@ __global__ __launch_bounds__(256) void rotate_kernel(const float *__restrict__ r
     }
 }
 
+// y[i][r] for r = 4 * blockIdx.x + wave, i = blockIdx.y: lane l adds the components t = l, l + 64,
+// ... in increasing t, then the 64 partial sums are added pairwise.
+__global__ __launch_bounds__(256) void rotate_few_kernel(const float *__restrict__ rot, int d,
+                                                         const float *__restrict__ x,
+                                                         float *__restrict__ y)
+{
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t i = blockIdx.y;
+    if (r >= d) return;  // whole wave
+    const float *xr = x + i * d;
+    const float *rr = rot + (size_t)r * d;
+    double acc = 0.0;
+    for (int t = lane; t < d; t += 64) acc = fma((double)rr[t], (double)xr[t], acc);
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
+    if (lane == 0) y[i * d + r] = (float)acc;
+}
+
+constexpr int ROT_FEW = 32;  // up to this many vectors take the one-wavefront-per-output kernel
+
 int rotate(const float *rot, int d, const float *x, int64_t n, float *y, hipStream_t st)
 {
     if (d < 1 || n < 0) return fail(QADC_EINVAL, "qadc_rotate: d=%d n=%lld", d, (long long)n);
     if (n == 0) return QADC_OK;
     if (!rot || !x || !y) return fail(QADC_EINVAL, "qadc_rotate: null pointer");
     if (x == y) return fail(QADC_EINVAL, "qadc_rotate: x and y must not overlap");
+    if (n <= ROT_FEW) {
+        launch(QADC_PROF_ROTATE, rotate_few_kernel, dim3((unsigned)ceil_div(d, 4), (unsigned)n), dim3(256), 0, st,
+               rot, d, x, y);
+        QADC_HIP_TRY(hipGetLastError());
+        return QADC_OK;
+    }
     const int64_t gy = ceil_div(n, ROT_TM);
     if (gy > 65535) {  // the y dimension of a grid is 16 bits wide: rows in slabs
         const int64_t slab = 65535ll * ROT_TM;
