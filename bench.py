@@ -50,6 +50,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=256, help="queries per step of the batched workload")
     ap.add_argument("--buffers", type=int, default=8, help="distinct code buffers rotated over")
     ap.add_argument("--m", type=int, default=None)
+    ap.add_argument("--d", type=int, default=128, help="dimensions of the vectors (scan and ivf workloads)")
     ap.add_argument("--R", type=int, default=100)
     ap.add_argument("--init", type=int, default=None)
     ap.add_argument("--queries", type=int, default=1000)
@@ -295,7 +296,7 @@ def run_ivf(args):
     m, n, K, R, init, nprobe, nb = args.m, args.n, args.K, args.R, args.init, args.nprobe, args.batch
     t0 = time.time()
     nq_total = nb * (args.steps + args.warmup)
-    index, sizes, queries = build_ivf_index(Q, torch, np, n, K, m, nq_total, dev)
+    index, sizes, queries = build_ivf_index(Q, torch, np, n, K, m, nq_total, dev, d=args.d)
     coarse, list_off, codes, _, cb = index.tensors
     t_build = time.time() - t0
 
@@ -584,7 +585,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    spec = MixtureSpec(d=128)
+    spec = MixtureSpec(d=args.d)
     m, n, R, init = args.m, args.n, args.R, args.init
     row = m // 2
 
@@ -741,9 +742,11 @@ def main():
         "value": round(gcodes, 2), "unit": "Gcodes/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "config 2: single-query scan, d=128 mixture, PQ m=%d x 4-bit (10 k-means "
+        "config": {"workload": "%s: single-query scan, d=%d mixture, PQ m=%d x 4-bit (10 k-means "
                    "iterations on 20k vectors), N=%d codes contiguous, queries one at a time, R=%d, "
-                   "init=%d, %d rotating code buffers" % (m, n, R, init, args.buffers),
+                   "init=%d, %d rotating code buffers"
+                   % ("config 2" if (args.d, m, n) == (128, 16, 10_000_000) else "config-2-shaped", args.d, m, n, R,
+                      init, args.buffers),
                    "n": n, "m": m, "R": R, "init": init, "nbins": 255, "buffers": args.buffers,
                    "entry": "build_luts+quantize_luts+scan_topk" if args.separate_calls else
                    ("qadc_rotate+qadc_search (optimized product quantizer, %d rounds)" % args.opq if rot is not None

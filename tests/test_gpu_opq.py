@@ -91,3 +91,38 @@ def test_search_with_an_optimized_product_quantizer(Q, O):
         assert np.abs(h_ql[iq].astype(int) - t["qlut"].astype(int)).max() <= 1
         wi, wd = O.top_r(O.scan_saturating(h_ql[iq], codes), R, pad_dist=255)
         assert np.array_equal(idx_np(gi)[iq], wi) and np.array_equal(gd[iq].cpu().numpy(), wd)
+
+
+@pytest.mark.parametrize("shape", [(960, 32, 400_000), (256, 16, 400_000), (960, 32, 20_000)])
+def test_search_on_high_dimensional_descriptors(Q, O, shape):
+    """Shapes of the paper's other datasets (Sections 4.5 and 4.6): 960-dimensional descriptors in
+    128-bit codes (m = 32, 30 dimensions per sub-space) and 256-dimensional L2-normalized ones in
+    64-bit codes.  qadc_search against the three calls and the oracle, on a database long enough
+    for the fused prepare kernel and on a short one."""
+    import torch
+    from oracle import cref
+    d, m, n = shape
+    rng = np.random.default_rng(d + n)
+    cb = rng.normal(size=(m, 16, d // m)).astype(np.float32)
+    if d == 256:
+        cb /= np.sqrt(d / m) * 4
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    queries = rng.normal(size=(4, d)).astype(np.float32)
+    if d == 256:
+        queries /= np.linalg.norm(queries, axis=1, keepdims=True)
+    R, init = 100, 200
+    g_cb, g_q, g_codes = to_gpu(cb), to_gpu(queries), to_gpu(codes)
+    ql = torch.empty((4, m, 16), dtype=torch.uint8, device="cuda:0")
+    si, sd = Q.qadc_search(g_cb, g_q, g_codes, R, init, qluts_out=ql)
+    luts = Q.qadc_build_luts(g_cb, g_q)
+    ql3, _, _, _ = Q.qadc_quantize_luts(luts, g_codes[:init], R)
+    ci, cd = Q.qadc_scan_topk(Q.QADC_U8_4BIT, g_codes, ql3, R)
+    torch.cuda.synchronize()
+    assert torch.equal(ql, ql3) and torch.equal(si, ci) and torch.equal(sd, cd)
+    np.testing.assert_allclose(luts.cpu().numpy(), O.build_luts(cb, queries), rtol=1e-4)
+    h_ql = ql.cpu().numpy()
+    for iq in range(4):
+        t = O.quick_adc_tables(cb, queries[iq], codes, init, R)
+        assert np.abs(h_ql[iq].astype(int) - t["qlut"].astype(int)).max() <= 1
+        wi, wd = cref.scan_topk_u8(codes, h_ql[iq][None], R)
+        assert np.array_equal(idx_np(si)[iq], wi[0]) and np.array_equal(sd[iq].cpu().numpy(), wd[0])
