@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--m", type=int, default=None)
     ap.add_argument("--d", type=int, default=128, help="dimensions of the vectors (scan and ivf workloads)")
     ap.add_argument("--R", type=int, default=100)
+    ap.add_argument("--nbins", type=int, default=255,
+                    help="scan workload: bins of the table quantizer (255: unsigned bytes; 127: the paper's signed bytes)")
     ap.add_argument("--init", type=int, default=None)
     ap.add_argument("--queries", type=int, default=1000)
     ap.add_argument("--cpu-queries", type=int, default=2048, help="queries of the CPU-oracle sample (0 = skip)")
@@ -130,11 +132,11 @@ def build_database(Q, torch, spec, m, n_total, n_keep, dev, opq_rounds=0):
     return cb, codes, raw
 
 
-def accuracy(Q, torch, np, cb, codes, raw, queries, R, init, rot=None):
+def accuracy(Q, torch, np, cb, codes, raw, queries, R, init, rot=None, nbins=255):
     """overlap@R of the quantized scan with float ADC on the same codes, and NN-recall@R of both."""
     luts = Q.qadc_build_luts(cb, Q.qadc_rotate(rot, queries) if rot is not None else queries)
-    ql, _, _, _ = Q.qadc_quantize_luts(luts, codes[:init], R)
-    qi, _ = Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes, ql, R)
+    ql, _, _, _ = Q.qadc_quantize_luts(luts, codes[:init], R, nbins)
+    qi, _ = Q.qadc_scan_topk(Q.QADC_U8_4BIT, codes, ql, R, nbins)
     fi, _ = Q.qadc_scan_topk(Q.QADC_F32_4BIT, codes, luts, R)
     # exact nearest neighbour of each query among the raw vectors (measurement only)
     best = torch.full((queries.shape[0],), float("inf"), device=queries.device)
@@ -612,13 +614,13 @@ def main():
         buf = bufs[i % args.buffers]
         if args.separate_calls:
             Q.qadc_build_luts(cb, queries[qi:qi + 1], out=luts)
-            ql, _, _, _ = Q.qadc_quantize_luts(luts, buf[:init], R)
-            Q.qadc_scan_topk(Q.QADC_U8_4BIT, buf, ql, R, workspace=ws, out_idx=out_idx, out_dist=out_dist)
+            ql, _, _, _ = Q.qadc_quantize_luts(luts, buf[:init], R, args.nbins)
+            Q.qadc_scan_topk(Q.QADC_U8_4BIT, buf, ql, R, args.nbins, workspace=ws, out_idx=out_idx, out_dist=out_dist)
         elif rot is not None:
             Q.qadc_rotate(rot, queries[qi:qi + 1], out=yrot)
-            Q.qadc_search(cb, yrot, buf, R, init, workspace=ws, out_idx=out_idx, out_dist=out_dist)
+            Q.qadc_search(cb, yrot, buf, R, init, args.nbins, workspace=ws, out_idx=out_idx, out_dist=out_dist)
         else:
-            Q.qadc_search(cb, queries[qi:qi + 1], buf, R, init, workspace=ws, out_idx=out_idx,
+            Q.qadc_search(cb, queries[qi:qi + 1], buf, R, init, args.nbins, workspace=ws, out_idx=out_idx,
                           out_dist=out_dist)
 
     if args.copy_calibration > 0:
@@ -656,7 +658,7 @@ def main():
             k = i % ns
             with torch.cuda.stream(streams[k]):
                 Q.qadc_search(cb, queries[i % args.queries:i % args.queries + 1], bufs[i % args.buffers], R, init,
-                              workspace=wss[k], out_idx=oi[k], out_dist=od[k])
+                              args.nbins, workspace=wss[k], out_idx=oi[k], out_dist=od[k])
 
         for i in range(args.warmup):
             mstep(i)
@@ -702,8 +704,8 @@ def main():
         # the same scan on ONE buffer every query: 80 MB stay in the 256 MB last-level cache
         Q.qadc_profile_enable(True)
         for i in range(100):
-            Q.qadc_search(cb, queries[i % args.queries:i % args.queries + 1], bufs[0], R, init, workspace=ws,
-                          out_idx=out_idx, out_dist=out_dist)
+            Q.qadc_search(cb, queries[i % args.queries:i % args.queries + 1], bufs[0], R, init, args.nbins,
+                          workspace=ws, out_idx=out_idx, out_dist=out_dist)
         torch.cuda.synchronize()
         ms, cnt = Q.qadc_profile_read(Q.QADC_PROF_SCAN)
         Q.qadc_profile_enable(False)
@@ -711,7 +713,7 @@ def main():
 
     acc = None
     if args.recall_queries > 0:
-        acc = accuracy(Q, torch, np, cb, bufs[0], raw, queries[:args.recall_queries].contiguous(), R, init, rot)
+        acc = accuracy(Q, torch, np, cb, bufs[0], raw, queries[:args.recall_queries].contiguous(), R, init, rot, args.nbins)
         acc["note"] = ("overlap = |top-R(Quick ADC) & top-R(float ADC, same codes)| / R; NN-recall = exact "
                        "nearest neighbour (raw vectors) among the R returned; first buffer only")
 
@@ -723,12 +725,12 @@ def main():
         h_codes = bufs[0].cpu().numpy()
         cq = mixture_vectors_torch(spec, SEED_QUERY, 0, nqc, dev)
         l = Q.qadc_build_luts(cb, Q.qadc_rotate(rot, cq) if rot is not None else cq)
-        ql, _, _, _ = Q.qadc_quantize_luts(l, bufs[0][:init], R)
-        gi, gd = Q.qadc_scan_topk(Q.QADC_U8_4BIT, bufs[0], ql, R)
+        ql, _, _, _ = Q.qadc_quantize_luts(l, bufs[0][:init], R, args.nbins)
+        gi, gd = Q.qadc_scan_topk(Q.QADC_U8_4BIT, bufs[0], ql, R, args.nbins)
         torch.cuda.synchronize()
         h_ql = ql.cpu().numpy()
         t0 = time.time()
-        ci, cd = cref.scan_topk_u8(h_codes, h_ql, R)
+        ci, cd = cref.scan_topk_u8(h_codes, h_ql, R, args.nbins)
         dt = time.time() - t0
         same = bool(np.array_equal(gi.cpu().numpy().view(np.uint32), ci)
                     and np.array_equal(gd.cpu().numpy(), cd))
@@ -747,7 +749,7 @@ def main():
                    "init=%d, %d rotating code buffers"
                    % ("config 2" if (args.d, m, n) == (128, 16, 10_000_000) else "config-2-shaped", args.d, m, n, R,
                       init, args.buffers),
-                   "n": n, "m": m, "R": R, "init": init, "nbins": 255, "buffers": args.buffers,
+                   "n": n, "m": m, "R": R, "init": init, "nbins": args.nbins, "buffers": args.buffers,
                    "entry": "build_luts+quantize_luts+scan_topk" if args.separate_calls else
                    ("qadc_rotate+qadc_search (optimized product quantizer, %d rounds)" % args.opq if rot is not None
                     else "qadc_search")},
