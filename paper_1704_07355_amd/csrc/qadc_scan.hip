@@ -196,6 +196,40 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
     }
 }
 
+// Ascending bitonic sort of 4 * 64 values held four per lane by one wavefront: element
+// e = 4 * lane + r.  Exchanges at distance < 4 stay inside a lane, the others go through
+// __shfl_xor.  Called by a whole wavefront.
+__device__ __forceinline__ void wave_bitonic_sort4(unsigned (&v)[4])
+{
+    const unsigned lane = (unsigned)lane_id();
+#pragma unroll
+    for (unsigned k = 2; k <= 256; k <<= 1) {
+#pragma unroll
+        for (unsigned j = k >> 1; j > 0; j >>= 1) {
+            if (j >= 4) {
+#pragma unroll
+                for (unsigned r = 0; r < 4; ++r) {
+                    const unsigned e = 4 * lane + r;
+                    const unsigned other = __shfl_xor(v[r], (int)(j >> 2));
+                    const bool up = (e & k) == 0, lower = (e & j) == 0;
+                    v[r] = (lower == up) ? min(v[r], other) : max(v[r], other);
+                }
+            } else {
+#pragma unroll
+                for (unsigned r = 0; r < 4; ++r) {
+                    if ((r & j) == 0) {
+                        const unsigned e = 4 * lane + r;
+                        const bool up = (e & k) == 0;
+                        const unsigned a = v[r], b = v[r ^ j];
+                        v[r] = up ? min(a, b) : max(a, b);
+                        v[r ^ j] = up ? max(a, b) : min(a, b);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // Prepare kernel of qadc_search: Tables (Eq. (1)), the init scan and the quantizer of
 // Section 3.3, the pair tables and the seed sample of the scan, all in one launch.  Every
 // workgroup recomputes the query's (tiny) tables for itself -- 16 x d subtractions and
@@ -203,6 +237,7 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
 // before the sample can be scanned; workgroup 0 writes the tables out.  The arithmetic is
 // the one of build_luts_kernel and quantize_luts_kernel, operation for operation.
 constexpr int PREP_MAX_D = 2048;
+constexpr int PREP_INIT_PER_LANE = 4;  // init codes per lane of the wavefront that selects qmax
 
 template <int B>
 __global__ __launch_bounds__(1024) void prepare_u8_kernel(
@@ -249,11 +284,20 @@ __global__ __launch_bounds__(1024) void prepare_u8_kernel(
 #pragma unroll
         for (int t = 0; t < DREG; ++t) cv[t] = (t < dsub) ? c[t] : 0.0f;
     }
-    unsigned cw[B / 4];
-    if (tid < n_init) {
-        const unsigned *c = reinterpret_cast<const unsigned *>(codes + (size_t)tid * B);
+    // init codes: wavefront 0 takes up to 4 per lane (the usual init of a few hundred codes)
+    constexpr int IPL = PREP_INIT_PER_LANE;
+    const bool small_init = n_init <= WAVE * IPL;  // uniform
+    unsigned cw[IPL][B / 4];
+    if (small_init && tid < WAVE) {
 #pragma unroll
-        for (int k = 0; k < B / 4; ++k) cw[k] = c[k];
+        for (int r = 0; r < IPL; ++r) {
+            const int i = tid * IPL + r;
+            if (i < n_init) {
+                const unsigned *c = reinterpret_cast<const unsigned *>(codes + (size_t)i * B);
+#pragma unroll
+                for (int k = 0; k < B / 4; ++k) cw[r][k] = c[k];
+            }
+        }
     }
     asm volatile("" ::: "memory");
     uint4 w[2];
@@ -291,62 +335,57 @@ __global__ __launch_bounds__(1024) void prepare_u8_kernel(
     __syncthreads();
 
     // qmax: the min(R, n_init)-th smallest float ADC distance (float32, increasing j) of the init codes
-    for (int i = tid; i < n_init; i += NT) {
-        float acc = 0.0f;
-        if (i == tid) {
+    const unsigned need = (unsigned)min(R, n_init);
+    if (small_init) {
+        // uniform.  Wavefront 0 alone: four distances per lane, a bitonic sort of the 256 values
+        // across the wavefront (no workgroup barrier), the need-th smallest read off.
+        if (tid < WAVE) {
+            unsigned v[IPL];
 #pragma unroll
-            for (int jb = 0; jb < B; ++jb) {
-                const unsigned comps = (cw[jb >> 2] >> (8 * (jb & 3))) & 0xffu;
-                acc = acc + lut[(2 * jb) * 16 + (comps & 15u)];
-                acc = acc + lut[(2 * jb + 1) * 16 + (comps >> 4)];
+            for (int r = 0; r < IPL; ++r) {
+                v[r] = 0xffffffffu;  // slots beyond the init codes sort last
+                if (tid * IPL + r < n_init) {
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int jb = 0; jb < B; ++jb) {
+                        const unsigned comps = (cw[r][jb >> 2] >> (8 * (jb & 3))) & 0xffu;
+                        acc = acc + lut[(2 * jb) * 16 + (comps & 15u)];
+                        acc = acc + lut[(2 * jb + 1) * 16 + (comps >> 4)];
+                    }
+                    v[r] = f2ord(acc);
+                }
             }
-        } else {
+            wave_bitonic_sort4(v);
+            const unsigned want = need - 1u;  // element index: lane want / 4, slot want % 4
+            const unsigned pick = (want & 3u) == 0u ? v[0] : (want & 3u) == 1u ? v[1] : (want & 3u) == 2u ? v[2] : v[3];
+            const unsigned kth = __shfl(pick, (int)(want >> 2));
+            if (tid == 0) qmax_ord = kth;
+        }
+    } else {
+        for (int i = tid; i < n_init; i += NT) {
             const uint8_t *c = codes + (size_t)i * B;
+            float acc = 0.0f;
             for (int jb = 0; jb < B; ++jb) {
                 const unsigned comps = c[jb];
                 acc = acc + lut[(2 * jb) * 16 + (comps & 15u)];
                 acc = acc + lut[(2 * jb + 1) * 16 + (comps >> 4)];
             }
+            cand[i] = f2ord(acc);
         }
-        cand[i] = f2ord(acc);
-    }
-    __syncthreads();
-    const unsigned need = (unsigned)min(R, n_init);
-    if (n_init <= 256) {
-        // uniform: select by counting.  Thread (i, part) compares candidate i = tid & 255 with
-        // candidates 64*part .. 64*part+63, fetched four at a time, and counts the smaller ones;
-        // unused slots hold the largest value.  Only the VALUE of the need-th smallest is
-        // wanted: it is the largest candidate with fewer than `need` smaller ones.
-        if (tid >= n_init && tid < 256) cand[tid] = 0xffffffffu;
-        if (tid == 0) qmax_ord = 0u;
         __syncthreads();
-        const int i = tid & 255, part = tid >> 8;
-        const unsigned mine = cand[i];
-        unsigned lt = 0;
-        const uint4 *c4 = reinterpret_cast<const uint4 *>(cand) + part * 16;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const uint4 o = c4[v];
-            lt += (o.x < mine) + (o.y < mine) + (o.z < mine) + (o.w < mine);
-        }
-        if (i < n_init) atomicAdd(&sc.hist[i], lt);
-        __syncthreads();
-        if (tid < n_init && sc.hist[tid] < need) atomicMax(&qmax_ord, cand[tid]);
-        __syncthreads();
-        if (tid < 256) sc.hist[tid] = 0;
-    } else {
         const unsigned kth = block_radix_select<unsigned, 4>(cand, (unsigned)n_init, need, &sc);
         if (tid == 0) qmax_ord = kth;
         __syncthreads();
         for (int e = tid; e < 256; e += NT) sc.hist[e] = 0;
     }
-    __syncthreads();
 
-    // quantizer of Section 3.3
-    if (tid < M) {
-        float b = lut[tid * 16];
-        for (int i = 1; i < 16; ++i) b = fminf(b, lut[tid * 16 + i]);
-        bias[tid] = b;
+    // quantizer of Section 3.3 (the per-table minima do not wait for qmax: the last wavefront
+    // computes them while the first one sorts)
+    if (tid >= NT - M) {
+        const int j = tid - (NT - M);
+        float b = lut[j * 16];
+        for (int i = 1; i < 16; ++i) b = fminf(b, lut[j * 16 + i]);
+        bias[j] = b;
     }
     __syncthreads();
     if (tid == 0) {
