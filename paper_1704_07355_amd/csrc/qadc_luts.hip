@@ -53,7 +53,7 @@ int build_luts(const float *codebooks, int d, int m, int ksub, const float *quer
 
 // -------------------------------------------------------------- Section 3.3
 
-constexpr int QUANT_NT = 256;
+constexpr int QUANT_NT = 1024;
 constexpr int QUANT_MAX_M = 64;
 
 __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
@@ -99,9 +99,22 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
         qmax = qmax_in[q];
     }
 
-    // bias_j = minimum of table j over every table set of the query
-    for (int e = tid; e < ngroup * entries; e += QUANT_NT)
-        atomicMin(&bias_ord[(e % entries) >> 4], f2ord(lq[e]));
+    // bias_j = minimum of table j over every table set of the query.  A thread meets the same
+    // table positions in every set (entries and the thread count divide one another): minimum in
+    // a register first, one LDS atomic per position.
+    if (entries >= QUANT_NT) {
+        for (int pos = tid; pos < entries; pos += QUANT_NT) {
+            unsigned mn = 0xffffffffu;
+            for (int g = 0; g < ngroup; ++g) mn = min(mn, f2ord(lq[(size_t)g * entries + pos]));
+            atomicMin(&bias_ord[pos >> 4], mn);
+        }
+    } else {
+        const int pos = tid % entries;
+        unsigned mn = 0xffffffffu;
+        for (int g = tid / entries; g < ngroup; g += QUANT_NT / entries)
+            mn = min(mn, f2ord(lq[(size_t)g * entries + pos]));
+        atomicMin(&bias_ord[pos >> 4], mn);
+    }
     __syncthreads();
     if (tid == 0) {
         float qmin;

@@ -178,6 +178,8 @@ __device__ __forceinline__ float ord2f(unsigned o)
 constexpr int MERGE_NT = 1024;
 constexpr int MERGE_CAP = 6144;   // keys staged in LDS
 constexpr int MERGE_WG_PER_THREAD = 8;
+constexpr int MERGE_FLAT_G = 256;        // regions and ...
+constexpr int MERGE_FLAT_SLOTS = 16384;  // ... key slots up to which every slot is visited
 
 // R best of the keys reported by the G workgroups of each query (64-bit keys
 // dist << 32 | index, at most R per workgroup), ordered; then everything the call wrote
@@ -205,6 +207,7 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     __shared__ SelectScratch sc;
     __shared__ unsigned lcnt, ccnt;
     __shared__ unsigned long long all_or, all_and;
+    __shared__ unsigned fcnt[MERGE_FLAT_G];
 
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
@@ -254,31 +257,44 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
             atomicAdd(&sc.hist[(unsigned)(k >> 32) & 255u], 1u);
         }
     };
+    // Few, well-filled regions (inverted-index scans, short databases): every slot of every
+    // region is visited, a slot per thread at a time, so that the loads are spread over the whole
+    // workgroup instead of one thread walking each region.
+    const bool flat = G <= MERGE_FLAT_G && (size_t)G * pitch <= (size_t)MERGE_FLAT_SLOTS;  // uniform
     unsigned mycnt[MERGE_WG_PER_THREAD];
+    if (flat) {
+        for (int g = tid; g < G; g += MERGE_NT) fcnt[g] = min(counts[g], (unsigned)pitch);
+        __syncthreads();
+        for (unsigned sidx = tid; sidx < (unsigned)G * pitch; sidx += MERGE_NT) {
+            const unsigned g = sidx / (unsigned)pitch, i = sidx - g * (unsigned)pitch;
+            if (i < fcnt[g]) take(lists[sidx]);
+        }
+    } else {
 #pragma unroll
-    for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
-        const int g = tid + t * MERGE_NT;
-        mycnt[t] = 0;
-        if (g < G) {
-            // count and first key fetched together: most regions hold zero or one key
-            const unsigned c = min(counts[g], (unsigned)pitch);
-            const uint64_t *l = lists + (size_t)g * pitch;
-            const uint64_t k0 = l[0];
-            mycnt[t] = c;
-            if (c) take(k0);
-            for (unsigned i = 1; i < c; i += 4) {  // four loads in flight
-                uint64_t k[4];
+        for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
+            const int g = tid + t * MERGE_NT;
+            mycnt[t] = 0;
+            if (g < G) {
+                // count and first key fetched together: most regions hold zero or one key
+                const unsigned c = min(counts[g], (unsigned)pitch);
+                const uint64_t *l = lists + (size_t)g * pitch;
+                const uint64_t k0 = l[0];
+                mycnt[t] = c;
+                if (c) take(k0);
+                for (unsigned i = 1; i < c; i += 4) {  // four loads in flight
+                    uint64_t k[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) k[u] = (i + u < c) ? l[i + u] : 0;
+                    for (int u = 0; u < 4; ++u) k[u] = (i + u < c) ? l[i + u] : 0;
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (i + u < c) take(k[u]);
+                    for (int u = 0; u < 4; ++u)
+                        if (i + u < c) take(k[u]);
+                }
             }
         }
-    }
-    for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {  // very wide grids
-        const unsigned c = min(counts[g], (unsigned)pitch);
-        for (unsigned i = 0; i < c; ++i) take(lists[(size_t)g * pitch + i]);
+        for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {  // very wide grids
+            const unsigned c = min(counts[g], (unsigned)pitch);
+            for (unsigned i = 0; i < c; ++i) take(lists[(size_t)g * pitch + i]);
+        }
     }
     if constexpr (ADAPT) {
         if (my_or != 0ull || my_and != ~0ull) {
@@ -382,18 +398,27 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
 
     // Leave every word this call wrote in the workspace zero again, so that the next call
     // finds clean control blocks wherever its own layout puts them.
-#pragma unroll
-    for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
-        const int g = tid + t * MERGE_NT;
-        if (g < G && mycnt[t]) {
-            for (unsigned i = 0; i < mycnt[t]; ++i) lists[(size_t)g * pitch + i] = 0;
-            counts[g] = 0;
+    if (flat) {
+        for (unsigned sidx = tid; sidx < (unsigned)G * pitch; sidx += MERGE_NT) {
+            const unsigned g = sidx / (unsigned)pitch, i = sidx - g * (unsigned)pitch;
+            if (i < fcnt[g]) lists[sidx] = 0;
         }
-    }
-    for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {
-        const unsigned c = min(counts[g], (unsigned)pitch);
-        for (unsigned i = 0; i < c; ++i) lists[(size_t)g * pitch + i] = 0;
-        if (c) counts[g] = 0;
+        for (int g = tid; g < G; g += MERGE_NT)
+            if (fcnt[g]) counts[g] = 0;
+    } else {
+#pragma unroll
+        for (int t = 0; t < MERGE_WG_PER_THREAD; ++t) {
+            const int g = tid + t * MERGE_NT;
+            if (g < G && mycnt[t]) {
+                for (unsigned i = 0; i < mycnt[t]; ++i) lists[(size_t)g * pitch + i] = 0;
+                counts[g] = 0;
+            }
+        }
+        for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {
+            const unsigned c = min(counts[g], (unsigned)pitch);
+            for (unsigned i = 0; i < c; ++i) lists[(size_t)g * pitch + i] = 0;
+            if (c) counts[g] = 0;
+        }
     }
     if (redone) {  // the abandoned report of the tiled kernel
         unsigned *ca = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + countsA_off);
