@@ -11,6 +11,7 @@ namespace {
 struct Pair { hipEvent_t a, b; int which; };
 bool g_on = false;
 std::vector<Pair> g_open;
+std::vector<hipEvent_t> g_free;   // events kept for reuse: creating one costs host time per launch
 double g_ms[QADC_PROF_COUNT];
 int64_t g_launches[QADC_PROF_COUNT];
 }  // namespace
@@ -20,8 +21,16 @@ bool prof_open(int which, hipEvent_t *start, hipEvent_t *stop)
     if (!g_on) return false;
     Pair p;
     p.which = which;
-    if (hipEventCreate(&p.a) != hipSuccess) return false;
-    if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return false; }
+    hipEvent_t *ev[2] = {&p.a, &p.b};
+    for (int i = 0; i < 2; ++i) {
+        if (!g_free.empty()) {
+            *ev[i] = g_free.back();
+            g_free.pop_back();
+        } else if (hipEventCreate(ev[i]) != hipSuccess) {
+            if (i) g_free.push_back(p.a);
+            return false;
+        }
+    }
     g_open.push_back(p);
     *start = p.a;
     *stop = p.b;
@@ -36,8 +45,8 @@ static void drain()
             g_ms[p.which] += ms;
             g_launches[p.which] += 1;
         }
-        (void)hipEventDestroy(p.a);
-        (void)hipEventDestroy(p.b);
+        g_free.push_back(p.a);
+        g_free.push_back(p.b);
     }
     g_open.clear();
 }
