@@ -11,7 +11,8 @@ slow and unblocked, so that it can be checked against the text by eye:
                        quantizers opq(x) = pq(R x), R orthonormal
   Section 2.2          inverted index, residual encoding
   Section 2.3, Alg. 1  Index / Tables / Scan, Eq. (1) tables, Eq. (2) ADC
-  Section 3.2, Fig. 2  two 4-bit components per byte, low nibble = even one
+  Section 3.2, Fig. 2  two 4-bit components per byte, low nibble = even one;
+                       lists transposed by blocks of 16 codes
   Section 3.3          8-bit quantization of the tables, qmin / qmax / Delta
   Section 3.4, Alg. 2  lookup, saturating add, top-R
 
@@ -54,7 +55,10 @@ non-increasing distortion and recovery of well-separated clusters.  The OPQ
 trainer is pinned by the orthonormality of R, by a distortion that does not grow
 from round to round, and by data that a known rotation makes separable per
 sub-space (it must get close to the distortion reached with that rotation);
-opq_rotate by permutation and block-rotation matrices worked by hand.
+opq_rotate by permutation and block-rotation matrices worked by hand.  The
+transposed layout of Fig. 2b is pinned by a block written out by hand, the
+positions of single bytes of a ragged list, and by Alg. 2 run over its blocks
+and rows giving the sums of the standard-layout scan and of the plain definition.
 """
 
 from __future__ import annotations
@@ -226,6 +230,66 @@ def unpack_nibbles(codes: np.ndarray) -> np.ndarray:
     comps[:, 0::2] = codes & 0x0F
     comps[:, 1::2] = codes >> 4
     return comps
+
+
+# --------------------------------------------------------------------------
+# Section 3.2 / Fig. 2b: lists transposed by blocks of 16 codes
+# --------------------------------------------------------------------------
+
+BLOCK = 16  # codes per block: one byte of 16 codes fills a 128-bit register
+
+
+def transposed_bytes(n: int, m: int) -> int:
+    """Size of a list of n codes in the transposed layout: whole blocks of 16 * m/2 bytes."""
+    return -(-n // BLOCK) * BLOCK * (m // 2)
+
+
+def pack_transposed(codes: np.ndarray) -> np.ndarray:
+    """Standard layout uint8 [n][m/2] -> transposed layout, flat uint8.
+
+    Each block of 16 codes (a .. p) is stored as m/2 rows of 16 bytes; row j holds
+    byte j (components 2j and 2j+1) of a, b, .. p in this order.  The last block
+    is filled up with zero bytes.
+    """
+    codes = np.asarray(codes, dtype=np.uint8)
+    n, half = codes.shape
+    nblk = -(-n // BLOCK)
+    out = np.zeros((nblk, half, BLOCK), dtype=np.uint8)
+    for i in range(n):  # code i is column i % 16 of block i // 16
+        out[i // BLOCK, :, i % BLOCK] = codes[i]
+    return out.reshape(-1)
+
+
+def unpack_transposed(packed: np.ndarray, n: int, m: int) -> np.ndarray:
+    """Inverse of pack_transposed for a list of n codes."""
+    half = m // 2
+    blocks = np.asarray(packed, dtype=np.uint8).reshape(-1, half, BLOCK)
+    out = np.empty((n, half), dtype=np.uint8)
+    for i in range(n):
+        out[i] = blocks[i // BLOCK, :, i % BLOCK]
+    return out
+
+
+def scan_blocks_transposed(qlut: np.ndarray, packed: np.ndarray, n: int, nbins: int = 255) -> np.ndarray:
+    """Alg. 2 quick_adc_scan over a block-transposed list: block by block, row by row.
+
+    A row is one "register" of 16 bytes; the accumulator holds the 16 sums of the
+    block.  Low nibbles -> table 2j, saturating add; shift by four; -> table 2j+1,
+    saturating add.  Returns the sums of the n codes of the list.
+    """
+    m = qlut.shape[0]
+    half = m // 2
+    blocks = np.asarray(packed, dtype=np.uint8).reshape(-1, half, BLOCK)
+    out = np.empty(len(blocks) * BLOCK, dtype=np.uint8)
+    for b, blk in enumerate(blocks):
+        acc = np.zeros(BLOCK, dtype=np.int64)
+        for j in range(half):
+            comps = blk[j]
+            acc = np.minimum(nbins, acc + qlut[2 * j][comps & 0x0F])
+            comps = comps >> 4
+            acc = np.minimum(nbins, acc + qlut[2 * j + 1][comps & 0x0F])
+        out[b * BLOCK:(b + 1) * BLOCK] = acc
+    return out[:n]
 
 
 # --------------------------------------------------------------------------

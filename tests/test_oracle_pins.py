@@ -92,6 +92,32 @@ def test_nibble_layout():
     assert O.pack_nibbles(c).shape == (1000, 16)
 
 
+def test_transposed_layout_by_hand_and_block_scan():
+    # Fig. 2b: a block of 16 codes a..p becomes m/2 rows; row j = byte j of a, b, .. p.
+    # Hand-made block, m = 4: code c has bytes (0x10 + c, 0xA0 + c).
+    codes = np.array([[0x10 + c, 0xA0 + c] for c in range(16)], dtype=np.uint8)
+    packed = O.pack_transposed(codes)
+    assert packed.tolist() == [0x10 + c for c in range(16)] + [0xA0 + c for c in range(16)]
+    # a ragged list: 37 codes of m = 16 -> three blocks of 16 * 8 bytes, zero filled
+    rng = np.random.default_rng(11)
+    codes = rng.integers(0, 256, size=(37, 8), dtype=np.uint8)
+    packed = O.pack_transposed(codes)
+    assert len(packed) == O.transposed_bytes(37, 16) == 3 * 128
+    assert packed[2 * 128 + 0 * 16 + 4] == codes[36, 0] and packed[2 * 128 + 7 * 16 + 4] == codes[36, 7]
+    assert not packed.reshape(3, 8, 16)[2, :, 5:].any()
+    assert packed[1 * 128 + 3 * 16 + 9] == codes[25, 3]        # block 1, row 3, column 9
+    assert np.array_equal(O.unpack_transposed(packed, 37, 16), codes)
+    # Alg. 2 run over blocks and rows gives the sums of the scan over the standard layout,
+    # and the plain definition min(n, sum of the 16 looked-up entries)
+    qlut = rng.integers(0, 90, size=(16, 16), dtype=np.uint8)
+    for nbins in (255, 127):
+        got = O.scan_blocks_transposed(qlut, packed, 37, nbins)
+        assert np.array_equal(got, O.scan_saturating(qlut, codes, nbins))
+        comps = O.unpack_nibbles(codes)
+        brute = [min(nbins, sum(int(qlut[j][comps[i, j]]) for j in range(16))) for i in range(37)]
+        assert got.tolist() == brute
+
+
 def test_c_encode_matches_numpy(tiny_pq):
     cb, x = tiny_pq["codebooks"], tiny_pq["base"][:5000]
     assert np.array_equal(cref.pq_encode(x, cb), O.pack_nibbles(O.pq_encode(x, cb)))
