@@ -196,8 +196,8 @@ size_t qadc_ivf_workspace_bytes(const qadc_ivf_index *ix, int nq, int nprobe, in
 
 /*
  * Database side, Section 2.1: enc(x) = (i_0 .. i_{m-1}), i_j = index of the centroid of
- * sub-quantizer j closest to sub-vector x^j (float32 distances from the differences,
- * ties to the lowest index), written in the standard layout.  Not on the query
+ * sub-quantizer j closest to sub-vector x^j (float64 distances from the differences, summed in
+ * increasing component order; ties to the lowest index), written in the standard layout.  Not on the query
  * path; it exists to build large databases directly in HBM.
  *   codebooks [m][ksub][d/m] f32, ksub in {16, 256} (m even when ksub == 16)
  *   x         [n][d] f32
@@ -205,6 +205,56 @@ size_t qadc_ivf_workspace_bytes(const qadc_ivf_index *ix, int nq, int nprobe, in
  */
 int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *x, int64_t n,
                    uint8_t *codes, void *stream);
+
+/*
+ * List layouts, Section 3.2 and Fig. 2.  QADC_LAYOUT_STANDARD is the layout every scan of this
+ * library reads (Fig. 2a).  QADC_LAYOUT_TRANSPOSED is the paper's offline re-layout (Fig. 2b):
+ * the list is cut into blocks of 16 codes and each block is stored as m/2 rows of 16 bytes, row
+ * j holding byte j (components 2j and 2j+1) of the block's 16 codes in order; the last block is
+ * filled with zero bytes.  qadc_pack_codes writes a list in `layout` from the standard one,
+ * qadc_unpack_codes restores the standard list (a database kept in the transposed layout is
+ * converted once before it is scanned here); with QADC_LAYOUT_STANDARD both are a copy.
+ * qadc_packed_bytes is the size of a list of n codes in `layout` (0 on bad arguments).
+ *   std_codes [n][m/2] u8;  packed [qadc_packed_bytes(n, m, layout)] u8; m in {8, 16, 32, 64};
+ *   both 16-byte aligned and distinct.
+ */
+#define QADC_LAYOUT_STANDARD   0
+#define QADC_LAYOUT_TRANSPOSED 1
+size_t qadc_packed_bytes(int64_t n, int m, int layout);
+int qadc_pack_codes(const uint8_t *std_codes, int64_t n, int m, int layout, uint8_t *packed,
+                    void *stream);
+int qadc_unpack_codes(const uint8_t *packed, int64_t n, int m, int layout, uint8_t *std_codes,
+                      void *stream);
+
+/*
+ * Building an inverted index, Section 2.2 (database side, not on the query path).
+ *
+ * qadc_ivf_assign: cells[i] = index of the coarse centroid closest to x[i] (the vector
+ * quantizer q_i; float64 distances from the differences, ties to the lowest cell).
+ *   coarse [K][d] f32;  x [n][d] f32;  cells [n] i32 (output)
+ *
+ * qadc_ivf_group: the list order of the database, a stable grouping by cell:
+ * list_off[c] = number of vectors in cells below c (list_off[K] = n) and
+ * ids[list_off[c] + r] = the r-th vector of cell c in input order -- the `list_off` and `ids`
+ * of qadc_ivf_index.  An entry of `cells` outside [0, K) is left out (list_off[K] < n then).
+ *   cells [n] i32, n <= 2^32;  K <= 2^24;  list_off [K+1] i64 (output);  ids [n] u32 (output)
+ *   workspace >= qadc_ivf_group_workspace_bytes(n, K), 16-byte aligned; it need not be cleared
+ *   and is not left cleared.
+ *
+ * qadc_ivf_encode: the codes of the index in list order: row p encodes the residual
+ * x[ids[p]] - coarse[cells[ids[p]]] (float32 subtraction) with the product quantizer
+ * `codebooks` as qadc_pq_encode does (ksub = 16).  A row whose id or cell is out of range is
+ * written as zero bytes.
+ *   x [n][d] f32;  cells [n] i32;  ids [n_list] u32;  codes [n_list][m/2] u8 (output)
+ */
+int qadc_ivf_assign(const float *coarse, int K, int d, const float *x, int64_t n, int32_t *cells,
+                    void *stream);
+size_t qadc_ivf_group_workspace_bytes(int64_t n, int K);
+int qadc_ivf_group(const int32_t *cells, int64_t n, int K, int64_t *list_off, uint32_t *ids,
+                   void *workspace, size_t workspace_bytes, void *stream);
+int qadc_ivf_encode(const float *coarse, int K, const float *codebooks, int d, int m, const float *x,
+                    int64_t n, const int32_t *cells, const uint32_t *ids, int64_t n_list,
+                    uint8_t *codes, void *stream);
 
 /*
  * Rotation of an optimized product quantizer, Section 2.1: opq(x) = pq(R x), R^T R = I.

@@ -24,12 +24,14 @@ QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
 QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT, QADC_WS_SEARCH = 0, 1, 2, 3
 (QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES,
  QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE, QADC_PROF_ROTATE) = range(9)
+QADC_LAYOUT_STANDARD, QADC_LAYOUT_TRANSPOSED = 0, 1
 
 EXPORTS = (
     "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
     "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train", "qadc_rotate",
     "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
-    "qadc_last_error", "qadc_version",
+    "qadc_last_error", "qadc_version", "qadc_packed_bytes", "qadc_pack_codes", "qadc_unpack_codes",
+    "qadc_ivf_assign", "qadc_ivf_group_workspace_bytes", "qadc_ivf_group", "qadc_ivf_encode",
 )
 
 _lib = None
@@ -84,6 +86,20 @@ def lib() -> ctypes.CDLL:
         L.qadc_workspace_bytes.restype = sz
         L.qadc_workspace_init.argtypes = [vp, sz, vp]
         L.qadc_workspace_init.restype = i32
+        L.qadc_packed_bytes.argtypes = [i64, i32, i32]
+        L.qadc_packed_bytes.restype = sz
+        L.qadc_pack_codes.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.qadc_pack_codes.restype = i32
+        L.qadc_unpack_codes.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.qadc_unpack_codes.restype = i32
+        L.qadc_ivf_assign.argtypes = [vp, i32, i32, vp, i64, vp, vp]
+        L.qadc_ivf_assign.restype = i32
+        L.qadc_ivf_group_workspace_bytes.argtypes = [i64, i32]
+        L.qadc_ivf_group_workspace_bytes.restype = sz
+        L.qadc_ivf_group.argtypes = [vp, i64, i32, vp, vp, vp, sz, vp]
+        L.qadc_ivf_group.restype = i32
+        L.qadc_ivf_encode.argtypes = [vp, i32, vp, i32, i32, vp, i64, vp, vp, i64, vp, vp]
+        L.qadc_ivf_encode.restype = i32
         L.qadc_last_error.restype = ctypes.c_char_p
         L.qadc_version.restype = ctypes.c_char_p
         _lib = L
@@ -209,6 +225,75 @@ def qadc_rotate(rot, x, out=None):
         out = torch.empty((n, d), dtype=torch.float32, device=x.device)
     _check(lib().qadc_rotate(_ptr(rot, torch.float32), d, _ptr(x, torch.float32), n, _ptr(out, torch.float32),
                              _stream()))
+    return out
+
+
+def qadc_packed_bytes(n: int, m: int, layout: int) -> int:
+    return int(lib().qadc_packed_bytes(n, m, layout))
+
+
+def qadc_pack_codes(std_codes, layout, out=None):
+    """std_codes u8 [n][m/2] -> the list in `layout`, flat u8 [qadc_packed_bytes(n, m, layout)]."""
+    n, half = std_codes.shape
+    if out is None:
+        out = torch.empty((qadc_packed_bytes(n, 2 * half, layout),), dtype=torch.uint8, device=std_codes.device)
+    _check(lib().qadc_pack_codes(_ptr(std_codes, torch.uint8), n, 2 * half, layout, _ptr(out, torch.uint8),
+                                 _stream()))
+    return out
+
+
+def qadc_unpack_codes(packed, n, m, layout, out=None):
+    """packed flat u8 (n codes in `layout`) -> std codes u8 [n][m/2]."""
+    if out is None:
+        out = torch.empty((n, m // 2), dtype=torch.uint8, device=packed.device)
+    _check(lib().qadc_unpack_codes(_ptr(packed, torch.uint8), n, m, layout, _ptr(out, torch.uint8), _stream()))
+    return out
+
+
+def qadc_ivf_assign(coarse, x, out=None):
+    """coarse f32 [K][d], x f32 [n][d] -> cells i32 [n]."""
+    K, d = coarse.shape
+    n = x.shape[0]
+    assert x.shape[1] == d
+    if out is None:
+        out = torch.empty((n,), dtype=torch.int32, device=x.device)
+    _check(lib().qadc_ivf_assign(_ptr(coarse, torch.float32), K, d, _ptr(x, torch.float32), n,
+                                 _ptr(out, torch.int32), _stream()))
+    return out
+
+
+def qadc_ivf_group_workspace_bytes(n: int, K: int) -> int:
+    return int(lib().qadc_ivf_group_workspace_bytes(n, K))
+
+
+def qadc_ivf_group(cells, K, workspace=None):
+    """cells i32 [n] -> (list_off i64 [K+1], ids u32 [n]) as torch int64 / int32-typed-as-uint32 tensors.
+
+    ids is returned as an int32 tensor holding the uint32 bit patterns (torch has no uint32 arithmetic).
+    """
+    n = cells.shape[0]
+    if workspace is None:
+        workspace = torch.empty((max(16, qadc_ivf_group_workspace_bytes(n, K)),), dtype=torch.uint8,
+                                device=cells.device)
+    list_off = torch.empty((K + 1,), dtype=torch.int64, device=cells.device)
+    ids = torch.zeros((n,), dtype=torch.int32, device=cells.device)
+    _check(lib().qadc_ivf_group(_ptr(cells, torch.int32), n, K, _ptr(list_off, torch.int64),
+                                _ptr(ids, torch.int32), _ptr(workspace, torch.uint8), workspace.numel(),
+                                _stream()))
+    return list_off, ids
+
+
+def qadc_ivf_encode(coarse, codebooks, x, cells, ids, out=None):
+    """Residual codes in list order: row p = enc(x[ids[p]] - coarse[cells[ids[p]]]); u8 [len(ids)][m/2]."""
+    K, d = coarse.shape
+    m = codebooks.shape[0]
+    n = x.shape[0]
+    n_list = ids.shape[0]
+    if out is None:
+        out = torch.empty((n_list, m // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().qadc_ivf_encode(_ptr(coarse, torch.float32), K, _ptr(codebooks, torch.float32), d, m,
+                                 _ptr(x, torch.float32), n, _ptr(cells, torch.int32), _ptr(ids, torch.int32),
+                                 n_list, _ptr(out, torch.uint8), _stream()))
     return out
 
 

@@ -35,6 +35,13 @@ int scan_topk_f32(int, const uint8_t *, int64_t, int, const float *, int, int, u
 size_t scan_topk_f32_workspace(int, int64_t, int, int, int);
 int pq_encode(const float *, int, int, int, const float *, int64_t, uint8_t *, hipStream_t);
 int rotate(const float *, int, const float *, int64_t, float *, hipStream_t);
+size_t packed_bytes(int64_t, int, int);
+int relayout(bool, const uint8_t *, int64_t, int, int, uint8_t *, hipStream_t);
+int ivf_assign(const float *, int, int, const float *, int64_t, int32_t *, hipStream_t);
+size_t ivf_group_workspace(int64_t, int);
+int ivf_group(const int32_t *, int64_t, int, int64_t *, uint32_t *, void *, size_t, hipStream_t);
+int ivf_encode(const float *, int, const float *, int, int, const float *, int64_t, const int32_t *,
+               const uint32_t *, int64_t, uint8_t *, hipStream_t);
 int workspace_init(void *, size_t, hipStream_t);
 int pq_train(const float *, int64_t, int, int, int, const int64_t *, int, float *, void *, size_t,
              hipStream_t);
@@ -115,6 +122,40 @@ int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *
 int qadc_rotate(const float *rot, int d, const float *x, int64_t n, float *y, void *stream)
 {
     return qadc::rotate(rot, d, x, n, y, (hipStream_t)stream);
+}
+
+size_t qadc_packed_bytes(int64_t n, int m, int layout) { return qadc::packed_bytes(n, m, layout); }
+
+int qadc_pack_codes(const uint8_t *std_codes, int64_t n, int m, int layout, uint8_t *packed, void *stream)
+{
+    return qadc::relayout(true, std_codes, n, m, layout, packed, (hipStream_t)stream);
+}
+
+int qadc_unpack_codes(const uint8_t *packed, int64_t n, int m, int layout, uint8_t *std_codes, void *stream)
+{
+    return qadc::relayout(false, packed, n, m, layout, std_codes, (hipStream_t)stream);
+}
+
+int qadc_ivf_assign(const float *coarse, int K, int d, const float *x, int64_t n, int32_t *cells,
+                    void *stream)
+{
+    return qadc::ivf_assign(coarse, K, d, x, n, cells, (hipStream_t)stream);
+}
+
+size_t qadc_ivf_group_workspace_bytes(int64_t n, int K) { return qadc::ivf_group_workspace(n, K); }
+
+int qadc_ivf_group(const int32_t *cells, int64_t n, int K, int64_t *list_off, uint32_t *ids,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return qadc::ivf_group(cells, n, K, list_off, ids, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int qadc_ivf_encode(const float *coarse, int K, const float *codebooks, int d, int m, const float *x,
+                    int64_t n, const int32_t *cells, const uint32_t *ids, int64_t n_list,
+                    uint8_t *codes, void *stream)
+{
+    return qadc::ivf_encode(coarse, K, codebooks, d, m, x, n, cells, ids, n_list, codes,
+                            (hipStream_t)stream);
 }
 
 int qadc_profile_enable(int on) { return qadc::profile_enable(on); }

@@ -1,7 +1,7 @@
 // Database side of product quantization on gfx950 (Section 2.1 of the paper):
 // enc(x) = (i_0 .. i_{m-1}), i_j = argmin_i || x^j - C^j[i] ||^2, written in the
-// standard code layout.  Used to build large synthetic databases in HBM; it is
-// not on the query path.
+// standard code layout; for an inverted index (Section 2.2) the vector encoded at storage
+// position p is the residual x[ids[p]] - coarse[cells[ids[p]]].  Not on the query path.
 
 #include "qadc_common.h"
 
@@ -9,30 +9,44 @@ namespace qadc {
 
 // One thread per output byte.  ksub == 16: the byte holds components 2jb (low
 // nibble) and 2jb+1 (high nibble); ksub == 256: the byte is component jb.
-// Distances in float32 from the differences; ties go to the lowest index.
+// Distances in float64 from the float32 differences' exact values, summed in increasing t with
+// separate multiply and add; ties go to the lowest index.  With `coarse`, row r of the output
+// encodes the float32 residual of vector ids[r].
 template <int KSUB>
 __global__ __launch_bounds__(256) void pq_encode_kernel(
     const float *__restrict__ codebooks, int d, int m, const float *__restrict__ x, int64_t n,
-    uint8_t *__restrict__ codes)
+    uint8_t *__restrict__ codes, const float *__restrict__ coarse, int K, const int32_t *__restrict__ cells,
+    const uint32_t *__restrict__ ids, int64_t n_x)
 {
+#pragma clang fp contract(off)
     const int dsub = d / m;
     const int row = (KSUB == 16) ? m / 2 : m;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= n * row) return;
     const int64_t r = gid / row;
     const int jb = (int)(gid - r * row);
+    const int64_t src = ids ? (int64_t)ids[r] : r;
+    const float *base = nullptr;
+    if (coarse) {  // an id or a cell out of range: a zero byte, no access
+        if (src >= n_x) { codes[gid] = 0; return; }
+        const int c = cells[src];
+        if (c < 0 || c >= K) { codes[gid] = 0; return; }
+        base = coarse + (size_t)c * d;
+    }
     const int ncomp = (KSUB == 16) ? 2 : 1;
     unsigned out = 0;
     for (int h = 0; h < ncomp; ++h) {
         const int j = (KSUB == 16) ? 2 * jb + h : jb;
-        const float *xs = x + r * d + (int64_t)j * dsub;
+        const float *xs = x + src * d + (int64_t)j * dsub;
+        const float *bs = base ? base + (int64_t)j * dsub : nullptr;
         const float *cb = codebooks + (size_t)j * KSUB * dsub;
-        float best = __builtin_inff();
+        double best = __builtin_inf();
         unsigned arg = 0;
         for (int i = 0; i < KSUB; ++i) {
-            float acc = 0.0f;
+            double acc = 0.0;
             for (int t = 0; t < dsub; ++t) {
-                const float df = xs[t] - cb[i * dsub + t];
+                const float xv = bs ? xs[t] - bs[t] : xs[t];
+                const double df = (double)xv - (double)cb[i * dsub + t];
                 acc += df * df;
             }
             if (acc < best) { best = acc; arg = (unsigned)i; }
@@ -42,24 +56,40 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(
     codes[gid] = (uint8_t)out;
 }
 
+static int encode_launch(const char *name, const float *codebooks, int d, int m, int ksub, const float *x,
+                         int64_t n, uint8_t *codes, const float *coarse, int K, const int32_t *cells,
+                         const uint32_t *ids, int64_t n_x, hipStream_t st)
+{
+    if (m < 1 || d < 1 || d % m != 0 || (ksub != 16 && ksub != 256) || (ksub == 16 && (m & 1)) || n < 0)
+        return fail(QADC_EINVAL, "%s: unsupported d=%d m=%d ksub=%d", name, d, m, ksub);
+    if (n == 0) return QADC_OK;
+    if (!codebooks || !x || !codes) return fail(QADC_EINVAL, "%s: null pointer", name);
+    const int64_t total = n * (ksub == 16 ? m / 2 : m);
+    const int64_t blocks = ceil_div(total, 256);
+    if (blocks > 0x7fffffffll) return fail(QADC_EINVAL, "%s: n too large for one call", name);
+    if (ksub == 16)
+        hipLaunchKernelGGL(pq_encode_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, st, codebooks, d,
+                           m, x, n, codes, coarse, K, cells, ids, n_x);
+    else
+        hipLaunchKernelGGL(pq_encode_kernel<256>, dim3((unsigned)blocks), dim3(256), 0, st, codebooks,
+                           d, m, x, n, codes, coarse, K, cells, ids, n_x);
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
 int pq_encode(const float *codebooks, int d, int m, int ksub, const float *x, int64_t n,
               uint8_t *codes, hipStream_t st)
 {
-    if (!codebooks || !x || !codes) return fail(QADC_EINVAL, "qadc_pq_encode: null pointer");
-    if (m < 1 || d % m != 0 || (ksub != 16 && ksub != 256) || (ksub == 16 && (m & 1)) || n < 0)
-        return fail(QADC_EINVAL, "qadc_pq_encode: unsupported d=%d m=%d ksub=%d", d, m, ksub);
-    if (n == 0) return QADC_OK;
-    const int64_t total = n * (ksub == 16 ? m / 2 : m);
-    const int64_t blocks = ceil_div(total, 256);
-    if (blocks > 0x7fffffffll) return fail(QADC_EINVAL, "qadc_pq_encode: n too large for one call");
-    if (ksub == 16)
-        hipLaunchKernelGGL(pq_encode_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, st, codebooks, d,
-                           m, x, n, codes);
-    else
-        hipLaunchKernelGGL(pq_encode_kernel<256>, dim3((unsigned)blocks), dim3(256), 0, st, codebooks,
-                           d, m, x, n, codes);
-    QADC_HIP_TRY(hipGetLastError());
-    return QADC_OK;
+    return encode_launch("qadc_pq_encode", codebooks, d, m, ksub, x, n, codes, nullptr, 0, nullptr, nullptr, n, st);
+}
+
+// codes[p] = enc(x[ids[p]] - coarse[cells[ids[p]]]) for the n_list storage positions p
+int ivf_encode(const float *coarse, int K, const float *codebooks, int d, int m, const float *x, int64_t n,
+               const int32_t *cells, const uint32_t *ids, int64_t n_list, uint8_t *codes, hipStream_t st)
+{
+    if (K < 1 || n < 0) return fail(QADC_EINVAL, "qadc_ivf_encode: K=%d n=%lld", K, (long long)n);
+    if (n_list > 0 && (!coarse || !cells || !ids)) return fail(QADC_EINVAL, "qadc_ivf_encode: null pointer");
+    return encode_launch("qadc_ivf_encode", codebooks, d, m, 16, x, n_list, codes, coarse, K, cells, ids, n, st);
 }
 
 }  // namespace qadc

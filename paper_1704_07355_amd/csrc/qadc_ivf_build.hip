@@ -1,0 +1,293 @@
+// Database side of the inverted index on gfx950 (Section 2.2 of the paper): which cell a vector
+// falls in, and the list order of a database.
+//
+//   assign   cell(x) = index of the closest coarse centroid (float64 distances from the
+//            differences, ties to the lowest cell) -- the vector quantizer q_i of Section 2.2.
+//   group    a stable grouping by cell: list_off[c] = number of vectors in cells < c, and
+//            ids[list_off[c] + r] = the r-th vector (in input order) of cell c.
+//
+// The codes of the residuals are then written in list order by the encoder (qadc_encode.hip).
+//
+// assign: a workgroup of 256 threads takes 64 vectors and walks over all cells 64 at a time;
+// 16 components of both go through LDS as float64 per step, every thread accumulates 4 x 4
+// distances (one subtraction and one fused multiply-add per component) and keeps, per vector,
+// the best of the cells it has seen; the 16 threads of a vector compare their candidates at the
+// end under the order (distance, cell).  Vector-ALU bound: 2 float64 operations per (vector,
+// cell, component).
+//
+// group: the database is cut into P contiguous parts, one wavefront per part.  Pass 1 counts
+// cnt[part][cell]; a column pass turns each column into running sums over the parts and yields
+// the list sizes; one workgroup scans those into list_off; in pass 2 every wavefront walks its
+// part 64 vectors at a time: lanes of the same cell find each other with one ballot per bit of
+// the cell id, the first of them advances cnt[part][cell] by their number with one atomic, and
+// each lane's position is list_off[cell] + that value + its rank among them.  Positions depend
+// only on the input, never on timing: a part's counters are touched by its wavefront alone.
+
+#include "qadc_common.h"
+#include <algorithm>
+
+namespace qadc {
+
+constexpr int ASG_TM = 64;  // vectors per workgroup
+constexpr int ASG_TN = 64;  // cells per step
+constexpr int ASG_TK = 16;  // components per step
+
+__global__ __launch_bounds__(256) void ivf_assign_kernel(const float *__restrict__ coarse, int K, int d,
+                                                         const float *__restrict__ x, int64_t n,
+                                                         int32_t *__restrict__ cells)
+{
+    __shared__ double xs[ASG_TK][ASG_TM + 1];
+    __shared__ double cs[ASG_TK][ASG_TN + 1];
+    __shared__ double cand_d[ASG_TM][16];
+    __shared__ int cand_c[ASG_TM][16];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;  // cells 4*tx.., vectors 4*ty..
+    const int64_t i0 = (int64_t)blockIdx.x * ASG_TM;
+    double best_d[4];
+    int best_c[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) { best_d[a] = __builtin_inf(); best_c[a] = 0x7fffffff; }
+
+    for (int c0 = 0; c0 < K; c0 += ASG_TN) {
+        double acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+        for (int t0 = 0; t0 < d; t0 += ASG_TK) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int idx = tid + e * 256;
+                const int row = idx >> 4, col = idx & 15;
+                const int t = t0 + col;
+                const int64_t i = i0 + row;
+                const int c = c0 + row;
+                xs[col][row] = (i < n && t < d) ? (double)x[i * d + t] : 0.0;
+                cs[col][row] = (c < K && t < d) ? (double)coarse[(size_t)c * d + t] : 0.0;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < ASG_TK; ++kk) {
+                double xv[4], cv[4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) xv[a] = xs[kk][4 * ty + a];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) cv[b] = cs[kk][4 * tx + b];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const double df = xv[a] - cv[b];
+                        acc[a][b] = fma(df, df, acc[a][b]);
+                    }
+            }
+            __syncthreads();
+        }
+        // cells in increasing order and a strict comparison: the lowest cell wins a tie
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int c = c0 + 4 * tx + b;
+                if (c < K && acc[a][b] < best_d[a]) { best_d[a] = acc[a][b]; best_c[a] = c; }
+            }
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        cand_d[4 * ty + a][tx] = best_d[a];
+        cand_c[4 * ty + a][tx] = best_c[a];
+    }
+    __syncthreads();
+    if (tid < ASG_TM) {
+        const int64_t i = i0 + tid;
+        if (i < n) {
+            double bd = cand_d[tid][0];
+            int bc = cand_c[tid][0];
+            for (int k = 1; k < 16; ++k) {
+                const double dd = cand_d[tid][k];
+                const int cc = cand_c[tid][k];
+                if (dd < bd || (dd == bd && cc < bc)) { bd = dd; bc = cc; }
+            }
+            cells[i] = bc;
+        }
+    }
+}
+
+int ivf_assign(const float *coarse, int K, int d, const float *x, int64_t n, int32_t *cells, hipStream_t st)
+{
+    if (K < 1 || d < 1 || n < 0)
+        return fail(QADC_EINVAL, "qadc_ivf_assign: K=%d d=%d n=%lld", K, d, (long long)n);
+    if (n == 0) return QADC_OK;
+    if (!coarse || !x || !cells) return fail(QADC_EINVAL, "qadc_ivf_assign: null pointer");
+    const int64_t grid = ceil_div(n, ASG_TM);
+    if (grid > 0x7fffffffll) return fail(QADC_EINVAL, "qadc_ivf_assign: n too large for one call");
+    hipLaunchKernelGGL(ivf_assign_kernel, dim3((unsigned)grid), dim3(256), 0, st, coarse, K, d, x, n, cells);
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+// ------------------------------------------------------------------ group
+
+constexpr int GRP_MAX_PARTS = 1024;
+constexpr int64_t GRP_MIN_PART = 4096;       // vectors per part, at least
+constexpr int64_t GRP_MAX_COUNTERS = 1ll << 26;  // parts * K, at most (256 MiB of counters)
+constexpr int GRP_MAX_K = 1 << 24;
+
+struct GroupPlan {
+    int P;
+    int64_t part;  // vectors per part, a multiple of 64
+    size_t cnt_off, size_off, total;
+};
+
+static bool make_group_plan(int64_t n, int K, GroupPlan *g)
+{
+    if (n < 0 || n > 0xffffffffll || K < 1 || K > GRP_MAX_K) return false;
+    int64_t P = std::max<int64_t>(1, std::min<int64_t>(GRP_MAX_PARTS, n / GRP_MIN_PART));
+    P = std::max<int64_t>(1, std::min<int64_t>(P, GRP_MAX_COUNTERS / K));
+    g->P = (int)P;
+    g->part = std::max<int64_t>(64, ceil_div(ceil_div(std::max<int64_t>(n, 1), P), 64) * 64);
+    g->cnt_off = 0;
+    g->size_off = align_up((size_t)P * K * sizeof(unsigned), 256);
+    g->total = g->size_off + align_up((size_t)K * sizeof(unsigned), 256);
+    return true;
+}
+
+size_t ivf_group_workspace(int64_t n, int K)
+{
+    GroupPlan g;
+    return make_group_plan(n, K, &g) ? g.total : 0;
+}
+
+__global__ void grp_zero_kernel(uint4 *p, size_t n16)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// one wavefront per part: cnt[part][cell] += 1
+__global__ __launch_bounds__(256) void grp_count_kernel(const int32_t *__restrict__ cells, int64_t n, int K,
+                                                        int64_t part, int P, unsigned *__restrict__ cnt)
+{
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= P) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t lo = (int64_t)w * part, hi = min(n, lo + part);
+    unsigned *row = cnt + (size_t)w * K;
+    for (int64_t i = lo + lane; i < hi; i += 64) {
+        const int c = cells[i];
+        if (c >= 0 && c < K) atomicAdd(&row[c], 1u);
+    }
+}
+
+// one thread per cell: the column becomes its running sums over the parts; size[cell] = its total
+__global__ __launch_bounds__(256) void grp_column_kernel(unsigned *__restrict__ cnt, int K, int P,
+                                                         unsigned *__restrict__ size)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= K) return;
+    unsigned run = 0;
+    for (int p = 0; p < P; ++p) {
+        const unsigned v = cnt[(size_t)p * K + c];
+        cnt[(size_t)p * K + c] = run;
+        run += v;
+    }
+    size[c] = run;
+}
+
+// one workgroup: list_off = exclusive running sum of size, list_off[K] = total
+__global__ __launch_bounds__(1024) void grp_offsets_kernel(const unsigned *__restrict__ size, int K,
+                                                           int64_t *__restrict__ list_off)
+{
+    __shared__ unsigned long long wsum[16];
+    __shared__ unsigned long long carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int c0 = 0; c0 < K; c0 += 1024) {
+        const int c = c0 + tid;
+        const unsigned long long v = c < K ? size[c] : 0;
+        unsigned long long inc = v;  // inclusive sum inside the wavefront
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            const unsigned long long o = __shfl_up(inc, s);
+            if (lane >= s) inc += o;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        unsigned long long before = carry_s;
+        for (int k = 0; k < wave; ++k) before += wsum[k];
+        if (c < K) list_off[c] = (int64_t)(before + inc - v);
+        __syncthreads();
+        if (tid == 1023) carry_s = before + inc;
+        __syncthreads();
+    }
+    if (tid == 0) list_off[K] = (int64_t)carry_s;
+}
+
+// one wavefront per part, 64 vectors per step, in input order
+__global__ __launch_bounds__(256) void grp_place_kernel(const int32_t *__restrict__ cells, int64_t n, int K,
+                                                        int nbits, int64_t part, int P,
+                                                        unsigned *__restrict__ cnt,
+                                                        const int64_t *__restrict__ list_off,
+                                                        uint32_t *__restrict__ ids)
+{
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= P) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t lo = (int64_t)w * part, hi = min(n, lo + part);
+    unsigned *row = cnt + (size_t)w * K;
+    for (int64_t s = lo; s < hi; s += 64) {  // uniform over the wavefront
+        const int64_t i = s + lane;
+        const int c = i < hi ? cells[i] : -1;
+        const bool valid = c >= 0 && c < K;
+        unsigned long long peers = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (c >> b) & 1;
+            const unsigned long long m = __ballot(valid && bit);
+            peers &= bit ? m : ~m;
+        }
+        if (valid) {  // peers holds this lane at least
+            const int leader = __ffsll((long long)peers) - 1;
+            unsigned base = 0;
+            if (lane == leader) base = atomicAdd(&row[c], (unsigned)__popcll(peers));
+            base = __shfl(base, leader);
+            const int64_t pos = list_off[c] + base + rank_in_mask(peers);
+            ids[pos] = (uint32_t)i;
+        }
+    }
+}
+
+int ivf_group(const int32_t *cells, int64_t n, int K, int64_t *list_off, uint32_t *ids, void *workspace,
+              size_t workspace_bytes, hipStream_t st)
+{
+    GroupPlan g;
+    if (!make_group_plan(n, K, &g))
+        return fail(QADC_EINVAL, "qadc_ivf_group: n=%lld (at most 2^32) K=%d (at most 2^24)", (long long)n, K);
+    if (!list_off || !workspace || (n > 0 && (!cells || !ids)))
+        return fail(QADC_EINVAL, "qadc_ivf_group: null pointer");
+    if (workspace_bytes < g.total || ((uintptr_t)workspace & 15))
+        return fail(QADC_ENOMEM, "qadc_ivf_group: workspace of %zu bytes, %zu needed (16-byte aligned)",
+                    workspace_bytes, g.total);
+    char *ws = (char *)workspace;
+    unsigned *cnt = (unsigned *)(ws + g.cnt_off);
+    unsigned *size = (unsigned *)(ws + g.size_off);
+    const size_t n16 = g.total / 16;
+    hipLaunchKernelGGL(grp_zero_kernel, dim3((unsigned)std::min<size_t>(4096, ceil_div(n16, 256))), dim3(256), 0,
+                       st, (uint4 *)ws, n16);
+    const unsigned wg = (unsigned)ceil_div(g.P, 4);
+    if (n > 0)
+        hipLaunchKernelGGL(grp_count_kernel, dim3(wg), dim3(256), 0, st, cells, n, K, g.part, g.P, cnt);
+    hipLaunchKernelGGL(grp_column_kernel, dim3((unsigned)ceil_div(K, 256)), dim3(256), 0, st, cnt, K, g.P, size);
+    hipLaunchKernelGGL(grp_offsets_kernel, dim3(1), dim3(1024), 0, st, size, K, list_off);
+    if (n > 0) {
+        int nbits = 1;
+        while ((1ll << nbits) < K) ++nbits;
+        hipLaunchKernelGGL(grp_place_kernel, dim3(wg), dim3(256), 0, st, cells, n, K, nbits, g.part, g.P, cnt,
+                           list_off, ids);
+    }
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+}  // namespace qadc
