@@ -38,10 +38,12 @@ HBM_PEAK_GBPS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--workload", choices=["scan", "batched", "ivf", "compare"], default="scan",
+    ap.add_argument("--workload", choices=["scan", "batched", "ivf", "compare", "build"], default="scan",
                     help="scan: config 2, one query at a time (default); batched: config 3, query batches "
                          "over 128-bit codes; ivf: config 4, inverted index with Zipf-skewed lists; "
-                         "compare: config 5, 8-bit PQ with float tables against Quick ADC on the same vectors")
+                         "compare: config 5, 8-bit PQ with float tables against Quick ADC on the same vectors; "
+                         "build: database side, an inverted index built from raw vectors (assign, group, "
+                         "encode residuals, transposed layout)")
     ap.add_argument("--K", type=int, default=65536, help="coarse centroids of the ivf workload")
     ap.add_argument("--nprobe", type=int, default=64)
     ap.add_argument("--steps", type=int, default=None)
@@ -74,7 +76,8 @@ def parse():
     dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200),
             "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000),
             "ivf": dict(steps=4, warmup=1, n=1_000_000_000, m=32, init=1000),
-            "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200)}[args.workload]
+            "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200),
+            "build": dict(steps=3, warmup=1, n=4_000_000, m=16, init=200)}[args.workload]
     for k, v in dflt.items():
         if getattr(args, k) is None:
             setattr(args, k, v)
@@ -566,16 +569,119 @@ def run_compare(args):
         "database_build_s": round(t_build, 2)}))
 
 
+def run_build(args):
+    """Database side: a step = one inverted index built from n raw vectors already in HBM
+    (qadc_ivf_assign, qadc_ivf_group, qadc_ivf_encode, then the list in the paper's transposed layout
+    and back).  Vectors: coarse centroid of a Zipf-weighted cell plus N(0, 18^2) noise."""
+    import numpy as np
+    import torch
+    import paper_1704_07355_amd as Q
+    from workloads import MixtureSpec, SEED_BASE, SEED_TRAIN, zipf_list_sizes, kmeans_init_rows
+    from workloads.mixture_torch import mixture_vectors_torch
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n, m, d = args.n, args.m, args.d
+    K = args.K if args.K != 65536 else 4096
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED_BASE * 31 + 5)
+    coarse = mixture_vectors_torch(MixtureSpec(d=d), SEED_TRAIN, 0, K, dev)
+    sizes = zipf_list_sizes(n, K, 0.8, SEED_BASE)
+    home = torch.multinomial(torch.from_numpy(sizes / sizes.sum()).to(dev), n, replacement=True, generator=gen)
+    x = (coarse[home] + 18.0 * torch.randn((n, d), generator=gen, device=dev)).contiguous()
+    del home
+    train = 18.0 * torch.randn((20_000, d), generator=gen, device=dev)
+    cb = Q.qadc_pq_train(train.contiguous(), m, 16, torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev), 10)
+    ws = torch.empty((Q.qadc_ivf_group_workspace_bytes(n, K),), dtype=torch.uint8, device=dev)
+    cells = torch.empty((n,), dtype=torch.int32, device=dev)
+    codes = torch.empty((n, m // 2), dtype=torch.uint8, device=dev)
+    packed = torch.empty((Q.qadc_packed_bytes(n, m, Q.QADC_LAYOUT_TRANSPOSED),), dtype=torch.uint8, device=dev)
+    back = torch.empty_like(codes)
+    names = ["assign", "group", "encode", "pack", "unpack"]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
+
+    def step(timed):
+        if timed:
+            ev[0].record()
+        Q.qadc_ivf_assign(coarse, x, out=cells)
+        if timed:
+            ev[1].record()
+        list_off, ids = Q.qadc_ivf_group(cells, K, workspace=ws)
+        if timed:
+            ev[2].record()
+        Q.qadc_ivf_encode(coarse, cb, x, cells, ids, out=codes)
+        if timed:
+            ev[3].record()
+        Q.qadc_pack_codes(codes, Q.QADC_LAYOUT_TRANSPOSED, out=packed)
+        if timed:
+            ev[4].record()
+        Q.qadc_unpack_codes(packed, n, m, Q.QADC_LAYOUT_TRANSPOSED, out=back)
+        if timed:
+            ev[5].record()
+        return list_off, ids
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    phase = dict.fromkeys(names, 0.0)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        list_off, ids = step(True)
+        torch.cuda.synchronize()
+        for i, k in enumerate(names):
+            phase[k] += ev[i].elapsed_time(ev[i + 1])
+    wall = (time.perf_counter() - t0) / args.steps
+    phase = {k: v / args.steps for k, v in phase.items()}
+    assert torch.equal(back, codes)
+
+    # the oracle builds the index of the first rows; same cells, and the same codes for those rows
+    cpu = None
+    if args.cpu_queries > 0:
+        from oracle import qadc_oracle as O
+        ns = min(n, 1500)
+        xs, cs, cbs = x[:ns].cpu().numpy(), coarse.cpu().numpy(), cb.cpu().numpy()
+        t1 = time.perf_counter()
+        ix = O.ivf_build(xs, cs, cbs)
+        secs = time.perf_counter() - t1
+        want_cells = O.ivf_assign(xs, cs)
+        inv = torch.empty((n,), dtype=torch.int64, device=dev)
+        inv[ids.long() & 0xFFFFFFFF] = torch.arange(n, device=dev)
+        mine = codes[inv[:ns]].cpu().numpy()           # code of input row i
+        theirs = np.empty_like(mine)
+        theirs[ix["ids"]] = ix["codes"]
+        same = bool(np.array_equal(cells[:ns].cpu().numpy(), want_cells) and np.array_equal(mine, theirs))
+        cpu = {"value": round(ns / secs, 1), "unit": "vectors/s", "cores": 1, "kind": "oracle",
+               "sample": "first %d vectors, NumPy oracle ivf_build against K=%d cells" % (ns, K),
+               "seconds": round(secs, 2), "gpu_matches_oracle": same}
+    flops = 3.0 * n * K * d                       # a subtraction and a fused multiply-add per component
+    out = {"metric": "vectors/s (inverted index built from raw vectors: assign + group + encode)",
+           "value": round(n / ((phase["assign"] + phase["group"] + phase["encode"]) * 1e-3), 1),
+           "unit": "vectors/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(wall * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f64", "data": "synthetic",
+           "config": {"workload": "index build: n=%d vectors d=%d, K=%d coarse centroids, m=%d x 4-bit residual codes"
+                                  % (n, d, K, m), "n": n, "d": d, "K": K, "m": m},
+           "phase_ms": {k: round(v, 3) for k, v in phase.items()},
+           "roofline": {"bound": "alu", "kernel": "ivf_assign_kernel", "achieved": round(flops / (phase["assign"] * 1e-3) / 1e12, 2),
+                        "peak": 78.6, "unit": "TFLOP/s", "frac": round(flops / (phase["assign"] * 1e-3) / 78.6e12, 4),
+                        "traffic": None},
+           "layout_gb_per_s": {"pack": round(2 * codes.numel() / (phase["pack"] * 1e-3) / 1e9, 1),
+                               "unpack": round(2 * codes.numel() / (phase["unpack"] * 1e-3) / 1e9, 1)},
+           "cpu_baseline": cpu}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
               "(no collectives, no sharding in this library)" % args.gpus, file=sys.stderr)
         sys.exit(2)
-    if args.workload in ("batched", "ivf", "compare"):
+    if args.workload in ("batched", "ivf", "compare", "build"):
         import paper_1704_07355_amd as Q
         Q.lib()
-        return {"batched": run_batched, "ivf": run_ivf, "compare": run_compare}[args.workload](args)
+        return {"batched": run_batched, "ivf": run_ivf, "compare": run_compare,
+                "build": run_build}[args.workload](args)
 
     import numpy as np
     import torch

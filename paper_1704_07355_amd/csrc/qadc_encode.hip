@@ -56,6 +56,69 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(
     codes[gid] = (uint8_t)out;
 }
 
+// ksub == 16 with the codebooks in LDS as [j][t][16] floats: one thread per output byte; for each
+// component it reads x^j[t] once and advances the 16 distances together, each still summed in
+// increasing t.  Same arithmetic and result as pq_encode_kernel<16>.
+__global__ __launch_bounds__(256) void pq_encode16_lds_kernel(
+    const float *__restrict__ codebooks, int d, int m, const float *__restrict__ x, int64_t n,
+    uint8_t *__restrict__ codes, const float *__restrict__ coarse, int K, const int32_t *__restrict__ cells,
+    const uint32_t *__restrict__ ids, int64_t n_x)
+{
+#pragma clang fp contract(off)
+    extern __shared__ __attribute__((aligned(16))) float cbt[];   // [m][dsub][16]
+    const int dsub = d / m;
+    for (int e = threadIdx.x; e < d * 16; e += 256) {
+        const int j = e / (16 * dsub), rem = e - j * 16 * dsub;   // codebooks[j][i][t]
+        const int i = rem / dsub, t = rem - i * dsub;
+        cbt[(j * dsub + t) * 16 + i] = codebooks[e];
+    }
+    __syncthreads();
+    const int row = m / 2;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= n * row) return;
+    const int64_t r = gid / row;
+    const int jb = (int)(gid - r * row);
+    const int64_t src = ids ? (int64_t)ids[r] : r;
+    const float *base = nullptr;
+    if (coarse) {
+        if (src >= n_x) { codes[gid] = 0; return; }
+        const int c = cells[src];
+        if (c < 0 || c >= K) { codes[gid] = 0; return; }
+        base = coarse + (size_t)c * d;
+    }
+    unsigned out = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int j = 2 * jb + h;
+        const float *xs = x + src * d + (int64_t)j * dsub;
+        const float *bs = base ? base + (int64_t)j * dsub : nullptr;
+        double acc[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.0;
+        for (int t = 0; t < dsub; ++t) {
+            const float xv = bs ? xs[t] - bs[t] : xs[t];
+            const float4 *c4 = reinterpret_cast<const float4 *>(cbt + (j * dsub + t) * 16);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 c = c4[q];
+                const float cv[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const double df = (double)xv - (double)cv[k];
+                    acc[4 * q + k] += df * df;
+                }
+            }
+        }
+        double best = __builtin_inf();
+        unsigned arg = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (acc[i] < best) { best = acc[i]; arg = (unsigned)i; }
+        out |= arg << (4 * h);
+    }
+    codes[gid] = (uint8_t)out;
+}
+
 static int encode_launch(const char *name, const float *codebooks, int d, int m, int ksub, const float *x,
                          int64_t n, uint8_t *codes, const float *coarse, int K, const int32_t *cells,
                          const uint32_t *ids, int64_t n_x, hipStream_t st)
@@ -67,7 +130,10 @@ static int encode_launch(const char *name, const float *codebooks, int d, int m,
     const int64_t total = n * (ksub == 16 ? m / 2 : m);
     const int64_t blocks = ceil_div(total, 256);
     if (blocks > 0x7fffffffll) return fail(QADC_EINVAL, "%s: n too large for one call", name);
-    if (ksub == 16)
+    if (ksub == 16 && (size_t)d * 64 <= 65536)
+        hipLaunchKernelGGL(pq_encode16_lds_kernel, dim3((unsigned)blocks), dim3(256), (size_t)d * 64, st,
+                           codebooks, d, m, x, n, codes, coarse, K, cells, ids, n_x);
+    else if (ksub == 16)
         hipLaunchKernelGGL(pq_encode_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, st, codebooks, d,
                            m, x, n, codes, coarse, K, cells, ids, n_x);
     else

@@ -8,8 +8,8 @@
 //
 // The codes of the residuals are then written in list order by the encoder (qadc_encode.hip).
 //
-// assign: a workgroup of 256 threads takes 64 vectors and walks over all cells 64 at a time;
-// 16 components of both go through LDS as float64 per step, every thread accumulates 4 x 4
+// assign: a workgroup of 256 threads takes 128 vectors and walks over all cells 128 at a time;
+// 16 components of both go through LDS as float64 per step, every thread accumulates 8 x 8
 // distances (one subtraction and one fused multiply-add per component) and keeps, per vector,
 // the best of the cells it has seen; the 16 threads of a vector compare their candidates at the
 // end under the order (distance, cell).  Vector-ALU bound: 2 float64 operations per (vector,
@@ -28,35 +28,40 @@
 
 namespace qadc {
 
-constexpr int ASG_TM = 64;  // vectors per workgroup
-constexpr int ASG_TN = 64;  // cells per step
-constexpr int ASG_TK = 16;  // components per step
+constexpr int ASG_TM = 128;  // vectors per workgroup
+constexpr int ASG_TN = 128;  // cells per step
+constexpr int ASG_TK = 16;   // components per step
+constexpr int ASG_LD = ASG_TM + 2;  // row stride in doubles: keeps 16-byte alignment, shifts the banks
 
+// Thread (tx, ty), tx = tid & 15, ty = tid >> 4, owns the vectors 8*ty .. 8*ty+7 of the tile and
+// the cells 32*k + 2*tx + e (k < 4, e < 2): a wavefront's 16-byte reads of the cells are
+// contiguous across its lanes, its reads of the vectors are the same for 16 lanes.
 __global__ __launch_bounds__(256) void ivf_assign_kernel(const float *__restrict__ coarse, int K, int d,
                                                          const float *__restrict__ x, int64_t n,
                                                          int32_t *__restrict__ cells)
 {
-    __shared__ double xs[ASG_TK][ASG_TM + 1];
-    __shared__ double cs[ASG_TK][ASG_TN + 1];
+    __shared__ __attribute__((aligned(16))) double xs[ASG_TK][ASG_LD];
+    __shared__ __attribute__((aligned(16))) double cs[ASG_TK][ASG_LD];
     __shared__ double cand_d[ASG_TM][16];
     __shared__ int cand_c[ASG_TM][16];
     const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;  // cells 4*tx.., vectors 4*ty..
+    const int tx = tid & 15, ty = tid >> 4;
     const int64_t i0 = (int64_t)blockIdx.x * ASG_TM;
-    double best_d[4];
-    int best_c[4];
+    double best_d[8];
+    int best_c[8];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) { best_d[a] = __builtin_inf(); best_c[a] = 0x7fffffff; }
+    for (int a = 0; a < 8; ++a) { best_d[a] = __builtin_inf(); best_c[a] = 0x7fffffff; }
 
     for (int c0 = 0; c0 < K; c0 += ASG_TN) {
-        double acc[4][4];
+        double acc[8][8];
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 8; ++a)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+            for (int b = 0; b < 8; ++b) acc[a][b] = 0.0;
         for (int t0 = 0; t0 < d; t0 += ASG_TK) {
+            // 128 x 16 elements of x and of the centroids, eight of each per thread, zero beyond the edges
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < 8; ++e) {
                 const int idx = tid + e * 256;
                 const int row = idx >> 4, col = idx & 15;
                 const int t = t0 + col;
@@ -66,36 +71,45 @@ __global__ __launch_bounds__(256) void ivf_assign_kernel(const float *__restrict
                 cs[col][row] = (c < K && t < d) ? (double)coarse[(size_t)c * d + t] : 0.0;
             }
             __syncthreads();
-#pragma unroll
+#pragma unroll 4
             for (int kk = 0; kk < ASG_TK; ++kk) {
-                double xv[4], cv[4];
+                double xv[8], cv[8];
 #pragma unroll
-                for (int a = 0; a < 4; ++a) xv[a] = xs[kk][4 * ty + a];
+                for (int a = 0; a < 8; a += 2) {
+                    const double2 v = *reinterpret_cast<const double2 *>(&xs[kk][8 * ty + a]);
+                    xv[a] = v.x; xv[a + 1] = v.y;
+                }
 #pragma unroll
-                for (int b = 0; b < 4; ++b) cv[b] = cs[kk][4 * tx + b];
+                for (int k = 0; k < 4; ++k) {
+                    const double2 v = *reinterpret_cast<const double2 *>(&cs[kk][32 * k + 2 * tx]);
+                    cv[2 * k] = v.x; cv[2 * k + 1] = v.y;
+                }
 #pragma unroll
-                for (int a = 0; a < 4; ++a)
+                for (int a = 0; a < 8; ++a)
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
+                    for (int b = 0; b < 8; ++b) {
                         const double df = xv[a] - cv[b];
                         acc[a][b] = fma(df, df, acc[a][b]);
                     }
             }
             __syncthreads();
         }
-        // cells in increasing order and a strict comparison: the lowest cell wins a tie
+        // the smaller distance wins, the lower cell among equal distances
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 8; ++a)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int c = c0 + 4 * tx + b;
-                if (c < K && acc[a][b] < best_d[a]) { best_d[a] = acc[a][b]; best_c[a] = c; }
+            for (int b = 0; b < 8; ++b) {
+                const int c = c0 + 32 * (b >> 1) + 2 * tx + (b & 1);
+                if (c < K && (acc[a][b] < best_d[a] || (acc[a][b] == best_d[a] && c < best_c[a]))) {
+                    best_d[a] = acc[a][b];
+                    best_c[a] = c;
+                }
             }
     }
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        cand_d[4 * ty + a][tx] = best_d[a];
-        cand_c[4 * ty + a][tx] = best_c[a];
+    for (int a = 0; a < 8; ++a) {
+        cand_d[8 * ty + a][tx] = best_d[a];
+        cand_c[8 * ty + a][tx] = best_c[a];
     }
     __syncthreads();
     if (tid < ASG_TM) {
