@@ -411,6 +411,20 @@ def scan_clamped(qlut: np.ndarray, codes: np.ndarray, nbins: int = 255) -> np.nd
     return np.minimum(total, nbins).astype(np.uint8)
 
 
+def scan_saturating_bytes(qlut: np.ndarray, comps: np.ndarray, nbins: int = 255) -> np.ndarray:
+    """The chain of Alg. 2 for 8-bit components: one byte and one 256-entry table per component.
+
+    The paper keeps 16-entry tables because a table has to fit a 128-bit register
+    (Section 3.1); where the tables live in a memory that takes 256 entries, the
+    quantization of Section 3.3 and the saturating sums apply unchanged to the
+    8-bit sub-quantizers of Section 2.1.  qlut uint8 [m][256], comps uint8 [n][m].
+    """
+    acc = np.zeros(len(comps), dtype=np.int64)
+    for j in range(qlut.shape[0]):
+        acc = np.minimum(nbins, acc + qlut[j][comps[:, j]])
+    return acc.astype(np.uint8)
+
+
 def top_r(dist: np.ndarray, R: int, pad_dist=None):
     """The R smallest under the order (dist, index), ascending.
 
@@ -453,6 +467,18 @@ def quick_adc_search(codebooks, query, codes, init, R, nbins=255, qmin_mode=QMIN
     idx, dist = top_r(sums, R, pad_dist=nbins)
     t.update(idx=idx, dist=dist)
     return t
+
+
+def quick_adc_bytes_search(codebooks, query, comps, init, R, nbins=255, qmin_mode=QMIN_PER_TABLE):
+    """Quick ADC with 8-bit sub-quantizers: Tables (Eq. 1, [m][256]), qmax from the first
+    `init` codes, the quantizer of Section 3.3, saturating scan, top-R.  comps uint8 [n][m]."""
+    lut = build_luts(codebooks, query[None, :])[0]
+    qmax = qmax_from_init(lut, comps[:min(init, len(comps))], R)
+    bias, delta = quantizer_params(lut, qmax, nbins, qmin_mode)
+    qlut = quantize_luts(lut, bias, delta, nbins)
+    sums = scan_saturating_bytes(qlut, comps, nbins)
+    idx, dist = top_r(sums, R, pad_dist=nbins)
+    return dict(lut=lut, qmax=qmax, bias=bias, delta=delta, qlut=qlut, idx=idx, dist=dist)
 
 
 def adc_search(codebooks, query, comps, R):

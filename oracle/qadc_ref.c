@@ -87,6 +87,17 @@ static inline unsigned qadc_one(const uint8_t *code, int m, const uint8_t *qlut,
     return acc;
 }
 
+/* The same chain for 8-bit components (one byte, one 256-entry table per component). */
+static inline unsigned qadc_one_bytes(const uint8_t *code, int m, const uint8_t *qlut, unsigned cap)
+{
+    unsigned acc = 0;
+    for (int j = 0; j < m; ++j) {
+        acc += qlut[j * 256 + code[j]];
+        if (acc > cap) acc = cap;
+    }
+    return acc;
+}
+
 /* Eq. (2) in float32, increasing j.  ksub 16 (nibbles) or 256 (bytes). */
 static inline float adc_one(const uint8_t *code, int m, int ksub, const float *lut)
 {
@@ -172,6 +183,28 @@ void ref_scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qlu
         const uint8_t *qlut = qluts + (size_t)q * m * 16;
         for (int64_t i = 0; i < n; ++i) {
             pair_t p = { (double)qadc_one(codes + i * (m / 2), m, qlut, (unsigned)cap), i };
+            heap_push(h, &len, R, p);
+        }
+        qsort(h, (size_t)len, sizeof(pair_t), pair_cmp);
+        for (int r = 0; r < R; ++r) {
+            out_idx[(size_t)q * R + r] = r < len ? (uint32_t)h[r].i : 0xFFFFFFFFu;
+            out_dist[(size_t)q * R + r] = r < len ? (uint8_t)h[r].d : (uint8_t)cap;
+        }
+        free(h);
+    }
+}
+
+/* Saturating scan of 8-bit codes [n][m] with quantized tables qluts [nq][m][256]. */
+void ref_scan_topk_u8_bytes(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, int nq,
+                            int cap, int R, uint32_t *out_idx, uint8_t *out_dist)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < nq; ++q) {
+        pair_t *h = (pair_t *)malloc(sizeof(pair_t) * (size_t)R);
+        int len = 0;
+        const uint8_t *qlut = qluts + (size_t)q * m * 256;
+        for (int64_t i = 0; i < n; ++i) {
+            pair_t p = { (double)qadc_one_bytes(codes + i * m, m, qlut, (unsigned)cap), i };
             heap_push(h, &len, R, p);
         }
         qsort(h, (size_t)len, sizeof(pair_t), pair_cmp);

@@ -298,6 +298,38 @@ def test_quantized_sum_brackets_float_adc(tiny_pq, nbins, mode):
 
 # ------------------------------------------------------------------ top-R
 
+def test_byte_component_variant_chain_bounds_and_c_twin():
+    # 8-bit sub-quantizers with quantized tables: the chain equals min(n, sum); an unsaturated sum
+    # s brackets the float ADC distance, B + Delta*s <= adc < B + Delta*(s+m); the plain-C twin
+    # returns the R best of the NumPy sums.
+    from oracle import cref
+    rng = np.random.default_rng(21)
+    m, k, dsub, n = 8, 256, 4, 3000
+    cb = rng.normal(scale=20, size=(m, k, dsub)).astype(np.float32)
+    x = rng.normal(scale=20, size=(n, m * dsub)).astype(np.float32)
+    comps = O.pq_encode(x, cb)
+    assert comps.shape == (n, m) and comps.max() > 15
+    y = rng.normal(scale=20, size=m * dsub).astype(np.float32)
+    for nbins, mode in ((255, O.QMIN_PER_TABLE), (127, O.QMIN_GLOBAL)):
+        r = O.quick_adc_bytes_search(cb, y, comps, 200, 50, nbins, mode)
+        sums = O.scan_saturating_bytes(r["qlut"], comps, nbins)
+        brute = np.array([min(nbins, sum(int(r["qlut"][j][comps[i, j]]) for j in range(m))) for i in range(n)])
+        assert np.array_equal(sums, brute)
+        adc = O.adc_float(r["lut"], comps).astype(np.float64)
+        B = float(r["bias"].astype(np.float64).sum())
+        D = float(r["delta"])
+        free = sums < nbins
+        assert free.any()
+        sf = sums[free].astype(np.int64)
+        lo, hi = B + D * sf, B + D * (sf + m)
+        tol = 1e-4 * np.abs(adc[free]) + 1e-3
+        assert (adc[free] >= lo - tol).all() and (adc[free] < hi + tol).all()
+        order = np.lexsort((np.arange(n), sums))[:50]
+        assert np.array_equal(r["idx"], order.astype(np.uint32)) and np.array_equal(r["dist"], sums[order])
+        ci, cd = cref.scan_topk_u8_bytes(comps, r["qlut"][None], 50, nbins)
+        assert np.array_equal(ci[0], r["idx"]) and np.array_equal(cd[0], r["dist"])
+
+
 def test_top_r_order_and_ties():
     rng = np.random.default_rng(9)
     s = rng.integers(0, 6, size=500).astype(np.uint8)  # massive ties
