@@ -28,8 +28,7 @@ def build(force: bool = True) -> str:
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(_SO):
-            build()
+        build(force=False)  # compiles when the library is missing or older than its source
         _lib = ctypes.CDLL(_SO)
         _lib.ref_num_threads.restype = ctypes.c_int
     return _lib
