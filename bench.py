@@ -442,6 +442,18 @@ def run_compare(args):
         Q.qadc_build_luts(cb8, queries[qi:qi + 1], out=luts8)
         Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, luts8, R, workspace=ws8, out_idx=idx8, out_dist=dist8)
 
+    # the 8-bit codes again, with their 256-entry tables quantized to uint8 and saturating sums
+    wsq = Q.qadc_workspace_init(torch.empty(Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_U8_8BIT, n, 8, 1, R),
+                                            dtype=torch.uint8, device=dev))
+    idxq = torch.empty((1, R), dtype=torch.int32, device=dev)
+    distq = torch.empty((1, R), dtype=torch.uint8, device=dev)
+
+    def pq8_u8(i):
+        qi = i % args.queries
+        Q.qadc_build_luts(cb8, queries[qi:qi + 1], out=luts8)
+        ql, _, _, _ = Q.qadc_quantize_luts(luts8, codes8[:init], R)
+        Q.qadc_scan_topk(Q.QADC_U8_8BIT, codes8, ql, R, workspace=wsq, out_idx=idxq, out_dist=distq)
+
     def timed(fn):
         for i in range(args.warmup):
             fn(i)
@@ -456,6 +468,7 @@ def run_compare(args):
 
     ms4 = timed(quick)
     ms8 = timed(pq8)
+    ms8q = timed(pq8_u8)
 
     # the same comparison on batches of 256 queries (one call each): Quick ADC shares code reads
     # between queries (query-tiled kernels), the float scan has no such form here
@@ -474,7 +487,10 @@ def run_compare(args):
 
     ms4b = timed_batch(lambda: Q.qadc_search(cb4, qb, codes4, R, init))
     ms8b = timed_batch(lambda: Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, luts8b, R))
+    ql8b = Q.qadc_quantize_luts(luts8b, codes8[:init], R)[0]
+    ms8qb = timed_batch(lambda: Q.qadc_scan_topk(Q.QADC_U8_8BIT, codes8, ql8b, R))
     batched = {"queries": nbq, "quick_adc_ms": round(ms4b, 3), "pq8_float_ms": round(ms8b, 3),
+               "pq8_uint8_tables_ms": round(ms8qb, 3),
                "quick_adc_gpairs_per_s": round(n * nbq / (ms4b * 1e-3) / 1e9, 1),
                "pq8_float_gpairs_per_s": round(n * nbq / (ms8b * 1e-3) / 1e9, 1),
                "speedup_quick_adc_over_pq8_float": round(ms8b / ms4b, 2)}
@@ -483,14 +499,15 @@ def run_compare(args):
     if not args.no_profile:
         nprof = min(args.steps, 200)
         per = {}
-        for name, fn in (("quick_adc", quick), ("pq8_float", pq8)):
+        for name, fn in (("quick_adc", quick), ("pq8_float", pq8), ("pq8_uint8_tables", pq8_u8)):
             Q.qadc_profile_enable(True)
             for i in range(nprof):
                 fn(i)
             torch.cuda.synchronize()
             per[name] = {}
             for k, which in (("scan", Q.QADC_PROF_SCAN), ("seed", Q.QADC_PROF_SEED), ("merge", Q.QADC_PROF_MERGE),
-                             ("tables", Q.QADC_PROF_TABLES), ("prepare", Q.QADC_PROF_PREPARE)):
+                             ("tables", Q.QADC_PROF_TABLES), ("quantize", Q.QADC_PROF_QUANTIZE),
+                             ("prepare", Q.QADC_PROF_PREPARE)):
                 ms, cnt = Q.qadc_profile_read(which)
                 if cnt:
                     per[name][k + "_us_per_query"] = round(ms / nprof * 1e3, 2)
@@ -512,7 +529,9 @@ def run_compare(args):
         qs = queries[:nq].contiguous()
         i4, _ = Q.qadc_search(cb4, qs, codes4, R, init)
         f4, _ = Q.qadc_scan_topk(Q.QADC_F32_4BIT, codes4, Q.qadc_build_luts(cb4, qs), R)
-        i8, _ = Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, Q.qadc_build_luts(cb8, qs), R)
+        l8 = Q.qadc_build_luts(cb8, qs)
+        i8, _ = Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, l8, R)
+        i8q, _ = Q.qadc_scan_topk(Q.QADC_U8_8BIT, codes8, Q.qadc_quantize_luts(l8, codes8[:init], R)[0], R)
         best = torch.full((nq,), float("inf"), device=dev)
         arg = torch.zeros((nq,), dtype=torch.int64, device=dev)
         qq = (qs * qs).sum(1)
@@ -525,13 +544,17 @@ def run_compare(args):
             arg[upd] = a[upd] + s
         torch.cuda.synchronize()
         nn = arg.cpu().numpy()
-        h = {k: v.cpu().numpy().view(np.uint32).astype(np.int64) for k, v in (("q", i4), ("f4", f4), ("f8", i8))}
+        h = {k: v.cpu().numpy().view(np.uint32).astype(np.int64)
+             for k, v in (("q", i4), ("f4", f4), ("f8", i8), ("q8", i8q))}
         rec = {k: float(np.mean([nn[i] in h[k][i] for i in range(nq)])) for k in h}
         ov = float(np.mean([len(np.intersect1d(a, b)) / R for a, b in zip(h["q"], h["f4"])]))
+        ov8 = float(np.mean([len(np.intersect1d(a, b)) / R for a, b in zip(h["q8"], h["f8"])]))
         acc = {"queries": nq, "nn_recall_at_R_quick_adc": round(rec["q"], 4),
                "nn_recall_at_R_float_adc_4bit_codes": round(rec["f4"], 4),
                "nn_recall_at_R_pq8_float": round(rec["f8"], 4),
+               "nn_recall_at_R_pq8_uint8_tables": round(rec["q8"], 4),
                "overlap_at_R_quick_vs_float_adc_same_codes": round(ov, 4),
+               "overlap_at_R_pq8_uint8_tables_vs_pq8_float": round(ov8, 4),
                "note": "NN-recall = exact nearest neighbour (raw vectors) among the R returned, the paper's "
                        "Recall@R; the mixture's within-component neighbours are isotropic noise, so every 64-bit "
                        "code sits near chance here -- the overlap with float ADC is the meaningful figure"}
@@ -563,6 +586,10 @@ def run_compare(args):
                    "PQ m=16 x 16 (Quick ADC, uint8 tables), 64-bit codes both, queries one at a time, R=%d, "
                    "init=%d" % (n, R, init), "n": n, "R": R, "init": init},
         "pq8_float": {"ms_per_query": round(ms8, 5), "gcodes_per_s": round(n / (ms8 * 1e-3) / 1e9, 2)},
+        "pq8_uint8_tables": {"ms_per_query": round(ms8q, 5), "gcodes_per_s": round(n / (ms8q * 1e-3) / 1e9, 2),
+                             "note": "the 8-bit codes scanned with their 256-entry tables quantized as in "
+                                     "Section 3.3 (qadc_build_luts + qadc_quantize_luts_8bit + qadc_scan_topk "
+                                     "QADC_U8_8BIT, three calls per query)"},
         "speedup_quick_adc_over_pq8_float": round(ms8 / ms4, 3),
         "batches_of_256": batched,
         "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,

@@ -62,12 +62,14 @@ extern "C" {
 #define QADC_U8_4BIT    0 /* Alg. 2: 4-bit codes, uint8 tables, saturating sums      */
 #define QADC_F32_4BIT   1 /* Alg. 1: 4-bit codes, float tables, float32 sums         */
 #define QADC_F32_8BIT   2 /* Alg. 1: 8-bit codes (ksub = 256), float tables          */
+#define QADC_U8_8BIT    3 /* Alg. 2's sums with 8-bit codes: uint8 tables of 256 entries */
 
 /* which call a workspace is for (qadc_workspace_bytes) */
 #define QADC_WS_SCAN_TOPK      0 /* qadc_scan_topk, variant QADC_U8_4BIT  */
 #define QADC_WS_SCAN_F32_4BIT  1 /* qadc_scan_topk, variant QADC_F32_4BIT */
 #define QADC_WS_SCAN_F32_8BIT  2 /* qadc_scan_topk, variant QADC_F32_8BIT */
 #define QADC_WS_SEARCH         3 /* qadc_search */
+#define QADC_WS_SCAN_U8_8BIT   4 /* qadc_scan_topk, variant QADC_U8_8BIT  */
 
 /*
  * Tables step, Eq. (1) of the paper:
@@ -113,22 +115,40 @@ int qadc_quantize_luts(const float *luts, int nq, int ngroup, int m,
                        void *stream);
 
 /*
+ * The same quantizer for 8-bit components (the standard product quantizer of Section 2.1,
+ * 256 centroids per sub-quantizer).  The paper keeps 16-entry tables because a table must fit
+ * a 128-bit register (Section 3.1); here tables live in LDS, where a 256-entry table costs one
+ * lookup per code byte as a pair of 16-entry tables does, so Section 3.3's quantization and
+ * Alg. 2's saturating sums apply unchanged to 8-bit codes (scan variant QADC_U8_8BIT).
+ *   luts [nq][ngroup][m][256] f32;  init_codes [n_init][m] u8;  m in {4, 8, 16, 32}
+ *   qluts [nq][ngroup][m][256] u8 (output);  everything else as qadc_quantize_luts
+ */
+int qadc_quantize_luts_8bit(const float *luts, int nq, int ngroup, int m,
+                            const uint8_t *init_codes, int64_t n_init, const float *qmax_in,
+                            int R, int nbins, int qmin_mode,
+                            uint8_t *qluts, float *bias, float *delta, float *qmax_out,
+                            void *stream);
+
+/*
  * Scan step + top-R (Alg. 1 / Alg. 2).  For every query q and code i < n:
  *   QADC_U8_4BIT   dist = min(nbins, sum_j luts_u8[q][j][c_i[j]])   (equal to the chain of
  *                  saturating adds of Alg. 2, entries being non-negative)
  *   QADC_F32_4BIT  dist = sum_j luts_f32[q][j][c_i[j]], float32, increasing j (Eq. (2))
  *   QADC_F32_8BIT  same with one byte per component and 256-entry tables
+ *   QADC_U8_8BIT   dist = min(nbins, sum_j luts_u8[q][j][c_i[j]]) with one byte per component
+ *                  and 256-entry uint8 tables (see qadc_quantize_luts_8bit)
  * and the R smallest (dist, i) are written in ascending order.
  *   codes    [n][m/2] u8 (4-bit variants) or [n][m] u8 (8-bit), standard layout
- *   m        4-bit variants: 8, 16, 32 or 64;  8-bit variant: 4, 8, 16 or 32
- *   luts     [nq][m][16] u8, [nq][m][16] f32 or [nq][m][256] f32 by variant (4-byte aligned;
+ *   m        4-bit variants: 8, 16, 32 or 64;  8-bit variants: 4, 8, 16 or 32
+ *   luts     [nq][m][16] u8, [nq][m][16] f32, [nq][m][256] f32 or [nq][m][256] u8 by variant
+ *            (4-byte aligned;
  *            float tables are expected non-negative, as squared distances are)
  *   nbins    saturation value of the u8 variant (1..255); ignored otherwise
  *   R        1..QADC_MAX_R
  *   out_idx  [nq][R] u32   position i of the code in `codes`
  *   out_dist [nq][R] u8 or f32 by variant
- *   workspace  >= qadc_workspace_bytes(QADC_WS_SCAN_TOPK | _F32_4BIT | _F32_8BIT, n, m, nq, R),
- *              by variant; the largest of the three serves every variant
+ *   workspace  >= qadc_workspace_bytes(QADC_WS_SCAN_TOPK | _F32_4BIT | _F32_8BIT | _U8_8BIT, n, m,
+ *              nq, R), by variant
  */
 int qadc_scan_topk(int variant, const void *codes, int64_t n, int m,
                    const void *luts, int nq, int R, int nbins,

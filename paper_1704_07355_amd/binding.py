@@ -20,14 +20,14 @@ QADC_OK, QADC_EINVAL, QADC_ENOMEM, QADC_EHIP = 0, -1, -2, -3
 QADC_MAX_R = 1024
 QADC_MAX_INIT = 8192
 QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
-QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT = 0, 1, 2
-QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT, QADC_WS_SEARCH = 0, 1, 2, 3
+QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT, QADC_U8_8BIT = 0, 1, 2, 3
+QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT, QADC_WS_SEARCH, QADC_WS_SCAN_U8_8BIT = 0, 1, 2, 3, 4
 (QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES,
  QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE, QADC_PROF_ROTATE) = range(9)
 QADC_LAYOUT_STANDARD, QADC_LAYOUT_TRANSPOSED = 0, 1
 
 EXPORTS = (
-    "qadc_build_luts", "qadc_quantize_luts", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
+    "qadc_build_luts", "qadc_quantize_luts", "qadc_quantize_luts_8bit", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
     "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train", "qadc_rotate",
     "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version", "qadc_packed_bytes", "qadc_pack_codes", "qadc_unpack_codes",
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.qadc_quantize_luts.argtypes = [vp, i32, i32, i32, vp, i64, vp, i32, i32, i32,
                                          vp, vp, vp, vp, vp]
         L.qadc_quantize_luts.restype = i32
+        L.qadc_quantize_luts_8bit.argtypes = L.qadc_quantize_luts.argtypes
+        L.qadc_quantize_luts_8bit.restype = i32
         L.qadc_scan_topk.argtypes = [i32, vp, i64, i32, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.qadc_scan_topk.restype = i32
         L.qadc_search.argtypes = [vp, i32, i32, vp, i32, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -157,7 +159,8 @@ def qadc_build_luts(codebooks, queries, base=None, out=None):
 
 
 def qadc_quantize_luts(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_TABLE, qmax_in=None):
-    """luts f32 [nq][m][16] or [nq][ngroup][m][16]; init_codes u8 [n_init][m/2] | None.
+    """luts f32 [nq][m][k] or [nq][ngroup][m][k], k = 16 (init_codes u8 [n_init][m/2] | None) or
+    k = 256 (8-bit components, init_codes u8 [n_init][m] | None: qadc_quantize_luts_8bit).
 
     Returns (qluts u8 like luts, bias f32 [nq][m], delta f32 [nq], qmax f32 [nq]).
     """
@@ -166,18 +169,18 @@ def qadc_quantize_luts(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_T
         ngroup = 1
     else:
         nq, ngroup, m, k = luts.shape
-    if k != 16:
-        raise ValueError("quantized tables need 16-entry (4-bit) tables")
+    if k not in (16, 256):
+        raise ValueError("tables of 16 or 256 entries expected")
+    fn = lib().qadc_quantize_luts if k == 16 else lib().qadc_quantize_luts_8bit
     dev = luts.device
     qluts = torch.empty(luts.shape, dtype=torch.uint8, device=dev)
     bias = torch.empty((nq, m), dtype=torch.float32, device=dev)
     delta = torch.empty((nq,), dtype=torch.float32, device=dev)
     qmax = torch.empty((nq,), dtype=torch.float32, device=dev)
     n_init = 0 if init_codes is None else init_codes.shape[0]
-    _check(lib().qadc_quantize_luts(_ptr(luts, torch.float32), nq, ngroup, m,
-                                    _ptr(init_codes, torch.uint8), n_init,
-                                    _ptr(qmax_in, torch.float32), R, nbins, qmin_mode,
-                                    _ptr(qluts), _ptr(bias), _ptr(delta), _ptr(qmax), _stream()))
+    _check(fn(_ptr(luts, torch.float32), nq, ngroup, m, _ptr(init_codes, torch.uint8), n_init,
+              _ptr(qmax_in, torch.float32), R, nbins, qmin_mode,
+              _ptr(qluts), _ptr(bias), _ptr(delta), _ptr(qmax), _stream()))
     return qluts, bias, delta, qmax
 
 
@@ -188,7 +191,7 @@ def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=N
     if n is None:
         n = codes.shape[0]
     dev = luts.device
-    want = torch.uint8 if variant == QADC_U8_4BIT else torch.float32
+    want = torch.uint8 if variant in (QADC_U8_4BIT, QADC_U8_8BIT) else torch.float32
     if luts.dtype != want:
         raise ValueError(f"variant {variant} needs {want} tables")
     if out_idx is None:
@@ -196,7 +199,8 @@ def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=N
     if out_dist is None:
         out_dist = torch.empty((nq, R), dtype=want, device=dev)
     need = qadc_workspace_bytes({QADC_U8_4BIT: QADC_WS_SCAN_TOPK, QADC_F32_4BIT: QADC_WS_SCAN_F32_4BIT,
-                                 QADC_F32_8BIT: QADC_WS_SCAN_F32_8BIT}[variant], n, m, nq, R)
+                                 QADC_F32_8BIT: QADC_WS_SCAN_F32_8BIT,
+                                 QADC_U8_8BIT: QADC_WS_SCAN_U8_8BIT}[variant], n, m, nq, R)
     if workspace is None:
         workspace = qadc_workspace_init(torch.empty((max(need, 256),), dtype=torch.uint8, device=dev))
     _check(lib().qadc_scan_topk(variant, _ptr(codes, torch.uint8), n, m, _ptr(luts), nq, R, nbins,

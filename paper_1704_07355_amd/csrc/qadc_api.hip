@@ -22,11 +22,11 @@ int fail(int code, const char *fmt, ...)
 }
 
 int build_luts(const float *, int, int, int, const float *, const float *, int, float *, hipStream_t);
-int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
+int quantize_luts(int, const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
                   int, uint8_t *, float *, float *, float *, hipStream_t);
-int scan_topk_u8(const uint8_t *, int64_t, int, const uint8_t *, int, int, int, uint32_t *,
+int scan_topk_u8(int, const uint8_t *, int64_t, int, const uint8_t *, int, int, int, uint32_t *,
                  uint8_t *, void *, size_t, hipStream_t);
-size_t scan_topk_u8_workspace(int64_t, int, int, int);
+size_t scan_topk_u8_workspace(int, int64_t, int, int, int);
 int search_u8(const float *, int, int, const float *, int, const uint8_t *, int64_t, int, int, int, int,
               uint32_t *, uint8_t *, uint8_t *, void *, size_t, hipStream_t);
 size_t search_workspace(int64_t, int, int, int);
@@ -63,7 +63,15 @@ int qadc_quantize_luts(const float *luts, int nq, int ngroup, int m, const uint8
                        int64_t n_init, const float *qmax_in, int R, int nbins, int qmin_mode,
                        uint8_t *qluts, float *bias, float *delta, float *qmax_out, void *stream)
 {
-    return qadc::quantize_luts(luts, nq, ngroup, m, init_codes, n_init, qmax_in, R, nbins,
+    return qadc::quantize_luts(16, luts, nq, ngroup, m, init_codes, n_init, qmax_in, R, nbins,
+                               qmin_mode, qluts, bias, delta, qmax_out, (hipStream_t)stream);
+}
+
+int qadc_quantize_luts_8bit(const float *luts, int nq, int ngroup, int m, const uint8_t *init_codes,
+                            int64_t n_init, const float *qmax_in, int R, int nbins, int qmin_mode,
+                            uint8_t *qluts, float *bias, float *delta, float *qmax_out, void *stream)
+{
+    return qadc::quantize_luts(256, luts, nq, ngroup, m, init_codes, n_init, qmax_in, R, nbins,
                                qmin_mode, qluts, bias, delta, qmax_out, (hipStream_t)stream);
 }
 
@@ -76,7 +84,8 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void 
     if (nq == 0) return QADC_OK;
     switch (variant) {
     case QADC_U8_4BIT:
-        return qadc::scan_topk_u8((const uint8_t *)codes, n, m, (const uint8_t *)luts, nq, R, nbins,
+    case QADC_U8_8BIT:
+        return qadc::scan_topk_u8(variant, (const uint8_t *)codes, n, m, (const uint8_t *)luts, nq, R, nbins,
                                   out_idx, (uint8_t *)out_dist, workspace, workspace_bytes,
                                   (hipStream_t)stream);
     case QADC_F32_4BIT:
@@ -175,7 +184,8 @@ int qadc_pq_train(const float *train, int64_t n, int d, int m, int ksub, const i
 size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)
 {
     switch (call) {
-    case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(n, m, nq, R);
+    case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(QADC_U8_4BIT, n, m, nq, R);
+    case QADC_WS_SCAN_U8_8BIT: return qadc::scan_topk_u8_workspace(QADC_U8_8BIT, n, m, nq, R);
     case QADC_WS_SCAN_F32_4BIT: return qadc::scan_topk_f32_workspace(QADC_F32_4BIT, n, m, nq, R);
     case QADC_WS_SCAN_F32_8BIT: return qadc::scan_topk_f32_workspace(QADC_F32_8BIT, n, m, nq, R);
     case QADC_WS_SEARCH: return qadc::search_workspace(n, m, nq, R);

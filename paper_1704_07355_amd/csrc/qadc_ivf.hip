@@ -610,7 +610,7 @@ __global__ void ivf_gather_ids_kernel(const uint32_t *__restrict__ ids, uint32_t
 
 // ------------------------------------------------------------------- host
 
-int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
+int quantize_luts(int, const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
                   int, uint8_t *, float *, float *, float *, hipStream_t);
 
 struct IvfPlan {
@@ -711,7 +711,7 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
                (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, probes, nprobe, luts);
         launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
                m, probes, nprobe, luts, init, R, qmax);
-        int rc = quantize_luts(luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
+        int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
                                nullptr, nullptr, st);
         if (rc != QADC_OK) return rc;
         // Scan

@@ -56,6 +56,10 @@ int build_luts(const float *codebooks, int d, int m, int ksub, const float *quer
 constexpr int QUANT_NT = 1024;
 constexpr int QUANT_MAX_M = 64;
 
+// KSUB = 16: 4-bit components, two per code byte (the paper's case).  KSUB = 256: 8-bit components,
+// one per code byte, the same quantizer applied to the 256-entry tables of Section 2.1's
+// standard product quantizer.
+template <int KSUB>
 __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
     const float *__restrict__ luts, int ngroup, int m, const uint8_t *__restrict__ init_codes,
     int n_init, const float *__restrict__ qmax_in, int R, int nbins, int qmin_mode,
@@ -71,24 +75,30 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
 
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
-    const int entries = m * 16;
+    constexpr int LOG = KSUB == 16 ? 4 : 8;
+    const int entries = m * KSUB;
     const float *lq = luts + (size_t)q * ngroup * entries;
 
-    for (int e = tid; e < entries; e += QUANT_NT) lut0[e] = lq[e];
+    if (KSUB == 16)
+        for (int e = tid; e < entries; e += QUANT_NT) lut0[e] = lq[e];
     for (int j = tid; j < m; j += QUANT_NT) bias_ord[j] = 0xffffffffu;
     __syncthreads();
 
     // qmax: R-th smallest float ADC distance (Eq. (2), float32, increasing j) of the init codes
     float qmax;
     if (init_codes) {
-        const int B = m / 2;
+        const int B = KSUB == 16 ? m / 2 : m;
         for (int i = tid; i < n_init; i += QUANT_NT) {
             const uint8_t *c = init_codes + (size_t)i * B;
             float acc = 0.0f;
             for (int jb = 0; jb < B; ++jb) {
                 const unsigned comps = c[jb];
-                acc = acc + lut0[(2 * jb) * 16 + (comps & 15u)];
-                acc = acc + lut0[(2 * jb + 1) * 16 + (comps >> 4)];
+                if (KSUB == 16) {
+                    acc = acc + lut0[(2 * jb) * 16 + (comps & 15u)];
+                    acc = acc + lut0[(2 * jb + 1) * 16 + (comps >> 4)];
+                } else {
+                    acc = acc + lq[jb * 256 + comps];  // the first table set; cached after the first touch
+                }
             }
             cand[i] = f2ord(acc);
         }
@@ -106,14 +116,14 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
         for (int pos = tid; pos < entries; pos += QUANT_NT) {
             unsigned mn = 0xffffffffu;
             for (int g = 0; g < ngroup; ++g) mn = min(mn, f2ord(lq[(size_t)g * entries + pos]));
-            atomicMin(&bias_ord[pos >> 4], mn);
+            atomicMin(&bias_ord[pos >> LOG], mn);
         }
     } else {
         const int pos = tid % entries;
         unsigned mn = 0xffffffffu;
         for (int g = tid / entries; g < ngroup; g += QUANT_NT / entries)
             mn = min(mn, f2ord(lq[(size_t)g * entries + pos]));
-        atomicMin(&bias_ord[pos >> 4], mn);
+        atomicMin(&bias_ord[pos >> LOG], mn);
     }
     __syncthreads();
     if (tid == 0) {
@@ -144,18 +154,19 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
     const float top = (float)nbins;
     uint8_t *qq = qluts + (size_t)q * ngroup * entries;
     for (int e = tid; e < ngroup * entries; e += QUANT_NT) {
-        const float off = fmaxf(0.0f, lq[e] - bias[(e % entries) >> 4]);
+        const float off = fmaxf(0.0f, lq[e] - bias[(e % entries) >> LOG]);
         const float t = floorf(__fdiv_rn(off, delta));
         qq[e] = (t < top) ? (uint8_t)t : (uint8_t)nbins;
     }
 }
 
-int quantize_luts(const float *luts, int nq, int ngroup, int m, const uint8_t *init_codes,
+int quantize_luts(int ksub, const float *luts, int nq, int ngroup, int m, const uint8_t *init_codes,
                   int64_t n_init, const float *qmax_in, int R, int nbins, int qmin_mode,
                   uint8_t *qluts, float *bias, float *delta, float *qmax_out, hipStream_t st)
 {
     if (!luts || !qluts) return fail(QADC_EINVAL, "qadc_quantize_luts: null pointer");
-    if (!(m == 8 || m == 16 || m == 32 || m == 64) || nq < 0 || ngroup < 1)
+    const int mm = ksub == 16 ? m : 2 * m;  // 8-bit components: m in {4, 8, 16, 32}
+    if (!(mm == 8 || mm == 16 || mm == 32 || mm == 64) || nq < 0 || ngroup < 1)
         return fail(QADC_EINVAL, "qadc_quantize_luts: unsupported m=%d nq=%d ngroup=%d", m, nq, ngroup);
     if (nbins < 1 || nbins > 255 || R < 1)
         return fail(QADC_EINVAL, "qadc_quantize_luts: nbins=%d R=%d", nbins, R);
@@ -169,8 +180,12 @@ int quantize_luts(const float *luts, int nq, int ngroup, int m, const uint8_t *i
         return fail(QADC_EINVAL, "qadc_quantize_luts: neither init_codes nor qmax_in given");
     }
     if (nq == 0) return QADC_OK;
-    launch(QADC_PROF_QUANTIZE, quantize_luts_kernel, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,
-           init_codes, (int)n_init, qmax_in, R, nbins, qmin_mode, qluts, bias, delta, qmax_out);
+    if (ksub == 16)
+        launch(QADC_PROF_QUANTIZE, quantize_luts_kernel<16>, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,
+               init_codes, (int)n_init, qmax_in, R, nbins, qmin_mode, qluts, bias, delta, qmax_out);
+    else
+        launch(QADC_PROF_QUANTIZE, quantize_luts_kernel<256>, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,
+               init_codes, (int)n_init, qmax_in, R, nbins, qmin_mode, qluts, bias, delta, qmax_out);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }

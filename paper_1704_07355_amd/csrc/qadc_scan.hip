@@ -121,10 +121,15 @@ __device__ __forceinline__ unsigned tile_slot_index(int c)
 }
 
 // Pair tables of one query in LDS: ptab[jb][v] = min(cap, q[2jb][v & 15] + q[2jb+1][v >> 4]).
+// `wide`: 8-bit components, the byte-indexed table is the caller's table of component jb itself.
 template <int B, int NT>
 __device__ __forceinline__ void build_pair_tables(const uint8_t *__restrict__ qlut, unsigned cap,
-                                                  uint8_t *ptab)
+                                                  uint8_t *ptab, bool wide = false)
 {
+    if (wide) {
+        for (int e = threadIdx.x; e < B * 256; e += NT) ptab[e] = (uint8_t)min((unsigned)qlut[e], cap);
+        return;
+    }
     for (int e = threadIdx.x; e < B * 256; e += NT) {
         const int jb = e >> 8, v = e & 255;
         const unsigned s = (unsigned)qlut[(2 * jb) * 16 + (v & 15)] +
@@ -143,7 +148,7 @@ template <int B>
 __global__ __launch_bounds__(1024) void seed_u8_kernel(
     const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
     int R, unsigned flush_need, int64_t seed_stride, int tiles_per_wg, char *__restrict__ ws,
-    size_t ws_stride)
+    size_t ws_stride, int wide)
 {
     constexpr int NT = 1024;
     using C = ScanCfg<B, NT>;
@@ -160,7 +165,7 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
     uint4 w[2];
     int nc[2];
     tile_load<B, NT>(codes, c0, min(n, c0 + C::TILE), w, nc);
-    build_pair_tables<B, NT>(qluts + (size_t)q * (2 * B) * 16, cap, ptab);
+    build_pair_tables<B, NT>(qluts + (size_t)q * (wide ? B * 256 : 2 * B * 16), cap, ptab, wide != 0);
     for (int e = tid; e < 256; e += NT) hist[e] = 0;
     __syncthreads();
 
@@ -473,10 +478,12 @@ __global__ __launch_bounds__(1024) void prepare_u8_kernel(
 template <int B, int NT>
 __global__ __launch_bounds__(NT) void scan_u8_kernel(
     const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, int has_seed, char *__restrict__ ws, size_t ws_stride, size_t counts_off,
+    int R, int mode, char *__restrict__ ws, size_t ws_stride, size_t counts_off,
     size_t lists_off, const unsigned *__restrict__ redo_flags)
 {
     using C = ScanCfg<B, NT>;
+    const int has_seed = mode & 1;   // the seed kernel ran: bound and pair tables are in the control block
+    const bool wide = (mode & 2) != 0;  // 8-bit components: qluts holds one 256-entry table per byte
     __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
     __shared__ __attribute__((aligned(16))) uint8_t qlut_s[2 * B * 16];
     __shared__ unsigned keys[C::CAP];
@@ -541,6 +548,8 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
 #pragma unroll
         for (int t = 0; t < PPT; ++t)
             if (tid + t * NT < B * 16) reinterpret_cast<uint4 *>(ptab)[tid + t * NT] = pt[t];
+    } else if (wide) {
+        build_pair_tables<B, NT>(qluts + (size_t)q * B * 256, cap, ptab, true);
     } else {
         const uint8_t *qlut = qluts + (size_t)q * (2 * B) * 16;
         for (int e = tid; e < 2 * B * 4; e += NT)
@@ -671,6 +680,7 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
 
 struct ScanPlan {
     int B, NT, G, qbatch;
+    bool wide;            // 8-bit components (QADC_U8_8BIT): a code byte is one component
     bool tiled;           // batches go through the query-tiled kernel
     TiledPlan t;
     size_t countsA_off, listsA_off, taus_off, flags_off;
@@ -683,7 +693,9 @@ struct ScanPlan {
 
 static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPlan *p)
 {
-    if (variant != QADC_U8_4BIT) return false;
+    if (variant != QADC_U8_4BIT && variant != QADC_U8_8BIT) return false;
+    p->wide = variant == QADC_U8_8BIT;
+    if (p->wide) m *= 2;  // bytes per code = m / 2 below
     if (!(m == 8 || m == 16 || m == 32 || m == 64)) return false;
     if (n < 0 || n > 0xfffffffell || nq < 1 || R < 1 || R > QADC_MAX_R) return false;
     p->B = m / 2;
@@ -754,7 +766,8 @@ static void launch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, c
 {
     dim3 grid(p.G, nq);
     launch(QADC_PROF_SCAN, (scan_u8_kernel<B, NT>), grid, dim3(NT), 0, st, codes, n, qluts, cap, R,
-                       p.seed_wgs > 0 ? 1 : 0, ws, p.stride, p.counts_off, p.lists_off, redo_flags);
+                       (p.seed_wgs > 0 ? 1 : 0) | (p.wide ? 2 : 0), ws, p.stride, p.counts_off, p.lists_off,
+                       redo_flags);
 }
 
 static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
@@ -767,19 +780,19 @@ static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
     switch (p.B) {
     case 4:
         launch(QADC_PROF_SEED, seed_u8_kernel<4>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           flush, p.seed_stride, tpw, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride, p.wide ? 1 : 0);
         break;
     case 8:
         launch(QADC_PROF_SEED, seed_u8_kernel<8>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           flush, p.seed_stride, tpw, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride, p.wide ? 1 : 0);
         break;
     case 16:
         launch(QADC_PROF_SEED, seed_u8_kernel<16>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           flush, p.seed_stride, tpw, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride, p.wide ? 1 : 0);
         break;
     default:
         launch(QADC_PROF_SEED, seed_u8_kernel<32>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
-                           flush, p.seed_stride, tpw, ws, p.stride);
+                           flush, p.seed_stride, tpw, ws, p.stride, p.wide ? 1 : 0);
         break;
     }
 }
@@ -818,12 +831,12 @@ static int scan_and_merge_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
                                     p.countsA_off, p.listsA_off, flags ? p.t.GC : 0, (int)TILED_LCAP, flags);
 }
 
-int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, int nq, int R,
+int scan_topk_u8(int variant, const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, int nq, int R,
                  int nbins, uint32_t *out_idx, uint8_t *out_dist, void *workspace,
                  size_t workspace_bytes, hipStream_t st)
 {
     ScanPlan p;
-    if (!make_scan_plan(QADC_U8_4BIT, n, m, nq, R, &p))
+    if (!make_scan_plan(variant, n, m, nq, R, &p))
         return fail(QADC_EINVAL, "qadc_scan_topk: unsupported n=%lld m=%d nq=%d R=%d",
                     (long long)n, m, nq, R);
     if (nbins < 1 || nbins > 255) return fail(QADC_EINVAL, "qadc_scan_topk: nbins=%d not in 1..255", nbins);
@@ -836,7 +849,7 @@ int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, i
     char *ws = (char *)workspace;
     for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
         const int nb = min(p.qbatch, nq - q0);
-        const uint8_t *ql = qluts + (size_t)q0 * m * 16;
+        const uint8_t *ql = qluts + (size_t)q0 * m * (p.wide ? 256 : 16);
         if (p.seed_wgs > 0) dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
         const int rc = scan_and_merge_u8(p, codes, n, ql, nb, nbins, R, ws, out_idx + (size_t)q0 * R,
                                          out_dist + (size_t)q0 * R, st);
@@ -847,7 +860,7 @@ int scan_topk_u8(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, i
 }
 
 int build_luts(const float *, int, int, int, const float *, const float *, int, float *, hipStream_t);
-int quantize_luts(const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
+int quantize_luts(int, const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
                   int, uint8_t *, float *, float *, float *, hipStream_t);
 
 // Workspace of qadc_search: the scan workspace, then float tables and quantized tables of a batch.
@@ -914,7 +927,7 @@ int search_u8(const float *codebooks, int d, int m, const float *queries, int nq
             // kernels, then the sampling kernel (large databases) or a self-seeding scan
             int rc = build_luts(codebooks, d, m, 16, yq, nullptr, nb, luts, st);
             if (rc != QADC_OK) return rc;
-            rc = quantize_luts(luts, nb, 1, m, codes, n_init, nullptr, R, nbins, qmin_mode, qluts, nullptr,
+            rc = quantize_luts(16, luts, nb, 1, m, codes, n_init, nullptr, R, nbins, qmin_mode, qluts, nullptr,
                                nullptr, nullptr, st);
             if (rc != QADC_OK) return rc;
             if (ql_out)
@@ -929,10 +942,10 @@ int search_u8(const float *codebooks, int d, int m, const float *queries, int nq
     return QADC_OK;
 }
 
-size_t scan_topk_u8_workspace(int64_t n, int m, int nq, int R)
+size_t scan_topk_u8_workspace(int variant, int64_t n, int m, int nq, int R)
 {
     ScanPlan p;
-    if (!make_scan_plan(QADC_U8_4BIT, n, m, nq, R, &p)) return 0;
+    if (!make_scan_plan(variant, n, m, nq, R, &p)) return 0;
     return p.ws_bytes;
 }
 
