@@ -62,8 +62,8 @@ def parse():
     ap.add_argument("--recall-queries", type=int, default=100, help="queries of the accuracy sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event timing pass")
     ap.add_argument("--copy-calibration", type=int, default=0,
-                    help="scan workload: also run this many plain device copies of one code buffer (untimed), so "
-                         "that a counter run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
+                    help="also run this many plain device copies of 80 MB of codes (untimed), so that a counter "
+                         "run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     ap.add_argument("--streams", type=int, default=2,
                     help="scan workload: also time the same steps dealt round-robin to this many HIP streams "
                          "(each with a workspace of its own), reported beside the single-stream value; 1 = skip")
@@ -82,6 +82,18 @@ def parse():
         if getattr(args, k) is None:
             setattr(args, k, v)
     return args
+
+
+def copy_calibration(torch, src, times):
+    """Plain device copies of the first 80,000,000 bytes of `src` (untimed): a counter run scales
+    FETCH_SIZE / WRITE_SIZE by these dispatches of known traffic."""
+    if times <= 0:
+        return
+    flat = src.reshape(-1)[:80_000_000]
+    dst = torch.empty_like(flat)
+    for _ in range(times):
+        dst.copy_(flat)
+    torch.cuda.synchronize()
 
 
 def train_opq(Q, torch, train, m, rows, rounds, iters=10):
@@ -168,6 +180,8 @@ def accuracy(Q, torch, np, cb, codes, raw, queries, R, init, rot=None, nbins=255
 # profiles/scan_u8_config2_hbm_traffic.md (scaled by a plain copy of known size); valid for the
 # workload it was measured on only: (n, m) -> (bytes read, bytes written).
 SCAN_TRAFFIC = {(10_000_000, 16): (39141.8 * 1.9994 * 1024, 53.1 * 1.0 * 1024)}
+TILED_TRAFFIC = 8_680_000_000   # config 3, scan_u8_tiled16_kernel<16, 2>: HBM bytes read per 256-query batch
+COMPARE_TRAFFIC = 400_060_000   # config 5, scan_u8_kernel<8, 256>: HBM bytes read per query
 
 ALU_PEAK_TLOOKUPS = 157.3  # 256 CUs x 64 lanes x 2.4 GHz x 4 byte lanes per 32-bit lane-op
 
@@ -189,6 +203,7 @@ def run_batched(args):
     nq_total = nb * (args.steps + args.warmup)
     queries = mixture_vectors_torch(spec, SEED_QUERY, 0, nq_total, dev)
     t_build = time.time() - t0
+    copy_calibration(torch, codes, args.copy_calibration)
     ws = Q.qadc_workspace_init(torch.empty(Q.qadc_workspace_bytes(Q.QADC_WS_SEARCH, n, m, nb, R),
                                            dtype=torch.uint8, device=dev))
     out_idx = torch.empty((nb, R), dtype=torch.int32, device=dev)
@@ -225,7 +240,9 @@ def run_batched(args):
         ach = n * nb * m / (ms_scan * 1e-3) / 1e12
         roofline = {"bound": "alu", "kernel": "scan_u8_tiled16_kernel (+ 16-bit-lane and redo launches)", "achieved": round(ach, 2),
                     "peak": ALU_PEAK_TLOOKUPS, "unit": "T lookup-adds/s", "frac": round(ach / ALU_PEAK_TLOOKUPS, 4),
-                    "traffic": None, "scan_ms": round(ms_scan, 3), "launches_timed": launches}
+                    "traffic": TILED_TRAFFIC if (n, m, nb) == (100_000_000, 32, 256) else None,
+                    "traffic_source": "profiles/hbm_traffic_configs_3_4_5.md (rocprofv3 --pmc FETCH_SIZE, bytes read per launch)",
+                    "scan_ms": round(ms_scan, 3), "launches_timed": launches}
         kernels = {"scan_ms": round(ms_scan, 3), "tables_quantize_ms": round(ms_prep, 3),
                    "seed_tau_ms": round(ms_seed, 3), "merge_ms": round(ms_merge, 3)}
 
@@ -304,6 +321,7 @@ def run_ivf(args):
     index, sizes, queries = build_ivf_index(Q, torch, np, n, K, m, nq_total, dev, d=args.d)
     coarse, list_off, codes, _, cb = index.tensors
     t_build = time.time() - t0
+    copy_calibration(torch, codes, args.copy_calibration)
 
     ws = Q.qadc_workspace_init(torch.empty(Q.qadc_ivf_workspace_bytes(index, nb, nprobe, R),
                                            dtype=torch.uint8, device=dev))
@@ -338,6 +356,8 @@ def run_ivf(args):
     ach = scanned * row / (phase["scan"] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "ivf_scan_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                "traffic_note": "depends on the batch; measured at 1.01 x the algorithmic bytes "
+                                "(profiles/hbm_traffic_configs_3_4_5.md)",
                 "scan_ms_per_batch": round(phase["scan"], 3), "codes_scanned_per_query": round(scanned / nb)}
 
     cpu = None
@@ -422,6 +442,7 @@ def run_compare(args):
     queries = mixture_vectors_torch(spec, SEED_QUERY, 0, args.queries, dev)
     torch.cuda.synchronize()
     t_build = time.time() - t0
+    copy_calibration(torch, codes4, args.copy_calibration)
 
     ws4 = Q.qadc_workspace_init(torch.empty(Q.qadc_workspace_bytes(Q.QADC_WS_SEARCH, n, 16, 1, R),
                                             dtype=torch.uint8, device=dev))
@@ -517,7 +538,9 @@ def run_compare(args):
         ach = n * 8 / (us * 1e-6) / 1e9
         us8 = per["pq8_float"]["scan_us_per_query"]
         roofline = {"bound": "hbm", "kernel": "scan_u8_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                    "traffic": COMPARE_TRAFFIC if n == 50_000_000 else None,
+                    "traffic_source": "profiles/hbm_traffic_configs_3_4_5.md (rocprofv3 --pmc FETCH_SIZE, bytes read per launch)",
                     "avg_kernel_us": us, "bytes_per_launch": n * 8, "launches_timed": nprof,
                     "pq8_float_scan_kernel": {"avg_kernel_us": us8,
                                               "achieved": round(n * 8 / (us8 * 1e-6) / 1e9, 1),
