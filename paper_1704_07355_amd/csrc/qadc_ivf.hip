@@ -46,10 +46,83 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
 #pragma unroll
         for (int qq = 0; qq < IVF_QT; ++qq) {
             const float df = yq[qq * d + t] - x;
-            acc[qq] += df * df;
+            acc[qq] = fmaf(df, df, acc[qq]);
         }
     }
     for (int qq = 0; qq < nqt; ++qq) dist[(size_t)(q0 + qq) * K + c] = acc[qq];
+}
+
+// The same distances (same operations in the same order for every pair) for batches of many
+// queries: a workgroup computes 128 queries x 128 cells, 16 components of both at a time through
+// LDS, 8 x 8 distances per thread.  Thread (tx, ty) owns queries 8*ty.. and the cells
+// 32*k + 2*tx + e, so that a wavefront's 8-byte LDS reads of the cells are contiguous.
+constexpr int IVF_CT = 128;  // queries and cells per workgroup
+constexpr int IVF_CK = 16;   // components per step
+
+__global__ __launch_bounds__(256) void ivf_coarse_dist_tiled_kernel(
+    const float *__restrict__ coarse, int K, int d, const float *__restrict__ queries, int nq,
+    float *__restrict__ dist)
+{
+    __shared__ __attribute__((aligned(16))) float ys[IVF_CK][IVF_CT + 4];
+    __shared__ __attribute__((aligned(16))) float cs[IVF_CK][IVF_CT + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int c0 = blockIdx.x * IVF_CT;
+    const int q0 = blockIdx.y * IVF_CT;
+    float acc[8][8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
+    for (int t0 = 0; t0 < d; t0 += IVF_CK) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int idx = tid + e * 256;
+            const int row = idx >> 4, col = idx & 15;
+            const int t = t0 + col;
+            const int q = q0 + row, c = c0 + row;
+            ys[col][row] = (q < nq && t < d) ? queries[(size_t)q * d + t] : 0.0f;
+            cs[col][row] = (c < K && t < d) ? coarse[(size_t)c * d + t] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int kk = 0; kk < IVF_CK; ++kk) {
+            float yv[8], cv[8];
+#pragma unroll
+            for (int a = 0; a < 8; a += 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(&ys[kk][8 * ty + a]);
+                yv[a] = v.x; yv[a + 1] = v.y; yv[a + 2] = v.z; yv[a + 3] = v.w;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float2 v = *reinterpret_cast<const float2 *>(&cs[kk][32 * k + 2 * tx]);
+                cv[2 * k] = v.x; cv[2 * k + 1] = v.y;
+            }
+#pragma unroll
+            for (int a = 0; a < 8; ++a)
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    const float df = yv[a] - cv[b];
+                    acc[a][b] = fmaf(df, df, acc[a][b]);
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+        const int q = q0 + 8 * ty + a;
+        if (q >= nq) continue;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int c = c0 + 32 * k + 2 * tx;
+            if (c + 1 < K && (K & 1) == 0) {  // K even: the pair is 8-byte aligned
+                *reinterpret_cast<float2 *>(&dist[(size_t)q * K + c]) = make_float2(acc[a][2 * k], acc[a][2 * k + 1]);
+            } else {
+                if (c < K) dist[(size_t)q * K + c] = acc[a][2 * k];
+                if (c + 1 < K) dist[(size_t)q * K + c + 1] = acc[a][2 * k + 1];
+            }
+        }
+    }
 }
 
 // probes[q][0..nprobe) = the nprobe closest cells, closest first, ties to the lowest cell id.
@@ -700,9 +773,15 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             QADC_HIP_TRY(hipMemcpyAsync(probes, probes_in + (size_t)q0 * nprobe,
                                         (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
         } else {
-            dim3 grid((unsigned)ceil_div(K, 256), (unsigned)ceil_div(nb, IVF_QT));
-            launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel, grid, dim3(256),
-                   (size_t)IVF_QT * d * sizeof(float), st, ix->coarse, K, d, yq, nb, dist);
+            if (nb >= 64) {
+                dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(nb, IVF_CT));
+                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_tiled_kernel, grid, dim3(256), 0, st, ix->coarse, K,
+                       d, yq, nb, dist);
+            } else {
+                dim3 grid((unsigned)ceil_div(K, 256), (unsigned)ceil_div(nb, IVF_QT));
+                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel, grid, dim3(256),
+                       (size_t)IVF_QT * d * sizeof(float), st, ix->coarse, K, d, yq, nb, dist);
+            }
             launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(nb), dim3(IVF_SEL_NT), 0, st, dist, K,
                    nprobe, probes);
         }

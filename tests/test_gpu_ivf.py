@@ -195,3 +195,32 @@ def test_ivf_probe_selection_many_cells_with_exact_ties(Q, O):
         for c, i in where.items():
             if c >= K // 2:   # the twin with the lower id comes right before
                 assert where.get(c - K // 2) == i - 1, (iq, c)
+
+
+@pytest.mark.parametrize("K,d", [(331, 64), (48, 40)])
+def test_ivf_index_step_of_large_batches_equals_small_batches(Q, O, K, d):
+    """Batches of 64 queries and more take the tiled distance kernel: same cells, same order, as the
+    same queries sent a few at a time (both sum the float32 differences in increasing component
+    order), and the oracle's cells up to float32 ties.  K odd, d not a multiple of 16, a ragged batch."""
+    import torch
+    m = 8
+    coarse, cb, x, index = build_ivf(O, n=20_000, K=K, d=d, m=m, seed=K)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(K)
+    nq = 203
+    queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, d))).astype(np.float32)
+    nprobe, R, init = 7, 20, 100
+    gq = to_gpu(queries)
+    ids, dist, probes, _ = Q.qadc_ivf_search(gix, gq, nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    probes = probes.cpu().numpy()
+    for s in range(0, nq, 29):
+        i2, d2, p2, _ = Q.qadc_ivf_search(gix, gq[s:s + 29].contiguous(), nprobe, R, init, debug=True)
+        assert np.array_equal(p2.cpu().numpy(), probes[s:s + 29])
+        assert np.array_equal(idx_np(i2), idx_np(ids)[s:s + 29])
+        assert np.array_equal(d2.cpu().numpy(), dist.cpu().numpy()[s:s + 29])
+    for iq in range(0, nq, 17):
+        want = O.ivf_probes(queries[iq], coarse, nprobe)
+        if not np.array_equal(probes[iq], want):
+            dq = O.sq_l2(queries[iq][None], coarse)[0]
+            np.testing.assert_allclose(dq[probes[iq]], dq[want], rtol=1e-5)
