@@ -28,7 +28,8 @@
  *    its high nibble (the 0x0f mask and the 4-bit shift of Alg. 2).  8-bit
  *    codes (ksub = 256) are m consecutive bytes.
  *  - Environment variables named QADC_* (QADC_SCAN_WGS, QADC_SCAN_NT, QADC_TILED,
- *    QADC_SEED_MIN_TILES, QADC_SEED_WGS, QADC_SCAN_F32_WGS, QADC_IVF_WGS, QADC_IVF_SEED)
+ *    QADC_SEED_MIN_TILES, QADC_SEED_WGS, QADC_SCAN_F32_WGS, QADC_IVF_WGS, QADC_IVF_UNITS,
+ *    QADC_IVF_SEED)
  *    change launch shapes and whether a sampled bound is used -- never a result.
  *    They are read at every call and exist for tuning and for tests.
  *  - Top-R outputs: row q holds the R best of query q, ascending under the

@@ -7,8 +7,8 @@
 //   Scan    every code of every probed list: pair-table lookups, clamped sum (Alg. 2),
 //           key = sum << 32 | storage position; R smallest keys per query; ids[position]
 // Inverted lists are skewed (a few lists hold millions of codes, most a few thousand), so a
-// query's lists are cut into units of at most IVF_UNIT codes and dealt round-robin to the
-// W workgroups of the query.
+// query's lists are cut into units of at most IVF_UNIT codes; a query gets workgroups in
+// proportion to its number of units, each taking a contiguous range of them.
 
 #include "qadc_scan_common.h"
 
@@ -248,9 +248,10 @@ __global__ __launch_bounds__(256) void ivf_build_luts_kernel(
 __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int m,
     const int32_t *__restrict__ probes, int nprobe, const float *__restrict__ luts, int init, int R,
-    float *__restrict__ qmax)
+    float *__restrict__ qmax, long long unit, unsigned *__restrict__ qunits)
 {
     __shared__ unsigned cand[QADC_MAX_INIT];
+    __shared__ unsigned units_s;
     __shared__ long long start[IVF_MAX_NPROBE + 1];  // codes before probe p in the walk
     __shared__ long long lo[IVF_MAX_NPROBE];
     __shared__ SelectScratch sc;
@@ -260,12 +261,16 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     // list lengths one thread per probe, exclusive prefix sum
     __shared__ unsigned long long wsum[256 / WAVE];
     unsigned long long len = 0;
+    if (tid == 0) units_s = 0;
+    __syncthreads();
     if (tid < nprobe) {
         const int cell = probes[(size_t)q * nprobe + tid];
         long long l = 0, h = 0;
         if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
         lo[tid] = l;
         len = (unsigned long long)(h - l);
+        // units the scan kernel cuts this list into (the same expression as there)
+        if (h > l) atomicAdd(&units_s, (unsigned)((h - l / 16 * 16 + unit - 1) / unit));
     }
     {
         const int l = lane_id();
@@ -283,6 +288,7 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
         if (tid == nprobe - 1) start[nprobe] = (long long)(before + inc);
     }
     __syncthreads();
+    if (tid == 0) qunits[q] = units_s;
     const long long total = start[nprobe];
     const int n_walk = (int)min((long long)init, total);
     if (n_walk == 0) {  // uniform
@@ -382,6 +388,80 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
 
 // ------------------------------------------------------------------- Scan
 
+constexpr int IVF_MAP_NT = 1024;
+constexpr int IVF_MAP_MAXQ = 4096;   // queries per batch, at most
+constexpr unsigned IVF_NO_WG = 0xffffffffu;
+
+// Workgroups of the scan: query q gets W_q = clamp(ceil(units_q / units_per_wg), 1, Wmax) of them
+// (work in proportion to the lists it probes); the queries with the most work come first in the
+// grid, so that the longest-running workgroups start first.  wgmap[b] = q << 12 | g for workgroup
+// b of the grid, IVF_NO_WG beyond the last one.  One workgroup; nb <= IVF_MAP_MAXQ, Wmax <= 4096.
+__global__ __launch_bounds__(IVF_MAP_NT) void ivf_wgmap_kernel(const unsigned *__restrict__ qunits, int nb,
+                                                              int units_per_wg, int Wmax,
+                                                              unsigned *__restrict__ wgmap)
+{
+    __shared__ unsigned un[IVF_MAP_MAXQ];      // units of query q
+    __shared__ unsigned byrank[IVF_MAP_MAXQ];  // query at rank r
+    __shared__ unsigned start[IVF_MAP_MAXQ + 1];  // first workgroup of rank r
+    __shared__ unsigned wsum[IVF_MAP_NT / WAVE];
+    __shared__ unsigned carry;
+    const int tid = threadIdx.x;
+    auto wgs_of = [&](unsigned u) {
+        return (unsigned)min((long long)Wmax, max(1ll, ((long long)u + units_per_wg - 1) / units_per_wg));
+    };
+    for (int q = tid; q < nb; q += IVF_MAP_NT) un[q] = qunits[q];
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    // rank by (units descending, query ascending): a total order, so ranks are distinct
+    for (int q = tid; q < nb; q += IVF_MAP_NT) {
+        const unsigned u = un[q];
+        unsigned r = 0;
+        for (int o = 0; o < nb; ++o) {
+            const unsigned v = un[o];
+            r += (v > u || (v == u && o < q)) ? 1u : 0u;
+        }
+        byrank[r] = (unsigned)q;
+    }
+    __syncthreads();
+    // exclusive running sum of the workgroup counts in rank order
+    for (int r0 = 0; r0 < nb; r0 += IVF_MAP_NT) {
+        const int r = r0 + tid;
+        const unsigned w = r < nb ? wgs_of(un[byrank[r]]) : 0u;
+        unsigned inc = w;
+        const int l = lane_id();
+#pragma unroll
+        for (int dd = 1; dd < WAVE; dd <<= 1) {
+            const unsigned up = __shfl_up(inc, dd);
+            if (l >= dd) inc += up;
+        }
+        if (l == WAVE - 1) wsum[tid / WAVE] = inc;
+        __syncthreads();
+        unsigned before = carry;
+        for (int wv = 0; wv < tid / WAVE; ++wv) before += wsum[wv];
+        if (r < nb) start[r] = before + inc - w;
+        __syncthreads();
+        if (tid == IVF_MAP_NT - 1) carry = before + inc;
+        __syncthreads();
+    }
+    if (tid == 0) start[nb] = carry;
+    __syncthreads();
+    const unsigned total = start[nb];
+    const unsigned slots = (unsigned)nb * (unsigned)Wmax;
+    for (unsigned b = tid; b < slots; b += IVF_MAP_NT) {
+        unsigned v = IVF_NO_WG;
+        if (b < total) {
+            int lo_r = 0, hi_r = nb;  // last rank whose first workgroup is <= b
+            while (hi_r - lo_r > 1) {
+                const int mid = (lo_r + hi_r) >> 1;
+                if (start[mid] <= b) lo_r = mid; else hi_r = mid;
+            }
+            v = (byrank[lo_r] << 12) | (b - start[lo_r]);
+        }
+        wgmap[b] = v;
+    }
+}
+
+
 struct IvfShared {
     SelectScratch sel;
     unsigned ccnt;
@@ -399,20 +479,22 @@ template <int B>
 __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int64_t n_total,
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off)
+    int R, int units_per_wg, int Wmax, const unsigned *__restrict__ wgmap, char *__restrict__ ws,
+    size_t ws_stride, size_t counts_off, size_t lists_off)
 {
     constexpr int NT = IVF_NT;
     using C = ScanCfg<B, NT>;
     constexpr long long UNIT = (long long)IVF_UNIT_TILES * C::TILE;
+    const unsigned me = wgmap[blockIdx.x];  // uniform
+    if (me == IVF_NO_WG) return;
     __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
     __shared__ __attribute__((aligned(16))) uint8_t qlut_s[2 * B * 16];
     __shared__ uint64_t keys[C::CAP];
     __shared__ IvfShared sh;
 
     const int tid = threadIdx.x;
-    const int q = blockIdx.y;
-    const int g = blockIdx.x;
-    const int W = gridDim.x;
+    const int q = (int)(me >> 12);
+    const int g = (int)(me & 4095u);
     const unsigned cap = (unsigned)cap_i;
     // bound + 1 left by the seed kernel (uniform load), 0 when there is none
     const unsigned tau1 = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ghist[0][0];
@@ -450,6 +532,11 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
     __syncthreads();
     const long long units = sh.ustart[nprobe];
+    // Workgroups of this query: in proportion to its work (a query whose cell is one of the few
+    // huge lists gets up to Wmax of them, a query of short lists a handful) -- the count the
+    // map kernel derived from the same number of units.
+    const int W = (int)min((long long)Wmax, max(1ll, (units + units_per_wg - 1) / units_per_wg));
+    if (g >= W) return;  // uniform; cannot happen with a consistent map
 
     uint64_t lim = ~0ull;  // keys >= lim cannot be among the R best of this workgroup's codes
     unsigned have = 0;
@@ -495,14 +582,39 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
         lim = (uint64_t)tau1 << 32;  // keys with sum <= bound
         for (long long u = ub; u < ue; ++u) {  // uniform
             const int p = probe_of(u);
-            if (p != cur_p) { load_tables(p); cur_p = p; }
             const long long lo = sh.lo[p], hi = sh.hi[p];
             const long long u0 = sh.a0[p] + (u - sh.ustart[p]) * UNIT;
             const long long u1 = min(hi, u0 + UNIT);
+            // The next tile of the unit is requested before the current one is used; on a change of
+            // list the new tables are requested first and the unit's first tile right behind them
+            // (loads return in the order they were issued), so the tile travels while the pair
+            // tables are rebuilt.
+            uint4 w[2], wn[2];
+            int nc[2], ncn[2];
+            const bool new_list = p != cur_p;  // uniform
+            unsigned qword = 0;
+            if (new_list && tid < 2 * B * 4)
+                qword = reinterpret_cast<const unsigned *>(qluts + ((size_t)q * nprobe + p) * (2 * B) * 16)[tid];
+            asm volatile("" ::: "memory");
+            tile_load<B, NT>(codes, u0, n_total, wn, ncn);
+            asm volatile("" ::: "memory");
+            if (new_list) {
+                __syncthreads();  // nobody still reads the previous pair tables
+                if (tid < 2 * B * 4) reinterpret_cast<unsigned *>(qlut_s)[tid] = qword;
+                __syncthreads();
+                for (int e = tid; e < B * 256; e += NT) {
+                    const int jb = e >> 8, v = e & 255;
+                    const unsigned sum = (unsigned)qlut_s[(2 * jb) * 16 + (v & 15)] +
+                                         (unsigned)qlut_s[(2 * jb + 1) * 16 + (v >> 4)];
+                    ptab[e] = (uint8_t)min(sum, cap);
+                }
+                __syncthreads();
+                cur_p = p;
+            }
             for (long long t0 = u0; t0 < u1; t0 += C::TILE) {
-                uint4 w[2];
-                int nc[2];
-                tile_load<B, NT>(codes, t0, n_total, w, nc);
+                w[0] = wn[0]; w[1] = wn[1];
+                nc[0] = ncn[0]; nc[1] = ncn[1];
+                if (t0 + C::TILE < u1) tile_load<B, NT>(codes, t0 + C::TILE, n_total, wn, ncn);  // uniform
                 uint64_t k[C::CPT];
                 if constexpr (B <= 16) {
                     constexpr int CPV = 16 / B;
@@ -690,7 +802,7 @@ struct IvfPlan {
     int qb, W;
     int seed_per_list;  // codes sampled per probed list for the bound of the scan (0: no seed kernel)
     ScanLayout l;
-    size_t off_dist, off_probes, off_luts, off_qluts, off_qmax, off_scan, bytes;
+    size_t off_dist, off_probes, off_luts, off_qluts, off_qmax, off_units, off_map, off_scan, bytes;
 };
 
 static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, IvfPlan *p)
@@ -698,8 +810,9 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     if (!ix || nq < 1 || nprobe < 1 || nprobe > IVF_MAX_NPROBE || R < 1 || R > QADC_MAX_R) return false;
     if (!(ix->m == 8 || ix->m == 16 || ix->m == 32 || ix->m == 64)) return false;
     if (ix->d < ix->m || ix->d % ix->m || ix->K < 1 || ix->n < 0 || ix->n > 0xfffffffell) return false;
-    p->W = env_int("QADC_IVF_WGS", 64);
+    p->W = env_int("QADC_IVF_WGS", 128);  // most workgroups a query can get
     if (p->W < 1) p->W = 1;
+    if (p->W > 4096) p->W = 4096;
     // about 1/16 of an average list, between 64 and 1024 codes
     int64_t spl = ix->n / ix->K / 16;
     if (spl < 64) spl = 64;
@@ -708,11 +821,11 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->l = scan_layout(p->W, R);
     const size_t per_q = align_up((size_t)ix->K * 4, 256) + align_up((size_t)nprobe * 4, 256) +
                          align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
-                         align_up((size_t)nprobe * ix->m * 16, 256) + 256 + p->l.stride;
+                         align_up((size_t)nprobe * ix->m * 16, 256) + 256 + 4 + (size_t)p->W * 4 + p->l.stride;
     int64_t qb = (int64_t)((512ull << 20) / per_q);
     if (qb < 1) qb = 1;
     if (qb > nq) qb = nq;
-    if (qb > 4096) qb = 4096;
+    if (qb > IVF_MAP_MAXQ) qb = IVF_MAP_MAXQ;
     p->qb = (int)qb;
     size_t o = 0;
     p->off_dist = o;   o += align_up((size_t)qb * ix->K * 4, 256);
@@ -720,6 +833,8 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->off_luts = o;   o += align_up((size_t)qb * nprobe * ix->m * 16 * 4, 256);
     p->off_qluts = o;  o += align_up((size_t)qb * nprobe * ix->m * 16, 256);
     p->off_qmax = o;   o += align_up((size_t)qb * 4, 256);
+    p->off_units = o;  o += align_up((size_t)qb * 4, 256);
+    p->off_map = o;    o += align_up((size_t)qb * p->W * 4, 256);
     p->off_scan = o;   o += p->l.stride * (size_t)qb;
     p->bytes = o;
     return true;
@@ -763,7 +878,11 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
     float *luts = (float *)(ws + p.off_luts);
     uint8_t *qluts = (uint8_t *)(ws + p.off_qluts);
     float *qmax = (float *)(ws + p.off_qmax);
+    unsigned *qunits = (unsigned *)(ws + p.off_units);
+    unsigned *wgmap = (unsigned *)(ws + p.off_map);
     char *scan_ws = ws + p.off_scan;
+    const int cpt = (m / 2 <= 16) ? SCAN_VEC * (16 / (m / 2)) : 1;
+    const long long unit = (long long)IVF_UNIT_TILES * IVF_NT * cpt;  // codes per unit of the scan kernel
 
     for (int q0 = 0; q0 < nq; q0 += p.qb) {
         const int nb = min(p.qb, nq - q0);
@@ -789,20 +908,23 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
                (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, probes, nprobe, luts);
         launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
-               m, probes, nprobe, luts, init, R, qmax);
+               m, probes, nprobe, luts, init, R, qmax, unit, qunits);
         int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
                                nullptr, nullptr, st);
         if (rc != QADC_OK) return rc;
-        // Scan
-        dim3 grid(p.W, nb);
+        // Scan: up to p.W workgroups per query, one per `upw` units of its lists (batches that fill
+        // the GPU by their number alone), one per unit otherwise
+        dim3 grid((unsigned)p.W * (unsigned)nb);
+        const int upw = nb >= 64 ? max(1, env_int("QADC_IVF_UNITS", 16)) : 1;
+        launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
         if (p.seed_per_list > 0)                                                                      \
             launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb), dim3(IVF_SEED_NT), 0, st, ix->list_off,  \
                    ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws, p.l.stride);  \
         launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
-               ix->n, probes, nprobe, qluts, nbins, R, scan_ws, p.l.stride, p.l.counts_off,           \
-               p.l.lists_off);                                                                        \
+               ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, wgmap, scan_ws, p.l.stride,          \
+               p.l.counts_off, p.l.lists_off);                                                        \
         break;
         switch (m / 2) {
             QADC_IVF_CASE(4)
