@@ -583,3 +583,25 @@ def test_search_batch_config1_shaped(Q, O):
         assert np.abs(h_ql[iq].astype(int) - t["qlut"].astype(int)).max() <= 1
         wi, wd = oracle_topk(codes, h_ql[iq], 100)
         assert np.array_equal(idx_np(si)[iq], wi) and np.array_equal(sd[iq].cpu().numpy(), wd)
+
+
+def test_scan_topk_random_shapes_against_c_twin(Q, O):
+    """Forty seeded draws of (n, m, queries, R, nbins, table range): sizes that end inside a tile, a
+    16-byte piece or below R; tables that saturate always, sometimes or never; unseeded, seeded and
+    query-tiled launches.  Indices and sums equal the plain-C scan bit for bit."""
+    from oracle import cref
+    rng = np.random.default_rng(2024)
+    for it in range(40):
+        m = int(rng.choice([8, 16, 32, 64]))
+        big = it % 4 == 0
+        n = int(rng.integers(260_000, 420_000)) if big else int(rng.integers(1, 40_000))
+        nq = int(rng.choice([1, 2, 5, 8, 11, 17])) if not big else int(rng.choice([1, 3, 8, 16]))
+        R = int(rng.choice([1, 7, 100, 257, 1024]))
+        nbins = int(rng.choice([255, 127, 31]))
+        hi = int(rng.choice([3, 20, 90, 256]))
+        codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+        qluts = rng.integers(0, hi, size=(nq, m, 16)).astype(np.uint8)
+        wi, wd = cref.scan_topk_u8(codes, qluts, R, nbins)
+        idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, to_gpu(codes), to_gpu(qluts), R, nbins)
+        assert np.array_equal(idx_np(idx), wi), (it, n, m, nq, R, nbins, hi)
+        assert np.array_equal(dist.cpu().numpy(), wd), (it, n, m, nq, R, nbins, hi)
