@@ -201,7 +201,8 @@ typedef struct qadc_ivf_index {
  * saturating sums, and the R smallest under the order (sum, storage position).
  *   queries    [nq][d] f32
  *   nprobe     1..256 (the paper's `ma`); init 1..QADC_MAX_INIT; nbins 1..255; R 1..QADC_MAX_R
- *   probes_in  [nq][nprobe] i32 or NULL; a negative entry is an unused slot
+ *   probes_in  [nq][nprobe] i32 or NULL; a negative entry is an unused slot, and so is an entry
+ *              >= K or one that repeats an earlier cell of the same query (a list is scanned once)
  *   out_ids    [nq][R] u32   ids[position] of the neighbours (0xFFFFFFFF padding)
  *   out_dist   [nq][R] u8    their quantized sums (nbins padding)
  *   dbg_probes [nq][nprobe] i32 or NULL: the cells scanned      (output, for replay/tests)

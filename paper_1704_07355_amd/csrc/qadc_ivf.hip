@@ -782,15 +782,32 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     for (unsigned i = tid; i < have; i += NT) dst[i] = keys[i];
 }
 
-// out_ids[q][r] = ids[position] for the positions the merge kernel wrote (in place).
+// out_ids[q][r] = ids[position] for the positions the merge kernel wrote (in place).  Anything
+// that is not a storage position becomes the padding value.
 __global__ void ivf_gather_ids_kernel(const uint32_t *__restrict__ ids, uint32_t *__restrict__ out,
-                                      int64_t total)
+                                      int64_t total, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < total) {
         const uint32_t pos = out[i];
-        if (pos != 0xffffffffu) out[i] = ids[pos];
+        out[i] = ((int64_t)pos < n) ? ids[pos] : 0xffffffffu;
     }
+}
+
+// Cells given by the caller: a cell outside [0, K) and a cell that an earlier slot of the same
+// query already names become unused slots (-1) -- a list is scanned once, so that keys stay
+// unique, and nothing outside list_off is read.
+__global__ void ivf_take_probes_kernel(const int32_t *__restrict__ in, int nprobe, int K, int64_t total,
+                                       int32_t *__restrict__ probes)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int64_t row = i / nprobe * nprobe;
+    int cell = in[i];
+    if (cell < 0 || cell >= K) cell = -1;
+    for (int64_t o = row; cell >= 0 && o < i; ++o)
+        if (in[o] == cell) cell = -1;
+    probes[i] = cell;
 }
 
 // ------------------------------------------------------------------- host
@@ -889,8 +906,9 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         const float *yq = queries + (size_t)q0 * d;
         // Index
         if (probes_in) {
-            QADC_HIP_TRY(hipMemcpyAsync(probes, probes_in + (size_t)q0 * nprobe,
-                                        (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+            const int64_t np_total = (int64_t)nb * nprobe;
+            launch(QADC_PROF_IVF_INDEX, ivf_take_probes_kernel, dim3((unsigned)ceil_div(np_total, 256)), dim3(256),
+                   0, st, probes_in + (size_t)q0 * nprobe, nprobe, K, np_total, probes);
         } else {
             if (nb >= 64) {
                 dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(nb, IVF_CT));
@@ -940,7 +958,7 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         if (rc != QADC_OK) return rc;
         const int64_t total = (int64_t)nb * R;
         launch(QADC_PROF_MERGE, ivf_gather_ids_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0,
-               st, ix->ids, oi, total);
+               st, ix->ids, oi, total, ix->n);
         if (dbg_probes)
             QADC_HIP_TRY(hipMemcpyAsync(dbg_probes + (size_t)q0 * nprobe, probes,
                                         (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));

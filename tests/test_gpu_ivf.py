@@ -224,3 +224,54 @@ def test_ivf_index_step_of_large_batches_equals_small_batches(Q, O, K, d):
         if not np.array_equal(probes[iq], want):
             dq = O.sq_l2(queries[iq][None], coarse)[0]
             np.testing.assert_allclose(dq[probes[iq]], dq[want], rtol=1e-5)
+
+
+def test_ivf_large_batch_with_empty_and_huge_lists(Q, O):
+    """1500 queries in one call (more than one pass of the workgroup-map kernel's ranking and running
+    sums), cells given by the caller: empty lists, unused slots, one list holding most codes.  Same
+    results as the same queries sent 50 at a time (a workgroup per unit there), and the oracle's
+    replay for a sample."""
+    import torch
+    coarse, cb, x, index = build_ivf(O, n=60_000, K=24, d=32, m=8, seed=77, zipf=True)
+    K = len(coarse)
+    # empty three lists by giving their codes to the neighbour list (offsets only move)
+    off = index["list_off"].copy()
+    for c in (3, 4, 17):
+        off[c + 1] = off[c]
+    off[K] = index["list_off"][K]
+    for c in range(K):
+        off[c + 1] = max(off[c + 1], off[c])
+    ix2 = dict(list_off=off, codes=index["codes"], ids=index["ids"])
+    gix = gpu_index(Q, coarse, cb, ix2)
+    rng = np.random.default_rng(7)
+    nq, nprobe, R, init = 1500, 5, 30, 120
+    queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, x.shape[1]))).astype(np.float32)
+    probes = rng.integers(0, K, size=(nq, nprobe)).astype(np.int32)
+    probes[::9, 2] = -1            # unused slots
+    probes[::13, 4] = K + 3        # a cell that does not exist: an unused slot too
+    probes[5] = [3, 4, 17, -1, -1]  # only empty lists
+    gq, gp = to_gpu(queries), to_gpu(probes)
+    ids, dist, pr, ql = Q.qadc_ivf_search(gix, gq, nprobe, R, init, probes_in=gp, debug=True)
+    torch.cuda.synchronize()
+    # the draw repeats cells inside many rows: the library scans a list once (first slot wins)
+    clean = probes.copy()
+    clean[(clean < 0) | (clean >= K)] = -1
+    for row in clean:
+        for t in range(1, nprobe):
+            if row[t] >= 0 and row[t] in row[:t]:
+                row[t] = -1
+    assert (clean != probes).sum() > 200
+    assert np.array_equal(pr.cpu().numpy(), clean)
+    probes = clean
+    assert (idx_np(ids)[5] == 0xFFFFFFFF).all()
+    for s in range(0, nq, 50):
+        i2, d2, _, _ = Q.qadc_ivf_search(gix, gq[s:s + 50].contiguous(), nprobe, R, init,
+                                         probes_in=gp[s:s + 50].contiguous(), debug=True)
+        assert np.array_equal(idx_np(i2), idx_np(ids)[s:s + 50]), s
+        assert np.array_equal(d2.cpu().numpy(), dist.cpu().numpy()[s:s + 50]), s
+    for iq in range(0, nq, 97):
+        mask = probes[iq] >= 0
+        rep = O.ivf_quick_adc_search(ix2, coarse, cb, queries[iq], int(mask.sum()), init, R,
+                                     probes=probes[iq][mask], qluts=ql[iq].cpu().numpy()[mask])
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
