@@ -319,7 +319,7 @@ int qadc_profile_read(int which, double *total_ms, int64_t *launches);
  * lowest index) and replaces each centroid by the mean of its sub-vectors (float64 sum in
  * row order, stored as float32; a centroid that owns nothing keeps its value).
  *   train      [n][d] f32
- *   init_rows  [ksub] i64 distinct row numbers (device)
+ *   init_rows  [ksub] i64 distinct row numbers (device); a number outside [0, n) is clamped
  *   codebooks  [m][ksub][d/m] f32   (output)
  *   workspace  >= n * m bytes
  */

@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void ivf_build_luts_kernel(
 __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int m,
     const int32_t *__restrict__ probes, int nprobe, const float *__restrict__ luts, int init, int R,
-    float *__restrict__ qmax, long long unit, unsigned *__restrict__ qunits)
+    float *__restrict__ qmax, long long unit, unsigned *__restrict__ qunits, int64_t n_total)
 {
     __shared__ unsigned cand[QADC_MAX_INIT];
     __shared__ unsigned units_s;
@@ -267,6 +267,7 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
         const int cell = probes[(size_t)q * nprobe + tid];
         long long l = 0, h = 0;
         if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
+        if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: nothing is read
         lo[tid] = l;
         len = (unsigned long long)(h - l);
         // units the scan kernel cuts this list into (the same expression as there)
@@ -329,7 +330,7 @@ template <int B>
 __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes,
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, int per_list, char *__restrict__ ws, size_t ws_stride)
+    int R, int per_list, char *__restrict__ ws, size_t ws_stride, int64_t n_total)
 {
     constexpr int NT = IVF_SEED_NT;
     constexpr int TAB = 2 * B * 16;  // bytes of one cell's quantized tables
@@ -344,6 +345,7 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
         const int cell = probes[(size_t)q * nprobe + tid];
         long long l = 0, h = 0;
         if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
+        if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: nothing is read
         lo[tid] = l;
         len[tid] = (int)min((long long)per_list, h - l);
     }
@@ -507,6 +509,7 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
         const int cell = probes[(size_t)q * nprobe + tid];
         long long l = 0, h = 0;
         if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
+        if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: nothing is read
         const long long a = l / 16 * 16;
         sh.lo[tid] = l;
         sh.hi[tid] = h;
@@ -926,7 +929,7 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
                (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, probes, nprobe, luts);
         launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
-               m, probes, nprobe, luts, init, R, qmax, unit, qunits);
+               m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n);
         int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
                                nullptr, nullptr, st);
         if (rc != QADC_OK) return rc;
@@ -939,7 +942,8 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
     case B_:                                                                                          \
         if (p.seed_per_list > 0)                                                                      \
             launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb), dim3(IVF_SEED_NT), 0, st, ix->list_off,  \
-                   ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws, p.l.stride);  \
+                   ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws, p.l.stride,   \
+                   ix->n);                                                                             \
         launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
                ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, wgmap, scan_ws, p.l.stride,          \
                p.l.counts_off, p.l.lists_off);                                                        \

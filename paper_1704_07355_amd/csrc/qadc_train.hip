@@ -11,14 +11,16 @@
 
 namespace qadc {
 
-__global__ void train_init_kernel(const float *__restrict__ train, int d, int m, int ksub,
+// A row number outside [0, n) is clamped to the nearest row: nothing outside `train` is read.
+__global__ void train_init_kernel(const float *__restrict__ train, int64_t n, int d, int m, int ksub,
                                   const int64_t *__restrict__ init_rows, float *__restrict__ cb)
 {
     const int dsub = d / m;
     const int e = blockIdx.x * blockDim.x + threadIdx.x;  // (j, i, t)
     if (e >= m * ksub * dsub) return;
     const int t = e % dsub, i = (e / dsub) % ksub, j = e / (dsub * ksub);
-    cb[e] = train[init_rows[i] * d + j * dsub + t];
+    const int64_t row = min(max(init_rows[i], (int64_t)0), n - 1);
+    cb[e] = train[row * d + j * dsub + t];
 }
 
 __global__ void train_assign_kernel(const float *__restrict__ train, int64_t n, int d, int m, int ksub,
@@ -74,7 +76,7 @@ int pq_train(const float *train, int64_t n, int d, int m, int ksub, const int64_
     uint8_t *labels = (uint8_t *)workspace;
     const int entries = m * ksub * (d / m);
     hipLaunchKernelGGL(train_init_kernel, dim3((unsigned)ceil_div(entries, 256)), dim3(256), 0, st, train,
-                       d, m, ksub, init_rows, codebooks);
+                       n, d, m, ksub, init_rows, codebooks);
     for (int it = 0; it < iters; ++it) {
         hipLaunchKernelGGL(train_assign_kernel, dim3((unsigned)ceil_div(n * m, 256)), dim3(256), 0, st,
                            train, n, d, m, ksub, codebooks, labels);
