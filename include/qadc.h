@@ -309,6 +309,9 @@ int qadc_rotate(const float *rot, int d, const float *x, int64_t n, float *y, vo
 #define QADC_PROF_ROTATE     8  /* qadc_rotate kernel */
 #define QADC_PROF_COUNT  9
 int qadc_profile_enable(int on);
+/* As qadc_profile_enable(1), but only the kernels of slot `which` carry events: their neighbours in
+ * the stream are launched as in an untimed run. */
+int qadc_profile_only(int which);
 int qadc_profile_read(int which, double *total_ms, int64_t *launches);
 
 /*

@@ -29,7 +29,7 @@ QADC_LAYOUT_STANDARD, QADC_LAYOUT_TRANSPOSED = 0, 1
 EXPORTS = (
     "qadc_build_luts", "qadc_quantize_luts", "qadc_quantize_luts_8bit", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
     "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train", "qadc_rotate",
-    "qadc_profile_enable", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
+    "qadc_profile_enable", "qadc_profile_only", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version", "qadc_packed_bytes", "qadc_pack_codes", "qadc_unpack_codes",
     "qadc_ivf_assign", "qadc_ivf_group_workspace_bytes", "qadc_ivf_group", "qadc_ivf_encode",
 )
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.qadc_rotate.restype = i32
         L.qadc_pq_train.argtypes = [vp, i64, i32, i32, i32, vp, i32, vp, vp, sz, vp]
         L.qadc_pq_train.restype = i32
+        L.qadc_profile_only.argtypes = [i32]
+        L.qadc_profile_only.restype = i32
         L.qadc_profile_enable.argtypes = [i32]
         L.qadc_profile_enable.restype = i32
         L.qadc_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -182,6 +184,14 @@ def qadc_quantize_luts(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_T
               _ptr(qmax_in, torch.float32), R, nbins, qmin_mode,
               _ptr(qluts), _ptr(bias), _ptr(delta), _ptr(qmax), _stream()))
     return qluts, bias, delta, qmax
+
+
+def qadc_quantize_luts_8bit(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_TABLE, qmax_in=None):
+    """qadc_quantize_luts for 256-entry tables: luts f32 [nq][m][256] or [nq][ngroup][m][256], init_codes
+    u8 [n_init][m] | None."""
+    if luts.shape[-1] != 256:
+        raise ValueError("tables of 256 entries expected")
+    return qadc_quantize_luts(luts, init_codes, R, nbins, qmin_mode, qmax_in)
 
 
 def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=None, out_dist=None,
@@ -303,6 +313,11 @@ def qadc_ivf_encode(coarse, codebooks, x, cells, ids, out=None):
 
 def qadc_profile_enable(on: bool) -> None:
     _check(lib().qadc_profile_enable(1 if on else 0))
+
+
+def qadc_profile_only(which: int) -> None:
+    """Profiling on for the kernels of one slot only; qadc_profile_enable(False) ends it."""
+    _check(lib().qadc_profile_only(which))
 
 
 def qadc_profile_read(which: int):

@@ -169,6 +169,8 @@ int qadc_ivf_encode(const float *coarse, int K, const float *codebooks, int d, i
 
 int qadc_profile_enable(int on) { return qadc::profile_enable(on); }
 
+int qadc_profile_only(int which) { return qadc::profile_only(which); }
+
 int qadc_profile_read(int which, double *total_ms, int64_t *launches)
 {
     return qadc::profile_read(which, total_ms, launches);

@@ -7,6 +7,7 @@
 namespace qadc {
 bool prof_open(int which, hipEvent_t *start, hipEvent_t *stop);
 int profile_enable(int on);
+int profile_only(int which);
 int profile_read(int which, double *total_ms, int64_t *launches);
 
 // Launches `kernel`; `which` names the profiling slot its duration is added to (-1: none).

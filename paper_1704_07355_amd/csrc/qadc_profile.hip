@@ -10,6 +10,7 @@ namespace qadc {
 namespace {
 struct Pair { hipEvent_t a, b; int which; };
 bool g_on = false;
+int g_only = -1;  // >= 0: only this slot is timed
 std::vector<Pair> g_open;
 std::vector<hipEvent_t> g_free;   // events kept for reuse: creating one costs host time per launch
 double g_ms[QADC_PROF_COUNT];
@@ -18,7 +19,7 @@ int64_t g_launches[QADC_PROF_COUNT];
 
 bool prof_open(int which, hipEvent_t *start, hipEvent_t *stop)
 {
-    if (!g_on) return false;
+    if (!g_on || (g_only >= 0 && which != g_only)) return false;
     Pair p;
     p.which = which;
     hipEvent_t *ev[2] = {&p.a, &p.b};
@@ -58,7 +59,16 @@ int profile_enable(int on)
         for (int i = 0; i < QADC_PROF_COUNT; ++i) { g_ms[i] = 0; g_launches[i] = 0; }
     }
     g_on = on != 0;
+    g_only = -1;
     return QADC_OK;
+}
+
+int profile_only(int which)
+{
+    if (which < 0 || which >= QADC_PROF_COUNT) return fail(QADC_EINVAL, "qadc_profile_only: bad slot %d", which);
+    const int rc = profile_enable(1);
+    g_only = which;
+    return rc;
 }
 
 int profile_read(int which, double *total_ms, int64_t *launches)
