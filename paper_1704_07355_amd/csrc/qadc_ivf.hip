@@ -15,63 +15,37 @@
 namespace qadc {
 
 constexpr int IVF_MAX_NPROBE = 256;
-constexpr int IVF_QT = 32;       // queries per workgroup of the coarse-distance kernel
 constexpr int IVF_NT = 256;      // threads of the scan workgroups
 constexpr int IVF_UNIT_TILES = 8;
 
 // ------------------------------------------------------------------ Index
 
-// dist[q][c] = sum_t (y[q][t] - coarse[c][t])^2, float32, t increasing.  One thread per
-// centroid, IVF_QT queries per workgroup held in LDS (broadcast reads).
+// dist[q][c] = sum_t (y[q][t] - coarse[c][t])^2, float32, summed in increasing t with one fused
+// multiply-add per component -- the same operations in the same order for a pair whatever the
+// batch, so that the cells a query gets do not depend on the queries sent with it.
+// A workgroup computes 16*AQ queries x 128 cells, 16 components of both at a time through LDS,
+// AQ x 8 distances per thread.  Thread (tx, ty) owns queries AQ*ty.. and the cells
+// 32*k + 2*tx + e, so that a wavefront's 8-byte LDS reads of the cells are contiguous.  AQ = 8
+// (128 queries per workgroup) for batches, AQ = 1 (16 queries) for a few queries, whose cost is
+// then one pass over the centroids.
+constexpr int IVF_CT = 128;  // cells per workgroup
+constexpr int IVF_CK = 16;   // components per step
+
+template <int AQ>
 __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
     const float *__restrict__ coarse, int K, int d, const float *__restrict__ queries, int nq,
     float *__restrict__ dist)
 {
-    extern __shared__ float yq[];  // [IVF_QT][d]
-    const int q0 = blockIdx.y * IVF_QT;
-    const int nqt = min(IVF_QT, nq - q0);
-    for (int e = threadIdx.x; e < IVF_QT * d; e += blockDim.x) {
-        const int qq = e / d;
-        yq[e] = (qq < nqt) ? queries[(size_t)(q0 + qq) * d + (e - qq * d)] : 0.0f;
-    }
-    __syncthreads();
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= K) return;
-    float acc[IVF_QT];
-#pragma unroll
-    for (int qq = 0; qq < IVF_QT; ++qq) acc[qq] = 0.0f;
-    const float *cv = coarse + (size_t)c * d;
-    for (int t = 0; t < d; ++t) {
-        const float x = cv[t];
-#pragma unroll
-        for (int qq = 0; qq < IVF_QT; ++qq) {
-            const float df = yq[qq * d + t] - x;
-            acc[qq] = fmaf(df, df, acc[qq]);
-        }
-    }
-    for (int qq = 0; qq < nqt; ++qq) dist[(size_t)(q0 + qq) * K + c] = acc[qq];
-}
-
-// The same distances (same operations in the same order for every pair) for batches of many
-// queries: a workgroup computes 128 queries x 128 cells, 16 components of both at a time through
-// LDS, 8 x 8 distances per thread.  Thread (tx, ty) owns queries 8*ty.. and the cells
-// 32*k + 2*tx + e, so that a wavefront's 8-byte LDS reads of the cells are contiguous.
-constexpr int IVF_CT = 128;  // queries and cells per workgroup
-constexpr int IVF_CK = 16;   // components per step
-
-__global__ __launch_bounds__(256) void ivf_coarse_dist_tiled_kernel(
-    const float *__restrict__ coarse, int K, int d, const float *__restrict__ queries, int nq,
-    float *__restrict__ dist)
-{
-    __shared__ __attribute__((aligned(16))) float ys[IVF_CK][IVF_CT + 4];
+    constexpr int QT = 16 * AQ;
+    __shared__ __attribute__((aligned(16))) float ys[IVF_CK][QT + 4];
     __shared__ __attribute__((aligned(16))) float cs[IVF_CK][IVF_CT + 4];
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int c0 = blockIdx.x * IVF_CT;
-    const int q0 = blockIdx.y * IVF_CT;
-    float acc[8][8];
+    const int q0 = blockIdx.y * QT;
+    float acc[AQ][8];
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
+    for (int a = 0; a < AQ; ++a)
 #pragma unroll
         for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
     for (int t0 = 0; t0 < d; t0 += IVF_CK) {
@@ -80,18 +54,26 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_tiled_kernel(
             const int idx = tid + e * 256;
             const int row = idx >> 4, col = idx & 15;
             const int t = t0 + col;
-            const int q = q0 + row, c = c0 + row;
-            ys[col][row] = (q < nq && t < d) ? queries[(size_t)q * d + t] : 0.0f;
+            const int c = c0 + row;
             cs[col][row] = (c < K && t < d) ? coarse[(size_t)c * d + t] : 0.0f;
+            if (row < QT) {
+                const int q = q0 + row;
+                ys[col][row] = (q < nq && t < d) ? queries[(size_t)q * d + t] : 0.0f;
+            }
         }
         __syncthreads();
 #pragma unroll 4
         for (int kk = 0; kk < IVF_CK; ++kk) {
-            float yv[8], cv[8];
+            float yv[AQ], cv[8];
+            if constexpr (AQ % 4 == 0) {
 #pragma unroll
-            for (int a = 0; a < 8; a += 4) {
-                const float4 v = *reinterpret_cast<const float4 *>(&ys[kk][8 * ty + a]);
-                yv[a] = v.x; yv[a + 1] = v.y; yv[a + 2] = v.z; yv[a + 3] = v.w;
+                for (int a = 0; a < AQ; a += 4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(&ys[kk][AQ * ty + a]);
+                    yv[a] = v.x; yv[a + 1] = v.y; yv[a + 2] = v.z; yv[a + 3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int a = 0; a < AQ; ++a) yv[a] = ys[kk][AQ * ty + a];
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -99,7 +81,7 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_tiled_kernel(
                 cv[2 * k] = v.x; cv[2 * k + 1] = v.y;
             }
 #pragma unroll
-            for (int a = 0; a < 8; ++a)
+            for (int a = 0; a < AQ; ++a)
 #pragma unroll
                 for (int b = 0; b < 8; ++b) {
                     const float df = yv[a] - cv[b];
@@ -109,8 +91,8 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_tiled_kernel(
         __syncthreads();
     }
 #pragma unroll
-    for (int a = 0; a < 8; ++a) {
-        const int q = q0 + 8 * ty + a;
+    for (int a = 0; a < AQ; ++a) {
+        const int q = q0 + AQ * ty + a;
         if (q >= nq) continue;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -890,8 +872,6 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
     if (((uintptr_t)workspace & 255) != 0)
         return fail(QADC_EINVAL, "qadc_ivf_search: workspace must be 256-byte aligned");
     const int d = ix->d, m = ix->m, K = ix->K;
-    if ((size_t)IVF_QT * d * sizeof(float) > 48 * 1024)
-        return fail(QADC_EINVAL, "qadc_ivf_search: d=%d too large", d);
     char *ws = (char *)workspace;
     float *dist = (float *)(ws + p.off_dist);
     int32_t *probes = (int32_t *)(ws + p.off_probes);
@@ -913,14 +893,14 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             launch(QADC_PROF_IVF_INDEX, ivf_take_probes_kernel, dim3((unsigned)ceil_div(np_total, 256)), dim3(256),
                    0, st, probes_in + (size_t)q0 * nprobe, nprobe, K, np_total, probes);
         } else {
-            if (nb >= 64) {
-                dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(nb, IVF_CT));
-                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_tiled_kernel, grid, dim3(256), 0, st, ix->coarse, K,
-                       d, yq, nb, dist);
+            if (nb > 32) {
+                dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(nb, 128));
+                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<8>, grid, dim3(256), 0, st, ix->coarse, K, d,
+                       yq, nb, dist);
             } else {
-                dim3 grid((unsigned)ceil_div(K, 256), (unsigned)ceil_div(nb, IVF_QT));
-                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel, grid, dim3(256),
-                       (size_t)IVF_QT * d * sizeof(float), st, ix->coarse, K, d, yq, nb, dist);
+                dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(nb, 16));
+                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<1>, grid, dim3(256), 0, st, ix->coarse, K, d,
+                       yq, nb, dist);
             }
             launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(nb), dim3(IVF_SEL_NT), 0, st, dist, K,
                    nprobe, probes);
