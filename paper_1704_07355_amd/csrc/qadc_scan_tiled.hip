@@ -18,6 +18,8 @@
 // alone with its exact machinery; the merge kernel takes whichever result is valid.
 
 #include "qadc_scan_common.h"
+#include <algorithm>
+
 #include "qadc_scan_tiled.h"
 
 namespace qadc {
@@ -359,10 +361,17 @@ bool make_tiled_plan(int64_t n, int m, int nq, TiledPlan *t)
     t->B = m / 2;
     const int cpt = (t->B <= 16) ? SCAN_VEC * (16 / t->B) : 1;
     const int tile = tiled_nt(t->B) * cpt;
-    // chunks: at most TILED_MAX_CHUNKS per query, at least 64 tiles long, a multiple of the tile,
-    // below 2^24 codes (index bits of a key)
+    // chunks: at most TILED_MAX_CHUNKS per query, a multiple of the tile, below 2^24 codes (index
+    // bits of a key); as long as possible (a workgroup builds its tables once per chunk) while
+    // groups x chunks still make about four workgroups per compute unit: 64 tiles with many query
+    // groups, down to 8 tiles for a batch of one or two groups over a short database
+    const int64_t groups = ceil_div(nq, 16);
+    const int64_t want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(1024, groups)));
     int64_t chunk = ceil_div(ceil_div(n, TILED_MAX_CHUNKS), tile) * tile;
-    if (chunk < 64ll * tile) chunk = 64ll * tile;
+    int64_t by_fill = ceil_div(ceil_div(n, want), tile) * tile;
+    if (by_fill > 64ll * tile) by_fill = 64ll * tile;
+    if (by_fill < 8ll * tile) by_fill = 8ll * tile;
+    if (chunk < by_fill) chunk = by_fill;
     const int64_t max_chunk = ((1ll << 24) - 1) / tile * tile;
     if (chunk > max_chunk) return false;
     t->chunk = chunk;
