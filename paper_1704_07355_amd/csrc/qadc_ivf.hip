@@ -320,8 +320,14 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     __shared__ long long lo[IVF_MAX_NPROBE];
     __shared__ int len[IVF_MAX_NPROBE];
     __shared__ unsigned hist[256];
+    __shared__ unsigned last_s;
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
+    // a few queries: the probed lists of a query are split over gridDim.y workgroups, which add
+    // their histograms into the query's control block; the last one to finish derives the bound
+    const int parts = gridDim.y;
+    const int per_part = (nprobe + parts - 1) / parts;
+    const int p_begin = blockIdx.y * per_part, p_end = min(nprobe, p_begin + per_part);
     const unsigned cap = (unsigned)cap_i;
     if (tid < nprobe) {
         const int cell = probes[(size_t)q * nprobe + tid];
@@ -332,8 +338,8 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
         len[tid] = (int)min((long long)per_list, h - l);
     }
     for (int e = tid; e < 256; e += NT) hist[e] = 0;
-    for (int p0 = 0; p0 < nprobe; p0 += IVF_SEED_PCH) {  // uniform
-        const int np = min(IVF_SEED_PCH, nprobe - p0);
+    for (int p0 = p_begin; p0 < p_end; p0 += IVF_SEED_PCH) {  // uniform
+        const int np = min(IVF_SEED_PCH, p_end - p0);
         __syncthreads();  // geometry and histogram ready; nobody still reads the previous tables
         const unsigned *src = reinterpret_cast<const unsigned *>(qluts + ((size_t)q * nprobe + p0) * TAB);
         for (int e = tid; e < np * (TAB / 4); e += NT) reinterpret_cast<unsigned *>(tab)[e] = src[e];
@@ -358,15 +364,31 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
         }
     }
     __syncthreads();
+    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+    if (parts > 1) {
+        // ghist[1][bin]: the query's histogram over all parts; ghist[0][1]: parts that have added theirs
+        if (tid < 256 && hist[tid])
+            __hip_atomic_fetch_add(&hdr->ghist[1][tid], hist[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned done = __hip_atomic_fetch_add(&hdr->ghist[0][1], 1u, __ATOMIC_ACQ_REL,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            last_s = (done == (unsigned)parts - 1u) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (!last_s) return;  // uniform
+        __threadfence();
+        if (tid < 256)
+            hist[tid] = __hip_atomic_load(&hdr->ghist[1][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+    }
     if (tid < WAVE) {
         unsigned h[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) h[b] = hist[4 * tid + b];
         const unsigned t = wave_threshold_bin<4>(h, (unsigned)R);
-        if (tid == 0) {
-            ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
-            hdr->ghist[0][0] = (t < 256u) ? t + 1u : 0u;
-        }
+        if (tid == 0) hdr->ghist[0][0] = (t < 256u) ? t + 1u : 0u;
     }
 }
 
@@ -917,11 +939,14 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         // the GPU by their number alone), one per unit otherwise
         dim3 grid((unsigned)p.W * (unsigned)nb);
         const int upw = nb >= 64 ? max(1, env_int("QADC_IVF_UNITS", 16)) : 1;
+        // a few queries: their lists are sampled by several workgroups each
+        const int seed_parts = nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
         launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
         if (p.seed_per_list > 0)                                                                      \
-            launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb), dim3(IVF_SEED_NT), 0, st, ix->list_off,  \
+            launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb, seed_parts), dim3(IVF_SEED_NT), 0, st,    \
+                   ix->list_off,                                                                       \
                    ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws, p.l.stride,   \
                    ix->n);                                                                             \
         launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \

@@ -275,3 +275,27 @@ def test_ivf_large_batch_with_empty_and_huge_lists(Q, O):
                                      probes=probes[iq][mask], qluts=ql[iq].cpu().numpy()[mask])
         assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
         assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
+
+
+@pytest.mark.parametrize("nprobe,nq", [(40, 3), (17, 1), (64, 15), (9, 2)])
+def test_ivf_bound_sampled_by_several_workgroups(Q, O, nprobe, nq):
+    """Fewer than 16 queries with more than 8 probed cells: a query's lists are sampled by several
+    workgroups that add their histograms in the control block.  The result is the oracle's, and the
+    same as when the queries arrive in a batch of 16 (one sampling workgroup per query)."""
+    import torch
+    coarse, cb, x, index = build_ivf(O, n=150_000, K=80, d=64, m=16, seed=31)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(nprobe)
+    queries = (x[rng.integers(0, len(x), size=16)] + rng.normal(scale=6, size=(16, x.shape[1]))).astype(np.float32)
+    R, init = 100, 500
+    gq = to_gpu(queries)
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, gq[:nq].contiguous(), nprobe, R, init, debug=True)
+    ids16, dist16, _, _ = Q.qadc_ivf_search(gix, gq, nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx_np(ids), idx_np(ids16)[:nq])
+    assert np.array_equal(dist.cpu().numpy(), dist16.cpu().numpy()[:nq])
+    for iq in range(nq):
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
