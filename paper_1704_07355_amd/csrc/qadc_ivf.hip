@@ -130,21 +130,48 @@ __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
     const unsigned need = (unsigned)min(nprobe, K);
 
     // this thread's smallest key: smallest value, lowest cell among equals (cells grow with c)
+    // (eight loads in flight per thread: the row is read at memory speed, not one latency per cell)
     uint64_t mine = ~0ull;
-    for (int c = tid; c < K; c += NT) {
-        const uint64_t k = ((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c;
-        mine = min(mine, k);
+    for (int c0 = tid; c0 < K; c0 += 8 * NT) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * NT;
+            v[u] = c < K ? dq[c] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * NT;
+            if (c < K) mine = min(mine, ((uint64_t)f2ord(v[u]) << 32) | (uint64_t)(unsigned)c);
+        }
     }
     const int nmin = min(K, NT);  // threads that hold at least one key
     if (tid < nmin) cand[tid] = mine;
     if (tid == 0) cnt = 0;
     __syncthreads();
-    const uint64_t T = block_radix_select<uint64_t, 8>(cand, (unsigned)nmin, need, &sc);
+    // Any T at or above the need-th smallest minimum will do: the three leading bytes of the
+    // distance decide it (three histogram passes instead of eight), everything below is set.
+    uint64_t T = block_radix_select_each<uint64_t, 3>(
+        [&](auto f) {
+            for (int i = tid; i < nmin; i += NT) f(cand[i] >> 40);
+        },
+        need, &sc);
+    T = (T << 40) | 0xffffffffffull;
     __syncthreads();  // everybody has T; the minima may be overwritten
-    if (mine <= T) {  // only these threads can hold candidates
-        for (int c = tid; c < K; c += NT) {
-            const uint64_t k = ((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c;
-            if (k <= T) {
+    // second pass over the row, by every thread as the first (only a thread whose minimum is <= T
+    // finds anything, but a few threads walking their cells alone would pay a latency per cell)
+    for (int c0 = tid; c0 < K; c0 += 8 * NT) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * NT;
+            v[u] = c < K ? dq[c] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * NT;
+            const uint64_t k = ((uint64_t)f2ord(v[u]) << 32) | (uint64_t)(unsigned)c;
+            if (c < K && k <= T) {
                 const unsigned slot = atomicAdd(&cnt, 1u);
                 if (slot < (unsigned)IVF_SEL_CAP) cand[slot] = k;
             }
@@ -158,6 +185,17 @@ __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
     auto each_row = [&](auto f) {
         for (int c = tid; c < K; c += NT) f(((uint64_t)f2ord(dq[c]) << 32) | (uint64_t)(unsigned)c);
     };
+    if (ncand <= (unsigned)NT) {
+        // a thread per candidate: its rank among all of them is its place among the probes
+        if ((unsigned)tid < ncand) {
+            const uint64_t k = cand[tid];
+            unsigned rank = 0;
+            for (unsigned j = 0; j < ncand; ++j) rank += (cand[j] < k) ? 1u : 0u;
+            if (rank < need) probes[(size_t)q * nprobe + rank] = (int32_t)(unsigned)k;
+        }
+        for (unsigned i = need + tid; i < (unsigned)nprobe; i += NT) probes[(size_t)q * nprobe + i] = -1;
+        return;  // uniform
+    }
     uint64_t kth;
     if (in_lds) kth = block_radix_select<uint64_t, 8>(cand, ncand, need, &sc);
     else kth = block_radix_select_each<uint64_t, 8>(each_row, need, &sc);
