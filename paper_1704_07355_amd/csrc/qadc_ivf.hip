@@ -48,20 +48,34 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
     for (int a = 0; a < AQ; ++a)
 #pragma unroll
         for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
-    for (int t0 = 0; t0 < d; t0 += IVF_CK) {
+    // the 16 components of the next step are requested while the current ones are used
+    float cn[8], yn[8];
+    auto fetch = [&](int t0) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int idx = tid + e * 256;
             const int row = idx >> 4, col = idx & 15;
             const int t = t0 + col;
             const int c = c0 + row;
-            cs[col][row] = (c < K && t < d) ? coarse[(size_t)c * d + t] : 0.0f;
+            cn[e] = (c < K && t < d) ? coarse[(size_t)c * d + t] : 0.0f;
+            yn[e] = 0.0f;
             if (row < QT) {
                 const int q = q0 + row;
-                ys[col][row] = (q < nq && t < d) ? queries[(size_t)q * d + t] : 0.0f;
+                if (q < nq && t < d) yn[e] = queries[(size_t)q * d + t];
             }
         }
+    };
+    fetch(0);
+    for (int t0 = 0; t0 < d; t0 += IVF_CK) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int idx = tid + e * 256;
+            const int row = idx >> 4, col = idx & 15;
+            cs[col][row] = cn[e];
+            if (row < QT) ys[col][row] = yn[e];
+        }
         __syncthreads();
+        if (t0 + IVF_CK < d) fetch(t0 + IVF_CK);  // uniform
 #pragma unroll 4
         for (int kk = 0; kk < IVF_CK; ++kk) {
             float yv[AQ], cv[8];
@@ -319,13 +333,23 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     for (int i = tid; i < n_walk; i += blockDim.x) {
         int p = 0;
         while (start[p + 1] <= i) ++p;  // lists are few; the walk is short
-        const uint8_t *c = codes + (size_t)(lo[p] + (i - start[p])) * B;
+        // the code as 32-bit words (B is a multiple of 4), then its table entries four bytes at a
+        // time: the eight loads of a word are in flight together, the sum keeps the order of j
+        const unsigned *cw = reinterpret_cast<const unsigned *>(codes + (size_t)(lo[p] + (i - start[p])) * B);
         const float *lut = luts + ((size_t)q * nprobe + p) * m * 16;
         float acc = 0.0f;
-        for (int jb = 0; jb < B; ++jb) {
-            const unsigned comps = c[jb];
-            acc = acc + lut[(2 * jb) * 16 + (comps & 15u)];
-            acc = acc + lut[(2 * jb + 1) * 16 + (comps >> 4)];
+        for (int k = 0; k < B / 4; ++k) {
+            const unsigned w = cw[k];
+            float e[8];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const unsigned comps = (w >> (8 * b)) & 0xffu;
+                const int jb = 4 * k + b;
+                e[2 * b] = lut[(2 * jb) * 16 + (comps & 15u)];
+                e[2 * b + 1] = lut[(2 * jb + 1) * 16 + (comps >> 4)];
+            }
+#pragma unroll
+            for (int b = 0; b < 8; ++b) acc = acc + e[b];
         }
         cand[i] = f2ord(acc);
     }

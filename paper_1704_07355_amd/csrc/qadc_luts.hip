@@ -115,12 +115,14 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
     if (entries >= QUANT_NT) {
         for (int pos = tid; pos < entries; pos += QUANT_NT) {
             unsigned mn = 0xffffffffu;
+#pragma unroll 8
             for (int g = 0; g < ngroup; ++g) mn = min(mn, f2ord(lq[(size_t)g * entries + pos]));
             atomicMin(&bias_ord[pos >> LOG], mn);
         }
     } else {
         const int pos = tid % entries;
         unsigned mn = 0xffffffffu;
+#pragma unroll 8
         for (int g = tid / entries; g < ngroup; g += QUANT_NT / entries)
             mn = min(mn, f2ord(lq[(size_t)g * entries + pos]));
         atomicMin(&bias_ord[pos >> LOG], mn);
@@ -153,6 +155,7 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
 
     const float top = (float)nbins;
     uint8_t *qq = qluts + (size_t)q * ngroup * entries;
+#pragma unroll 4
     for (int e = tid; e < ngroup * entries; e += QUANT_NT) {
         const float off = fmaxf(0.0f, lq[e] - bias[(e % entries) >> LOG]);
         const float t = floorf(__fdiv_rn(off, delta));
