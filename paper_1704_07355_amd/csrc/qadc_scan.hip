@@ -175,12 +175,18 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
             reinterpret_cast<unsigned *>(hdr0->ptab)[e] = reinterpret_cast<const unsigned *>(ptab)[e];
     }
     for (int t = 0; t < tiles_per_wg && c0 < n; ++t, c0 += seed_stride) {  // uniform
-        if (t) tile_load<B, NT>(codes, c0, min(n, c0 + C::TILE), w, nc);
+        // the next sample tile is requested before this one is used
+        uint4 wn[2] = {w[0], w[1]};
+        int ncn[2] = {nc[0], nc[1]};
+        const int64_t c1 = c0 + seed_stride;
+        if (t + 1 < tiles_per_wg && c1 < n) tile_load<B, NT>(codes, c1, min(n, c1 + C::TILE), wn, ncn);
         unsigned k[C::CPT];
         tile_keys<B, NT>(w, nc, 0u, ptab, cap, k);
 #pragma unroll
         for (int c = 0; c < C::CPT; ++c)
             if ((k[c] >> 24) < cap) atomicAdd(&hist[k[c] >> 24], 1u);  // NO_KEY has sum 255 >= cap
+        w[0] = wn[0]; w[1] = wn[1];
+        nc[0] = ncn[0]; nc[1] = ncn[1];
     }
     __syncthreads();
     if (tid < WAVE) {
