@@ -776,9 +776,15 @@ static void launch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n, c
                        redo_flags);
 }
 
-static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
-                             const uint8_t *qluts, int nq, int cap, int R, char *ws, hipStream_t st)
+static int dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
+                            const uint8_t *qluts, int nq, int cap, int R, char *ws, hipStream_t st)
 {
+    // batches that the query-tiled kernels scan are sampled in the query-tiled way too
+    if (p.tiled && nq >= TILED_MIN_Q && env_int("QADC_TILED_SEED", 1) != 0) {
+        const int cpt = (p.B <= 16) ? SCAN_VEC * (16 / p.B) : 1;
+        return run_tiled_seed(p.t, codes, n, qluts, nq, cap, R, p.wide ? 1 : 0, (int64_t)p.seed_wgs * 1024 * cpt,
+                              ws, p.stride, st);
+    }
     // batches: several tiles per workgroup, so that building the pair tables pays
     const int tpw = (nq >= TILED_MIN_Q) ? 8 : 1;
     dim3 grid((unsigned)ceil_div(p.seed_wgs, tpw), nq);
@@ -801,6 +807,7 @@ static void dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
                            flush, p.seed_stride, tpw, ws, p.stride, p.wide ? 1 : 0);
         break;
     }
+    return QADC_OK;
 }
 
 template <int NT>
@@ -856,7 +863,10 @@ int scan_topk_u8(int variant, const uint8_t *codes, int64_t n, int m, const uint
     for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
         const int nb = min(p.qbatch, nq - q0);
         const uint8_t *ql = qluts + (size_t)q0 * m * (p.wide ? 256 : 16);
-        if (p.seed_wgs > 0) dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
+        if (p.seed_wgs > 0) {
+            const int rs = dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
+            if (rs != QADC_OK) return rs;
+        }
         const int rc = scan_and_merge_u8(p, codes, n, ql, nb, nbins, R, ws, out_idx + (size_t)q0 * R,
                                          out_dist + (size_t)q0 * R, st);
         if (rc != QADC_OK) return rc;
@@ -938,7 +948,10 @@ int search_u8(const float *codebooks, int d, int m, const float *queries, int nq
             if (rc != QADC_OK) return rc;
             if (ql_out)
                 QADC_HIP_TRY(hipMemcpyAsync(ql_out, qluts, (size_t)nb * m * 16, hipMemcpyDeviceToDevice, st));
-            if (p.seed_wgs > 0) dispatch_seed_u8(p, codes, n, qluts, nb, nbins, R, ws, st);
+            if (p.seed_wgs > 0) {
+                rc = dispatch_seed_u8(p, codes, n, qluts, nb, nbins, R, ws, st);
+                if (rc != QADC_OK) return rc;
+            }
         }
         const int rc = scan_and_merge_u8(p, codes, n, qluts, nb, nbins, R, ws, out_idx + (size_t)q0 * R,
                                          out_dist + (size_t)q0 * R, st);

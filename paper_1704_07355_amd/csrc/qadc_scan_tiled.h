@@ -28,4 +28,9 @@ int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, 
                    unsigned *taus, char *ws, size_t ws_stride, size_t countsA_off, size_t listsA_off,
                    unsigned *flags, hipStream_t st);
 
+// Pair tables of the batch + the sampled histograms behind the bounds, in the query-tiled way:
+// what seed_u8_kernel does per query.  `sample_codes`: codes of the sample per query.
+int run_tiled_seed(const TiledPlan &t, const uint8_t *codes, int64_t n, const uint8_t *qluts, int nq, int cap,
+                   int R, int wide, int64_t sample_codes, char *ws, size_t ws_stride, hipStream_t st);
+
 }  // namespace qadc

@@ -404,6 +404,184 @@ static int launch_tiled(const TiledPlan &t, const uint8_t *codes, int64_t n, int
     return QADC_OK;
 }
 
+// ------------------------------------------------------------------ seed for batches
+//
+// The bound of a scan comes from a sample of the database (see seed_u8_kernel).  For a batch the
+// sample is the same codes for every query, so it is scanned in the query-tiled way too: a
+// workgroup walks a few sample tiles for eight queries at once (16-bit lanes, as
+// scan_u8_tiled_kernel) and counts every sum in the query's histogram in LDS; at the end one
+// wavefront per query adds the lowest bins (the workgroup's best `flush_need` codes, never
+// beyond its own R-th) to the query's grid-wide histogram.  The pair tables of the batch are
+// written to the control blocks beforehand by ptab_build_kernel.
+
+// hdr->ptab of every query: ptab[jb][v] = min(cap, q[2jb][v & 15] + q[2jb+1][v >> 4]); `wide`:
+// 8-bit components, min(cap, q[jb][v]).  Four entries per thread.
+template <int B>
+__global__ __launch_bounds__(256) void ptab_build_kernel(const uint8_t *__restrict__ qluts, int cap_i,
+                                                         int wide, char *__restrict__ ws, size_t ws_stride)
+{
+    const int q = blockIdx.x;
+    const unsigned cap = (unsigned)cap_i;
+    const uint8_t *ql = qluts + (size_t)q * (wide ? B * 256 : 2 * B * 16);
+    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
+    for (int e4 = threadIdx.x; e4 < B * 64; e4 += 256) {
+        unsigned packed = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int e = 4 * e4 + k;
+            const int jb = e >> 8, v = e & 255;
+            const unsigned sum = wide ? (unsigned)ql[e]
+                                      : (unsigned)ql[(2 * jb) * 16 + (v & 15)] + (unsigned)ql[(2 * jb + 1) * 16 + (v >> 4)];
+            packed |= min(sum, cap) << (8 * k);
+        }
+        reinterpret_cast<unsigned *>(hdr->ptab)[e4] = packed;
+    }
+}
+
+template <int B>
+__global__ __launch_bounds__(tiled_nt(B)) void seed_u8_tiled_kernel(
+    const uint8_t *__restrict__ codes, int64_t n, int nq, int cap_i, int R, unsigned flush_need,
+    int64_t stride, int tiles_per_wg, int n_tiles, char *__restrict__ ws, size_t ws_stride)
+{
+    constexpr int NT = tiled_nt(B);
+    using C = ScanCfg<B, NT>;
+    extern __shared__ uint4 tab[];  // [B * 256] entries of eight 16-bit pair sums
+    __shared__ unsigned hist[TILED_Q][256];
+
+    const int tid = threadIdx.x;
+    const int ngroups = (nq + TILED_Q - 1) / TILED_Q;
+    const int grp = (int)(blockIdx.x % (unsigned)ngroups);
+    const int part = (int)(blockIdx.x / (unsigned)ngroups);
+    const int q0 = grp * TILED_Q;
+    const unsigned cap = (unsigned)cap_i;
+    const int t_begin = part * tiles_per_wg;
+    const int t_end = min(n_tiles, t_begin + tiles_per_wg);
+    if (t_begin >= t_end) return;  // uniform
+
+    uint4 w[2];
+    int nc[2];
+    {
+        const int64_t c0 = (int64_t)t_begin * stride;
+        tile_load<B, NT>(codes, c0, min(n, c0 + C::TILE), w, nc);
+    }
+    for (int e = tid; e < B * 256; e += NT) {
+        unsigned v[TILED_Q];
+#pragma unroll
+        for (int k = 0; k < TILED_Q; ++k) {
+            const int q = q0 + k;
+            v[k] = 0;
+            if (q < nq) v[k] = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ptab[e];
+        }
+        tab[e] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+    }
+    for (int e = tid; e < TILED_Q * 256; e += NT) (&hist[0][0])[e] = 0;
+    __syncthreads();
+
+    for (int t = t_begin; t < t_end; ++t) {  // uniform
+        // the next sample tile is requested before this one is used
+        uint4 wn[2] = {w[0], w[1]};
+        int ncn[2] = {nc[0], nc[1]};
+        if (t + 1 < t_end) {
+            const int64_t c1 = (int64_t)(t + 1) * stride;
+            tile_load<B, NT>(codes, c1, min(n, c1 + C::TILE), wn, ncn);
+        }
+        constexpr int CPV = (B <= 16) ? 16 / B : 1;
+        constexpr int NV = (B <= 16) ? 2 : 1;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+#pragma unroll
+            for (int c = 0; c < CPV; ++c) {
+                unsigned a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+                if constexpr (B <= 16) {
+#pragma unroll
+                    for (int jb = 0; jb < B; ++jb) {
+                        const uint4 e = tab[jb * 256 + byte_of(w[v], c * B + jb)];
+                        a0 += e.x; a1 += e.y; a2 += e.z; a3 += e.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int jb = 0; jb < 32; ++jb) {
+                        const uint4 e = tab[jb * 256 + byte_of(w[jb >> 4], jb & 15)];
+                        a0 += e.x; a1 += e.y; a2 += e.z; a3 += e.w;
+                    }
+                }
+                const bool valid = (B <= 16) ? (c < nc[v]) : (nc[0] != 0);
+                const unsigned acc[4] = {a0, a1, a2, a3};
+#pragma unroll
+                for (int k = 0; k < TILED_Q; ++k) {
+                    const unsigned sum = (k & 1) ? (acc[k >> 1] >> 16) : (acc[k >> 1] & 0xffffu);
+                    // saturated sums carry no information; a slot without a query counts nothing
+                    if (valid && q0 + k < nq && sum < cap) atomicAdd(&hist[k][sum], 1u);
+                }
+            }
+        }
+        w[0] = wn[0]; w[1] = wn[1];
+        nc[0] = ncn[0]; nc[1] = ncn[1];
+    }
+    __syncthreads();
+
+    // wavefront k reports for query q0 + k
+    const int k = tid / WAVE;
+    const int l = tid % WAVE;
+    if (k < TILED_Q && q0 + k < nq) {  // whole wavefronts
+        unsigned h[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) h[b] = hist[k][4 * l + b];
+        const unsigned f = min(wave_threshold_bin<4>(h, (unsigned)R), wave_threshold_bin<4>(h, flush_need));
+        ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)(q0 + k) * ws_stride);
+        unsigned *ghist = hdr->ghist[part % GH_REP];
+        for (unsigned b0 = 0; b0 <= f && b0 < 256u; b0 += WAVE) {  // uniform over the wavefront
+            const unsigned bin = b0 + l;
+            const unsigned c = hist[k][bin];
+            if (bin <= f && bin < cap && c)
+                __hip_atomic_fetch_add(&ghist[bin], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+template <int B>
+static int launch_tiled_seed(const TiledPlan &t, const uint8_t *codes, int64_t n, const uint8_t *qluts, int nq,
+                             int cap, int R, int wide, int64_t sample_codes, char *ws, size_t ws_stride,
+                             hipStream_t st)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&seed_u8_tiled_kernel<B>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes));
+        attr_set = true;
+    }
+    constexpr int cpt = (B <= 16) ? SCAN_VEC * (16 / B) : 1;
+    const int64_t tile = (int64_t)tiled_nt(B) * cpt;
+    int64_t n_tiles = std::max<int64_t>(1, sample_codes / tile);
+    if (n_tiles > n / tile) n_tiles = std::max<int64_t>(1, n / tile);
+    const int64_t stride = std::max<int64_t>(tile, (n / n_tiles) / 16 * 16);
+    const int64_t groups = ceil_div(nq, TILED_Q);
+    // tiles per workgroup: long enough for the table build to pay, short enough to fill the GPU
+    int64_t tpw = n_tiles * groups / 1024;
+    if (tpw < 4) tpw = 4;
+    if (tpw > 32) tpw = 32;
+    const int64_t parts = ceil_div(n_tiles, tpw);
+    int64_t flush = ceil_div(4ll * R, parts);
+    if (flush < 16) flush = 16;
+    if (flush > R) flush = R;
+    launch(QADC_PROF_SEED, ptab_build_kernel<B>, dim3((unsigned)nq), dim3(256), 0, st, qluts, cap, wide, ws,
+           ws_stride);
+    launch(QADC_PROF_SEED, seed_u8_tiled_kernel<B>, dim3((unsigned)(groups * parts)), dim3(tiled_nt(B)), t.lds_bytes,
+           st, codes, n, nq, cap, R, (unsigned)flush, stride, (int)tpw, (int)n_tiles, ws, ws_stride);
+    return QADC_OK;
+}
+
+int run_tiled_seed(const TiledPlan &t, const uint8_t *codes, int64_t n, const uint8_t *qluts, int nq, int cap,
+                   int R, int wide, int64_t sample_codes, char *ws, size_t ws_stride, hipStream_t st)
+{
+    switch (t.B) {
+    case 4: return launch_tiled_seed<4>(t, codes, n, qluts, nq, cap, R, wide, sample_codes, ws, ws_stride, st);
+    case 8: return launch_tiled_seed<8>(t, codes, n, qluts, nq, cap, R, wide, sample_codes, ws, ws_stride, st);
+    case 16: return launch_tiled_seed<16>(t, codes, n, qluts, nq, cap, R, wide, sample_codes, ws, ws_stride, st);
+    default: return launch_tiled_seed<32>(t, codes, n, qluts, nq, cap, R, wide, sample_codes, ws, ws_stride, st);
+    }
+}
+
 int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, int cap, int R,
                    unsigned *taus, char *ws, size_t ws_stride, size_t countsA_off, size_t listsA_off,
                    unsigned *flags, hipStream_t st)
