@@ -491,8 +491,9 @@ def run_compare(args):
     ms8 = timed(pq8)
     ms8q = timed(pq8_u8)
 
-    # the same comparison on batches of 256 queries (one call each): Quick ADC shares code reads
-    # between queries (query-tiled kernels), the float scan has no such form here
+    # the same comparison on batches of 256 queries (one call each): both share code reads between
+    # queries (query-tiled kernels: 16 queries per LDS read for the uint8 tables, 8 queries per two
+    # LDS reads for the float tables)
     nbq = min(256, args.queries)
     qb = queries[:nbq].contiguous()
     luts8b = Q.qadc_build_luts(cb8, qb)

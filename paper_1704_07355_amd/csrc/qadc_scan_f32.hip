@@ -11,6 +11,8 @@
 // list that is cut back to its R smallest keys by an exact radix select whenever it fills.
 // A workgroup reports at most R keys; the merge kernel orders the R smallest of all of them.
 
+#include <algorithm>
+
 #include "qadc_scan_common.h"
 
 namespace qadc {
@@ -216,7 +218,7 @@ template <int KSUB, int ROW>
 __global__ __launch_bounds__(F32_NT) void scan_f32_kernel(
     const uint8_t *__restrict__ codes, int64_t n, const float *__restrict__ luts,
     const F32Range *__restrict__ ranges, int has_seed, int R, char *__restrict__ ws,
-    size_t ws_stride, size_t counts_off, size_t lists_off)
+    size_t ws_stride, size_t counts_off, size_t lists_off, const unsigned *__restrict__ redo_flags)
 {
     constexpr int NT = F32_NT;
     using C = ScanCfg<ROW, NT>;
@@ -230,6 +232,7 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_kernel(
     const int g = blockIdx.x;
     const int64_t G = gridDim.x;
     if ((int64_t)g * C::TILE >= n) return;  // uniform
+    if (redo_flags && redo_flags[q] == 0) return;  // uniform: only the queries the tiled scan gave up on
     const ScanHeader *hdr = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride);
 
     if (tid < WAVE) {
@@ -337,12 +340,166 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_kernel(
     }
 }
 
+// ------------------------------------------------------------------ query batches
+//
+// Query-tiled form of the float scan for 8-bit codes (KSUB = 256): a workgroup scans a chunk of
+// the database for eight queries at once.  The eight queries' tables are interleaved in LDS:
+// entry (j, v) is 32 bytes = eight float32 entries D_q^j[v], so one code byte costs two 16-byte
+// LDS reads and eight adds, and a code fetched from memory serves eight queries.  Each sum is
+// float32 in increasing j, exactly as in scan_f32_kernel.  Bounds: each query's bin bound from
+// its sampled histogram (read by one wavefront per query at the start); sums whose bin is at or
+// below it go to small per-query LDS lists; a list that overflows marks its query for
+// scan_f32_kernel, which redoes that query alone, and the merge kernel takes whichever report
+// is valid.  Workgroup ids map to (query group, chunk) so that the groups of a chunk follow
+// each other in each XCD's share of the ids.
+constexpr int F32T_Q = 8;
+constexpr int F32T_LCAP = 64;
+constexpr int F32T_MAX_CHUNKS = 1024;
+constexpr int F32T_MIN_Q = 8;
+
+template <int ROW>
+__global__ __launch_bounds__(F32_NT) void scan_f32_tiled_kernel(
+    const uint8_t *__restrict__ codes, int64_t n, int64_t chunk, int nq, const float *__restrict__ luts,
+    const F32Range *__restrict__ ranges, int R, char *__restrict__ ws, size_t ws_stride, size_t countsA_off,
+    size_t listsA_off, unsigned *__restrict__ flags)
+{
+    constexpr int NT = F32_NT;
+    static_assert(NT / WAVE == F32T_Q, "one wavefront per query reads its bound");
+    using C = ScanCfg<ROW, NT>;
+    extern __shared__ float4 ftab[];  // [ROW * 256][2]: eight floats per entry
+    __shared__ uint64_t keys[F32T_Q][F32T_LCAP];
+    __shared__ unsigned cnt[F32T_Q];
+    __shared__ unsigned tau_s[F32T_Q];
+
+    const int tid = threadIdx.x;
+    const int ngroups = (nq + F32T_Q - 1) / F32T_Q;
+    const unsigned id = blockIdx.x, slot_id = id >> 3;
+    const int grp = (int)(slot_id % (unsigned)ngroups);
+    const int gc = (int)((slot_id / (unsigned)ngroups) * 8u + (id & 7u));
+    const int q0 = grp * F32T_Q;
+    const int64_t c0 = (int64_t)gc * chunk;
+    const int64_t c1 = min(n, c0 + chunk);
+    if (c0 >= c1) return;  // uniform
+
+    uint4 w[2];
+    int nc[2];
+    tile_load<ROW, NT>(codes, c0, c1, w, nc);
+
+    {   // wavefront k: the bound of query q0 + k from its histogram (255: nothing is known)
+        const int k = tid / WAVE, l = tid % WAVE;
+        unsigned t = 256;
+        if (q0 + k < nq) {  // whole wavefronts
+            const ScanHeader *hdr = reinterpret_cast<const ScanHeader *>(ws + (size_t)(q0 + k) * ws_stride);
+            unsigned carry = 0;
+            for (unsigned b0 = 0; b0 < 256; b0 += 128) {  // uniform
+                const unsigned bin = b0 + 2u * l;
+                unsigned h[2] = {0, 0};
+#pragma unroll
+                for (int r = 0; r < GH_REP; ++r) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(&hdr->ghist[r][bin]);
+                    h[0] += v.x;
+                    h[1] += v.y;
+                }
+                unsigned tot;
+                const unsigned hit = wave_threshold_bin<2>(h, (unsigned)R - carry, &tot);
+                if (hit < 128u) { t = b0 + hit; break; }
+                carry += tot;
+            }
+        }
+        if (l == 0) { tau_s[k] = t; cnt[k] = 0; }
+    }
+    for (int e = tid; e < ROW * 256; e += NT) {
+        float v[F32T_Q];
+#pragma unroll
+        for (int k = 0; k < F32T_Q; ++k) {
+            const int q = q0 + k;
+            v[k] = (q < nq) ? luts[(size_t)q * ROW * 256 + e] : __builtin_inff();
+        }
+        ftab[2 * e] = make_float4(v[0], v[1], v[2], v[3]);
+        ftab[2 * e + 1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    __syncthreads();
+    // a query without a usable bound (bin 255 is never counted) lets everything through: its list
+    // overflows and it is redone alone
+    unsigned tau[F32T_Q];
+    F32Range rg[F32T_Q];
+#pragma unroll
+    for (int k = 0; k < F32T_Q; ++k) {
+        tau[k] = tau_s[k];
+        rg[k] = (q0 + k < nq) ? ranges[q0 + k] : F32Range{0.0f, 0.0f};
+    }
+
+    unsigned rel = 0;
+    for (int64_t t0 = c0; t0 < c1; t0 += C::TILE, rel += C::TILE) {
+        if (rel) tile_load<ROW, NT>(codes, t0, c1, w, nc);
+        constexpr int CPV = 16 / ROW;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+#pragma unroll
+            for (int c = 0; c < CPV; ++c) {
+                float acc[F32T_Q];
+#pragma unroll
+                for (int k = 0; k < F32T_Q; ++k) acc[k] = 0.0f;
+#pragma unroll
+                for (int jb = 0; jb < ROW; ++jb) {
+                    const unsigned e = (unsigned)jb * 256u + byte_of(w[v], c * ROW + jb);
+                    const float4 lo4 = ftab[2 * e], hi4 = ftab[2 * e + 1];
+                    acc[0] = acc[0] + lo4.x; acc[1] = acc[1] + lo4.y; acc[2] = acc[2] + lo4.z; acc[3] = acc[3] + lo4.w;
+                    acc[4] = acc[4] + hi4.x; acc[5] = acc[5] + hi4.y; acc[6] = acc[6] + hi4.z; acc[7] = acc[7] + hi4.w;
+                }
+                const bool valid = c < nc[v];
+                const unsigned li = rel + (unsigned)((v * NT + tid) * CPV + c);
+                bool pass[F32T_Q], any = false;
+#pragma unroll
+                for (int k = 0; k < F32T_Q; ++k) {
+                    pass[k] = valid && (q0 + k < nq) && (tau[k] >= 255u || f32_bin(acc[k], rg[k]) <= tau[k]);
+                    any = any || pass[k];
+                }
+                if (__ballot(any) != 0ull) {  // the append code only runs in waves with a hit
+#pragma unroll
+                    for (int k = 0; k < F32T_Q; ++k) {
+                        const unsigned slot = wave_append_slot(pass[k], &cnt[k]);
+                        if (pass[k] && slot < (unsigned)F32T_LCAP)
+                            keys[k][slot] = ((uint64_t)f2ord(acc[k]) << 32) | li;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+#pragma unroll 1
+    for (int k = 0; k < F32T_Q; ++k) {
+        const int q = q0 + k;
+        if (q >= nq) break;
+        const unsigned c = cnt[k];
+        if (c == 0) continue;
+        if (c > (unsigned)F32T_LCAP) {  // keys were dropped: this query is redone on its own
+            if (tid == 0) flags[q] = 1u;
+            continue;
+        }
+        char *base = ws + (size_t)q * ws_stride;
+        unsigned *counts = reinterpret_cast<unsigned *>(base + countsA_off);
+        uint64_t *dst = reinterpret_cast<uint64_t *>(base + listsA_off) + (size_t)gc * F32T_LCAP;
+        if (tid == 0) counts[gc] = c;
+        for (unsigned i = tid; i < c; i += NT) {
+            const uint64_t key = keys[k][i];
+            dst[i] = (key & 0xffffffff00000000ull) | (uint64_t)(c0 + (int64_t)(key & 0xffffffffull));
+        }
+    }
+}
+
 struct F32Plan {
     int ROW, KSUB, G, qbatch;
     int seed_wgs;
     int64_t seed_stride;
     unsigned flush_need;
     ScanLayout l;
+    size_t stride;        // bytes of workspace per query
+    bool tiled;           // batches of 8-bit codes go through the query-tiled kernel
+    int GC;               // database chunks of the tiled kernel
+    int64_t chunk;
+    size_t countsA_off, listsA_off, flags_off, tiled_lds;
     size_t ranges_off, ws_bytes;
 };
 
@@ -385,16 +542,69 @@ static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan 
         if (fl > R) fl = R;
         p->flush_need = (unsigned)fl;
     }
+    // batches of 8-bit codes: query-tiled kernel over chunks, the single-query kernel only redoes
+    // queries whose lists overflowed
+    p->tiled = false;
+    p->GC = 0;
+    p->chunk = 0;
+    p->tiled_lds = (size_t)p->ROW * 256 * 2 * sizeof(float4);
+    if (p->KSUB == 256 && p->ROW <= 16 && p->seed_wgs > 0 && nq >= F32T_MIN_Q && env_int("QADC_TILED", 1) != 0) {
+        const int64_t groups = ceil_div(nq, F32T_Q);
+        const int64_t want = std::max<int64_t>(1, std::min<int64_t>(F32T_MAX_CHUNKS, ceil_div(1024, groups)));
+        int64_t chunk = ceil_div(ceil_div(n, F32T_MAX_CHUNKS), tile) * tile;
+        int64_t by_fill = ceil_div(ceil_div(n, want), tile) * tile;
+        if (by_fill > 64ll * tile) by_fill = 64ll * tile;
+        if (by_fill < 8ll * tile) by_fill = 8ll * tile;
+        if (chunk < by_fill) chunk = by_fill;
+        if (chunk <= 0xffffffffll) {
+            p->tiled = true;
+            p->chunk = chunk;
+            p->GC = (int)ceil_div(n, chunk);
+            if (p->G > 256) p->G = 256;
+        }
+    }
     p->l = scan_layout(p->G, R);
-    p->qbatch = scan_query_batch(p->l.stride, nq);
-    p->ranges_off = p->l.stride * (size_t)p->qbatch;
+    p->stride = p->l.stride;
+    p->countsA_off = p->listsA_off = p->flags_off = 0;
+    if (p->tiled) {
+        p->countsA_off = p->stride;
+        p->listsA_off = p->countsA_off + align_up((size_t)p->GC * sizeof(unsigned), 256);
+        p->stride = p->listsA_off + align_up((size_t)p->GC * F32T_LCAP * sizeof(uint64_t), 256);
+    }
+    p->qbatch = scan_query_batch(p->stride, nq);
+    p->ranges_off = p->stride * (size_t)p->qbatch;
     p->ws_bytes = p->ranges_off + align_up((size_t)p->qbatch * sizeof(F32Range), 256);
+    if (p->tiled) {
+        p->flags_off = p->ws_bytes;
+        p->ws_bytes = p->flags_off + align_up((size_t)p->qbatch * sizeof(unsigned), 256);
+    }
     return true;
 }
 
+template <int ROW>
+static int launch_f32_tiled(const F32Plan &p, const uint8_t *codes, int64_t n, const float *luts, int nq, int R,
+                            const F32Range *ranges, char *ws, unsigned *flags, hipStream_t st)
+{
+    if constexpr (ROW <= 16) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_f32_tiled_kernel<ROW>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.tiled_lds));
+            attr_set = true;
+        }
+        const unsigned gc8 = (unsigned)ceil_div(p.GC, 8) * 8u;  // chunk slots, eight at a time
+        dim3 grid((unsigned)ceil_div(nq, F32T_Q) * gc8);
+        launch(QADC_PROF_SCAN, scan_f32_tiled_kernel<ROW>, grid, dim3(F32_NT), p.tiled_lds, st, codes, n, p.chunk,
+               nq, luts, ranges, R, ws, p.stride, p.countsA_off, p.listsA_off, flags);
+    }
+    return QADC_OK;
+}
+
+// Seed (large databases), query-tiled scan (batches of 8-bit codes), single-query scan: of
+// everything, or of the queries the tiled scan flagged.  `flags`: null without a tiled scan.
 template <int KSUB>
-static void dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, const float *luts, int nq,
-                         int R, char *ws, hipStream_t st)
+static int dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, const float *luts, int nq,
+                        int R, char *ws, unsigned *flags, hipStream_t st)
 {
     dim3 grid(p.G, nq), block(F32_NT);
     F32Range *ranges = reinterpret_cast<F32Range *>(ws + p.ranges_off);
@@ -405,11 +615,15 @@ static void dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, cons
             launch(QADC_PROF_SEED, (f32_range_kernel<KSUB, ROW_>), dim3(nq), block, 0, st, codes, n0, luts, R, \
                    ranges);                                                                          \
             launch(QADC_PROF_SEED, (seed_f32_kernel<KSUB, ROW_>), dim3(p.seed_wgs, nq), block, 0, st, codes, n, \
-                   luts, (const F32Range *)ranges, R, p.flush_need, p.seed_stride, ws, p.l.stride);   \
+                   luts, (const F32Range *)ranges, R, p.flush_need, p.seed_stride, ws, p.stride);     \
+        }                                                                                            \
+        if (flags) {                                                                                 \
+            const int rc = launch_f32_tiled<ROW_>(p, codes, n, luts, nq, R, ranges, ws, flags, st);  \
+            if (rc != QADC_OK) return rc;                                                            \
         }                                                                                            \
         launch(QADC_PROF_SCAN, (scan_f32_kernel<KSUB, ROW_>), grid, block, 0, st, codes, n, luts,     \
-               (const F32Range *)ranges, p.seed_wgs > 0 ? 1 : 0, R, ws, p.l.stride, p.l.counts_off,   \
-               p.l.lists_off);                                                                       \
+               (const F32Range *)ranges, p.seed_wgs > 0 ? 1 : 0, R, ws, p.stride, p.l.counts_off,     \
+               p.l.lists_off, (const unsigned *)flags);                                              \
         break;
     switch (p.ROW) {
         QADC_F32_CASE(4)
@@ -418,6 +632,7 @@ static void dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, cons
         QADC_F32_CASE(32)
     }
 #undef QADC_F32_CASE
+    return QADC_OK;
 }
 
 int scan_topk_f32(int variant, const uint8_t *codes, int64_t n, int m, const float *luts, int nq,
@@ -438,12 +653,14 @@ int scan_topk_f32(int variant, const uint8_t *codes, int64_t n, int m, const flo
     for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
         const int nb = min(p.qbatch, nq - q0);
         const float *lq = luts + (size_t)q0 * M * p.KSUB;
-        if (p.KSUB == 16) dispatch_f32<16>(p, codes, n, lq, nb, R, ws, st);
-        else dispatch_f32<256>(p, codes, n, lq, nb, R, ws, st);
-        const int rc = launch_merge<float, 8>(nb, st, ws, p.l.stride, p.l.counts_off, p.l.lists_off, p.G,
-                                              (unsigned)min((int64_t)R, n), R, __builtin_inff(),
-                                              out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R, (size_t)0,
-                                              (size_t)0, 0, 0, (unsigned *)nullptr);
+        unsigned *flags = (p.tiled && nb >= F32T_MIN_Q) ? reinterpret_cast<unsigned *>(ws + p.flags_off) : nullptr;
+        int rc = (p.KSUB == 16) ? dispatch_f32<16>(p, codes, n, lq, nb, R, ws, flags, st)
+                                : dispatch_f32<256>(p, codes, n, lq, nb, R, ws, flags, st);
+        if (rc != QADC_OK) return rc;
+        rc = launch_merge<float, 8>(nb, st, ws, p.stride, p.l.counts_off, p.l.lists_off, p.G,
+                                    (unsigned)min((int64_t)R, n), R, __builtin_inff(),
+                                    out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R, p.countsA_off,
+                                    p.listsA_off, flags ? p.GC : 0, (int)F32T_LCAP, flags);
         if (rc != QADC_OK) return rc;
     }
     QADC_HIP_TRY(hipGetLastError());

@@ -605,3 +605,36 @@ def test_scan_topk_random_shapes_against_c_twin(Q, O):
         idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, to_gpu(codes), to_gpu(qluts), R, nbins)
         assert np.array_equal(idx_np(idx), wi), (it, n, m, nq, R, nbins, hi)
         assert np.array_equal(dist.cpu().numpy(), wd), (it, n, m, nq, R, nbins, hi)
+
+
+@pytest.mark.parametrize("m,n,nq", [(8, 300_007, 8), (8, 300_007, 19), (4, 700_000, 16), (16, 280_000, 9)])
+def test_float_scan_of_8bit_codes_in_query_batches(Q, O, m, n, nq):
+    """Batches of eight queries and more over 8-bit codes take the query-tiled float kernel: indices
+    and float32 distances equal the plain-C scan bit for bit (same order of additions)."""
+    from oracle import cref
+    rng = np.random.default_rng(m + n + nq)
+    codes = rng.integers(0, 256, size=(n, m), dtype=np.uint8)
+    luts = (rng.gamma(2.0, 50.0, size=(nq, m, 256))).astype(np.float32)
+    R = 100
+    wi, wd = cref.scan_topk_f32(codes, luts, R)
+    idx, dist = Q.qadc_scan_topk(Q.QADC_F32_8BIT, to_gpu(codes), to_gpu(luts), R)
+    assert np.array_equal(idx_np(idx), wi)
+    assert np.array_equal(dist.cpu().numpy(), wd)
+
+
+def test_float_scan_batches_with_ties_and_useless_bounds(Q, O):
+    """All codes equal (every distance ties: the bound lets everything through, the lists of the
+    tiled kernel overflow and each query is redone alone) and tables with a few huge entries."""
+    from oracle import cref
+    rng = np.random.default_rng(12)
+    m, n, nq, R = 8, 290_000, 10, 100
+    luts = rng.gamma(2.0, 50.0, size=(nq, m, 256)).astype(np.float32)
+    codes = np.full((n, m), 7, dtype=np.uint8)
+    wi, wd = cref.scan_topk_f32(codes, luts, R)
+    idx, dist = Q.qadc_scan_topk(Q.QADC_F32_8BIT, to_gpu(codes), to_gpu(luts), R)
+    assert np.array_equal(idx_np(idx), wi) and np.array_equal(dist.cpu().numpy(), wd)
+    codes = rng.integers(0, 256, size=(n, m), dtype=np.uint8)
+    luts[:, :, ::17] = 1e30
+    wi, wd = cref.scan_topk_f32(codes, luts, R)
+    idx, dist = Q.qadc_scan_topk(Q.QADC_F32_8BIT, to_gpu(codes), to_gpu(luts), R)
+    assert np.array_equal(idx_np(idx), wi) and np.array_equal(dist.cpu().numpy(), wd)
