@@ -183,6 +183,8 @@ SCAN_TRAFFIC = {(10_000_000, 16): (39141.8 * 1.9994 * 1024, 53.1 * 1.0 * 1024)}
 TILED_TRAFFIC = 8_680_000_000   # config 3, scan_u8_tiled16_kernel<16, 2>: HBM bytes read per 256-query batch
 COMPARE_TRAFFIC = 400_060_000   # config 5, scan_u8_kernel<8, 256>: HBM bytes read per query
 
+MFMA_TRAFFIC = 1_617_500_000    # config 3, scan_u8_mfma_kernel<16>: HBM bytes read per 256-query batch
+MFMA_I8_PEAK_TOPS = 5000.0      # dense int8 MFMA peak of the chip
 ALU_PEAK_TLOOKUPS = 157.3  # 256 CUs x 64 lanes x 2.4 GHz x 4 byte lanes per 32-bit lane-op
 
 
@@ -238,11 +240,23 @@ def run_batched(args):
         ms_merge, _ = Q.qadc_profile_read(Q.QADC_PROF_MERGE)
         Q.qadc_profile_enable(False)
         ach = n * nb * m / (ms_scan * 1e-3) / 1e12
-        roofline = {"bound": "alu", "kernel": "scan_u8_tiled16_kernel (+ 16-bit-lane and redo launches)", "achieved": round(ach, 2),
-                    "peak": ALU_PEAK_TLOOKUPS, "unit": "T lookup-adds/s", "frac": round(ach / ALU_PEAK_TLOOKUPS, 4),
-                    "traffic": TILED_TRAFFIC if (n, m, nb) == (100_000_000, 32, 256) else None,
-                    "traffic_source": "profiles/hbm_traffic_configs_3_4_5.md (rocprofv3 --pmc FETCH_SIZE, bytes read per launch)",
-                    "scan_ms": round(ms_scan, 3), "launches_timed": launches}
+        on_matrix_cores = nb >= 96 and m <= 32 and os.environ.get("QADC_TILED_MFMA", "1") != "0"
+        if on_matrix_cores:
+            # one-hot products: every (code, query, table) lookup is a 16-term int8 dot product
+            ops = n * nb * m * 16 * 2 / (ms_scan * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "kernel": "scan_u8_mfma_kernel (+ the redo launch)", "achieved": round(ops, 1),
+                        "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s", "frac": round(ops / MFMA_I8_PEAK_TOPS, 4),
+                        "note": "int8 operations issued; 15 of 16 multiply by a zero of the one-hot operand",
+                        "useful_T_lookup_adds_per_s": round(ach, 2),
+                        "traffic": MFMA_TRAFFIC if (n, m, nb) == (100_000_000, 32, 256) else None,
+                        "traffic_source": "profiles/hbm_traffic_configs_3_4_5.md (rocprofv3 --pmc FETCH_SIZE, bytes read per launch)",
+                        "scan_ms": round(ms_scan, 3), "launches_timed": launches}
+        else:
+            roofline = {"bound": "alu", "kernel": "scan_u8_tiled16_kernel (+ 16-bit-lane and redo launches)", "achieved": round(ach, 2),
+                        "peak": ALU_PEAK_TLOOKUPS, "unit": "T lookup-adds/s", "frac": round(ach / ALU_PEAK_TLOOKUPS, 4),
+                        "traffic": TILED_TRAFFIC if (n, m, nb) == (100_000_000, 32, 256) else None,
+                        "traffic_source": "profiles/hbm_traffic_configs_3_4_5.md (rocprofv3 --pmc FETCH_SIZE, bytes read per launch)",
+                        "scan_ms": round(ms_scan, 3), "launches_timed": launches}
         kernels = {"scan_ms": round(ms_scan, 3), "tables_quantize_ms": round(ms_prep, 3),
                    "seed_tau_ms": round(ms_seed, 3), "merge_ms": round(ms_merge, 3)}
 
@@ -267,7 +281,7 @@ def run_batched(args):
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": "config 3: d=128 mixture, PQ m=%d x 4-bit, N=%d codes, batches of %d queries "
-                   "through qadc_search (16 queries share each code read in a workgroup), R=%d, init=%d"
+                   "through qadc_search (a wavefront scans each code for 64 queries), R=%d, init=%d"
                    % (m, n, nb, R, init), "n": n, "m": m, "R": R, "init": init, "batch": nb},
         "gcodes_per_s_per_query": round(pairs / nb / 1e9, 2),
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))

@@ -14,6 +14,7 @@ SO = os.path.join(HERE, "libqadc.so")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-mfma-vgpr-form",  # MFMA accumulators in VGPRs: the scan tests them with plain VALU ops
     "-Wno-unused-command-line-argument",
 ]
 

@@ -744,7 +744,7 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
         p->flush_need = (unsigned)fl;
     }
     p->tiled = p->seed_wgs > 0 && nq >= TILED_MIN_Q && env_int("QADC_TILED", 1) != 0 &&
-               make_tiled_plan(n, m, nq, &p->t);
+               make_tiled_plan(n, m, nq, !p->wide, &p->t);
     if (p->tiled && p->G > 256) p->G = 256;  // the single-query kernel only redoes rare queries
     const ScanLayout l = scan_layout(p->G, R);
     p->counts_off = l.counts_off;
@@ -833,7 +833,7 @@ static int scan_and_merge_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
         unsigned *taus = reinterpret_cast<unsigned *>(ws + p.taus_off);
         flags = reinterpret_cast<unsigned *>(ws + p.flags_off);
         const int rc = run_tiled_scan(p.t, codes, n, nb, nbins, R, taus, ws, p.stride, p.countsA_off,
-                                      p.listsA_off, flags, st);
+                                      p.listsA_off, flags, p.wide ? nullptr : qluts, st);
         if (rc != QADC_OK) return rc;
     }
     if (p.NT == 1024) dispatch_scan_u8<1024>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);

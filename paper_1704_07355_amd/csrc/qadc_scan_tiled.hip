@@ -356,21 +356,32 @@ __global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled16_kernel(
     }
 }
 
-bool make_tiled_plan(int64_t n, int m, int nq, TiledPlan *t)
+bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 {
     t->B = m / 2;
     const int cpt = (t->B <= 16) ? SCAN_VEC * (16 / t->B) : 1;
     const int tile = tiled_nt(t->B) * cpt;
+    // 4-bit codes, up to 32 code bytes, a batch that fills a good part of a 64-query wavefront:
+    // the matrix-core kernel scans it
+    t->mfma = codes4 && t->B <= 16 && nq >= TILED_MFMA_MIN_Q && env_int("QADC_TILED_MFMA", 1) != 0;
     // chunks: at most TILED_MAX_CHUNKS per query, a multiple of the tile, below 2^24 codes (index
     // bits of a key); as long as possible (a workgroup builds its tables once per chunk) while
     // groups x chunks still make about four workgroups per compute unit: 64 tiles with many query
-    // groups, down to 8 tiles for a batch of one or two groups over a short database
+    // groups, down to 8 tiles for a batch of one or two groups over a short database.  The
+    // matrix-core kernel runs one wavefront per (64 queries, chunk): it wants about 4096 of them
+    // (two rounds of two per SIMD), each at least two tiles long.
     const int64_t groups = ceil_div(nq, 16);
-    const int64_t want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(1024, groups)));
+    int64_t want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(1024, groups)));
+    int64_t lo = 8, hi = 64;
+    if (t->mfma) {
+        want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(4096, ceil_div(nq, 64))));
+        lo = 2;
+        hi = 1ll << 40;
+    }
     int64_t chunk = ceil_div(ceil_div(n, TILED_MAX_CHUNKS), tile) * tile;
     int64_t by_fill = ceil_div(ceil_div(n, want), tile) * tile;
-    if (by_fill > 64ll * tile) by_fill = 64ll * tile;
-    if (by_fill < 8ll * tile) by_fill = 8ll * tile;
+    if (by_fill > hi * tile) by_fill = hi * tile;
+    if (by_fill < lo * tile) by_fill = lo * tile;
     if (chunk < by_fill) chunk = by_fill;
     const int64_t max_chunk = ((1ll << 24) - 1) / tile * tile;
     if (chunk > max_chunk) return false;
@@ -378,6 +389,197 @@ bool make_tiled_plan(int64_t n, int m, int nq, TiledPlan *t)
     t->GC = (int)ceil_div(n, chunk);
     t->lds_bytes = (size_t)t->B * 256 * sizeof(uint4);
     return t->GC >= 1 && t->GC <= 65535 && nq >= 1;
+}
+
+// ------------------------------------------------------------------ matrix-core form
+//
+// The lookups of a batch as a matrix product on the MFMA units: with onehot(c) the 16-vector that
+// is 1 at position c, the sum of a code for a query is  sum_j onehot(c_j) . q^j  -- a row of 0/1
+// bytes times a column of table entries, exact in int32.  One v_mfma_i32_32x32x32_i8 multiplies
+// 32 codes by 32 queries over 32 values of k = two tables: lanes 0..31 hold the low nibble of a
+// code byte as a one-hot 16-byte operand (table 2jb), lanes 32..63 the high nibble (table
+// 2jb+1); the other operand is simply the 16 entries of that table of query (lane mod 32), as
+// they lie in memory.  So a code byte costs one MFMA for 32 codes x 32 queries, the tables stay in
+// registers for the whole scan (the one-hot operand is read from a 16-entry table in LDS:
+// composing it with compares and selects made the vector ALU the limit), and 15 of 16 multiplications
+// are by zero -- which the matrix units can afford: measured here they run 4.0 Pop/s of int8.
+// A workgroup is ONE wavefront: it scans a chunk for 64 queries (two groups of 32, two
+// independent accumulator chains).  Lane l of the 32 x 32 result holds 16 sums of query
+// (l mod 32): each is compared with that query's bound, and the rare pass is appended to the
+// query's list in LDS.  Outputs as the other query-tiled kernels: lists per (query, chunk), a
+// flag on overflow.  (The matrix units multiply signed bytes; the entries go in shifted by 128.)
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+constexpr int MFMA_QW = 64;    // queries per wavefront
+constexpr int MFMA_SUB = 2;    // 32-code steps per load
+
+template <int B>
+__global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
+    const uint8_t *__restrict__ codes, int64_t n, int64_t chunk, int nq, int cap_i,
+    const uint8_t *__restrict__ qluts, const unsigned *__restrict__ taus, char *__restrict__ ws,
+    size_t ws_stride, size_t countsA_off, size_t listsA_off, unsigned *__restrict__ flags)
+{
+    constexpr int WPC = B / 4;  // 32-bit words per code
+    __shared__ unsigned keys[MFMA_QW][TILED_LCAP];
+    __shared__ unsigned cnt[MFMA_QW];
+    __shared__ v4i_t onehot[16];  // onehot[c]: 16 bytes, byte c is 1
+
+    const int l = threadIdx.x;
+    const int row = l & 31, half = l >> 5;
+    int set, gc;
+    tiled_group_and_chunk((nq + MFMA_QW - 1) / MFMA_QW, set, gc);
+    const int q0 = set * MFMA_QW;
+    const unsigned cap = (unsigned)cap_i;
+    const int64_t c0 = (int64_t)gc * chunk;
+    const int64_t c1 = min(n, c0 + chunk);
+    if (c0 >= c1) return;  // uniform
+
+    // this lane's table entries: for code byte jb, the 16 entries of table 2jb + half of query
+    // q0 + 32g + row (zeros for a query that does not exist: it never passes)
+    // The matrix unit multiplies SIGNED bytes: an entry e goes in as e - 128 (= e xor 0x80), every
+    // sum then comes out as sum - 128 * (2B tables) and the bounds are shifted by the same amount.
+    constexpr int SHIFT = 128 * 2 * B;
+    v4i_t tb[2][B];
+    int thr[2];  // a shifted sum passes when it is <= thr
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int q = q0 + 32 * g + row;
+        thr[g] = -1 - SHIFT;  // no query in this slot: nothing passes
+        if (q < nq) {
+            const unsigned t = taus[q];
+            thr[g] = ((t >= cap) ? 0x7fffffff : (int)t) - SHIFT;
+        }
+#pragma unroll
+        for (int jb = 0; jb < B; ++jb) {  // (loads without a branch around them: all in flight at once)
+            const v4i_t e = *reinterpret_cast<const v4i_t *>(qluts + ((size_t)min(q, nq - 1) * (2 * B) + 2 * jb + half) * 16);
+            const int flip = (q < nq) ? (int)0x80808080u : 0, keep = (q < nq) ? -1 : 0;
+            tb[g][jb] = v4i_t{(e[0] ^ flip) & keep, (e[1] ^ flip) & keep, (e[2] ^ flip) & keep, (e[3] ^ flip) & keep};
+        }
+    }
+    cnt[l] = 0;
+    if (l < 16) {
+        const int bit = 1 << (8 * (l & 3));
+        onehot[l] = v4i_t{(l >> 2) == 0 ? bit : 0, (l >> 2) == 1 ? bit : 0, (l >> 2) == 2 ? bit : 0, (l >> 2) == 3 ? bit : 0};
+    }
+    __syncthreads();
+
+    // codes: lane (row, half) reads code `row` of each 32-code step (both halves read the same code)
+    unsigned cw[MFMA_SUB][WPC], cn[MFMA_SUB][WPC];
+    auto fetch = [&](int64_t t0, unsigned (&dst)[MFMA_SUB][WPC]) {
+#pragma unroll
+        for (int s = 0; s < MFMA_SUB; ++s) {
+            const int64_t i = t0 + 32 * s + row;
+            const bool in = i < c1;
+            const unsigned *src = reinterpret_cast<const unsigned *>(codes + (in ? i : c0) * B);
+#pragma unroll
+            for (int k = 0; k < WPC; ++k) dst[s][k] = in ? src[k] : 0u;
+        }
+    };
+    fetch(c0, cn);
+    // the one-hot operand of code byte jb of a code whose words are w[]: read from LDS at offset
+    // 16 * (this lane's nibble of the byte)
+    auto operand = [&](const unsigned (&w)[WPC], int jb) {
+        const unsigned nib16 = ((half ? (w[jb >> 2] >> 4) : w[jb >> 2]) & 0x0f0f0f0fu) << 4;
+        const unsigned off = (nib16 >> (8 * (jb & 3))) & 0xffu;
+        return *reinterpret_cast<const v4i_t *>(reinterpret_cast<const char *>(onehot) + off);
+    };
+    // the operands are read two products ahead, across the steps as well
+    v4i_t a0 = operand(cn[0], 0), a1 = operand(cn[0], 1);
+    for (int64_t t0 = c0; t0 < c1; t0 += 32 * MFMA_SUB) {  // uniform
+#pragma unroll
+        for (int s = 0; s < MFMA_SUB; ++s)
+#pragma unroll
+            for (int k = 0; k < WPC; ++k) cw[s][k] = cn[s][k];
+        if (t0 + 32 * MFMA_SUB < c1) fetch(t0 + 32 * MFMA_SUB, cn);  // the next codes travel meanwhile
+#pragma unroll
+        for (int s = 0; s < MFMA_SUB; ++s) {
+            if (t0 + 32 * s >= c1) break;  // uniform
+            v16i_t acc0, acc1;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { acc0[v] = 0; acc1[v] = 0; }
+#pragma unroll
+            for (int jb = 0; jb < B; ++jb) {
+                const v4i_t a = a0;
+                a0 = a1;
+                // (past the last step of the last load these are operands nobody uses)
+                if (jb + 2 < B) a1 = operand(cw[s], jb + 2);
+                else if (s + 1 < MFMA_SUB) a1 = operand(cw[s + 1], jb + 2 - B);
+                else a1 = operand(cn[0], jb + 2 - B);
+                acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, tb[0][jb], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, tb[1][jb], acc1, 0, 0, 0);
+            }
+            // result v of this lane: code (v / 4) * 8 + half * 4 + v % 4 of the step, query row (+32)
+            const unsigned rel = (unsigned)(t0 - c0) + 32u * s;
+            // smallest sum of each group of four results, then of all: one compare per query group
+            int qm0[4], qm1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                qm0[u] = min(min(acc0[4 * u], acc0[4 * u + 1]), min(acc0[4 * u + 2], acc0[4 * u + 3]));
+                qm1[u] = min(min(acc1[4 * u], acc1[4 * u + 1]), min(acc1[4 * u + 2], acc1[4 * u + 3]));
+            }
+            const int lo0 = min(min(qm0[0], qm0[1]), min(qm0[2], qm0[3]));
+            const int lo1 = min(min(qm1[0], qm1[1]), min(qm1[2], qm1[3]));
+            const bool any = lo0 <= thr[0] || lo1 <= thr[1];
+            if (__ballot(any) != 0ull) {  // some sum of the step passes: find it group by group
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (__ballot(qm0[u] <= thr[0]) != 0ull) {
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
+                            if (c0 + (int64_t)li < c1 && acc0[4 * u + w] <= thr[0]) {
+                                const unsigned slot = atomicAdd(&cnt[row], 1u);
+                                if (slot < (unsigned)TILED_LCAP)
+                                    keys[row][slot] = (min((unsigned)(acc0[4 * u + w] + SHIFT), cap) << 24) | li;
+                            }
+                        }
+                    }
+                    if (__ballot(qm1[u] <= thr[1]) != 0ull) {
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
+                            if (c0 + (int64_t)li < c1 && acc1[4 * u + w] <= thr[1]) {
+                                const unsigned slot = atomicAdd(&cnt[32 + row], 1u);
+                                if (slot < (unsigned)TILED_LCAP)
+                                    keys[32 + row][slot] = (min((unsigned)(acc1[4 * u + w] + SHIFT), cap) << 24) | li;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // lane l reports for query q0 + l
+    const int q = q0 + l;
+    if (q < nq) {
+        const unsigned c = cnt[l];
+        if (c > (unsigned)TILED_LCAP) {
+            flags[q] = 1u;  // keys were dropped: this query is redone on its own
+        } else if (c) {
+            char *base = ws + (size_t)q * ws_stride;
+            unsigned *counts = reinterpret_cast<unsigned *>(base + countsA_off);
+            uint64_t *dst = reinterpret_cast<uint64_t *>(base + listsA_off) + (size_t)gc * TILED_LCAP;
+            counts[gc] = c;
+            for (unsigned i = 0; i < c; ++i) {
+                const unsigned key = keys[l][i];
+                dst[i] = ((uint64_t)(key >> 24) << 32) | (uint64_t)(c0 + (key & 0xffffffu));
+            }
+        }
+    }
+}
+
+template <int B>
+static int launch_tiled_mfma(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, int cap,
+                             const uint8_t *qluts, const unsigned *taus, char *ws, size_t ws_stride,
+                             size_t countsA_off, size_t listsA_off, unsigned *flags, hipStream_t st)
+{
+    const unsigned gc8 = (unsigned)ceil_div(t.GC, 8) * 8u;
+    dim3 grid((unsigned)ceil_div(nq, MFMA_QW) * gc8);
+    launch(QADC_PROF_SCAN, scan_u8_mfma_kernel<B>, grid, dim3(64), 0, st, codes, n, t.chunk, nq, cap, qluts, taus,
+           ws, ws_stride, countsA_off, listsA_off, flags);
+    return QADC_OK;
 }
 
 template <int B>
@@ -584,10 +786,18 @@ int run_tiled_seed(const TiledPlan &t, const uint8_t *codes, int64_t n, const ui
 
 int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, int cap, int R,
                    unsigned *taus, char *ws, size_t ws_stride, size_t countsA_off, size_t listsA_off,
-                   unsigned *flags, hipStream_t st)
+                   unsigned *flags, const uint8_t *qluts16, hipStream_t st)
 {
     launch(QADC_PROF_SEED, scan_tau_kernel, dim3((unsigned)ceil_div(nq, 4)), dim3(256), 0, st,
            (const char *)ws, ws_stride, nq, R, taus);
+    // (a last, short sub-batch of a large batch goes to the other kernels, over the same chunks)
+    if (t.mfma && qluts16 && nq >= TILED_MFMA_MIN_Q) {
+        switch (t.B) {
+        case 4: return launch_tiled_mfma<4>(t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
+        case 8: return launch_tiled_mfma<8>(t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
+        default: return launch_tiled_mfma<16>(t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
+        }
+    }
     switch (t.B) {
     case 4: return launch_tiled<4>(t, codes, n, nq, cap, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
     case 8: return launch_tiled<8>(t, codes, n, nq, cap, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
