@@ -12,13 +12,14 @@ constexpr int tiled_nt(int B) { return B >= 32 ? 1024 : 512; }
 constexpr int TILED_LCAP = 64;         // keys a workgroup can report per query
 constexpr int TILED_MAX_CHUNKS = 1024; // database chunks per query
 constexpr int TILED_MIN_Q = 8;         // smallest batch worth tiling
-constexpr int TILED_MFMA_MIN_Q = 96;   // smallest batch for the matrix-core kernel (64 queries per wavefront)
+constexpr int TILED_MFMA_MIN_Q = 32;   // smallest batch for the matrix-core kernel (32 queries per wavefront; twice that below 16 code bytes)
+constexpr int TILED_MFMA_MIN_Q2 = 128; // smallest batch for its 64-queries-per-wavefront form
 
 struct TiledPlan {
     int B, GC;
     int64_t chunk;
     size_t lds_bytes;
-    bool mfma;  // batches of at least TILED_MFMA_MIN_Q queries go to the matrix-core kernel
+    bool mfma;  // (sub-)batches of TILED_MFMA_MIN_Q queries or more go to the matrix-core kernel
 };
 
 // codes4: 4-bit codes with the queries' 16-entry tables at hand (what the matrix-core kernel reads)

@@ -356,14 +356,23 @@ __global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled16_kernel(
     }
 }
 
+// smallest batches for the matrix-core kernel (from 32 queries with 16 code bytes or more, from 64
+// with fewer: measured against the vector-ALU kernels over 10 M codes) and for its
+// 64-queries-per-wavefront form
+static int mfma_min_q(int B)
+{
+    return std::max(1, env_int("QADC_MFMA_MIN_Q", B >= 16 ? TILED_MFMA_MIN_Q : 2 * TILED_MFMA_MIN_Q));
+}
+static int mfma_min_q2() { return std::max(1, env_int("QADC_MFMA_MIN_Q2", TILED_MFMA_MIN_Q2)); }
+
 bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 {
     t->B = m / 2;
     const int cpt = (t->B <= 16) ? SCAN_VEC * (16 / t->B) : 1;
     const int tile = tiled_nt(t->B) * cpt;
-    // 4-bit codes, up to 32 code bytes, a batch that fills a good part of a 64-query wavefront:
-    // the matrix-core kernel scans it
-    t->mfma = codes4 && t->B <= 16 && nq >= TILED_MFMA_MIN_Q && env_int("QADC_TILED_MFMA", 1) != 0;
+    // 4-bit codes and a batch that fills a good part of a wavefront's 32 or 64 queries: the
+    // matrix-core kernel scans it
+    t->mfma = codes4 && nq >= mfma_min_q(t->B) && env_int("QADC_TILED_MFMA", 1) != 0;
     // chunks: at most TILED_MAX_CHUNKS per query, a multiple of the tile, below 2^24 codes (index
     // bits of a key); as long as possible (a workgroup builds its tables once per chunk) while
     // groups x chunks still make about four workgroups per compute unit: 64 tiles with many query
@@ -374,7 +383,8 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
     int64_t want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(1024, groups)));
     int64_t lo = 8, hi = 64;
     if (t->mfma) {
-        want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(4096, ceil_div(nq, 64))));
+        const int qw = (t->B <= 16 && nq >= mfma_min_q2()) ? 64 : 32;
+        want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(4096, ceil_div(nq, qw))));
         lo = 2;
         hi = 1ll << 40;
     }
@@ -403,32 +413,35 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 // registers for the whole scan (the one-hot operand is read from a 16-entry table in LDS:
 // composing it with compares and selects made the vector ALU the limit), and 15 of 16 multiplications
 // are by zero -- which the matrix units can afford: measured here they run 4.0 Pop/s of int8.
-// A workgroup is ONE wavefront: it scans a chunk for 64 queries (two groups of 32, two
-// independent accumulator chains).  Lane l of the 32 x 32 result holds 16 sums of query
+// A workgroup is ONE wavefront: it scans a chunk for 32 G queries (G groups of 32, G independent
+// accumulator chains).  Lane l of the 32 x 32 result holds 16 sums of query
 // (l mod 32): each is compared with that query's bound, and the rare pass is appended to the
 // query's list in LDS.  Outputs as the other query-tiled kernels: lists per (query, chunk), a
 // flag on overflow.  (The matrix units multiply signed bytes; the entries go in shifted by 128.)
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
-constexpr int MFMA_QW = 64;    // queries per wavefront
 constexpr int MFMA_SUB = 2;    // 32-code steps per load
 
-template <int B>
+// G: groups of 32 queries per wavefront.  2 for large batches of up to 32 code bytes (the table
+// operands of 64 queries fill 128 registers when B = 16); 1 for B = 32 and for batches that would
+// leave most of a 64-query wavefront empty.
+template <int B, int G>
 __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     const uint8_t *__restrict__ codes, int64_t n, int64_t chunk, int nq, int cap_i,
     const uint8_t *__restrict__ qluts, const unsigned *__restrict__ taus, char *__restrict__ ws,
     size_t ws_stride, size_t countsA_off, size_t listsA_off, unsigned *__restrict__ flags)
 {
-    constexpr int WPC = B / 4;  // 32-bit words per code
-    __shared__ unsigned keys[MFMA_QW][TILED_LCAP];
-    __shared__ unsigned cnt[MFMA_QW];
+    constexpr int WPC = B / 4;   // 32-bit words per code
+    constexpr int QW = 32 * G;   // queries per wavefront
+    __shared__ unsigned keys[QW][TILED_LCAP];
+    __shared__ unsigned cnt[QW];
     __shared__ v4i_t onehot[16];  // onehot[c]: 16 bytes, byte c is 1
 
     const int l = threadIdx.x;
     const int row = l & 31, half = l >> 5;
     int set, gc;
-    tiled_group_and_chunk((nq + MFMA_QW - 1) / MFMA_QW, set, gc);
-    const int q0 = set * MFMA_QW;
+    tiled_group_and_chunk((nq + QW - 1) / QW, set, gc);
+    const int q0 = set * QW;
     const unsigned cap = (unsigned)cap_i;
     const int64_t c0 = (int64_t)gc * chunk;
     const int64_t c1 = min(n, c0 + chunk);
@@ -439,10 +452,10 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     // The matrix unit multiplies SIGNED bytes: an entry e goes in as e - 128 (= e xor 0x80), every
     // sum then comes out as sum - 128 * (2B tables) and the bounds are shifted by the same amount.
     constexpr int SHIFT = 128 * 2 * B;
-    v4i_t tb[2][B];
-    int thr[2];  // a shifted sum passes when it is <= thr
+    v4i_t tb[G][B];
+    int thr[G];  // a shifted sum passes when it is <= thr
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
+    for (int g = 0; g < G; ++g) {
         const int q = q0 + 32 * g + row;
         thr[g] = -1 - SHIFT;  // no query in this slot: nothing passes
         if (q < nq) {
@@ -456,7 +469,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
             tb[g][jb] = v4i_t{(e[0] ^ flip) & keep, (e[1] ^ flip) & keep, (e[2] ^ flip) & keep, (e[3] ^ flip) & keep};
         }
     }
-    cnt[l] = 0;
+    if (l < QW) cnt[l] = 0;
     if (l < 16) {
         const int bit = 1 << (8 * (l & 3));
         onehot[l] = v4i_t{(l >> 2) == 0 ? bit : 0, (l >> 2) == 1 ? bit : 0, (l >> 2) == 2 ? bit : 0, (l >> 2) == 3 ? bit : 0};
@@ -494,9 +507,11 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
 #pragma unroll
         for (int s = 0; s < MFMA_SUB; ++s) {
             if (t0 + 32 * s >= c1) break;  // uniform
-            v16i_t acc0, acc1;
+            v16i_t acc[G];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { acc0[v] = 0; acc1[v] = 0; }
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[g][v] = 0;
 #pragma unroll
             for (int jb = 0; jb < B; ++jb) {
                 const v4i_t a = a0;
@@ -505,43 +520,35 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
                 if (jb + 2 < B) a1 = operand(cw[s], jb + 2);
                 else if (s + 1 < MFMA_SUB) a1 = operand(cw[s + 1], jb + 2 - B);
                 else a1 = operand(cn[0], jb + 2 - B);
-                acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, tb[0][jb], acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, tb[1][jb], acc1, 0, 0, 0);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, tb[g][jb], acc[g], 0, 0, 0);
             }
-            // result v of this lane: code (v / 4) * 8 + half * 4 + v % 4 of the step, query row (+32)
+            // result v of this lane: code (v / 4) * 8 + half * 4 + v % 4 of the step, query row (+32g)
             const unsigned rel = (unsigned)(t0 - c0) + 32u * s;
             // smallest sum of each group of four results, then of all: one compare per query group
-            int qm0[4], qm1[4];
+            int qm[G][4];
+            bool any = false;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                qm0[u] = min(min(acc0[4 * u], acc0[4 * u + 1]), min(acc0[4 * u + 2], acc0[4 * u + 3]));
-                qm1[u] = min(min(acc1[4 * u], acc1[4 * u + 1]), min(acc1[4 * u + 2], acc1[4 * u + 3]));
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    qm[g][u] = min(min(acc[g][4 * u], acc[g][4 * u + 1]), min(acc[g][4 * u + 2], acc[g][4 * u + 3]));
+                any = any || min(min(qm[g][0], qm[g][1]), min(qm[g][2], qm[g][3])) <= thr[g];
             }
-            const int lo0 = min(min(qm0[0], qm0[1]), min(qm0[2], qm0[3]));
-            const int lo1 = min(min(qm1[0], qm1[1]), min(qm1[2], qm1[3]));
-            const bool any = lo0 <= thr[0] || lo1 <= thr[1];
             if (__ballot(any) != 0ull) {  // some sum of the step passes: find it group by group
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    if (__ballot(qm0[u] <= thr[0]) != 0ull) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        if (__ballot(qm[g][u] <= thr[g]) == 0ull) continue;
 #pragma unroll
                         for (int w = 0; w < 4; ++w) {
                             const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
-                            if (c0 + (int64_t)li < c1 && acc0[4 * u + w] <= thr[0]) {
-                                const unsigned slot = atomicAdd(&cnt[row], 1u);
+                            if (c0 + (int64_t)li < c1 && acc[g][4 * u + w] <= thr[g]) {
+                                const unsigned slot = atomicAdd(&cnt[32 * g + row], 1u);
                                 if (slot < (unsigned)TILED_LCAP)
-                                    keys[row][slot] = (min((unsigned)(acc0[4 * u + w] + SHIFT), cap) << 24) | li;
-                            }
-                        }
-                    }
-                    if (__ballot(qm1[u] <= thr[1]) != 0ull) {
-#pragma unroll
-                        for (int w = 0; w < 4; ++w) {
-                            const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
-                            if (c0 + (int64_t)li < c1 && acc1[4 * u + w] <= thr[1]) {
-                                const unsigned slot = atomicAdd(&cnt[32 + row], 1u);
-                                if (slot < (unsigned)TILED_LCAP)
-                                    keys[32 + row][slot] = (min((unsigned)(acc1[4 * u + w] + SHIFT), cap) << 24) | li;
+                                    keys[32 * g + row][slot] = (min((unsigned)(acc[g][4 * u + w] + SHIFT), cap) << 24) | li;
                             }
                         }
                     }
@@ -553,7 +560,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
 
     // lane l reports for query q0 + l
     const int q = q0 + l;
-    if (q < nq) {
+    if (l < QW && q < nq) {
         const unsigned c = cnt[l];
         if (c > (unsigned)TILED_LCAP) {
             flags[q] = 1u;  // keys were dropped: this query is redone on its own
@@ -570,14 +577,14 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     }
 }
 
-template <int B>
+template <int B, int G>
 static int launch_tiled_mfma(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, int cap,
                              const uint8_t *qluts, const unsigned *taus, char *ws, size_t ws_stride,
                              size_t countsA_off, size_t listsA_off, unsigned *flags, hipStream_t st)
 {
     const unsigned gc8 = (unsigned)ceil_div(t.GC, 8) * 8u;
-    dim3 grid((unsigned)ceil_div(nq, MFMA_QW) * gc8);
-    launch(QADC_PROF_SCAN, scan_u8_mfma_kernel<B>, grid, dim3(64), 0, st, codes, n, t.chunk, nq, cap, qluts, taus,
+    dim3 grid((unsigned)ceil_div(nq, 32 * G) * gc8);
+    launch(QADC_PROF_SCAN, (scan_u8_mfma_kernel<B, G>), grid, dim3(64), 0, st, codes, n, t.chunk, nq, cap, qluts, taus,
            ws, ws_stride, countsA_off, listsA_off, flags);
     return QADC_OK;
 }
@@ -791,12 +798,16 @@ int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, 
     launch(QADC_PROF_SEED, scan_tau_kernel, dim3((unsigned)ceil_div(nq, 4)), dim3(256), 0, st,
            (const char *)ws, ws_stride, nq, R, taus);
     // (a last, short sub-batch of a large batch goes to the other kernels, over the same chunks)
-    if (t.mfma && qluts16 && nq >= TILED_MFMA_MIN_Q) {
+    if (t.mfma && qluts16 && nq >= mfma_min_q(t.B)) {
+#define QADC_MFMA_ARGS t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st
+        const bool two = t.B <= 16 && nq >= mfma_min_q2();  // 64 queries per wavefront
         switch (t.B) {
-        case 4: return launch_tiled_mfma<4>(t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
-        case 8: return launch_tiled_mfma<8>(t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
-        default: return launch_tiled_mfma<16>(t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);
+        case 4: return two ? launch_tiled_mfma<4, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<4, 1>(QADC_MFMA_ARGS);
+        case 8: return two ? launch_tiled_mfma<8, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<8, 1>(QADC_MFMA_ARGS);
+        case 16: return two ? launch_tiled_mfma<16, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<16, 1>(QADC_MFMA_ARGS);
+        default: return launch_tiled_mfma<32, 1>(QADC_MFMA_ARGS);
         }
+#undef QADC_MFMA_ARGS
     }
     switch (t.B) {
     case 4: return launch_tiled<4>(t, codes, n, nq, cap, taus, ws, ws_stride, countsA_off, listsA_off, flags, st);

@@ -563,13 +563,13 @@ def test_scan_topk_query_groups_by_bound(Q, O, m):
         assert np.array_equal(gd[iq], wd), (m, iq)
 
 
-@pytest.mark.parametrize("m", [8, 16, 32])
-@pytest.mark.parametrize("nq,R,nbins", [(130, 100, 255), (97, 1000, 127), (256, 10, 255)])
+@pytest.mark.parametrize("m", [8, 16, 32, 64])
+@pytest.mark.parametrize("nq,R,nbins", [(130, 100, 255), (97, 1000, 127), (256, 10, 255), (40, 100, 255)])
 def test_scan_topk_large_batches_on_the_matrix_cores(Q, O, m, nq, R, nbins):
-    """Batches of about a hundred queries and more of 4-bit codes are scanned as one-hot matrix
-    products (64 queries per wavefront): full and partial 64-query sets, a ragged database tail,
-    tables that tie heavily, saturate, exceed nbins or are all zero (those queries overflow their
-    lists and are redone one by one).  Indices and sums equal the plain-C scan bit for bit."""
+    """Batches of 4-bit codes from 32 queries up (64 for short codes) are scanned as one-hot matrix
+    products, 32 or 64 queries per wavefront: full and partial sets of queries, a ragged database
+    tail, tables that tie heavily, saturate, exceed nbins or are all zero (those queries overflow
+    their lists and are redone one by one).  Indices and sums equal the plain-C scan bit for bit."""
     from oracle import cref
     rng = np.random.default_rng(m * 1000 + nq)
     n = 600_011
@@ -578,9 +578,9 @@ def test_scan_topk_large_batches_on_the_matrix_cores(Q, O, m, nq, R, nbins):
     qluts = rng.integers(0, 1 + 255 // m, size=(nq, m, 16)).astype(np.uint8)
     qluts[3] = 0                                        # every sum ties
     qluts[11] = rng.integers(0, 2, size=(m, 16))        # two-valued entries
-    qluts[40] = 255                                     # everything saturates
-    qluts[64] = rng.integers(100, 256, size=(m, 16))    # entries beyond nbins = 127
-    qluts[70, :, :8] = 0                                # many zero sums
+    qluts[33] = 255                                     # everything saturates
+    qluts[64 % nq] = rng.integers(100, 256, size=(m, 16))    # entries beyond nbins = 127
+    qluts[70 % nq, :, :8] = 0                           # many zero sums
     qluts[nq - 1] = rng.integers(0, 4, size=(m, 16))
     wi, wd = cref.scan_topk_u8(codes, qluts, R, nbins)
     idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, to_gpu(codes), to_gpu(qluts), R, nbins)
