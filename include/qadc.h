@@ -143,7 +143,8 @@ int qadc_quantize_luts_8bit(const float *luts, int nq, int ngroup, int m,
  *   codes    [n][m/2] u8 (4-bit variants) or [n][m] u8 (8-bit), standard layout
  *   m        4-bit variants: 8, 16, 32 or 64;  8-bit variants: 4, 8, 16 or 32
  *   luts     [nq][m][16] u8, [nq][m][16] f32, [nq][m][256] f32 or [nq][m][256] u8 by variant
- *            (4-byte aligned;
+ *            (4-byte aligned; batches of 16-entry u8 tables that are 16-byte aligned can be
+ *            scanned by the matrix-core kernel, others take the vector kernels -- same results;
  *            float tables are expected non-negative, as squared distances are)
  *   nbins    saturation value of the u8 variant (1..255); ignored otherwise
  *   R        1..QADC_MAX_R

@@ -798,7 +798,8 @@ int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, 
     launch(QADC_PROF_SEED, scan_tau_kernel, dim3((unsigned)ceil_div(nq, 4)), dim3(256), 0, st,
            (const char *)ws, ws_stride, nq, R, taus);
     // (a last, short sub-batch of a large batch goes to the other kernels, over the same chunks)
-    if (t.mfma && qluts16 && nq >= mfma_min_q(t.B)) {
+    // (its table operands are 16-byte loads: tables at any other alignment go the other way too)
+    if (t.mfma && qluts16 && reinterpret_cast<uintptr_t>(qluts16) % 16 == 0 && nq >= mfma_min_q(t.B)) {
 #define QADC_MFMA_ARGS t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st
         const bool two = t.B <= 16 && nq >= mfma_min_q2();  // 64 queries per wavefront
         switch (t.B) {

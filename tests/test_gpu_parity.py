@@ -588,6 +588,25 @@ def test_scan_topk_large_batches_on_the_matrix_cores(Q, O, m, nq, R, nbins):
     assert np.array_equal(dist.cpu().numpy(), wd)
 
 
+def test_scan_topk_batch_with_tables_at_a_4_byte_offset(Q, O):
+    """Tables that are only 4-byte aligned (the documented minimum) in a batch large enough for the
+    matrix-core kernel, whose operands are 16-byte loads: the batch takes the other kernels."""
+    import torch
+    from oracle import cref
+    rng = np.random.default_rng(77)
+    n, m, nq, R = 300_011, 32, 70, 100
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    qluts = rng.integers(0, 9, size=(nq, m, 16)).astype(np.uint8)
+    buf = torch.zeros((qluts.size + 64,), dtype=torch.uint8, device="cuda:0")
+    off = 4 + (-buf.data_ptr()) % 16            # address = 4 mod 16
+    g = buf[off:off + qluts.size].view(nq, m, 16)
+    g.copy_(to_gpu(qluts))
+    assert g.data_ptr() % 16 == 4
+    wi, wd = cref.scan_topk_u8(codes, qluts, R, 255)
+    idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, to_gpu(codes), g, R)
+    assert np.array_equal(idx_np(idx), wi) and np.array_equal(dist.cpu().numpy(), wd)
+
+
 def test_search_batch_config1_shaped(Q, O):
     """qadc_search on a batch of 16 mixture queries over a long database (fused prepare kernel +
     query-tiled scan) against the oracle's replay of the integer part and its own tables."""
