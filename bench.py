@@ -248,6 +248,7 @@ def run_batched(args):
                         "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s", "frac": round(ops / MFMA_I8_PEAK_TOPS, 4),
                         "note": "int8 operations issued; 15 of 16 multiply by a zero of the one-hot operand",
                         "useful_T_lookup_adds_per_s": round(ach, 2),
+                        "frac_of_vector_alu_byte_lane_ceiling": round(ach / ALU_PEAK_TLOOKUPS, 4),
                         "traffic": MFMA_TRAFFIC if (n, m, nb) == (100_000_000, 32, 256) else None,
                         "traffic_source": "profiles/hbm_traffic_configs_3_4_5.md (rocprofv3 --pmc FETCH_SIZE, bytes read per launch)",
                         "scan_ms": round(ms_scan, 3), "launches_timed": launches}

@@ -377,18 +377,20 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
     // bits of a key); as long as possible (a workgroup builds its tables once per chunk) while
     // groups x chunks still make about four workgroups per compute unit: 64 tiles with many query
     // groups, down to 8 tiles for a batch of one or two groups over a short database.  The
-    // matrix-core kernel runs one wavefront per (64 queries, chunk): it wants about 4096 of them
-    // (two rounds of two per SIMD), each at least two tiles long.
+    // matrix-core kernel runs one wavefront per (32 or 64 queries, chunk): it wants about 4096 of
+    // them (two to four per SIMD, twice over), each at least two tiles long, so a batch of one or
+    // two such sets is cut into up to TILED_MFMA_MAX_CHUNKS chunks.
     const int64_t groups = ceil_div(nq, 16);
     int64_t want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(1024, groups)));
-    int64_t lo = 8, hi = 64;
+    int64_t lo = 8, hi = 64, max_chunks = TILED_MAX_CHUNKS;
     if (t->mfma) {
         const int qw = (t->B <= 16 && nq >= mfma_min_q2()) ? 64 : 32;
-        want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(4096, ceil_div(nq, qw))));
+        max_chunks = TILED_MFMA_MAX_CHUNKS;
+        want = std::max<int64_t>(1, std::min<int64_t>(max_chunks, ceil_div(4096, ceil_div(nq, qw))));
         lo = 2;
         hi = 1ll << 40;
     }
-    int64_t chunk = ceil_div(ceil_div(n, TILED_MAX_CHUNKS), tile) * tile;
+    int64_t chunk = ceil_div(ceil_div(n, max_chunks), tile) * tile;
     int64_t by_fill = ceil_div(ceil_div(n, want), tile) * tile;
     if (by_fill > hi * tile) by_fill = hi * tile;
     if (by_fill < lo * tile) by_fill = lo * tile;
