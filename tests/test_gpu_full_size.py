@@ -51,8 +51,8 @@ def test_config2_single_query_search_10m_codes(env):
 
 
 def test_config3_query_batch_100m_codes(env):
-    """N = 100 M, m = 32: a 256-query batch through qadc_search (query-tiled kernel); 12 of its
-    queries are rescanned in full by the oracle."""
+    """N = 100 M, m = 32: a 256-query batch through qadc_search (matrix-core batched scan); 12 of
+    its queries are rescanned in full by the oracle."""
     Q, torch, bench, O, cref = env
     from workloads import MixtureSpec, SEED_QUERY
     from workloads.mixture_torch import mixture_vectors_torch
@@ -68,6 +68,13 @@ def test_config3_query_batch_100m_codes(env):
     wi, wd = cref.scan_topk_u8(h_codes, ql.cpu().numpy()[pick], R)
     assert np.array_equal(idx_np(gi)[pick], wi)
     assert np.array_equal(gd.cpu().numpy()[pick], wd)
+    # the same queries in tiles of 64 and of 32 (other launch shapes: 32 queries per wavefront, more
+    # and shorter chunks) give the same rows
+    for t0, t1 in ((0, 64), (64, 96)):
+        ti, td = Q.qadc_search(cb, queries[t0:t1], codes, R, init)
+        torch.cuda.synchronize()
+        assert np.array_equal(idx_np(ti), idx_np(gi)[t0:t1])
+        assert np.array_equal(td.cpu().numpy(), gd.cpu().numpy()[t0:t1])
 
 
 def test_config5_float_and_quantized_scans_50m_codes(env):
