@@ -588,6 +588,19 @@ def test_scan_topk_large_batches_on_the_matrix_cores(Q, O, m, nq, R, nbins):
     assert np.array_equal(dist.cpu().numpy(), wd)
 
 
+def test_scan_topk_a_thousand_queries_in_one_call(Q, O):
+    """A call with far more queries than one launch takes (the workspace bounds the queries per
+    launch): full sub-batches and a last short one."""
+    from oracle import cref
+    rng = np.random.default_rng(5)
+    n, m, nq, R = 600_011, 16, 1003, 10
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    qluts = rng.integers(0, 17, size=(nq, m, 16)).astype(np.uint8)
+    wi, wd = cref.scan_topk_u8(codes, qluts, R, 255)
+    idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, to_gpu(codes), to_gpu(qluts), R)
+    assert np.array_equal(idx_np(idx), wi) and np.array_equal(dist.cpu().numpy(), wd)
+
+
 def test_scan_topk_batch_with_tables_at_a_4_byte_offset(Q, O):
     """Tables that are only 4-byte aligned (the documented minimum) in a batch large enough for the
     matrix-core kernel, whose operands are 16-byte loads: the batch takes the other kernels."""
