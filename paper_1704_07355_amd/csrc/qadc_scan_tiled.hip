@@ -386,7 +386,7 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
     if (t->mfma) {
         const int qw = (t->B <= 16 && nq >= mfma_min_q2()) ? 64 : 32;
         max_chunks = TILED_MFMA_MAX_CHUNKS;
-        want = std::max<int64_t>(1, std::min<int64_t>(max_chunks, ceil_div(4096, ceil_div(nq, qw))));
+        want = std::max<int64_t>(1, std::min<int64_t>(max_chunks, ceil_div(std::max(64, env_int("QADC_MFMA_WAVES", 4096)), ceil_div(nq, qw))));
         lo = 2;
         hi = 1ll << 40;
     }
