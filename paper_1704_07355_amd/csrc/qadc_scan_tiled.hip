@@ -364,6 +364,7 @@ static int mfma_min_q(int B)
     return std::max(1, env_int("QADC_MFMA_MIN_Q", B >= 16 ? TILED_MFMA_MIN_Q : 2 * TILED_MFMA_MIN_Q));
 }
 static int mfma_min_q2() { return std::max(1, env_int("QADC_MFMA_MIN_Q2", TILED_MFMA_MIN_Q2)); }
+static int mfma_min_q4() { return std::max(1, env_int("QADC_MFMA_MIN_Q4", TILED_MFMA_MIN_Q4)); }
 
 bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 {
@@ -384,8 +385,12 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
     int64_t want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(1024, groups)));
     int64_t lo = 8, hi = 64, max_chunks = TILED_MAX_CHUNKS;
     if (t->mfma) {
-        const int qw = (t->B <= 16 && nq >= mfma_min_q2()) ? 64 : 32;
-        max_chunks = TILED_MFMA_MAX_CHUNKS;
+        const int qw = (t->B <= 8 && nq >= mfma_min_q4()) ? 128 : (t->B <= 16 && nq >= mfma_min_q2()) ? 64 : 32;
+        // more chunks for small batches, as long as the lists of the whole batch (516 bytes per
+        // query and chunk) stay within half of the 256 MiB that one launch's workspace may take:
+        // beyond that the batch would be split into two launches
+        max_chunks = std::min<int64_t>(TILED_MFMA_MAX_CHUNKS,
+                                       std::max<int64_t>(TILED_MAX_CHUNKS, (128ll << 20) / (516ll * nq)));
         want = std::max<int64_t>(1, std::min<int64_t>(max_chunks, ceil_div(std::max(64, env_int("QADC_MFMA_WAVES", 4096)), ceil_div(nq, qw))));
         lo = 2;
         hi = 1ll << 40;
@@ -435,7 +440,8 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
 {
     constexpr int WPC = B / 4;   // 32-bit words per code
     constexpr int QW = 32 * G;   // queries per wavefront
-    __shared__ unsigned keys[QW][TILED_LCAP];
+    constexpr int LC = (G > 2) ? TILED_LCAP / 2 : TILED_LCAP;  // keys kept per query (LDS: 16 KiB of lists)
+    __shared__ unsigned keys[QW][LC];
     __shared__ unsigned cnt[QW];
     __shared__ v4i_t onehot[16];  // onehot[c]: 16 bytes, byte c is 1
 
@@ -471,7 +477,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
             tb[g][jb] = v4i_t{(e[0] ^ flip) & keep, (e[1] ^ flip) & keep, (e[2] ^ flip) & keep, (e[3] ^ flip) & keep};
         }
     }
-    if (l < QW) cnt[l] = 0;
+    for (int i = l; i < QW; i += 64) cnt[i] = 0;
     if (l < 16) {
         const int bit = 1 << (8 * (l & 3));
         onehot[l] = v4i_t{(l >> 2) == 0 ? bit : 0, (l >> 2) == 1 ? bit : 0, (l >> 2) == 2 ? bit : 0, (l >> 2) == 3 ? bit : 0};
@@ -549,7 +555,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
                             const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
                             if (c0 + (int64_t)li < c1 && acc[g][4 * u + w] <= thr[g]) {
                                 const unsigned slot = atomicAdd(&cnt[32 * g + row], 1u);
-                                if (slot < (unsigned)TILED_LCAP)
+                                if (slot < (unsigned)LC)
                                     keys[32 * g + row][slot] = (min((unsigned)(acc[g][4 * u + w] + SHIFT), cap) << 24) | li;
                             }
                         }
@@ -560,11 +566,12 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     }
     __syncthreads();
 
-    // lane l reports for query q0 + l
-    const int q = q0 + l;
-    if (l < QW && q < nq) {
-        const unsigned c = cnt[l];
-        if (c > (unsigned)TILED_LCAP) {
+    // a lane reports for query q0 + k, k = lane, lane + 64
+    for (int k = l; k < QW; k += 64) {
+        const int q = q0 + k;
+        if (q >= nq) break;
+        const unsigned c = cnt[k];
+        if (c > (unsigned)LC) {
             flags[q] = 1u;  // keys were dropped: this query is redone on its own
         } else if (c) {
             char *base = ws + (size_t)q * ws_stride;
@@ -572,7 +579,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
             uint64_t *dst = reinterpret_cast<uint64_t *>(base + listsA_off) + (size_t)gc * TILED_LCAP;
             counts[gc] = c;
             for (unsigned i = 0; i < c; ++i) {
-                const unsigned key = keys[l][i];
+                const unsigned key = keys[k][i];
                 dst[i] = ((uint64_t)(key >> 24) << 32) | (uint64_t)(c0 + (key & 0xffffffu));
             }
         }
@@ -804,9 +811,10 @@ int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, 
     if (t.mfma && qluts16 && reinterpret_cast<uintptr_t>(qluts16) % 16 == 0 && nq >= mfma_min_q(t.B)) {
 #define QADC_MFMA_ARGS t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st
         const bool two = t.B <= 16 && nq >= mfma_min_q2();  // 64 queries per wavefront
+        const bool four = t.B <= 8 && nq >= mfma_min_q4();  // 128
         switch (t.B) {
-        case 4: return two ? launch_tiled_mfma<4, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<4, 1>(QADC_MFMA_ARGS);
-        case 8: return two ? launch_tiled_mfma<8, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<8, 1>(QADC_MFMA_ARGS);
+        case 4: return four ? launch_tiled_mfma<4, 4>(QADC_MFMA_ARGS) : two ? launch_tiled_mfma<4, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<4, 1>(QADC_MFMA_ARGS);
+        case 8: return four ? launch_tiled_mfma<8, 4>(QADC_MFMA_ARGS) : two ? launch_tiled_mfma<8, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<8, 1>(QADC_MFMA_ARGS);
         case 16: return two ? launch_tiled_mfma<16, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<16, 1>(QADC_MFMA_ARGS);
         default: return launch_tiled_mfma<32, 1>(QADC_MFMA_ARGS);
         }
