@@ -10,6 +10,7 @@ slow and unblocked, so that it can be checked against the text by eye:
   Section 2.1          vector / product quantizers, codes of m*b bits; optimized product
                        quantizers opq(x) = pq(R x), R orthonormal
   Section 2.2          inverted index, residual encoding
+  Section 5 (related)  inverted multi-index as the coarse partition
   Section 2.3, Alg. 1  Index / Tables / Scan, Eq. (1) tables, Eq. (2) ADC
   Section 3.2, Fig. 2  two 4-bit components per byte, low nibble = even one;
                        lists transposed by blocks of 16 codes
@@ -517,6 +518,65 @@ def ivf_probes(query: np.ndarray, coarse: np.ndarray, nprobe: int) -> np.ndarray
     """Index step: the nprobe closest cells, closest first (ties -> lowest id)."""
     dist = sq_l2(query[None, :], coarse)[0]
     return np.argsort(dist, kind="stable")[:nprobe].astype(np.int32)
+
+
+# --------------------------------------------------------------------------
+# Related work: inverted multi-index as the coarse partition
+# --------------------------------------------------------------------------
+#
+# The paper's related-work section notes that Quick ADC, needing no minimum
+# list size, combines with the finer partition of an inverted multi-index.
+# There the coarse quantizer is a product of two quantizers over the two
+# halves of the vector: cell (i, j), id i*K + j, has the centroid
+# (halves[0][i], halves[1][j]).  Everything after the Index step is the
+# inverted-index search over those K*K cells.
+
+def multi_index_cells(halves: np.ndarray) -> np.ndarray:
+    """halves float32 [2][K][d/2] -> the K*K cell centroids float32 [K*K][d], cell id = i*K + j."""
+    K, dh = halves.shape[1], halves.shape[2]
+    out = np.empty((K, K, 2 * dh), dtype=np.float32)
+    out[:, :, :dh] = halves[0][:, None, :]
+    out[:, :, dh:] = halves[1][None, :, :]
+    return out.reshape(K * K, 2 * dh)
+
+
+def multi_index_assign(x: np.ndarray, halves: np.ndarray) -> np.ndarray:
+    """Cell of every vector: each half goes to its closest half-centroid (ties -> lowest)."""
+    K, dh = halves.shape[1], halves.shape[2]
+    return vq_encode(x[:, :dh], halves[0]) * K + vq_encode(x[:, dh:], halves[1])
+
+
+def multi_index_probes(query: np.ndarray, halves: np.ndarray, nprobe: int) -> np.ndarray:
+    """The nprobe cells with the smallest d1[i] + d2[j], smallest first (ties -> lowest cell id):
+    the definition, written out over all K*K cells."""
+    K, dh = halves.shape[1], halves.shape[2]
+    d1 = sq_l2(query[None, :dh], halves[0])[0]
+    d2 = sq_l2(query[None, dh:], halves[1])[0]
+    sums = (d1[:, None] + d2[None, :]).reshape(K * K)
+    return np.argsort(sums, kind="stable")[:nprobe].astype(np.int32)
+
+
+def multi_sequence(d1: np.ndarray, d2: np.ndarray, count: int):
+    """Cells (i, j) by increasing d1[i] + d2[j] without forming the K*K sums: walk the two sorted
+    lists from their heads; a pair enters the queue once both its predecessors (one rank lower in
+    either list) have been output.  Returns the first `count` (i, j)."""
+    import heapq
+    o1, o2 = np.argsort(d1, kind="stable"), np.argsort(d2, kind="stable")
+    K1, K2 = len(d1), len(d2)
+    done = set()
+    heap = [(d1[o1[0]] + d2[o2[0]], 0, 0)]
+    pushed = {(0, 0)}
+    out = []
+    while heap and len(out) < count:
+        _, r1, r2 = heapq.heappop(heap)
+        out.append((int(o1[r1]), int(o2[r2])))
+        done.add((r1, r2))
+        for a, b in ((r1 + 1, r2), (r1, r2 + 1)):
+            if a < K1 and b < K2 and (a, b) not in pushed:
+                if (a == 0 or (a - 1, b) in done) and (b == 0 or (a, b - 1) in done):
+                    heapq.heappush(heap, (d1[o1[a]] + d2[o2[b]], a, b))
+                    pushed.add((a, b))
+    return out
 
 
 def ivf_quick_adc_search(index, coarse, codebooks, query, nprobe, init, R, nbins=255,

@@ -501,3 +501,37 @@ def test_opq_with_identity_rotation_is_the_product_quantizer():
     rot, cb, hist = O.opq_train(x, 4, 16, 0, 3, rows)
     assert np.array_equal(rot, np.eye(8, dtype=np.float32)) and hist == []
     assert np.array_equal(cb, O.pq_train(x, 4, 16, 3, rows))
+
+
+# ------------------------------------------------------------------ inverted multi-index (Section 5)
+
+def test_multi_index_probe_order_on_a_worked_example():
+    """One component per half, query at the origin: d1 = (0, 1, 4), d2 = (0, 4, 9).  The nine sums in
+    order, equal sums by cell id: 0 (0,0); 1 (1,0); 4 (0,1) then (2,0); 5 (1,1); 8 (2,1); 9 (0,2);
+    10 (1,2); 13 (2,2)."""
+    from oracle import qadc_oracle as O
+    halves = np.array([[[0.0], [1.0], [2.0]], [[0.0], [2.0], [3.0]]], dtype=np.float32)
+    got = O.multi_index_probes(np.zeros(2, dtype=np.float32), halves, 9)
+    assert got.tolist() == [0, 3, 1, 6, 4, 7, 2, 5, 8]
+    cells = O.multi_index_cells(halves)
+    assert cells.shape == (9, 2) and cells[5].tolist() == [1.0, 3.0] and cells[6].tolist() == [2.0, 0.0]
+
+
+def test_multi_index_is_the_inverted_index_over_the_product_cells():
+    """The product structure: the closest cell is the pair of closest half-centroids, and the cells
+    by increasing d1 + d2 are the cells by increasing distance to the concatenated centroids; the
+    multi-sequence walk (which never forms the K*K sums) outputs the same order."""
+    from oracle import qadc_oracle as O
+    rng = np.random.default_rng(8)
+    K, dh, n = 23, 5, 400
+    halves = rng.normal(size=(2, K, dh)).astype(np.float32)
+    x = rng.normal(size=(n, 2 * dh)).astype(np.float32)
+    coarse = O.multi_index_cells(halves)
+    assert np.array_equal(O.multi_index_assign(x, halves), O.ivf_assign(x, coarse))
+    for y in x[:20]:
+        want = O.ivf_probes(y, coarse, 60)
+        assert np.array_equal(O.multi_index_probes(y, halves, 60), want)
+        d1 = O.sq_l2(y[None, :dh], halves[0])[0]
+        d2 = O.sq_l2(y[None, dh:], halves[1])[0]
+        walk = [i * K + j for i, j in O.multi_sequence(d1, d2, 60)]
+        assert walk == want.tolist()
