@@ -375,6 +375,28 @@ def run_ivf(args):
                                 "(profiles/hbm_traffic_configs_3_4_5.md)",
                 "scan_ms_per_batch": round(phase["scan"], 3), "codes_scanned_per_query": round(scanned / nb)}
 
+    # beside it: the Index step of an inverted multi-index with as many cells (two quantizers of
+    # sqrt(K) half-centroids, seeded at random: only the step's cost is measured here)
+    multi_index = None
+    kh = int(round(K ** 0.5))
+    if kh * kh == K and kh <= 4096 and nprobe <= 256:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        halves = torch.rand((2, kh, args.d // 2), generator=gen, device=dev) * 255.0
+        qb = queries[last * nb:(last + 1) * nb]
+        mi_ws = torch.empty((Q.qadc_multi_index_workspace_bytes(kh, nb, nprobe),), dtype=torch.uint8, device=dev)
+        mi_out = torch.empty((nb, nprobe), dtype=torch.int32, device=dev)
+        for _ in range(2):
+            Q.qadc_multi_index_probes(halves, qb, nprobe, workspace=mi_ws, out=mi_out)
+        m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        m0.record()
+        for _ in range(10):
+            Q.qadc_multi_index_probes(halves, qb, nprobe, workspace=mi_ws, out=mi_out)
+        m1.record()
+        torch.cuda.synchronize()
+        multi_index = {"half_centroids": kh, "cells": K, "index_step_ms_per_batch": round(m0.elapsed_time(m1) / 10, 4),
+                       "inverted_index_step_ms_per_batch": round(phase["index"], 4)}
+
     cpu = None
     if args.cpu_queries > 0:
         from oracle import qadc_oracle as O
@@ -420,6 +442,7 @@ def run_ivf(args):
                    "n": n, "K": K, "m": m, "nprobe": nprobe, "R": R, "init": init, "batch": nb},
         "gcodes_scanned_per_s": round(scanned / (ms_per_step * 1e-3) / 1e9, 2),
         "phase_ms_per_query": {k: round(v / nb, 5) for k, v in phase.items()},
+        "multi_index": multi_index,
         "roofline": roofline, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
 
 

@@ -282,6 +282,34 @@ int qadc_ivf_encode(const float *coarse, int K, const float *codebooks, int d, i
                     uint8_t *codes, void *stream);
 
 /*
+ * Inverted multi-index as the coarse partition (Section 5, related work: Quick ADC needs no minimum
+ * list size and so combines with the finer partition of a multi-index).  The coarse quantizer is
+ * the product of two quantizers of K centroids over the two halves of the vector: cell (i, j) has
+ * id i*K + j and centroid (halves[0][i], halves[1][j]).  An index over those K*K cells is a
+ * qadc_ivf_index: build it with qadc_multi_index_assign -> qadc_ivf_group -> qadc_ivf_encode (coarse =
+ * the output of qadc_multi_index_cells) and search it with qadc_ivf_search, probes_in = the output of
+ * qadc_multi_index_probes.
+ *   halves [2][K][d/2] f32, K <= 4096, d even
+ *
+ * qadc_multi_index_cells:  coarse[i*K + j] = (halves[0][i], halves[1][j]);  coarse [K*K][d] f32 (output)
+ * qadc_multi_index_assign: cells[v] = K * (closest of halves[0] to the first half of x[v]) + (closest
+ *   of halves[1] to its second half), float64 distances, ties to the lowest;  x [n][d];  cells [n] i32
+ * qadc_multi_index_probes: probes[q] = the nprobe (<= 256) cells with the smallest d1[i] + d2[j],
+ *   smallest first, equal sums by cell id; d1, d2 = float32 squared distances of the query's halves to
+ *   the half-centroids (summed in increasing component).  Found from the min(nprobe, K) closest
+ *   half-centroids of each half, never from the K*K sums.  Slots beyond K*K cells are -1.
+ *   queries [nq][d] f32, nq <= 65535;  probes [nq][nprobe] i32 (output)
+ *   workspace >= qadc_multi_index_workspace_bytes(K, nq, nprobe) (0: unsupported arguments),
+ *   16-byte aligned; it need not be cleared.
+ */
+int qadc_multi_index_cells(const float *halves, int K, int d, float *coarse, void *stream);
+int qadc_multi_index_assign(const float *halves, int K, int d, const float *x, int64_t n, int32_t *cells,
+                            void *stream);
+size_t qadc_multi_index_workspace_bytes(int K, int nq, int nprobe);
+int qadc_multi_index_probes(const float *halves, int K, int d, const float *queries, int nq, int nprobe,
+                            int32_t *probes, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Rotation of an optimized product quantizer, Section 2.1: opq(x) = pq(R x), R^T R = I.
  *     y[i][r] = sum_t rot[r][t] * x[i][t]
  * with products and sums in float64 in increasing t and one rounding to float32.  At query time

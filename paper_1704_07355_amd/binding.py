@@ -32,6 +32,8 @@ EXPORTS = (
     "qadc_profile_enable", "qadc_profile_only", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version", "qadc_packed_bytes", "qadc_pack_codes", "qadc_unpack_codes",
     "qadc_ivf_assign", "qadc_ivf_group_workspace_bytes", "qadc_ivf_group", "qadc_ivf_encode",
+    "qadc_multi_index_cells", "qadc_multi_index_assign", "qadc_multi_index_workspace_bytes",
+    "qadc_multi_index_probes",
 )
 
 _lib = None
@@ -104,6 +106,14 @@ def lib() -> ctypes.CDLL:
         L.qadc_ivf_group.restype = i32
         L.qadc_ivf_encode.argtypes = [vp, i32, vp, i32, i32, vp, i64, vp, vp, i64, vp, vp]
         L.qadc_ivf_encode.restype = i32
+        L.qadc_multi_index_cells.argtypes = [vp, i32, i32, vp, vp]
+        L.qadc_multi_index_cells.restype = i32
+        L.qadc_multi_index_assign.argtypes = [vp, i32, i32, vp, i64, vp, vp]
+        L.qadc_multi_index_assign.restype = i32
+        L.qadc_multi_index_workspace_bytes.argtypes = [i32, i32, i32]
+        L.qadc_multi_index_workspace_bytes.restype = sz
+        L.qadc_multi_index_probes.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, sz, vp]
+        L.qadc_multi_index_probes.restype = i32
         L.qadc_last_error.restype = ctypes.c_char_p
         L.qadc_version.restype = ctypes.c_char_p
         _lib = L
@@ -273,6 +283,48 @@ def qadc_ivf_assign(coarse, x, out=None):
         out = torch.empty((n,), dtype=torch.int32, device=x.device)
     _check(lib().qadc_ivf_assign(_ptr(coarse, torch.float32), K, d, _ptr(x, torch.float32), n,
                                  _ptr(out, torch.int32), _stream()))
+    return out
+
+
+def qadc_multi_index_cells(halves, out=None):
+    """halves f32 [2][K][d/2] -> the K*K cell centroids f32 [K*K][d], cell id = i*K + j."""
+    _, K, dh = halves.shape
+    if out is None:
+        out = torch.empty((K * K, 2 * dh), dtype=torch.float32, device=halves.device)
+    _check(lib().qadc_multi_index_cells(_ptr(halves, torch.float32), K, 2 * dh, _ptr(out, torch.float32),
+                                        _stream()))
+    return out
+
+
+def qadc_multi_index_assign(halves, x, out=None):
+    """halves f32 [2][K][d/2], x f32 [n][d] -> cells i32 [n]."""
+    _, K, dh = halves.shape
+    n = x.shape[0]
+    assert x.shape[1] == 2 * dh
+    if out is None:
+        out = torch.empty((n,), dtype=torch.int32, device=x.device)
+    _check(lib().qadc_multi_index_assign(_ptr(halves, torch.float32), K, 2 * dh, _ptr(x, torch.float32), n,
+                                         _ptr(out, torch.int32), _stream()))
+    return out
+
+
+def qadc_multi_index_workspace_bytes(K: int, nq: int, nprobe: int) -> int:
+    return int(lib().qadc_multi_index_workspace_bytes(K, nq, nprobe))
+
+
+def qadc_multi_index_probes(halves, queries, nprobe, workspace=None, out=None):
+    """halves f32 [2][K][d/2], queries f32 [nq][d] -> probes i32 [nq][nprobe]."""
+    _, K, dh = halves.shape
+    nq = queries.shape[0]
+    assert queries.shape[1] == 2 * dh
+    if workspace is None:
+        workspace = torch.empty((max(16, qadc_multi_index_workspace_bytes(K, nq, nprobe)),), dtype=torch.uint8,
+                                device=queries.device)
+    if out is None:
+        out = torch.empty((nq, nprobe), dtype=torch.int32, device=queries.device)
+    _check(lib().qadc_multi_index_probes(_ptr(halves, torch.float32), K, 2 * dh, _ptr(queries, torch.float32), nq,
+                                         nprobe, _ptr(out, torch.int32), _ptr(workspace, torch.uint8),
+                                         workspace.numel(), _stream()))
     return out
 
 

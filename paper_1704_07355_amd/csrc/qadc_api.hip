@@ -42,6 +42,10 @@ size_t ivf_group_workspace(int64_t, int);
 int ivf_group(const int32_t *, int64_t, int, int64_t *, uint32_t *, void *, size_t, hipStream_t);
 int ivf_encode(const float *, int, const float *, int, int, const float *, int64_t, const int32_t *,
                const uint32_t *, int64_t, uint8_t *, hipStream_t);
+int multi_index_assign(const float *, int, int, const float *, int64_t, int32_t *, hipStream_t);
+int multi_index_cells(const float *, int, int, float *, hipStream_t);
+size_t multi_index_workspace(int, int, int);
+int multi_index_probes(const float *, int, int, const float *, int, int, int32_t *, void *, size_t, hipStream_t);
 int workspace_init(void *, size_t, hipStream_t);
 int pq_train(const float *, int64_t, int, int, int, const int64_t *, int, float *, void *, size_t,
              hipStream_t);
@@ -165,6 +169,29 @@ int qadc_ivf_encode(const float *coarse, int K, const float *codebooks, int d, i
 {
     return qadc::ivf_encode(coarse, K, codebooks, d, m, x, n, cells, ids, n_list, codes,
                             (hipStream_t)stream);
+}
+
+int qadc_multi_index_cells(const float *halves, int K, int d, float *coarse, void *stream)
+{
+    return qadc::multi_index_cells(halves, K, d, coarse, (hipStream_t)stream);
+}
+
+int qadc_multi_index_assign(const float *halves, int K, int d, const float *x, int64_t n, int32_t *cells,
+                            void *stream)
+{
+    return qadc::multi_index_assign(halves, K, d, x, n, cells, (hipStream_t)stream);
+}
+
+size_t qadc_multi_index_workspace_bytes(int K, int nq, int nprobe)
+{
+    return qadc::multi_index_workspace(K, nq, nprobe);
+}
+
+int qadc_multi_index_probes(const float *halves, int K, int d, const float *queries, int nq, int nprobe,
+                            int32_t *probes, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return qadc::multi_index_probes(halves, K, d, queries, nq, nprobe, probes, workspace, workspace_bytes,
+                                    (hipStream_t)stream);
 }
 
 int qadc_profile_enable(int on) { return qadc::profile_enable(on); }

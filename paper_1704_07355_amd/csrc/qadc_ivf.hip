@@ -238,6 +238,14 @@ __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
     }
 }
 
+// rows of `dist` [rows][K] -> out[rows][count]: the count smallest of each row, smallest first
+// (for the multi-index's half distances)
+void ivf_select_smallest(const float *dist, int rows, int K, int count, int32_t *out, hipStream_t st)
+{
+    launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3((unsigned)rows), dim3(IVF_SEL_NT), 0, st, dist, K,
+           count, out);
+}
+
 // ----------------------------------------------------------------- Tables
 
 // luts[q][p][j][i] = || (y_q - coarse[probes[q][p]])^j - C^j[i] ||^2, float64 inside, one

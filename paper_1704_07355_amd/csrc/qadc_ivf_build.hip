@@ -37,8 +37,8 @@ constexpr int ASG_LD = ASG_TM + 2;  // row stride in doubles: keeps 16-byte alig
 // the cells 32*k + 2*tx + e (k < 4, e < 2): a wavefront's 16-byte reads of the cells are
 // contiguous across its lanes, its reads of the vectors are the same for 16 lanes.
 __global__ __launch_bounds__(256) void ivf_assign_kernel(const float *__restrict__ coarse, int K, int d,
-                                                         const float *__restrict__ x, int64_t n,
-                                                         int32_t *__restrict__ cells)
+                                                         const float *__restrict__ x, int64_t ldx, int64_t n,
+                                                         int32_t *__restrict__ cells, int scale, int accumulate)
 {
     __shared__ __attribute__((aligned(16))) double xs[ASG_TK][ASG_LD];
     __shared__ __attribute__((aligned(16))) double cs[ASG_TK][ASG_LD];
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void ivf_assign_kernel(const float *__restrict
                 const int t = t0 + col;
                 const int64_t i = i0 + row;
                 const int c = c0 + row;
-                xs[col][row] = (i < n && t < d) ? (double)x[i * d + t] : 0.0;
+                xs[col][row] = (i < n && t < d) ? (double)x[i * ldx + t] : 0.0;
                 cs[col][row] = (c < K && t < d) ? (double)coarse[(size_t)c * d + t] : 0.0;
             }
             __syncthreads();
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void ivf_assign_kernel(const float *__restrict
                 const int cc = cand_c[tid][k];
                 if (dd < bd || (dd == bd && cc < bc)) { bd = dd; bc = cc; }
             }
-            cells[i] = bc;
+            cells[i] = (accumulate ? cells[i] : 0) + bc * scale;
         }
     }
 }
@@ -135,7 +135,30 @@ int ivf_assign(const float *coarse, int K, int d, const float *x, int64_t n, int
     if (!coarse || !x || !cells) return fail(QADC_EINVAL, "qadc_ivf_assign: null pointer");
     const int64_t grid = ceil_div(n, ASG_TM);
     if (grid > 0x7fffffffll) return fail(QADC_EINVAL, "qadc_ivf_assign: n too large for one call");
-    hipLaunchKernelGGL(ivf_assign_kernel, dim3((unsigned)grid), dim3(256), 0, st, coarse, K, d, x, n, cells);
+    hipLaunchKernelGGL(ivf_assign_kernel, dim3((unsigned)grid), dim3(256), 0, st, coarse, K, d, x, (int64_t)d, n,
+                       cells, 1, 0);
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+// Cells of an inverted multi-index: the coarse quantizer is the product of two quantizers of K
+// centroids over the two halves of the vector, cell = K * (closest of halves[0] to the first half)
+// + (closest of halves[1] to the second half).  Two passes of the assignment kernel over the
+// halves of the rows of x.
+int multi_index_assign(const float *halves, int K, int d, const float *x, int64_t n, int32_t *cells,
+                       hipStream_t st)
+{
+    if (K < 1 || K > 4096 || d < 2 || (d & 1) || n < 0)
+        return fail(QADC_EINVAL, "qadc_multi_index_assign: K=%d d=%d n=%lld", K, d, (long long)n);
+    if (n == 0) return QADC_OK;
+    if (!halves || !x || !cells) return fail(QADC_EINVAL, "qadc_multi_index_assign: null pointer");
+    const int64_t grid = ceil_div(n, ASG_TM);
+    if (grid > 0x7fffffffll) return fail(QADC_EINVAL, "qadc_multi_index_assign: n too large for one call");
+    const int dh = d / 2;
+    hipLaunchKernelGGL(ivf_assign_kernel, dim3((unsigned)grid), dim3(256), 0, st, halves, K, dh, x, (int64_t)d, n,
+                       cells, K, 0);
+    hipLaunchKernelGGL(ivf_assign_kernel, dim3((unsigned)grid), dim3(256), 0, st, halves + (size_t)K * dh, K, dh,
+                       x + dh, (int64_t)d, n, cells, 1, 1);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }
