@@ -48,3 +48,30 @@ def test_workspace_query_needs_no_gpu():
     assert Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, 1000, 7, 1, 100) == 0  # odd m: rejected
     assert Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, 1000, 16, 1, 5000) == 0  # R too large
     assert Q.qadc_version().startswith("qadc")
+
+
+def test_batch_plans_fit_one_launch(monkeypatch):
+    """Host-side planning of the batched scans: a batch's lists stay within the 256 MiB that one
+    launch may take (plus the per-query control blocks), small batches get more and shorter chunks
+    (a larger share per query), and the kernel choice changes the size, never the validity."""
+    import paper_1704_07355_amd as Q
+    n, m, R = 100_000_000, 32, 100
+    full = Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, n, m, 256, R)
+    small = Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, n, m, 32, R)
+    assert 0 < full <= (256 << 20) + (1 << 20)
+    assert 0 < small < full and small / 32 > full / 256
+    monkeypatch.setenv("QADC_TILED_MFMA", "0")
+    other = Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, n, m, 32, R)
+    assert 0 < other < small
+    monkeypatch.delenv("QADC_TILED_MFMA")
+    # ten thousand queries in one call are cut into launches: the workspace does not grow with them
+    assert Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_TOPK, n, m, 10_000, R) <= (256 << 20) + (4 << 20)
+
+
+def test_multi_index_workspace_query():
+    import paper_1704_07355_amd as Q
+    a = Q.qadc_multi_index_workspace_bytes(256, 256, 64)
+    assert a >= 256 * 2 * 256 * 4 + 256 * 2 * 64 * 4
+    assert Q.qadc_multi_index_workspace_bytes(256, 512, 64) > a
+    for bad in ((0, 1, 1), (4097, 1, 1), (16, 0, 1), (16, 1, 0), (16, 1, 257), (16, 70000, 4)):
+        assert Q.qadc_multi_index_workspace_bytes(*bad) == 0
