@@ -84,22 +84,23 @@ __global__ __launch_bounds__(256) void mi_combine_kernel(const float *__restrict
         d1[r] = hd[((size_t)q * 2) * K + a];
         d2[r] = hd[((size_t)q * 2 + 1) * K + b];
     }
+    for (int a = tid; a < T; a += 256) row_off[a + 1] = min(T, nprobe / (a + 1));  // sizes first
+    __syncthreads();
     if (tid == 0) {
-        int off = 0;
-        for (int a = 0; a < T; ++a) {
-            row_off[a] = off;
-            off += min(T, nprobe / (a + 1));
-        }
-        row_off[T] = off;
+        row_off[0] = 0;
+        for (int a = 0; a < T; ++a) row_off[a + 1] += row_off[a];
     }
     __syncthreads();
     const int P = row_off[T];  // <= MI_MAX_PAIRS (checked on the host)
-    for (int a = 0; a < T; ++a) {
-        const int nb = row_off[a + 1] - row_off[a];
-        for (int b = tid; b < nb; b += 256) {
-            const float sum = d1[a] + d2[b];
-            keys[row_off[a] + b] = ((uint64_t)f2ord(sum) << 32) | (uint64_t)(unsigned)(c1[a] * K + c2[b]);
+    for (int p = tid; p < P; p += 256) {
+        int lo = 0, hi = T - 1;  // the row a with row_off[a] <= p < row_off[a + 1]
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (row_off[mid] <= p) lo = mid; else hi = mid - 1;
         }
+        const int a = lo, b = p - row_off[lo];
+        const float sum = d1[a] + d2[b];
+        keys[p] = ((uint64_t)f2ord(sum) << 32) | (uint64_t)(unsigned)(c1[a] * K + c2[b]);
     }
     __syncthreads();
     const int need = min(nprobe, P);
