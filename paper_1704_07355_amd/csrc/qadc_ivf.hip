@@ -1010,7 +1010,8 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         dim3 grid((unsigned)p.W * (unsigned)nb);
         const int upw = nb >= 64 ? max(1, env_int("QADC_IVF_UNITS", 16)) : 1;
         // a few queries: their lists are sampled by several workgroups each
-        const int seed_parts = nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
+        const int seed_parts_env = env_int("QADC_IVF_SEED_PARTS", 0);
+        const int seed_parts = seed_parts_env > 0 ? min(seed_parts_env, nprobe) : nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
         launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
