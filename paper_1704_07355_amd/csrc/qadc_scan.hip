@@ -757,6 +757,9 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
         p->stride = p->listsA_off + align_up((size_t)p->t.GC * TILED_LCAP * sizeof(uint64_t), 256);
     }
     p->qbatch = scan_query_batch(p->stride, nq);
+    // a call cut into several launches: whole sets of queries per launch (the batched kernels take
+    // 16 to 128 queries per workgroup; a launch that ends in a nearly empty set wastes its share)
+    if (p->tiled && p->qbatch < nq && p->qbatch >= 128) p->qbatch = p->qbatch / 128 * 128;
     p->ws_bytes = p->stride * (size_t)p->qbatch;
     if (p->tiled) {
         p->taus_off = p->ws_bytes;

@@ -391,7 +391,11 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
         // beyond that the batch would be split into two launches
         max_chunks = std::min<int64_t>(TILED_MFMA_MAX_CHUNKS,
                                        std::max<int64_t>(TILED_MAX_CHUNKS, (128ll << 20) / (516ll * nq)));
-        want = std::max<int64_t>(1, std::min<int64_t>(max_chunks, ceil_div(std::max(64, env_int("QADC_MFMA_WAVES", 4096)), ceil_div(nq, qw))));
+        // never fewer than 512 chunks, however many sets of queries there are: a query's few
+        // thousand candidates must stay well below the 64 (or 32) keys a wavefront can report per
+        // query and chunk, or queries overflow and are redone one by one
+        want = std::max<int64_t>(512, ceil_div(std::max(64, env_int("QADC_MFMA_WAVES", 4096)), ceil_div(nq, qw)));
+        want = std::min<int64_t>(max_chunks, want);
         lo = 2;
         hi = 1ll << 40;
     }
