@@ -75,3 +75,17 @@ def test_multi_index_workspace_query():
     assert Q.qadc_multi_index_workspace_bytes(256, 512, 64) > a
     for bad in ((0, 1, 1), (4097, 1, 1), (16, 0, 1), (16, 1, 0), (16, 1, 257), (16, 70000, 4)):
         assert Q.qadc_multi_index_workspace_bytes(*bad) == 0
+
+
+def test_multi_index_argument_checks_need_no_gpu():
+    """Arguments are checked on the host before anything is launched."""
+    import paper_1704_07355_amd as Q
+    L = Q.lib()
+    assert L.qadc_multi_index_cells(None, 4, 8, None, None) == Q.QADC_EINVAL          # null pointers
+    assert L.qadc_multi_index_cells(None, 0, 8, None, None) == Q.QADC_EINVAL          # K < 1
+    assert L.qadc_multi_index_cells(None, 4, 7, None, None) == Q.QADC_EINVAL          # odd d
+    assert L.qadc_multi_index_assign(None, 4, 8, None, 10, None, None) == Q.QADC_EINVAL
+    assert L.qadc_multi_index_assign(None, 4, 8, None, 0, None, None) == Q.QADC_OK    # nothing to do
+    assert L.qadc_multi_index_probes(None, 4, 8, None, 0, 4, None, None, 0, None) == Q.QADC_OK
+    assert L.qadc_multi_index_probes(None, 4, 8, None, 3, 4, None, None, 0, None) == Q.QADC_EINVAL
+    assert b"qadc_multi_index_probes" in L.qadc_last_error()
