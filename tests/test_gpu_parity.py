@@ -610,6 +610,27 @@ def test_scan_topk_random_large_batches_against_c_twin(Q, O):
         assert np.array_equal(dist.cpu().numpy(), wd), (it, n, m, nq, R, nbins, hi)
 
 
+@pytest.mark.parametrize("knobs", [{"QADC_TILED_MFMA": "0"}, {"QADC_MFMA_MIN_Q2": "100000", "QADC_MFMA_MIN_Q4": "100000"},
+                                   {"QADC_MFMA_MIN_Q": "8", "QADC_MFMA_MIN_Q2": "8", "QADC_MFMA_MIN_Q4": "8"},
+                                   {"QADC_MFMA_WAVES": "300"}, {"QADC_TILED_SEED": "0"}, {"QADC_TILED": "0"}])
+def test_kernel_choice_knobs_never_change_results(Q, O, monkeypatch, knobs):
+    """The tuning variables pick among equivalent kernels and launch shapes: the vector-ALU kernels
+    instead of the matrix-core one, each of its forms (32, 64, 128 queries per wavefront) forced on
+    batches that would not take it, few long chunks, the per-query sample, no query tiling at all."""
+    from oracle import cref
+    for k, v in knobs.items():
+        monkeypatch.setenv(k, v)
+    rng = np.random.default_rng(99)
+    for m, nq in ((16, 130), (8, 300), (64, 40)):
+        n, R = 560_003, 100
+        codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+        qluts = rng.integers(0, 1 + 255 // m, size=(nq, m, 16)).astype(np.uint8)
+        qluts[1] = 0
+        wi, wd = cref.scan_topk_u8(codes, qluts, R, 255)
+        idx, dist = Q.qadc_scan_topk(Q.QADC_U8_4BIT, to_gpu(codes), to_gpu(qluts), R)
+        assert np.array_equal(idx_np(idx), wi) and np.array_equal(dist.cpu().numpy(), wd), (knobs, m, nq)
+
+
 def test_scan_topk_a_thousand_queries_in_one_call(Q, O):
     """A call with far more queries than one launch takes (the workspace bounds the queries per
     launch): full sub-batches and a last short one."""
