@@ -49,7 +49,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--n", type=int, default=None, help="codes per query scan")
-    ap.add_argument("--batch", type=int, default=256, help="queries per step of the batched workload")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="queries per step of the batched (default 256) and ivf (default 4096) workloads")
     ap.add_argument("--buffers", type=int, default=8, help="distinct code buffers rotated over")
     ap.add_argument("--m", type=int, default=None)
     ap.add_argument("--d", type=int, default=128, help="dimensions of the vectors (scan and ivf workloads)")
@@ -73,11 +74,11 @@ def parse():
     ap.add_argument("--separate-calls", action="store_true",
                     help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
     args = ap.parse_args()
-    dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200),
-            "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000),
-            "ivf": dict(steps=4, warmup=1, n=1_000_000_000, m=32, init=1000),
-            "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200),
-            "build": dict(steps=3, warmup=1, n=4_000_000, m=16, init=200)}[args.workload]
+    dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200, batch=256),
+            "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000, batch=256),
+            "ivf": dict(steps=4, warmup=1, n=1_000_000_000, m=32, init=1000, batch=4096),
+            "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200, batch=256),
+            "build": dict(steps=3, warmup=1, n=4_000_000, m=16, init=200, batch=256)}[args.workload]
     for k, v in dflt.items():
         if getattr(args, k) is None:
             setattr(args, k, v)
