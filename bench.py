@@ -243,11 +243,15 @@ def run_batched(args):
         ach = n * nb * m / (ms_scan * 1e-3) / 1e12
         on_matrix_cores = nb >= (32 if m >= 32 else 64) and os.environ.get("QADC_TILED_MFMA", "1") != "0"
         if on_matrix_cores:
-            # one-hot products: every (code, query, table) lookup is a 16-term int8 dot product
-            ops = n * nb * m * 16 * 2 / (ms_scan * 1e-3) / 1e12
+            # one-hot products on the sparse matrix instruction: every (code, query, table) lookup is a
+            # 16-term int8 dot product of which the hardware executes 8 terms (two of every four)
+            ops = n * nb * m * 8 * 2 / (ms_scan * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": "scan_u8_mfma_kernel (+ the redo launch)", "achieved": round(ops, 1),
                         "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s", "frac": round(ops / MFMA_I8_PEAK_TOPS, 4),
-                        "note": "int8 operations issued; 15 of 16 multiply by a zero of the one-hot operand",
+                        "note": "int8 operations executed by v_smfmac_i32_32x32x64_i8 against the dense int8 peak "
+                                "(the instruction issues at the dense rate and covers twice the k range); "
+                                "all but one of 16 products of a lookup are by a zero of the one-hot operand",
+                        "dense_equivalent_tops": round(2 * ops, 1),
                         "useful_T_lookup_adds_per_s": round(ach, 2),
                         "frac_of_vector_alu_byte_lane_ceiling": round(ach / ALU_PEAK_TLOOKUPS, 4),
                         "traffic": MFMA_TRAFFIC if (n, m, nb) == (100_000_000, 32, 256) else None,

@@ -416,20 +416,29 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 //
 // The lookups of a batch as a matrix product on the MFMA units: with onehot(c) the 16-vector that
 // is 1 at position c, the sum of a code for a query is  sum_j onehot(c_j) . q^j  -- a row of 0/1
-// bytes times a column of table entries, exact in int32.  One v_mfma_i32_32x32x32_i8 multiplies
-// 32 codes by 32 queries over 32 values of k = two tables: lanes 0..31 hold the low nibble of a
-// code byte as a one-hot 16-byte operand (table 2jb), lanes 32..63 the high nibble (table
-// 2jb+1); the other operand is simply the 16 entries of that table of query (lane mod 32), as
-// they lie in memory.  So a code byte costs one MFMA for 32 codes x 32 queries, the tables stay in
-// registers for the whole scan (the one-hot operand is read from a 16-entry table in LDS:
-// composing it with compares and selects made the vector ALU the limit), and 15 of 16 multiplications
-// are by zero -- which the matrix units can afford: measured here they run 4.0 Pop/s of int8.
-// A workgroup is ONE wavefront: it scans a chunk for 32 G queries (G groups of 32, G independent
-// accumulator chains).  Lane l of the 32 x 32 result holds 16 sums of query
-// (l mod 32): each is compared with that query's bound, and the rare pass is appended to the
-// query's list in LDS.  Outputs as the other query-tiled kernels: lists per (query, chunk), a
+// bytes times a column of table entries, exact in int32.  A one-hot row is a structured-sparse row
+// (one non-zero in 16, so at most two in every four), which is what the sparse matrix instruction
+// takes: one v_smfmac_i32_32x32x64_i8 multiplies 32 codes by 32 queries over 64 values of k = four
+// tables = two code bytes, at the issue rate of the dense 32x32x32 instruction (measured here:
+// 8.0 Pop/s counted densely).  Operands, as found by probing the instruction:
+//   B (dense, 32 bytes per lane): lane (query = lane mod 32, half = lane / 32) holds k = 32 half ..
+//     32 half + 31, i.e. the 16 entries of tables 4jp + 2 half and 4jp + 2 half + 1 of its query as
+//     they lie in memory;
+//   A (compressed, 16 bytes per lane + a register of 2-bit positions): lane (code = lane mod 32,
+//     half) holds 16 stored values in pairs, pair g of the first eight for k = 16 half + 4g .. + 3,
+//     pair g of the last eight for k = 32 + 16 half + 4g .. + 3; each stored value carries the
+//     position (0..3) of its k inside the four.  So lanes 0..31 take the LOW nibbles of code bytes
+//     2jp and 2jp + 1 (tables 4jp and 4jp + 2), lanes 32..63 the HIGH nibbles (tables 4jp + 1 and
+//     4jp + 3): a nibble c puts a 1 into the first value of pair c / 4 with position c mod 4.
+//   The 8 value bytes and the 16 position bits of a nibble come from a 16-entry table in LDS.
+// So two code bytes cost one instruction for 32 codes x 32 queries, and the tables stay in
+// registers for the whole scan.  A workgroup is ONE wavefront: it scans a chunk for 32 G queries
+// (G groups of 32, G independent accumulator chains).  Lane l of the 32 x 32 result holds 16 sums
+// of query (l mod 32): each is compared with that query's bound, and the rare pass is appended to
+// the query's list in LDS.  Outputs as the other query-tiled kernels: lists per (query, chunk), a
 // flag on overflow.  (The matrix units multiply signed bytes; the entries go in shifted by 128.)
 typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
 constexpr int MFMA_SUB = 2;    // 32-code steps per load
 
@@ -447,7 +456,11 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     constexpr int LC = (G > 2) ? TILED_LCAP / 2 : TILED_LCAP;  // keys kept per query (LDS: 16 KiB of lists)
     __shared__ unsigned keys[QW][LC];
     __shared__ unsigned cnt[QW];
-    __shared__ v4i_t onehot[16];  // onehot[c]: 16 bytes, byte c is 1
+    // of nibble c, at offset 16 c of either table: the 8 value bytes (byte 2 (c / 4) is 1) and the
+    // position bits.  (Two tables, so that the two reads of a nibble stay an 8-byte and a 4-byte read
+    // that land in the operand's registers, instead of one 12-byte read that has to be moved there.)
+    __shared__ v4i_t nibval[16];
+    __shared__ v4i_t nibpos[16];
 
     const int l = threadIdx.x;
     const int row = l & 31, half = l >> 5;
@@ -464,7 +477,8 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     // The matrix unit multiplies SIGNED bytes: an entry e goes in as e - 128 (= e xor 0x80), every
     // sum then comes out as sum - 128 * (2B tables) and the bounds are shifted by the same amount.
     constexpr int SHIFT = 128 * 2 * B;
-    v4i_t tb[G][B];
+    constexpr int NP = B / 2;  // pairs of code bytes = instructions per 32-code step and group
+    v8i_t tb[G][NP];
     int thr[G];  // a shifted sum passes when it is <= thr
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -475,16 +489,22 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
             thr[g] = ((t >= cap) ? 0x7fffffff : (int)t) - SHIFT;
         }
 #pragma unroll
-        for (int jb = 0; jb < B; ++jb) {  // (loads without a branch around them: all in flight at once)
-            const v4i_t e = *reinterpret_cast<const v4i_t *>(qluts + ((size_t)min(q, nq - 1) * (2 * B) + 2 * jb + half) * 16);
+        for (int jp = 0; jp < NP; ++jp) {  // (loads without a branch around them: all in flight at once)
+            const v4i_t *src = reinterpret_cast<const v4i_t *>(qluts + ((size_t)min(q, nq - 1) * (2 * B) + 4 * jp + 2 * half) * 16);
+            const v4i_t e0 = src[0], e1 = src[1];
             const int flip = (q < nq) ? (int)0x80808080u : 0, keep = (q < nq) ? -1 : 0;
-            tb[g][jb] = v4i_t{(e[0] ^ flip) & keep, (e[1] ^ flip) & keep, (e[2] ^ flip) & keep, (e[3] ^ flip) & keep};
+            tb[g][jp] = v8i_t{(e0[0] ^ flip) & keep, (e0[1] ^ flip) & keep, (e0[2] ^ flip) & keep, (e0[3] ^ flip) & keep,
+                              (e1[0] ^ flip) & keep, (e1[1] ^ flip) & keep, (e1[2] ^ flip) & keep, (e1[3] ^ flip) & keep};
         }
     }
     for (int i = l; i < QW; i += 64) cnt[i] = 0;
     if (l < 16) {
-        const int bit = 1 << (8 * (l & 3));
-        onehot[l] = v4i_t{(l >> 2) == 0 ? bit : 0, (l >> 2) == 1 ? bit : 0, (l >> 2) == 2 ? bit : 0, (l >> 2) == 3 ? bit : 0};
+        // pair l / 4 holds the 1 in its first value, at position l mod 4; every other stored value is 0
+        // (the two positions of a pair are kept different: (0, 3) for the empty pairs)
+        const int pr = l >> 2, pos = l & 3;
+        const int bits = (0xcccc & ~(15 << (4 * pr))) | ((pos | ((pos == 3 ? 2 : 3) << 2)) << (4 * pr));
+        nibval[l] = v4i_t{pr < 2 ? 1 << (16 * pr) : 0, pr >= 2 ? 1 << (16 * (pr - 2)) : 0, 0, 0};
+        nibpos[l] = v4i_t{bits, 0, 0, 0};
     }
     __syncthreads();
 
@@ -501,15 +521,66 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
         }
     };
     fetch(c0, cn);
-    // the one-hot operand of code byte jb of a code whose words are w[]: read from LDS at offset
-    // 16 * (this lane's nibble of the byte)
-    auto operand = [&](const unsigned (&w)[WPC], int jb) {
-        const unsigned nib16 = ((half ? (w[jb >> 2] >> 4) : w[jb >> 2]) & 0x0f0f0f0fu) << 4;
-        const unsigned off = (nib16 >> (8 * (jb & 3))) & 0xffu;
-        return *reinterpret_cast<const v4i_t *>(reinterpret_cast<const char *>(onehot) + off);
+    // the sparse operand of code bytes 2jp and 2jp + 1 of a code whose words are w[]: this lane's
+    // nibble of either byte; its value bytes (8) and position bits come from the nibble table in LDS
+    // at offset 16 * nibble (an 8-byte and a 4-byte read each, straight into their registers)
+    typedef int v2i_t __attribute__((ext_vector_type(2)));
+    struct Operand {  // as read; put together only where it is used, so that nothing waits for the reads early
+        v2i_t v0, v1;
+        int p0, p1;
+    };
+    auto operand = [&](const unsigned (&w)[WPC], int jp) {
+        // every byte of x: 16 * (this lane's nibble of the code byte), the offset of the nibble's entries
+        const unsigned x = (half ? w[jp >> 1] : (w[jp >> 1] << 4)) & 0xf0f0f0f0u;
+        const unsigned o0 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1), 8), o1 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1) + 8, 8);
+        const char *tv = reinterpret_cast<const char *>(nibval), *tp = reinterpret_cast<const char *>(nibpos);
+        return Operand{*reinterpret_cast<const v2i_t *>(tv + o0), *reinterpret_cast<const v2i_t *>(tv + o1),
+                       *reinterpret_cast<const int *>(tp + o0), *reinterpret_cast<const int *>(tp + o1)};
+    };
+    // Tests the G x 16 sums a lane holds after a step whose first code is `rel` (relative to c0).
+    // Result v of a lane: code (v / 4) * 8 + half * 4 + v % 4 of the step, query row (+32g).
+    auto test = [&](const v16i_t (&sum)[G], unsigned rel) {
+        // the smallest of a group's 16 sums against its bound (three-input minima: 8 operations)
+        bool any = false;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            int lo = sum[g][0];
+#pragma unroll
+            for (int v = 1; v < 15; v += 2) lo = min(min(lo, sum[g][v]), sum[g][v + 1]);
+            lo = min(lo, sum[g][15]);
+            any = any | (lo <= thr[g]);
+        }
+        if (__ballot(any) != 0ull) {  // some sum of the step passes: find it by groups of four results
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int qm = min(min(sum[g][4 * u], sum[g][4 * u + 1]), min(sum[g][4 * u + 2], sum[g][4 * u + 3]));
+                    if (__ballot(qm <= thr[g]) == 0ull) continue;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
+                        if (c0 + (int64_t)li < c1 && sum[g][4 * u + w] <= thr[g]) {
+                            const unsigned slot = atomicAdd(&cnt[32 * g + row], 1u);
+                            if (slot < (unsigned)LC)
+                                keys[32 * g + row][slot] = (min((unsigned)(sum[g][4 * u + w] + SHIFT), cap) << 24) | li;
+                        }
+                    }
+                }
+            }
+        }
     };
     // the operands are read two products ahead, across the steps as well
-    v4i_t a0 = operand(cn[0], 0), a1 = operand(cn[0], 1);
+    Operand a0 = operand(cn[0], 0), a1 = operand(cn[0], NP > 1 ? 1 : 0);
+    // With room in the registers (G <= 2) there are two sets of accumulators, alternating by step:
+    // the sums of a step are tested in the middle of the next step's products, so that the matrix
+    // pipe does not drain while they are looked at.
+    constexpr bool PIPE = false;  // (measured: no room for it in the registers where it would matter)
+    static_assert(MFMA_SUB % 2 == 0, "accumulator sets alternate by the step's parity");
+    v16i_t acc[PIPE ? 2 : 1][G];
+    unsigned prel = 0;
+    bool pending = false;
+    int last = 0;
     for (int64_t t0 = c0; t0 < c1; t0 += 32 * MFMA_SUB) {  // uniform
 #pragma unroll
         for (int s = 0; s < MFMA_SUB; ++s)
@@ -519,54 +590,40 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
 #pragma unroll
         for (int s = 0; s < MFMA_SUB; ++s) {
             if (t0 + 32 * s >= c1) break;  // uniform
-            v16i_t acc[G];
+            const int par = PIPE ? (s & 1) : 0;  // static: the loop is unrolled
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[g][v] = 0;
+                for (int v = 0; v < 16; ++v) acc[par][g][v] = 0;
 #pragma unroll
-            for (int jb = 0; jb < B; ++jb) {
-                const v4i_t a = a0;
+            for (int jp = 0; jp < NP; ++jp) {
+                const Operand a = a0;
                 a0 = a1;
                 // (past the last step of the last load these are operands nobody uses)
-                if (jb + 2 < B) a1 = operand(cw[s], jb + 2);
-                else if (s + 1 < MFMA_SUB) a1 = operand(cw[s + 1], jb + 2 - B);
-                else a1 = operand(cn[0], jb + 2 - B);
+                if (jp + 2 < NP) a1 = operand(cw[s], jp + 2);
+                else if (s + 1 < MFMA_SUB) a1 = operand(cw[s + 1], (jp + 2 - NP) % NP);
+                else a1 = operand(cn[0], (jp + 2 - NP) % NP);
+                asm volatile("" ::: "memory");  // the reads above are issued before the products below, not sunk to their use
+                const v4i_t av = v4i_t{a.v0[0], a.v0[1], a.v1[0], a.v1[1]};
+                const int ap = a.p0 | (a.p1 << 16);
 #pragma unroll
                 for (int g = 0; g < G; ++g)
-                    acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, tb[g][jb], acc[g], 0, 0, 0);
+                    acc[par][g] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, tb[g][jp], acc[par][g], ap, 0, 0);
+                if (PIPE && jp == NP / 2 - 1 && pending) test(acc[PIPE ? (par ^ 1) : 0], prel);
             }
-            // result v of this lane: code (v / 4) * 8 + half * 4 + v % 4 of the step, query row (+32g)
             const unsigned rel = (unsigned)(t0 - c0) + 32u * s;
-            // smallest sum of each group of four results, then of all: one compare per query group
-            int qm[G][4];
-            bool any = false;
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    qm[g][u] = min(min(acc[g][4 * u], acc[g][4 * u + 1]), min(acc[g][4 * u + 2], acc[g][4 * u + 3]));
-                any = any || min(min(qm[g][0], qm[g][1]), min(qm[g][2], qm[g][3])) <= thr[g];
-            }
-            if (__ballot(any) != 0ull) {  // some sum of the step passes: find it group by group
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        if (__ballot(qm[g][u] <= thr[g]) == 0ull) continue;
-#pragma unroll
-                        for (int w = 0; w < 4; ++w) {
-                            const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
-                            if (c0 + (int64_t)li < c1 && acc[g][4 * u + w] <= thr[g]) {
-                                const unsigned slot = atomicAdd(&cnt[32 * g + row], 1u);
-                                if (slot < (unsigned)LC)
-                                    keys[32 * g + row][slot] = (min((unsigned)(acc[g][4 * u + w] + SHIFT), cap) << 24) | li;
-                            }
-                        }
-                    }
-                }
+            if (PIPE) {
+                prel = rel;
+                pending = true;
+                last = par;
+            } else {
+                test(acc[0], rel);
             }
         }
+    }
+    if (PIPE && pending) {  // uniform
+        if (last == 0) test(acc[0], prel);
+        else test(acc[PIPE ? 1 : 0], prel);
     }
     __syncthreads();
 
