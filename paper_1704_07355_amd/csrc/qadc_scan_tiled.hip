@@ -508,18 +508,20 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     }
     __syncthreads();
 
-    // codes: lane (row, half) reads code `row` of each 32-code step (both halves read the same code)
+    // codes: lane (row, half) reads code `row` of each 32-code step (both halves read the same code).
+    // Past the end of the chunk the last code is read again: loads without a branch around them, and
+    // sums of positions beyond the chunk are never kept.
     unsigned cw[MFMA_SUB][WPC], cn[MFMA_SUB][WPC];
     auto fetch = [&](int64_t t0, unsigned (&dst)[MFMA_SUB][WPC]) {
 #pragma unroll
         for (int s = 0; s < MFMA_SUB; ++s) {
-            const int64_t i = t0 + 32 * s + row;
-            const bool in = i < c1;
-            const unsigned *src = reinterpret_cast<const unsigned *>(codes + (in ? i : c0) * B);
+            const int64_t i = min(t0 + 32 * s + row, c1 - 1);
+            const unsigned *src = reinterpret_cast<const unsigned *>(codes + i * B);
 #pragma unroll
-            for (int k = 0; k < WPC; ++k) dst[s][k] = in ? src[k] : 0u;
+            for (int k = 0; k < WPC; ++k) dst[s][k] = src[k];
         }
     };
+    const unsigned nibsh = half ? 0u : 4u;  // low nibbles (lanes 0..31) are moved up to the high ones' place
     fetch(c0, cn);
     // the sparse operand of code bytes 2jp and 2jp + 1 of a code whose words are w[]: this lane's
     // nibble of either byte; its value bytes (8) and position bits come from the nibble table in LDS
@@ -531,7 +533,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     };
     auto operand = [&](const unsigned (&w)[WPC], int jp) {
         // every byte of x: 16 * (this lane's nibble of the code byte), the offset of the nibble's entries
-        const unsigned x = (half ? w[jp >> 1] : (w[jp >> 1] << 4)) & 0xf0f0f0f0u;
+        const unsigned x = (w[jp >> 1] << nibsh) & 0xf0f0f0f0u;
         const unsigned o0 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1), 8), o1 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1) + 8, 8);
         const char *tv = reinterpret_cast<const char *>(nibval), *tp = reinterpret_cast<const char *>(nibpos);
         return Operand{*reinterpret_cast<const v2i_t *>(tv + o0), *reinterpret_cast<const v2i_t *>(tv + o1),
@@ -541,18 +543,20 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     // Result v of a lane: code (v / 4) * 8 + half * 4 + v % 4 of the step, query row (+32g).
     auto test = [&](const v16i_t (&sum)[G], unsigned rel) {
         // the smallest of a group's 16 sums against its bound (three-input minima: 8 operations)
+        int lo[G];
         bool any = false;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            int lo = sum[g][0];
+            lo[g] = sum[g][0];
 #pragma unroll
-            for (int v = 1; v < 15; v += 2) lo = min(min(lo, sum[g][v]), sum[g][v + 1]);
-            lo = min(lo, sum[g][15]);
-            any = any | (lo <= thr[g]);
+            for (int v = 1; v < 15; v += 2) lo[g] = min(min(lo[g], sum[g][v]), sum[g][v + 1]);
+            lo[g] = min(lo[g], sum[g][15]);
+            any = any | (lo[g] <= thr[g]);
         }
-        if (__ballot(any) != 0ull) {  // some sum of the step passes: find it by groups of four results
+        if (__ballot(any) != 0ull) {  // some sum of the step passes: which group, which four results, which one
 #pragma unroll
             for (int g = 0; g < G; ++g) {
+                if (__ballot(lo[g] <= thr[g]) == 0ull) continue;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int qm = min(min(sum[g][4 * u], sum[g][4 * u + 1]), min(sum[g][4 * u + 2], sum[g][4 * u + 3]));
@@ -605,7 +609,9 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
                 else a1 = operand(cn[0], (jp + 2 - NP) % NP);
                 asm volatile("" ::: "memory");  // the reads above are issued before the products below, not sunk to their use
                 const v4i_t av = v4i_t{a.v0[0], a.v0[1], a.v1[0], a.v1[1]};
-                const int ap = a.p0 | (a.p1 << 16);
+                int p0 = a.p0, p1 = a.p1;
+                asm volatile("" : "+v"(p0), "+v"(p1));  // the position halves are joined here, not right behind their reads
+                const int ap = p0 | (p1 << 16);
 #pragma unroll
                 for (int g = 0; g < G; ++g)
                     acc[par][g] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, tb[g][jp], acc[par][g], ap, 0, 0);
