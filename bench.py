@@ -241,7 +241,7 @@ def run_batched(args):
         ms_merge, _ = Q.qadc_profile_read(Q.QADC_PROF_MERGE)
         Q.qadc_profile_enable(False)
         ach = n * nb * m / (ms_scan * 1e-3) / 1e12
-        on_matrix_cores = nb >= (32 if m >= 32 else 64) and os.environ.get("QADC_TILED_MFMA", "1") != "0"
+        on_matrix_cores = nb >= (16 if m >= 16 else 32) and os.environ.get("QADC_TILED_MFMA", "1") != "0"
         if on_matrix_cores:
             # one-hot products on the sparse matrix instruction: every (code, query, table) lookup is a
             # 16-term int8 dot product of which the hardware executes 8 terms (two of every four)

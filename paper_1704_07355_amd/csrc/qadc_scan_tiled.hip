@@ -356,12 +356,12 @@ __global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled16_kernel(
     }
 }
 
-// smallest batches for the matrix-core kernel (from 32 queries with 16 code bytes or more, from 64
-// with fewer: measured against the vector-ALU kernels over 10 M codes) and for its
-// 64-queries-per-wavefront form
+// smallest batches for the matrix-core kernel (from 16 queries with 8 code bytes or more, from 32
+// with 4: measured against the vector-ALU kernels over 10 M codes) and for its forms with 64 and 128
+// queries per wavefront
 static int mfma_min_q(int B)
 {
-    return std::max(1, env_int("QADC_MFMA_MIN_Q", B >= 16 ? TILED_MFMA_MIN_Q : 2 * TILED_MFMA_MIN_Q));
+    return std::max(1, env_int("QADC_MFMA_MIN_Q", B >= 8 ? TILED_MFMA_MIN_Q : 2 * TILED_MFMA_MIN_Q));
 }
 static int mfma_min_q2() { return std::max(1, env_int("QADC_MFMA_MIN_Q2", TILED_MFMA_MIN_Q2)); }
 static int mfma_min_q4() { return std::max(1, env_int("QADC_MFMA_MIN_Q4", TILED_MFMA_MIN_Q4)); }

@@ -566,7 +566,7 @@ def test_scan_topk_query_groups_by_bound(Q, O, m):
 @pytest.mark.parametrize("m", [8, 16, 32, 64])
 @pytest.mark.parametrize("nq,R,nbins", [(130, 100, 255), (97, 1000, 127), (256, 10, 255), (40, 100, 255)])
 def test_scan_topk_large_batches_on_the_matrix_cores(Q, O, m, nq, R, nbins):
-    """Batches of 4-bit codes from 32 queries up (64 for short codes) are scanned as one-hot matrix
+    """Batches of 4-bit codes from 16 queries up (32 for the shortest codes) are scanned as one-hot matrix
     products, 32 or 64 queries per wavefront: full and partial sets of queries, a ragged database
     tail, tables that tie heavily, saturate, exceed nbins or are all zero (those queries overflow
     their lists and are redone one by one).  Indices and sums equal the plain-C scan bit for bit."""
