@@ -576,15 +576,6 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     };
     // the operands are read two products ahead, across the steps as well
     Operand a0 = operand(cn[0], 0), a1 = operand(cn[0], NP > 1 ? 1 : 0);
-    // With room in the registers (G <= 2) there are two sets of accumulators, alternating by step:
-    // the sums of a step are tested in the middle of the next step's products, so that the matrix
-    // pipe does not drain while they are looked at.
-    constexpr bool PIPE = false;  // (measured: no room for it in the registers where it would matter)
-    static_assert(MFMA_SUB % 2 == 0, "accumulator sets alternate by the step's parity");
-    v16i_t acc[PIPE ? 2 : 1][G];
-    unsigned prel = 0;
-    bool pending = false;
-    int last = 0;
     for (int64_t t0 = c0; t0 < c1; t0 += 32 * MFMA_SUB) {  // uniform
 #pragma unroll
         for (int s = 0; s < MFMA_SUB; ++s)
@@ -594,11 +585,11 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
 #pragma unroll
         for (int s = 0; s < MFMA_SUB; ++s) {
             if (t0 + 32 * s >= c1) break;  // uniform
-            const int par = PIPE ? (s & 1) : 0;  // static: the loop is unrolled
+            v16i_t acc[G];  // (the sparse instruction has no zero addend: cleared by hand)
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[par][g][v] = 0;
+                for (int v = 0; v < 16; ++v) acc[g][v] = 0;
 #pragma unroll
             for (int jp = 0; jp < NP; ++jp) {
                 const Operand a = a0;
@@ -614,22 +605,10 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
                 const int ap = p0 | (p1 << 16);
 #pragma unroll
                 for (int g = 0; g < G; ++g)
-                    acc[par][g] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, tb[g][jp], acc[par][g], ap, 0, 0);
-                if (PIPE && jp == NP / 2 - 1 && pending) test(acc[PIPE ? (par ^ 1) : 0], prel);
+                    acc[g] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, tb[g][jp], acc[g], ap, 0, 0);
             }
-            const unsigned rel = (unsigned)(t0 - c0) + 32u * s;
-            if (PIPE) {
-                prel = rel;
-                pending = true;
-                last = par;
-            } else {
-                test(acc[0], rel);
-            }
+            test(acc, (unsigned)(t0 - c0) + 32u * s);
         }
-    }
-    if (PIPE && pending) {  // uniform
-        if (last == 0) test(acc[0], prel);
-        else test(acc[PIPE ? 1 : 0], prel);
     }
     __syncthreads();
 
