@@ -15,7 +15,7 @@ constexpr int TILED_MFMA_MAX_CHUNKS = 4096;  // the same for small batches on th
 constexpr int TILED_MIN_Q = 8;         // smallest batch worth tiling
 constexpr int TILED_MFMA_MIN_Q = 16;   // smallest batch for the matrix-core kernel (32 queries per wavefront; twice that below 8 code bytes)
 constexpr int TILED_MFMA_MIN_Q2 = 64;  // smallest batch for its 64-queries-per-wavefront form
-constexpr int TILED_MFMA_MIN_Q4 = 256; // ... for 128 queries per wavefront (codes of up to 8 bytes)
+constexpr int TILED_MFMA_MIN_Q4 = 128; // ... for 128 queries per wavefront (codes of up to 8 bytes)
 
 struct TiledPlan {
     int B, GC;

@@ -364,7 +364,12 @@ static int mfma_min_q(int B)
     return std::max(1, env_int("QADC_MFMA_MIN_Q", B >= 8 ? TILED_MFMA_MIN_Q : 2 * TILED_MFMA_MIN_Q));
 }
 static int mfma_min_q2() { return std::max(1, env_int("QADC_MFMA_MIN_Q2", TILED_MFMA_MIN_Q2)); }
-static int mfma_min_q4() { return std::max(1, env_int("QADC_MFMA_MIN_Q4", TILED_MFMA_MIN_Q4)); }
+// 128 queries per wavefront (codes of up to 8 bytes): when the last set of 128 is more than half full
+static bool mfma_four(int B, int nq)
+{
+    const int min_q4 = std::max(1, env_int("QADC_MFMA_MIN_Q4", TILED_MFMA_MIN_Q4));
+    return B <= 8 && nq >= min_q4 && ((nq & 127) == 0 || (nq & 127) > 64);
+}
 
 bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 {
@@ -385,7 +390,7 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
     int64_t want = std::max<int64_t>(1, std::min<int64_t>(TILED_MAX_CHUNKS, ceil_div(1024, groups)));
     int64_t lo = 8, hi = 64, max_chunks = TILED_MAX_CHUNKS;
     if (t->mfma) {
-        const int qw = (t->B <= 8 && nq >= mfma_min_q4()) ? 128 : (t->B <= 16 && nq >= mfma_min_q2()) ? 64 : 32;
+        const int qw = mfma_four(t->B, nq) ? 128 : (t->B <= 16 && nq >= mfma_min_q2()) ? 64 : 32;
         // more chunks for small batches, as long as the lists of the whole batch (516 bytes per
         // query and chunk) stay within half of the 256 MiB that one launch's workspace may take:
         // beyond that the batch would be split into two launches
@@ -857,7 +862,7 @@ int run_tiled_scan(const TiledPlan &t, const uint8_t *codes, int64_t n, int nq, 
     if (t.mfma && qluts16 && reinterpret_cast<uintptr_t>(qluts16) % 16 == 0 && nq >= mfma_min_q(t.B)) {
 #define QADC_MFMA_ARGS t, codes, n, nq, cap, qluts16, taus, ws, ws_stride, countsA_off, listsA_off, flags, st
         const bool two = t.B <= 16 && nq >= mfma_min_q2();  // 64 queries per wavefront
-        const bool four = t.B <= 8 && nq >= mfma_min_q4();  // 128
+        const bool four = mfma_four(t.B, nq);               // 128
         switch (t.B) {
         case 4: return four ? launch_tiled_mfma<4, 4>(QADC_MFMA_ARGS) : two ? launch_tiled_mfma<4, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<4, 1>(QADC_MFMA_ARGS);
         case 8: return four ? launch_tiled_mfma<8, 4>(QADC_MFMA_ARGS) : two ? launch_tiled_mfma<8, 2>(QADC_MFMA_ARGS) : launch_tiled_mfma<8, 1>(QADC_MFMA_ARGS);
