@@ -424,8 +424,8 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 // bytes times a column of table entries, exact in int32.  A one-hot row is a structured-sparse row
 // (one non-zero in 16, so at most two in every four), which is what the sparse matrix instruction
 // takes: one v_smfmac_i32_32x32x64_i8 multiplies 32 codes by 32 queries over 64 values of k = four
-// tables = two code bytes, at the issue rate of the dense 32x32x32 instruction (measured here:
-// 8.0 Pop/s counted densely).  Operands, as found by probing the instruction:
+// tables = two code bytes, and occupies the matrix pipe as long as the dense 32x32x32 instruction
+// (32 cycles).  Operands, as found by probing the instruction with single non-zeros:
 //   B (dense, 32 bytes per lane): lane (query = lane mod 32, half = lane / 32) holds k = 32 half ..
 //     32 half + 31, i.e. the 16 entries of tables 4jp + 2 half and 4jp + 2 half + 1 of its query as
 //     they lie in memory;
