@@ -692,7 +692,9 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
                 w[0] = wn[0]; w[1] = wn[1];
                 nc[0] = ncn[0]; nc[1] = ncn[1];
                 if (t0 + C::TILE < u1) tile_load<B, NT>(codes, t0 + C::TILE, n_total, wn, ncn);  // uniform
-                uint64_t k[C::CPT];
+                // Sums only; positions, validity and keys are worked out in the wavefronts that hold a
+                // sum small enough to pass (a slot without a code may hold one too: it is dropped there).
+                unsigned sm[C::CPT];
                 if constexpr (B <= 16) {
                     constexpr int CPV = 16 / B;
 #pragma unroll
@@ -702,28 +704,38 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
                             unsigned s = 0;
 #pragma unroll
                             for (int jb = 0; jb < B; ++jb) s += ptab[jb * 256 + byte_of(w[v], c * B + jb)];
-                            const long long pos = t0 + (long long)((v * NT + tid) * CPV + c);
-                            const bool valid = (c < nc[v]) && pos >= lo && pos < u1;
-                            k[v * CPV + c] = valid ? (((uint64_t)s << 32) | (uint64_t)pos) : ~0ull;
+                            sm[v * CPV + c] = s;
                         }
                     }
                 } else {
                     unsigned s = 0;
 #pragma unroll
                     for (int jb = 0; jb < 32; ++jb) s += ptab[jb * 256 + byte_of(w[jb >> 4], jb & 15)];
-                    const long long pos = t0 + tid;
-                    const bool valid = nc[0] && pos >= lo && pos < u1;
-                    k[0] = valid ? (((uint64_t)s << 32) | (uint64_t)pos) : ~0ull;
+                    sm[0] = s;
                 }
-                uint64_t best = k[0];
+                unsigned best = sm[0];
 #pragma unroll
-                for (int c = 1; c < C::CPT; ++c) best = min(best, k[c]);
-                if (__ballot(best < lim) != 0ull) {
+                for (int c = 1; c < C::CPT; ++c) best = min(best, sm[c]);
+                // a key below lim has a sum of at most (lim - 1) >> 32
+                const unsigned limsum = (unsigned)((lim - 1ull) >> 32);
+                if (__ballot(best <= limsum) != 0ull) {
 #pragma unroll
                     for (int c = 0; c < C::CPT; ++c) {
-                        const bool pass = k[c] < lim;
+                        long long pos;
+                        bool valid;
+                        if constexpr (B <= 16) {
+                            constexpr int CPV = 16 / B;
+                            const int v = c / CPV, cc = c % CPV;
+                            pos = t0 + (long long)((v * NT + tid) * CPV + cc);
+                            valid = (cc < nc[v]) && pos >= lo && pos < u1;
+                        } else {
+                            pos = t0 + tid;
+                            valid = nc[0] && pos >= lo && pos < u1;
+                        }
+                        const uint64_t key = ((uint64_t)sm[c] << 32) | (uint64_t)pos;
+                        const bool pass = valid && key < lim;
                         const unsigned slot = wave_append_slot(pass, &sh.fcnt);
-                        if (pass && slot < (unsigned)C::CAP) keys[slot] = k[c];
+                        if (pass && slot < (unsigned)C::CAP) keys[slot] = key;
                     }
                 }
             }
