@@ -14,6 +14,10 @@
 
 namespace qadc {
 
+#ifndef QADC_IVF_EARLY_STAGES
+// (a check at a quarter and at half of the bytes measured the same as the one check at half)
+#define QADC_IVF_EARLY_STAGES(B) ((B) >= 4 ? 2 : 1)
+#endif
 constexpr int IVF_MAX_NPROBE = 256;
 constexpr int IVF_NT = 256;      // threads of the scan workgroups
 constexpr int IVF_UNIT_TILES = 8;
@@ -694,30 +698,53 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
                 if (t0 + C::TILE < u1) tile_load<B, NT>(codes, t0 + C::TILE, n_total, wn, ncn);  // uniform
                 // Sums only; positions, validity and keys are worked out in the wavefronts that hold a
                 // sum small enough to pass (a slot without a code may hold one too: it is dropped there).
+                // Entries are not negative, so a code whose first half of the bytes already sums to more
+                // than a passing sum may cannot pass: only the lanes that hold a code still in the race
+                // look up the other half (a wavefront without one skips it; with few lanes left they no
+                // longer collide on the LDS banks), the others keep their partial sum.
+                // a key below lim has a sum of at most (lim - 1) >> 32
+                const unsigned limsum = (unsigned)((lim - 1ull) >> 32);
                 unsigned sm[C::CPT];
                 if constexpr (B <= 16) {
                     constexpr int CPV = 16 / B;
+                    // stages of bytes, a check after each but the last
+                    constexpr int NS = QADC_IVF_EARLY_STAGES(B);
+                    constexpr int cut[4] = {0, NS == 3 ? B / 4 : (NS == 2 ? B / 2 : B), NS == 3 ? B / 2 : B, B};
 #pragma unroll
-                    for (int v = 0; v < 2; ++v) {
+                    for (int c = 0; c < 2 * CPV; ++c) sm[c] = 0;
+                    bool go = true;
 #pragma unroll
-                        for (int c = 0; c < CPV; ++c) {
-                            unsigned s = 0;
+                    for (int st = 0; st < NS; ++st) {
+                        if (go) {
+                            unsigned part = 0xffffffffu;
 #pragma unroll
-                            for (int jb = 0; jb < B; ++jb) s += ptab[jb * 256 + byte_of(w[v], c * B + jb)];
-                            sm[v * CPV + c] = s;
+                            for (int v = 0; v < 2; ++v) {
+#pragma unroll
+                                for (int c = 0; c < CPV; ++c) {
+                                    unsigned s = sm[v * CPV + c];
+#pragma unroll
+                                    for (int jb = cut[st]; jb < cut[st + 1]; ++jb)
+                                        s += ptab[jb * 256 + byte_of(w[v], c * B + jb)];
+                                    sm[v * CPV + c] = s;
+                                    part = min(part, s);
+                                }
+                            }
+                            go = part <= limsum;
                         }
                     }
                 } else {
                     unsigned s = 0;
 #pragma unroll
-                    for (int jb = 0; jb < 32; ++jb) s += ptab[jb * 256 + byte_of(w[jb >> 4], jb & 15)];
+                    for (int jb = 0; jb < 16; ++jb) s += ptab[jb * 256 + byte_of(w[0], jb)];
+                    if (s <= limsum) {
+#pragma unroll
+                        for (int jb = 16; jb < 32; ++jb) s += ptab[jb * 256 + byte_of(w[1], jb & 15)];
+                    }
                     sm[0] = s;
                 }
                 unsigned best = sm[0];
 #pragma unroll
                 for (int c = 1; c < C::CPT; ++c) best = min(best, sm[c]);
-                // a key below lim has a sum of at most (lim - 1) >> 32
-                const unsigned limsum = (unsigned)((lim - 1ull) >> 32);
                 if (__ballot(best <= limsum) != 0ull) {
 #pragma unroll
                     for (int c = 0; c < C::CPT; ++c) {

@@ -38,6 +38,11 @@ struct ScanShared {
     unsigned fcnt;     // append counter of the barrier-free pass (may run past the list's end)
 };
 
+#ifndef QADC_EARLY_STAGES
+// (a check at a quarter and at half of the bytes measured the same as the one check at half)
+#define QADC_EARLY_STAGES(B) ((B) >= 4 ? 2 : 1)
+#endif
+
 // One pair-table entry, known to the compiler as a byte value.
 __device__ __forceinline__ unsigned pair_entry(const uint8_t *ptab, int jb, unsigned v)
 {
@@ -80,30 +85,50 @@ __device__ __forceinline__ void tile_keys(const uint4 (&w)[2], const int (&nc)[2
     }
 }
 
-// Unclamped sums of a whole tile (every slot holds a code), for the pass that only keeps
-// sums at or below a bound smaller than the saturation value.
+// Unclamped sums of a whole tile (every slot holds a code), for the pass that only keeps sums at or
+// below `bound`, itself smaller than the saturation value.  Entries are not negative, so a code
+// whose first B/2 bytes already sum to more than the bound cannot pass: the lookups of the other
+// bytes are done only by the lanes that hold a code still in the race (a wavefront without one skips
+// them; with few lanes left they no longer collide on the LDS banks), and the others report their
+// partial sum, which is above the bound as the full one would be.
 template <int B, int NT>
-__device__ __forceinline__ void tile_sums(const uint4 (&w)[2], const uint8_t *ptab,
+__device__ __forceinline__ void tile_sums(const uint4 (&w)[2], const uint8_t *ptab, unsigned bound,
                                           unsigned (&sm)[ScanCfg<B, NT>::CPT])
 {
     if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
+        // the bytes are summed in stages, with a check after each stage but the last
+        constexpr int NS = QADC_EARLY_STAGES(B);
+        constexpr int cut[4] = {0, NS == 3 ? B / 4 : (NS == 2 ? B / 2 : B), NS == 3 ? B / 2 : B, B};
 #pragma unroll
-        for (int v = 0; v < 2; ++v) {
+        for (int c = 0; c < 2 * CPV; ++c) sm[c] = 0;
+        bool go = true;
 #pragma unroll
-            for (int c = 0; c < CPV; ++c) {
-                unsigned s = 0;
+        for (int st = 0; st < NS; ++st) {
+            if (go) {
+                unsigned best = 0xffffffffu;
 #pragma unroll
-                for (int jb = 0; jb < B; ++jb) s += pair_entry(ptab, jb, byte_of(w[v], c * B + jb));
-                sm[v * CPV + c] = s;
+                for (int v = 0; v < 2; ++v) {
+#pragma unroll
+                    for (int c = 0; c < CPV; ++c) {
+                        unsigned s = sm[v * CPV + c];
+#pragma unroll
+                        for (int jb = cut[st]; jb < cut[st + 1]; ++jb) s += pair_entry(ptab, jb, byte_of(w[v], c * B + jb));
+                        sm[v * CPV + c] = s;
+                        best = min(best, s);
+                    }
+                }
+                go = best <= bound;
             }
         }
     } else {
         unsigned s = 0;
 #pragma unroll
         for (int jb = 0; jb < 16; ++jb) s += pair_entry(ptab, jb, byte_of(w[0], jb));
+        if (s <= bound) {
 #pragma unroll
-        for (int jb = 0; jb < 16; ++jb) s += pair_entry(ptab, 16 + jb, byte_of(w[1], jb));
+            for (int jb = 0; jb < 16; ++jb) s += pair_entry(ptab, 16 + jb, byte_of(w[1], jb));
+        }
         sm[0] = s;
     }
 }
@@ -585,7 +610,7 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
             if (t0 + C::TILE <= n) {  // uniform: a whole tile, no bounds to check
                 if (rel) tile_load<B, NT, true>(codes, t0, n, w, nc);
                 unsigned sm[C::CPT];
-                tile_sums<B, NT>(w, ptab, sm);
+                tile_sums<B, NT>(w, ptab, tau, sm);
                 unsigned best = sm[0];
 #pragma unroll
                 for (int c = 1; c < C::CPT; ++c) best = min(best, sm[c]);
