@@ -943,7 +943,14 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     if (!ix || nq < 1 || nprobe < 1 || nprobe > IVF_MAX_NPROBE || R < 1 || R > QADC_MAX_R) return false;
     if (!(ix->m == 8 || ix->m == 16 || ix->m == 32 || ix->m == 64)) return false;
     if (ix->d < ix->m || ix->d % ix->m || ix->K < 1 || ix->n < 0 || ix->n > 0xfffffffell) return false;
-    p->W = env_int("QADC_IVF_WGS", 128);  // most workgroups a query can get
+    // Most workgroups a query can get: 128 for up to 128 queries, fewer for larger calls, about
+    // 16384 workgroup slots per launch (measured at N = 1e9: 4096 queries 161 K queries/s with 24 to
+    // 32 against 156 K with 128; 1024 queries best with 24, 512 with 32 to 48, 256 with 64, 128 with
+    // 96 to 128); the regions of a query shrink with it, so a launch holds more queries.
+    int w_def = 16384 / nq;
+    if (w_def < 24) w_def = 24;
+    if (w_def > 128) w_def = 128;
+    p->W = env_int("QADC_IVF_WGS", w_def);
     if (p->W < 1) p->W = 1;
     if (p->W > 4096) p->W = 4096;
     // about 1/16 of an average list, between 64 and 1024 codes
