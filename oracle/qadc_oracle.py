@@ -60,6 +60,11 @@ opq_rotate by permutation and block-rotation matrices worked by hand.  The
 transposed layout of Fig. 2b is pinned by a block written out by hand, the
 positions of single bytes of a ragged list, and by Alg. 2 run over its blocks
 and rows giving the sums of the standard-layout scan and of the plain definition.
+The inverted-index search is pinned by hand-built indexes: the qmax walk (first
+`init` codes in probe order, each with its own cell's tables) against brute-force
+distances to centroid + decoded residual, the (sum, storage position) order
+against sorted tuples on lists probed in reverse storage order, the Index step
+on repeated centroids; overlap, NN-recall and exact_nn on rows worked by hand.
 """
 
 from __future__ import annotations
