@@ -770,7 +770,9 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
             have = sh.fcnt;
             __syncthreads();  // everybody has read the count before the next unit bumps it
             if (have > (unsigned)C::CAP) { careful = true; break; }  // uniform: keys were dropped
-            if (have > (unsigned)SCAN_SLACK / 2) {
+            // cut the list back once it holds more than R keys and has grown past half its slack
+            // (a list of at most R keys is the workgroup's result so far: nothing to drop)
+            if (have > max((unsigned)R, (unsigned)SCAN_SLACK / 2)) {
                 const uint64_t kth = compact_candidates<uint64_t, 5, NT, C::CAP>(
                     keys, have, (unsigned)R, &sh.sel, &sh.ccnt);
                 lim = min(lim, kth + 1ull);

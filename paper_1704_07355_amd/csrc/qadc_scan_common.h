@@ -72,13 +72,16 @@ __device__ __forceinline__ unsigned wave_threshold_bin(const unsigned (&h)[NB], 
     return __shfl(bin, first);
 }
 
-// Cuts keys[0..cnt) back to its `keep` smallest keys (cnt > keep) and returns the largest
-// key kept.  K = key type, NBYTES = key bytes that can be non-zero.  Called by every thread
-// of the workgroup; `ccnt` is an LDS counter of the workgroup.
+// Cuts keys[0..cnt) back to its `keep` smallest keys and returns the largest key kept.  A list
+// of at most `keep` keys is left as it is (the value returned then bounds nothing).  K = key
+// type, NBYTES = key bytes that can be non-zero.  Called by every thread of the workgroup with
+// the same cnt and keep; `ccnt` is an LDS counter of the workgroup.  The caller's list then
+// holds min(cnt, keep) keys.
 template <typename K, int NBYTES, int NT, int CAP>
 __device__ K compact_candidates(K *keys, unsigned cnt, unsigned keep, SelectScratch *sel,
                                 unsigned *ccnt)
 {
+    if (cnt <= keep) return ~(K)0 - 1;  // uniform
     const K kth = block_radix_select<K, NBYTES>(keys, cnt, keep, sel);
     constexpr int PER = (CAP + NT - 1) / NT;
     K mine[PER];

@@ -16,7 +16,8 @@ struct SelectScratch {
 };
 
 // Scan of a 256-bin histogram by the first wave: finds the bin holding the
-// `need`-th smallest element (1-based) and the rank of that element inside the bin.
+// `need`-th smallest element (1-based) and the rank of that element inside the bin
+// (the last element when fewer than `need` were counted).
 __device__ __forceinline__ void select_bin(SelectScratch *sc, unsigned need)
 {
     if (threadIdx.x < WAVE) {
@@ -30,6 +31,11 @@ __device__ __forceinline__ void select_bin(SelectScratch *sc, unsigned need)
             unsigned up = __shfl_up(inc, d);
             if (l >= d) inc += up;
         }
+        // a request beyond the histogram's total is answered with its last element, an empty
+        // histogram with bin 0 and rank 0: the result is defined for every input
+        const unsigned total = __shfl(inc, WAVE - 1);
+        if (need > total) need = total;
+        if (need == 0 && l == 0) { sc->bin = 0; sc->need = 0; }
         unsigned excl = inc - tot;
         unsigned h[4] = {h0, h1, h2, h3};
 #pragma unroll

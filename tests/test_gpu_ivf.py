@@ -299,3 +299,26 @@ def test_ivf_bound_sampled_by_several_workgroups(Q, O, nprobe, nq):
                                      probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
         assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
         assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
+
+
+@pytest.mark.parametrize("R", [600, 1000])
+@pytest.mark.parametrize("nq", [3, 70])
+def test_ivf_large_R_many_probes(Q, O, R, nq):
+    """R above half the candidate list's slack, 32 probed cells: a workgroup's list grows past 512 keys
+    while it still holds fewer than R (nothing to cut back yet), for a few queries (a workgroup per
+    unit) and for a batch (a workgroup walks many units).  Oracle replay on the GPU's cells and tables."""
+    import torch
+    coarse, cb, x, index = build_ivf(O, n=300_000, K=40, d=64, m=16, seed=R)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(R + nq)
+    queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, x.shape[1]))).astype(np.float32)
+    nprobe, init = 32, 1000
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    ids, dist, probes, qluts = idx_np(ids), dist.cpu().numpy(), probes.cpu().numpy(), qluts.cpu().numpy()
+    for iq in range(0, nq, max(1, nq // 10)):
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=probes[iq], qluts=qluts[iq])
+        assert len(set(ids[iq].tolist())) == R, iq  # every slot written, no neighbour twice
+        assert np.array_equal(ids[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq], rep["dist"]), iq
