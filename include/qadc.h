@@ -176,6 +176,26 @@ int qadc_search(const float *codebooks, int d, int m, const float *queries, int 
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * qadc_search for callers that cannot allocate device memory or own no workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results as qadc_search, without the workspace: the scratch of the scan is a static device array
+ * of QADC_STATIC_SCRATCH_BYTES inside the library (each GPU the entry point is used on holds its
+ * own copy until the process ends).  The call allocates nothing and frees nothing.
+ *   - Limit: the scratch of ONE query (qadc_workspace_bytes(QADC_WS_SEARCH, n, m, 1, R)) must fit
+ *     the array, else QADC_ENOMEM and nothing is enqueued; batches larger than the array holds are
+ *     cut into several launch sequences on `stream` (same results).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU -- from two
+ *     streams or two threads -- race; order them on one stream.  The array is cleared by a kernel
+ *     on `stream` at the first call on a GPU and after a call that failed with QADC_EHIP; every
+ *     successful call leaves it cleared for the next.
+ */
+#define QADC_STATIC_SCRATCH_BYTES (32u << 20)
+int qadc_search_static(const float *codebooks, int d, int m, const float *queries, int nq,
+                       const uint8_t *codes, int64_t n, int R, int init, int nbins, int qmin_mode,
+                       uint32_t *out_idx, uint8_t *out_dist, uint8_t *qluts_out, void *stream);
+size_t qadc_static_scratch_bytes(void);
+
+/*
  * Inverted index (Section 2.2): K cells around the coarse centroids; the codes of the
  * RESIDUALS x - centroid of a cell's vectors are stored contiguously (one inverted list per
  * cell, cell c holding storage positions list_off[c] .. list_off[c+1]-1), with the vector

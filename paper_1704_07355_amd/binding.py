@@ -33,7 +33,7 @@ EXPORTS = (
     "qadc_last_error", "qadc_version", "qadc_packed_bytes", "qadc_pack_codes", "qadc_unpack_codes",
     "qadc_ivf_assign", "qadc_ivf_group_workspace_bytes", "qadc_ivf_group", "qadc_ivf_encode",
     "qadc_multi_index_cells", "qadc_multi_index_assign", "qadc_multi_index_workspace_bytes",
-    "qadc_multi_index_probes",
+    "qadc_multi_index_probes", "qadc_search_static", "qadc_static_scratch_bytes",
 )
 
 _lib = None
@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.qadc_scan_topk.restype = i32
         L.qadc_search.argtypes = [vp, i32, i32, vp, i32, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         L.qadc_search.restype = i32
+        L.qadc_search_static.argtypes = [vp, i32, i32, vp, i32, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp]
+        L.qadc_search_static.restype = i32
+        L.qadc_static_scratch_bytes.argtypes = []
+        L.qadc_static_scratch_bytes.restype = sz
         L.qadc_ivf_search.argtypes = [ctypes.POINTER(qadc_ivf_index), vp, i32, i32, i32, i32, i32, i32,
                                       vp, vp, vp, vp, vp, vp, sz, vp]
         L.qadc_ivf_search.restype = i32
@@ -449,4 +453,22 @@ def qadc_search(codebooks, queries, codes, R, init, nbins=255, qmin_mode=QADC_QM
                              _ptr(codes, torch.uint8), n, R, init, nbins, qmin_mode, _ptr(out_idx),
                              _ptr(out_dist), _ptr(qluts_out, torch.uint8), _ptr(workspace),
                              workspace.numel() * workspace.element_size(), _stream()))
+    return out_idx, out_dist
+
+
+def qadc_static_scratch_bytes() -> int:
+    return int(lib().qadc_static_scratch_bytes())
+
+
+def qadc_search_static(codebooks, queries, codes, R, init, out_idx, out_dist, nbins=255,
+                       qmin_mode=QADC_QMIN_PER_TABLE, qluts_out=None, n=None):
+    """qadc_search without a workspace and without any allocation: the caller passes the outputs
+    (idx i32 [nq][R], dist u8 [nq][R]); the scratch is the library's static device array."""
+    m, ksub, dsub = codebooks.shape
+    nq, d = queries.shape
+    if n is None:
+        n = codes.shape[0]
+    _check(lib().qadc_search_static(_ptr(codebooks, torch.float32), d, m, _ptr(queries, torch.float32), nq,
+                                    _ptr(codes, torch.uint8), n, R, init, nbins, qmin_mode, _ptr(out_idx),
+                                    _ptr(out_dist), _ptr(qluts_out, torch.uint8), _stream()))
     return out_idx, out_dist
