@@ -35,6 +35,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
+WORKLOAD_DEFAULTS = {
+    "scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200, batch=256),
+    "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000, batch=256),
+    "ivf": dict(steps=4, warmup=1, n=1_000_000_000, m=32, init=1000, batch=4096),
+    "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200, batch=256),
+    "build": dict(steps=3, warmup=1, n=4_000_000, m=16, init=200, batch=256),
+}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -71,15 +80,12 @@ def parse():
     ap.add_argument("--opq", type=int, default=0, metavar="ROUNDS",
                     help="scan workload: train an optimized product quantizer with this many rounds; database "
                          "vectors are rotated before encoding and every query by qadc_rotate before qadc_search")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="scan workload: skip the short runs of configs 3, 4 and 5 nested in the same line")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time qadc_build_luts + qadc_quantize_luts + qadc_scan_topk instead of qadc_search")
     args = ap.parse_args()
-    dflt = {"scan": dict(steps=1000, warmup=50, n=10_000_000, m=16, init=200, batch=256),
-            "batched": dict(steps=8, warmup=1, n=100_000_000, m=32, init=1000, batch=256),
-            "ivf": dict(steps=4, warmup=1, n=1_000_000_000, m=32, init=1000, batch=4096),
-            "compare": dict(steps=1000, warmup=20, n=50_000_000, m=16, init=200, batch=256),
-            "build": dict(steps=3, warmup=1, n=4_000_000, m=16, init=200, batch=256)}[args.workload]
-    for k, v in dflt.items():
+    for k, v in WORKLOAD_DEFAULTS[args.workload].items():
         if getattr(args, k) is None:
             setattr(args, k, v)
     return args
@@ -243,17 +249,20 @@ def run_batched(args):
         ach = n * nb * m / (ms_scan * 1e-3) / 1e12
         on_matrix_cores = nb >= (16 if m >= 16 else 32) and os.environ.get("QADC_TILED_MFMA", "1") != "0"
         if on_matrix_cores:
-            # one-hot products on the sparse matrix instruction: every (code, query, table) lookup is a
-            # 16-term int8 dot product of which the hardware executes 8 terms (two of every four)
+            # The method's work is m lookup-adds per (code, query) pair (Alg. 2); the ceiling quoted for
+            # it is the vector ALU's byte-lane rate, whatever unit executes it.  This kernel forms the
+            # sums as one-hot int8 products on the sparse matrix instruction: every lookup-add is a
+            # 16-term dot product of which the hardware executes 8 terms (two of every four) -- reported
+            # beside it, not as the fraction.
             ops = n * nb * m * 8 * 2 / (ms_scan * 1e-3) / 1e12
-            roofline = {"bound": "mfma", "kernel": "scan_u8_mfma_kernel (+ the redo launch)", "achieved": round(ops, 1),
-                        "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s", "frac": round(ops / MFMA_I8_PEAK_TOPS, 4),
-                        "note": "int8 operations executed by v_smfmac_i32_32x32x64_i8 against the dense int8 peak "
-                                "(the instruction issues at the dense rate and covers twice the k range); "
-                                "all but one of 16 products of a lookup are by a zero of the one-hot operand",
-                        "dense_equivalent_tops": round(2 * ops, 1),
-                        "useful_T_lookup_adds_per_s": round(ach, 2),
-                        "frac_of_vector_alu_byte_lane_ceiling": round(ach / ALU_PEAK_TLOOKUPS, 4),
+            roofline = {"bound": "alu", "kernel": "scan_u8_mfma_kernel (+ the redo launch)", "achieved": round(ach, 2),
+                        "peak": ALU_PEAK_TLOOKUPS, "unit": "T lookup-adds/s", "frac": round(ach / ALU_PEAK_TLOOKUPS, 4),
+                        "note": "m lookup-adds per (code, query) pair against the byte-lane ceiling of the vector ALU "
+                                "(256 CUs x 64 lanes x 2.4 GHz x 4 byte lanes); the kernel executes them on the matrix "
+                                "cores as one-hot products, 15 of every 16 by zero",
+                        "int8_ops_executed_tops": round(ops, 1),
+                        "int8_ops_executed_frac_of_dense_mfma_peak": round(ops / MFMA_I8_PEAK_TOPS, 4),
+                        "lookup_adds_as_int8_macs_frac_of_mfma_peak": round(2 * ach / MFMA_I8_PEAK_TOPS, 4),
                         "traffic": MFMA_TRAFFIC if (n, m, nb) == (100_000_000, 32, 256) else None,
                         "traffic_source": "profiles/hbm_traffic_configs_3_4_5.md (rocprofv3 --pmc FETCH_SIZE, bytes read per launch)",
                         "scan_ms": round(ms_scan, 3), "launches_timed": launches}
@@ -281,7 +290,7 @@ def run_batched(args):
                % (nqc, n), "seconds": round(dt, 2),
                "gpu_matches_oracle": bool(np.array_equal(gi, ci) and np.array_equal(gd, cd))}
 
-    print(json.dumps({
+    return ({
         "metric": "G (code, query) pairs scanned/s (query-batched 4-bit Quick ADC scan, whole path per batch)",
         "value": round(pairs / 1e9, 1), "unit": "Gpairs/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
@@ -290,7 +299,7 @@ def run_batched(args):
                    "through qadc_search (a wavefront scans each code for 64 queries), R=%d, init=%d"
                    % (m, n, nb, R, init), "n": n, "m": m, "R": R, "init": init, "batch": nb},
         "gcodes_per_s_per_query": round(pairs / nb / 1e9, 2),
-        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)})
 
 
 def build_ivf_index(Q, torch, np, n, K, m, n_queries, dev, d=128, sigma=18.0):
@@ -437,7 +446,7 @@ def run_ivf(args):
                "sample": "%d queries of the last batch, NumPy oracle replay of the GPU's cells and tables "
                "(%d codes)" % (nqc, codes_done), "seconds": round(dt, 2), "gpu_sums_match_oracle": bool(same)}
 
-    print(json.dumps({
+    return ({
         "metric": "queries/s (IVF + Quick ADC, whole path per batch)",
         "value": round(nb / (ms_per_step * 1e-3), 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
@@ -448,7 +457,7 @@ def run_ivf(args):
         "gcodes_scanned_per_s": round(scanned / (ms_per_step * 1e-3) / 1e9, 2),
         "phase_ms_per_query": {k: round(v / nb, 5) for k, v in phase.items()},
         "multi_index": multi_index,
-        "roofline": roofline, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)}))
+        "roofline": roofline, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)})
 
 
 def run_compare(args):
@@ -643,7 +652,7 @@ def run_compare(args):
                "gpu_matches_oracle": bool(np.array_equal(gi.cpu().numpy().view(np.uint32), ci)
                                           and np.array_equal(gd.cpu().numpy(), cd))}
 
-    print(json.dumps({
+    return ({
         "metric": "G PQ codes scanned/s (Quick ADC m=16 x 4-bit, whole path per query) with the 8-bit PQ "
                   "float-table scan of the same vectors beside it",
         "value": round(n / (ms4 * 1e-3) / 1e9, 2), "unit": "Gcodes/s", "n_gpus": 1, "steps": args.steps,
@@ -660,7 +669,7 @@ def run_compare(args):
         "speedup_quick_adc_over_pq8_float": round(ms8 / ms4, 3),
         "batches_of_256": batched,
         "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,
-        "database_build_s": round(t_build, 2)}))
+        "database_build_s": round(t_build, 2)})
 
 
 def run_build(args):
@@ -762,7 +771,38 @@ def run_build(args):
            "layout_gb_per_s": {"pack": round(2 * codes.numel() / (phase["pack"] * 1e-3) / 1e9, 1),
                                "unpack": round(2 * codes.numel() / (phase["unpack"] * 1e-3) / 1e9, 1)},
            "cpu_baseline": cpu}
-    print(json.dumps(out))
+    return out
+
+
+def other_workloads(argv_args):
+    """Short runs of the other workloads (configs 3, 4, 5 at their full sizes), each with the record its
+    own `--workload` run prints; nested under one key of the headline line."""
+    import gc
+    import torch
+    out = {}
+    plans = (("config3_batched", "batched", dict(steps=4, warmup=1)),
+             ("config4_ivf", "ivf", dict(steps=2, warmup=1)),
+             ("config5_compare", "compare", dict(steps=300, warmup=20)))
+    for key, workload, over in plans:
+        a = argparse.Namespace(**vars(argv_args))
+        a.workload = workload
+        for k, v in {**WORKLOAD_DEFAULTS[workload], **over}.items():
+            setattr(a, k, v)
+        a.d, a.R, a.nbins, a.K, a.nprobe, a.copy_calibration, a.opq = 128, 100, 255, 65536, 64, 0, 0
+        a.queries, a.recall_queries = 1000, 100
+        t0 = time.time()
+        try:
+            rec = RUNNERS[workload](a)
+            rec["wall_s"] = round(time.time() - t0, 1)
+        except Exception as e:  # an extra must not take the headline with it
+            rec = {"error": "%s: %s" % (type(e).__name__, e)}
+        out[key] = rec
+        gc.collect()
+        torch.cuda.empty_cache()
+    return out
+
+
+RUNNERS = {"batched": run_batched, "ivf": run_ivf, "compare": run_compare, "build": run_build}
 
 
 def main():
@@ -774,8 +814,8 @@ def main():
     if args.workload in ("batched", "ivf", "compare", "build"):
         import paper_1704_07355_amd as Q
         Q.lib()
-        return {"batched": run_batched, "ivf": run_ivf, "compare": run_compare,
-                "build": run_build}[args.workload](args)
+        print(json.dumps(RUNNERS[args.workload](args)))
+        return
 
     import numpy as np
     import torch
@@ -970,6 +1010,13 @@ def main():
         "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,
         "database_build_s": round(t_build, 2),
     }
+    if roofline is not None:
+        # the same bytes over the whole path of a query (every launch and the gaps between them)
+        roofline["whole_path"] = {"achieved": rec["hbm_gbps_whole_path"], "frac": round(rec["hbm_gbps_whole_path"] / HBM_PEAK_GBPS, 4),
+                                  "us_per_query": round(ms_per_step * 1e3, 2)}
+    if not args.no_extras and (args.d, m, n) == (128, 16, 10_000_000) and not args.separate_calls and rot is None:
+        del codes, bufs, raw
+        rec["other_workloads"] = other_workloads(args)
     print(json.dumps(rec))
 
 
