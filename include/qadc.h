@@ -33,7 +33,7 @@
  *    QADC_MFMA_WAVES, QADC_IVF_SEED_PARTS)
  *    change launch shapes, which of the equivalent kernels scans a batch and whether a
  *    sampled bound is used -- never a result.
- *    They are read at every call and exist for tuning and for tests.
+ *    They are read once per call of an entry point and exist for tuning and for tests.
  *  - Top-R outputs: row q holds the R best of query q, ascending under the
  *    total order (distance, index) -- lowest index first among equal
  *    distances.  When fewer than R codes exist the tail is padded with index

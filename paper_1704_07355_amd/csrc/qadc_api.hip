@@ -1,7 +1,9 @@
 // extern "C" boundary of the library: argument checks and dispatch only.
 // Every step of the path runs in the kernels of the other translation units.
 
-#include "qadc_common.h"
+#include <stdlib.h>
+
+#include "qadc_scan_common.h"
 #include "qadc_profile.h"
 
 namespace qadc {
@@ -19,6 +21,40 @@ int fail(int code, const char *fmt, ...)
     vsnprintf(err_buf(), 512, fmt, ap);
     va_end(ap);
     return code;
+}
+
+namespace {
+thread_local Knobs g_knobs = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
+int env_knob(const char *name)
+{
+    const char *s = getenv(name);
+    if (!s || !*s) return -1;
+    const int v = atoi(s);
+    return v < 0 ? 0 : v;
+}
+}  // namespace
+
+const Knobs &knobs() { return g_knobs; }
+
+void knobs_refresh()
+{
+    Knobs &k = g_knobs;
+    k.scan_nt = env_knob("QADC_SCAN_NT");
+    k.scan_wgs = env_knob("QADC_SCAN_WGS");
+    k.seed_min_tiles = env_knob("QADC_SEED_MIN_TILES");
+    k.seed_wgs = env_knob("QADC_SEED_WGS");
+    k.tiled = env_knob("QADC_TILED");
+    k.tiled_seed = env_knob("QADC_TILED_SEED");
+    k.scan_f32_wgs = env_knob("QADC_SCAN_F32_WGS");
+    k.tiled_mfma = env_knob("QADC_TILED_MFMA");
+    k.mfma_min_q = env_knob("QADC_MFMA_MIN_Q");
+    k.mfma_min_q2 = env_knob("QADC_MFMA_MIN_Q2");
+    k.mfma_min_q4 = env_knob("QADC_MFMA_MIN_Q4");
+    k.mfma_waves = env_knob("QADC_MFMA_WAVES");
+    k.ivf_wgs = env_knob("QADC_IVF_WGS");
+    k.ivf_seed = env_knob("QADC_IVF_SEED");
+    k.ivf_units = env_knob("QADC_IVF_UNITS");
+    k.ivf_seed_parts = env_knob("QADC_IVF_SEED_PARTS");
 }
 
 int build_luts(const float *, int, int, int, const float *, const float *, int, float *, hipStream_t);
@@ -83,6 +119,7 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void 
                    int R, int nbins, uint32_t *out_idx, void *out_dist, void *workspace,
                    size_t workspace_bytes, void *stream)
 {
+    qadc::knobs_refresh();
     if (!luts || !out_idx || !out_dist || (!codes && n > 0))
         return qadc::fail(QADC_EINVAL, "qadc_scan_topk: null pointer");
     if (nq == 0) return QADC_OK;
@@ -107,6 +144,7 @@ int qadc_search(const float *codebooks, int d, int m, const float *queries, int 
                 uint32_t *out_idx, uint8_t *out_dist, uint8_t *qluts_out, void *workspace,
                 size_t workspace_bytes, void *stream)
 {
+    qadc::knobs_refresh();
     return qadc::search_u8(codebooks, d, m, queries, nq, codes, n, R, init, nbins, qmin_mode, out_idx,
                            out_dist, qluts_out, workspace, workspace_bytes, (hipStream_t)stream);
 }
@@ -116,6 +154,7 @@ int qadc_ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int 
                     uint32_t *out_ids, uint8_t *out_dist, int32_t *dbg_probes, uint8_t *dbg_qluts,
                     void *workspace, size_t workspace_bytes, void *stream)
 {
+    qadc::knobs_refresh();
     return qadc::ivf_search(ix, queries, nq, nprobe, R, init, nbins, qmin_mode, probes_in, out_ids,
                             out_dist, dbg_probes, dbg_qluts, workspace, workspace_bytes,
                             (hipStream_t)stream);
@@ -123,6 +162,7 @@ int qadc_ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int 
 
 size_t qadc_ivf_workspace_bytes(const qadc_ivf_index *ix, int nq, int nprobe, int R)
 {
+    qadc::knobs_refresh();
     return qadc::ivf_workspace_bytes(ix, nq, nprobe, R);
 }
 
@@ -212,6 +252,7 @@ int qadc_pq_train(const float *train, int64_t n, int d, int m, int ksub, const i
 
 size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)
 {
+    qadc::knobs_refresh();
     switch (call) {
     case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(QADC_U8_4BIT, n, m, nq, R);
     case QADC_WS_SCAN_U8_8BIT: return qadc::scan_topk_u8_workspace(QADC_U8_8BIT, n, m, nq, R);

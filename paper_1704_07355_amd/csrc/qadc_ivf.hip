@@ -952,14 +952,14 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     int w_def = 16384 / nq;
     if (w_def < 24) w_def = 24;
     if (w_def > 128) w_def = 128;
-    p->W = env_int("QADC_IVF_WGS", w_def);
+    p->W = knob_or(knobs().ivf_wgs, w_def);
     if (p->W < 1) p->W = 1;
     if (p->W > 4096) p->W = 4096;
     // about 1/16 of an average list, between 64 and 1024 codes
     int64_t spl = ix->n / ix->K / 16;
     if (spl < 64) spl = 64;
     if (spl > 1024) spl = 1024;
-    p->seed_per_list = env_int("QADC_IVF_SEED", 1) ? (int)spl : 0;
+    p->seed_per_list = knob_or(knobs().ivf_seed, 1) ? (int)spl : 0;
     p->l = scan_layout(p->W, R);
     const size_t per_q = align_up((size_t)ix->K * 4, 256) + align_up((size_t)nprobe * 4, 256) +
                          align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
@@ -1056,9 +1056,9 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         // Scan: up to p.W workgroups per query, one per `upw` units of its lists (batches that fill
         // the GPU by their number alone), one per unit otherwise
         dim3 grid((unsigned)p.W * (unsigned)nb);
-        const int upw = nb >= 64 ? max(1, env_int("QADC_IVF_UNITS", 16)) : 1;
+        const int upw = nb >= 64 ? max(1, knob_or(knobs().ivf_units, 16)) : 1;
         // a few queries: their lists are sampled by several workgroups each
-        const int seed_parts_env = env_int("QADC_IVF_SEED_PARTS", 0);
+        const int seed_parts_env = knob_or(knobs().ivf_seed_parts, 0);
         const int seed_parts = seed_parts_env > 0 ? min(seed_parts_env, nprobe) : nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
         launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap);
 #define QADC_IVF_CASE(B_)                                                                              \

@@ -564,14 +564,14 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
     if (!(m == 8 || m == 16 || m == 32 || m == 64)) return false;
     if (n < 0 || n > 0xfffffffell || nq < 1 || R < 1 || R > QADC_MAX_R) return false;
     p->B = m / 2;
-    const int nt = env_int("QADC_SCAN_NT", 256);
+    const int nt = knob_or(knobs().scan_nt, 256);
     p->NT = (nt == 1024 || nt == 512) ? nt : 256;
     const int cpt = (p->B <= 16) ? SCAN_VEC * (16 / p->B) : 1;
     const int tile = p->NT * cpt;
     const int64_t tiles = n > 0 ? ceil_div(n, tile) : 1;
     // every workgroup takes tiles g, g+G, ...; its tiles must number below 2^24 / tile, the
     // range of the index bits of a candidate key
-    int64_t G = env_int("QADC_SCAN_WGS", 2048);
+    int64_t G = knob_or(knobs().scan_wgs, 2048);
     if (G < 1) G = 1;
     if (G > tiles) G = tiles;
     const int64_t max_tiles_per_wg = ((1ll << 24) - 1) / tile;
@@ -586,8 +586,8 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
     p->seed_wgs = 0;
     p->seed_stride = 0;
     p->flush_need = 16;
-    if (seed_tiles >= env_int("QADC_SEED_MIN_TILES", 64)) {
-        int64_t S = env_int("QADC_SEED_WGS", 0);
+    if (seed_tiles >= knob_or(knobs().seed_min_tiles, 64)) {
+        int64_t S = knob_or(knobs().seed_wgs, 0);
         if (S <= 0) {  // about 1/40 of the database, between 256 and 1024 tiles
             S = seed_tiles / 40;
             if (S < 256) S = 256;
@@ -602,7 +602,7 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
         if (fl > R) fl = R;
         p->flush_need = (unsigned)fl;
     }
-    p->tiled = p->seed_wgs > 0 && nq >= TILED_MIN_Q && env_int("QADC_TILED", 1) != 0 &&
+    p->tiled = p->seed_wgs > 0 && nq >= TILED_MIN_Q && knob_or(knobs().tiled, 1) != 0 &&
                make_tiled_plan(n, m, nq, !p->wide, &p->t);
     if (p->tiled && p->G > 256) p->G = 256;  // the single-query kernel only redoes rare queries
     const ScanLayout l = scan_layout(p->G, R);
@@ -642,7 +642,7 @@ static int dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
                             const uint8_t *qluts, int nq, int cap, int R, char *ws, hipStream_t st)
 {
     // batches that the query-tiled kernels scan are sampled in the query-tiled way too
-    if (p.tiled && nq >= TILED_MIN_Q && env_int("QADC_TILED_SEED", 1) != 0) {
+    if (p.tiled && nq >= TILED_MIN_Q && knob_or(knobs().tiled_seed, 1) != 0) {
         const int cpt = (p.B <= 16) ? SCAN_VEC * (16 / p.B) : 1;
         return run_tiled_seed(p.t, codes, n, qluts, nq, cap, R, p.wide ? 1 : 0, (int64_t)p.seed_wgs * 1024 * cpt,
                               ws, p.stride, st);

@@ -470,10 +470,16 @@ inline int scan_query_batch(size_t stride, int nq)
     return (int)qb;
 }
 
-inline int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    return (s && *s) ? atoi(s) : dflt;
-}
+// Tuning knobs: the QADC_* environment variables.  They change launch shapes and which of the
+// equivalent kernels runs, never a result.  An entry point reads them ONCE, when it is called
+// (knobs_refresh), into the calling thread's copy; everything below it uses that copy.  -1: not set.
+struct Knobs {
+    int scan_nt, scan_wgs, seed_min_tiles, seed_wgs, tiled, tiled_seed, scan_f32_wgs;
+    int tiled_mfma, mfma_min_q, mfma_min_q2, mfma_min_q4, mfma_waves;
+    int ivf_wgs, ivf_seed, ivf_units, ivf_seed_parts;
+};
+const Knobs &knobs();
+void knobs_refresh();
+inline int knob_or(int value, int dflt) { return value >= 0 ? value : dflt; }
 
 }  // namespace qadc

@@ -11,6 +11,8 @@
 // list that is cut back to its R smallest keys by an exact radix select whenever it fills.
 // A workgroup reports at most R keys; the merge kernel orders the R smallest of all of them.
 
+#include <mutex>
+
 #include <algorithm>
 
 #include "qadc_scan_common.h"
@@ -520,7 +522,7 @@ static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan 
     const int cpt = (p->ROW <= 16) ? SCAN_VEC * (16 / p->ROW) : 1;
     const int tile = F32_NT * cpt;
     const int64_t tiles = n > 0 ? ceil_div(n, tile) : 1;
-    int64_t G = env_int("QADC_SCAN_F32_WGS", 1024);
+    int64_t G = knob_or(knobs().scan_f32_wgs, 1024);
     if (G < 1) G = 1;
     if (G > tiles) G = tiles;
     const int64_t max_tiles_per_wg = 0xffffffffll / tile;
@@ -530,7 +532,7 @@ static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan 
     p->seed_wgs = 0;
     p->seed_stride = 0;
     p->flush_need = 16;
-    if (tiles >= env_int("QADC_SEED_MIN_TILES", 64) * 2) {
+    if (tiles >= knob_or(knobs().seed_min_tiles, 64) * 2) {
         int64_t S = tiles / 40;
         if (S < 256) S = 256;
         if (S > 1024) S = 1024;
@@ -548,7 +550,7 @@ static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan 
     p->GC = 0;
     p->chunk = 0;
     p->tiled_lds = (size_t)p->ROW * 256 * 2 * sizeof(float4);
-    if (p->KSUB == 256 && p->ROW <= 16 && p->seed_wgs > 0 && nq >= F32T_MIN_Q && env_int("QADC_TILED", 1) != 0) {
+    if (p->KSUB == 256 && p->ROW <= 16 && p->seed_wgs > 0 && nq >= F32T_MIN_Q && knob_or(knobs().tiled, 1) != 0) {
         const int64_t groups = ceil_div(nq, F32T_Q);
         const int64_t want = std::max<int64_t>(1, std::min<int64_t>(F32T_MAX_CHUNKS, ceil_div(1024, groups)));
         int64_t chunk = ceil_div(ceil_div(n, F32T_MAX_CHUNKS), tile) * tile;
@@ -586,12 +588,13 @@ static int launch_f32_tiled(const F32Plan &p, const uint8_t *codes, int64_t n, c
                             const F32Range *ranges, char *ws, unsigned *flags, hipStream_t st)
 {
     if constexpr (ROW <= 16) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_f32_tiled_kernel<ROW>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.tiled_lds));
-            attr_set = true;
-        }
+        static std::once_flag attr_once;  // the kernel may use more dynamic LDS than the default limit
+        hipError_t attr_rc = hipSuccess;
+        std::call_once(attr_once, [&] {
+            attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_f32_tiled_kernel<ROW>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.tiled_lds);  // fixed by ROW
+        });
+        QADC_HIP_TRY(attr_rc);
         const unsigned gc8 = (unsigned)ceil_div(p.GC, 8) * 8u;  // chunk slots, eight at a time
         dim3 grid((unsigned)ceil_div(nq, F32T_Q) * gc8);
         launch(QADC_PROF_SCAN, scan_f32_tiled_kernel<ROW>, grid, dim3(F32_NT), p.tiled_lds, st, codes, n, p.chunk,

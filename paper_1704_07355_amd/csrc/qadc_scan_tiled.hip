@@ -17,6 +17,8 @@
 // list that overflows marks its query for the single-query kernel, which redoes that query
 // alone with its exact machinery; the merge kernel takes whichever result is valid.
 
+#include <mutex>
+
 #include "qadc_scan_common.h"
 #include <algorithm>
 
@@ -361,13 +363,13 @@ __global__ __launch_bounds__(tiled_nt(B)) void scan_u8_tiled16_kernel(
 // queries per wavefront
 static int mfma_min_q(int B)
 {
-    return std::max(1, env_int("QADC_MFMA_MIN_Q", B >= 8 ? TILED_MFMA_MIN_Q : 2 * TILED_MFMA_MIN_Q));
+    return std::max(1, knob_or(knobs().mfma_min_q, B >= 8 ? TILED_MFMA_MIN_Q : 2 * TILED_MFMA_MIN_Q));
 }
-static int mfma_min_q2() { return std::max(1, env_int("QADC_MFMA_MIN_Q2", TILED_MFMA_MIN_Q2)); }
+static int mfma_min_q2() { return std::max(1, knob_or(knobs().mfma_min_q2, TILED_MFMA_MIN_Q2)); }
 // 128 queries per wavefront (codes of up to 8 bytes): when the last set of 128 is more than half full
 static bool mfma_four(int B, int nq)
 {
-    const int min_q4 = std::max(1, env_int("QADC_MFMA_MIN_Q4", TILED_MFMA_MIN_Q4));
+    const int min_q4 = std::max(1, knob_or(knobs().mfma_min_q4, TILED_MFMA_MIN_Q4));
     return B <= 8 && nq >= min_q4 && ((nq & 127) == 0 || (nq & 127) > 64);
 }
 
@@ -378,7 +380,7 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
     const int tile = tiled_nt(t->B) * cpt;
     // 4-bit codes and a batch that fills a good part of a wavefront's 32 or 64 queries: the
     // matrix-core kernel scans it
-    t->mfma = codes4 && nq >= mfma_min_q(t->B) && env_int("QADC_TILED_MFMA", 1) != 0;
+    t->mfma = codes4 && nq >= mfma_min_q(t->B) && knob_or(knobs().tiled_mfma, 1) != 0;
     // chunks: at most TILED_MAX_CHUNKS per query, a multiple of the tile, below 2^24 codes (index
     // bits of a key); as long as possible (a workgroup builds its tables once per chunk) while
     // groups x chunks still make about four workgroups per compute unit: 64 tiles with many query
@@ -399,7 +401,7 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
         // never fewer than 512 chunks, however many sets of queries there are: a query's few
         // thousand candidates must stay well below the 64 (or 32) keys a wavefront can report per
         // query and chunk, or queries overflow and are redone one by one
-        want = std::max<int64_t>(512, ceil_div(std::max(64, env_int("QADC_MFMA_WAVES", 4096)), ceil_div(nq, qw)));
+        want = std::max<int64_t>(512, ceil_div(std::max(64, knob_or(knobs().mfma_waves, 4096)), ceil_div(nq, qw)));
         want = std::min<int64_t>(max_chunks, want);
         lo = 2;
         hi = 1ll << 40;
@@ -654,14 +656,16 @@ static int launch_tiled(const TiledPlan &t, const uint8_t *codes, int64_t n, int
                         const unsigned *taus, char *ws, size_t ws_stride, size_t countsA_off,
                         size_t listsA_off, unsigned *flags, hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_u8_tiled_kernel<B>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes));
-        QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_u8_tiled16_kernel<B, TILED16_GP>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes));
-        attr_set = true;
-    }
+    static std::once_flag attr_once;  // the kernels use more dynamic LDS than the default limit (size fixed by B)
+    hipError_t attr_rc = hipSuccess;
+    std::call_once(attr_once, [&] {
+        attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_u8_tiled_kernel<B>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes);
+        if (attr_rc == hipSuccess)
+            attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_u8_tiled16_kernel<B, TILED16_GP>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes);
+    });
+    QADC_HIP_TRY(attr_rc);
     // every group of 16 queries is scanned by exactly one of the two kernels
     const unsigned gc8 = (unsigned)ceil_div(t.GC, 8) * 8u;  // chunk slots, eight at a time
     dim3 grid16((unsigned)ceil_div(nq, 16) * gc8);
@@ -813,12 +817,13 @@ static int launch_tiled_seed(const TiledPlan &t, const uint8_t *codes, int64_t n
                              int cap, int R, int wide, int64_t sample_codes, char *ws, size_t ws_stride,
                              hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        QADC_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&seed_u8_tiled_kernel<B>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes));
-        attr_set = true;
-    }
+    static std::once_flag attr_once;
+    hipError_t attr_rc = hipSuccess;
+    std::call_once(attr_once, [&] {
+        attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(&seed_u8_tiled_kernel<B>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)t.lds_bytes);
+    });
+    QADC_HIP_TRY(attr_rc);
     constexpr int cpt = (B <= 16) ? SCAN_VEC * (16 / B) : 1;
     const int64_t tile = (int64_t)tiled_nt(B) * cpt;
     int64_t n_tiles = std::max<int64_t>(1, sample_codes / tile);

@@ -5,7 +5,7 @@
 
 #include <mutex>
 
-#include "qadc_common.h"
+#include "qadc_scan_common.h"
 
 namespace qadc {
 
@@ -41,6 +41,7 @@ int search_static(const float *codebooks, int d, int m, const float *queries, in
                   const uint8_t *codes, int64_t n, int R, int init, int nbins, int qmin_mode,
                   uint32_t *out_idx, uint8_t *out_dist, uint8_t *qluts_out, hipStream_t st)
 {
+    knobs_refresh();
     if (nq < 0) return fail(QADC_EINVAL, "qadc_search_static: nq=%d", nq);
     if (nq == 0) return QADC_OK;
     // the largest number of queries per launch sequence whose scratch fits the array
