@@ -99,6 +99,19 @@ def scan_topk_u8_bytes(codes, qluts, R, cap=255):
     return idx, dist
 
 
+def scan_topk_u8_sixbit(codes, qluts, R, cap=255):
+    """6-bit codes uint8 [n][3m/4], quantized tables uint8 [nq][m][64] -> (idx, dist)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    qluts = np.ascontiguousarray(qluts, dtype=np.uint8)
+    nq, m, k = qluts.shape
+    assert k == 64 and codes.shape[1] == 3 * m // 4
+    idx = np.empty((nq, R), dtype=np.uint32)
+    dist = np.empty((nq, R), dtype=np.uint8)
+    lib().ref_scan_topk_u8_sixbit(_p(codes), ctypes.c_int64(len(codes)), m, _p(qluts), nq, cap, R,
+                                  _p(idx), _p(dist))
+    return idx, dist
+
+
 def scan_topk_f32(codes, luts, R):
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     luts = np.ascontiguousarray(luts, dtype=np.float32)

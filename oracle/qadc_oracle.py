@@ -44,6 +44,12 @@ listed in the design notes of the repository):
   * Inverted index with several probed cells: one quantizer per query, shared
     by all probed cells; ties are broken by storage position in the
     concatenated lists.
+  * 6-bit sub-quantizers (named in the Conclusion as what wider registers buy,
+    without a layout): the m six-bit components of a code are stored back to
+    back, least significant bit first -- component j is bits 6j .. 6j+5 of the
+    code read as one little-endian number, so four components fill three
+    bytes; tables have 64 entries; quantization and saturating sums as for
+    4-bit components.
 
 Pins (tests/test_oracle_*.py): Eq. (1) against scipy cdist; encode against the
 argmin of the same; Eq. (2) against Eq. (3) by brute force; centroid-tuple
@@ -236,6 +242,63 @@ def unpack_nibbles(codes: np.ndarray) -> np.ndarray:
     comps[:, 0::2] = codes & 0x0F
     comps[:, 1::2] = codes >> 4
     return comps
+
+
+# --------------------------------------------------------------------------
+# 6-bit components (Conclusion): four components per three bytes
+# --------------------------------------------------------------------------
+
+def pack_sixbit(comps: np.ndarray) -> np.ndarray:
+    """uint8 [n][m] (values < 64, m a multiple of 4) -> uint8 [n][3m/4].
+
+    The code is the number sum_j c[j] << 6j written in little-endian bytes.
+    """
+    comps = np.asarray(comps, dtype=np.uint8)
+    n, m = comps.shape
+    assert m % 4 == 0 and comps.max(initial=0) < 64
+    out = np.zeros((n, 3 * m // 4), dtype=np.uint8)
+    for j in range(m):
+        for b in range(6):  # bit b of component j is bit 6j + b of the code
+            bit = 6 * j + b
+            out[:, bit // 8] |= (((comps[:, j] >> b) & 1) << (bit % 8)).astype(np.uint8)
+    return out
+
+
+def unpack_sixbit(codes: np.ndarray) -> np.ndarray:
+    """Inverse of pack_sixbit: uint8 [n][3m/4] -> uint8 [n][m]."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    n, nbytes = codes.shape
+    assert nbytes % 3 == 0
+    m = nbytes * 4 // 3
+    comps = np.zeros((n, m), dtype=np.uint8)
+    for j in range(m):
+        for b in range(6):
+            bit = 6 * j + b
+            comps[:, j] |= (((codes[:, bit // 8] >> (bit % 8)) & 1) << b).astype(np.uint8)
+    return comps
+
+
+def scan_saturating_sixbit(qlut: np.ndarray, codes: np.ndarray, nbins: int = 255) -> np.ndarray:
+    """The chain of Alg. 2 for 6-bit components: component j -> 64-entry table j, saturating add.
+    qlut uint8 [m][64], codes uint8 [n][3m/4] (pack_sixbit)."""
+    comps = unpack_sixbit(codes)
+    acc = np.zeros(len(codes), dtype=np.int64)
+    for j in range(qlut.shape[0]):
+        acc = np.minimum(nbins, acc + qlut[j][comps[:, j]])
+    return acc.astype(np.uint8)
+
+
+def quick_adc_sixbit_search(codebooks, query, codes, init, R, nbins=255, qmin_mode=QMIN_PER_TABLE):
+    """Quick ADC with 6-bit sub-quantizers: Tables (Eq. 1, [m][64]), qmax from the first `init`
+    codes (Section 3.3), the quantizer, saturating scan, top-R.  codes uint8 [n][3m/4]."""
+    lut = build_luts(codebooks, query[None, :])[0]
+    comps = unpack_sixbit(codes)
+    qmax = qmax_from_init(lut, comps[:min(init, len(comps))], R)
+    bias, delta = quantizer_params(lut, qmax, nbins, qmin_mode)
+    qlut = quantize_luts(lut, bias, delta, nbins)
+    sums = scan_saturating_sixbit(qlut, codes, nbins)
+    idx, dist = top_r(sums, R, pad_dist=nbins)
+    return dict(lut=lut, qmax=qmax, bias=bias, delta=delta, qlut=qlut, idx=idx, dist=dist)
 
 
 # --------------------------------------------------------------------------

@@ -87,6 +87,28 @@ static inline unsigned qadc_one(const uint8_t *code, int m, const uint8_t *qlut,
     return acc;
 }
 
+/* The same chain for 6-bit components: component j is bits 6j .. 6j+5 of the code read as a
+ * little-endian number; one 64-entry table per component. */
+static inline unsigned sixbit_at(const uint8_t *code, int j)
+{
+    unsigned c = 0;
+    for (int b = 0; b < 6; ++b) {
+        const int bit = 6 * j + b;
+        c |= ((code[bit >> 3] >> (bit & 7)) & 1u) << b;
+    }
+    return c;
+}
+
+static inline unsigned qadc_one_sixbit(const uint8_t *code, int m, const uint8_t *qlut, unsigned cap)
+{
+    unsigned acc = 0;
+    for (int j = 0; j < m; ++j) {
+        acc += qlut[j * 64 + sixbit_at(code, j)];
+        if (acc > cap) acc = cap;
+    }
+    return acc;
+}
+
 /* The same chain for 8-bit components (one byte, one 256-entry table per component). */
 static inline unsigned qadc_one_bytes(const uint8_t *code, int m, const uint8_t *qlut, unsigned cap)
 {
@@ -205,6 +227,29 @@ void ref_scan_topk_u8_bytes(const uint8_t *codes, int64_t n, int m, const uint8_
         const uint8_t *qlut = qluts + (size_t)q * m * 256;
         for (int64_t i = 0; i < n; ++i) {
             pair_t p = { (double)qadc_one_bytes(codes + i * m, m, qlut, (unsigned)cap), i };
+            heap_push(h, &len, R, p);
+        }
+        qsort(h, (size_t)len, sizeof(pair_t), pair_cmp);
+        for (int r = 0; r < R; ++r) {
+            out_idx[(size_t)q * R + r] = r < len ? (uint32_t)h[r].i : 0xFFFFFFFFu;
+            out_dist[(size_t)q * R + r] = r < len ? (uint8_t)h[r].d : (uint8_t)cap;
+        }
+        free(h);
+    }
+}
+
+/* Saturating scan of 6-bit codes [n][3m/4] with quantized tables qluts [nq][m][64]. */
+void ref_scan_topk_u8_sixbit(const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, int nq,
+                             int cap, int R, uint32_t *out_idx, uint8_t *out_dist)
+{
+    const int nbytes = 3 * m / 4;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < nq; ++q) {
+        pair_t *h = (pair_t *)malloc(sizeof(pair_t) * (size_t)R);
+        int len = 0;
+        const uint8_t *qlut = qluts + (size_t)q * m * 64;
+        for (int64_t i = 0; i < n; ++i) {
+            pair_t p = { (double)qadc_one_sixbit(codes + i * nbytes, m, qlut, (unsigned)cap), i };
             heap_push(h, &len, R, p);
         }
         qsort(h, (size_t)len, sizeof(pair_t), pair_cmp);
