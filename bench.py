@@ -479,8 +479,10 @@ def run_compare(args):
     train = mixture_vectors_torch(spec, SEED_TRAIN, 0, 20_000, dev)
     cb8 = Q.qadc_pq_train(train, 8, 256, torch.from_numpy(kmeans_init_rows(20_000, 256)).to(dev), 10)
     cb4 = Q.qadc_pq_train(train, 16, 16, torch.from_numpy(kmeans_init_rows(20_000, 16)).to(dev), 10)
+    cb6 = Q.qadc_pq_train(train, 16, 64, torch.from_numpy(kmeans_init_rows(20_000, 64)).to(dev), 10)
     codes8 = torch.empty((n, 8), dtype=torch.uint8, device=dev)
     codes4 = torch.empty((n, 8), dtype=torch.uint8, device=dev)
+    codes6 = torch.empty((n, 12), dtype=torch.uint8, device=dev)  # m = 16 x 6-bit: 96-bit codes
     keep = args.recall_queries > 0
     raw = torch.empty((n, spec.d), dtype=torch.float32, device=dev) if keep else None
     chunk = 4 * BLOCK
@@ -489,6 +491,7 @@ def run_compare(args):
         x = mixture_vectors_torch(spec, SEED_BASE, s, cnt, dev)
         Q.qadc_pq_encode(cb8, x, out=codes8[s:s + cnt])
         Q.qadc_pq_encode(cb4, x, out=codes4[s:s + cnt])
+        Q.qadc_pq_encode(cb6, x, out=codes6[s:s + cnt])
         if keep:
             raw[s:s + cnt] = x
     queries = mixture_vectors_torch(spec, SEED_QUERY, 0, args.queries, dev)
@@ -527,6 +530,19 @@ def run_compare(args):
         ql, _, _, _ = Q.qadc_quantize_luts(luts8, codes8[:init], R)
         Q.qadc_scan_topk(Q.QADC_U8_8BIT, codes8, ql, R, workspace=wsq, out_idx=idxq, out_dist=distq)
 
+    # 6-bit sub-quantizers (the paper's Conclusion): m = 16 x 64 centroids, 64-entry uint8 tables
+    ws6 = Q.qadc_workspace_init(torch.empty(Q.qadc_workspace_bytes(Q.QADC_WS_SCAN_U8_6BIT, n, 16, 1, R),
+                                            dtype=torch.uint8, device=dev))
+    luts6 = torch.empty((1, 16, 64), dtype=torch.float32, device=dev)
+    idx6 = torch.empty((1, R), dtype=torch.int32, device=dev)
+    dist6 = torch.empty((1, R), dtype=torch.uint8, device=dev)
+
+    def pq6_u8(i):
+        qi = i % args.queries
+        Q.qadc_build_luts(cb6, queries[qi:qi + 1], out=luts6)
+        ql, _, _, _ = Q.qadc_quantize_luts(luts6, codes6[:init], R)
+        Q.qadc_scan_topk(Q.QADC_U8_6BIT, codes6, ql, R, workspace=ws6, out_idx=idx6, out_dist=dist6)
+
     def timed(fn):
         for i in range(args.warmup):
             fn(i)
@@ -542,6 +558,7 @@ def run_compare(args):
     ms4 = timed(quick)
     ms8 = timed(pq8)
     ms8q = timed(pq8_u8)
+    ms6 = timed(pq6_u8)
 
     # the same comparison on batches of 256 queries (one call each): both share code reads between
     # queries (query-tiled kernels: 16 queries per LDS read for the uint8 tables, 8 queries per two
@@ -573,7 +590,8 @@ def run_compare(args):
     if not args.no_profile:
         nprof = min(args.steps, 200)
         per = {}
-        for name, fn in (("quick_adc", quick), ("pq8_float", pq8), ("pq8_uint8_tables", pq8_u8)):
+        for name, fn in (("quick_adc", quick), ("pq8_float", pq8), ("pq8_uint8_tables", pq8_u8),
+                         ("pq6_uint8_tables", pq6_u8)):
             Q.qadc_profile_enable(True)
             for i in range(nprof):
                 fn(i)
@@ -597,7 +615,11 @@ def run_compare(args):
                     "avg_kernel_us": us, "bytes_per_launch": n * 8, "launches_timed": nprof,
                     "pq8_float_scan_kernel": {"avg_kernel_us": us8,
                                               "achieved": round(n * 8 / (us8 * 1e-6) / 1e9, 1),
-                                              "frac": round(n * 8 / (us8 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}}
+                                              "frac": round(n * 8 / (us8 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
+                    "pq6_uint8_scan_kernel": {"avg_kernel_us": per["pq6_uint8_tables"]["scan_us_per_query"],
+                                              "bytes_per_launch": n * 12,
+                                              "achieved": round(n * 12 / (per["pq6_uint8_tables"]["scan_us_per_query"] * 1e-6) / 1e9, 1),
+                                              "frac": round(n * 12 / (per["pq6_uint8_tables"]["scan_us_per_query"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}}
 
     acc = None
     if keep:
@@ -608,6 +630,8 @@ def run_compare(args):
         l8 = Q.qadc_build_luts(cb8, qs)
         i8, _ = Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, l8, R)
         i8q, _ = Q.qadc_scan_topk(Q.QADC_U8_8BIT, codes8, Q.qadc_quantize_luts(l8, codes8[:init], R)[0], R)
+        i6q, _ = Q.qadc_scan_topk(Q.QADC_U8_6BIT, codes6,
+                                  Q.qadc_quantize_luts(Q.qadc_build_luts(cb6, qs), codes6[:init], R)[0], R)
         best = torch.full((nq,), float("inf"), device=dev)
         arg = torch.zeros((nq,), dtype=torch.int64, device=dev)
         qq = (qs * qs).sum(1)
@@ -621,7 +645,7 @@ def run_compare(args):
         torch.cuda.synchronize()
         nn = arg.cpu().numpy()
         h = {k: v.cpu().numpy().view(np.uint32).astype(np.int64)
-             for k, v in (("q", i4), ("f4", f4), ("f8", i8), ("q8", i8q))}
+             for k, v in (("q", i4), ("f4", f4), ("f8", i8), ("q8", i8q), ("q6", i6q))}
         rec = {k: float(np.mean([nn[i] in h[k][i] for i in range(nq)])) for k in h}
         ov = float(np.mean([len(np.intersect1d(a, b)) / R for a, b in zip(h["q"], h["f4"])]))
         ov8 = float(np.mean([len(np.intersect1d(a, b)) / R for a, b in zip(h["q8"], h["f8"])]))
@@ -629,6 +653,7 @@ def run_compare(args):
                "nn_recall_at_R_float_adc_4bit_codes": round(rec["f4"], 4),
                "nn_recall_at_R_pq8_float": round(rec["f8"], 4),
                "nn_recall_at_R_pq8_uint8_tables": round(rec["q8"], 4),
+               "nn_recall_at_R_pq6_uint8_tables_96bit": round(rec["q6"], 4),
                "overlap_at_R_quick_vs_float_adc_same_codes": round(ov, 4),
                "overlap_at_R_pq8_uint8_tables_vs_pq8_float": round(ov8, 4),
                "note": "NN-recall = exact nearest neighbour (raw vectors) among the R returned, the paper's "
@@ -666,6 +691,10 @@ def run_compare(args):
                              "note": "the 8-bit codes scanned with their 256-entry tables quantized as in "
                                      "Section 3.3 (qadc_build_luts + qadc_quantize_luts_8bit + qadc_scan_topk "
                                      "QADC_U8_8BIT, three calls per query)"},
+        "pq6_uint8_tables": {"ms_per_query": round(ms6, 5), "gcodes_per_s": round(n / (ms6 * 1e-3) / 1e9, 2),
+                             "note": "the same vectors as m=16 x 6-bit codes (96 bits, four components per three "
+                                     "bytes) with 64-entry uint8 tables: qadc_build_luts + qadc_quantize_luts_6bit + "
+                                     "qadc_scan_topk QADC_U8_6BIT, three calls per query"},
         "speedup_quick_adc_over_pq8_float": round(ms8 / ms4, 3),
         "batches_of_256": batched,
         "roofline": roofline, "kernels": kernels, "accuracy": acc, "cpu_baseline": cpu,

@@ -66,6 +66,7 @@ extern "C" {
 #define QADC_F32_4BIT   1 /* Alg. 1: 4-bit codes, float tables, float32 sums         */
 #define QADC_F32_8BIT   2 /* Alg. 1: 8-bit codes (ksub = 256), float tables          */
 #define QADC_U8_8BIT    3 /* Alg. 2's sums with 8-bit codes: uint8 tables of 256 entries */
+#define QADC_U8_6BIT    4 /* Alg. 2's sums with 6-bit codes: uint8 tables of 64 entries  */
 
 /* which call a workspace is for (qadc_workspace_bytes) */
 #define QADC_WS_SCAN_TOPK      0 /* qadc_scan_topk, variant QADC_U8_4BIT  */
@@ -73,13 +74,14 @@ extern "C" {
 #define QADC_WS_SCAN_F32_8BIT  2 /* qadc_scan_topk, variant QADC_F32_8BIT */
 #define QADC_WS_SEARCH         3 /* qadc_search */
 #define QADC_WS_SCAN_U8_8BIT   4 /* qadc_scan_topk, variant QADC_U8_8BIT  */
+#define QADC_WS_SCAN_U8_6BIT   5 /* qadc_scan_topk, variant QADC_U8_6BIT  */
 
 /*
  * Tables step, Eq. (1) of the paper:
  *     luts[q][j][i] = || y'_q^j - codebooks[j][i] ||^2 ,  y'_q = queries[q] - base[q]
  * for j < m sub-spaces of d/m dimensions and i < ksub centroids.  Differences and
  * their squares are summed in float64 (no norm expansion) and rounded once to float32.
- *   codebooks [m][ksub][d/m] f32   ksub in {16, 256}; d % m == 0
+ *   codebooks [m][ksub][d/m] f32   ksub in {16, 64, 256}; d % m == 0
  *   queries   [nq][d] f32
  *   base      [nq][d] f32 or NULL   (NULL: exhaustive search, y' = y;  else the
  *             centroid of the probed cell, Section 2.3 "Index")
@@ -133,6 +135,23 @@ int qadc_quantize_luts_8bit(const float *luts, int nq, int ngroup, int m,
                             void *stream);
 
 /*
+ * The same quantizer for 6-bit components: 64 centroids per sub-quantizer, which the paper's
+ * Conclusion names as what registers of 512 bits would allow (a 64-entry table of bytes fills
+ * one).  The paper gives no layout; here the m components of a code are stored back to back,
+ * least significant bit first: component j is bits 6j .. 6j+5 of the code read as one
+ * little-endian number, so four components fill three bytes and a code has 3m/4 bytes.
+ * Section 3.3's quantization and Alg. 2's saturating sums apply unchanged (scan variant
+ * QADC_U8_6BIT); codes come from qadc_pq_encode with ksub = 64, tables from qadc_build_luts.
+ *   luts [nq][ngroup][m][64] f32;  init_codes [n_init][3m/4] u8;  m in {8, 16, 32}
+ *   qluts [nq][ngroup][m][64] u8 (output);  everything else as qadc_quantize_luts
+ */
+int qadc_quantize_luts_6bit(const float *luts, int nq, int ngroup, int m,
+                            const uint8_t *init_codes, int64_t n_init, const float *qmax_in,
+                            int R, int nbins, int qmin_mode,
+                            uint8_t *qluts, float *bias, float *delta, float *qmax_out,
+                            void *stream);
+
+/*
  * Scan step + top-R (Alg. 1 / Alg. 2).  For every query q and code i < n:
  *   QADC_U8_4BIT   dist = min(nbins, sum_j luts_u8[q][j][c_i[j]])   (equal to the chain of
  *                  saturating adds of Alg. 2, entries being non-negative)
@@ -140,10 +159,12 @@ int qadc_quantize_luts_8bit(const float *luts, int nq, int ngroup, int m,
  *   QADC_F32_8BIT  same with one byte per component and 256-entry tables
  *   QADC_U8_8BIT   dist = min(nbins, sum_j luts_u8[q][j][c_i[j]]) with one byte per component
  *                  and 256-entry uint8 tables (see qadc_quantize_luts_8bit)
+ *   QADC_U8_6BIT   the same with 6-bit components, four per three bytes, and 64-entry uint8
+ *                  tables (see qadc_quantize_luts_6bit); m in {8, 16, 32}; one scan per query
  * and the R smallest (dist, i) are written in ascending order.
- *   codes    [n][m/2] u8 (4-bit variants) or [n][m] u8 (8-bit), standard layout
+ *   codes    [n][m/2] u8 (4-bit variants), [n][m] u8 (8-bit) or [n][3m/4] u8 (6-bit), standard layout
  *   m        4-bit variants: 8, 16, 32 or 64;  8-bit variants: 4, 8, 16 or 32
- *   luts     [nq][m][16] u8, [nq][m][16] f32, [nq][m][256] f32 or [nq][m][256] u8 by variant
+ *   luts     [nq][m][16] u8, [nq][m][16] f32, [nq][m][256] f32, [nq][m][256] u8 or [nq][m][64] u8 by variant
  *            (4-byte aligned; batches of 16-entry u8 tables that are 16-byte aligned can be
  *            scanned by the matrix-core kernel, others take the vector kernels -- same results;
  *            float tables are expected non-negative, as squared distances are)
@@ -244,9 +265,11 @@ size_t qadc_ivf_workspace_bytes(const qadc_ivf_index *ix, int nq, int nprobe, in
  * sub-quantizer j closest to sub-vector x^j (float64 distances from the differences, summed in
  * increasing component order; ties to the lowest index), written in the standard layout.  Not on the query
  * path; it exists to build large databases directly in HBM.
- *   codebooks [m][ksub][d/m] f32, ksub in {16, 256} (m even when ksub == 16)
+ *   codebooks [m][ksub][d/m] f32, ksub in {16, 64, 256} (m even when ksub == 16, a multiple of 4
+ *             when ksub == 64)
  *   x         [n][d] f32
- *   codes     [n][m/2] u8 (ksub 16) or [n][m] u8 (ksub 256)   (output)
+ *   codes     [n][m/2] u8 (ksub 16), [n][3m/4] u8 (ksub 64: components back to back, least
+ *             significant bit first) or [n][m] u8 (ksub 256)   (output)
  */
 int qadc_pq_encode(const float *codebooks, int d, int m, int ksub, const float *x, int64_t n,
                    uint8_t *codes, void *stream);

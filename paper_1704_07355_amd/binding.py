@@ -20,14 +20,15 @@ QADC_OK, QADC_EINVAL, QADC_ENOMEM, QADC_EHIP = 0, -1, -2, -3
 QADC_MAX_R = 1024
 QADC_MAX_INIT = 8192
 QADC_QMIN_PER_TABLE, QADC_QMIN_GLOBAL = 0, 1
-QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT, QADC_U8_8BIT = 0, 1, 2, 3
+QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT, QADC_U8_8BIT, QADC_U8_6BIT = 0, 1, 2, 3, 4
 QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT, QADC_WS_SEARCH, QADC_WS_SCAN_U8_8BIT = 0, 1, 2, 3, 4
+QADC_WS_SCAN_U8_6BIT = 5
 (QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES,
  QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE, QADC_PROF_ROTATE) = range(9)
 QADC_LAYOUT_STANDARD, QADC_LAYOUT_TRANSPOSED = 0, 1
 
 EXPORTS = (
-    "qadc_build_luts", "qadc_quantize_luts", "qadc_quantize_luts_8bit", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
+    "qadc_build_luts", "qadc_quantize_luts", "qadc_quantize_luts_8bit", "qadc_quantize_luts_6bit", "qadc_scan_topk", "qadc_search", "qadc_ivf_search",
     "qadc_ivf_workspace_bytes", "qadc_pq_encode", "qadc_pq_train", "qadc_rotate",
     "qadc_profile_enable", "qadc_profile_only", "qadc_profile_read", "qadc_workspace_bytes", "qadc_workspace_init",
     "qadc_last_error", "qadc_version", "qadc_packed_bytes", "qadc_pack_codes", "qadc_unpack_codes",
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.qadc_quantize_luts.restype = i32
         L.qadc_quantize_luts_8bit.argtypes = L.qadc_quantize_luts.argtypes
         L.qadc_quantize_luts_8bit.restype = i32
+        L.qadc_quantize_luts_6bit.argtypes = L.qadc_quantize_luts.argtypes
+        L.qadc_quantize_luts_6bit.restype = i32
         L.qadc_scan_topk.argtypes = [i32, vp, i64, i32, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.qadc_scan_topk.restype = i32
         L.qadc_search.argtypes = [vp, i32, i32, vp, i32, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -176,7 +179,8 @@ def qadc_build_luts(codebooks, queries, base=None, out=None):
 
 def qadc_quantize_luts(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_TABLE, qmax_in=None):
     """luts f32 [nq][m][k] or [nq][ngroup][m][k], k = 16 (init_codes u8 [n_init][m/2] | None) or
-    k = 256 (8-bit components, init_codes u8 [n_init][m] | None: qadc_quantize_luts_8bit).
+    k = 256 (8-bit components, init_codes u8 [n_init][m] | None: qadc_quantize_luts_8bit) or k = 64
+    (6-bit components, init_codes u8 [n_init][3m/4] | None: qadc_quantize_luts_6bit).
 
     Returns (qluts u8 like luts, bias f32 [nq][m], delta f32 [nq], qmax f32 [nq]).
     """
@@ -185,9 +189,9 @@ def qadc_quantize_luts(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_T
         ngroup = 1
     else:
         nq, ngroup, m, k = luts.shape
-    if k not in (16, 256):
-        raise ValueError("tables of 16 or 256 entries expected")
-    fn = lib().qadc_quantize_luts if k == 16 else lib().qadc_quantize_luts_8bit
+    if k not in (16, 64, 256):
+        raise ValueError("tables of 16, 64 or 256 entries expected")
+    fn = {16: lib().qadc_quantize_luts, 64: lib().qadc_quantize_luts_6bit, 256: lib().qadc_quantize_luts_8bit}[k]
     dev = luts.device
     qluts = torch.empty(luts.shape, dtype=torch.uint8, device=dev)
     bias = torch.empty((nq, m), dtype=torch.float32, device=dev)
@@ -208,6 +212,14 @@ def qadc_quantize_luts_8bit(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_
     return qadc_quantize_luts(luts, init_codes, R, nbins, qmin_mode, qmax_in)
 
 
+def qadc_quantize_luts_6bit(luts, init_codes, R, nbins=255, qmin_mode=QADC_QMIN_PER_TABLE, qmax_in=None):
+    """qadc_quantize_luts for 64-entry tables: luts f32 [nq][m][64] or [nq][ngroup][m][64], init_codes
+    u8 [n_init][3m/4] | None."""
+    if luts.shape[-1] != 64:
+        raise ValueError("tables of 64 entries expected")
+    return qadc_quantize_luts(luts, init_codes, R, nbins, qmin_mode, qmax_in)
+
+
 def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=None, out_dist=None,
                    n=None):
     """codes u8 [n][row]; luts [nq][m][ksub] (u8 or f32 by variant) -> (idx i64-viewable u32 [nq][R], dist)."""
@@ -215,7 +227,7 @@ def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=N
     if n is None:
         n = codes.shape[0]
     dev = luts.device
-    want = torch.uint8 if variant in (QADC_U8_4BIT, QADC_U8_8BIT) else torch.float32
+    want = torch.uint8 if variant in (QADC_U8_4BIT, QADC_U8_8BIT, QADC_U8_6BIT) else torch.float32
     if luts.dtype != want:
         raise ValueError(f"variant {variant} needs {want} tables")
     if out_idx is None:
@@ -224,7 +236,8 @@ def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=N
         out_dist = torch.empty((nq, R), dtype=want, device=dev)
     need = qadc_workspace_bytes({QADC_U8_4BIT: QADC_WS_SCAN_TOPK, QADC_F32_4BIT: QADC_WS_SCAN_F32_4BIT,
                                  QADC_F32_8BIT: QADC_WS_SCAN_F32_8BIT,
-                                 QADC_U8_8BIT: QADC_WS_SCAN_U8_8BIT}[variant], n, m, nq, R)
+                                 QADC_U8_8BIT: QADC_WS_SCAN_U8_8BIT,
+                                 QADC_U8_6BIT: QADC_WS_SCAN_U8_6BIT}[variant], n, m, nq, R)
     if workspace is None:
         workspace = qadc_workspace_init(torch.empty((max(need, 256),), dtype=torch.uint8, device=dev))
     _check(lib().qadc_scan_topk(variant, _ptr(codes, torch.uint8), n, m, _ptr(luts), nq, R, nbins,
@@ -234,10 +247,11 @@ def qadc_scan_topk(variant, codes, luts, R, nbins=255, workspace=None, out_idx=N
 
 
 def qadc_pq_encode(codebooks, x, out=None):
-    """codebooks f32 [m][ksub][dsub], x f32 [n][d] -> codes u8 [n][m/2] (ksub 16) or [n][m] (ksub 256)."""
+    """codebooks f32 [m][ksub][dsub], x f32 [n][d] -> codes u8 [n][m/2] (ksub 16), [n][3m/4] (ksub 64)
+    or [n][m] (ksub 256)."""
     m, ksub, dsub = codebooks.shape
     n, d = x.shape
-    row = m // 2 if ksub == 16 else m
+    row = m // 2 if ksub == 16 else 3 * m // 4 if ksub == 64 else m
     if out is None:
         out = torch.empty((n, row), dtype=torch.uint8, device=x.device)
     _check(lib().qadc_pq_encode(_ptr(codebooks, torch.float32), d, m, ksub, _ptr(x, torch.float32),

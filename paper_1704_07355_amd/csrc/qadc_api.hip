@@ -115,6 +115,14 @@ int qadc_quantize_luts_8bit(const float *luts, int nq, int ngroup, int m, const 
                                qmin_mode, qluts, bias, delta, qmax_out, (hipStream_t)stream);
 }
 
+int qadc_quantize_luts_6bit(const float *luts, int nq, int ngroup, int m, const uint8_t *init_codes,
+                            int64_t n_init, const float *qmax_in, int R, int nbins, int qmin_mode,
+                            uint8_t *qluts, float *bias, float *delta, float *qmax_out, void *stream)
+{
+    return qadc::quantize_luts(64, luts, nq, ngroup, m, init_codes, n_init, qmax_in, R, nbins,
+                               qmin_mode, qluts, bias, delta, qmax_out, (hipStream_t)stream);
+}
+
 int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void *luts, int nq,
                    int R, int nbins, uint32_t *out_idx, void *out_dist, void *workspace,
                    size_t workspace_bytes, void *stream)
@@ -126,6 +134,7 @@ int qadc_scan_topk(int variant, const void *codes, int64_t n, int m, const void 
     switch (variant) {
     case QADC_U8_4BIT:
     case QADC_U8_8BIT:
+    case QADC_U8_6BIT:
         return qadc::scan_topk_u8(variant, (const uint8_t *)codes, n, m, (const uint8_t *)luts, nq, R, nbins,
                                   out_idx, (uint8_t *)out_dist, workspace, workspace_bytes,
                                   (hipStream_t)stream);
@@ -256,6 +265,7 @@ size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R)
     switch (call) {
     case QADC_WS_SCAN_TOPK: return qadc::scan_topk_u8_workspace(QADC_U8_4BIT, n, m, nq, R);
     case QADC_WS_SCAN_U8_8BIT: return qadc::scan_topk_u8_workspace(QADC_U8_8BIT, n, m, nq, R);
+    case QADC_WS_SCAN_U8_6BIT: return qadc::scan_topk_u8_workspace(QADC_U8_6BIT, n, m, nq, R);
     case QADC_WS_SCAN_F32_4BIT: return qadc::scan_topk_f32_workspace(QADC_F32_4BIT, n, m, nq, R);
     case QADC_WS_SCAN_F32_8BIT: return qadc::scan_topk_f32_workspace(QADC_F32_8BIT, n, m, nq, R);
     case QADC_WS_SEARCH: return qadc::search_workspace(n, m, nq, R);

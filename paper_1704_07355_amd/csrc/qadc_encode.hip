@@ -56,6 +56,42 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(
     codes[gid] = (uint8_t)out;
 }
 
+// ksub == 64 (6-bit components): one thread per group of four components = three output bytes;
+// component j is bits 6j .. 6j+5 of the code read as a little-endian number.  Arithmetic as above.
+__global__ __launch_bounds__(256) void pq_encode6_kernel(
+    const float *__restrict__ codebooks, int d, int m, const float *__restrict__ x, int64_t n,
+    uint8_t *__restrict__ codes)
+{
+#pragma clang fp contract(off)
+    const int dsub = d / m;
+    const int groups = m / 4;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= n * groups) return;
+    const int64_t r = gid / groups;
+    const int gq = (int)(gid - r * groups);
+    unsigned out = 0;
+    for (int h = 0; h < 4; ++h) {
+        const int j = 4 * gq + h;
+        const float *xs = x + r * d + (int64_t)j * dsub;
+        const float *cb = codebooks + (size_t)j * 64 * dsub;
+        double best = __builtin_inf();
+        unsigned arg = 0;
+        for (int i = 0; i < 64; ++i) {
+            double acc = 0.0;
+            for (int t = 0; t < dsub; ++t) {
+                const double df = (double)xs[t] - (double)cb[i * dsub + t];
+                acc += df * df;
+            }
+            if (acc < best) { best = acc; arg = (unsigned)i; }
+        }
+        out |= arg << (6 * h);
+    }
+    uint8_t *o = codes + r * (int64_t)(3 * groups) + 3 * gq;
+    o[0] = (uint8_t)out;
+    o[1] = (uint8_t)(out >> 8);
+    o[2] = (uint8_t)(out >> 16);
+}
+
 // ksub == 16 with the codebooks in LDS as [j][t][16] floats: one thread per output byte; for each
 // component it reads x^j[t] once and advances the 16 distances together, each still summed in
 // increasing t.  Same arithmetic and result as pq_encode_kernel<16>.
@@ -123,10 +159,18 @@ static int encode_launch(const char *name, const float *codebooks, int d, int m,
                          int64_t n, uint8_t *codes, const float *coarse, int K, const int32_t *cells,
                          const uint32_t *ids, int64_t n_x, hipStream_t st)
 {
-    if (m < 1 || d < 1 || d % m != 0 || (ksub != 16 && ksub != 256) || (ksub == 16 && (m & 1)) || n < 0)
+    if (m < 1 || d < 1 || d % m != 0 || (ksub != 16 && ksub != 64 && ksub != 256) || (ksub == 16 && (m & 1)) ||
+        (ksub == 64 && ((m & 3) || coarse)) || n < 0)
         return fail(QADC_EINVAL, "%s: unsupported d=%d m=%d ksub=%d", name, d, m, ksub);
     if (n == 0) return QADC_OK;
     if (!codebooks || !x || !codes) return fail(QADC_EINVAL, "%s: null pointer", name);
+    if (ksub == 64) {
+        const int64_t blocks6 = ceil_div(n * (m / 4), 256);
+        if (blocks6 > 0x7fffffffll) return fail(QADC_EINVAL, "%s: n too large for one call", name);
+        hipLaunchKernelGGL(pq_encode6_kernel, dim3((unsigned)blocks6), dim3(256), 0, st, codebooks, d, m, x, n, codes);
+        QADC_HIP_TRY(hipGetLastError());
+        return QADC_OK;
+    }
     const int64_t total = n * (ksub == 16 ? m / 2 : m);
     const int64_t blocks = ceil_div(total, 256);
     if (blocks > 0x7fffffffll) return fail(QADC_EINVAL, "%s: n too large for one call", name);

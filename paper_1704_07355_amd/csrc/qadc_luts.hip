@@ -42,7 +42,7 @@ int build_luts(const float *codebooks, int d, int m, int ksub, const float *quer
                const float *base, int nq, float *luts, hipStream_t st)
 {
     if (!codebooks || !queries || !luts) return fail(QADC_EINVAL, "qadc_build_luts: null pointer");
-    if (m < 1 || d < m || d % m != 0 || (ksub != 16 && ksub != 256) || nq < 0 || d > 8192)
+    if (m < 1 || d < m || d % m != 0 || (ksub != 16 && ksub != 64 && ksub != 256) || nq < 0 || d > 8192)
         return fail(QADC_EINVAL, "qadc_build_luts: unsupported d=%d m=%d ksub=%d nq=%d", d, m, ksub, nq);
     if (nq == 0) return QADC_OK;
     launch(QADC_PROF_TABLES, build_luts_kernel, dim3(nq), dim3(256), (size_t)d * sizeof(double), st,
@@ -58,7 +58,8 @@ constexpr int QUANT_MAX_M = 64;
 
 // KSUB = 16: 4-bit components, two per code byte (the paper's case).  KSUB = 256: 8-bit components,
 // one per code byte, the same quantizer applied to the 256-entry tables of Section 2.1's
-// standard product quantizer.
+// standard product quantizer.  KSUB = 64: 6-bit components (the paper's Conclusion), stored back to
+// back, least significant bit first, four per three bytes.
 template <int KSUB>
 __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
     const float *__restrict__ luts, int ngroup, int m, const uint8_t *__restrict__ init_codes,
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
 
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
-    constexpr int LOG = KSUB == 16 ? 4 : 8;
+    constexpr int LOG = KSUB == 16 ? 4 : KSUB == 64 ? 6 : 8;
     const int entries = m * KSUB;
     const float *lq = luts + (size_t)q * ngroup * entries;
 
@@ -87,10 +88,18 @@ __global__ __launch_bounds__(QUANT_NT) void quantize_luts_kernel(
     // qmax: R-th smallest float ADC distance (Eq. (2), float32, increasing j) of the init codes
     float qmax;
     if (init_codes) {
-        const int B = KSUB == 16 ? m / 2 : m;
+        const int B = KSUB == 16 ? m / 2 : KSUB == 64 ? 3 * m / 4 : m;
         for (int i = tid; i < n_init; i += QUANT_NT) {
             const uint8_t *c = init_codes + (size_t)i * B;
             float acc = 0.0f;
+            if (KSUB == 64) {
+                for (int j = 0; j < m; ++j) {
+                    const int bit = 6 * j, k = bit >> 3, sh = bit & 7;
+                    unsigned v = c[k];
+                    if (sh > 2) v |= (unsigned)c[k + 1] << 8;  // the field crosses into the next byte
+                    acc = acc + lq[j * 64 + ((v >> sh) & 63u)];  // the first table set
+                }
+            } else
             for (int jb = 0; jb < B; ++jb) {
                 const unsigned comps = c[jb];
                 if (KSUB == 16) {
@@ -168,8 +177,8 @@ int quantize_luts(int ksub, const float *luts, int nq, int ngroup, int m, const 
                   uint8_t *qluts, float *bias, float *delta, float *qmax_out, hipStream_t st)
 {
     if (!luts || !qluts) return fail(QADC_EINVAL, "qadc_quantize_luts: null pointer");
-    const int mm = ksub == 16 ? m : 2 * m;  // 8-bit components: m in {4, 8, 16, 32}
-    if (!(mm == 8 || mm == 16 || mm == 32 || mm == 64) || nq < 0 || ngroup < 1)
+    const int mm = ksub == 256 ? 2 * m : m;  // 8-bit components: m in {4, 8, 16, 32}
+    if (!(mm == 8 || mm == 16 || mm == 32 || (mm == 64 && ksub != 64)) || nq < 0 || ngroup < 1)
         return fail(QADC_EINVAL, "qadc_quantize_luts: unsupported m=%d nq=%d ngroup=%d", m, nq, ngroup);
     if (nbins < 1 || nbins > 255 || R < 1)
         return fail(QADC_EINVAL, "qadc_quantize_luts: nbins=%d R=%d", nbins, R);
@@ -185,6 +194,9 @@ int quantize_luts(int ksub, const float *luts, int nq, int ngroup, int m, const 
     if (nq == 0) return QADC_OK;
     if (ksub == 16)
         launch(QADC_PROF_QUANTIZE, quantize_luts_kernel<16>, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,
+               init_codes, (int)n_init, qmax_in, R, nbins, qmin_mode, qluts, bias, delta, qmax_out);
+    else if (ksub == 64)
+        launch(QADC_PROF_QUANTIZE, quantize_luts_kernel<64>, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,
                init_codes, (int)n_init, qmax_in, R, nbins, qmin_mode, qluts, bias, delta, qmax_out);
     else
         launch(QADC_PROF_QUANTIZE, quantize_luts_kernel<256>, dim3(nq), dim3(QUANT_NT), 0, st, luts, ngroup, m,

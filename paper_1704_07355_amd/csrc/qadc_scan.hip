@@ -45,7 +45,7 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
 {
     constexpr int NT = 1024;
     using C = ScanCfg<B, NT>;
-    __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
+    __shared__ __attribute__((aligned(16))) uint8_t ptab[C::TAB_BYTES];
     __shared__ unsigned hist[256];
 
     const int tid = threadIdx.x;
@@ -55,21 +55,23 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
     int64_t c0 = (int64_t)g * tiles_per_wg * seed_stride;
     if (c0 >= n) return;
 
-    uint4 w[2];
+    uint4 w[C::NVEC];
     int nc[2];
     tile_load<B, NT>(codes, c0, min(n, c0 + C::TILE), w, nc);
-    build_pair_tables<B, NT>(qluts + (size_t)q * (wide ? B * 256 : 2 * B * 16), cap, ptab, wide != 0);
+    build_pair_tables<B, NT>(qluts + (size_t)q * (C::SIX || wide ? C::TAB_BYTES : 2 * B * 16), cap, ptab, wide != 0);
     for (int e = tid; e < 256; e += NT) hist[e] = 0;
     __syncthreads();
 
     if (g == 0) {  // the scan kernel takes the pair tables from here instead of rebuilding them
         ScanHeader *hdr0 = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
-        for (int e = tid; e < B * 64; e += NT)
+        for (int e = tid; e < C::TAB_BYTES / 4; e += NT)
             reinterpret_cast<unsigned *>(hdr0->ptab)[e] = reinterpret_cast<const unsigned *>(ptab)[e];
     }
     for (int t = 0; t < tiles_per_wg && c0 < n; ++t, c0 += seed_stride) {  // uniform
         // the next sample tile is requested before this one is used
-        uint4 wn[2] = {w[0], w[1]};
+        uint4 wn[C::NVEC];
+#pragma unroll
+        for (int v = 0; v < C::NVEC; ++v) wn[v] = w[v];
         int ncn[2] = {nc[0], nc[1]};
         const int64_t c1 = c0 + seed_stride;
         if (t + 1 < tiles_per_wg && c1 < n) tile_load<B, NT>(codes, c1, min(n, c1 + C::TILE), wn, ncn);
@@ -78,7 +80,8 @@ __global__ __launch_bounds__(1024) void seed_u8_kernel(
 #pragma unroll
         for (int c = 0; c < C::CPT; ++c)
             if ((k[c] >> 24) < cap) atomicAdd(&hist[k[c] >> 24], 1u);  // NO_KEY has sum 255 >= cap
-        w[0] = wn[0]; w[1] = wn[1];
+#pragma unroll
+        for (int v = 0; v < C::NVEC; ++v) w[v] = wn[v];
         nc[0] = ncn[0]; nc[1] = ncn[1];
     }
     __syncthreads();
@@ -349,8 +352,8 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     using C = ScanCfg<B, NT>;
     const int has_seed = mode & 1;   // the seed kernel ran: bound and pair tables are in the control block
     const bool wide = (mode & 2) != 0;  // 8-bit components: qluts holds one 256-entry table per byte
-    __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
-    __shared__ __attribute__((aligned(16))) uint8_t qlut_s[2 * B * 16];
+    __shared__ __attribute__((aligned(16))) uint8_t ptab[C::TAB_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t qlut_s[C::SIX ? 16 : 2 * B * 16];
     __shared__ unsigned keys[C::CAP];
     __shared__ ScanShared sh;
 
@@ -366,20 +369,21 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     // Loads are returned in the order they were issued: the small ones the set-up waits for
     // (the seed kernel's pair tables and the low half of its histogram) go first, the first
     // tile of codes after them, so that set-up runs while the tile is in flight.
-    constexpr int PPT = (B * 16 + NT - 1) / NT;  // 16-byte pieces of the pair tables per thread
+    constexpr int PIECES = C::TAB_BYTES / 16;      // 16-byte pieces of the tables
+    constexpr int PPT = (PIECES + NT - 1) / NT;    // ... per thread
     uint4 pt[PPT];
     uint2 gh[GH_REP];
     if (has_seed) {
 #pragma unroll
         for (int t = 0; t < PPT; ++t)
-            if (tid + t * NT < B * 16) pt[t] = reinterpret_cast<const uint4 *>(hdr->ptab)[tid + t * NT];
+            if (tid + t * NT < PIECES) pt[t] = reinterpret_cast<const uint4 *>(hdr->ptab)[tid + t * NT];
         if (tid < WAVE) {
 #pragma unroll
             for (int r = 0; r < GH_REP; ++r) gh[r] = *reinterpret_cast<const uint2 *>(&hdr->ghist[r][2 * tid]);
         }
         asm volatile("" ::: "memory");
     }
-    uint4 w[2];
+    uint4 w[C::NVEC];
     int nc[2];
     tile_load<B, NT>(codes, (int64_t)g * C::TILE, n, w, nc);
     asm volatile("" ::: "memory");
@@ -412,10 +416,10 @@ __global__ __launch_bounds__(NT) void scan_u8_kernel(
     if (has_seed) {
 #pragma unroll
         for (int t = 0; t < PPT; ++t)
-            if (tid + t * NT < B * 16) reinterpret_cast<uint4 *>(ptab)[tid + t * NT] = pt[t];
-    } else if (wide) {
-        build_pair_tables<B, NT>(qluts + (size_t)q * B * 256, cap, ptab, true);
-    } else {
+            if (tid + t * NT < PIECES) reinterpret_cast<uint4 *>(ptab)[tid + t * NT] = pt[t];
+    } else if (C::SIX || wide) {
+        build_pair_tables<B, NT>(qluts + (size_t)q * C::TAB_BYTES, cap, ptab, true);
+    } else if constexpr (!C::SIX) {
         const uint8_t *qlut = qluts + (size_t)q * (2 * B) * 16;
         for (int e = tid; e < 2 * B * 4; e += NT)
             reinterpret_cast<unsigned *>(qlut_s)[e] = reinterpret_cast<const unsigned *>(qlut)[e];
@@ -558,15 +562,16 @@ struct ScanPlan {
 
 static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPlan *p)
 {
-    if (variant != QADC_U8_4BIT && variant != QADC_U8_8BIT) return false;
+    if (variant != QADC_U8_4BIT && variant != QADC_U8_8BIT && variant != QADC_U8_6BIT) return false;
     p->wide = variant == QADC_U8_8BIT;
+    const bool six = variant == QADC_U8_6BIT;  // 6-bit components: B = SIXBIT + m, a thread takes 48 bytes per tile
     if (p->wide) m *= 2;  // bytes per code = m / 2 below
-    if (!(m == 8 || m == 16 || m == 32 || m == 64)) return false;
+    if (!(m == 8 || m == 16 || m == 32 || (m == 64 && !six))) return false;
     if (n < 0 || n > 0xfffffffell || nq < 1 || R < 1 || R > QADC_MAX_R) return false;
-    p->B = m / 2;
+    p->B = six ? SIXBIT + m : m / 2;
     const int nt = knob_or(knobs().scan_nt, 256);
     p->NT = (nt == 1024 || nt == 512) ? nt : 256;
-    const int cpt = (p->B <= 16) ? SCAN_VEC * (16 / p->B) : 1;
+    const int cpt = six ? 64 / m : (p->B <= 16) ? SCAN_VEC * (16 / p->B) : 1;
     const int tile = p->NT * cpt;
     const int64_t tiles = n > 0 ? ceil_div(n, tile) : 1;
     // every workgroup takes tiles g, g+G, ...; its tiles must number below 2^24 / tile, the
@@ -602,7 +607,7 @@ static bool make_scan_plan(int variant, int64_t n, int m, int nq, int R, ScanPla
         if (fl > R) fl = R;
         p->flush_need = (unsigned)fl;
     }
-    p->tiled = p->seed_wgs > 0 && nq >= TILED_MIN_Q && knob_or(knobs().tiled, 1) != 0 &&
+    p->tiled = !six && p->seed_wgs > 0 && nq >= TILED_MIN_Q && knob_or(knobs().tiled, 1) != 0 &&
                make_tiled_plan(n, m, nq, !p->wide, &p->t);
     if (p->tiled && p->G > 256) p->G = 256;  // the single-query kernel only redoes rare queries
     const ScanLayout l = scan_layout(p->G, R);
@@ -664,9 +669,21 @@ static int dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
         launch(QADC_PROF_SEED, seed_u8_kernel<16>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
                            flush, p.seed_stride, tpw, ws, p.stride, p.wide ? 1 : 0);
         break;
-    default:
+    case 32:
         launch(QADC_PROF_SEED, seed_u8_kernel<32>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
                            flush, p.seed_stride, tpw, ws, p.stride, p.wide ? 1 : 0);
+        break;
+    case SIXBIT + 8:
+        launch(QADC_PROF_SEED, seed_u8_kernel<SIXBIT + 8>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+                           flush, p.seed_stride, tpw, ws, p.stride, 0);
+        break;
+    case SIXBIT + 16:
+        launch(QADC_PROF_SEED, seed_u8_kernel<SIXBIT + 16>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+                           flush, p.seed_stride, tpw, ws, p.stride, 0);
+        break;
+    default:
+        launch(QADC_PROF_SEED, seed_u8_kernel<SIXBIT + 32>, grid, dim3(1024), 0, st, codes, n, qluts, cap, R,
+                           flush, p.seed_stride, tpw, ws, p.stride, 0);
         break;
     }
     return QADC_OK;
@@ -681,7 +698,10 @@ static void dispatch_scan_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
     case 4: launch_scan_u8<4, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
     case 8: launch_scan_u8<8, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
     case 16: launch_scan_u8<16, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
-    default: launch_scan_u8<32, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
+    case 32: launch_scan_u8<32, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
+    case SIXBIT + 8: launch_scan_u8<SIXBIT + 8, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
+    case SIXBIT + 16: launch_scan_u8<SIXBIT + 16, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
+    default: launch_scan_u8<SIXBIT + 32, NT>(p, codes, n, qluts, nq, cap, R, ws, redo_flags, st); break;
     }
 }
 
@@ -724,7 +744,7 @@ int scan_topk_u8(int variant, const uint8_t *codes, int64_t n, int m, const uint
     char *ws = (char *)workspace;
     for (int q0 = 0; q0 < nq; q0 += p.qbatch) {
         const int nb = min(p.qbatch, nq - q0);
-        const uint8_t *ql = qluts + (size_t)q0 * m * (p.wide ? 256 : 16);
+        const uint8_t *ql = qluts + (size_t)q0 * m * (p.wide ? 256 : variant == QADC_U8_6BIT ? 64 : 16);
         if (p.seed_wgs > 0) {
             const int rs = dispatch_seed_u8(p, codes, n, ql, nb, nbins, R, ws, st);
             if (rs != QADC_OK) return rs;

@@ -22,12 +22,21 @@ struct alignas(256) ScanHeader {
     uint8_t ptab[32 * 256];       // the query's pair tables, left by the seed kernel for the scan
 };
 
+// Geometry of a scan.  B = bytes per code for 4-bit components (two per byte; also for 8-bit
+// components, one per byte); B = SIXBIT + m for codes of m 6-bit components (3m/4 bytes, stored
+// back to back, least significant bit first), whose thread takes 48 contiguous bytes per tile.
+constexpr int SIXBIT = 1000;
 template <int B, int NT>
 struct ScanCfg {
-    static constexpr int CPV = (B <= 16) ? 16 / B : 1;            // codes per 16-byte load
-    static constexpr int CPT = (B <= 16) ? SCAN_VEC * CPV : 1;    // codes per thread and tile
+    static constexpr bool SIX = B >= SIXBIT;
+    static constexpr int M6 = SIX ? B - SIXBIT : 0;               // 6-bit components per code
+    static constexpr int BYTES = SIX ? 3 * M6 / 4 : B;            // bytes per code
+    static constexpr int NVEC = SIX ? 3 : SCAN_VEC;               // 16-byte loads per thread and tile
+    static constexpr int CPV = (!SIX && B <= 16) ? 16 / B : 1;    // codes per 16-byte load (4-bit)
+    static constexpr int CPT = SIX ? 48 / BYTES : ((B <= 16) ? SCAN_VEC * CPV : 1);  // codes per thread and tile
     static constexpr int TILE = NT * CPT;
     static constexpr int CAP = TILE + SCAN_SLACK;
+    static constexpr int TAB_BYTES = SIX ? M6 * 64 : B * 256;     // lookup tables of a query in LDS
 };
 
 __device__ __forceinline__ unsigned byte_of(const uint4 &v, int k)
@@ -116,10 +125,27 @@ __device__ __forceinline__ uint4 stream_load16(const uint8_t *p)
 // tile lies inside the database (t0 + TILE <= c1), no bounds to check.
 template <int B, int NT, bool FULL = false>
 __device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int64_t t0, int64_t c1,
-                                          uint4 (&w)[2], int (&nc)[2])
+                                          uint4 (&w)[ScanCfg<B, NT>::NVEC], int (&nc)[2])
 {
     const int tid = threadIdx.x;
-    if constexpr (FULL) {
+    if constexpr (ScanCfg<B, NT>::SIX) {
+        // 6-bit components: the thread's CPT codes are 48 contiguous bytes; nc[0] = codes present
+        using C = ScanCfg<B, NT>;
+        const int64_t base = t0 + (int64_t)tid * C::CPT;
+        const uint8_t *p = codes + base * C::BYTES;
+        nc[1] = 0;
+        if (FULL || base + C::CPT <= c1) {
+#pragma unroll
+            for (int v = 0; v < 3; ++v) w[v] = stream_load16(p + 16 * v);
+            nc[0] = C::CPT;
+        } else {
+            nc[0] = base < c1 ? (int)(c1 - base) : 0;
+            unsigned tmp[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            for (int k = 0; k < nc[0] * C::BYTES; ++k) tmp[k >> 2] |= (unsigned)p[k] << (8 * (k & 3));
+#pragma unroll
+            for (int v = 0; v < 3; ++v) w[v] = make_uint4(tmp[4 * v], tmp[4 * v + 1], tmp[4 * v + 2], tmp[4 * v + 3]);
+        }
+    } else if constexpr (FULL) {
         if constexpr (B <= 16) {
             constexpr int CPV = 16 / B;
 #pragma unroll

@@ -27,15 +27,41 @@ __device__ __forceinline__ unsigned pair_entry(const uint8_t *ptab, int jb, unsi
     return e;
 }
 
+// Component j of code c of a thread's 48 bytes of 6-bit codes (compile-time position).
+template <int BYTES>
+__device__ __forceinline__ unsigned sixbit_field(const uint4 (&w)[3], int c, int j)
+{
+    const int bit = c * BYTES * 8 + 6 * j;
+    const int word = bit >> 5, sh = bit & 31;
+    auto dword = [&](int i) {
+        const uint4 &v = w[i >> 2];
+        return (i & 3) == 0 ? v.x : (i & 3) == 1 ? v.y : (i & 3) == 2 ? v.z : v.w;
+    };
+    const unsigned lo = dword(word);
+    if (sh <= 26) return (lo >> sh) & 63u;
+    return __funnelshift_r(lo, dword(word + 1), sh) & 63u;  // the field crosses into the next word
+}
+
 // Lookups, sum, clamp, key = sum << 24 | index among the workgroup's codes (NO_KEY where no
 // code; FULL: every slot of the tile holds a code).
 template <int B, int NT, bool FULL = false>
-__device__ __forceinline__ void tile_keys(const uint4 (&w)[2], const int (&nc)[2], unsigned rel0,
+__device__ __forceinline__ void tile_keys(const uint4 (&w)[ScanCfg<B, NT>::NVEC], const int (&nc)[2], unsigned rel0,
                                           const uint8_t *ptab, unsigned cap,
                                           unsigned (&k)[ScanCfg<B, NT>::CPT])
 {
     const int tid = threadIdx.x;
-    if constexpr (B <= 16) {
+    if constexpr (ScanCfg<B, NT>::SIX) {
+        using C = ScanCfg<B, NT>;
+#pragma unroll
+        for (int c = 0; c < C::CPT; ++c) {
+            unsigned s = 0;
+#pragma unroll
+            for (int j = 0; j < C::M6; ++j) s += ptab[j * 64 + sixbit_field<C::BYTES>(w, c, j)];
+            s = min(s, cap);
+            const unsigned key = (s << 24) | (rel0 + (unsigned)(tid * C::CPT + c));
+            k[c] = (FULL || c < nc[0]) ? key : NO_KEY;
+        }
+    } else if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
 #pragma unroll
         for (int v = 0; v < 2; ++v) {
@@ -68,10 +94,31 @@ __device__ __forceinline__ void tile_keys(const uint4 (&w)[2], const int (&nc)[2
 // them; with few lanes left they no longer collide on the LDS banks), and the others report their
 // partial sum, which is above the bound as the full one would be.
 template <int B, int NT>
-__device__ __forceinline__ void tile_sums(const uint4 (&w)[2], const uint8_t *ptab, unsigned bound,
+__device__ __forceinline__ void tile_sums(const uint4 (&w)[ScanCfg<B, NT>::NVEC], const uint8_t *ptab, unsigned bound,
                                           unsigned (&sm)[ScanCfg<B, NT>::CPT])
 {
-    if constexpr (B <= 16) {
+    if constexpr (ScanCfg<B, NT>::SIX) {
+        // two stages of m / 2 components, a check between them
+        using C = ScanCfg<B, NT>;
+        unsigned best = 0xffffffffu;
+#pragma unroll
+        for (int c = 0; c < C::CPT; ++c) {
+            unsigned s = 0;
+#pragma unroll
+            for (int j = 0; j < C::M6 / 2; ++j) s += ptab[j * 64 + sixbit_field<C::BYTES>(w, c, j)];
+            sm[c] = s;
+            best = min(best, s);
+        }
+        if (best <= bound) {
+#pragma unroll
+            for (int c = 0; c < C::CPT; ++c) {
+                unsigned s = sm[c];
+#pragma unroll
+                for (int j = C::M6 / 2; j < C::M6; ++j) s += ptab[j * 64 + sixbit_field<C::BYTES>(w, c, j)];
+                sm[c] = s;
+            }
+        }
+    } else if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
         // the bytes are summed in stages, with a check after each stage but the last
         constexpr int NS = QADC_EARLY_STAGES(B);
@@ -113,7 +160,9 @@ __device__ __forceinline__ void tile_sums(const uint4 (&w)[2], const uint8_t *pt
 template <int B, int NT>
 __device__ __forceinline__ unsigned tile_slot_index(int c)
 {
-    if constexpr (B <= 16) {
+    if constexpr (ScanCfg<B, NT>::SIX) {
+        return (unsigned)((int)threadIdx.x * ScanCfg<B, NT>::CPT + c);
+    } else if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
         return (unsigned)(((c / CPV) * NT + (int)threadIdx.x) * CPV + c % CPV);
     } else {
@@ -127,6 +176,10 @@ template <int B, int NT>
 __device__ __forceinline__ void build_pair_tables(const uint8_t *__restrict__ qlut, unsigned cap,
                                                   uint8_t *ptab, bool wide = false)
 {
+    if constexpr (ScanCfg<B, NT>::SIX) {  // 6-bit components: the caller's m tables of 64 entries
+        for (int e = threadIdx.x; e < ScanCfg<B, NT>::TAB_BYTES; e += NT) ptab[e] = (uint8_t)min((unsigned)qlut[e], cap);
+        return;
+    } else {
     if (wide) {
         for (int e = threadIdx.x; e < B * 256; e += NT) ptab[e] = (uint8_t)min((unsigned)qlut[e], cap);
         return;
@@ -136,6 +189,7 @@ __device__ __forceinline__ void build_pair_tables(const uint8_t *__restrict__ ql
         const unsigned s = (unsigned)qlut[(2 * jb) * 16 + (v & 15)] +
                            (unsigned)qlut[(2 * jb + 1) * 16 + (v >> 4)];
         ptab[e] = (uint8_t)min(s, cap);
+    }
     }
 }
 

@@ -68,7 +68,7 @@ int pq_train(const float *train, int64_t n, int d, int m, int ksub, const int64_
              float *codebooks, void *workspace, size_t workspace_bytes, hipStream_t st)
 {
     if (!train || !init_rows || !codebooks) return fail(QADC_EINVAL, "qadc_pq_train: null pointer");
-    if (m < 1 || d < m || d % m != 0 || (ksub != 16 && ksub != 256) || n < 1 || iters < 0)
+    if (m < 1 || d < m || d % m != 0 || (ksub != 16 && ksub != 64 && ksub != 256) || n < 1 || iters < 0)
         return fail(QADC_EINVAL, "qadc_pq_train: unsupported n=%lld d=%d m=%d ksub=%d iters=%d",
                     (long long)n, d, m, ksub, iters);
     if (!workspace || workspace_bytes < (size_t)n * m)
