@@ -578,10 +578,14 @@ def run_compare(args):
 
     ms4b = timed_batch(lambda: Q.qadc_search(cb4, qb, codes4, R, init))
     ms8b = timed_batch(lambda: Q.qadc_scan_topk(Q.QADC_F32_8BIT, codes8, luts8b, R))
+    luts4b = Q.qadc_build_luts(cb4, qb)
+    ms4fb = timed_batch(lambda: Q.qadc_scan_topk(Q.QADC_F32_4BIT, codes4, luts4b, R))
     ql8b = Q.qadc_quantize_luts(luts8b, codes8[:init], R)[0]
     ms8qb = timed_batch(lambda: Q.qadc_scan_topk(Q.QADC_U8_8BIT, codes8, ql8b, R))
     batched = {"queries": nbq, "quick_adc_ms": round(ms4b, 3), "pq8_float_ms": round(ms8b, 3),
                "pq8_uint8_tables_ms": round(ms8qb, 3),
+               "float_adc_4bit_codes_ms": round(ms4fb, 3),
+               "speedup_quick_adc_over_float_adc_same_codes": round(ms4fb / ms4b, 2),
                "quick_adc_gpairs_per_s": round(n * nbq / (ms4b * 1e-3) / 1e9, 1),
                "pq8_float_gpairs_per_s": round(n * nbq / (ms8b * 1e-3) / 1e9, 1),
                "speedup_quick_adc_over_pq8_float": round(ms8b / ms4b, 2)}

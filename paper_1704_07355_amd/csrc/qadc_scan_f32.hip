@@ -359,7 +359,7 @@ constexpr int F32T_LCAP = 64;
 constexpr int F32T_MAX_CHUNKS = 1024;
 constexpr int F32T_MIN_Q = 8;
 
-template <int ROW>
+template <int KSUB, int ROW>
 __global__ __launch_bounds__(F32_NT) void scan_f32_tiled_kernel(
     const uint8_t *__restrict__ codes, int64_t n, int64_t chunk, int nq, const float *__restrict__ luts,
     const F32Range *__restrict__ ranges, int R, char *__restrict__ ws, size_t ws_stride, size_t countsA_off,
@@ -368,7 +368,10 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_tiled_kernel(
     constexpr int NT = F32_NT;
     static_assert(NT / WAVE == F32T_Q, "one wavefront per query reads its bound");
     using C = ScanCfg<ROW, NT>;
-    extern __shared__ float4 ftab[];  // [ROW * 256][2]: eight floats per entry
+    // table entry (component, value) = eight floats, one per query of the group: [ROW * 256][2]
+    // float4 for 8-bit components, [2 * ROW * 16][2] for 4-bit ones
+    constexpr int ENTRIES = KSUB == 256 ? ROW * 256 : 2 * ROW * 16;
+    extern __shared__ float4 ftab[];
     __shared__ uint64_t keys[F32T_Q][F32T_LCAP];
     __shared__ unsigned cnt[F32T_Q];
     __shared__ unsigned tau_s[F32T_Q];
@@ -410,12 +413,12 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_tiled_kernel(
         }
         if (l == 0) { tau_s[k] = t; cnt[k] = 0; }
     }
-    for (int e = tid; e < ROW * 256; e += NT) {
+    for (int e = tid; e < ENTRIES; e += NT) {
         float v[F32T_Q];
 #pragma unroll
         for (int k = 0; k < F32T_Q; ++k) {
             const int q = q0 + k;
-            v[k] = (q < nq) ? luts[(size_t)q * ROW * 256 + e] : __builtin_inff();
+            v[k] = (q < nq) ? luts[(size_t)q * ENTRIES + e] : __builtin_inff();
         }
         ftab[2 * e] = make_float4(v[0], v[1], v[2], v[3]);
         ftab[2 * e + 1] = make_float4(v[4], v[5], v[6], v[7]);
@@ -442,12 +445,20 @@ __global__ __launch_bounds__(F32_NT) void scan_f32_tiled_kernel(
                 float acc[F32T_Q];
 #pragma unroll
                 for (int k = 0; k < F32T_Q; ++k) acc[k] = 0.0f;
-#pragma unroll
-                for (int jb = 0; jb < ROW; ++jb) {
-                    const unsigned e = (unsigned)jb * 256u + byte_of(w[v], c * ROW + jb);
+                auto add = [&](unsigned e) {  // float32 additions in increasing component order
                     const float4 lo4 = ftab[2 * e], hi4 = ftab[2 * e + 1];
                     acc[0] = acc[0] + lo4.x; acc[1] = acc[1] + lo4.y; acc[2] = acc[2] + lo4.z; acc[3] = acc[3] + lo4.w;
                     acc[4] = acc[4] + hi4.x; acc[5] = acc[5] + hi4.y; acc[6] = acc[6] + hi4.z; acc[7] = acc[7] + hi4.w;
+                };
+#pragma unroll
+                for (int jb = 0; jb < ROW; ++jb) {
+                    const unsigned b = byte_of(w[v], c * ROW + jb);
+                    if constexpr (KSUB == 256) {
+                        add((unsigned)jb * 256u + b);
+                    } else {  // two 4-bit components per byte: the low nibble is the even one
+                        add((unsigned)(2 * jb) * 16u + (b & 15u));
+                        add((unsigned)(2 * jb + 1) * 16u + (b >> 4));
+                    }
                 }
                 const bool valid = c < nc[v];
                 const unsigned li = rel + (unsigned)((v * NT + tid) * CPV + c);
@@ -498,7 +509,7 @@ struct F32Plan {
     unsigned flush_need;
     ScanLayout l;
     size_t stride;        // bytes of workspace per query
-    bool tiled;           // batches of 8-bit codes go through the query-tiled kernel
+    bool tiled;           // batches go through the query-tiled kernel
     int GC;               // database chunks of the tiled kernel
     int64_t chunk;
     size_t countsA_off, listsA_off, flags_off, tiled_lds;
@@ -544,13 +555,13 @@ static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan 
         if (fl > R) fl = R;
         p->flush_need = (unsigned)fl;
     }
-    // batches of 8-bit codes: query-tiled kernel over chunks, the single-query kernel only redoes
-    // queries whose lists overflowed
+    // batches: query-tiled kernel over chunks (8-bit codes: a table entry per byte; 4-bit codes: two
+    // per byte), the single-query kernel only redoes queries whose lists overflowed
     p->tiled = false;
     p->GC = 0;
     p->chunk = 0;
-    p->tiled_lds = (size_t)p->ROW * 256 * 2 * sizeof(float4);
-    if (p->KSUB == 256 && p->ROW <= 16 && p->seed_wgs > 0 && nq >= F32T_MIN_Q && knob_or(knobs().tiled, 1) != 0) {
+    p->tiled_lds = (size_t)(p->KSUB == 256 ? p->ROW * 256 : 2 * p->ROW * 16) * 2 * sizeof(float4);
+    if (p->ROW <= 16 && p->seed_wgs > 0 && nq >= F32T_MIN_Q && knob_or(knobs().tiled, 1) != 0) {
         const int64_t groups = ceil_div(nq, F32T_Q);
         const int64_t want = std::max<int64_t>(1, std::min<int64_t>(F32T_MAX_CHUNKS, ceil_div(1024, groups)));
         int64_t chunk = ceil_div(ceil_div(n, F32T_MAX_CHUNKS), tile) * tile;
@@ -583,7 +594,7 @@ static bool make_f32_plan(int variant, int64_t n, int m, int nq, int R, F32Plan 
     return true;
 }
 
-template <int ROW>
+template <int KSUB, int ROW>
 static int launch_f32_tiled(const F32Plan &p, const uint8_t *codes, int64_t n, const float *luts, int nq, int R,
                             const F32Range *ranges, char *ws, unsigned *flags, hipStream_t st)
 {
@@ -591,19 +602,19 @@ static int launch_f32_tiled(const F32Plan &p, const uint8_t *codes, int64_t n, c
         static std::once_flag attr_once;  // the kernel may use more dynamic LDS than the default limit
         hipError_t attr_rc = hipSuccess;
         std::call_once(attr_once, [&] {
-            attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_f32_tiled_kernel<ROW>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.tiled_lds);  // fixed by ROW
+            attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_f32_tiled_kernel<KSUB, ROW>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.tiled_lds);  // fixed by KSUB, ROW
         });
         QADC_HIP_TRY(attr_rc);
         const unsigned gc8 = (unsigned)ceil_div(p.GC, 8) * 8u;  // chunk slots, eight at a time
         dim3 grid((unsigned)ceil_div(nq, F32T_Q) * gc8);
-        launch(QADC_PROF_SCAN, scan_f32_tiled_kernel<ROW>, grid, dim3(F32_NT), p.tiled_lds, st, codes, n, p.chunk,
+        launch(QADC_PROF_SCAN, (scan_f32_tiled_kernel<KSUB, ROW>), grid, dim3(F32_NT), p.tiled_lds, st, codes, n, p.chunk,
                nq, luts, ranges, R, ws, p.stride, p.countsA_off, p.listsA_off, flags);
     }
     return QADC_OK;
 }
 
-// Seed (large databases), query-tiled scan (batches of 8-bit codes), single-query scan: of
+// Seed (large databases), query-tiled scan (batches), single-query scan: of
 // everything, or of the queries the tiled scan flagged.  `flags`: null without a tiled scan.
 template <int KSUB>
 static int dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, const float *luts, int nq,
@@ -621,7 +632,7 @@ static int dispatch_f32(const F32Plan &p, const uint8_t *codes, int64_t n, const
                    luts, (const F32Range *)ranges, R, p.flush_need, p.seed_stride, ws, p.stride);     \
         }                                                                                            \
         if (flags) {                                                                                 \
-            const int rc = launch_f32_tiled<ROW_>(p, codes, n, luts, nq, R, ranges, ws, flags, st);  \
+            const int rc = launch_f32_tiled<KSUB, ROW_>(p, codes, n, luts, nq, R, ranges, ws, flags, st);  \
             if (rc != QADC_OK) return rc;                                                            \
         }                                                                                            \
         launch(QADC_PROF_SCAN, (scan_f32_kernel<KSUB, ROW_>), grid, block, 0, st, codes, n, luts,     \

@@ -738,3 +738,24 @@ def test_float_scan_batches_with_ties_and_useless_bounds(Q, O):
     wi, wd = cref.scan_topk_f32(codes, luts, R)
     idx, dist = Q.qadc_scan_topk(Q.QADC_F32_8BIT, to_gpu(codes), to_gpu(luts), R)
     assert np.array_equal(idx_np(idx), wi) and np.array_equal(dist.cpu().numpy(), wd)
+
+
+@pytest.mark.parametrize("m,n,nq", [(16, 300_007, 8), (16, 300_007, 19), (8, 700_000, 16), (32, 280_000, 9)])
+def test_float_scan_of_4bit_codes_in_query_batches(Q, O, m, n, nq):
+    """Batches of eight queries and more over 4-bit codes take the query-tiled float kernel too (two
+    table entries per code byte, added in increasing component order): indices and float32
+    distances equal the plain-C scan of Alg. 1 bit for bit."""
+    from oracle import cref
+    rng = np.random.default_rng(m + n + nq)
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    luts = (rng.gamma(2.0, 50.0, size=(nq, m, 16))).astype(np.float32)
+    R = 100
+    wi, wd = cref.scan_topk_f32(codes, luts, R)
+    idx, dist = Q.qadc_scan_topk(Q.QADC_F32_4BIT, to_gpu(codes), to_gpu(luts), R)
+    assert np.array_equal(idx_np(idx), wi)
+    assert np.array_equal(dist.cpu().numpy(), wd)
+    # ties: every code equal, every list of the tiled kernel overflows, each query is redone alone
+    codes[:] = 0x5a
+    wi, wd = cref.scan_topk_f32(codes, luts, R)
+    idx, dist = Q.qadc_scan_topk(Q.QADC_F32_4BIT, to_gpu(codes), to_gpu(luts), R)
+    assert np.array_equal(idx_np(idx), wi) and np.array_equal(dist.cpu().numpy(), wd)
