@@ -71,6 +71,9 @@ The inverted-index search is pinned by hand-built indexes: the qmax walk (first
 distances to centroid + decoded residual, the (sum, storage position) order
 against sorted tuples on lists probed in reverse storage order, the Index step
 on repeated centroids; overlap, NN-recall and exact_nn on rows worked by hand.
+The multi-index over occupied cells is pinned by a six-vector example whose cells,
+list boundaries and centroids are written by hand, its codes by brute force over
+all codes, and by equality with the inverted index over all K*K cells.
 """
 
 from __future__ import annotations
@@ -645,6 +648,37 @@ def multi_sequence(d1: np.ndarray, d2: np.ndarray, count: int):
                     heapq.heappush(heap, (d1[o1[a]] + d2[o2[b]], a, b))
                     pushed.add((a, b))
     return out
+
+
+def multi_index_build_occupied(x: np.ndarray, halves: np.ndarray, codebooks: np.ndarray):
+    """The multi-index at its usual size (K*K far above the number of vectors): only the cells that
+    hold a vector get an inverted list.  Lists are in increasing cell id; inside a list vectors keep
+    their input order; the residual is taken against (halves[0][i], halves[1][j]).
+
+    Returns dict(cell_ids uint32 [L] ascending, centroids float32 [L][d], list_off int64 [L+1],
+    codes uint8 [n][m/2], ids uint32 [n]): an inverted index over L lists, list s being cell
+    cell_ids[s]; ivf_quick_adc_search takes it with coarse = centroids and probes = list numbers.
+    """
+    K = halves.shape[1]
+    cell = multi_index_assign(x, halves)
+    cell_ids = np.unique(cell)
+    order = np.argsort(cell, kind="stable")
+    i, j = cell[order] // K, cell[order] % K
+    resid = x[order] - np.concatenate([halves[0][i], halves[1][j]], axis=1)
+    comps = pq_encode(resid.astype(np.float32), codebooks)
+    list_off = np.zeros(len(cell_ids) + 1, dtype=np.int64)
+    list_off[1:] = np.cumsum([np.count_nonzero(cell == c) for c in cell_ids])
+    centroids = np.concatenate([halves[0][cell_ids // K], halves[1][cell_ids % K]], axis=1)
+    return dict(cell_ids=cell_ids.astype(np.uint32), centroids=centroids.astype(np.float32),
+                list_off=list_off, codes=pack_nibbles(comps), ids=order.astype(np.uint32))
+
+
+def multi_index_slots(cell_ids: np.ndarray, cells: np.ndarray) -> np.ndarray:
+    """List number of every cell id in `cells` (its place in the ascending `cell_ids`), -1 for a
+    cell that holds no vector."""
+    where = {int(c): s for s, c in enumerate(cell_ids)}
+    return np.array([where.get(int(c), -1) for c in np.asarray(cells).ravel()],
+                    dtype=np.int32).reshape(np.shape(cells))
 
 
 def ivf_quick_adc_search(index, coarse, codebooks, query, nprobe, init, R, nbins=255,
