@@ -222,15 +222,26 @@ size_t qadc_static_scratch_bytes(void);
  * cell, cell c holding storage positions list_off[c] .. list_off[c+1]-1), with the vector
  * id of every position.  The struct itself lives in HOST memory; its pointers are device
  * pointers.
+ *
+ * A multi-index at its usual size (far more product cells than vectors, see
+ * qadc_multi_index_group) keeps lists for its occupied cells only and no table of K centroids:
+ * then coarse is NULL, the K lists are the occupied cells in increasing cell id, cell_ids[s] is
+ * the product cell of list s and its centroid is (halves[0][cell_ids[s] / Kh],
+ * halves[1][cell_ids[s] % Kh]).  Such an index is searched with probes_in given as list numbers
+ * (qadc_multi_index_probes, then qadc_multi_index_slots).  With coarse set, halves, cell_ids and Kh
+ * are not read.
  */
 typedef struct qadc_ivf_index {
-    const float *coarse;      /* [K][d] f32 coarse centroids                         */
+    const float *coarse;      /* [K][d] f32 coarse centroids, or NULL (see above)    */
     const int64_t *list_off;  /* [K+1] i64, list_off[0] = 0, list_off[K] = n         */
     const uint8_t *codes;     /* [n][m/2] u8, standard layout, in list order, 16-byte aligned */
     const uint32_t *ids;      /* [n] u32 vector id of each storage position          */
     const float *codebooks;   /* [m][16][d/m] f32 product quantizer of the residuals */
     int d, m, K;
     int64_t n;
+    const float *halves;      /* [2][Kh][d/2] f32 half-centroids, read when coarse is NULL */
+    const uint32_t *cell_ids; /* [K] u32 ascending product cell of every list, same      */
+    int Kh;                   /* half-centroids per half, same                           */
 } qadc_ivf_index;
 
 /*
@@ -246,7 +257,8 @@ typedef struct qadc_ivf_index {
  *   queries    [nq][d] f32
  *   nprobe     1..256 (the paper's `ma`); init 1..QADC_MAX_INIT; nbins 1..255; R 1..QADC_MAX_R
  *   probes_in  [nq][nprobe] i32 or NULL; a negative entry is an unused slot, and so is an entry
- *              >= K or one that repeats an earlier cell of the same query (a list is scanned once)
+ *              >= K or one that repeats an earlier cell of the same query (a list is scanned once).
+ *              Required (QADC_EINVAL without) when the index has no coarse centroids.
  *   out_ids    [nq][R] u32   ids[position] of the neighbours (0xFFFFFFFF padding)
  *   out_dist   [nq][R] u8    their quantized sums (nbins padding)
  *   dbg_probes [nq][nprobe] i32 or NULL: the cells scanned      (output, for replay/tests)
@@ -332,9 +344,16 @@ int qadc_ivf_encode(const float *coarse, int K, const float *codebooks, int d, i
  * qadc_ivf_index: build it with qadc_multi_index_assign -> qadc_ivf_group -> qadc_ivf_encode (coarse =
  * the output of qadc_multi_index_cells) and search it with qadc_ivf_search, probes_in = the output of
  * qadc_multi_index_probes.
- *   halves [2][K][d/2] f32, K <= 4096, d even
+ *   halves [2][K][d/2] f32, K <= 16384, d even
  *
- * qadc_multi_index_cells:  coarse[i*K + j] = (halves[0][i], halves[1][j]);  coarse [K*K][d] f32 (output)
+ * At the usual size of a multi-index (K = 2^14, 2^28 cells for 10^9 vectors) most cells are empty:
+ * neither K*K centroids nor K*K list boundaries are stored.  qadc_multi_index_group writes the lists
+ * of the occupied cells only, qadc_multi_index_encode takes the residuals from the half-centroids,
+ * the qadc_ivf_index carries halves and cell_ids in place of coarse, and qadc_multi_index_slots turns
+ * the cells of qadc_multi_index_probes into list numbers (an empty cell becomes an unused slot).
+ *
+ * qadc_multi_index_cells:  coarse[i*K + j] = (halves[0][i], halves[1][j]);  coarse [K*K][d] f32 (output;
+ *   K*K*d < 2^39)
  * qadc_multi_index_assign: cells[v] = K * (closest of halves[0] to the first half of x[v]) + (closest
  *   of halves[1] to its second half), float64 distances, ties to the lowest;  x [n][d];  cells [n] i32
  * qadc_multi_index_probes: probes[q] = the nprobe (<= 256) cells with the smallest d1[i] + d2[j],
@@ -344,6 +363,22 @@ int qadc_ivf_encode(const float *coarse, int K, const float *codebooks, int d, i
  *   queries [nq][d] f32, nq <= 65535;  probes [nq][nprobe] i32 (output)
  *   workspace >= qadc_multi_index_workspace_bytes(K, nq, nprobe) (0: unsupported arguments),
  *   16-byte aligned; it need not be cleared.
+ * qadc_multi_index_group: the list order of a database over the occupied cells: a stable sort of
+ *   the vectors by cell id.  n_lists[0] = L = number of distinct cells in `cells`; cell_ids[0..L-1] =
+ *   those cells, ascending; list_off[s] = number of vectors in cells below cell_ids[s], list_off[L] =
+ *   number of vectors placed; ids[list_off[s] + r] = the r-th vector of cell cell_ids[s] in input
+ *   order.  An entry of `cells` outside [0, K*K) is left out.
+ *   cells [n] i32, n <= 2^32;  max_lists >= min(n, K*K): the capacity of cell_ids [max_lists] u32
+ *   and list_off [max_lists + 1] i64 (outputs, device);  ids [n] u32 (output);  n_lists [1] i64
+ *   (output, device);  workspace >= qadc_multi_index_group_workspace_bytes(n, K) (0: unsupported),
+ *   16-byte aligned; it need not be cleared.
+ * qadc_multi_index_encode: codes[p] = the code of x[ids[p]] - (halves[0][c / K], halves[1][c % K]),
+ *   c = cells[ids[p]], float32 subtraction, encoded as qadc_ivf_encode does (ksub = 16, m even: a
+ *   sub-vector lies in one half).  A row whose id or cell is out of range is written as zero bytes.
+ *   x [n][d] f32;  cells [n] i32;  ids [n_list] u32;  codes [n_list][m/2] u8 (output)
+ * qadc_multi_index_slots: slots[e] = s with cell_ids[s] == cells[e], or -1 when no list has that
+ *   cell (or cells[e] < 0).  cell_ids [n_lists] u32 ascending;  cells, slots [count] i32 (slots is
+ *   the output; the two may be the same array)
  */
 int qadc_multi_index_cells(const float *halves, int K, int d, float *coarse, void *stream);
 int qadc_multi_index_assign(const float *halves, int K, int d, const float *x, int64_t n, int32_t *cells,
@@ -351,6 +386,15 @@ int qadc_multi_index_assign(const float *halves, int K, int d, const float *x, i
 size_t qadc_multi_index_workspace_bytes(int K, int nq, int nprobe);
 int qadc_multi_index_probes(const float *halves, int K, int d, const float *queries, int nq, int nprobe,
                             int32_t *probes, void *workspace, size_t workspace_bytes, void *stream);
+size_t qadc_multi_index_group_workspace_bytes(int64_t n, int K);
+int qadc_multi_index_group(const int32_t *cells, int64_t n, int K, int64_t max_lists, uint32_t *cell_ids,
+                           int64_t *list_off, uint32_t *ids, int64_t *n_lists, void *workspace,
+                           size_t workspace_bytes, void *stream);
+int qadc_multi_index_encode(const float *halves, int K, const float *codebooks, int d, int m, const float *x,
+                            int64_t n, const int32_t *cells, const uint32_t *ids, int64_t n_list,
+                            uint8_t *codes, void *stream);
+int qadc_multi_index_slots(const uint32_t *cell_ids, int64_t n_lists, const int32_t *cells, int64_t count,
+                           int32_t *slots, void *stream);
 
 /*
  * Rotation of an optimized product quantizer, Section 2.1: opq(x) = pq(R x), R^T R = I.

@@ -34,7 +34,8 @@ EXPORTS = (
     "qadc_last_error", "qadc_version", "qadc_packed_bytes", "qadc_pack_codes", "qadc_unpack_codes",
     "qadc_ivf_assign", "qadc_ivf_group_workspace_bytes", "qadc_ivf_group", "qadc_ivf_encode",
     "qadc_multi_index_cells", "qadc_multi_index_assign", "qadc_multi_index_workspace_bytes",
-    "qadc_multi_index_probes", "qadc_search_static", "qadc_static_scratch_bytes",
+    "qadc_multi_index_probes", "qadc_multi_index_group_workspace_bytes", "qadc_multi_index_group",
+    "qadc_multi_index_encode", "qadc_multi_index_slots", "qadc_search_static", "qadc_static_scratch_bytes",
 )
 
 _lib = None
@@ -44,7 +45,8 @@ class qadc_ivf_index(ctypes.Structure):
     """Mirror of the C struct: device pointers + shapes (include/qadc.h)."""
     _fields_ = [("coarse", ctypes.c_void_p), ("list_off", ctypes.c_void_p), ("codes", ctypes.c_void_p),
                 ("ids", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("d", ctypes.c_int),
-                ("m", ctypes.c_int), ("K", ctypes.c_int), ("n", ctypes.c_int64)]
+                ("m", ctypes.c_int), ("K", ctypes.c_int), ("n", ctypes.c_int64),
+                ("halves", ctypes.c_void_p), ("cell_ids", ctypes.c_void_p), ("Kh", ctypes.c_int)]
 
 
 class QadcError(RuntimeError):
@@ -121,6 +123,14 @@ def lib() -> ctypes.CDLL:
         L.qadc_multi_index_workspace_bytes.restype = sz
         L.qadc_multi_index_probes.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, sz, vp]
         L.qadc_multi_index_probes.restype = i32
+        L.qadc_multi_index_group_workspace_bytes.argtypes = [i64, i32]
+        L.qadc_multi_index_group_workspace_bytes.restype = sz
+        L.qadc_multi_index_group.argtypes = [vp, i64, i32, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.qadc_multi_index_group.restype = i32
+        L.qadc_multi_index_encode.argtypes = [vp, i32, vp, i32, i32, vp, i64, vp, vp, i64, vp, vp]
+        L.qadc_multi_index_encode.restype = i32
+        L.qadc_multi_index_slots.argtypes = [vp, i64, vp, i64, vp, vp]
+        L.qadc_multi_index_slots.restype = i32
         L.qadc_last_error.restype = ctypes.c_char_p
         L.qadc_version.restype = ctypes.c_char_p
         _lib = L
@@ -346,6 +356,57 @@ def qadc_multi_index_probes(halves, queries, nprobe, workspace=None, out=None):
     return out
 
 
+def qadc_multi_index_group_workspace_bytes(n: int, K: int) -> int:
+    return int(lib().qadc_multi_index_group_workspace_bytes(n, K))
+
+
+def qadc_multi_index_group(cells, K, workspace=None):
+    """cells i32 [n] (product cells of K half-centroids per half) -> (cell_ids u32-bits [L], list_off i64 [L+1],
+    ids u32-bits [n_placed]): the lists of the occupied cells, ascending.  Reads L back from the device."""
+    n = cells.shape[0]
+    cap = min(n, K * K)
+    dev = cells.device
+    if workspace is None:
+        workspace = torch.empty((max(16, qadc_multi_index_group_workspace_bytes(n, K)),), dtype=torch.uint8, device=dev)
+    cell_ids = torch.zeros((max(cap, 1),), dtype=torch.int32, device=dev)
+    list_off = torch.zeros((cap + 1,), dtype=torch.int64, device=dev)
+    ids = torch.zeros((max(n, 1),), dtype=torch.int32, device=dev)
+    n_lists = torch.zeros((1,), dtype=torch.int64, device=dev)
+    _check(lib().qadc_multi_index_group(_ptr(cells, torch.int32), n, K, cap, _ptr(cell_ids, torch.int32),
+                                        _ptr(list_off, torch.int64), _ptr(ids, torch.int32),
+                                        _ptr(n_lists, torch.int64), _ptr(workspace, torch.uint8),
+                                        workspace.numel(), _stream()))
+    L = int(n_lists.item())
+    list_off = list_off[:L + 1].clone()
+    placed = int(list_off[L].item())
+    return cell_ids[:L].clone(), list_off, ids[:placed].clone()
+
+
+def qadc_multi_index_encode(halves, codebooks, x, cells, ids, out=None):
+    """Residual codes in list order against the half-centroids: row p = enc(x[ids[p]] - (halves[0][c // K],
+    halves[1][c % K])), c = cells[ids[p]]; u8 [len(ids)][m/2]."""
+    _, K, dh = halves.shape
+    m = codebooks.shape[0]
+    n = x.shape[0]
+    n_list = ids.shape[0]
+    assert x.shape[1] == 2 * dh
+    if out is None:
+        out = torch.empty((n_list, m // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().qadc_multi_index_encode(_ptr(halves, torch.float32), K, _ptr(codebooks, torch.float32), 2 * dh, m,
+                                         _ptr(x, torch.float32), n, _ptr(cells, torch.int32),
+                                         _ptr(ids, torch.int32), n_list, _ptr(out, torch.uint8), _stream()))
+    return out
+
+
+def qadc_multi_index_slots(cell_ids, cells, out=None):
+    """cell_ids u32-bits [L] ascending, cells i32 [...] -> list numbers i32 [...], -1 for cells without a list."""
+    if out is None:
+        out = torch.empty_like(cells)
+    _check(lib().qadc_multi_index_slots(_ptr(cell_ids, torch.int32), cell_ids.numel(), _ptr(cells, torch.int32),
+                                        cells.numel(), _ptr(out, torch.int32), _stream()))
+    return out
+
+
 def qadc_ivf_group_workspace_bytes(n: int, K: int) -> int:
     return int(lib().qadc_ivf_group_workspace_bytes(n, K))
 
@@ -398,18 +459,29 @@ def qadc_profile_read(which: int):
 
 
 class IvfIndex:
-    """Holds the tensors of an inverted index on the GPU and the C struct that points at them."""
+    """Holds the tensors of an inverted index on the GPU and the C struct that points at them.
 
-    def __init__(self, coarse, list_off, codes, ids, codebooks):
-        K, d = coarse.shape
+    coarse f32 [K][d], or None for a multi-index over its occupied cells: then `halves` f32 [2][Kh][d/2]
+    and `cell_ids` u32-bits [K] (ascending product cell of every list) stand in for the centroids.
+    """
+
+    def __init__(self, coarse, list_off, codes, ids, codebooks, halves=None, cell_ids=None):
         m = codebooks.shape[0]
+        if coarse is not None:
+            K, d = coarse.shape
+            hp, cp, Kh = None, None, 0
+        else:
+            assert halves is not None and cell_ids is not None
+            _, Kh, dh = halves.shape
+            K, d = cell_ids.numel(), 2 * dh
+            hp, cp = _ptr(halves, torch.float32).value, _ptr(cell_ids, torch.int32).value
         assert codebooks.shape[1] == 16 and codes.shape[1] == m // 2
         assert list_off.dtype == torch.int64 and list_off.numel() == K + 1
         assert ids.dtype == torch.int32 or ids.dtype == torch.uint32
-        self.tensors = (coarse, list_off, codes, ids, codebooks)  # keep alive
-        self.c = qadc_ivf_index(_ptr(coarse, torch.float32).value, _ptr(list_off).value,
-                                _ptr(codes, torch.uint8).value, _ptr(ids).value,
-                                _ptr(codebooks, torch.float32).value, d, m, K, codes.shape[0])
+        self.tensors = (coarse, list_off, codes, ids, codebooks, halves, cell_ids)  # keep alive
+        self.c = qadc_ivf_index(_ptr(coarse, torch.float32).value if coarse is not None else None,
+                                _ptr(list_off).value, _ptr(codes, torch.uint8).value, _ptr(ids).value,
+                                _ptr(codebooks, torch.float32).value, d, m, K, codes.shape[0], hp, cp, Kh)
         self.d, self.m, self.K, self.n = d, m, K, codes.shape[0]
 
 

@@ -82,6 +82,12 @@ int multi_index_assign(const float *, int, int, const float *, int64_t, int32_t 
 int multi_index_cells(const float *, int, int, float *, hipStream_t);
 size_t multi_index_workspace(int, int, int);
 int multi_index_probes(const float *, int, int, const float *, int, int, int32_t *, void *, size_t, hipStream_t);
+size_t multi_index_group_workspace(int64_t, int);
+int multi_index_group(const int32_t *, int64_t, int, int64_t, uint32_t *, int64_t *, uint32_t *, int64_t *, void *,
+                      size_t, hipStream_t);
+int multi_index_encode(const float *, int, const float *, int, int, const float *, int64_t, const int32_t *,
+                       const uint32_t *, int64_t, uint8_t *, hipStream_t);
+int multi_index_slots(const uint32_t *, int64_t, const int32_t *, int64_t, int32_t *, hipStream_t);
 int workspace_init(void *, size_t, hipStream_t);
 int pq_train(const float *, int64_t, int, int, int, const int64_t *, int, float *, void *, size_t,
              hipStream_t);
@@ -241,6 +247,30 @@ int qadc_multi_index_probes(const float *halves, int K, int d, const float *quer
 {
     return qadc::multi_index_probes(halves, K, d, queries, nq, nprobe, probes, workspace, workspace_bytes,
                                     (hipStream_t)stream);
+}
+
+size_t qadc_multi_index_group_workspace_bytes(int64_t n, int K) { return qadc::multi_index_group_workspace(n, K); }
+
+int qadc_multi_index_group(const int32_t *cells, int64_t n, int K, int64_t max_lists, uint32_t *cell_ids,
+                           int64_t *list_off, uint32_t *ids, int64_t *n_lists, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    return qadc::multi_index_group(cells, n, K, max_lists, cell_ids, list_off, ids, n_lists, workspace,
+                                   workspace_bytes, (hipStream_t)stream);
+}
+
+int qadc_multi_index_encode(const float *halves, int K, const float *codebooks, int d, int m, const float *x,
+                            int64_t n, const int32_t *cells, const uint32_t *ids, int64_t n_list,
+                            uint8_t *codes, void *stream)
+{
+    return qadc::multi_index_encode(halves, K, codebooks, d, m, x, n, cells, ids, n_list, codes,
+                                    (hipStream_t)stream);
+}
+
+int qadc_multi_index_slots(const uint32_t *cell_ids, int64_t n_lists, const int32_t *cells, int64_t count,
+                           int32_t *slots, void *stream)
+{
+    return qadc::multi_index_slots(cell_ids, n_lists, cells, count, slots, (hipStream_t)stream);
 }
 
 int qadc_profile_enable(int on) { return qadc::profile_enable(on); }

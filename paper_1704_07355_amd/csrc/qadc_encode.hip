@@ -7,6 +7,24 @@
 
 namespace qadc {
 
+// Where the centroids of the cells come from: a table of K rows, or the two half-quantizers of a
+// multi-index (cell c = i*Kh + j, centroid (halves[0][i], halves[1][j]); with m even a sub-vector
+// lies inside one half).  `off` = first dimension of the sub-vector.
+struct CellCentroids {
+    const float *coarse;
+    const float *halves;
+    int K;   // cells: ids outside [0, K) are invalid
+    int Kh;
+};
+
+__device__ inline const float *centroid_part(const CellCentroids &cc, int c, int off, int d)
+{
+    if (cc.coarse) return cc.coarse + (size_t)c * d + off;
+    const int dh = d >> 1;
+    const int i = c / cc.Kh, j = c - i * cc.Kh;
+    return off < dh ? cc.halves + (size_t)i * dh + off : cc.halves + ((size_t)cc.Kh + j) * dh + (off - dh);
+}
+
 // One thread per output byte.  ksub == 16: the byte holds components 2jb (low
 // nibble) and 2jb+1 (high nibble); ksub == 256: the byte is component jb.
 // Distances in float64 from the float32 differences' exact values, summed in increasing t with
@@ -15,7 +33,7 @@ namespace qadc {
 template <int KSUB>
 __global__ __launch_bounds__(256) void pq_encode_kernel(
     const float *__restrict__ codebooks, int d, int m, const float *__restrict__ x, int64_t n,
-    uint8_t *__restrict__ codes, const float *__restrict__ coarse, int K, const int32_t *__restrict__ cells,
+    uint8_t *__restrict__ codes, CellCentroids cc, const int32_t *__restrict__ cells,
     const uint32_t *__restrict__ ids, int64_t n_x)
 {
 #pragma clang fp contract(off)
@@ -26,19 +44,19 @@ __global__ __launch_bounds__(256) void pq_encode_kernel(
     const int64_t r = gid / row;
     const int jb = (int)(gid - r * row);
     const int64_t src = ids ? (int64_t)ids[r] : r;
-    const float *base = nullptr;
-    if (coarse) {  // an id or a cell out of range: a zero byte, no access
+    const bool resid = cc.coarse || cc.halves;
+    int c = 0;
+    if (resid) {  // an id or a cell out of range: a zero byte, no access
         if (src >= n_x) { codes[gid] = 0; return; }
-        const int c = cells[src];
-        if (c < 0 || c >= K) { codes[gid] = 0; return; }
-        base = coarse + (size_t)c * d;
+        c = cells[src];
+        if (c < 0 || c >= cc.K) { codes[gid] = 0; return; }
     }
     const int ncomp = (KSUB == 16) ? 2 : 1;
     unsigned out = 0;
     for (int h = 0; h < ncomp; ++h) {
         const int j = (KSUB == 16) ? 2 * jb + h : jb;
         const float *xs = x + src * d + (int64_t)j * dsub;
-        const float *bs = base ? base + (int64_t)j * dsub : nullptr;
+        const float *bs = resid ? centroid_part(cc, c, j * dsub, d) : nullptr;
         const float *cb = codebooks + (size_t)j * KSUB * dsub;
         double best = __builtin_inf();
         unsigned arg = 0;
@@ -97,7 +115,7 @@ __global__ __launch_bounds__(256) void pq_encode6_kernel(
 // increasing t.  Same arithmetic and result as pq_encode_kernel<16>.
 __global__ __launch_bounds__(256) void pq_encode16_lds_kernel(
     const float *__restrict__ codebooks, int d, int m, const float *__restrict__ x, int64_t n,
-    uint8_t *__restrict__ codes, const float *__restrict__ coarse, int K, const int32_t *__restrict__ cells,
+    uint8_t *__restrict__ codes, CellCentroids cc, const int32_t *__restrict__ cells,
     const uint32_t *__restrict__ ids, int64_t n_x)
 {
 #pragma clang fp contract(off)
@@ -115,19 +133,19 @@ __global__ __launch_bounds__(256) void pq_encode16_lds_kernel(
     const int64_t r = gid / row;
     const int jb = (int)(gid - r * row);
     const int64_t src = ids ? (int64_t)ids[r] : r;
-    const float *base = nullptr;
-    if (coarse) {
+    const bool resid = cc.coarse || cc.halves;
+    int c = 0;
+    if (resid) {
         if (src >= n_x) { codes[gid] = 0; return; }
-        const int c = cells[src];
-        if (c < 0 || c >= K) { codes[gid] = 0; return; }
-        base = coarse + (size_t)c * d;
+        c = cells[src];
+        if (c < 0 || c >= cc.K) { codes[gid] = 0; return; }
     }
     unsigned out = 0;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int j = 2 * jb + h;
         const float *xs = x + src * d + (int64_t)j * dsub;
-        const float *bs = base ? base + (int64_t)j * dsub : nullptr;
+        const float *bs = resid ? centroid_part(cc, c, j * dsub, d) : nullptr;
         double acc[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.0;
@@ -156,11 +174,11 @@ __global__ __launch_bounds__(256) void pq_encode16_lds_kernel(
 }
 
 static int encode_launch(const char *name, const float *codebooks, int d, int m, int ksub, const float *x,
-                         int64_t n, uint8_t *codes, const float *coarse, int K, const int32_t *cells,
+                         int64_t n, uint8_t *codes, CellCentroids cc, const int32_t *cells,
                          const uint32_t *ids, int64_t n_x, hipStream_t st)
 {
     if (m < 1 || d < 1 || d % m != 0 || (ksub != 16 && ksub != 64 && ksub != 256) || (ksub == 16 && (m & 1)) ||
-        (ksub == 64 && ((m & 3) || coarse)) || n < 0)
+        (ksub == 64 && ((m & 3) || cc.coarse || cc.halves)) || n < 0)
         return fail(QADC_EINVAL, "%s: unsupported d=%d m=%d ksub=%d", name, d, m, ksub);
     if (n == 0) return QADC_OK;
     if (!codebooks || !x || !codes) return fail(QADC_EINVAL, "%s: null pointer", name);
@@ -176,13 +194,13 @@ static int encode_launch(const char *name, const float *codebooks, int d, int m,
     if (blocks > 0x7fffffffll) return fail(QADC_EINVAL, "%s: n too large for one call", name);
     if (ksub == 16 && (size_t)d * 64 <= 65536)
         hipLaunchKernelGGL(pq_encode16_lds_kernel, dim3((unsigned)blocks), dim3(256), (size_t)d * 64, st,
-                           codebooks, d, m, x, n, codes, coarse, K, cells, ids, n_x);
+                           codebooks, d, m, x, n, codes, cc, cells, ids, n_x);
     else if (ksub == 16)
         hipLaunchKernelGGL(pq_encode_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, st, codebooks, d,
-                           m, x, n, codes, coarse, K, cells, ids, n_x);
+                           m, x, n, codes, cc, cells, ids, n_x);
     else
         hipLaunchKernelGGL(pq_encode_kernel<256>, dim3((unsigned)blocks), dim3(256), 0, st, codebooks,
-                           d, m, x, n, codes, coarse, K, cells, ids, n_x);
+                           d, m, x, n, codes, cc, cells, ids, n_x);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }
@@ -190,7 +208,8 @@ static int encode_launch(const char *name, const float *codebooks, int d, int m,
 int pq_encode(const float *codebooks, int d, int m, int ksub, const float *x, int64_t n,
               uint8_t *codes, hipStream_t st)
 {
-    return encode_launch("qadc_pq_encode", codebooks, d, m, ksub, x, n, codes, nullptr, 0, nullptr, nullptr, n, st);
+    return encode_launch("qadc_pq_encode", codebooks, d, m, ksub, x, n, codes, CellCentroids{nullptr, nullptr, 0, 0},
+                         nullptr, nullptr, n, st);
 }
 
 // codes[p] = enc(x[ids[p]] - coarse[cells[ids[p]]]) for the n_list storage positions p
@@ -199,7 +218,20 @@ int ivf_encode(const float *coarse, int K, const float *codebooks, int d, int m,
 {
     if (K < 1 || n < 0) return fail(QADC_EINVAL, "qadc_ivf_encode: K=%d n=%lld", K, (long long)n);
     if (n_list > 0 && (!coarse || !cells || !ids)) return fail(QADC_EINVAL, "qadc_ivf_encode: null pointer");
-    return encode_launch("qadc_ivf_encode", codebooks, d, m, 16, x, n_list, codes, coarse, K, cells, ids, n, st);
+    return encode_launch("qadc_ivf_encode", codebooks, d, m, 16, x, n_list, codes,
+                         CellCentroids{coarse, nullptr, K, 0}, cells, ids, n, st);
+}
+
+// codes[p] = enc(x[ids[p]] - (halves[0][c / Kh], halves[1][c % Kh])), c = cells[ids[p]]
+int multi_index_encode(const float *halves, int Kh, const float *codebooks, int d, int m, const float *x,
+                       int64_t n, const int32_t *cells, const uint32_t *ids, int64_t n_list, uint8_t *codes,
+                       hipStream_t st)
+{
+    if (Kh < 1 || Kh > 16384 || n < 0 || d < 2 || (d & 1))
+        return fail(QADC_EINVAL, "qadc_multi_index_encode: K=%d d=%d n=%lld", Kh, d, (long long)n);
+    if (n_list > 0 && (!halves || !cells || !ids)) return fail(QADC_EINVAL, "qadc_multi_index_encode: null pointer");
+    return encode_launch("qadc_multi_index_encode", codebooks, d, m, 16, x, n_list, codes,
+                         CellCentroids{nullptr, halves, Kh * Kh, Kh}, cells, ids, n, st);
 }
 
 }  // namespace qadc

@@ -257,8 +257,8 @@ void ivf_select_smallest(const float *dist, int rows, int K, int count, int32_t 
 // (cell id < 0) get +inf tables: nothing of them is ever scanned.
 __global__ __launch_bounds__(256) void ivf_build_luts_kernel(
     const float *__restrict__ codebooks, int d, int m, const float *__restrict__ queries,
-    const float *__restrict__ coarse, const int32_t *__restrict__ probes, int nprobe,
-    float *__restrict__ luts)
+    const float *__restrict__ coarse, const float *__restrict__ halves, const uint32_t *__restrict__ cell_ids,
+    int Kh, const int32_t *__restrict__ probes, int nprobe, float *__restrict__ luts)
 {
     extern __shared__ double yr[];  // [d]
     const int p = blockIdx.x, q = blockIdx.y;
@@ -270,8 +270,17 @@ __global__ __launch_bounds__(256) void ivf_build_luts_kernel(
         for (int e = threadIdx.x; e < entries; e += blockDim.x) out[e] = __builtin_inff();
         return;
     }
-    for (int t = threadIdx.x; t < d; t += blockDim.x)
-        yr[t] = (double)queries[(size_t)q * d + t] - (double)coarse[(size_t)cell * d + t];
+    if (coarse) {
+        for (int t = threadIdx.x; t < d; t += blockDim.x)
+            yr[t] = (double)queries[(size_t)q * d + t] - (double)coarse[(size_t)cell * d + t];
+    } else {  // list `cell` of a multi-index: the centroid is a pair of half-centroids
+        const int dh = d >> 1;
+        const unsigned id = cell_ids[cell];
+        const float *h0 = halves + (size_t)(id / (unsigned)Kh) * dh;
+        const float *h1 = halves + ((size_t)Kh + id % (unsigned)Kh) * dh;
+        for (int t = threadIdx.x; t < d; t += blockDim.x)
+            yr[t] = (double)queries[(size_t)q * d + t] - (double)(t < dh ? h0[t] : h1[t - dh]);
+    }
     __syncthreads();
     for (int e = threadIdx.x; e < entries; e += blockDim.x) {
         const int j = e >> 4;
@@ -961,7 +970,8 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     if (spl > 1024) spl = 1024;
     p->seed_per_list = knob_or(knobs().ivf_seed, 1) ? (int)spl : 0;
     p->l = scan_layout(p->W, R);
-    const size_t per_q = align_up((size_t)ix->K * 4, 256) + align_up((size_t)nprobe * 4, 256) +
+    const size_t kdist = ix->coarse ? (size_t)ix->K : 0;  // the Index step's distances
+    const size_t per_q = align_up(kdist * 4, 256) + align_up((size_t)nprobe * 4, 256) +
                          align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
                          align_up((size_t)nprobe * ix->m * 16, 256) + 256 + 4 + (size_t)p->W * 4 + p->l.stride;
     int64_t qb = (int64_t)((512ull << 20) / per_q);
@@ -970,7 +980,7 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     if (qb > IVF_MAP_MAXQ) qb = IVF_MAP_MAXQ;
     p->qb = (int)qb;
     size_t o = 0;
-    p->off_dist = o;   o += align_up((size_t)qb * ix->K * 4, 256);
+    p->off_dist = o;   o += align_up((size_t)qb * kdist * 4, 256);
     p->off_probes = o; o += align_up((size_t)qb * nprobe * 4, 256);
     p->off_luts = o;   o += align_up((size_t)qb * nprobe * ix->m * 16 * 4, 256);
     p->off_qluts = o;  o += align_up((size_t)qb * nprobe * ix->m * 16, 256);
@@ -1001,8 +1011,16 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
     if (!make_ivf_plan(ix, nq, nprobe, R, &p))
         return fail(QADC_EINVAL, "qadc_ivf_search: unsupported nq=%d nprobe=%d R=%d d=%d m=%d K=%d", nq,
                     nprobe, R, ix->d, ix->m, ix->K);
-    if (!ix->coarse || !ix->list_off || !ix->codes || !ix->ids || !ix->codebooks)
+    if (!ix->list_off || !ix->codes || !ix->ids || !ix->codebooks)
         return fail(QADC_EINVAL, "qadc_ivf_search: index has a null pointer");
+    if (!ix->coarse) {
+        if (!ix->halves || !ix->cell_ids || ix->Kh < 1 || ix->Kh > 16384 || (ix->d & 1))
+            return fail(QADC_EINVAL, "qadc_ivf_search: index has neither coarse centroids nor half-centroids with "
+                                     "cell ids (Kh=%d d=%d)", ix->Kh, ix->d);
+        if (!probes_in)
+            return fail(QADC_EINVAL, "qadc_ivf_search: an index without coarse centroids is searched with probes_in "
+                                     "(list numbers from qadc_multi_index_slots)");
+    }
     if (init < 1 || init > QADC_MAX_INIT || nbins < 1 || nbins > 255)
         return fail(QADC_EINVAL, "qadc_ivf_search: init=%d nbins=%d", init, nbins);
     if (((uintptr_t)ix->codes & 15) != 0)
@@ -1047,7 +1065,8 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         }
         // Tables
         launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
-               (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, probes, nprobe, luts);
+               (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids, ix->Kh,
+               probes, nprobe, luts);
         launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
                m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n);
         int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,

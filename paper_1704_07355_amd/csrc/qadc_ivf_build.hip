@@ -148,7 +148,7 @@ int ivf_assign(const float *coarse, int K, int d, const float *x, int64_t n, int
 int multi_index_assign(const float *halves, int K, int d, const float *x, int64_t n, int32_t *cells,
                        hipStream_t st)
 {
-    if (K < 1 || K > 4096 || d < 2 || (d & 1) || n < 0)
+    if (K < 1 || K > 16384 || d < 2 || (d & 1) || n < 0)
         return fail(QADC_EINVAL, "qadc_multi_index_assign: K=%d d=%d n=%lld", K, d, (long long)n);
     if (n == 0) return QADC_OK;
     if (!halves || !x || !cells) return fail(QADC_EINVAL, "qadc_multi_index_assign: null pointer");
@@ -202,18 +202,41 @@ __global__ void grp_zero_kernel(uint4 *p, size_t n16)
     for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
 }
 
-// one wavefront per part: cnt[part][cell] += 1
-__global__ __launch_bounds__(256) void grp_count_kernel(const int32_t *__restrict__ cells, int64_t n, int K,
-                                                        int64_t part, int P, unsigned *__restrict__ cnt)
+// What a grouping pass sorts by.  The vector met at place i of the pass is perm[i] (i itself
+// without perm); its cell is cells[that vector]; the key is the cell (mode 0), or, for the two
+// passes over the product cells c = hi*Kh + lo of a multi-index, lo (mode 1) and hi (mode 2).  A
+// cell outside [0, cell_end) has no key: the vector is left out.  n_dev, when set, holds the
+// number of places of the pass (what the pass before placed).
+struct GroupKeys {
+    const int32_t *cells;
+    const uint32_t *perm;
+    const int64_t *n_dev;
+    int mode, Kh, cell_end;
+};
+
+__device__ inline int group_key(const GroupKeys &g, int64_t i, uint32_t *vec)
+{
+    const uint32_t v = g.perm ? g.perm[i] : (uint32_t)i;
+    *vec = v;
+    const int c = g.cells[v];
+    if (c < 0 || c >= g.cell_end) return -1;
+    return g.mode == 0 ? c : g.mode == 1 ? c % g.Kh : c / g.Kh;
+}
+
+// one wavefront per part: cnt[part][key] += 1
+__global__ __launch_bounds__(256) void grp_count_kernel(GroupKeys g, int64_t n, int K, int64_t part, int P,
+                                                        unsigned *__restrict__ cnt)
 {
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (w >= P) return;
     const int lane = threadIdx.x & 63;
+    if (g.n_dev) n = min(n, *g.n_dev);
     const int64_t lo = (int64_t)w * part, hi = min(n, lo + part);
     unsigned *row = cnt + (size_t)w * K;
     for (int64_t i = lo + lane; i < hi; i += 64) {
-        const int c = cells[i];
-        if (c >= 0 && c < K) atomicAdd(&row[c], 1u);
+        uint32_t v;
+        const int c = group_key(g, i, &v);
+        if (c >= 0) atomicAdd(&row[c], 1u);
     }
 }
 
@@ -262,22 +285,23 @@ __global__ __launch_bounds__(1024) void grp_offsets_kernel(const unsigned *__res
     if (tid == 0) list_off[K] = (int64_t)carry_s;
 }
 
-// one wavefront per part, 64 vectors per step, in input order
-__global__ __launch_bounds__(256) void grp_place_kernel(const int32_t *__restrict__ cells, int64_t n, int K,
-                                                        int nbits, int64_t part, int P,
-                                                        unsigned *__restrict__ cnt,
+// one wavefront per part, 64 vectors per step, in the order of the pass
+__global__ __launch_bounds__(256) void grp_place_kernel(GroupKeys g, int64_t n, int K, int nbits, int64_t part,
+                                                        int P, unsigned *__restrict__ cnt,
                                                         const int64_t *__restrict__ list_off,
                                                         uint32_t *__restrict__ ids)
 {
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (w >= P) return;
     const int lane = threadIdx.x & 63;
+    if (g.n_dev) n = min(n, *g.n_dev);
     const int64_t lo = (int64_t)w * part, hi = min(n, lo + part);
     unsigned *row = cnt + (size_t)w * K;
     for (int64_t s = lo; s < hi; s += 64) {  // uniform over the wavefront
         const int64_t i = s + lane;
-        const int c = i < hi ? cells[i] : -1;
-        const bool valid = c >= 0 && c < K;
+        uint32_t v = 0;
+        const int c = i < hi ? group_key(g, i, &v) : -1;
+        const bool valid = c >= 0;
         unsigned long long peers = __ballot(valid);
         for (int b = 0; b < nbits; ++b) {
             const bool bit = (c >> b) & 1;
@@ -290,8 +314,30 @@ __global__ __launch_bounds__(256) void grp_place_kernel(const int32_t *__restric
             if (lane == leader) base = atomicAdd(&row[c], (unsigned)__popcll(peers));
             base = __shfl(base, leader);
             const int64_t pos = list_off[c] + base + rank_in_mask(peers);
-            ids[pos] = (uint32_t)i;
+            ids[pos] = v;
         }
+    }
+}
+
+// One grouping pass: list_off [K+1] and ids from the keys of `g`; cnt and size are scratch of the
+// plan's sizes and are cleared here.
+static void group_pass(const GroupKeys &g, int64_t n, int K, const GroupPlan &pl, char *ws, int64_t *list_off,
+                       uint32_t *ids, hipStream_t st)
+{
+    unsigned *cnt = (unsigned *)(ws + pl.cnt_off);
+    unsigned *size = (unsigned *)(ws + pl.size_off);
+    const size_t n16 = pl.total / 16;
+    hipLaunchKernelGGL(grp_zero_kernel, dim3((unsigned)std::min<size_t>(4096, ceil_div(n16, 256))), dim3(256), 0,
+                       st, (uint4 *)ws, n16);
+    const unsigned wg = (unsigned)ceil_div(pl.P, 4);
+    if (n > 0) hipLaunchKernelGGL(grp_count_kernel, dim3(wg), dim3(256), 0, st, g, n, K, pl.part, pl.P, cnt);
+    hipLaunchKernelGGL(grp_column_kernel, dim3((unsigned)ceil_div(K, 256)), dim3(256), 0, st, cnt, K, pl.P, size);
+    hipLaunchKernelGGL(grp_offsets_kernel, dim3(1), dim3(1024), 0, st, size, K, list_off);
+    if (n > 0) {
+        int nbits = 1;
+        while ((1ll << nbits) < K) ++nbits;
+        hipLaunchKernelGGL(grp_place_kernel, dim3(wg), dim3(256), 0, st, g, n, K, nbits, pl.part, pl.P, cnt,
+                           list_off, ids);
     }
 }
 
@@ -306,23 +352,152 @@ int ivf_group(const int32_t *cells, int64_t n, int K, int64_t *list_off, uint32_
     if (workspace_bytes < g.total || ((uintptr_t)workspace & 15))
         return fail(QADC_ENOMEM, "qadc_ivf_group: workspace of %zu bytes, %zu needed (16-byte aligned)",
                     workspace_bytes, g.total);
-    char *ws = (char *)workspace;
-    unsigned *cnt = (unsigned *)(ws + g.cnt_off);
-    unsigned *size = (unsigned *)(ws + g.size_off);
-    const size_t n16 = g.total / 16;
-    hipLaunchKernelGGL(grp_zero_kernel, dim3((unsigned)std::min<size_t>(4096, ceil_div(n16, 256))), dim3(256), 0,
-                       st, (uint4 *)ws, n16);
-    const unsigned wg = (unsigned)ceil_div(g.P, 4);
-    if (n > 0)
-        hipLaunchKernelGGL(grp_count_kernel, dim3(wg), dim3(256), 0, st, cells, n, K, g.part, g.P, cnt);
-    hipLaunchKernelGGL(grp_column_kernel, dim3((unsigned)ceil_div(K, 256)), dim3(256), 0, st, cnt, K, g.P, size);
-    hipLaunchKernelGGL(grp_offsets_kernel, dim3(1), dim3(1024), 0, st, size, K, list_off);
-    if (n > 0) {
-        int nbits = 1;
-        while ((1ll << nbits) < K) ++nbits;
-        hipLaunchKernelGGL(grp_place_kernel, dim3(wg), dim3(256), 0, st, cells, n, K, nbits, g.part, g.P, cnt,
-                           list_off, ids);
+    group_pass(GroupKeys{cells, nullptr, nullptr, 0, 1, K}, n, K, g, (char *)workspace, list_off, ids, st);
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+// ---------------------------------------------------- group, occupied cells of a multi-index
+//
+// K*K cells are too many for one counter each, and most are empty.  The vectors are sorted by cell
+// with two stable grouping passes over K keys -- by the second half's centroid, then, in that order,
+// by the first half's -- which leaves them ordered by (first, second) = by cell id, input order
+// kept inside a cell.  The places where the cell changes are the list boundaries: workgroups count
+// them per 1024 places, one workgroup turns the counts into running sums, and a second pass writes
+// each boundary's cell and place at its number.
+
+constexpr int MIG_BLOCK = 1024;  // places per workgroup of the boundary kernels, 4 per thread
+
+struct MiGroupPlan {
+    GroupPlan g;
+    int64_t nblocks;
+    size_t perm_off, offa_off, offb_off, bcnt_off, boff_off, total;
+};
+
+static bool make_mi_group_plan(int64_t n, int Kh, MiGroupPlan *p)
+{
+    if (Kh < 1 || Kh > 16384 || !make_group_plan(n, Kh, &p->g)) return false;
+    p->nblocks = std::max<int64_t>(1, ceil_div(n, MIG_BLOCK));
+    size_t o = align_up(p->g.total, 256);
+    p->perm_off = o; o += align_up((size_t)std::max<int64_t>(n, 1) * sizeof(uint32_t), 256);
+    p->offa_off = o; o += align_up((size_t)(Kh + 1) * sizeof(int64_t), 256);
+    p->offb_off = o; o += align_up((size_t)(Kh + 1) * sizeof(int64_t), 256);
+    p->bcnt_off = o; o += align_up((size_t)p->nblocks * sizeof(unsigned), 256);
+    p->boff_off = o; o += align_up((size_t)(p->nblocks + 1) * sizeof(int64_t), 256);
+    p->total = o;
+    return true;
+}
+
+size_t multi_index_group_workspace(int64_t n, int Kh)
+{
+    MiGroupPlan p;
+    return make_mi_group_plan(n, Kh, &p) ? p.total : 0;
+}
+
+// is place p the first of its cell?  (places at and beyond n_valid are no boundaries)
+__device__ inline bool mig_boundary(const int32_t *cells, const uint32_t *ids, int64_t p, int64_t n_valid, int *cell)
+{
+    if (p >= n_valid) return false;
+    const int c = cells[ids[p]];
+    *cell = c;
+    return p == 0 || cells[ids[p - 1]] != c;
+}
+
+__global__ __launch_bounds__(256) void mig_count_kernel(const int32_t *__restrict__ cells,
+                                                        const uint32_t *__restrict__ ids,
+                                                        const int64_t *__restrict__ n_valid_p,
+                                                        unsigned *__restrict__ bcnt)
+{
+    __shared__ unsigned wsum[4];
+    const int64_t n_valid = *n_valid_p;
+    const int64_t p0 = (int64_t)blockIdx.x * MIG_BLOCK + threadIdx.x * 4;
+    unsigned c = 0;
+    int cell;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c += mig_boundary(cells, ids, p0 + e, n_valid, &cell) ? 1u : 0u;
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) c += __shfl_xor(c, s);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) bcnt[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+__global__ __launch_bounds__(256) void mig_write_kernel(const int32_t *__restrict__ cells,
+                                                        const uint32_t *__restrict__ ids,
+                                                        const int64_t *__restrict__ n_valid_p,
+                                                        const int64_t *__restrict__ boff, int64_t nblocks,
+                                                        int64_t max_lists, uint32_t *__restrict__ cell_ids,
+                                                        int64_t *__restrict__ list_off,
+                                                        int64_t *__restrict__ n_lists)
+{
+    __shared__ unsigned wsum[4];
+    const int64_t n_valid = *n_valid_p;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t p0 = (int64_t)blockIdx.x * MIG_BLOCK + tid * 4;
+    bool flag[4];
+    int cell[4];
+    unsigned c = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        cell[e] = 0;
+        flag[e] = mig_boundary(cells, ids, p0 + e, n_valid, &cell[e]);
+        c += flag[e] ? 1u : 0u;
     }
+    unsigned inc = c;  // inclusive sum inside the wavefront
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        const unsigned o = __shfl_up(inc, s);
+        if (lane >= s) inc += o;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    unsigned before = inc - c;
+    for (int k = 0; k < wave; ++k) before += wsum[k];
+    int64_t slot = boff[blockIdx.x] + before;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (flag[e]) {
+            if (slot < max_lists) {
+                cell_ids[slot] = (uint32_t)cell[e];
+                list_off[slot] = p0 + e;
+            }
+            ++slot;
+        }
+    if (blockIdx.x == 0 && tid == 0) {
+        const int64_t L = boff[nblocks];
+        n_lists[0] = L;
+        list_off[min(L, max_lists)] = n_valid;
+    }
+}
+
+int multi_index_group(const int32_t *cells, int64_t n, int Kh, int64_t max_lists, uint32_t *cell_ids,
+                      int64_t *list_off, uint32_t *ids, int64_t *n_lists, void *workspace, size_t workspace_bytes,
+                      hipStream_t st)
+{
+    MiGroupPlan p;
+    if (!make_mi_group_plan(n, Kh, &p))
+        return fail(QADC_EINVAL, "qadc_multi_index_group: n=%lld (at most 2^32) K=%d (at most 16384)", (long long)n, Kh);
+    if (max_lists < std::min<int64_t>(n, (int64_t)Kh * Kh))
+        return fail(QADC_EINVAL, "qadc_multi_index_group: max_lists=%lld, min(n, K*K)=%lld needed", (long long)max_lists,
+                    (long long)std::min<int64_t>(n, (int64_t)Kh * Kh));
+    if (!list_off || !n_lists || !workspace || (n > 0 && (!cells || !ids || !cell_ids)))
+        return fail(QADC_EINVAL, "qadc_multi_index_group: null pointer");
+    if (workspace_bytes < p.total || ((uintptr_t)workspace & 15))
+        return fail(QADC_ENOMEM, "qadc_multi_index_group: workspace of %zu bytes, %zu needed (16-byte aligned)",
+                    workspace_bytes, p.total);
+    char *ws = (char *)workspace;
+    uint32_t *perm = (uint32_t *)(ws + p.perm_off);
+    int64_t *offa = (int64_t *)(ws + p.offa_off);
+    int64_t *offb = (int64_t *)(ws + p.offb_off);
+    unsigned *bcnt = (unsigned *)(ws + p.bcnt_off);
+    int64_t *boff = (int64_t *)(ws + p.boff_off);
+    const int cell_end = Kh * Kh;
+    group_pass(GroupKeys{cells, nullptr, nullptr, 1, Kh, cell_end}, n, Kh, p.g, ws, offa, perm, st);
+    group_pass(GroupKeys{cells, perm, offa + Kh, 2, Kh, cell_end}, n, Kh, p.g, ws, offb, ids, st);
+    hipLaunchKernelGGL(mig_count_kernel, dim3((unsigned)p.nblocks), dim3(256), 0, st, cells, ids, offb + Kh, bcnt);
+    hipLaunchKernelGGL(grp_offsets_kernel, dim3(1), dim3(1024), 0, st, bcnt, (int)p.nblocks, boff);
+    hipLaunchKernelGGL(mig_write_kernel, dim3((unsigned)p.nblocks), dim3(256), 0, st, cells, ids, offb + Kh, boff,
+                       p.nblocks, max_lists, cell_ids, list_off, n_lists);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }

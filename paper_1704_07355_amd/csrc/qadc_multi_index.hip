@@ -6,8 +6,9 @@
 // distance of a query to it is d1[i] + d2[j].  After the Index step everything is the inverted
 // index search over K*K cells (qadc_ivf_search with the probes given), so this file holds only
 //
-//   cells    the K*K centroids written out, the `coarse` of a qadc_ivf_index;
-//   probes   the nprobe cells with the smallest d1[i] + d2[j] without forming the K*K sums.
+//   cells    the K*K centroids written out, the `coarse` of a qadc_ivf_index (small K only);
+//   probes   the nprobe cells with the smallest d1[i] + d2[j] without forming the K*K sums;
+//   slots    the list number of a cell in an index that keeps lists for its occupied cells only.
 //
 // probes: 2K half distances per query (float32, summed in increasing component with one fused
 // multiply-add each, as the Index step of the inverted index), the T = min(nprobe, K) smallest
@@ -24,7 +25,7 @@ namespace qadc {
 
 void ivf_select_smallest(const float *dist, int rows, int K, int count, int32_t *out, hipStream_t st);
 
-constexpr int MI_MAX_K = 4096;       // K*K cells <= 2^24, the limit of the grouping
+constexpr int MI_MAX_K = 16384;      // K*K cells <= 2^28: a cell id fits an int32
 constexpr int MI_MAX_NPROBE = 256;   // as qadc_ivf_search
 constexpr int MI_MAX_PAIRS = 2048;   // sum over a of floor(256 / a) = 1546
 
@@ -178,6 +179,42 @@ int multi_index_probes(const float *halves, int K, int d, const float *queries, 
     ivf_select_smallest(hd, 2 * nq, K, p.T, top, st);
     launch(QADC_PROF_IVF_INDEX, mi_combine_kernel, dim3((unsigned)nq), dim3(256), 0, st, (const float *)hd,
            (const int32_t *)top, K, p.T, nprobe, probes);
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+// slots[e] = place of cells[e] in the ascending cell_ids, -1 when it is not there
+__global__ __launch_bounds__(256) void mi_slots_kernel(const uint32_t *__restrict__ cell_ids, int64_t n_lists,
+                                                       const int32_t *__restrict__ cells, int64_t count,
+                                                       int32_t *__restrict__ slots)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= count) return;
+    const int32_t c = cells[e];
+    int32_t out = -1;
+    if (c >= 0 && n_lists > 0) {
+        int64_t lo = 0, hi = n_lists - 1;  // first place whose cell is >= c
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (cell_ids[mid] < (uint32_t)c) lo = mid + 1; else hi = mid;
+        }
+        if (cell_ids[lo] == (uint32_t)c) out = (int32_t)lo;
+    }
+    slots[e] = out;
+}
+
+int multi_index_slots(const uint32_t *cell_ids, int64_t n_lists, const int32_t *cells, int64_t count,
+                      int32_t *slots, hipStream_t st)
+{
+    if (n_lists < 0 || n_lists > 0x7fffffffll || count < 0)
+        return fail(QADC_EINVAL, "qadc_multi_index_slots: n_lists=%lld count=%lld", (long long)n_lists,
+                    (long long)count);
+    if (count == 0) return QADC_OK;
+    if (!cells || !slots || (n_lists > 0 && !cell_ids)) return fail(QADC_EINVAL, "qadc_multi_index_slots: null pointer");
+    const int64_t grid = ceil_div(count, 256);
+    if (grid > 0x7fffffffll) return fail(QADC_EINVAL, "qadc_multi_index_slots: count too large for one call");
+    launch(QADC_PROF_IVF_INDEX, mi_slots_kernel, dim3((unsigned)grid), dim3(256), 0, st, cell_ids, n_lists, cells,
+           count, slots);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }

@@ -73,7 +73,7 @@ def test_multi_index_workspace_query():
     a = Q.qadc_multi_index_workspace_bytes(256, 256, 64)
     assert a >= 256 * 2 * 256 * 4 + 256 * 2 * 64 * 4
     assert Q.qadc_multi_index_workspace_bytes(256, 512, 64) > a
-    for bad in ((0, 1, 1), (4097, 1, 1), (16, 0, 1), (16, 1, 0), (16, 1, 257), (16, 70000, 4)):
+    for bad in ((0, 1, 1), (16385, 1, 1), (16, 0, 1), (16, 1, 0), (16, 1, 257), (16, 70000, 4)):
         assert Q.qadc_multi_index_workspace_bytes(*bad) == 0
 
 
@@ -89,3 +89,17 @@ def test_multi_index_argument_checks_need_no_gpu():
     assert L.qadc_multi_index_probes(None, 4, 8, None, 0, 4, None, None, 0, None) == Q.QADC_OK
     assert L.qadc_multi_index_probes(None, 4, 8, None, 3, 4, None, None, 0, None) == Q.QADC_EINVAL
     assert b"qadc_multi_index_probes" in L.qadc_last_error()
+
+
+def test_occupied_cell_entry_points_check_arguments_on_the_host():
+    import paper_1704_07355_amd as Q
+    L = Q.lib()
+    assert Q.qadc_multi_index_group_workspace_bytes(1000, 16384) > 1000 * 4
+    assert Q.qadc_multi_index_group_workspace_bytes(1000, 16385) == 0
+    assert L.qadc_multi_index_group(None, 10, 8, 5, None, None, None, None, None, 0, None) == Q.QADC_EINVAL   # capacity
+    assert b"max_lists" in L.qadc_last_error()
+    assert L.qadc_multi_index_group(None, 10, 8, 10, None, None, None, None, None, 0, None) == Q.QADC_EINVAL  # null
+    assert L.qadc_multi_index_slots(None, 0, None, 0, None, None) == Q.QADC_OK                                 # nothing to do
+    assert L.qadc_multi_index_slots(None, 4, None, 3, None, None) == Q.QADC_EINVAL
+    assert L.qadc_multi_index_encode(None, 0, None, 8, 4, None, 0, None, None, 0, None, None) == Q.QADC_EINVAL  # K < 1
+    assert L.qadc_multi_index_encode(None, 4, None, 7, 4, None, 0, None, None, 0, None, None) == Q.QADC_EINVAL  # odd d

@@ -93,7 +93,7 @@ def test_probe_errors(Q):
     halves = torch.zeros((2, 8, 4), dtype=torch.float32, device="cuda:0")
     y = torch.zeros((3, 8), dtype=torch.float32, device="cuda:0")
     assert Q.qadc_multi_index_workspace_bytes(8, 3, 300) == 0          # nprobe beyond the limit
-    assert Q.qadc_multi_index_workspace_bytes(5000, 3, 8) == 0         # K beyond the limit
+    assert Q.qadc_multi_index_workspace_bytes(20000, 3, 8) == 0        # K beyond the limit
     with pytest.raises(Q.QadcError):
         Q.qadc_multi_index_probes(halves, y, 300)
     ws = torch.zeros((16,), dtype=torch.uint8, device="cuda:0")
@@ -148,3 +148,154 @@ def test_search_over_a_multi_index(Q, O):
                                      probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
         assert np.array_equal(idx_np(got_ids)[iq], rep["ids"])
         assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"])
+
+
+# ------------------------------------------------------- lists for the occupied cells only
+
+def _group_want(cells, K):
+    """Stable sort by cell of the entries inside [0, K*K): (cell_ids, list_off, ids) written with numpy."""
+    valid = np.nonzero((cells >= 0) & (cells < K * K))[0]
+    order = valid[np.argsort(cells[valid], kind="stable")]
+    cell_ids, counts = np.unique(cells[valid], return_counts=True)
+    list_off = np.zeros(len(cell_ids) + 1, dtype=np.int64)
+    np.cumsum(counts, out=list_off[1:])
+    return cell_ids.astype(np.uint32), list_off, order.astype(np.uint32)
+
+
+@pytest.mark.parametrize("n,K,kind", [
+    (0, 8, "uniform"), (1, 8, "uniform"), (5_000, 64, "uniform"), (70_001, 7, "uniform"),
+    (300_000, 16384, "uniform"), (300_000, 16384, "clustered"), (40_000, 300, "invalid"),
+    (2_000_000, 1000, "clustered"),
+])
+def test_group_of_occupied_cells(Q, n, K, kind):
+    import torch
+    rng = np.random.default_rng(n + K)
+    if kind == "clustered":   # a few thousand occupied cells with skewed sizes, far apart in cell id
+        homes = rng.integers(0, K * K, size=3000)
+        cells = homes[np.minimum(rng.zipf(1.3, size=n) - 1, 2999)].astype(np.int32)
+    else:
+        cells = rng.integers(0, K * K, size=n).astype(np.int32)
+    if kind == "invalid":
+        cells[::7] = -1
+        cells[3::11] = K * K + 5
+    want_cells, want_off, want_ids = _group_want(cells, K)
+    assert Q.qadc_multi_index_group_workspace_bytes(n, K) > 0
+    g = to_gpu(cells) if n else torch.zeros((0,), dtype=torch.int32, device="cuda")
+    cell_ids, list_off, ids = Q.qadc_multi_index_group(g, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx_np(cell_ids), want_cells)
+    assert np.array_equal(list_off.cpu().numpy(), want_off)
+    assert np.array_equal(idx_np(ids), want_ids)
+
+
+def test_group_rejects_bad_arguments(Q):
+    import torch
+    assert Q.qadc_multi_index_group_workspace_bytes(10, 16385) == 0
+    assert Q.qadc_multi_index_group_workspace_bytes(-1, 16) == 0
+    cells = torch.zeros((100,), dtype=torch.int32, device="cuda")
+    with pytest.raises(Q.QadcError):
+        Q.qadc_multi_index_group(cells, 16385)
+    with pytest.raises(Q.QadcError):
+        Q.qadc_multi_index_group(cells, 16, workspace=torch.empty((16,), dtype=torch.uint8, device="cuda"))
+
+
+def test_slots_of_cells(Q, O):
+    import torch
+    rng = np.random.default_rng(4)
+    cell_ids = np.unique(rng.integers(0, 1 << 28, size=50_000)).astype(np.uint32)
+    cells = rng.integers(0, 1 << 28, size=(37, 64)).astype(np.int32)
+    cells[:, ::3] = rng.choice(cell_ids, size=cells[:, ::3].shape).astype(np.int32)   # present
+    cells[5, 7] = -1
+    cells[0, 0], cells[0, 1] = int(cell_ids[0]), int(cell_ids[-1])                     # both ends
+    got = Q.qadc_multi_index_slots(to_gpu(cell_ids.view(np.int32)), to_gpu(cells)).cpu().numpy()
+    assert np.array_equal(got, O.multi_index_slots(cell_ids, cells))
+    assert (got >= 0).sum() >= 37 * 22 and (got < 0).any()
+    none = Q.qadc_multi_index_slots(torch.zeros((0,), dtype=torch.int32, device="cuda"), to_gpu(cells))
+    assert (none.cpu().numpy() == -1).all()                                            # an index without lists
+
+
+def _sparse_case(O, K, dh, m, n, homes, seed):
+    from oracle import cref
+    rng = np.random.default_rng(seed)
+    d = 2 * dh
+    halves = make_halves(K, dh, seed)
+    home = rng.choice(K * K, size=homes, replace=False)
+    hc = np.concatenate([halves[0][home // K], halves[1][home % K]], axis=1)
+    x = (hc[rng.integers(0, homes, size=n)] + rng.normal(scale=10, size=(n, d))).astype(np.float32)
+    dsub = d // m
+    cells_h = O.multi_index_assign(x, halves)
+    cen = np.concatenate([halves[0][cells_h[:4000] // K], halves[1][cells_h[:4000] % K]], axis=1)
+    resid_sample = (x[:4000] - cen).astype(np.float32)
+    rows = rng.permutation(4000)[:16]
+    cb = np.stack([O.kmeans_lloyd(resid_sample[:, j * dsub:(j + 1) * dsub], rows, 3)[0] for j in range(m)])
+    # the oracle's index over the occupied cells, its encoding done by the plain-C twin
+    cell_ids, list_off, order = _group_want(cells_h, K)
+    cen = np.concatenate([halves[0][cells_h[order] // K], halves[1][cells_h[order] % K]], axis=1)
+    codes = cref.pq_encode((x[order] - cen).astype(np.float32), cb)
+    centroids = np.concatenate([halves[0][cell_ids // K], halves[1][cell_ids % K]], axis=1).astype(np.float32)
+    index = dict(cell_ids=cell_ids, centroids=centroids, list_off=list_off, codes=codes, ids=order)
+    return halves, x, cb, cells_h, index
+
+
+@pytest.mark.parametrize("K,m,homes", [(64, 16, 400), (300, 8, 20_000)])
+def test_search_over_occupied_cells(Q, O, K, m, homes):
+    """The multi-index at its usual shape -- far more product cells than lists: built on the GPU (assign ->
+    group -> encode against the half-centroids) it equals the oracle's index over the occupied cells, and a
+    search with the multi-index probes mapped to list numbers equals the oracle's search of that index."""
+    import torch
+    dh, n = 16, 30_000
+    d = 2 * dh
+    halves, x, cb, cells_h, index = _sparse_case(O, K, dh, m, n, homes, 31 + K)
+    small = O.multi_index_build_occupied(x[:3000], halves, cb)   # the oracle's own builder on a part
+    gh, gx, gcb = to_gpu(halves), to_gpu(x), to_gpu(cb)
+    cells = Q.qadc_multi_index_assign(gh, gx)
+    assert np.array_equal(cells.cpu().numpy(), cells_h)
+    cell_ids, list_off, ids = Q.qadc_multi_index_group(cells, K)
+    codes = Q.qadc_multi_index_encode(gh, gcb, gx, cells, ids)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx_np(cell_ids), index["cell_ids"])
+    assert np.array_equal(list_off.cpu().numpy(), index["list_off"])
+    assert np.array_equal(idx_np(ids), index["ids"])
+    assert np.array_equal(codes.cpu().numpy(), index["codes"])
+    assert len(index["cell_ids"]) < K * K // 4
+    # the same builder on the first 3000 vectors against the oracle's builder
+    c3 = cells[:3000].contiguous()
+    ci3, lo3, id3 = Q.qadc_multi_index_group(c3, K)
+    co3 = Q.qadc_multi_index_encode(gh, gcb, gx[:3000].contiguous(), c3, id3)
+    assert np.array_equal(idx_np(ci3), small["cell_ids"]) and np.array_equal(lo3.cpu().numpy(), small["list_off"])
+    assert np.array_equal(idx_np(id3), small["ids"]) and np.array_equal(co3.cpu().numpy(), small["codes"])
+
+    gix = Q.IvfIndex(None, list_off, codes, ids, gcb, halves=gh, cell_ids=cell_ids)
+    rng = np.random.default_rng(2)
+    nq, nprobe, R, init = 14, 48, 60, 300
+    queries = (x[rng.integers(0, n, size=nq)] + rng.normal(scale=5, size=(nq, d))).astype(np.float32)
+    gq = to_gpu(queries)
+    probes = Q.qadc_multi_index_probes(gh, gq, nprobe)
+    slots = Q.qadc_multi_index_slots(cell_ids, probes)
+    slots_h = slots.cpu().numpy()
+    assert np.array_equal(slots_h, O.multi_index_slots(index["cell_ids"], probes.cpu().numpy()))
+    assert (slots_h < 0).any() and ((slots_h >= 0).sum(axis=1) >= 1).all() and (slots_h >= 0).sum() >= 3 * nq
+    got_ids, dist, pr, qluts = Q.qadc_ivf_search(gix, gq, nprobe, R, init, probes_in=slots, debug=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(pr.cpu().numpy(), slots_h)
+    for iq in range(nq):
+        used = np.nonzero(slots_h[iq] >= 0)[0]
+        # whole search by the oracle on the occupied probes: tables within one quantization step
+        full = O.ivf_quick_adc_search(index, index["centroids"], cb, queries[iq], len(used), init, R,
+                                      probes=slots_h[iq][used])
+        ql = qluts[iq].cpu().numpy()
+        assert np.abs(ql[used].astype(int) - full["qluts"].astype(int)).max() <= 1
+        # integer part replayed on the GPU's tables: bit-exact
+        rep = O.ivf_quick_adc_search(index, index["centroids"], cb, queries[iq], len(used), init, R,
+                                     probes=slots_h[iq][used], qluts=ql[used])
+        assert np.array_equal(idx_np(got_ids)[iq], rep["ids"])
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"])
+
+
+def test_index_without_centroids_needs_probes(Q, O):
+    import torch
+    halves, x, cb, cells_h, index = _sparse_case(O, 32, 8, 8, 5000, 50, 3)
+    gix = Q.IvfIndex(None, to_gpu(index["list_off"]), to_gpu(index["codes"]), to_gpu(index["ids"].view(np.int32)),
+                     to_gpu(cb), halves=to_gpu(halves), cell_ids=to_gpu(index["cell_ids"].view(np.int32)))
+    with pytest.raises(Q.QadcError):
+        Q.qadc_ivf_search(gix, to_gpu(x[:3]), 4, 10, 100)
