@@ -328,6 +328,71 @@ def build_ivf_index(Q, torch, np, n, K, m, n_queries, dev, d=128, sigma=18.0):
     return index, sizes, queries
 
 
+def multi_index_usual_size(Q, torch, coarse, codes, cb, queries, last, nb, nprobe, R, init, dev, d, kh=16384):
+    """The same codes under a multi-index of kh x kh product cells with lists for the occupied cells only
+    (2^28 cells for 10^9 vectors: most are empty, lists are short).  Half-centroids are halves of vectors
+    drawn like the coarse centroids; a stored vector's cell is one of the 4 closest cells of a point drawn
+    around a coarse centroid, as the queries are, so the probes of a query meet occupied cells.  Times the grouping (database side) and one batch of queries
+    through Index (probes, then list numbers) and qadc_ivf_search."""
+    from workloads import MixtureSpec, SEED_TRAIN
+    from workloads.mixture_torch import mixture_vectors_torch
+    n = codes.shape[0]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    # half-centroids: the halves of vectors drawn like the coarse centroids (rows after theirs)
+    hv = mixture_vectors_torch(MixtureSpec(d=d), SEED_TRAIN, 1 << 20, kh, dev)
+    halves = torch.stack([hv[:, :d // 2], hv[:, d // 2:]]).contiguous()
+    # a pool of cells around the coarse centroids, where the queries are drawn too
+    chunk = 8192
+    mi_ws = torch.empty((Q.qadc_multi_index_workspace_bytes(kh, chunk, 4),), dtype=torch.uint8, device=dev)
+    pool = []
+    for s in range(0, max(chunk, min(1 << 20, n // 256)), chunk):
+        home = torch.randint(0, coarse.shape[0], (chunk,), generator=gen, device=dev)
+        pts = (coarse[home] + 18.0 * torch.randn((chunk, d), generator=gen, device=dev)).contiguous()
+        pool.append(Q.qadc_multi_index_probes(halves, pts, 4, workspace=mi_ws).reshape(-1).clone())
+    pool = torch.cat(pool)
+    cells = torch.empty((n,), dtype=torch.int32, device=dev)
+    for s in range(0, n, 1 << 26):
+        cnt = min(1 << 26, n - s)
+        cells[s:s + cnt] = pool[torch.randint(0, pool.numel(), (cnt,), generator=gen, device=dev)]
+    del mi_ws
+    ws = torch.empty((Q.qadc_multi_index_group_workspace_bytes(n, kh),), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    cell_ids, list_off, ids = Q.qadc_multi_index_group(cells, kh, workspace=ws)
+    torch.cuda.synchronize()
+    t_group = time.time() - t0
+    del ws, cells
+    index = Q.IvfIndex(None, list_off, codes, ids, cb, halves=halves, cell_ids=cell_ids)
+    qb = queries[last * nb:(last + 1) * nb]
+    mi_ws = torch.empty((Q.qadc_multi_index_workspace_bytes(kh, nb, nprobe),), dtype=torch.uint8, device=dev)
+    probes = torch.empty((nb, nprobe), dtype=torch.int32, device=dev)
+    sws = Q.qadc_workspace_init(torch.empty(Q.qadc_ivf_workspace_bytes(index, nb, nprobe, R), dtype=torch.uint8,
+                                            device=dev))
+
+    def batch():
+        Q.qadc_multi_index_probes(halves, qb, nprobe, workspace=mi_ws, out=probes)
+        slots = Q.qadc_multi_index_slots(cell_ids, probes, out=probes)
+        return slots, Q.qadc_ivf_search(index, qb, nprobe, R, init, probes_in=slots, workspace=sws)
+
+    batch()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        slots, _ = batch()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 3
+    used = slots.clamp(min=0).long()
+    lens = (list_off[used + 1] - list_off[used]) * (slots >= 0)
+    sizes = list_off[1:] - list_off[:-1]
+    return {"half_centroids": kh, "cells": kh * kh, "occupied_cells": int(cell_ids.numel()),
+            "largest_list": int(sizes.max().item()), "grouping_s": round(t_group, 3),
+            "occupied_probes_per_query": round(float((slots >= 0).sum().item()) / nb, 2),
+            "codes_scanned_per_query": round(float(lens.sum().item()) / nb, 1),
+            "ms_per_batch": round(ms, 3), "queries_per_s": round(nb / (ms * 1e-3), 1)}
+
+
 def run_ivf(args):
     """Config 4: IVF + Quick ADC.  A step = one batch of queries through qadc_ivf_search.
 
@@ -410,6 +475,10 @@ def run_ivf(args):
         torch.cuda.synchronize()
         multi_index = {"half_centroids": kh, "cells": K, "index_step_ms_per_batch": round(m0.elapsed_time(m1) / 10, 4),
                        "inverted_index_step_ms_per_batch": round(phase["index"], 4)}
+
+    if multi_index is not None:
+        multi_index["usual_size"] = multi_index_usual_size(Q, torch, coarse, codes, cb, queries, last, nb, nprobe, R,
+                                                           init, dev, args.d)
 
     cpu = None
     if args.cpu_queries > 0:

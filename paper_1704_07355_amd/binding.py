@@ -478,7 +478,8 @@ class IvfIndex:
         assert codebooks.shape[1] == 16 and codes.shape[1] == m // 2
         assert list_off.dtype == torch.int64 and list_off.numel() == K + 1
         assert ids.dtype == torch.int32 or ids.dtype == torch.uint32
-        self.tensors = (coarse, list_off, codes, ids, codebooks, halves, cell_ids)  # keep alive
+        self.tensors = (coarse, list_off, codes, ids, codebooks)  # keep alive
+        self.half_tensors = (halves, cell_ids)
         self.c = qadc_ivf_index(_ptr(coarse, torch.float32).value if coarse is not None else None,
                                 _ptr(list_off).value, _ptr(codes, torch.uint8).value, _ptr(ids).value,
                                 _ptr(codebooks, torch.float32).value, d, m, K, codes.shape[0], hp, cp, Kh)
