@@ -55,6 +55,8 @@ void knobs_refresh()
     k.ivf_seed = env_knob("QADC_IVF_SEED");
     k.ivf_units = env_knob("QADC_IVF_UNITS");
     k.ivf_seed_parts = env_knob("QADC_IVF_SEED_PARTS");
+    k.ivf_shared = env_knob("QADC_IVF_SHARED");
+    k.ivf_shared_wgs = env_knob("QADC_IVF_SHARED_WGS");
 }
 
 int build_luts(const float *, int, int, int, const float *, const float *, int, float *, hipStream_t);

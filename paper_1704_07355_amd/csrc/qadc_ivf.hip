@@ -10,6 +10,8 @@
 // query's lists are cut into units of at most IVF_UNIT codes; a query gets workgroups in
 // proportion to its number of units, each taking a contiguous range of them.
 
+#include <algorithm>
+
 #include "qadc_scan_common.h"
 
 namespace qadc {
@@ -485,9 +487,11 @@ constexpr unsigned IVF_NO_WG = 0xffffffffu;
 // (work in proportion to the lists it probes); the queries with the most work come first in the
 // grid, so that the longest-running workgroups start first.  wgmap[b] = q << 12 | g for workgroup
 // b of the grid, IVF_NO_WG beyond the last one.  One workgroup; nb <= IVF_MAP_MAXQ, Wmax <= 4096.
+// With `only`, a query whose entry is zero gets no workgroup.
 __global__ __launch_bounds__(IVF_MAP_NT) void ivf_wgmap_kernel(const unsigned *__restrict__ qunits, int nb,
                                                               int units_per_wg, int Wmax,
-                                                              unsigned *__restrict__ wgmap)
+                                                              unsigned *__restrict__ wgmap,
+                                                              const unsigned *__restrict__ only)
 {
     __shared__ unsigned un[IVF_MAP_MAXQ];      // units of query q
     __shared__ unsigned byrank[IVF_MAP_MAXQ];  // query at rank r
@@ -515,7 +519,8 @@ __global__ __launch_bounds__(IVF_MAP_NT) void ivf_wgmap_kernel(const unsigned *_
     // exclusive running sum of the workgroup counts in rank order
     for (int r0 = 0; r0 < nb; r0 += IVF_MAP_NT) {
         const int r = r0 + tid;
-        const unsigned w = r < nb ? wgs_of(un[byrank[r]]) : 0u;
+        // (`only`: the queries that are scanned by this launch at all)
+        const unsigned w = (r < nb && (!only || only[byrank[r]])) ? wgs_of(un[byrank[r]]) : 0u;
         unsigned inc = w;
         const int l = lane_id();
 #pragma unroll
@@ -937,6 +942,20 @@ __global__ void ivf_take_probes_kernel(const int32_t *__restrict__ in, int nprob
     probes[i] = cell;
 }
 
+// The control words of a batch -- the histograms of the control blocks and the counts of the report
+// regions -- are cleared at the start of every call: calls of different shapes lay the workspace out
+// differently, and what one call left as table data may lie where the next one keeps its counts.
+__global__ __launch_bounds__(256) void ivf_clear_kernel(char *__restrict__ ws, size_t ws_stride, size_t counts_off,
+                                                        int W, size_t countsA_off)
+{
+    char *base = ws + (size_t)blockIdx.x * ws_stride;
+    unsigned *gh = reinterpret_cast<unsigned *>(base);  // ScanHeader::ghist comes first
+    for (int i = threadIdx.x; i < GH_REP * 256; i += 256) gh[i] = 0;
+    unsigned *counts = reinterpret_cast<unsigned *>(base + counts_off);
+    for (int i = threadIdx.x; i < W; i += 256) counts[i] = 0;
+    if (countsA_off && threadIdx.x == 0) *reinterpret_cast<unsigned *>(base + countsA_off) = 0;
+}
+
 // ------------------------------------------------------------------- host
 
 int quantize_luts(int, const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
@@ -947,7 +966,22 @@ struct IvfPlan {
     int seed_per_list;  // codes sampled per probed list for the bound of the scan (0: no seed kernel)
     ScanLayout l;
     size_t off_dist, off_probes, off_luts, off_qluts, off_qmax, off_units, off_map, off_scan, bytes;
+    // shared-list scan of large batches (ivf_shared_scan): a second report region per query, the
+    // pairs sorted by cell and their offsets
+    bool shared;
+    int shared_wgs;
+    size_t stride, countsA_off, listsA_off;
+    size_t off_paircnt, off_pairoff, off_item0, off_item1, off_pairs, off_taus, off_flags;
 };
+
+constexpr int IVF_SHARED_PITCH = MERGE_CAP;   // keys of a query's region: what the merge kernel holds in LDS
+constexpr int IVF_SHARED_MIN_Q = 256;         // smallest batch scanned list by list
+constexpr int IVF_SHARED_MAX_R = 128;         // the region must hold a few dozen times R keys
+constexpr int IVF_SHARED_MAX_K = 1 << 18;     // one workgroup sums the per-cell counts
+
+int ivf_shared_scan(int, const int64_t *, const uint8_t *, int64_t, int, const int32_t *, int, int, const uint8_t *,
+                    int, char *, size_t, size_t, size_t, int, unsigned *, unsigned *, unsigned *, unsigned *,
+                    unsigned *, unsigned *, unsigned *, int, hipStream_t);
 
 static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, IvfPlan *p)
 {
@@ -970,10 +1004,24 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     if (spl > 1024) spl = 1024;
     p->seed_per_list = knob_or(knobs().ivf_seed, 1) ? (int)spl : 0;
     p->l = scan_layout(p->W, R);
+    // large batches over a moderate number of cells: every list is scanned once for all the queries
+    // that probe it (QADC_IVF_SHARED=1 / 0 forces / forbids it)
+    const int shared_knob = knobs().ivf_shared;
+    p->shared = R <= IVF_SHARED_MAX_R && ix->K <= IVF_SHARED_MAX_K && p->seed_per_list > 0 && ix->m <= 64 &&
+                (shared_knob >= 0 ? shared_knob != 0 : nq >= IVF_SHARED_MIN_Q);
+    p->shared_wgs = std::max(1, std::min(65535, knob_or(knobs().ivf_shared_wgs, 4096)));
+    p->stride = p->l.stride;
+    p->countsA_off = p->listsA_off = 0;
+    if (p->shared) {
+        p->countsA_off = p->l.stride;
+        p->listsA_off = p->countsA_off + 256;
+        p->stride = p->listsA_off + align_up((size_t)IVF_SHARED_PITCH * sizeof(uint64_t), 256);
+    }
     const size_t kdist = ix->coarse ? (size_t)ix->K : 0;  // the Index step's distances
     const size_t per_q = align_up(kdist * 4, 256) + align_up((size_t)nprobe * 4, 256) +
                          align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
-                         align_up((size_t)nprobe * ix->m * 16, 256) + 256 + 4 + (size_t)p->W * 4 + p->l.stride;
+                         align_up((size_t)nprobe * ix->m * 16, 256) + 256 + 4 + (size_t)p->W * 4 + p->stride +
+                         (p->shared ? (size_t)nprobe * 4 + 8 : 0);
     int64_t qb = (int64_t)((512ull << 20) / per_q);
     if (qb < 1) qb = 1;
     if (qb > nq) qb = nq;
@@ -987,7 +1035,18 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->off_qmax = o;   o += align_up((size_t)qb * 4, 256);
     p->off_units = o;  o += align_up((size_t)qb * 4, 256);
     p->off_map = o;    o += align_up((size_t)qb * p->W * 4, 256);
-    p->off_scan = o;   o += p->l.stride * (size_t)qb;
+    p->off_scan = o;   o += p->stride * (size_t)qb;
+    p->off_paircnt = p->off_pairoff = p->off_item0 = p->off_item1 = p->off_pairs = p->off_taus = p->off_flags = 0;
+    if (p->shared) {
+        const size_t kk = align_up(((size_t)ix->K + 1) * 4, 256);
+        p->off_paircnt = o; o += kk;
+        p->off_pairoff = o; o += kk;
+        p->off_item0 = o;   o += kk;
+        p->off_item1 = o;   o += kk;
+        p->off_pairs = o;   o += align_up((size_t)qb * nprobe * 4, 256);
+        p->off_taus = o;    o += align_up((size_t)qb * 4, 256);
+        p->off_flags = o;   o += align_up((size_t)qb * 4, 256);
+    }
     p->bytes = o;
     return true;
 }
@@ -1079,16 +1138,41 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         // a few queries: their lists are sampled by several workgroups each
         const int seed_parts_env = knob_or(knobs().ivf_seed_parts, 0);
         const int seed_parts = seed_parts_env > 0 ? min(seed_parts_env, nprobe) : nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
-        launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap);
+        launch(QADC_PROF_SEED, ivf_clear_kernel, dim3(nb), dim3(256), 0, st, scan_ws, p.stride, p.l.counts_off, p.W,
+               p.countsA_off);
+        unsigned *flags = p.shared ? (unsigned *)(ws + p.off_flags) : nullptr;
+#define QADC_IVF_SEED_CASE(B_)                                                                          \
+    case B_:                                                                                           \
+        launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb, seed_parts), dim3(IVF_SEED_NT), 0, st,    \
+               ix->list_off, ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws,     \
+               p.stride, ix->n);                                                                       \
+        break;
+        if (p.seed_per_list > 0) {
+            switch (m / 2) {
+                QADC_IVF_SEED_CASE(4)
+                QADC_IVF_SEED_CASE(8)
+                QADC_IVF_SEED_CASE(16)
+                QADC_IVF_SEED_CASE(32)
+            }
+        }
+#undef QADC_IVF_SEED_CASE
+        if (p.shared) {
+            // every list once for all the queries that probe it; the queries it leaves flagged are
+            // the only ones that get workgroups of the per-query kernel below
+            rc = ivf_shared_scan(m / 2, ix->list_off, ix->codes, ix->n, K, probes, nb, nprobe, qluts, R, scan_ws,
+                                 p.stride, p.countsA_off, p.listsA_off, IVF_SHARED_PITCH,
+                                 (unsigned *)(ws + p.off_paircnt), (unsigned *)(ws + p.off_pairoff),
+                                 (unsigned *)(ws + p.off_item0), (unsigned *)(ws + p.off_item1),
+                                 (unsigned *)(ws + p.off_pairs), (unsigned *)(ws + p.off_taus), flags, p.shared_wgs,
+                                 st);
+            if (rc != QADC_OK) return rc;
+        }
+        launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap,
+               (const unsigned *)flags);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
-        if (p.seed_per_list > 0)                                                                      \
-            launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb, seed_parts), dim3(IVF_SEED_NT), 0, st,    \
-                   ix->list_off,                                                                       \
-                   ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws, p.l.stride,   \
-                   ix->n);                                                                             \
         launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
-               ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, wgmap, scan_ws, p.l.stride,          \
+               ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, wgmap, scan_ws, p.stride,            \
                p.l.counts_off, p.l.lists_off);                                                        \
         break;
         switch (m / 2) {
@@ -1099,9 +1183,9 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         }
 #undef QADC_IVF_CASE
         uint32_t *oi = out_ids + (size_t)q0 * R;
-        rc = launch_merge<uint8_t, 5>(nb, st, scan_ws, p.l.stride, p.l.counts_off, p.l.lists_off, p.W,
-                                      (unsigned)R, R, (uint8_t)nbins, oi, out_dist + (size_t)q0 * R, (size_t)0,
-                                      (size_t)0, 0, 0, (unsigned *)nullptr);
+        rc = launch_merge<uint8_t, 5>(nb, st, scan_ws, p.stride, p.l.counts_off, p.l.lists_off, p.W,
+                                      (unsigned)R, R, (uint8_t)nbins, oi, out_dist + (size_t)q0 * R, p.countsA_off,
+                                      p.listsA_off, p.shared ? 1 : 0, p.shared ? IVF_SHARED_PITCH : 0, flags);
         if (rc != QADC_OK) return rc;
         const int64_t total = (int64_t)nb * R;
         launch(QADC_PROF_MERGE, ivf_gather_ids_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0,

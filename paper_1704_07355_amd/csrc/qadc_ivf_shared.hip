@@ -1,0 +1,405 @@
+// Shared-list form of the inverted-index scan (Section 2.3 of the paper with the tables of
+// Section 3.3) for large batches on gfx950.
+//
+// A batch of a few thousand queries probes the same inverted lists over and over: with 4096
+// queries x 64 cells over 65536 lists every code of a popular list is wanted by tens to hundreds
+// of queries.  Scanning query by query reads such a list once per query and is bound by memory;
+// here the (query, cell) pairs of the batch are sorted by cell and every list is scanned once for
+// all the pairs that probe it, 32 pairs at a time, on the matrix units: the sum of a code for a
+// pair is a one-hot row times the pair's tables (see scan_u8_mfma_kernel for the operand layout),
+// so 32 codes x 32 pairs cost m/4 sparse matrix instructions, and the result of a code byte
+// fetched from memory is used 32 times.  Every pair has its own tables (the residual of its
+// query against its cell); the bound a sum must meet is its query's.
+//
+// Selection.  A query's bound comes from the seed kernel (a few dozen codes per probed list) and
+// is loose for a query whose lists are long; sums at or below it are appended to the query's
+// region of the workspace with one atomic per (pair, chunk).  To keep that region small the scan
+// runs in two parts: first the leading 1/16 of every list, after which the R-th smallest sum
+// found so far replaces the query's bound (a sample in proportion to what the query scans,
+// whatever the sizes of its lists), then the rest.  A query whose region still overflows, or that
+// has no bound at all, is flagged and redone by the per-query kernel; the merge kernel takes
+// whichever report is complete.  Results do not depend on the route: every code whose sum is at
+// or below a valid bound is reported, and the merge orders by (sum, storage position).
+
+#include "qadc_scan_common.h"
+
+namespace qadc {
+
+constexpr unsigned IVFS_NONE = 0xffffffffu;
+constexpr int IVFS_CHUNK = 8192;   // codes of a list per work item, at most (relative positions fit 24 bits)
+constexpr int IVFS_LC = 64;        // keys a wavefront holds per pair before it writes them out
+
+// codes of the leading part of a list of n codes: 1/16, whole 32-code steps, at least one
+__host__ __device__ inline long long ivfs_lead(long long n)
+{
+    long long s = ((n + 15) / 16 + 31) / 32 * 32;
+    return s < n ? s : n;
+}
+
+__global__ __launch_bounds__(256) void ivfs_zero_kernel(unsigned *__restrict__ p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// One thread per (query, probe slot): counts the pairs of every cell; the thread of a query's
+// first slot copies the query's bound (IVFS_NONE and a flag when the seed kernel found none).
+__global__ __launch_bounds__(256) void ivfs_count_kernel(const int32_t *__restrict__ probes, int nprobe,
+                                                         int64_t npairs, int K, const char *__restrict__ ws,
+                                                         size_t ws_stride, unsigned *__restrict__ pair_cnt,
+                                                         unsigned *__restrict__ taus, unsigned *__restrict__ flags)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= npairs) return;
+    const int cell = probes[i];
+    if (cell >= 0 && cell < K) atomicAdd(&pair_cnt[cell], 1u);
+    if (i % nprobe == 0) {
+        const int64_t q = i / nprobe;
+        const unsigned tau1 = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ghist[0][0];
+        taus[q] = tau1 ? tau1 - 1u : IVFS_NONE;
+        if (!tau1) flags[q] = 1u;
+    }
+}
+
+// One workgroup: exclusive running sums over the cells of (pairs, work items of the leading
+// parts, work items of the rest).  A cell with P pairs and n codes is ceil(P / qw) sets of pairs
+// times ceil(len / IVFS_CHUNK) chunks of either part.
+__global__ __launch_bounds__(1024) void ivfs_offsets_kernel(const unsigned *__restrict__ pair_cnt,
+                                                            const int64_t *__restrict__ list_off, int K,
+                                                            int64_t n_total, int qw,
+                                                            unsigned *__restrict__ pair_off,
+                                                            unsigned *__restrict__ item_off0,
+                                                            unsigned *__restrict__ item_off1)
+{
+    __shared__ unsigned wsum[3][16];
+    __shared__ unsigned carry[3];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 3) carry[tid] = 0;
+    __syncthreads();
+    for (int c0 = 0; c0 < K; c0 += 1024) {
+        const int c = c0 + tid;
+        unsigned v[3] = {0, 0, 0};
+        if (c < K) {
+            const unsigned P = pair_cnt[c];
+            long long l = list_off[c], h = list_off[c + 1];
+            if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: no work
+            const long long n = h - l, s = ivfs_lead(n);
+            const unsigned sets = (P + (unsigned)qw - 1u) / (unsigned)qw;
+            v[0] = P;
+            v[1] = sets * (unsigned)((s + IVFS_CHUNK - 1) / IVFS_CHUNK);
+            v[2] = sets * (unsigned)((n - s + IVFS_CHUNK - 1) / IVFS_CHUNK);
+        }
+        unsigned inc[3] = {v[0], v[1], v[2]};
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const unsigned o = __shfl_up(inc[k], s);
+                if (lane >= s) inc[k] += o;
+            }
+        }
+        if (lane == 63) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) wsum[k][wave] = inc[k];
+        }
+        __syncthreads();
+        unsigned before[3];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            before[k] = carry[k];
+            for (int w = 0; w < wave; ++w) before[k] += wsum[k][w];
+        }
+        if (c < K) {
+            pair_off[c] = before[0] + inc[0] - v[0];
+            item_off0[c] = before[1] + inc[1] - v[1];
+            item_off1[c] = before[2] + inc[2] - v[2];
+        }
+        __syncthreads();
+        if (tid == 1023) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) carry[k] = before[k] + inc[k];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        pair_off[K] = carry[0];
+        item_off0[K] = carry[1];
+        item_off1[K] = carry[2];
+    }
+}
+
+// One thread per pair: its place among the pairs of its cell (in no particular order: each pair's
+// finds go to its own query).  Takes the counts back down to zero.
+__global__ __launch_bounds__(256) void ivfs_place_kernel(const int32_t *__restrict__ probes, int64_t npairs, int K,
+                                                         const unsigned *__restrict__ pair_off,
+                                                         unsigned *__restrict__ pair_cnt,
+                                                         unsigned *__restrict__ pairs)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= npairs) return;
+    const int cell = probes[i];
+    if (cell < 0 || cell >= K) return;
+    const unsigned old = atomicSub(&pair_cnt[cell], 1u);
+    pairs[pair_off[cell] + old - 1u] = (unsigned)i;
+}
+
+typedef int v2i_t __attribute__((ext_vector_type(2)));
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v8i_t __attribute__((ext_vector_type(8)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+
+// One wavefront per workgroup; the work items (cell, set of 32 pairs, chunk of one part of the
+// cell's list) are dealt to the workgroups in turn.  The arithmetic of an item is that of
+// scan_u8_mfma_kernel with one group of 32 "queries" = pairs.
+template <int B>
+__global__ __launch_bounds__(64) void ivfs_scan_kernel(
+    int part, const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int64_t n_total, int K,
+    const unsigned *__restrict__ pair_off, const unsigned *__restrict__ item_off,
+    const unsigned *__restrict__ pairs, int nprobe, const uint8_t *__restrict__ qluts,
+    const unsigned *__restrict__ taus, char *__restrict__ ws, size_t ws_stride, size_t countsA_off,
+    size_t listsA_off, int pitchA, unsigned *__restrict__ flags)
+{
+    constexpr int WPC = B / 4;   // 32-bit words per code
+    constexpr int QW = 32;       // pairs per wavefront
+    constexpr int LC = IVFS_LC;
+    constexpr int SUB = 2;       // 32-code steps per load
+    constexpr int SHIFT = 128 * 2 * B;  // the matrix units multiply signed bytes: entries go in minus 128
+    constexpr int NP = B / 2;    // pairs of code bytes = instructions per 32-code step
+    __shared__ unsigned keys[QW][LC];
+    __shared__ unsigned cnt[QW];
+    __shared__ v4i_t nibval[16];
+    __shared__ v4i_t nibpos[16];
+
+    const int l = threadIdx.x;
+    const int row = l & 31, half = l >> 5;
+    if (l < QW) cnt[l] = 0;
+    if (l < 16) {
+        const int pr = l >> 2, pos = l & 3;
+        const int bits = (0xcccc & ~(15 << (4 * pr))) | ((pos | ((pos == 3 ? 2 : 3) << 2)) << (4 * pr));
+        nibval[l] = v4i_t{pr < 2 ? 1 << (16 * pr) : 0, pr >= 2 ? 1 << (16 * (pr - 2)) : 0, 0, 0};
+        nibpos[l] = v4i_t{bits, 0, 0, 0};
+    }
+    __syncthreads();
+    const unsigned total = item_off[K];
+    const unsigned nibsh = half ? 0u : 4u;
+
+    for (unsigned item = blockIdx.x; item < total; item += gridDim.x) {  // uniform
+        // the cell of the item: the last one whose first item is not beyond it
+        int clo = 0, chi = K;
+        while (chi - clo > 1) {
+            const int mid = (clo + chi) >> 1;
+            if (item_off[mid] <= item) clo = mid; else chi = mid;
+        }
+        const int cell = clo;
+        const unsigned p0 = pair_off[cell], P = pair_off[cell + 1] - p0;
+        long long ll = list_off[cell], lh = list_off[cell + 1];
+        if (P == 0 || ll < 0 || lh > n_total || lh <= ll) continue;  // cannot happen with consistent offsets
+        const unsigned sets = (P + QW - 1) / QW;
+        const unsigned local = item - item_off[cell];
+        const unsigned set = local % sets, ch = local / sets;
+        const long long lead = ivfs_lead(lh - ll);
+        const long long r0 = part == 0 ? ll : ll + lead, r1 = part == 0 ? ll + lead : lh;
+        const int64_t c0 = r0 + (long long)ch * IVFS_CHUNK;
+        const int64_t c1 = min((long long)r1, (long long)c0 + IVFS_CHUNK);
+        if (c0 >= c1) continue;
+
+        // this lane's pair: its tables (code byte jb: the 16 entries of table 2jb + half) and bound
+        const unsigned k = set * QW + (unsigned)row;
+        const bool live = k < P;
+        const unsigned pr = pairs[p0 + min(k, P - 1u)];
+        const unsigned q = pr / (unsigned)nprobe;
+        int thr = -1 - SHIFT;  // nothing passes
+        if (live) {
+            const unsigned t = taus[q];
+            if (t != IVFS_NONE) thr = (int)t - SHIFT;
+        }
+        v8i_t tb[NP];
+#pragma unroll
+        for (int jp = 0; jp < NP; ++jp) {
+            const v4i_t *src = reinterpret_cast<const v4i_t *>(qluts + ((size_t)pr * (2 * B) + 4 * jp + 2 * half) * 16);
+            const v4i_t e0 = src[0], e1 = src[1];
+            const int flip = live ? (int)0x80808080u : 0, keep = live ? -1 : 0;
+            tb[jp] = v8i_t{(e0[0] ^ flip) & keep, (e0[1] ^ flip) & keep, (e0[2] ^ flip) & keep, (e0[3] ^ flip) & keep,
+                           (e1[0] ^ flip) & keep, (e1[1] ^ flip) & keep, (e1[2] ^ flip) & keep, (e1[3] ^ flip) & keep};
+        }
+
+        // Writes the pairs' keys to their queries' regions and empties the lists.  Lane k < 32 reports
+        // for pair k of the set, which is its own (half 0).
+        auto flush = [&]() {
+            __syncthreads();
+            if (l < QW) {
+                const unsigned c = min(cnt[l], (unsigned)LC);
+                if (c) {
+                    char *base = ws + (size_t)q * ws_stride;
+                    unsigned *counts = reinterpret_cast<unsigned *>(base + countsA_off);
+                    uint64_t *dst = reinterpret_cast<uint64_t *>(base + listsA_off);
+                    const unsigned slot = atomicAdd(&counts[0], c);
+                    if (slot + c <= (unsigned)pitchA) {
+                        for (unsigned i = 0; i < c; ++i) {
+                            const unsigned key = keys[l][i];
+                            dst[slot + i] = ((uint64_t)(key >> 24) << 32) | (uint64_t)(c0 + (key & 0xffffffu));
+                        }
+                    } else {
+                        flags[q] = 1u;  // the region is full: this query is redone on its own
+                    }
+                    cnt[l] = 0;
+                }
+            }
+            __syncthreads();
+        };
+
+        unsigned cw[SUB][WPC], cn[SUB][WPC];
+        auto fetch = [&](int64_t t0, unsigned (&dst)[SUB][WPC]) {
+#pragma unroll
+            for (int s = 0; s < SUB; ++s) {
+                const int64_t i = min(t0 + 32 * s + row, c1 - 1);
+                const unsigned *src = reinterpret_cast<const unsigned *>(codes + i * B);
+#pragma unroll
+                for (int w = 0; w < WPC; ++w) dst[s][w] = src[w];
+            }
+        };
+        struct Operand {
+            v2i_t v0, v1;
+            int p0, p1;
+        };
+        auto operand = [&](const unsigned (&w)[WPC], int jp) {
+            const unsigned x = (w[jp >> 1] << nibsh) & 0xf0f0f0f0u;
+            const unsigned o0 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1), 8), o1 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1) + 8, 8);
+            const char *tv = reinterpret_cast<const char *>(nibval), *tp = reinterpret_cast<const char *>(nibpos);
+            return Operand{*reinterpret_cast<const v2i_t *>(tv + o0), *reinterpret_cast<const v2i_t *>(tv + o1),
+                           *reinterpret_cast<const int *>(tp + o0), *reinterpret_cast<const int *>(tp + o1)};
+        };
+        // Result v of a lane: code (v / 4) * 8 + half * 4 + v % 4 of the step, pair `row`.
+        auto test = [&](const v16i_t &sum, unsigned rel) {
+            int lo = sum[0];
+#pragma unroll
+            for (int v = 1; v < 15; v += 2) lo = min(min(lo, sum[v]), sum[v + 1]);
+            lo = min(lo, sum[15]);
+            if (__ballot(lo <= thr) == 0ull) return;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int qm = min(min(sum[4 * u], sum[4 * u + 1]), min(sum[4 * u + 2], sum[4 * u + 3]));
+                if (__ballot(qm <= thr) == 0ull) continue;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const unsigned li = rel + (unsigned)(u * 8 + half * 4 + w);
+                    if (c0 + (int64_t)li < c1 && sum[4 * u + w] <= thr) {
+                        const unsigned slot = atomicAdd(&cnt[row], 1u);
+                        if (slot < (unsigned)LC) keys[row][slot] = ((unsigned)(sum[4 * u + w] + SHIFT) << 24) | li;
+                    }
+                }
+            }
+            // a step adds at most 32 keys to a pair's list: written out once a list is half full, it never
+            // runs over
+            __syncthreads();
+            const bool full = l < QW && cnt[l] > (unsigned)(LC - 32);
+            if (__ballot(full) != 0ull) flush();
+        };
+
+        fetch(c0, cn);
+        Operand a0 = operand(cn[0], 0), a1 = operand(cn[0], NP > 1 ? 1 : 0);
+        for (int64_t t0 = c0; t0 < c1; t0 += 32 * SUB) {  // uniform
+#pragma unroll
+            for (int s = 0; s < SUB; ++s)
+#pragma unroll
+                for (int w = 0; w < WPC; ++w) cw[s][w] = cn[s][w];
+            if (t0 + 32 * SUB < c1) fetch(t0 + 32 * SUB, cn);
+#pragma unroll
+            for (int s = 0; s < SUB; ++s) {
+                if (t0 + 32 * s >= c1) break;  // uniform
+                v16i_t acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+                for (int jp = 0; jp < NP; ++jp) {
+                    const Operand a = a0;
+                    a0 = a1;
+                    if (jp + 2 < NP) a1 = operand(cw[s], jp + 2);
+                    else if (s + 1 < SUB) a1 = operand(cw[s + 1], (jp + 2 - NP) % NP);
+                    else a1 = operand(cn[0], (jp + 2 - NP) % NP);
+                    asm volatile("" ::: "memory");
+                    const v4i_t av = v4i_t{a.v0[0], a.v0[1], a.v1[0], a.v1[1]};
+                    int ap0 = a.p0, ap1 = a.p1;
+                    asm volatile("" : "+v"(ap0), "+v"(ap1));
+                    const int ap = ap0 | (ap1 << 16);
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, tb[jp], acc, ap, 0, 0);
+                }
+                test(acc, (unsigned)(t0 - c0) + 32u * s);
+            }
+        }
+        flush();
+    }
+}
+
+// One workgroup per query, between the two parts of the scan: the R-th smallest sum among the
+// keys reported so far replaces the query's bound when it is tighter.
+__global__ __launch_bounds__(256) void ivfs_refine_kernel(const char *__restrict__ ws, size_t ws_stride,
+                                                          size_t countsA_off, size_t listsA_off, int pitchA, int R,
+                                                          unsigned *__restrict__ taus,
+                                                          const unsigned *__restrict__ flags)
+{
+    __shared__ unsigned hist[256];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    if (flags[q]) return;  // uniform
+    const char *base = ws + (size_t)q * ws_stride;
+    const unsigned c = min(*reinterpret_cast<const unsigned *>(base + countsA_off), (unsigned)pitchA);
+    if (c < (unsigned)R) return;  // uniform
+    const uint64_t *keys = reinterpret_cast<const uint64_t *>(base + listsA_off);
+    hist[tid] = 0;
+    __syncthreads();
+    for (unsigned i = tid; i < c; i += 256) atomicAdd(&hist[(unsigned)(keys[i] >> 32) & 255u], 1u);
+    __syncthreads();
+    if (tid < WAVE) {
+        unsigned h[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) h[b] = hist[4 * tid + b];
+        const unsigned t = wave_threshold_bin<4>(h, (unsigned)R);
+        if (tid == 0 && t < 256u && t < taus[q]) taus[q] = t;
+    }
+}
+
+// The scan of one batch (after the seed kernel): pairs by cell, the two parts with the bounds
+// refined in between.  Every array is device memory of the sizes named in IvfPlan.
+int ivf_shared_scan(int B, const int64_t *list_off, const uint8_t *codes, int64_t n_total, int K,
+                    const int32_t *probes, int nb, int nprobe, const uint8_t *qluts, int R, char *scan_ws,
+                    size_t ws_stride, size_t countsA_off, size_t listsA_off, int pitchA, unsigned *pair_cnt,
+                    unsigned *pair_off, unsigned *item_off0, unsigned *item_off1, unsigned *pairs, unsigned *taus,
+                    unsigned *flags, int wgs, hipStream_t st)
+{
+    const int64_t npairs = (int64_t)nb * nprobe;
+    const unsigned pgrid = (unsigned)ceil_div(npairs, 256);
+    launch(QADC_PROF_SEED, ivfs_zero_kernel, dim3((unsigned)ceil_div(K, 256)), dim3(256), 0, st, pair_cnt, (int64_t)K);
+    launch(QADC_PROF_SEED, ivfs_zero_kernel, dim3((unsigned)ceil_div(nb, 256)), dim3(256), 0, st, flags, (int64_t)nb);
+    launch(QADC_PROF_SEED, ivfs_count_kernel, dim3(pgrid), dim3(256), 0, st, probes, nprobe, npairs, K,
+           (const char *)scan_ws, ws_stride, pair_cnt, taus, flags);
+    launch(QADC_PROF_SEED, ivfs_offsets_kernel, dim3(1), dim3(1024), 0, st, (const unsigned *)pair_cnt, list_off, K,
+           n_total, 32, pair_off, item_off0, item_off1);
+    launch(QADC_PROF_SEED, ivfs_place_kernel, dim3(pgrid), dim3(256), 0, st, probes, npairs, K,
+           (const unsigned *)pair_off, pair_cnt, pairs);
+#define QADC_IVFS_CASE(B_)                                                                                      \
+    case B_:                                                                                                   \
+        launch(QADC_PROF_SCAN, ivfs_scan_kernel<B_>, dim3((unsigned)wgs), dim3(64), 0, st, 0, list_off, codes,  \
+               n_total, K, (const unsigned *)pair_off, (const unsigned *)item_off0, (const unsigned *)pairs,   \
+               nprobe, qluts, (const unsigned *)taus, scan_ws, ws_stride, countsA_off, listsA_off, pitchA,     \
+               flags);                                                                                         \
+        launch(QADC_PROF_SEED, ivfs_refine_kernel, dim3((unsigned)nb), dim3(256), 0, st, (const char *)scan_ws, \
+               ws_stride, countsA_off, listsA_off, pitchA, R, taus, (const unsigned *)flags);                  \
+        launch(QADC_PROF_SCAN, ivfs_scan_kernel<B_>, dim3((unsigned)wgs), dim3(64), 0, st, 1, list_off, codes,  \
+               n_total, K, (const unsigned *)pair_off, (const unsigned *)item_off1, (const unsigned *)pairs,   \
+               nprobe, qluts, (const unsigned *)taus, scan_ws, ws_stride, countsA_off, listsA_off, pitchA,     \
+               flags);                                                                                         \
+        break;
+    switch (B) {
+        QADC_IVFS_CASE(4)
+        QADC_IVFS_CASE(8)
+        QADC_IVFS_CASE(16)
+        QADC_IVFS_CASE(32)
+    default:
+        return fail(QADC_EINVAL, "qadc_ivf_search: %d code bytes", B);
+    }
+#undef QADC_IVFS_CASE
+    QADC_HIP_TRY(hipGetLastError());
+    return QADC_OK;
+}
+
+}  // namespace qadc
