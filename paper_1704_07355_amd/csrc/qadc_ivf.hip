@@ -397,13 +397,14 @@ template <int B>
 __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes,
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, int per_list, char *__restrict__ ws, size_t ws_stride, int64_t n_total)
+    int R, int per_list, char *__restrict__ ws, size_t ws_stride, int64_t n_total, int long_shift)
 {
     constexpr int NT = IVF_SEED_NT;
     constexpr int TAB = 2 * B * 16;  // bytes of one cell's quantized tables
     __shared__ __attribute__((aligned(16))) uint8_t tab[IVF_SEED_PCH * TAB];
     __shared__ long long lo[IVF_MAX_NPROBE];
     __shared__ int len[IVF_MAX_NPROBE];
+    __shared__ int more[IVF_MAX_NPROBE];  // codes sampled beyond per_list (long lists, long_shift > 0)
     __shared__ unsigned hist[256];
     __shared__ unsigned last_s;
     const int tid = threadIdx.x;
@@ -421,6 +422,9 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
         if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: nothing is read
         lo[tid] = l;
         len[tid] = (int)min((long long)per_list, h - l);
+        // with long_shift the sample of a list is at least its 2^-long_shift part: the bound then
+        // reflects the lists in proportion to their lengths
+        more[tid] = long_shift > 0 ? (int)max(0ll, min((h - l) >> long_shift, 1ll << 30) - per_list) : 0;
     }
     for (int e = tid; e < 256; e += NT) hist[e] = 0;
     for (int p0 = p_begin; p0 < p_end; p0 += IVF_SEED_PCH) {  // uniform
@@ -446,6 +450,25 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
                 }
             }
             if (sum < cap) atomicAdd(&hist[sum], 1u);  // saturated sums carry no information
+        }
+        for (int pp = 0; pp < np; ++pp) {  // uniform
+            const int extra = more[p0 + pp];
+            const uint8_t *t = tab + pp * TAB;
+            for (int c = per_list + tid; c < per_list + extra; c += NT) {
+                const unsigned *cw = reinterpret_cast<const unsigned *>(codes + (size_t)(lo[p0 + pp] + c) * B);
+                unsigned sum = 0;
+#pragma unroll
+                for (int k = 0; k < B / 4; ++k) {
+                    const unsigned x = cw[k];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const unsigned v = (x >> (8 * b)) & 0xffu;
+                        const int jb = 4 * k + b;
+                        sum += (unsigned)t[(2 * jb) * 16 + (v & 15u)] + (unsigned)t[(2 * jb + 1) * 16 + (v >> 4)];
+                    }
+                }
+                if (sum < cap) atomicAdd(&hist[sum], 1u);
+            }
         }
     }
     __syncthreads();
@@ -487,11 +510,13 @@ constexpr unsigned IVF_NO_WG = 0xffffffffu;
 // (work in proportion to the lists it probes); the queries with the most work come first in the
 // grid, so that the longest-running workgroups start first.  wgmap[b] = q << 12 | g for workgroup
 // b of the grid, IVF_NO_WG beyond the last one.  One workgroup; nb <= IVF_MAP_MAXQ, Wmax <= 4096.
-// With `only`, a query whose entry is zero gets no workgroup.
+// With `flags`, a query whose flag is not 1 is scanned over its other set of cells (see ivf_scan_kernel)
+// and its units are qunits_alt's.
 __global__ __launch_bounds__(IVF_MAP_NT) void ivf_wgmap_kernel(const unsigned *__restrict__ qunits, int nb,
                                                               int units_per_wg, int Wmax,
                                                               unsigned *__restrict__ wgmap,
-                                                              const unsigned *__restrict__ only)
+                                                              const unsigned *__restrict__ qunits_alt,
+                                                              const unsigned *__restrict__ flags)
 {
     __shared__ unsigned un[IVF_MAP_MAXQ];      // units of query q
     __shared__ unsigned byrank[IVF_MAP_MAXQ];  // query at rank r
@@ -502,7 +527,7 @@ __global__ __launch_bounds__(IVF_MAP_NT) void ivf_wgmap_kernel(const unsigned *_
     auto wgs_of = [&](unsigned u) {
         return (unsigned)min((long long)Wmax, max(1ll, ((long long)u + units_per_wg - 1) / units_per_wg));
     };
-    for (int q = tid; q < nb; q += IVF_MAP_NT) un[q] = qunits[q];
+    for (int q = tid; q < nb; q += IVF_MAP_NT) un[q] = (flags && flags[q] != 1u) ? qunits_alt[q] : qunits[q];
     if (tid == 0) carry = 0;
     __syncthreads();
     // rank by (units descending, query ascending): a total order, so ranks are distinct
@@ -519,8 +544,7 @@ __global__ __launch_bounds__(IVF_MAP_NT) void ivf_wgmap_kernel(const unsigned *_
     // exclusive running sum of the workgroup counts in rank order
     for (int r0 = 0; r0 < nb; r0 += IVF_MAP_NT) {
         const int r = r0 + tid;
-        // (`only`: the queries that are scanned by this launch at all)
-        const unsigned w = (r < nb && (!only || only[byrank[r]])) ? wgs_of(un[byrank[r]]) : 0u;
+        const unsigned w = r < nb ? wgs_of(un[byrank[r]]) : 0u;
         unsigned inc = w;
         const int l = lane_id();
 #pragma unroll
@@ -574,7 +598,8 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int64_t n_total,
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
     int R, int units_per_wg, int Wmax, const unsigned *__restrict__ wgmap, char *__restrict__ ws,
-    size_t ws_stride, size_t counts_off, size_t lists_off)
+    size_t ws_stride, size_t counts_off, size_t lists_off, const int32_t *__restrict__ probes_alt,
+    const unsigned *__restrict__ flags)
 {
     constexpr int NT = IVF_NT;
     using C = ScanCfg<B, NT>;
@@ -597,8 +622,11 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     // unit counts.
     static_assert(IVF_MAX_NPROBE <= NT, "one thread per probe");
     unsigned long long my_units = 0;
+    // (with flags: a query whose flag is not 1 leaves some of its cells to the shared-list scan and
+    // takes the others, probes_alt, here; the tables stay indexed by the slot)
+    const int32_t *pr = (flags && flags[q] != 1u) ? probes_alt : probes;  // uniform
     if (tid < nprobe) {
-        const int cell = probes[(size_t)q * nprobe + tid];
+        const int cell = pr[(size_t)q * nprobe + tid];
         long long l = 0, h = 0;
         if (cell >= 0) { l = list_off[cell]; h = list_off[cell + 1]; }
         if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: nothing is read
@@ -963,6 +991,7 @@ int quantize_luts(int, const float *, int, int, int, const uint8_t *, int64_t, c
 
 struct IvfPlan {
     int qb, W;
+    int qd;  // queries per pass of the Index step (its distances take K floats per query)
     int seed_per_list;  // codes sampled per probed list for the bound of the scan (0: no seed kernel)
     ScanLayout l;
     size_t off_dist, off_probes, off_luts, off_qluts, off_qmax, off_units, off_map, off_scan, bytes;
@@ -971,7 +1000,8 @@ struct IvfPlan {
     bool shared;
     int shared_wgs;
     size_t stride, countsA_off, listsA_off;
-    size_t off_paircnt, off_pairoff, off_item0, off_item1, off_pairs, off_taus, off_flags;
+    size_t off_paircnt, off_pairoff, off_item0, off_item1, off_pairs, off_taus, off_flags, off_plight, off_ulight;
+    int shared_min_pairs;
 };
 
 constexpr int IVF_SHARED_PITCH = MERGE_CAP;   // keys of a query's region: what the merge kernel holds in LDS
@@ -979,9 +1009,11 @@ constexpr int IVF_SHARED_MIN_Q = 256;         // smallest batch scanned list by 
 constexpr int IVF_SHARED_MAX_R = 128;         // the region must hold a few dozen times R keys
 constexpr int IVF_SHARED_MAX_K = 1 << 18;     // one workgroup sums the per-cell counts
 
+constexpr int IVF_SHARED_MIN_PAIRS = 8;       // pairs of a cell from which its list is scanned once for all of them
+
 int ivf_shared_scan(int, const int64_t *, const uint8_t *, int64_t, int, const int32_t *, int, int, const uint8_t *,
                     int, char *, size_t, size_t, size_t, int, unsigned *, unsigned *, unsigned *, unsigned *,
-                    unsigned *, unsigned *, unsigned *, int, hipStream_t);
+                    unsigned *, unsigned *, unsigned *, int32_t *, unsigned *, long long, int, int, hipStream_t);
 
 static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, IvfPlan *p)
 {
@@ -1010,6 +1042,7 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->shared = R <= IVF_SHARED_MAX_R && ix->K <= IVF_SHARED_MAX_K && p->seed_per_list > 0 && ix->m <= 64 &&
                 (shared_knob >= 0 ? shared_knob != 0 : nq >= IVF_SHARED_MIN_Q);
     p->shared_wgs = std::max(1, std::min(65535, knob_or(knobs().ivf_shared_wgs, 4096)));
+    p->shared_min_pairs = std::max(1, knob_or(knobs().ivf_shared_min_pairs, IVF_SHARED_MIN_PAIRS));
     p->stride = p->l.stride;
     p->countsA_off = p->listsA_off = 0;
     if (p->shared) {
@@ -1018,17 +1051,25 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
         p->stride = p->listsA_off + align_up((size_t)IVF_SHARED_PITCH * sizeof(uint64_t), 256);
     }
     const size_t kdist = ix->coarse ? (size_t)ix->K : 0;  // the Index step's distances
-    const size_t per_q = align_up(kdist * 4, 256) + align_up((size_t)nprobe * 4, 256) +
-                         align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
+    const size_t per_q = align_up((size_t)nprobe * 4, 256) + align_up((size_t)nprobe * ix->m * 16 * 4, 256) +
                          align_up((size_t)nprobe * ix->m * 16, 256) + 256 + 4 + (size_t)p->W * 4 + p->stride +
-                         (p->shared ? (size_t)nprobe * 4 + 8 : 0);
-    int64_t qb = (int64_t)((512ull << 20) / per_q);
+                         (p->shared ? (size_t)nprobe * 8 + 12 : 0);
+    // Queries per launch sequence.  The shared-list scan gains with every query that joins the batch
+    // (more pairs per list), so it takes up to IVF_MAP_MAXQ queries in up to 1.5 GiB; the per-query
+    // scan is indifferent and stays within 512 MiB.  The Index step's distances (K floats per query)
+    // are computed for at most 256 MiB of queries at a time inside a sequence.
+    const size_t budget = p->shared ? (1536ull << 20) : (512ull << 20);
+    const size_t dist_budget = p->shared ? (256ull << 20) : 0;
+    int64_t qb = (int64_t)(budget / (per_q + (p->shared ? 0 : align_up(kdist * 4, 256))));
     if (qb < 1) qb = 1;
     if (qb > nq) qb = nq;
     if (qb > IVF_MAP_MAXQ) qb = IVF_MAP_MAXQ;
     p->qb = (int)qb;
+    int64_t qd = qb;  // queries per pass of the Index step
+    if (dist_budget && kdist) qd = std::max<int64_t>(1, std::min<int64_t>(qb, (int64_t)(dist_budget / (kdist * 4))));
+    p->qd = (int)qd;
     size_t o = 0;
-    p->off_dist = o;   o += align_up((size_t)qb * kdist * 4, 256);
+    p->off_dist = o;   o += align_up((size_t)qd * kdist * 4, 256);
     p->off_probes = o; o += align_up((size_t)qb * nprobe * 4, 256);
     p->off_luts = o;   o += align_up((size_t)qb * nprobe * ix->m * 16 * 4, 256);
     p->off_qluts = o;  o += align_up((size_t)qb * nprobe * ix->m * 16, 256);
@@ -1037,6 +1078,7 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->off_map = o;    o += align_up((size_t)qb * p->W * 4, 256);
     p->off_scan = o;   o += p->stride * (size_t)qb;
     p->off_paircnt = p->off_pairoff = p->off_item0 = p->off_item1 = p->off_pairs = p->off_taus = p->off_flags = 0;
+    p->off_plight = p->off_ulight = 0;
     if (p->shared) {
         const size_t kk = align_up(((size_t)ix->K + 1) * 4, 256);
         p->off_paircnt = o; o += kk;
@@ -1046,6 +1088,8 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
         p->off_pairs = o;   o += align_up((size_t)qb * nprobe * 4, 256);
         p->off_taus = o;    o += align_up((size_t)qb * 4, 256);
         p->off_flags = o;   o += align_up((size_t)qb * 4, 256);
+        p->off_plight = o;  o += align_up((size_t)qb * nprobe * 4, 256);
+        p->off_ulight = o;  o += align_up((size_t)qb * 4, 256);
     }
     p->bytes = o;
     return true;
@@ -1110,17 +1154,21 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             launch(QADC_PROF_IVF_INDEX, ivf_take_probes_kernel, dim3((unsigned)ceil_div(np_total, 256)), dim3(256),
                    0, st, probes_in + (size_t)q0 * nprobe, nprobe, K, np_total, probes);
         } else {
-            if (nb > 32) {
-                dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(nb, 128));
-                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<8>, grid, dim3(256), 0, st, ix->coarse, K, d,
-                       yq, nb, dist);
-            } else {
-                dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(nb, 16));
-                launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<1>, grid, dim3(256), 0, st, ix->coarse, K, d,
-                       yq, nb, dist);
+            for (int i0 = 0; i0 < nb; i0 += p.qd) {
+                const int ni = min(p.qd, nb - i0);
+                const float *yi = yq + (size_t)i0 * d;
+                if (nb > 32) {
+                    dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(ni, 128));
+                    launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<8>, grid, dim3(256), 0, st, ix->coarse, K, d,
+                           yi, ni, dist);
+                } else {
+                    dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(ni, 16));
+                    launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<1>, grid, dim3(256), 0, st, ix->coarse, K, d,
+                           yi, ni, dist);
+                }
+                launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(ni), dim3(IVF_SEL_NT), 0, st, dist, K,
+                       nprobe, probes + (size_t)i0 * nprobe);
             }
-            launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(nb), dim3(IVF_SEL_NT), 0, st, dist, K,
-                   nprobe, probes);
         }
         // Tables
         launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
@@ -1145,7 +1193,7 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
     case B_:                                                                                           \
         launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb, seed_parts), dim3(IVF_SEED_NT), 0, st,    \
                ix->list_off, ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws,     \
-               p.stride, ix->n);                                                                       \
+               p.stride, ix->n, p.shared ? 8 : 0);                                                     \
         break;
         if (p.seed_per_list > 0) {
             switch (m / 2) {
@@ -1156,24 +1204,26 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             }
         }
 #undef QADC_IVF_SEED_CASE
+        int32_t *probes_light = p.shared ? (int32_t *)(ws + p.off_plight) : nullptr;
+        unsigned *qunits_light = p.shared ? (unsigned *)(ws + p.off_ulight) : nullptr;
         if (p.shared) {
-            // every list once for all the queries that probe it; the queries it leaves flagged are
-            // the only ones that get workgroups of the per-query kernel below
+            // the lists wanted by many queries once for all of them; then the per-query kernel takes the
+            // remaining cells of every query (all cells of a query left flagged 1)
             rc = ivf_shared_scan(m / 2, ix->list_off, ix->codes, ix->n, K, probes, nb, nprobe, qluts, R, scan_ws,
                                  p.stride, p.countsA_off, p.listsA_off, IVF_SHARED_PITCH,
                                  (unsigned *)(ws + p.off_paircnt), (unsigned *)(ws + p.off_pairoff),
                                  (unsigned *)(ws + p.off_item0), (unsigned *)(ws + p.off_item1),
-                                 (unsigned *)(ws + p.off_pairs), (unsigned *)(ws + p.off_taus), flags, p.shared_wgs,
-                                 st);
+                                 (unsigned *)(ws + p.off_pairs), (unsigned *)(ws + p.off_taus), flags, probes_light,
+                                 qunits_light, unit, p.shared_min_pairs, p.shared_wgs, st);
             if (rc != QADC_OK) return rc;
         }
         launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap,
-               (const unsigned *)flags);
+               (const unsigned *)qunits_light, (const unsigned *)flags);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
         launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
                ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, wgmap, scan_ws, p.stride,            \
-               p.l.counts_off, p.l.lists_off);                                                        \
+               p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light, (const unsigned *)flags);  \
         break;
         switch (m / 2) {
             QADC_IVF_CASE(4)

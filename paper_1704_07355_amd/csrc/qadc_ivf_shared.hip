@@ -2,24 +2,27 @@
 // Section 3.3) for large batches on gfx950.
 //
 // A batch of a few thousand queries probes the same inverted lists over and over: with 4096
-// queries x 64 cells over 65536 lists every code of a popular list is wanted by tens to hundreds
-// of queries.  Scanning query by query reads such a list once per query and is bound by memory;
-// here the (query, cell) pairs of the batch are sorted by cell and every list is scanned once for
-// all the pairs that probe it, 32 pairs at a time, on the matrix units: the sum of a code for a
-// pair is a one-hot row times the pair's tables (see scan_u8_mfma_kernel for the operand layout),
-// so 32 codes x 32 pairs cost m/4 sparse matrix instructions, and the result of a code byte
-// fetched from memory is used 32 times.  Every pair has its own tables (the residual of its
-// query against its cell); the bound a sum must meet is its query's.
+// queries x 64 cells over 65536 Zipf-sized lists, half of all (query, code) pairs fall on the dozen
+// longest lists, each wanted by tens of queries, while most lists are wanted by one to four.
+// Scanning query by query reads a popular list once per query and is bound by memory.  Here the
+// (query, cell) pairs of the batch are counted per cell; the cells probed by at least `min_pairs`
+// pairs are scanned ONCE for all their pairs, 32 pairs at a time, on the matrix units: the sum of a
+// code for a pair is a one-hot row times the pair's tables (see scan_u8_mfma_kernel for the operand
+// layout), so 32 codes x 32 pairs cost m/4 sparse matrix instructions and a code byte fetched from
+// memory is used up to 32 times.  Every pair has its own tables (the residual of its query against
+// its cell); the bound a sum must meet is its query's.  The other cells stay with the per-query
+// kernel (ivf_scan_kernel), which is given the query's remaining cells; the merge kernel joins the
+// two reports.
 //
-// Selection.  A query's bound comes from the seed kernel (a few dozen codes per probed list) and
-// is loose for a query whose lists are long; sums at or below it are appended to the query's
-// region of the workspace with one atomic per (pair, chunk).  To keep that region small the scan
-// runs in two parts: first the leading 1/16 of every list, after which the R-th smallest sum
-// found so far replaces the query's bound (a sample in proportion to what the query scans,
-// whatever the sizes of its lists), then the rest.  A query whose region still overflows, or that
-// has no bound at all, is flagged and redone by the per-query kernel; the merge kernel takes
-// whichever report is complete.  Results do not depend on the route: every code whose sum is at
-// or below a valid bound is reported, and the merge orders by (sum, storage position).
+// Selection.  A query's first bound comes from the seed kernel (whose sample takes 1/256 of a long
+// list, so that the bound reflects the lists in proportion to their lengths); sums at or below the
+// bound are appended to the query's region of the workspace with one atomic per (pair, chunk).  To
+// keep that region small the scan runs in two parts: first the leading 1/16 of every shared list,
+// after which the R-th smallest sum found so far replaces the query's bound and the keys beyond it
+// are dropped, then the rest.  A query whose region still overflows, or that has no bound at all,
+// is flagged (1) and redone over all its cells by the per-query kernel.  Results do not depend on
+// the route: every code whose sum is at or below a valid bound is reported, and the merge orders by
+// (sum, storage position).
 
 #include "qadc_scan_common.h"
 
@@ -43,7 +46,7 @@ __global__ __launch_bounds__(256) void ivfs_zero_kernel(unsigned *__restrict__ p
 }
 
 // One thread per (query, probe slot): counts the pairs of every cell; the thread of a query's
-// first slot copies the query's bound (IVFS_NONE and a flag when the seed kernel found none).
+// first slot copies the query's bound and sets its flag (IVFS_NONE and 1 when the seed kernel found none).
 __global__ __launch_bounds__(256) void ivfs_count_kernel(const int32_t *__restrict__ probes, int nprobe,
                                                          int64_t npairs, int K, const char *__restrict__ ws,
                                                          size_t ws_stride, unsigned *__restrict__ pair_cnt,
@@ -57,16 +60,16 @@ __global__ __launch_bounds__(256) void ivfs_count_kernel(const int32_t *__restri
         const int64_t q = i / nprobe;
         const unsigned tau1 = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ghist[0][0];
         taus[q] = tau1 ? tau1 - 1u : IVFS_NONE;
-        if (!tau1) flags[q] = 1u;
+        flags[q] = tau1 ? 2u : 1u;  // 2: shared lists here, the others by the per-query kernel; 1: all by that one
     }
 }
 
 // One workgroup: exclusive running sums over the cells of (pairs, work items of the leading
-// parts, work items of the rest).  A cell with P pairs and n codes is ceil(P / qw) sets of pairs
-// times ceil(len / IVFS_CHUNK) chunks of either part.
+// parts, work items of the rest).  A cell with P >= min_pairs pairs and n codes is ceil(P / qw) sets
+// of pairs times ceil(len / IVFS_CHUNK) chunks of either part; a cell with fewer pairs is no work here.
 __global__ __launch_bounds__(1024) void ivfs_offsets_kernel(const unsigned *__restrict__ pair_cnt,
                                                             const int64_t *__restrict__ list_off, int K,
-                                                            int64_t n_total, int qw,
+                                                            int64_t n_total, int qw, int min_pairs,
                                                             unsigned *__restrict__ pair_off,
                                                             unsigned *__restrict__ item_off0,
                                                             unsigned *__restrict__ item_off1)
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(1024) void ivfs_offsets_kernel(const unsigned *__re
             long long l = list_off[c], h = list_off[c + 1];
             if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: no work
             const long long n = h - l, s = ivfs_lead(n);
-            const unsigned sets = (P + (unsigned)qw - 1u) / (unsigned)qw;
+            const unsigned sets = P >= (unsigned)min_pairs ? (P + (unsigned)qw - 1u) / (unsigned)qw : 0u;
             v[0] = P;
             v[1] = sets * (unsigned)((s + IVFS_CHUNK - 1) / IVFS_CHUNK);
             v[2] = sets * (unsigned)((n - s + IVFS_CHUNK - 1) / IVFS_CHUNK);
@@ -332,48 +335,105 @@ __global__ __launch_bounds__(64) void ivfs_scan_kernel(
 }
 
 // One workgroup per query, between the two parts of the scan: the R-th smallest sum among the
-// keys reported so far replaces the query's bound when it is tighter.
-__global__ __launch_bounds__(256) void ivfs_refine_kernel(const char *__restrict__ ws, size_t ws_stride,
-                                                          size_t countsA_off, size_t listsA_off, int pitchA, int R,
-                                                          unsigned *__restrict__ taus,
-                                                          const unsigned *__restrict__ flags)
+// keys reported so far replaces the query's bound when it is tighter, and only the keys within the
+// new bound stay in the region (the others cannot be among the R best).
+constexpr int IVFS_REFINE_NT = 256;
+__global__ __launch_bounds__(IVFS_REFINE_NT) void ivfs_refine_kernel(char *__restrict__ ws, size_t ws_stride,
+                                                                     size_t countsA_off, size_t listsA_off,
+                                                                     int pitchA, int R, unsigned *__restrict__ taus,
+                                                                     const unsigned *__restrict__ flags)
 {
+    constexpr int NT = IVFS_REFINE_NT;
+    __shared__ uint64_t lkeys[MERGE_CAP];
     __shared__ unsigned hist[256];
+    __shared__ unsigned tnew, kept;
     const int q = blockIdx.x, tid = threadIdx.x;
-    if (flags[q]) return;  // uniform
-    const char *base = ws + (size_t)q * ws_stride;
-    const unsigned c = min(*reinterpret_cast<const unsigned *>(base + countsA_off), (unsigned)pitchA);
-    if (c < (unsigned)R) return;  // uniform
-    const uint64_t *keys = reinterpret_cast<const uint64_t *>(base + listsA_off);
-    hist[tid] = 0;
+    if (flags[q] == 1u || pitchA > MERGE_CAP) return;  // uniform
+    char *base = ws + (size_t)q * ws_stride;
+    unsigned *counts = reinterpret_cast<unsigned *>(base + countsA_off);
+    const unsigned c = counts[0];
+    if (c < (unsigned)R || c > (unsigned)pitchA) return;  // uniform
+    uint64_t *keys = reinterpret_cast<uint64_t *>(base + listsA_off);
+    for (int i = tid; i < 256; i += NT) hist[i] = 0;
+    if (tid == 0) { tnew = 256u; kept = 0; }
     __syncthreads();
-    for (unsigned i = tid; i < c; i += 256) atomicAdd(&hist[(unsigned)(keys[i] >> 32) & 255u], 1u);
+    for (unsigned i = tid; i < c; i += NT) {
+        const uint64_t k = keys[i];
+        lkeys[i] = k;
+        atomicAdd(&hist[(unsigned)(k >> 32) & 255u], 1u);
+    }
     __syncthreads();
     if (tid < WAVE) {
         unsigned h[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) h[b] = hist[4 * tid + b];
         const unsigned t = wave_threshold_bin<4>(h, (unsigned)R);
-        if (tid == 0 && t < 256u && t < taus[q]) taus[q] = t;
+        if (tid == 0) tnew = t;
+    }
+    __syncthreads();
+    const unsigned t = tnew;
+    if (t >= 256u || t >= taus[q]) return;  // uniform: no tighter bound
+    for (unsigned i = tid; i < c; i += NT) {
+        const uint64_t k = lkeys[i];
+        if (((unsigned)(k >> 32) & 255u) <= t) keys[atomicAdd(&kept, 1u)] = k;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        taus[q] = t;
+        counts[0] = kept;
     }
 }
 
-// The scan of one batch (after the seed kernel): pairs by cell, the two parts with the bounds
-// refined in between.  Every array is device memory of the sizes named in IvfPlan.
+// One wavefront per query, after the shared lists are scanned: the cells that are left to the
+// per-query kernel (-1 in the slots of the shared cells), their units of work as ivf_qmax_kernel
+// counts them, and the query's tightened bound back into its control block for that kernel.
+__global__ __launch_bounds__(256) void ivfs_light_kernel(const int32_t *__restrict__ probes, int nprobe, int nb, int K,
+                                                         const unsigned *__restrict__ pair_off, int min_pairs,
+                                                         const int64_t *__restrict__ list_off, int64_t n_total,
+                                                         long long unit, const unsigned *__restrict__ flags,
+                                                         const unsigned *__restrict__ taus, char *__restrict__ ws,
+                                                         size_t ws_stride, int32_t *__restrict__ probes_light,
+                                                         unsigned *__restrict__ qunits_light)
+{
+    const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= nb) return;  // whole wavefront
+    const int lane = threadIdx.x & 63;
+    unsigned units = 0;
+    for (int p = lane; p < nprobe; p += 64) {
+        int cell = probes[(size_t)q * nprobe + p];
+        if (cell >= 0 && cell < K && pair_off[cell + 1] - pair_off[cell] >= (unsigned)min_pairs) cell = -1;
+        probes_light[(size_t)q * nprobe + p] = cell;
+        if (cell >= 0 && cell < K) {
+            const long long l = list_off[cell], h = list_off[cell + 1];
+            if (l >= 0 && h <= n_total && h > l) units += (unsigned)((h - l / 16 * 16 + unit - 1) / unit);
+        }
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) units += __shfl_xor(units, s);
+    if (lane == 0) {
+        qunits_light[q] = units;
+        if (flags[q] == 2u && taus[q] != IVFS_NONE)
+            reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride)->ghist[0][0] = taus[q] + 1u;
+    }
+}
+
+// The shared part of the scan of one batch (after the seed kernel): pairs by cell, the two parts
+// with the bounds refined in between, then what is left for the per-query kernel.  Every array is
+// device memory of the sizes named in IvfPlan.
 int ivf_shared_scan(int B, const int64_t *list_off, const uint8_t *codes, int64_t n_total, int K,
                     const int32_t *probes, int nb, int nprobe, const uint8_t *qluts, int R, char *scan_ws,
                     size_t ws_stride, size_t countsA_off, size_t listsA_off, int pitchA, unsigned *pair_cnt,
                     unsigned *pair_off, unsigned *item_off0, unsigned *item_off1, unsigned *pairs, unsigned *taus,
-                    unsigned *flags, int wgs, hipStream_t st)
+                    unsigned *flags, int32_t *probes_light, unsigned *qunits_light, long long unit, int min_pairs,
+                    int wgs, hipStream_t st)
 {
     const int64_t npairs = (int64_t)nb * nprobe;
     const unsigned pgrid = (unsigned)ceil_div(npairs, 256);
     launch(QADC_PROF_SEED, ivfs_zero_kernel, dim3((unsigned)ceil_div(K, 256)), dim3(256), 0, st, pair_cnt, (int64_t)K);
-    launch(QADC_PROF_SEED, ivfs_zero_kernel, dim3((unsigned)ceil_div(nb, 256)), dim3(256), 0, st, flags, (int64_t)nb);
     launch(QADC_PROF_SEED, ivfs_count_kernel, dim3(pgrid), dim3(256), 0, st, probes, nprobe, npairs, K,
            (const char *)scan_ws, ws_stride, pair_cnt, taus, flags);
     launch(QADC_PROF_SEED, ivfs_offsets_kernel, dim3(1), dim3(1024), 0, st, (const unsigned *)pair_cnt, list_off, K,
-           n_total, 32, pair_off, item_off0, item_off1);
+           n_total, 32, min_pairs, pair_off, item_off0, item_off1);
     launch(QADC_PROF_SEED, ivfs_place_kernel, dim3(pgrid), dim3(256), 0, st, probes, npairs, K,
            (const unsigned *)pair_off, pair_cnt, pairs);
 #define QADC_IVFS_CASE(B_)                                                                                      \
@@ -382,7 +442,7 @@ int ivf_shared_scan(int B, const int64_t *list_off, const uint8_t *codes, int64_
                n_total, K, (const unsigned *)pair_off, (const unsigned *)item_off0, (const unsigned *)pairs,   \
                nprobe, qluts, (const unsigned *)taus, scan_ws, ws_stride, countsA_off, listsA_off, pitchA,     \
                flags);                                                                                         \
-        launch(QADC_PROF_SEED, ivfs_refine_kernel, dim3((unsigned)nb), dim3(256), 0, st, (const char *)scan_ws, \
+        launch(QADC_PROF_SEED, ivfs_refine_kernel, dim3((unsigned)nb), dim3(IVFS_REFINE_NT), 0, st, scan_ws,    \
                ws_stride, countsA_off, listsA_off, pitchA, R, taus, (const unsigned *)flags);                  \
         launch(QADC_PROF_SCAN, ivfs_scan_kernel<B_>, dim3((unsigned)wgs), dim3(64), 0, st, 1, list_off, codes,  \
                n_total, K, (const unsigned *)pair_off, (const unsigned *)item_off1, (const unsigned *)pairs,   \
@@ -398,6 +458,9 @@ int ivf_shared_scan(int B, const int64_t *list_off, const uint8_t *codes, int64_
         return fail(QADC_EINVAL, "qadc_ivf_search: %d code bytes", B);
     }
 #undef QADC_IVFS_CASE
+    launch(QADC_PROF_SEED, ivfs_light_kernel, dim3((unsigned)ceil_div(nb, 4)), dim3(256), 0, st, probes, nprobe, nb, K,
+           (const unsigned *)pair_off, min_pairs, list_off, n_total, unit, (const unsigned *)flags,
+           (const unsigned *)taus, scan_ws, ws_stride, probes_light, qunits_light);
     QADC_HIP_TRY(hipGetLastError());
     return QADC_OK;
 }

@@ -221,8 +221,10 @@ constexpr int MERGE_FLAT_SLOTS = 16384;  // ... key slots up to which every slot
 // which selects and orders in one step.  Massive ties fall back to the full radix select.
 // Two report regions may exist per query: region B (G workgroups, up to R keys each) written
 // by the single-query kernels, and region A (GA workgroups, up to pitchA keys each) written
-// by the query-tiled kernel.  flags[q] != 0 says that region A of query q is incomplete and
-// region B holds the result; without flags only region B exists.
+// by the query-tiled kernel.  flags[q]: 0 = region A holds the result of query q; 1 = region A is
+// incomplete and region B holds the result; 2 = the result is spread over both regions (the lists
+// of an inverted index scanned partly by one kernel, partly by the other).  Without flags only
+// region B exists.
 template <typename DistT, int KBYTES>
 __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off, int G,
@@ -244,8 +246,12 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     unsigned *counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + counts_off);
     uint64_t *lists = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + lists_off);
     int pitch = R;
-    const bool redone = flags && flags[q] != 0;  // uniform
-    if (flags && !redone) {                      // the tiled kernel's report is the result
+    const unsigned flag = flags ? flags[q] : 1u;  // uniform
+    const bool redone = flags && flag == 1u;
+    const bool both = flag == 2u;
+    unsigned *countsA = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + countsA_off);
+    uint64_t *listsA = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + listsA_off);
+    if (flag == 0u) {                             // the tiled kernel's report is the result
         counts = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + countsA_off);
         lists = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + listsA_off);
         G = GA;
@@ -263,6 +269,12 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
                     if (i + u < c) f(k[u]);
+            }
+        }
+        if (both) {
+            for (int g = 0; g < GA; ++g) {
+                const unsigned c = min(countsA[g], (unsigned)pitchA);
+                for (unsigned i = tid; i < c; i += MERGE_NT) f(listsA[(size_t)g * pitchA + i]);
             }
         }
     };
@@ -323,6 +335,12 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         for (int g = tid + MERGE_WG_PER_THREAD * MERGE_NT; g < G; g += MERGE_NT) {  // very wide grids
             const unsigned c = min(counts[g], (unsigned)pitch);
             for (unsigned i = 0; i < c; ++i) take(lists[(size_t)g * pitch + i]);
+        }
+    }
+    if (both) {  // region A on top of region B (few regions, spread over the whole workgroup)
+        for (int g = 0; g < GA; ++g) {
+            const unsigned c = min(countsA[g], (unsigned)pitchA);
+            for (unsigned i = tid; i < c; i += MERGE_NT) take(listsA[(size_t)g * pitchA + i]);
         }
     }
     if constexpr (ADAPT) {
@@ -449,14 +467,14 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
             if (c) counts[g] = 0;
         }
     }
-    if (redone) {  // the abandoned report of the tiled kernel
-        unsigned *ca = reinterpret_cast<unsigned *>(ws + (size_t)q * ws_stride + countsA_off);
-        uint64_t *la = reinterpret_cast<uint64_t *>(ws + (size_t)q * ws_stride + listsA_off);
-        for (int g = tid; g < GA; g += MERGE_NT) {
-            const unsigned c = min(ca[g], (unsigned)pitchA);
-            for (unsigned i = 0; i < c; ++i) la[(size_t)g * pitchA + i] = 0;
-            if (c) ca[g] = 0;
+    if (redone || both) {  // the abandoned report of the tiled kernel, or the second half of the result
+        __syncthreads();  // (both: every thread is done reading region A)
+        for (int g = 0; g < GA; ++g) {
+            const unsigned c = min(countsA[g], (unsigned)pitchA);
+            for (unsigned i = tid; i < c; i += MERGE_NT) listsA[(size_t)g * pitchA + i] = 0;
         }
+        __syncthreads();
+        for (int g = tid; g < GA; g += MERGE_NT) countsA[g] = 0;
         if (tid == 0) flags[q] = 0;
     }
     unsigned *z = reinterpret_cast<unsigned *>(hdr);
@@ -502,7 +520,7 @@ inline int scan_query_batch(size_t stride, int nq)
 struct Knobs {
     int scan_nt, scan_wgs, seed_min_tiles, seed_wgs, tiled, tiled_seed, scan_f32_wgs;
     int tiled_mfma, mfma_min_q, mfma_min_q2, mfma_min_q4, mfma_waves;
-    int ivf_wgs, ivf_seed, ivf_units, ivf_seed_parts, ivf_shared, ivf_shared_wgs;
+    int ivf_wgs, ivf_seed, ivf_units, ivf_seed_parts, ivf_shared, ivf_shared_wgs, ivf_shared_min_pairs;
 };
 const Knobs &knobs();
 void knobs_refresh();

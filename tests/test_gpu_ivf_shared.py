@@ -154,3 +154,31 @@ def test_workspace_is_left_clean_between_routes(Q, O, monkeypatch):
             assert np.array_equal(got[0], ref[key][0]) and np.array_equal(got[1], ref[key][1]), (route, key)
         ref[key] = got
     monkeypatch.delenv("QADC_IVF_SHARED")
+
+
+@pytest.mark.parametrize("min_pairs", [None, "2", "40"])
+def test_cells_split_between_the_two_scans(Q, O, monkeypatch, min_pairs):
+    """Many cells, Zipf-sized: some are probed by enough queries to be scanned once for all of them, the
+    others stay with the per-query kernel; most queries have cells of both kinds and the two reports are
+    joined.  (QADC_IVF_SHARED_MIN_PAIRS moves the line between the two.)"""
+    coarse, cb, x, index = build_ivf(O, n=150_000, K=400, d=64, m=16, seed=77)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(8)
+    nq, nprobe, R, init = 260, 12, 50, 400
+    queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, x.shape[1]))).astype(np.float32)
+    if min_pairs is not None:
+        monkeypatch.setenv("QADC_IVF_SHARED_MIN_PAIRS", min_pairs)
+    (ids, dist, probes, qluts), (ids2, dist2, _, _) = both_routes(Q, monkeypatch, gix, to_gpu(queries), nprobe, R, init)
+    pr = probes.cpu().numpy()
+    per_cell = np.bincount(pr.ravel(), minlength=400)
+    line = 8 if min_pairs is None else int(min_pairs)
+    shared = per_cell[pr] >= line
+    if line == 8:
+        assert (shared.any(axis=1) & (~shared).any(axis=1)).sum() > nq // 2   # queries with cells of both kinds
+    assert np.array_equal(idx_np(ids), idx_np(ids2))
+    assert np.array_equal(dist.cpu().numpy(), dist2.cpu().numpy())
+    for iq in range(0, nq, 20):
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=pr[iq], qluts=qluts[iq].cpu().numpy())
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
