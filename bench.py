@@ -80,6 +80,8 @@ def parse():
     ap.add_argument("--opq", type=int, default=0, metavar="ROUNDS",
                     help="scan workload: train an optimized product quantizer with this many rounds; database "
                          "vectors are rotated before encoding and every query by qadc_rotate before qadc_search")
+    ap.add_argument("--no-mi-full", action="store_true",
+                    help="ivf workload: skip the multi-index of 2^14 x 2^14 cells over the same codes")
     ap.add_argument("--no-extras", action="store_true",
                     help="scan workload: skip the short runs of configs 3, 4 and 5 nested in the same line")
     ap.add_argument("--separate-calls", action="store_true",
@@ -476,7 +478,7 @@ def run_ivf(args):
         multi_index = {"half_centroids": kh, "cells": K, "index_step_ms_per_batch": round(m0.elapsed_time(m1) / 10, 4),
                        "inverted_index_step_ms_per_batch": round(phase["index"], 4)}
 
-    if multi_index is not None:
+    if multi_index is not None and not getattr(args, "no_mi_full", False):
         multi_index["usual_size"] = multi_index_usual_size(Q, torch, coarse, codes, cb, queries, last, nb, nprobe, R,
                                                            init, dev, args.d)
 

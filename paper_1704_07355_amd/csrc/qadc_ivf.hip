@@ -1009,7 +1009,7 @@ constexpr int IVF_SHARED_MIN_Q = 256;         // smallest batch scanned list by 
 constexpr int IVF_SHARED_MAX_R = 128;         // the region must hold a few dozen times R keys
 constexpr int IVF_SHARED_MAX_K = 1 << 18;     // one workgroup sums the per-cell counts
 
-constexpr int IVF_SHARED_MIN_PAIRS = 8;       // pairs of a cell from which its list is scanned once for all of them
+constexpr int IVF_SHARED_MIN_PAIRS = 4;       // pairs of a cell from which its list is scanned once for all of them
 
 int ivf_shared_scan(int, const int64_t *, const uint8_t *, int64_t, int, const int32_t *, int, int, const uint8_t *,
                     int, char *, size_t, size_t, size_t, int, unsigned *, unsigned *, unsigned *, unsigned *,
@@ -1041,7 +1041,7 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     const int shared_knob = knobs().ivf_shared;
     p->shared = R <= IVF_SHARED_MAX_R && ix->K <= IVF_SHARED_MAX_K && p->seed_per_list > 0 && ix->m <= 64 &&
                 (shared_knob >= 0 ? shared_knob != 0 : nq >= IVF_SHARED_MIN_Q);
-    p->shared_wgs = std::max(1, std::min(65535, knob_or(knobs().ivf_shared_wgs, 4096)));
+    p->shared_wgs = std::max(1, std::min(65535, knob_or(knobs().ivf_shared_wgs, 32768)));
     p->shared_min_pairs = std::max(1, knob_or(knobs().ivf_shared_min_pairs, IVF_SHARED_MIN_PAIRS));
     p->stride = p->l.stride;
     p->countsA_off = p->listsA_off = 0;
