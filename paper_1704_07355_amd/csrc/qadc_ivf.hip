@@ -305,8 +305,21 @@ __global__ __launch_bounds__(256) void ivf_build_luts_kernel(
 __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int m,
     const int32_t *__restrict__ probes, int nprobe, const float *__restrict__ luts, int init, int R,
-    float *__restrict__ qmax, long long unit, unsigned *__restrict__ qunits, int64_t n_total)
+    float *__restrict__ qmax, long long unit, unsigned *__restrict__ qunits, int64_t n_total,
+    char *__restrict__ ws, size_t ws_stride, size_t counts_off, int W, size_t countsA_off)
 {
+    // The control words of the query's scan -- the histograms of its control block and the counts of
+    // its report regions -- are cleared here, at the start of every call: calls of different shapes
+    // lay the workspace out differently, and what one call left as table data may lie where the next
+    // one keeps its counts.
+    {
+        char *base = ws + (size_t)blockIdx.x * ws_stride;
+        unsigned *gh = reinterpret_cast<unsigned *>(base);  // ScanHeader::ghist comes first
+        for (int i = threadIdx.x; i < GH_REP * 256; i += blockDim.x) gh[i] = 0;
+        unsigned *counts = reinterpret_cast<unsigned *>(base + counts_off);
+        for (int i = threadIdx.x; i < W; i += blockDim.x) counts[i] = 0;
+        if (countsA_off && threadIdx.x == 0) *reinterpret_cast<unsigned *>(base + countsA_off) = 0;
+    }
     __shared__ unsigned cand[QADC_MAX_INIT];
     __shared__ unsigned units_s;
     __shared__ long long start[IVF_MAX_NPROBE + 1];  // codes before probe p in the walk
@@ -604,7 +617,9 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     constexpr int NT = IVF_NT;
     using C = ScanCfg<B, NT>;
     constexpr long long UNIT = (long long)IVF_UNIT_TILES * C::TILE;
-    const unsigned me = wgmap[blockIdx.x];  // uniform
+    // without a map (a few queries): Wmax workgroup slots per query, in query order
+    const unsigned me = wgmap ? wgmap[blockIdx.x]
+                              : ((blockIdx.x / (unsigned)Wmax) << 12) | (blockIdx.x % (unsigned)Wmax);  // uniform
     if (me == IVF_NO_WG) return;
     __shared__ __attribute__((aligned(16))) uint8_t ptab[B * 256];
     __shared__ __attribute__((aligned(16))) uint8_t qlut_s[2 * B * 16];
@@ -659,7 +674,7 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
     // huge lists gets up to Wmax of them, a query of short lists a handful) -- the count the
     // map kernel derived from the same number of units.
     const int W = (int)min((long long)Wmax, max(1ll, (units + units_per_wg - 1) / units_per_wg));
-    if (g >= W) return;  // uniform; cannot happen with a consistent map
+    if (g >= W) return;  // uniform; with a map it cannot happen
 
     uint64_t lim = ~0ull;  // keys >= lim cannot be among the R best of this workgroup's codes
     unsigned have = 0;
@@ -970,20 +985,6 @@ __global__ void ivf_take_probes_kernel(const int32_t *__restrict__ in, int nprob
     probes[i] = cell;
 }
 
-// The control words of a batch -- the histograms of the control blocks and the counts of the report
-// regions -- are cleared at the start of every call: calls of different shapes lay the workspace out
-// differently, and what one call left as table data may lie where the next one keeps its counts.
-__global__ __launch_bounds__(256) void ivf_clear_kernel(char *__restrict__ ws, size_t ws_stride, size_t counts_off,
-                                                        int W, size_t countsA_off)
-{
-    char *base = ws + (size_t)blockIdx.x * ws_stride;
-    unsigned *gh = reinterpret_cast<unsigned *>(base);  // ScanHeader::ghist comes first
-    for (int i = threadIdx.x; i < GH_REP * 256; i += 256) gh[i] = 0;
-    unsigned *counts = reinterpret_cast<unsigned *>(base + counts_off);
-    for (int i = threadIdx.x; i < W; i += 256) counts[i] = 0;
-    if (countsA_off && threadIdx.x == 0) *reinterpret_cast<unsigned *>(base + countsA_off) = 0;
-}
-
 // ------------------------------------------------------------------- host
 
 int quantize_luts(int, const float *, int, int, int, const uint8_t *, int64_t, const float *, int, int,
@@ -1005,7 +1006,7 @@ struct IvfPlan {
 };
 
 constexpr int IVF_SHARED_PITCH = MERGE_CAP;   // keys of a query's region: what the merge kernel holds in LDS
-constexpr int IVF_SHARED_MIN_Q = 256;         // smallest batch scanned list by list
+constexpr int IVF_SHARED_MIN_Q = 640;         // smallest batch whose popular lists are scanned once for all (even at 512 on 65536 Zipf lists)
 constexpr int IVF_SHARED_MAX_R = 128;         // the region must hold a few dozen times R keys
 constexpr int IVF_SHARED_MAX_K = 1 << 18;     // one workgroup sums the per-cell counts
 
@@ -1175,7 +1176,8 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
                (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids, ix->Kh,
                probes, nprobe, luts);
         launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
-               m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n);
+               m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n, scan_ws, p.stride, p.l.counts_off,
+               p.W, p.countsA_off);
         int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
                                nullptr, nullptr, st);
         if (rc != QADC_OK) return rc;
@@ -1186,8 +1188,6 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         // a few queries: their lists are sampled by several workgroups each
         const int seed_parts_env = knob_or(knobs().ivf_seed_parts, 0);
         const int seed_parts = seed_parts_env > 0 ? min(seed_parts_env, nprobe) : nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
-        launch(QADC_PROF_SEED, ivf_clear_kernel, dim3(nb), dim3(256), 0, st, scan_ws, p.stride, p.l.counts_off, p.W,
-               p.countsA_off);
         unsigned *flags = p.shared ? (unsigned *)(ws + p.off_flags) : nullptr;
 #define QADC_IVF_SEED_CASE(B_)                                                                          \
     case B_:                                                                                           \
@@ -1217,12 +1217,16 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
                                  qunits_light, unit, p.shared_min_pairs, p.shared_wgs, st);
             if (rc != QADC_OK) return rc;
         }
-        launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap,
-               (const unsigned *)qunits_light, (const unsigned *)flags);
+        // (a few queries need no map: every query gets its p.W workgroup slots in turn)
+        const bool mapped = nb >= 64 || p.shared;
+        if (mapped)
+            launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap,
+                   (const unsigned *)qunits_light, (const unsigned *)flags);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
         launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
-               ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, wgmap, scan_ws, p.stride,            \
+               ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws,   \
+               p.stride,                                                                              \
                p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light, (const unsigned *)flags);  \
         break;
         switch (m / 2) {
