@@ -443,18 +443,46 @@ def run_ivf(args):
     phase = {}
     for name, which in (("index", Q.QADC_PROF_IVF_INDEX), ("tables", Q.QADC_PROF_IVF_TABLES),
                         ("quantize", Q.QADC_PROF_QUANTIZE), ("seed", Q.QADC_PROF_SEED),
-                        ("scan", Q.QADC_PROF_SCAN), ("merge", Q.QADC_PROF_MERGE)):
+                        ("scan", Q.QADC_PROF_SCAN), ("scan_shared", Q.QADC_PROF_IVF_SHARED),
+                        ("merge", Q.QADC_PROF_MERGE)):
         phase[name] = Q.qadc_profile_read(which)[0]
     Q.qadc_profile_enable(False)
     h_probes = probes.cpu().numpy()
-    scanned = float(sizes[h_probes.clip(0)].sum())  # codes scanned by the last batch
+    scanned = float(sizes[h_probes.clip(0)].sum())  # (code, query) pairs of the last batch
     row = m // 2
-    ach = scanned * row / (phase["scan"] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "ivf_scan_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
-                "traffic_note": "depends on the batch; measured at 1.01 x the algorithmic bytes "
-                                "(profiles/hbm_traffic_configs_3_4_5.md)",
-                "scan_ms_per_batch": round(phase["scan"], 3), "codes_scanned_per_query": round(scanned / nb)}
+    if phase["scan_shared"] > 0:
+        # Large batches: the lists probed by several queries are scanned once for all of them on the
+        # matrix units (ivfs_scan_kernel), the others query by query (ivf_scan_kernel).  The method's
+        # work is m lookup-adds per (code, query) pair; as for the batched exhaustive scan, the ceiling
+        # quoted for it is the byte-lane rate of the vector ALU.
+        per_cell = np.bincount(h_probes[h_probes >= 0].ravel(), minlength=K)
+        min_pairs = int(os.environ.get("QADC_IVF_SHARED_MIN_PAIRS", "4"))
+        shared = (h_probes >= 0) & (per_cell[h_probes.clip(0)] >= min_pairs)
+        pairs_shared = float(sizes[h_probes[shared]].sum())
+        pairs_own = scanned - pairs_shared
+        codes_once = float(sizes[per_cell >= min_pairs].sum())  # codes of the shared lists, each read once per 32 pairs
+        ach = pairs_shared * m / (phase["scan_shared"] * 1e-3) / 1e12
+        own = pairs_own * row / (phase["scan"] * 1e-3) / 1e9 if phase["scan"] > 0 else 0.0
+        roofline = {"bound": "alu", "kernel": "ivfs_scan_kernel", "achieved": round(ach, 2), "peak": ALU_PEAK_TLOOKUPS,
+                    "unit": "T lookup-adds/s", "frac": round(ach / ALU_PEAK_TLOOKUPS, 4), "traffic": None,
+                    "note": "m lookup-adds per (code, query) pair of the lists shared by >= %d queries of the batch, "
+                            "against the byte-lane ceiling of the vector ALU; executed as one-hot int8 products on "
+                            "the sparse matrix instruction, 32 pairs per wavefront whatever the number that exist"
+                            % min_pairs,
+                    "scan_shared_ms_per_batch": round(phase["scan_shared"], 3),
+                    "pairs_shared_per_query": round(pairs_shared / nb), "shared_list_codes": round(codes_once),
+                    "per_query_kernel": {"kernel": "ivf_scan_kernel", "bound": "hbm", "achieved": round(own, 1),
+                                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(own / HBM_PEAK_GBPS, 4),
+                                         "scan_ms_per_batch": round(phase["scan"], 3),
+                                         "pairs_per_query": round(pairs_own / nb)},
+                    "codes_scanned_per_query": round(scanned / nb)}
+    else:
+        ach = scanned * row / (phase["scan"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "ivf_scan_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "traffic_note": "depends on the batch; measured at 1.01 x the algorithmic bytes "
+                                    "(profiles/hbm_traffic_configs_3_4_5.md)",
+                    "scan_ms_per_batch": round(phase["scan"], 3), "codes_scanned_per_query": round(scanned / nb)}
 
     # beside it: the Index step of an inverted multi-index with as many cells (two quantizers of
     # sqrt(K) half-centroids, seeded at random: only the step's cost is measured here)

@@ -425,7 +425,8 @@ int qadc_rotate(const float *rot, int d, const float *x, int64_t n, float *y, vo
 #define QADC_PROF_QUANTIZE   6  /* qadc_quantize_luts kernel */
 #define QADC_PROF_PREPARE    7  /* tables + quantizer + sampling kernel of qadc_search */
 #define QADC_PROF_ROTATE     8  /* qadc_rotate kernel */
-#define QADC_PROF_COUNT  9
+#define QADC_PROF_IVF_SHARED 9  /* shared-list scan kernel of qadc_ivf_search (large batches) */
+#define QADC_PROF_COUNT  10
 int qadc_profile_enable(int on);
 /* As qadc_profile_enable(1), but only the kernels of slot `which` carry events: their neighbours in
  * the stream are launched as in an untimed run. */

@@ -24,7 +24,7 @@ QADC_U8_4BIT, QADC_F32_4BIT, QADC_F32_8BIT, QADC_U8_8BIT, QADC_U8_6BIT = 0, 1, 2
 QADC_WS_SCAN_TOPK, QADC_WS_SCAN_F32_4BIT, QADC_WS_SCAN_F32_8BIT, QADC_WS_SEARCH, QADC_WS_SCAN_U8_8BIT = 0, 1, 2, 3, 4
 QADC_WS_SCAN_U8_6BIT = 5
 (QADC_PROF_SCAN, QADC_PROF_MERGE, QADC_PROF_SEED, QADC_PROF_IVF_INDEX, QADC_PROF_IVF_TABLES,
- QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE, QADC_PROF_ROTATE) = range(9)
+ QADC_PROF_TABLES, QADC_PROF_QUANTIZE, QADC_PROF_PREPARE, QADC_PROF_ROTATE, QADC_PROF_IVF_SHARED) = range(10)
 QADC_LAYOUT_STANDARD, QADC_LAYOUT_TRANSPOSED = 0, 1
 
 EXPORTS = (

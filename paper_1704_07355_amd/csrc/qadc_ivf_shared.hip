@@ -438,13 +438,13 @@ int ivf_shared_scan(int B, const int64_t *list_off, const uint8_t *codes, int64_
            (const unsigned *)pair_off, pair_cnt, pairs);
 #define QADC_IVFS_CASE(B_)                                                                                      \
     case B_:                                                                                                   \
-        launch(QADC_PROF_SCAN, ivfs_scan_kernel<B_>, dim3((unsigned)wgs), dim3(64), 0, st, 0, list_off, codes,  \
+        launch(QADC_PROF_IVF_SHARED, ivfs_scan_kernel<B_>, dim3((unsigned)wgs), dim3(64), 0, st, 0, list_off, codes,  \
                n_total, K, (const unsigned *)pair_off, (const unsigned *)item_off0, (const unsigned *)pairs,   \
                nprobe, qluts, (const unsigned *)taus, scan_ws, ws_stride, countsA_off, listsA_off, pitchA,     \
                flags);                                                                                         \
         launch(QADC_PROF_SEED, ivfs_refine_kernel, dim3((unsigned)nb), dim3(IVFS_REFINE_NT), 0, st, scan_ws,    \
                ws_stride, countsA_off, listsA_off, pitchA, R, taus, (const unsigned *)flags);                  \
-        launch(QADC_PROF_SCAN, ivfs_scan_kernel<B_>, dim3((unsigned)wgs), dim3(64), 0, st, 1, list_off, codes,  \
+        launch(QADC_PROF_IVF_SHARED, ivfs_scan_kernel<B_>, dim3((unsigned)wgs), dim3(64), 0, st, 1, list_off, codes,  \
                n_total, K, (const unsigned *)pair_off, (const unsigned *)item_off1, (const unsigned *)pairs,   \
                nprobe, qluts, (const unsigned *)taus, scan_ws, ws_stride, countsA_off, listsA_off, pitchA,     \
                flags);                                                                                         \
