@@ -188,11 +188,11 @@ def accuracy(Q, torch, np, cb, codes, raw, queries, R, init, rot=None, nbins=255
 # HBM bytes per scan_u8_kernel launch from the FETCH_SIZE / WRITE_SIZE counter runs summarized in
 # profiles/scan_u8_config2_hbm_traffic.md (scaled by a plain copy of known size); valid for the
 # workload it was measured on only: (n, m) -> (bytes read, bytes written).
-SCAN_TRAFFIC = {(10_000_000, 16): (39141.8 * 1.9994 * 1024, 53.1 * 1.0 * 1024)}
+SCAN_TRAFFIC = {(10_000_000, 16): (39152.4 * 1.9994 * 1024, 53.1 * 1.0 * 1024)}
 TILED_TRAFFIC = 8_680_000_000   # config 3, scan_u8_tiled16_kernel<16, 2>: HBM bytes read per 256-query batch
 COMPARE_TRAFFIC = 400_060_000   # config 5, scan_u8_kernel<8, 256>: HBM bytes read per query
 
-MFMA_TRAFFIC = 1_622_500_000    # config 3, scan_u8_mfma_kernel<16>: HBM bytes read per 256-query batch
+MFMA_TRAFFIC = 1_619_000_000    # config 3, scan_u8_mfma_kernel<16>: HBM bytes read per 256-query batch
 MFMA_I8_PEAK_TOPS = 5000.0      # dense int8 MFMA peak of the chip
 ALU_PEAK_TLOOKUPS = 157.3  # 256 CUs x 64 lanes x 2.4 GHz x 4 byte lanes per 32-bit lane-op
 
