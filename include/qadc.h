@@ -17,8 +17,13 @@
  *  - Scratch memory comes from the caller: `workspace` (device, 256-byte
  *    aligned) of at least qadc_workspace_bytes(...) bytes.  The library never
  *    allocates device memory.  A workspace holds control words that every call
- *    expects to be zero and leaves zero: clear it ONCE with qadc_workspace_init
- *    before its first use (and again after a call on it failed or was aborted).
+ *    expects to be zero and leaves zero: clear it with qadc_workspace_init before
+ *    its first use, after a call on it failed or was aborted, and before a call
+ *    whose entry point or sizes (n, m, nq, R, nprobe) differ from those of the
+ *    call before it on that workspace -- another shape lays the workspace out
+ *    differently, and table data of the earlier call may lie where the new one
+ *    keeps its control words.  Calls of one shape need no clearing in between.
+ *    (qadc_ivf_search clears its own control words at every call.)
  *    Calls that share a workspace must be ordered on one stream.
  *  - Return value: QADC_OK, or a negative error.  On QADC_EINVAL / QADC_ENOMEM
  *    nothing was enqueued and the outputs are untouched.  qadc_last_error()
@@ -207,8 +212,9 @@ int qadc_search(const float *codebooks, int d, int m, const float *queries, int 
  *     cut into several launch sequences on `stream` (same results).
  *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU -- from two
  *     streams or two threads -- race; order them on one stream.  The array is cleared by a kernel
- *     on `stream` at the first call on a GPU and after a call that failed with QADC_EHIP; every
- *     successful call leaves it cleared for the next.
+ *     on `stream` at the first call on a GPU, at a call whose sizes (n, m, nq, R) differ from the
+ *     previous call's on that GPU, and after a call that failed with QADC_EHIP; calls of one shape
+ *     leave it cleared for the next.
  */
 #define QADC_STATIC_SCRATCH_BYTES (32u << 20)
 int qadc_search_static(const float *codebooks, int d, int m, const float *queries, int nq,
@@ -452,9 +458,10 @@ int qadc_pq_train(const float *train, int64_t n, int d, int m, int ksub, const i
 size_t qadc_workspace_bytes(int call, int64_t n, int m, int nq, int R);
 
 /*
- * Clears a workspace (asynchronous memset on `stream`).  Required once before the
- * first call that uses the workspace; every call leaves the workspace ready for the
- * next one.  Do not record it into a HIP graph: clear the workspace before capture.
+ * Clears a workspace (asynchronous memset on `stream`).  Required before the first call
+ * that uses the workspace and before a call of another shape (see the conventions at the
+ * top); a call leaves the workspace ready for the next call of its own shape.  Do not
+ * record it into a HIP graph: clear the workspace before capture.
  */
 int qadc_workspace_init(void *workspace, size_t bytes, void *stream);
 

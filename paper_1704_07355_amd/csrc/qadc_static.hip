@@ -31,7 +31,11 @@ namespace {
 constexpr int MAX_DEVICES = 64;
 struct DeviceScratch {
     void *ptr = nullptr;   // device address of `scratch` on this GPU
-    bool clean = false;    // control words known to be zero (every successful call leaves them so)
+    bool clean = false;    // control words known to be zero where the next call of the shape below keeps them
+    // shape of the last call: a call of another shape lays the array out differently, and the table
+    // data the last one left may lie where the new one keeps its control words
+    int64_t n = -1;
+    int m = 0, nb = 0, R = 0;
 };
 DeviceScratch g_dev[MAX_DEVICES];
 std::mutex g_mu;
@@ -73,9 +77,11 @@ int search_static(const float *codebooks, int d, int m, const float *queries, in
             return fail(QADC_EHIP, "qadc_search_static: bad address %p for the scratch array", p);
         ds.ptr = p;
     }
+    if (ds.n != n || ds.m != m || ds.nb != nb || ds.R != R) ds.clean = false;
+    ds.n = n; ds.m = m; ds.nb = nb; ds.R = R;
     if (!ds.clean) {
-        // first call on this GPU, or a call failed part-way: a fill kernel, not a memset node, so
-        // that a caller may capture the call into a graph
+        // first call on this GPU, a call of a new shape, or a call failed part-way: a fill kernel, not
+        // a memset node, so that a caller may capture the call into a graph
         hipLaunchKernelGGL(static_scratch_clear_kernel, dim3(2048), dim3(256), 0, st, (uint4 *)ds.ptr,
                            STATIC_SCRATCH_BYTES / 16);
         QADC_HIP_TRY(hipGetLastError());

@@ -55,9 +55,13 @@ def test_static_scratch_search_equals_workspace_search():
     i1, d1, q1 = _call_both(Q, L, torch, cb, queries[:1].contiguous(), big, R, init)
     small = big[:30_001].contiguous()
     i2, d2, q2 = _call_both(Q, L, torch, cb, queries[:3].contiguous(), small, R, init)
+    # third call: a larger shape again (a batch over the long database): the array is laid out anew and
+    # table data of the calls before must not be taken for control words
+    i3, d3, q3 = _call_both(Q, L, torch, cb, queries[:16].contiguous(), big, R, init)
     # and against the oracle on the library's own tables (bit-exact)
     for (idx, dist, ql, codes_np, nq) in ((i1, d1, q1, np.tile(c["codes"], (4, 1)), 1),
-                                          (i2, d2, q2, np.tile(c["codes"], (4, 1))[:30_001], 3)):
+                                          (i2, d2, q2, np.tile(c["codes"], (4, 1))[:30_001], 3),
+                                          (i3, d3, q3, np.tile(c["codes"], (4, 1)), 16)):
         for iq in range(nq):
             wi, wd = O.top_r(O.scan_saturating(ql[iq].cpu().numpy(), codes_np), R, pad_dist=255)
             assert np.array_equal(idx[iq].cpu().numpy().view(np.uint32), wi)
