@@ -150,6 +150,18 @@ typedef int v2i_t __attribute__((ext_vector_type(2)));
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
+typedef long v8l_t __attribute__((ext_vector_type(8)));
+
+// Sixteen accumulator registers set to zero with eight 64-bit moves written straight into the
+// registers the first product accumulates in (the sparse instruction has no zero addend; left to
+// itself the compiler clears them with 23 moves per step).
+__device__ __forceinline__ v16i_t mfma_zero_acc()
+{
+    v8l_t z;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) asm volatile("v_mov_b64 %0, 0" : "=v"(z[k]));
+    return __builtin_bit_cast(v16i_t, z);
+}
 
 // One wavefront per workgroup; the work items (cell, set of 32 pairs, chunk of one part of the
 // cell's list) are dealt to the workgroups in turn.  The arithmetic of an item is that of
@@ -310,9 +322,7 @@ __global__ __launch_bounds__(64) void ivfs_scan_kernel(
 #pragma unroll
             for (int s = 0; s < SUB; ++s) {
                 if (t0 + 32 * s >= c1) break;  // uniform
-                v16i_t acc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0;
+                v16i_t acc = mfma_zero_acc();
 #pragma unroll
                 for (int jp = 0; jp < NP; ++jp) {
                     const Operand a = a0;

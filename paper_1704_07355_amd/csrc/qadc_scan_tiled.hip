@@ -447,7 +447,19 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
+typedef long v8l_t __attribute__((ext_vector_type(8)));
 constexpr int MFMA_SUB = 2;    // 32-code steps per load
+
+// Sixteen accumulator registers set to zero with eight 64-bit moves written straight into the
+// registers the first product accumulates in (left to itself the compiler clears them with 23
+// moves, and every vector instruction costs the matrix pipe its issue slot).
+__device__ __forceinline__ v16i_t mfma_zero_acc()
+{
+    v8l_t z;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) asm volatile("v_mov_b64 %0, 0" : "=v"(z[k]));
+    return __builtin_bit_cast(v16i_t, z);
+}
 
 // G: groups of 32 queries per wavefront.  2 for large batches of up to 32 code bytes (the table
 // operands of 64 queries fill 128 registers when B = 16); 1 for B = 32 and for batches that would
@@ -594,9 +606,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
             if (t0 + 32 * s >= c1) break;  // uniform
             v16i_t acc[G];  // (the sparse instruction has no zero addend: cleared by hand)
 #pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[g][v] = 0;
+            for (int g = 0; g < G; ++g) acc[g] = mfma_zero_acc();
 #pragma unroll
             for (int jp = 0; jp < NP; ++jp) {
                 const Operand a = a0;
