@@ -25,6 +25,7 @@
 // (sum, storage position).
 
 #include "qadc_scan_common.h"
+#include "qadc_onehot.h"
 
 namespace qadc {
 
@@ -146,23 +147,6 @@ __global__ __launch_bounds__(256) void ivfs_place_kernel(const int32_t *__restri
     pairs[pair_off[cell] + old - 1u] = (unsigned)i;
 }
 
-typedef int v2i_t __attribute__((ext_vector_type(2)));
-typedef int v4i_t __attribute__((ext_vector_type(4)));
-typedef int v8i_t __attribute__((ext_vector_type(8)));
-typedef int v16i_t __attribute__((ext_vector_type(16)));
-typedef long v8l_t __attribute__((ext_vector_type(8)));
-
-// Sixteen accumulator registers set to zero with eight 64-bit moves written straight into the
-// registers the first product accumulates in (the sparse instruction has no zero addend; left to
-// itself the compiler clears them with 23 moves per step).
-__device__ __forceinline__ v16i_t mfma_zero_acc()
-{
-    v8l_t z;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) asm volatile("v_mov_b64 %0, 0" : "=v"(z[k]));
-    return __builtin_bit_cast(v16i_t, z);
-}
-
 // One wavefront per workgroup; the work items (cell, set of 32 pairs, chunk of one part of the
 // cell's list) are dealt to the workgroups in turn.  The arithmetic of an item is that of
 // scan_u8_mfma_kernel with one group of 32 "queries" = pairs.
@@ -188,12 +172,7 @@ __global__ __launch_bounds__(64) void ivfs_scan_kernel(
     const int l = threadIdx.x;
     const int row = l & 31, half = l >> 5;
     if (l < QW) cnt[l] = 0;
-    if (l < 16) {
-        const int pr = l >> 2, pos = l & 3;
-        const int bits = (0xcccc & ~(15 << (4 * pr))) | ((pos | ((pos == 3 ? 2 : 3) << 2)) << (4 * pr));
-        nibval[l] = v4i_t{pr < 2 ? 1 << (16 * pr) : 0, pr >= 2 ? 1 << (16 * (pr - 2)) : 0, 0, 0};
-        nibpos[l] = v4i_t{bits, 0, 0, 0};
-    }
+    if (l < 16) onehot_nibble_entry(l, nibval, nibpos);
     __syncthreads();
     const unsigned total = item_off[K];
     const unsigned nibsh = half ? 0u : 4u;

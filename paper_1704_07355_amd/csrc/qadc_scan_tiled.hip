@@ -23,6 +23,7 @@
 #include <algorithm>
 
 #include "qadc_scan_tiled.h"
+#include "qadc_onehot.h"
 
 namespace qadc {
 
@@ -444,22 +445,7 @@ bool make_tiled_plan(int64_t n, int m, int nq, bool codes4, TiledPlan *t)
 // of query (l mod 32): each is compared with that query's bound, and the rare pass is appended to
 // the query's list in LDS.  Outputs as the other query-tiled kernels: lists per (query, chunk), a
 // flag on overflow.  (The matrix units multiply signed bytes; the entries go in shifted by 128.)
-typedef int v4i_t __attribute__((ext_vector_type(4)));
-typedef int v8i_t __attribute__((ext_vector_type(8)));
-typedef int v16i_t __attribute__((ext_vector_type(16)));
-typedef long v8l_t __attribute__((ext_vector_type(8)));
 constexpr int MFMA_SUB = 2;    // 32-code steps per load
-
-// Sixteen accumulator registers set to zero with eight 64-bit moves written straight into the
-// registers the first product accumulates in (left to itself the compiler clears them with 23
-// moves, and every vector instruction costs the matrix pipe its issue slot).
-__device__ __forceinline__ v16i_t mfma_zero_acc()
-{
-    v8l_t z;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) asm volatile("v_mov_b64 %0, 0" : "=v"(z[k]));
-    return __builtin_bit_cast(v16i_t, z);
-}
 
 // G: groups of 32 queries per wavefront.  2 for large batches of up to 32 code bytes (the table
 // operands of 64 queries fill 128 registers when B = 16); 1 for B = 32 and for batches that would
@@ -517,14 +503,7 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
         }
     }
     for (int i = l; i < QW; i += 64) cnt[i] = 0;
-    if (l < 16) {
-        // pair l / 4 holds the 1 in its first value, at position l mod 4; every other stored value is 0
-        // (the two positions of a pair are kept different: (0, 3) for the empty pairs)
-        const int pr = l >> 2, pos = l & 3;
-        const int bits = (0xcccc & ~(15 << (4 * pr))) | ((pos | ((pos == 3 ? 2 : 3) << 2)) << (4 * pr));
-        nibval[l] = v4i_t{pr < 2 ? 1 << (16 * pr) : 0, pr >= 2 ? 1 << (16 * (pr - 2)) : 0, 0, 0};
-        nibpos[l] = v4i_t{bits, 0, 0, 0};
-    }
+    if (l < 16) onehot_nibble_entry(l, nibval, nibpos);
     __syncthreads();
 
     // codes: lane (row, half) reads code `row` of each 32-code step (both halves read the same code).
@@ -545,7 +524,6 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     // the sparse operand of code bytes 2jp and 2jp + 1 of a code whose words are w[]: this lane's
     // nibble of either byte; its value bytes (8) and position bits come from the nibble table in LDS
     // at offset 16 * nibble (an 8-byte and a 4-byte read each, straight into their registers)
-    typedef int v2i_t __attribute__((ext_vector_type(2)));
     struct Operand {  // as read; put together only where it is used, so that nothing waits for the reads early
         v2i_t v0, v1;
         int p0, p1;
