@@ -543,8 +543,14 @@ __global__ __launch_bounds__(IVF_MAP_NT) void ivf_wgmap_kernel(const unsigned *_
     for (int q = tid; q < nb; q += IVF_MAP_NT) un[q] = (flags && flags[q] != 1u) ? qunits_alt[q] : qunits[q];
     if (tid == 0) carry = 0;
     __syncthreads();
-    // rank by (units descending, query ascending): a total order, so ranks are distinct
+    // rank by (units descending, query ascending): a total order, so ranks are distinct.  (With
+    // `flags` the long lists have been scanned elsewhere and what is left is short and even: the
+    // queries keep their order, which saves the nb x nb comparisons.)
     for (int q = tid; q < nb; q += IVF_MAP_NT) {
+        if (flags) {
+            byrank[q] = (unsigned)q;
+            continue;
+        }
         const unsigned u = un[q];
         unsigned r = 0;
         for (int o = 0; o < nb; ++o) {
