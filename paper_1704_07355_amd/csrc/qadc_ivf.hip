@@ -297,6 +297,55 @@ __global__ __launch_bounds__(256) void ivf_build_luts_kernel(
     }
 }
 
+// The same tables for batches: one workgroup per query, one thread per table entry (m * 16 threads);
+// the thread keeps its centroid's sub-vector in registers and walks the query's probed cells, reading
+// the cell's coarse centroid (or half-centroids) where its sub-vector lies.  Same arithmetic, value by
+// value, as ivf_build_luts_kernel; a workgroup per (query, cell) spends most of its time starting up.
+template <int DSUB>
+__global__ __launch_bounds__(1024) void ivf_build_luts_batch_kernel(
+    const float *__restrict__ codebooks, int d, int m, const float *__restrict__ queries,
+    const float *__restrict__ coarse, const float *__restrict__ halves, const uint32_t *__restrict__ cell_ids,
+    int Kh, const int32_t *__restrict__ probes, int nprobe, float *__restrict__ luts)
+{
+    const int q = blockIdx.x;
+    const int e = threadIdx.x;  // entry: table j = e / 16, centroid e % 16
+    constexpr int dsub = DSUB;  // d / m
+    const int entries = m * 16;
+    if (e >= entries) return;
+    const int j = e >> 4;
+    const int t0 = j * dsub;
+    double c[DSUB], y[DSUB];
+#pragma unroll
+    for (int t = 0; t < dsub; ++t) {
+        c[t] = (double)codebooks[(size_t)e * dsub + t];
+        y[t] = (double)queries[(size_t)q * d + t0 + t];
+    }
+    const int dh = d >> 1;
+    for (int p = 0; p < nprobe; ++p) {
+        const int cell = probes[(size_t)q * nprobe + p];
+        float *out = luts + ((size_t)q * nprobe + p) * entries;
+        if (cell < 0) {
+            out[e] = __builtin_inff();
+            continue;
+        }
+        const float *cen;  // the centroid's components t0 .. t0 + dsub - 1 (inside one half)
+        if (coarse) {
+            cen = coarse + (size_t)cell * d + t0;
+        } else {
+            const unsigned id = cell_ids[cell];
+            cen = t0 < dh ? halves + (size_t)(id / (unsigned)Kh) * dh + t0
+                          : halves + ((size_t)Kh + id % (unsigned)Kh) * dh + (t0 - dh);
+        }
+        double acc = 0.0;
+#pragma unroll
+        for (int t = 0; t < dsub; ++t) {
+            const double df = (y[t] - (double)cen[t]) - c[t];
+            acc += df * df;
+        }
+        out[e] = (float)acc;
+    }
+}
+
 // ------------------------------------------------------------------- qmax
 
 // qmax[q] = min(R, n_walk)-th smallest float ADC distance (Eq. (2), float32, increasing j)
@@ -1178,9 +1227,28 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             }
         }
         // Tables
-        launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
-               (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids, ix->Kh,
-               probes, nprobe, luts);
+        bool batch_tables = nb >= 64;
+        if (batch_tables) {
+#define QADC_LUTS_CASE(D_)                                                                                       \
+    case D_:                                                                                                    \
+        launch(QADC_PROF_IVF_TABLES, ivf_build_luts_batch_kernel<D_>, dim3(nb), dim3(m * 16), 0, st, ix->codebooks, d, \
+               m, yq, ix->coarse, ix->halves, ix->cell_ids, ix->Kh, probes, nprobe, luts);                      \
+        break;
+            switch (d / m) {
+                QADC_LUTS_CASE(2)
+                QADC_LUTS_CASE(4)
+                QADC_LUTS_CASE(6)
+                QADC_LUTS_CASE(8)
+                QADC_LUTS_CASE(16)
+            default:
+                batch_tables = false;
+            }
+#undef QADC_LUTS_CASE
+        }
+        if (!batch_tables)
+            launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
+                   (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids,
+                   ix->Kh, probes, nprobe, luts);
         launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
                m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n, scan_ws, p.stride, p.l.counts_off,
                p.W, p.countsA_off);
