@@ -30,7 +30,7 @@
 namespace qadc {
 
 constexpr unsigned IVFS_NONE = 0xffffffffu;
-constexpr int IVFS_CHUNK = 8192;   // codes of a list per work item, at most (relative positions fit 24 bits)
+constexpr int IVFS_CHUNK = 4096;   // codes of a list per work item, at most (relative positions fit 24 bits)
 constexpr int IVFS_LC = 64;        // keys a wavefront holds per pair before it writes them out
 
 // codes of the leading part of a list of n codes: 1/16, whole 32-code steps, at least one
