@@ -166,8 +166,8 @@ __global__ __launch_bounds__(64) void ivfs_scan_kernel(
     constexpr int NP = B / 2;    // pairs of code bytes = instructions per 32-code step
     __shared__ unsigned keys[QW][LC];
     __shared__ unsigned cnt[QW];
-    __shared__ v4i_t nibval[16];
-    __shared__ v4i_t nibpos[16];
+    __shared__ v2i_t nibval[16];
+    __shared__ v2i_t nibpos[16];
 
     const int l = threadIdx.x;
     const int row = l & 31, half = l >> 5;
@@ -175,7 +175,6 @@ __global__ __launch_bounds__(64) void ivfs_scan_kernel(
     if (l < 16) onehot_nibble_entry(l, nibval, nibpos);
     __syncthreads();
     const unsigned total = item_off[K];
-    const unsigned nibsh = half ? 0u : 4u;
 
     for (unsigned item = blockIdx.x; item < total; item += gridDim.x) {  // uniform
         // the cell of the item: the last one whose first item is not beyond it
@@ -257,7 +256,7 @@ __global__ __launch_bounds__(64) void ivfs_scan_kernel(
             int p0, p1;
         };
         auto operand = [&](const unsigned (&w)[WPC], int jp) {
-            const unsigned x = (w[jp >> 1] << nibsh) & 0xf0f0f0f0u;
+            const unsigned x = onehot_nibble_offsets(w[jp >> 1], half);
             const unsigned o0 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1), 8), o1 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1) + 8, 8);
             const char *tv = reinterpret_cast<const char *>(nibval), *tp = reinterpret_cast<const char *>(nibpos);
             return Operand{*reinterpret_cast<const v2i_t *>(tv + o0), *reinterpret_cast<const v2i_t *>(tv + o1),

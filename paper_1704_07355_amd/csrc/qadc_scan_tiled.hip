@@ -461,11 +461,11 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
     constexpr int LC = (G > 2) ? TILED_LCAP / 2 : TILED_LCAP;  // keys kept per query (LDS: 16 KiB of lists)
     __shared__ unsigned keys[QW][LC];
     __shared__ unsigned cnt[QW];
-    // of nibble c, at offset 16 c of either table: the 8 value bytes (byte 2 (c / 4) is 1) and the
+    // of nibble c, at offset 8 c of either table: the 8 value bytes (byte 2 (c / 4) is 1) and the
     // position bits.  (Two tables, so that the two reads of a nibble stay an 8-byte and a 4-byte read
     // that land in the operand's registers, instead of one 12-byte read that has to be moved there.)
-    __shared__ v4i_t nibval[16];
-    __shared__ v4i_t nibpos[16];
+    __shared__ v2i_t nibval[16];
+    __shared__ v2i_t nibpos[16];
 
     const int l = threadIdx.x;
     const int row = l & 31, half = l >> 5;
@@ -519,18 +519,17 @@ __global__ __launch_bounds__(64) void scan_u8_mfma_kernel(
             for (int k = 0; k < WPC; ++k) dst[s][k] = src[k];
         }
     };
-    const unsigned nibsh = half ? 0u : 4u;  // low nibbles (lanes 0..31) are moved up to the high ones' place
     fetch(c0, cn);
     // the sparse operand of code bytes 2jp and 2jp + 1 of a code whose words are w[]: this lane's
     // nibble of either byte; its value bytes (8) and position bits come from the nibble table in LDS
-    // at offset 16 * nibble (an 8-byte and a 4-byte read each, straight into their registers)
+    // at offset 8 * nibble (an 8-byte and a 4-byte read each, straight into their registers)
     struct Operand {  // as read; put together only where it is used, so that nothing waits for the reads early
         v2i_t v0, v1;
         int p0, p1;
     };
     auto operand = [&](const unsigned (&w)[WPC], int jp) {
-        // every byte of x: 16 * (this lane's nibble of the code byte), the offset of the nibble's entries
-        const unsigned x = (w[jp >> 1] << nibsh) & 0xf0f0f0f0u;
+        // every byte of x: 8 * (this lane's nibble of the code byte), the offset of the nibble's entries
+        const unsigned x = onehot_nibble_offsets(w[jp >> 1], half);
         const unsigned o0 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1), 8), o1 = __builtin_amdgcn_ubfe(x, 16 * (jp & 1) + 8, 8);
         const char *tv = reinterpret_cast<const char *>(nibval), *tp = reinterpret_cast<const char *>(nibpos);
         return Operand{*reinterpret_cast<const v2i_t *>(tv + o0), *reinterpret_cast<const v2i_t *>(tv + o1),
