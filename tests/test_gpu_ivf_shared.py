@@ -182,3 +182,28 @@ def test_cells_split_between_the_two_scans(Q, O, monkeypatch, min_pairs):
                                      probes=pr[iq], qluts=qluts[iq].cpu().numpy())
         assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
         assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
+
+
+@pytest.mark.parametrize("m,nprobe,R", [(16, 64, 128), (64, 100, 30)])
+def test_large_batch_takes_the_shared_route_by_itself(Q, O, m, nprobe, R):
+    """700 queries (no knob set: calls of 640 queries and more share lists), most cells probed by most
+    queries -- many sets of 32 pairs per cell -- with the largest R and nprobe beyond one table chunk of the
+    seed kernel; against the oracle and against the same queries sent in calls of 100 (per-query scan)."""
+    import torch
+    coarse, cb, x, index = build_ivf(O, n=100_000, K=100, d=64, m=m, seed=300 + m)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(17)
+    nq, init = 700, 500
+    queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, x.shape[1]))).astype(np.float32)
+    gq = to_gpu(queries)
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, gq, nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    for s in range(0, nq, 100):
+        i2, d2 = Q.qadc_ivf_search(gix, gq[s:s + 100].contiguous(), nprobe, R, init)
+        assert np.array_equal(idx_np(i2), idx_np(ids)[s:s + 100]), s
+        assert np.array_equal(d2.cpu().numpy(), dist.cpu().numpy()[s:s + 100]), s
+    for iq in range(0, nq, 140):
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
