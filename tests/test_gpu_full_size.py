@@ -121,14 +121,19 @@ def test_config4_ivf_search(env, n):
     """Inverted index of the benchmark's shape (K = 65536, Zipf(0.8) lists, m = 32, nprobe = 64) at
     N = 1e8 and at the full N = 1e9: a 4096-query batch, the benchmark's; for a sample of its queries the oracle
     rescans every probed list with the GPU's cells and tables and selects by (sum, storage
-    position)."""
+    position); vector ids are a hash of the position."""
     Q, torch, bench, O, cref = env
     dev = torch.device("cuda:0")
     K, m, R, init, nprobe, nb = 65536, 32, 100, 1000, 64, 4096
     index, sizes, queries = bench.build_ivf_index(Q, torch, np, n, K, m, nb, dev)
+    coarse, list_off, codes, _, cb = index.tensors
+    # vector ids that are not the storage positions: id(p) = (p * 2654435761 + 12345) mod 2^32
+    vid = torch.arange(n, dtype=torch.int64, device=dev)
+    vid.mul_(2654435761).add_(12345).bitwise_and_(0xFFFFFFFF)
+    vid = torch.where(vid >= 2 ** 31, vid - 2 ** 32, vid).to(torch.int32)   # the same 32 bits, as int32
+    index = Q.IvfIndex(coarse, list_off, codes, vid, cb)
     ids, dist, probes, qluts = Q.qadc_ivf_search(index, queries, nprobe, R, init, debug=True)
     torch.cuda.synchronize()
-    coarse, list_off, codes, _, cb = index.tensors
     h_off = list_off.cpu().numpy()
     h_probes = probes.cpu().numpy()
     for iq in (0, 1, 7, 63, 64, 255, 256, 1000, 2047, 2048, 3333, 4095):
@@ -142,5 +147,23 @@ def test_config4_ivf_search(env, n):
         sums, pos = np.concatenate(sums), np.concatenate(pos)
         order = np.argsort(pos, kind="stable")  # storage position decides ties
         sel, d = O.top_r(sums[order], R, pad_dist=255)
-        assert np.array_equal(idx_np(ids)[iq].astype(np.int64), pos[order][sel]), iq  # ids = positions here
+        want_ids = (pos[order][sel] * 2654435761 + 12345) & 0xFFFFFFFF
+        assert np.array_equal(idx_np(ids)[iq].astype(np.int64), want_ids), iq
         assert np.array_equal(dist[iq].cpu().numpy(), d), iq
+    # the float side at this size: the oracle's own cells, tables and quantizer for a few queries
+    h_coarse, h_cb = coarse.cpu().numpy(), cb.cpu().numpy()
+    for iq in (0, 1000, 4095):
+        y = queries[iq].cpu().numpy()
+        want_probes = O.ivf_probes(y, h_coarse, nprobe)
+        if not np.array_equal(h_probes[iq], want_probes):   # float32 against float64 distances: near-ties may swap
+            dq = O.sq_l2(y[None], h_coarse)[0]
+            np.testing.assert_allclose(dq[h_probes[iq]], dq[want_probes], rtol=1e-5)
+            continue
+        cells = h_probes[iq]
+        lens = (h_off[cells + 1] - h_off[cells]).astype(np.int64)
+        sub_off = np.zeros(len(cells) + 1, dtype=np.int64)
+        np.cumsum(lens, out=sub_off[1:])
+        sub_codes = torch.cat([codes[h_off[c]:h_off[c + 1]] for c in cells]).cpu().numpy()
+        sub = dict(list_off=sub_off, codes=sub_codes, ids=np.zeros(int(sub_off[-1]), dtype=np.uint32))
+        full = O.ivf_quick_adc_search(sub, h_coarse[cells], h_cb, y, nprobe, init, R, probes=np.arange(nprobe))
+        assert np.abs(qluts[iq].cpu().numpy().astype(int) - full["qluts"].astype(int)).max() <= 1, iq
