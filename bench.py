@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the Quick ADC hot path on one MI355X.
 
-Workload (BASELINE config 2, "single-query bandwidth scan"): d=128 mixture
+Workload (config 2, "single-query bandwidth scan"): d=128 mixture
 data, PQ m=16 x 16 centroids (64-bit codes) trained by 10 k-means iterations
 on 20,000 vectors, N = 10,000,000 codes contiguous in HBM, queries issued one
 at a time, uint8 tables (init = 200), R = 100.

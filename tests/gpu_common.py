@@ -7,7 +7,7 @@ import numpy as np
 
 @functools.lru_cache(maxsize=None)
 def config1(n=100_000, m=16, d=128, nq=16, train_n=20_000, iters=10):
-    """BASELINE config 1: mixture data, PQ m x 16 trained by 10 k-means iterations on 20k vectors."""
+    """Config 1: mixture data, PQ m x 16 trained by 10 k-means iterations on 20k vectors."""
     from oracle import qadc_oracle as O, cref
     from workloads import (MixtureSpec, mixture_vectors, kmeans_init_rows,
                            SEED_TRAIN, SEED_BASE, SEED_QUERY)
