@@ -453,13 +453,14 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
 // The sample uses the 16-entry tables directly (two lookups per code byte): building pair
 // tables for every cell would cost more than the sample itself.
 constexpr int IVF_SEED_NT = 1024;
+constexpr int IVF_SEED_PROBES = 16;  // closest cells whose lists are sampled
 constexpr int IVF_SEED_PCH = 32;  // probed cells whose tables are in LDS at a time
 
 template <int B>
 __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes,
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, int per_list, char *__restrict__ ws, size_t ws_stride, int64_t n_total, int long_shift)
+    int R, int per_list, char *__restrict__ ws, size_t ws_stride, int64_t n_total, int long_shift, int nseed)
 {
     constexpr int NT = IVF_SEED_NT;
     constexpr int TAB = 2 * B * 16;  // bytes of one cell's quantized tables
@@ -474,8 +475,9 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     // a few queries: the probed lists of a query are split over gridDim.y workgroups, which add
     // their histograms into the query's control block; the last one to finish derives the bound
     const int parts = gridDim.y;
-    const int per_part = (nprobe + parts - 1) / parts;
-    const int p_begin = blockIdx.y * per_part, p_end = min(nprobe, p_begin + per_part);
+    // (nseed <= nprobe: only the lists of the nseed closest cells are sampled)
+    const int per_part = (nseed + parts - 1) / parts;
+    const int p_begin = blockIdx.y * per_part, p_end = min(nseed, p_begin + per_part);
     const unsigned cap = (unsigned)cap_i;
     if (tid < nprobe) {
         const int cell = probes[(size_t)q * nprobe + tid];
@@ -1262,12 +1264,15 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         // a few queries: their lists are sampled by several workgroups each
         const int seed_parts_env = knob_or(knobs().ivf_seed_parts, 0);
         const int seed_parts = seed_parts_env > 0 ? min(seed_parts_env, nprobe) : nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
+        // the bound is sampled from the lists of the closest cells only: they hold most of a query's best
+        // codes, and the sample is most of the seed kernel's cost
+        const int nseed = std::min(nprobe, std::max(1, knob_or(knobs().ivf_seed_probes, IVF_SEED_PROBES)));
         unsigned *flags = p.shared ? (unsigned *)(ws + p.off_flags) : nullptr;
 #define QADC_IVF_SEED_CASE(B_)                                                                          \
     case B_:                                                                                           \
         launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb, seed_parts), dim3(IVF_SEED_NT), 0, st,    \
                ix->list_off, ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws,     \
-               p.stride, ix->n, p.shared ? 8 : 0);                                                     \
+               p.stride, ix->n, p.shared ? 8 : 0, nseed);                                              \
         break;
         if (p.seed_per_list > 0) {
             switch (m / 2) {
