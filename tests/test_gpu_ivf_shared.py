@@ -207,3 +207,27 @@ def test_large_batch_takes_the_shared_route_by_itself(Q, O, m, nprobe, R):
                                      probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
         assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
         assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
+
+
+def test_calls_beyond_one_launch_sequence_and_tiny_indexes(Q, O):
+    """4500 queries (more than one launch sequence takes) over a small index, and an index of a single cell:
+    both equal the same queries sent in small calls."""
+    import torch
+    for K, n, nq, nprobe in ((40, 30_000, 4500, 6), (1, 5_000, 700, 1)):
+        coarse, cb, x, index = build_ivf(O, n=n, K=K, d=32, m=8, seed=K + 1, zipf=K > 1)
+        gix = gpu_index(Q, coarse, cb, index)
+        rng = np.random.default_rng(K)
+        queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, 32))).astype(np.float32)
+        gq = to_gpu(queries)
+        R, init = 20, 100
+        ids, dist, probes, qluts = Q.qadc_ivf_search(gix, gq, nprobe, R, init, debug=True)
+        torch.cuda.synchronize()
+        for s in (0, nq // 2, nq - 100):
+            i2, d2 = Q.qadc_ivf_search(gix, gq[s:s + 100].contiguous(), nprobe, R, init)
+            assert np.array_equal(idx_np(i2), idx_np(ids)[s:s + 100]), (K, s)
+            assert np.array_equal(d2.cpu().numpy(), dist.cpu().numpy()[s:s + 100]), (K, s)
+        for iq in (0, nq // 2, nq - 1):
+            rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                         probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
+            assert np.array_equal(idx_np(ids)[iq], rep["ids"]), (K, iq)
+            assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), (K, iq)
