@@ -121,7 +121,35 @@ __device__ __forceinline__ uint4 stream_load16(const uint8_t *p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// The two 16-byte loads of one thread for the tile starting at code t0.  FULL: the whole
+// 12-byte streaming load (the address is a multiple of four).
+typedef unsigned v3u __attribute__((ext_vector_type(3)));
+typedef v3u v3u_a4 __attribute__((aligned(4)));
+__device__ __forceinline__ v3u stream_load12(const uint8_t *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const v3u_a4 *>(p));
+}
+
+// How a wavefront shares out its 64 * 48 bytes of 6-bit codes: in groups of whole codes of 12 or
+// 24 bytes, group g of lane l being group 64 g + l of the wavefront's bytes, so that one load
+// instruction reads consecutive groups.  The thread keeps its groups one after the other: code c of
+// the thread starts at byte c * BYTES of its 48 bytes and is code
+// (64 (c / CPG) + l) * CPG + c % CPG of the wavefront.
+template <int BYTES>
+struct SixbitLayout {
+    static constexpr int UPG = BYTES > 12 ? BYTES / 12 : 1;   // 12-byte loads per group
+    static constexpr int CPG = BYTES > 12 ? 1 : 12 / BYTES;   // codes per group
+    static constexpr int GROUPS = 4 / UPG;                    // groups per thread and tile
+    static_assert(BYTES == 6 || BYTES == 12 || BYTES == 24, "6-bit codes of 8, 16 or 32 components");
+    // index of code c of thread `tid` inside the tile
+    static __device__ __forceinline__ unsigned slot(int tid, int c)
+    {
+        constexpr int CPT = 48 / BYTES;
+        return (unsigned)((tid & ~(WAVE - 1)) * CPT + ((c / CPG) * WAVE + (tid & (WAVE - 1))) * CPG + c % CPG);
+    }
+};
+
+// The two 16-byte loads of one thread for the tile starting at code t0 (6-bit components: its
+// four groups, as three vectors).  FULL: the whole
 // tile lies inside the database (t0 + TILE <= c1), no bounds to check.
 template <int B, int NT, bool FULL = false>
 __device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int64_t t0, int64_t c1,
@@ -129,22 +157,41 @@ __device__ __forceinline__ void tile_load(const uint8_t *__restrict__ codes, int
 {
     const int tid = threadIdx.x;
     if constexpr (ScanCfg<B, NT>::SIX) {
-        // 6-bit components: the thread's CPT codes are 48 contiguous bytes; nc[0] = codes present
+        // 6-bit components: four groups of 12 or 24 bytes per thread (sixbit_layout); nc[0] = bit c
+        // set when code c of the thread lies inside the database
         using C = ScanCfg<B, NT>;
-        const int64_t base = t0 + (int64_t)tid * C::CPT;
-        const uint8_t *p = codes + base * C::BYTES;
+        using L = SixbitLayout<C::BYTES>;
+        const int64_t wave0 = t0 + (int64_t)(tid & ~(WAVE - 1)) * C::CPT;  // first code of the wavefront
+        const int lane = tid & (WAVE - 1);
+        unsigned d[12];
+        nc[0] = 0;
         nc[1] = 0;
-        if (FULL || base + C::CPT <= c1) {
 #pragma unroll
-            for (int v = 0; v < 3; ++v) w[v] = stream_load16(p + 16 * v);
-            nc[0] = C::CPT;
-        } else {
-            nc[0] = base < c1 ? (int)(c1 - base) : 0;
-            unsigned tmp[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-            for (int k = 0; k < nc[0] * C::BYTES; ++k) tmp[k >> 2] |= (unsigned)p[k] << (8 * (k & 3));
+        for (int g = 0; g < L::GROUPS; ++g) {
+            const int64_t first = wave0 + (int64_t)(g * WAVE + lane) * L::CPG;  // first code of the group
+            const uint8_t *p = codes + first * C::BYTES;
+            if (FULL || first + L::CPG <= c1) {
 #pragma unroll
-            for (int v = 0; v < 3; ++v) w[v] = make_uint4(tmp[4 * v], tmp[4 * v + 1], tmp[4 * v + 2], tmp[4 * v + 3]);
+                for (int u = 0; u < L::UPG; ++u) {
+                    const v3u v = stream_load12(p + 12 * u);
+                    d[(g * L::UPG + u) * 3] = v.x;
+                    d[(g * L::UPG + u) * 3 + 1] = v.y;
+                    d[(g * L::UPG + u) * 3 + 2] = v.z;
+                }
+                nc[0] |= ((1 << L::CPG) - 1) << (g * L::CPG);
+            } else {  // ragged end of the database: byte loads, no read past the end
+                const int have = first < c1 ? (int)(c1 - first) : 0;
+                unsigned tmp[3 * L::UPG];
+#pragma unroll
+                for (int k = 0; k < 3 * L::UPG; ++k) tmp[k] = 0;
+                for (int k = 0; k < have * C::BYTES; ++k) tmp[k >> 2] |= (unsigned)p[k] << (8 * (k & 3));
+#pragma unroll
+                for (int k = 0; k < 3 * L::UPG; ++k) d[g * L::UPG * 3 + k] = tmp[k];
+                nc[0] |= ((1 << have) - 1) << (g * L::CPG);
+            }
         }
+#pragma unroll
+        for (int v = 0; v < 3; ++v) w[v] = make_uint4(d[4 * v], d[4 * v + 1], d[4 * v + 2], d[4 * v + 3]);
     } else if constexpr (FULL) {
         if constexpr (B <= 16) {
             constexpr int CPV = 16 / B;

@@ -42,6 +42,17 @@ __device__ __forceinline__ unsigned sixbit_field(const uint4 (&w)[3], int c, int
     return __funnelshift_r(lo, dword(word + 1), sh) & 63u;  // the field crosses into the next word
 }
 
+// Sum of the table entries of code c of a thread's 6-bit codes over the components [first, last).
+template <int B, int NT>
+__device__ __forceinline__ unsigned sixbit_sum(const uint4 (&w)[3], const uint8_t *ptab, int c, int first, int last)
+{
+    using C = ScanCfg<B, NT>;
+    unsigned s = 0;
+#pragma unroll
+    for (int j = first; j < last; ++j) s += ptab[j * 64 + sixbit_field<C::BYTES>(w, c, j)];
+    return s;
+}
+
 // Lookups, sum, clamp, key = sum << 24 | index among the workgroup's codes (NO_KEY where no
 // code; FULL: every slot of the tile holds a code).
 template <int B, int NT, bool FULL = false>
@@ -54,12 +65,10 @@ __device__ __forceinline__ void tile_keys(const uint4 (&w)[ScanCfg<B, NT>::NVEC]
         using C = ScanCfg<B, NT>;
 #pragma unroll
         for (int c = 0; c < C::CPT; ++c) {
-            unsigned s = 0;
-#pragma unroll
-            for (int j = 0; j < C::M6; ++j) s += ptab[j * 64 + sixbit_field<C::BYTES>(w, c, j)];
+            unsigned s = sixbit_sum<B, NT>(w, ptab, c, 0, C::M6);
             s = min(s, cap);
-            const unsigned key = (s << 24) | (rel0 + (unsigned)(tid * C::CPT + c));
-            k[c] = (FULL || c < nc[0]) ? key : NO_KEY;
+            const unsigned key = (s << 24) | (rel0 + SixbitLayout<C::BYTES>::slot(tid, c));
+            k[c] = (FULL || ((nc[0] >> c) & 1)) ? key : NO_KEY;
         }
     } else if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
@@ -100,23 +109,16 @@ __device__ __forceinline__ void tile_sums(const uint4 (&w)[ScanCfg<B, NT>::NVEC]
     if constexpr (ScanCfg<B, NT>::SIX) {
         // two stages of m / 2 components, a check between them
         using C = ScanCfg<B, NT>;
+        constexpr int NL = C::M6;
         unsigned best = 0xffffffffu;
 #pragma unroll
         for (int c = 0; c < C::CPT; ++c) {
-            unsigned s = 0;
-#pragma unroll
-            for (int j = 0; j < C::M6 / 2; ++j) s += ptab[j * 64 + sixbit_field<C::BYTES>(w, c, j)];
-            sm[c] = s;
-            best = min(best, s);
+            sm[c] = sixbit_sum<B, NT>(w, ptab, c, 0, NL / 2);
+            best = min(best, sm[c]);
         }
         if (best <= bound) {
 #pragma unroll
-            for (int c = 0; c < C::CPT; ++c) {
-                unsigned s = sm[c];
-#pragma unroll
-                for (int j = C::M6 / 2; j < C::M6; ++j) s += ptab[j * 64 + sixbit_field<C::BYTES>(w, c, j)];
-                sm[c] = s;
-            }
+            for (int c = 0; c < C::CPT; ++c) sm[c] += sixbit_sum<B, NT>(w, ptab, c, NL / 2, NL);
         }
     } else if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
@@ -161,7 +163,7 @@ template <int B, int NT>
 __device__ __forceinline__ unsigned tile_slot_index(int c)
 {
     if constexpr (ScanCfg<B, NT>::SIX) {
-        return (unsigned)((int)threadIdx.x * ScanCfg<B, NT>::CPT + c);
+        return SixbitLayout<ScanCfg<B, NT>::BYTES>::slot((int)threadIdx.x, c);
     } else if constexpr (B <= 16) {
         constexpr int CPV = 16 / B;
         return (unsigned)(((c / CPV) * NT + (int)threadIdx.x) * CPV + c % CPV);
