@@ -1016,16 +1016,6 @@ __global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
 
 // out_ids[q][r] = ids[position] for the positions the merge kernel wrote (in place).  Anything
 // that is not a storage position becomes the padding value.
-__global__ void ivf_gather_ids_kernel(const uint32_t *__restrict__ ids, uint32_t *__restrict__ out,
-                                      int64_t total, int64_t n)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < total) {
-        const uint32_t pos = out[i];
-        out[i] = ((int64_t)pos < n) ? ids[pos] : 0xffffffffu;
-    }
-}
-
 // Cells given by the caller: a cell outside [0, K) and a cell that an earlier slot of the same
 // query already names become unused slots (-1) -- a list is scanned once, so that keys stay
 // unique, and nothing outside list_off is read.
@@ -1318,11 +1308,9 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         uint32_t *oi = out_ids + (size_t)q0 * R;
         rc = launch_merge<uint8_t, 5>(nb, st, scan_ws, p.stride, p.l.counts_off, p.l.lists_off, p.W,
                                       (unsigned)R, R, (uint8_t)nbins, oi, out_dist + (size_t)q0 * R, p.countsA_off,
-                                      p.listsA_off, p.shared ? 1 : 0, p.shared ? IVF_SHARED_PITCH : 0, flags);
+                                      p.listsA_off, p.shared ? 1 : 0, p.shared ? IVF_SHARED_PITCH : 0, flags,
+                                      (const uint32_t *)ix->ids, (int64_t)ix->n);  // positions -> vector ids
         if (rc != QADC_OK) return rc;
-        const int64_t total = (int64_t)nb * R;
-        launch(QADC_PROF_MERGE, ivf_gather_ids_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0,
-               st, ix->ids, oi, total, ix->n);
         if (dbg_probes)
             QADC_HIP_TRY(hipMemcpyAsync(dbg_probes + (size_t)q0 * nprobe, probes,
                                         (size_t)nb * nprobe * sizeof(int32_t), hipMemcpyDeviceToDevice, st));

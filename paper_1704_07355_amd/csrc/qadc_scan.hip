@@ -723,7 +723,8 @@ static int scan_and_merge_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
     else dispatch_scan_u8<256>(p, codes, n, qluts, nb, nbins, R, ws, flags, st);
     return launch_merge<uint8_t, 5>(nb, st, ws, p.stride, p.counts_off, p.lists_off, p.G,
                                     (unsigned)min((int64_t)R, n), R, (uint8_t)nbins, out_idx, out_dist,
-                                    p.countsA_off, p.listsA_off, flags ? p.t.GC : 0, (int)TILED_LCAP, flags);
+                                    p.countsA_off, p.listsA_off, flags ? p.t.GC : 0, (int)TILED_LCAP, flags,
+                                    (const uint32_t *)nullptr, (int64_t)0);
 }
 
 int scan_topk_u8(int variant, const uint8_t *codes, int64_t n, int m, const uint8_t *qluts, int nq, int R,

@@ -277,9 +277,10 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
     char *__restrict__ ws, size_t ws_stride, size_t counts_off, size_t lists_off, int G,
     unsigned need, int R, DistT pad_dist, uint32_t *__restrict__ out_idx,
     DistT *__restrict__ out_dist, size_t countsA_off, size_t listsA_off, int GA, int pitchA,
-    unsigned *__restrict__ flags)
+    unsigned *__restrict__ flags, const uint32_t *__restrict__ ids, int64_t n_ids)
 {
     // need = min(R, number of codes scanned): at least that many keys were reported.
+    // ids: the keys' low words are storage positions and out_idx gets ids[position] (inverted index).
     __shared__ uint64_t lkeys[MERGE_CAP];
     __shared__ uint64_t cand[MERGE_NT];
     __shared__ SelectScratch sc;
@@ -304,9 +305,19 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         G = GA;
         pitch = pitchA;
     }
-    // every reported key, spread over the threads by workgroup
+    // Few, well-filled regions (inverted-index scans, short databases): every slot of every
+    // region is visited, a slot per thread at a time, so that the loads are spread over the whole
+    // workgroup instead of one thread walking each region.
+    const bool flat = G <= MERGE_FLAT_G && (size_t)G * pitch <= (size_t)MERGE_FLAT_SLOTS;  // uniform
+    // every reported key, spread over the threads by workgroup (after the gather below)
     auto each_key = [&](auto f) {
-        for (int g = tid; g < G; g += MERGE_NT) {
+        if (flat) {
+            for (unsigned sidx = tid; sidx < (unsigned)G * pitch; sidx += MERGE_NT) {
+                const unsigned g = sidx / (unsigned)pitch, i = sidx - g * (unsigned)pitch;
+                if (i < fcnt[g]) f(lists[sidx]);
+            }
+        }
+        for (int g = tid; g < G && !flat; g += MERGE_NT) {
             const unsigned c = min(counts[g], (unsigned)pitch);
             const uint64_t *l = lists + (size_t)g * pitch;
             for (unsigned i = 0; i < c; i += 8) {  // eight loads in flight before the first use
@@ -324,6 +335,11 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
                 for (unsigned i = tid; i < c; i += MERGE_NT) f(listsA[(size_t)g * pitchA + i]);
             }
         }
+    };
+
+    auto index_of = [&](uint32_t pos) -> uint32_t {
+        if (!ids) return pos;
+        return ((int64_t)pos < n_ids) ? ids[pos] : 0xffffffffu;
     };
 
     // Gather, region by region.
@@ -345,10 +361,6 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
             atomicAdd(&sc.hist[(unsigned)(k >> 32) & 255u], 1u);
         }
     };
-    // Few, well-filled regions (inverted-index scans, short databases): every slot of every
-    // region is visited, a slot per thread at a time, so that the loads are spread over the whole
-    // workgroup instead of one thread walking each region.
-    const bool flat = G <= MERGE_FLAT_G && (size_t)G * pitch <= (size_t)MERGE_FLAT_SLOTS;  // uniform
     unsigned mycnt[MERGE_WG_PER_THREAD];
     if (flat) {
         for (int g = tid; g < G; g += MERGE_NT) fcnt[g] = min(counts[g], (unsigned)pitch);
@@ -397,9 +409,30 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
         }
     }
     __syncthreads();
-    const unsigned total = lcnt;
+    unsigned total = lcnt;
     need = min(need, total);
-    const bool in_lds = total <= (unsigned)MERGE_CAP;
+    bool in_lds = total <= (unsigned)MERGE_CAP;
+    if constexpr (!ADAPT) {
+        // More keys than LDS holds (loose bounds, many regions): the histogram counted all of them, so
+        // the bin of the need-th key is known, and only the keys up to that bin are gathered again.
+        if (!in_lds && need > 0) {  // uniform
+            select_bin(&sc, need);
+            __syncthreads();
+            const unsigned bin = sc.bin;
+            const unsigned upto = need - sc.need + sc.hist[bin];  // keys in the bins up to `bin`
+            __syncthreads();
+            if (upto <= (unsigned)MERGE_CAP) {
+                if (tid == 0) lcnt = 0;
+                __syncthreads();
+                each_key([&](uint64_t k) {
+                    if (((unsigned)(k >> 32) & 255u) <= bin) lkeys[atomicAdd(&lcnt, 1u)] = k;
+                });
+                __syncthreads();
+                total = upto;
+                in_lds = true;
+            }
+        }
+    }
     int TOP = 32;
     if constexpr (ADAPT) {
         const unsigned long long diff = all_or ^ all_and;
@@ -435,7 +468,7 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
                     DistT d;
                     if constexpr (sizeof(DistT) == 1) d = (DistT)((k >> 32) & 0xff);
                     else d = ord2f((unsigned)(k >> 32));
-                    out_idx[(size_t)q * R + rank] = (uint32_t)k;
+                    out_idx[(size_t)q * R + rank] = index_of((uint32_t)k);
                     out_dist[(size_t)q * R + rank] = d;
                 }
             }
@@ -481,7 +514,7 @@ __global__ __launch_bounds__(MERGE_NT) void merge_topk_kernel(
             DistT d;
             if constexpr (sizeof(DistT) == 1) d = (DistT)((k >> 32) & 0xff);
             else d = ord2f((unsigned)(k >> 32));
-            out_idx[(size_t)q * R + rank] = (uint32_t)k;
+            out_idx[(size_t)q * R + rank] = index_of((uint32_t)k);
             out_dist[(size_t)q * R + rank] = d;
         }
     }

@@ -674,7 +674,8 @@ int scan_topk_f32(int variant, const uint8_t *codes, int64_t n, int m, const flo
         rc = launch_merge<float, 8>(nb, st, ws, p.stride, p.l.counts_off, p.l.lists_off, p.G,
                                     (unsigned)min((int64_t)R, n), R, __builtin_inff(),
                                     out_idx + (size_t)q0 * R, out_dist + (size_t)q0 * R, p.countsA_off,
-                                    p.listsA_off, flags ? p.GC : 0, (int)F32T_LCAP, flags);
+                                    p.listsA_off, flags ? p.GC : 0, (int)F32T_LCAP, flags, (const uint32_t *)nullptr,
+                                    (int64_t)0);
         if (rc != QADC_OK) return rc;
     }
     QADC_HIP_TRY(hipGetLastError());
