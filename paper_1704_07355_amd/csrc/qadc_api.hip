@@ -59,6 +59,7 @@ void knobs_refresh()
     k.ivf_shared_wgs = env_knob("QADC_IVF_SHARED_WGS");
     k.ivf_shared_min_pairs = env_knob("QADC_IVF_SHARED_MIN_PAIRS");
     k.ivf_seed_probes = env_knob("QADC_IVF_SEED_PROBES");
+    k.ivf_wide_q = env_knob("QADC_IVF_WIDE_Q");
 }
 
 int build_luts(const float *, int, int, int, const float *, const float *, int, float *, hipStream_t);

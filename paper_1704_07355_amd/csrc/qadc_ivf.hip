@@ -23,6 +23,7 @@ namespace qadc {
 constexpr int IVF_MAX_NPROBE = 256;
 constexpr int IVF_NT = 256;      // threads of the scan workgroups
 constexpr int IVF_UNIT_TILES = 8;
+constexpr int IVF_WIDE_MAX_Q = 12;  // calls of up to this many queries scan with workgroups of 1024 threads
 
 // ------------------------------------------------------------------ Index
 
@@ -656,24 +657,26 @@ struct IvfShared {
     unsigned tcnt[3];
     unsigned tau;
     unsigned fcnt;                         // append counter of the barrier-free pass
-    unsigned long long wsum[IVF_NT / WAVE];  // unit counts of the wavefronts (prefix sum)
+    unsigned long long wsum[1024 / WAVE];  // unit counts of the wavefronts (prefix sum)
     long long ustart[IVF_MAX_NPROBE + 1];  // units before probe p
     long long a0[IVF_MAX_NPROBE];          // list start rounded down to 16 codes
     long long lo[IVF_MAX_NPROBE];
     long long hi[IVF_MAX_NPROBE];
 };
 
-template <int B>
-__global__ __launch_bounds__(IVF_NT) void ivf_scan_kernel(
+// NT threads per workgroup: IVF_NT for batches; 1024 for a few queries, whose lists must be read
+// by few workgroups at once (a workgroup has one tile in flight and the next one requested).
+template <int B, int NT>
+__global__ __launch_bounds__(NT) void ivf_scan_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int64_t n_total,
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
     int R, int units_per_wg, int Wmax, const unsigned *__restrict__ wgmap, char *__restrict__ ws,
     size_t ws_stride, size_t counts_off, size_t lists_off, const int32_t *__restrict__ probes_alt,
     const unsigned *__restrict__ flags)
 {
-    constexpr int NT = IVF_NT;
     using C = ScanCfg<B, NT>;
-    constexpr long long UNIT = (long long)IVF_UNIT_TILES * C::TILE;
+    constexpr long long UNIT = (long long)IVF_UNIT_TILES * IVF_NT * C::CPT;  // the same codes whatever NT
+    static_assert(UNIT % C::TILE == 0, "whole tiles per unit");
     // without a map (a few queries): Wmax workgroup slots per query, in query order
     const unsigned me = wgmap ? wgmap[blockIdx.x]
                               : ((blockIdx.x / (unsigned)Wmax) << 12) | (blockIdx.x % (unsigned)Wmax);  // uniform
@@ -1072,9 +1075,10 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     // 16384 workgroup slots per launch (measured at N = 1e9: 4096 queries 161 K queries/s with 24 to
     // 32 against 156 K with 128; 1024 queries best with 24, 512 with 32 to 48, 256 with 64, 128 with
     // 96 to 128); the regions of a query shrink with it, so a launch holds more queries.
+    // (13 to 63 queries: 256, measured 0.286 against 0.320 ms at 16 queries, 0.402 against 0.458 at 32)
     int w_def = 16384 / nq;
     if (w_def < 24) w_def = 24;
-    if (w_def > 128) w_def = 128;
+    if (w_def > 128) w_def = (nq > IVF_WIDE_MAX_Q && nq < 64) ? 256 : 128;
     p->W = knob_or(knobs().ivf_wgs, w_def);
     if (p->W < 1) p->W = 1;
     if (p->W > 4096) p->W = 4096;
@@ -1288,15 +1292,24 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         }
         // (a few queries need no map: every query gets its p.W workgroup slots in turn)
         const bool mapped = nb >= 64 || p.shared;
+        // a few queries: workgroups of 1024 threads (measured at N = 1e9: 1 query 0.121 against 0.136 ms,
+        // 4 queries 0.163 against 0.181, 8 queries 0.208 against 0.220, 12 the same, 16 slower)
+        const bool wide_wgs = !mapped && nb <= knob_or(knobs().ivf_wide_q, IVF_WIDE_MAX_Q);
         if (mapped)
             launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap,
                    (const unsigned *)qunits_light, (const unsigned *)flags);
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
-        launch(QADC_PROF_SCAN, ivf_scan_kernel<B_>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes,    \
-               ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws,   \
-               p.stride,                                                                              \
-               p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light, (const unsigned *)flags);  \
+        if (wide_wgs)                                                                                  \
+            launch(QADC_PROF_SCAN, ivf_scan_kernel<B_, 1024>, grid, dim3(1024), 0, st, ix->list_off, ix->codes, \
+                   ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws, \
+                   p.stride, p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light,              \
+                   (const unsigned *)flags);                                                           \
+        else                                                                                           \
+            launch(QADC_PROF_SCAN, ivf_scan_kernel<B_, IVF_NT>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes, \
+                   ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws, \
+                   p.stride, p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light,              \
+                   (const unsigned *)flags);                                                           \
         break;
         switch (m / 2) {
             QADC_IVF_CASE(4)

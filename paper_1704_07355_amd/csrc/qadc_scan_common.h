@@ -600,7 +600,8 @@ inline int scan_query_batch(size_t stride, int nq)
 struct Knobs {
     int scan_nt, scan_wgs, seed_min_tiles, seed_wgs, tiled, tiled_seed, scan_f32_wgs;
     int tiled_mfma, mfma_min_q, mfma_min_q2, mfma_min_q4, mfma_waves;
-    int ivf_wgs, ivf_seed, ivf_units, ivf_seed_parts, ivf_shared, ivf_shared_wgs, ivf_shared_min_pairs, ivf_seed_probes;
+    int ivf_wgs, ivf_seed, ivf_units, ivf_seed_parts, ivf_shared, ivf_shared_wgs, ivf_shared_min_pairs, ivf_seed_probes,
+        ivf_wide_q;
 };
 const Knobs &knobs();
 void knobs_refresh();

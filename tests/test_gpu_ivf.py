@@ -322,3 +322,27 @@ def test_ivf_large_R_many_probes(Q, O, R, nq):
         assert len(set(ids[iq].tolist())) == R, iq  # every slot written, no neighbour twice
         assert np.array_equal(ids[iq], rep["ids"]), iq
         assert np.array_equal(dist[iq], rep["dist"]), iq
+
+
+@pytest.mark.parametrize("m", [8, 16, 32, 64])
+@pytest.mark.parametrize("wide_q,seed_kernel", [("64", "1"), ("0", "1"), ("64", "0")])
+def test_ivf_few_queries_both_workgroup_shapes(Q, O, m, wide_q, seed_kernel, monkeypatch):
+    """Calls of a few queries scan with workgroups of 1024 threads, larger calls with 256 (QADC_IVF_WIDE_Q
+    moves the limit): both shapes, with the sampled bound and without it (the pass with a barrier per
+    tile), give the oracle's result on lists long enough for a workgroup to walk several units."""
+    import torch
+    monkeypatch.setenv("QADC_IVF_WIDE_Q", wide_q)
+    monkeypatch.setenv("QADC_IVF_SEED", seed_kernel)
+    monkeypatch.setenv("QADC_IVF_WGS", "3")  # few workgroups per query: several units each
+    coarse, cb, x, index = build_ivf(O, n=120_000, K=12, d=64, m=m, seed=100 + m)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(m)
+    nq, nprobe, R, init = 5, 6, 100, 300
+    queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, x.shape[1]))).astype(np.float32)
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    for iq in range(nq):
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
+        assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
+        assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
