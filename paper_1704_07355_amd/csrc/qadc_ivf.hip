@@ -25,6 +25,32 @@ constexpr int IVF_NT = 256;      // threads of the scan workgroups
 constexpr int IVF_UNIT_TILES = 8;
 constexpr int IVF_WIDE_MAX_Q = 12;  // calls of up to this many queries scan with workgroups of 1024 threads
 
+// A few queries: the tables of the probed cells stay float in memory, and every kernel that needs a
+// cell's 8-bit tables applies the query's quantizer (Section 3.3) itself -- the arithmetic of
+// quantize_luts_kernel, entry by entry -- which saves a pass over the tables between launches.
+struct IvfQuantizer {
+    const float *luts;   // [nq][nprobe][m][16]; null: the tables are quantized in memory
+    const float *bias;   // [nq][m]
+    const float *delta;  // [nq]
+};
+
+__device__ __forceinline__ unsigned quantize_entry(float D, float bias, float delta, unsigned nbins)
+{
+    const float off = fmaxf(0.0f, D - bias);
+    const float t = floorf(__fdiv_rn(off, delta));
+    return (t < (float)nbins) ? (unsigned)(uint8_t)t : nbins;
+}
+
+// entries 4 w .. 4 w + 3 of a cell's tables (inside one table: a table has 16 entries) as four bytes
+__device__ __forceinline__ unsigned quantize_word(const float *cell_luts, int w, const float *bias, float delta,
+                                                  unsigned nbins)
+{
+    const float4 v = *reinterpret_cast<const float4 *>(cell_luts + 4 * w);
+    const float b = bias[w >> 2];
+    return quantize_entry(v.x, b, delta, nbins) | (quantize_entry(v.y, b, delta, nbins) << 8) |
+           (quantize_entry(v.z, b, delta, nbins) << 16) | (quantize_entry(v.w, b, delta, nbins) << 24);
+}
+
 // ------------------------------------------------------------------ Index
 
 // dist[q][c] = sum_t (y[q][t] - coarse[c][t])^2, float32, summed in increasing t with one fused
@@ -128,6 +154,121 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
     }
 }
 
+// The same distances for up to a few dozen queries, whose cost is one pass over the centroids: the
+// workgroup's 128 centroids are requested at once (IVF_FEW_DK components of each, 64 KiB in flight per
+// workgroup) and staged in LDS as they lie in memory; thread t then walks the components of cell
+// t % 128, four at a time, for the queries 8 (t / 128) .. + 7 of the workgroup's 16, whose components
+// every lane of the wavefront reads from the same LDS address.  Also written: the smallest distance of every
+// (query, workgroup) as its order-preserving image, from which the selection kernel finds its
+// threshold without reading the row.
+constexpr int IVF_FEW_DK = 128;  // components staged at a time
+constexpr int IVF_FEW_Q = 16;    // queries per workgroup
+
+__global__ __launch_bounds__(256) void ivf_coarse_dist_few_kernel(
+    const float *__restrict__ coarse, int K, int d, const float *__restrict__ queries, int nq,
+    float *__restrict__ dist, unsigned *__restrict__ blockmin, int nblk, int vec4)
+{
+    constexpr int LD = IVF_FEW_DK + 4;  // rows 16-byte aligned, eight neighbouring cells on all the banks
+    constexpr int QH = IVF_FEW_Q / 2;   // queries per thread
+    __shared__ __attribute__((aligned(16))) float cs[IVF_CT][LD];
+    __shared__ __attribute__((aligned(16))) float ys[IVF_FEW_Q][LD];
+    __shared__ unsigned wmin[256 / WAVE][QH];
+    const int tid = threadIdx.x;
+    const int cell = tid & (IVF_CT - 1);
+    const int c0 = blockIdx.x * IVF_CT;
+    const int qh = QH * (tid / IVF_CT);                 // first query of this thread among the workgroup's
+    const int q0 = blockIdx.y * IVF_FEW_Q + qh;         // (the same for a whole wavefront)
+    const int nmine = min(QH, nq - q0);                            // its queries (may be <= 0)
+    float acc[QH];
+#pragma unroll
+    for (int a = 0; a < QH; ++a) acc[a] = 0.0f;
+    for (int t0 = 0; t0 < d; t0 += IVF_FEW_DK) {  // uniform
+        const int dk = min(IVF_FEW_DK, d - t0);
+        const int dk4 = (dk + 3) >> 2;  // groups of four components, the last one padded with zeros
+        if (t0) __syncthreads();  // everybody is done with the previous components
+        if (vec4) {  // d a multiple of four, rows 16-byte aligned
+            constexpr int PER = IVF_CT * (IVF_FEW_DK / 4) / 256;  // 16 loads per thread, all in flight
+            float4 v[PER];
+#pragma unroll
+            for (int e = 0; e < PER; ++e) {
+                const int idx = tid + e * 256;
+                const int row = idx / dk4, col4 = idx - row * dk4;
+                v[e] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (row < IVF_CT && c0 + row < K)
+                    v[e] = *reinterpret_cast<const float4 *>(coarse + (size_t)(c0 + row) * d + t0 + 4 * col4);
+            }
+            for (int idx = tid; idx < IVF_FEW_Q * dk4; idx += 256) {
+                const int row = idx / dk4, col4 = idx - row * dk4;
+                float4 y = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                const int q = blockIdx.y * IVF_FEW_Q + row;
+                if (q < nq) y = *reinterpret_cast<const float4 *>(queries + (size_t)q * d + t0 + 4 * col4);
+                *reinterpret_cast<float4 *>(&ys[row][4 * col4]) = y;
+            }
+#pragma unroll
+            for (int e = 0; e < PER; ++e) {
+                const int idx = tid + e * 256;
+                const int row = idx / dk4, col4 = idx - row * dk4;
+                if (row < IVF_CT) *reinterpret_cast<float4 *>(&cs[row][4 * col4]) = v[e];
+            }
+        } else {
+            for (int idx = tid; idx < IVF_FEW_Q * 4 * dk4; idx += 256) {
+                const int row = idx / (4 * dk4), col = idx - row * (4 * dk4);
+                const int q = blockIdx.y * IVF_FEW_Q + row;
+                ys[row][col] = (q < nq && col < dk) ? queries[(size_t)q * d + t0 + col] : 0.0f;
+            }
+            for (int idx = tid; idx < IVF_CT * 4 * dk4; idx += 256) {
+                const int row = idx / (4 * dk4), col = idx - row * (4 * dk4);
+                cs[row][col] = (c0 + row < K && col < dk) ? coarse[(size_t)(c0 + row) * d + t0 + col] : 0.0f;
+            }
+        }
+        __syncthreads();
+        if (nmine <= 0) continue;  // uniform in a wavefront: no query for it
+        // (a padded component is 0 - 0: the fused multiply-add leaves the sum as it is)
+#pragma unroll 2
+        for (int kk = 0; kk < 4 * dk4; kk += 4) {
+            const float4 c = *reinterpret_cast<const float4 *>(&cs[cell][kk]);
+#pragma unroll
+            for (int a = 0; a < QH; ++a) {
+                if (a < nmine) {  // uniform
+                    const float4 y = *reinterpret_cast<const float4 *>(&ys[qh + a][kk]);
+                    float df = y.x - c.x;
+                    acc[a] = fmaf(df, df, acc[a]);
+                    df = y.y - c.y;
+                    acc[a] = fmaf(df, df, acc[a]);
+                    df = y.z - c.z;
+                    acc[a] = fmaf(df, df, acc[a]);
+                    df = y.w - c.w;
+                    acc[a] = fmaf(df, df, acc[a]);
+                }
+            }
+        }
+    }
+    const int c = c0 + cell;
+    unsigned mn[QH];
+#pragma unroll
+    for (int a = 0; a < QH; ++a) {
+        mn[a] = 0xffffffffu;
+        if (a < nmine && c < K) {
+            dist[(size_t)(q0 + a) * K + c] = acc[a];
+            mn[a] = f2ord(acc[a]);
+        }
+    }
+    if (!blockmin) return;  // uniform
+    // smallest image per query: inside the wavefront, then across the two wavefronts of a query
+#pragma unroll
+    for (int a = 0; a < QH; ++a) {
+#pragma unroll
+        for (int o = 1; o < WAVE; o <<= 1) mn[a] = min(mn[a], (unsigned)__shfl_xor((int)mn[a], o));
+        if (lane_id() == 0) wmin[tid / WAVE][a] = mn[a];
+    }
+    __syncthreads();
+    if (tid < IVF_FEW_Q) {
+        const int h = tid / QH, a = tid % QH;  // wavefronts 2h and 2h + 1 hold query 8h + a
+        const int q = blockIdx.y * IVF_FEW_Q + tid;
+        if (q < nq) blockmin[(size_t)q * nblk + blockIdx.x] = min(wmin[2 * h][a], wmin[2 * h + 1][a]);
+    }
+}
+
 // probes[q][0..nprobe) = the nprobe closest cells, closest first, ties to the lowest cell id.
 // Keys are order(dist) << 32 | cell (unique).  Thread t looks at cells t, t + NT, ...  The
 // need-th smallest of the threads' minima, T, bounds the need-th smallest key of the whole
@@ -135,11 +276,16 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
 // keys <= T: at most need * ceil(K / NT) candidates, normally about `need` of them.  A second
 // pass over the row gathers the candidates in LDS, where the exact selection runs.  A
 // candidate list that does not fit takes the radix select over the whole row instead.
+// With `blockmin` (the smallest distance of every run of IVF_CT cells, at least `need` runs): T = the
+// need-th smallest of those minima, by the same argument, and only the runs whose minimum is <= T are
+// read at all -- the row is not walked twice by one workgroup.
 constexpr int IVF_SEL_NT = 1024;
 constexpr int IVF_SEL_CAP = 4096;
+constexpr int IVF_SEL_MAXBLK = 4096;  // runs of cells whose minima fit in LDS
 
 __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
-    const float *__restrict__ dist, int K, int nprobe, int32_t *__restrict__ probes)
+    const float *__restrict__ dist, int K, int nprobe, int32_t *__restrict__ probes,
+    const unsigned *__restrict__ blockmin, int nblk)
 {
     constexpr int NT = IVF_SEL_NT;
     __shared__ SelectScratch sc;
@@ -150,6 +296,43 @@ __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
     const float *dq = dist + (size_t)q * K;
     const unsigned need = (unsigned)min(nprobe, K);
 
+    if (blockmin) {  // uniform
+        __shared__ unsigned bm[IVF_SEL_MAXBLK];
+        __shared__ unsigned hits[IVF_SEL_MAXBLK];
+        __shared__ unsigned nhit_s;
+        for (int b = tid; b < nblk; b += NT) bm[b] = blockmin[(size_t)q * nblk + b];
+        if (tid == 0) { cnt = 0; nhit_s = 0; }
+        __syncthreads();
+        // the three leading bytes of the need-th smallest minimum, everything below them set
+        unsigned Tm = block_radix_select_each<unsigned, 3>(
+            [&](auto f) {
+                for (int b = tid; b < nblk; b += NT) f(bm[b] >> 8);
+            },
+            need, &sc);
+        Tm = (Tm << 8) | 0xffu;
+        for (int b = tid; b < nblk; b += NT)
+            if (bm[b] <= Tm) hits[atomicAdd(&nhit_s, 1u)] = (unsigned)b;
+        __syncthreads();
+        const unsigned ncell = nhit_s * (unsigned)IVF_CT;
+        for (unsigned i0 = tid; i0 < ncell; i0 += 4 * NT) {
+            float v[4];
+            int c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned i = i0 + u * NT;
+                c[u] = i < ncell ? (int)(hits[i / IVF_CT] * IVF_CT + i % IVF_CT) : K;
+                v[u] = c[u] < K ? dq[c[u]] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned o = f2ord(v[u]);
+                if (c[u] < K && o <= Tm) {
+                    const unsigned slot = atomicAdd(&cnt, 1u);
+                    if (slot < (unsigned)IVF_SEL_CAP) cand[slot] = ((uint64_t)o << 32) | (uint64_t)(unsigned)c[u];
+                }
+            }
+        }
+    } else {
     // this thread's smallest key: smallest value, lowest cell among equals (cells grow with c)
     // (eight loads in flight per thread: the row is read at memory speed, not one latency per cell)
     uint64_t mine = ~0ull;
@@ -197,6 +380,7 @@ __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
                 if (slot < (unsigned)IVF_SEL_CAP) cand[slot] = k;
             }
         }
+    }
     }
     __syncthreads();
     const unsigned ncand = cnt;
@@ -250,7 +434,7 @@ __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
 void ivf_select_smallest(const float *dist, int rows, int K, int count, int32_t *out, hipStream_t st)
 {
     launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3((unsigned)rows), dim3(IVF_SEL_NT), 0, st, dist, K,
-           count, out);
+           count, out, (const unsigned *)nullptr, 0);
 }
 
 // ----------------------------------------------------------------- Tables
@@ -352,7 +536,7 @@ __global__ __launch_bounds__(1024) void ivf_build_luts_batch_kernel(
 // qmax[q] = min(R, n_walk)-th smallest float ADC distance (Eq. (2), float32, increasing j)
 // of the first n_walk = min(init, codes in the probed lists) codes met walking the lists in
 // probe order, each code with the tables of its own cell; 0 when the lists are empty.
-__global__ __launch_bounds__(256) void ivf_qmax_kernel(
+__global__ __launch_bounds__(1024) void ivf_qmax_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int m,
     const int32_t *__restrict__ probes, int nprobe, const float *__restrict__ luts, int init, int R,
     float *__restrict__ qmax, long long unit, unsigned *__restrict__ qunits, int64_t n_total,
@@ -379,7 +563,7 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(
     const int tid = threadIdx.x;
     const int B = m / 2;
     // list lengths one thread per probe, exclusive prefix sum
-    __shared__ unsigned long long wsum[256 / WAVE];
+    __shared__ unsigned long long wsum[1024 / WAVE];
     unsigned long long len = 0;
     if (tid == 0) units_s = 0;
     __syncthreads();
@@ -461,7 +645,8 @@ template <int B>
 __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes,
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
-    int R, int per_list, char *__restrict__ ws, size_t ws_stride, int64_t n_total, int long_shift, int nseed)
+    int R, int per_list, char *__restrict__ ws, size_t ws_stride, int64_t n_total, int long_shift, int nseed,
+    IvfQuantizer fq)
 {
     constexpr int NT = IVF_SEED_NT;
     constexpr int TAB = 2 * B * 16;  // bytes of one cell's quantized tables
@@ -495,8 +680,17 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     for (int p0 = p_begin; p0 < p_end; p0 += IVF_SEED_PCH) {  // uniform
         const int np = min(IVF_SEED_PCH, p_end - p0);
         __syncthreads();  // geometry and histogram ready; nobody still reads the previous tables
-        const unsigned *src = reinterpret_cast<const unsigned *>(qluts + ((size_t)q * nprobe + p0) * TAB);
-        for (int e = tid; e < np * (TAB / 4); e += NT) reinterpret_cast<unsigned *>(tab)[e] = src[e];
+        if (fq.luts) {  // uniform
+            const float *src = fq.luts + ((size_t)q * nprobe + p0) * TAB;
+            const float delta = fq.delta[q];
+            for (int e = tid; e < np * (TAB / 4); e += NT)
+                reinterpret_cast<unsigned *>(tab)[e] =
+                    quantize_word(src + (size_t)(e / (TAB / 4)) * TAB, e % (TAB / 4),
+                                  fq.bias + (size_t)q * (2 * B), delta, cap);
+        } else {
+            const unsigned *src = reinterpret_cast<const unsigned *>(qluts + ((size_t)q * nprobe + p0) * TAB);
+            for (int e = tid; e < np * (TAB / 4); e += NT) reinterpret_cast<unsigned *>(tab)[e] = src[e];
+        }
         __syncthreads();
         for (int i = tid; i < np * per_list; i += NT) {
             const int pp = i / per_list, c = i - pp * per_list;
@@ -672,7 +866,7 @@ __global__ __launch_bounds__(NT) void ivf_scan_kernel(
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
     int R, int units_per_wg, int Wmax, const unsigned *__restrict__ wgmap, char *__restrict__ ws,
     size_t ws_stride, size_t counts_off, size_t lists_off, const int32_t *__restrict__ probes_alt,
-    const unsigned *__restrict__ flags)
+    const unsigned *__restrict__ flags, IvfQuantizer fq)
 {
     using C = ScanCfg<B, NT>;
     constexpr long long UNIT = (long long)IVF_UNIT_TILES * IVF_NT * C::CPT;  // the same codes whatever NT
@@ -755,9 +949,17 @@ __global__ __launch_bounds__(NT) void ivf_scan_kernel(
     // pair tables of probe p (called by the whole workgroup)
     auto load_tables = [&](int p) {
         __syncthreads();  // nobody still reads the previous pair tables
-        const uint8_t *qlut = qluts + ((size_t)q * nprobe + p) * (2 * B) * 16;
-        for (int e = tid; e < 2 * B * 4; e += NT)
-            reinterpret_cast<unsigned *>(qlut_s)[e] = reinterpret_cast<const unsigned *>(qlut)[e];
+        if (fq.luts) {  // uniform
+            const float *lt = fq.luts + ((size_t)q * nprobe + p) * (2 * B) * 16;
+            const float delta = fq.delta[q];
+            for (int e = tid; e < 2 * B * 4; e += NT)
+                reinterpret_cast<unsigned *>(qlut_s)[e] =
+                    quantize_word(lt, e, fq.bias + (size_t)q * (2 * B), delta, cap);
+        } else {
+            const uint8_t *qlut = qluts + ((size_t)q * nprobe + p) * (2 * B) * 16;
+            for (int e = tid; e < 2 * B * 4; e += NT)
+                reinterpret_cast<unsigned *>(qlut_s)[e] = reinterpret_cast<const unsigned *>(qlut)[e];
+        }
         __syncthreads();
         for (int e = tid; e < B * 256; e += NT) {
             const int jb = e >> 8, v = e & 255;
@@ -791,13 +993,24 @@ __global__ __launch_bounds__(NT) void ivf_scan_kernel(
             int nc[2], ncn[2];
             const bool new_list = p != cur_p;  // uniform
             unsigned qword = 0;
-            if (new_list && tid < 2 * B * 4)
-                qword = reinterpret_cast<const unsigned *>(qluts + ((size_t)q * nprobe + p) * (2 * B) * 16)[tid];
+            float4 fword = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (new_list && tid < 2 * B * 4) {
+                if (fq.luts)  // uniform
+                    fword = reinterpret_cast<const float4 *>(fq.luts + ((size_t)q * nprobe + p) * (2 * B) * 16)[tid];
+                else
+                    qword = reinterpret_cast<const unsigned *>(qluts + ((size_t)q * nprobe + p) * (2 * B) * 16)[tid];
+            }
             asm volatile("" ::: "memory");
             tile_load<B, NT>(codes, u0, n_total, wn, ncn);
             asm volatile("" ::: "memory");
             if (new_list) {
                 __syncthreads();  // nobody still reads the previous pair tables
+                if (fq.luts && tid < 2 * B * 4) {  // the query's quantizer applied to the four entries
+                    const float b = fq.bias[(size_t)q * (2 * B) + (tid >> 2)];
+                    const float delta = fq.delta[q];
+                    qword = quantize_entry(fword.x, b, delta, cap) | (quantize_entry(fword.y, b, delta, cap) << 8) |
+                            (quantize_entry(fword.z, b, delta, cap) << 16) | (quantize_entry(fword.w, b, delta, cap) << 24);
+                }
                 if (tid < 2 * B * 4) reinterpret_cast<unsigned *>(qlut_s)[tid] = qword;
                 __syncthreads();
                 for (int e = tid; e < B * 256; e += NT) {
@@ -1045,7 +1258,7 @@ struct IvfPlan {
     int qd;  // queries per pass of the Index step (its distances take K floats per query)
     int seed_per_list;  // codes sampled per probed list for the bound of the scan (0: no seed kernel)
     ScanLayout l;
-    size_t off_dist, off_probes, off_luts, off_qluts, off_qmax, off_units, off_map, off_scan, bytes;
+    size_t off_dist, off_bmin, off_front, off_probes, off_luts, off_qluts, off_qmax, off_units, off_map, off_scan, bytes;
     // shared-list scan of large batches (ivf_shared_scan): a second report region per query, the
     // pairs sorted by cell and their offsets
     bool shared;
@@ -1122,6 +1335,8 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->qd = (int)qd;
     size_t o = 0;
     p->off_dist = o;   o += align_up((size_t)qd * kdist * 4, 256);
+    p->off_bmin = o;   o += align_up((size_t)32 * ceil_div((int64_t)kdist, (int64_t)IVF_CT) * 4, 256);  // (calls of up to 32 queries)
+    p->off_front = o;  o += align_up((size_t)32 * (64 + 1) * 4, 256);  // quantizers of up to 32 queries (m <= 64)
     p->off_probes = o; o += align_up((size_t)qb * nprobe * 4, 256);
     p->off_luts = o;   o += align_up((size_t)qb * nprobe * ix->m * 16 * 4, 256);
     p->off_qluts = o;  o += align_up((size_t)qb * nprobe * ix->m * 16, 256);
@@ -1209,17 +1424,23 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             for (int i0 = 0; i0 < nb; i0 += p.qd) {
                 const int ni = min(p.qd, nb - i0);
                 const float *yi = yq + (size_t)i0 * d;
+                unsigned *bmin = nullptr;
                 if (nb > 32) {
                     dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(ni, 128));
                     launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<8>, grid, dim3(256), 0, st, ix->coarse, K, d,
                            yi, ni, dist);
                 } else {
-                    dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(ni, 16));
-                    launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<1>, grid, dim3(256), 0, st, ix->coarse, K, d,
-                           yi, ni, dist);
+                    // a few queries: the minima of the runs of IVF_CT cells go with the distances, and
+                    // the selection reads only the runs that matter (when there are enough runs)
+                    const int nblk = (int)ceil_div(K, IVF_CT);
+                    if (nblk >= 2 * nprobe && nblk <= IVF_SEL_MAXBLK) bmin = (unsigned *)(ws + p.off_bmin);
+                    const int vec4 = (d % 4 == 0 && ((uintptr_t)ix->coarse & 15) == 0 && ((uintptr_t)yi & 15) == 0) ? 1 : 0;
+                    dim3 grid((unsigned)nblk, (unsigned)ceil_div(ni, IVF_FEW_Q));
+                    launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_few_kernel, grid, dim3(256), 0, st, ix->coarse, K, d,
+                           yi, ni, dist, bmin, nblk, vec4);
                 }
                 launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(ni), dim3(IVF_SEL_NT), 0, st, dist, K,
-                       nprobe, probes + (size_t)i0 * nprobe);
+                       nprobe, probes + (size_t)i0 * nprobe, (const unsigned *)bmin, (int)ceil_div(K, IVF_CT));
             }
         }
         // Tables
@@ -1245,11 +1466,18 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
                    (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids,
                    ix->Kh, probes, nprobe, luts);
-        launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(256), 0, st, ix->list_off, ix->codes,
+        // (a few queries: a thread per init code, so that the walk is one round of loads)
+        launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(nb <= 32 ? 1024 : 256), 0, st, ix->list_off, ix->codes,
                m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n, scan_ws, p.stride, p.l.counts_off,
                p.W, p.countsA_off);
-        int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
-                               nullptr, nullptr, st);
+        // a few queries: the quantizer's parameters only, applied by the kernels that read the tables
+        const bool float_tables = nb <= 32 && !p.shared;
+        float *qbias = (float *)(ws + p.off_front);
+        float *qdelta = qbias + 32 * 64;
+        IvfQuantizer fq = {nullptr, nullptr, nullptr};
+        if (float_tables) fq = IvfQuantizer{luts, qbias, qdelta};
+        int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts,
+                               float_tables ? qbias : nullptr, float_tables ? qdelta : nullptr, nullptr, st);
         if (rc != QADC_OK) return rc;
         // Scan: up to p.W workgroups per query, one per `upw` units of its lists (batches that fill
         // the GPU by their number alone), one per unit otherwise
@@ -1266,7 +1494,7 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
     case B_:                                                                                           \
         launch(QADC_PROF_SEED, ivf_seed_kernel<B_>, dim3(nb, seed_parts), dim3(IVF_SEED_NT), 0, st,    \
                ix->list_off, ix->codes, probes, nprobe, qluts, nbins, R, p.seed_per_list, scan_ws,     \
-               p.stride, ix->n, p.shared ? 8 : 0, nseed);                                              \
+               p.stride, ix->n, p.shared ? 8 : 0, nseed, fq);                                          \
         break;
         if (p.seed_per_list > 0) {
             switch (m / 2) {
@@ -1304,12 +1532,12 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             launch(QADC_PROF_SCAN, ivf_scan_kernel<B_, 1024>, grid, dim3(1024), 0, st, ix->list_off, ix->codes, \
                    ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws, \
                    p.stride, p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light,              \
-                   (const unsigned *)flags);                                                           \
+                   (const unsigned *)flags, fq);                                                       \
         else                                                                                           \
             launch(QADC_PROF_SCAN, ivf_scan_kernel<B_, IVF_NT>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes, \
                    ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws, \
                    p.stride, p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light,              \
-                   (const unsigned *)flags);                                                           \
+                   (const unsigned *)flags, fq);                                                       \
         break;
         switch (m / 2) {
             QADC_IVF_CASE(4)
