@@ -51,6 +51,27 @@ __device__ __forceinline__ unsigned quantize_word(const float *cell_luts, int w,
            (quantize_entry(v.z, b, delta, nbins) << 16) | (quantize_entry(v.w, b, delta, nbins) << 24);
 }
 
+// The control words of a query's scan -- the histograms of its control block and the counts of its
+// report regions -- are cleared at the start of every call: calls of different shapes lay the
+// workspace out differently, and what one call left as table data may lie where the next one keeps
+// its counts.  Called by a whole workgroup for its query.
+__device__ __forceinline__ void ivf_clear_control(char *base, size_t counts_off, int W, size_t countsA_off)
+{
+    unsigned *gh = reinterpret_cast<unsigned *>(base);  // ScanHeader::ghist comes first
+    for (int i = threadIdx.x; i < GH_REP * 256; i += blockDim.x) gh[i] = 0;
+    unsigned *counts = reinterpret_cast<unsigned *>(base + counts_off);
+    for (int i = threadIdx.x; i < W; i += blockDim.x) counts[i] = 0;
+    if (countsA_off && threadIdx.x == 0) *reinterpret_cast<unsigned *>(base + countsA_off) = 0;
+}
+
+// Where the kernels of the Index step clear a query's control words (calls of a few queries, which
+// have no qmax kernel to do it); scan_ws null: not here.
+struct IvfClear {
+    char *scan_ws;
+    size_t ws_stride, counts_off, countsA_off;
+    int W;
+};
+
 // ------------------------------------------------------------------ Index
 
 // dist[q][c] = sum_t (y[q][t] - coarse[c][t])^2, float32, summed in increasing t with one fused
@@ -285,9 +306,12 @@ constexpr int IVF_SEL_MAXBLK = 4096;  // runs of cells whose minima fit in LDS
 
 __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
     const float *__restrict__ dist, int K, int nprobe, int32_t *__restrict__ probes,
-    const unsigned *__restrict__ blockmin, int nblk)
+    const unsigned *__restrict__ blockmin, int nblk, IvfClear clr)
 {
     constexpr int NT = IVF_SEL_NT;
+    if (clr.scan_ws) {  // uniform
+        ivf_clear_control(clr.scan_ws + (size_t)blockIdx.x * clr.ws_stride, clr.counts_off, clr.W, clr.countsA_off);
+    }
     __shared__ SelectScratch sc;
     __shared__ uint64_t cand[IVF_SEL_CAP];  // thread minima first, then the candidates
     __shared__ unsigned cnt;
@@ -434,7 +458,7 @@ __global__ __launch_bounds__(IVF_SEL_NT) void ivf_select_probes_kernel(
 void ivf_select_smallest(const float *dist, int rows, int K, int count, int32_t *out, hipStream_t st)
 {
     launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3((unsigned)rows), dim3(IVF_SEL_NT), 0, st, dist, K,
-           count, out, (const unsigned *)nullptr, 0);
+           count, out, (const unsigned *)nullptr, 0, IvfClear{nullptr, 0, 0, 0, 0});
 }
 
 // ----------------------------------------------------------------- Tables
@@ -542,18 +566,7 @@ __global__ __launch_bounds__(1024) void ivf_qmax_kernel(
     float *__restrict__ qmax, long long unit, unsigned *__restrict__ qunits, int64_t n_total,
     char *__restrict__ ws, size_t ws_stride, size_t counts_off, int W, size_t countsA_off)
 {
-    // The control words of the query's scan -- the histograms of its control block and the counts of
-    // its report regions -- are cleared here, at the start of every call: calls of different shapes
-    // lay the workspace out differently, and what one call left as table data may lie where the next
-    // one keeps its counts.
-    {
-        char *base = ws + (size_t)blockIdx.x * ws_stride;
-        unsigned *gh = reinterpret_cast<unsigned *>(base);  // ScanHeader::ghist comes first
-        for (int i = threadIdx.x; i < GH_REP * 256; i += blockDim.x) gh[i] = 0;
-        unsigned *counts = reinterpret_cast<unsigned *>(base + counts_off);
-        for (int i = threadIdx.x; i < W; i += blockDim.x) counts[i] = 0;
-        if (countsA_off && threadIdx.x == 0) *reinterpret_cast<unsigned *>(base + countsA_off) = 0;
-    }
+    ivf_clear_control(ws + (size_t)blockIdx.x * ws_stride, counts_off, W, countsA_off);
     __shared__ unsigned cand[QADC_MAX_INIT];
     __shared__ unsigned units_s;
     __shared__ long long start[IVF_MAX_NPROBE + 1];  // codes before probe p in the walk
@@ -627,6 +640,184 @@ __global__ __launch_bounds__(1024) void ivf_qmax_kernel(
     const unsigned need = (unsigned)min(R, n_walk);
     const unsigned kth = block_radix_select<unsigned, 4>(cand, (unsigned)n_walk, need, &sc);
     if (tid == 0) qmax[q] = ord2f(kth);
+}
+
+// Calls of a few queries: Tables and the sums of the qmax walk in one launch.  Workgroup (p, q)
+// builds the float tables of the query's p-th cell (the arithmetic of ivf_build_luts_kernel), leaves
+// the minimum of each table, and computes the float ADC sums of the init codes that the walk of
+// ivf_qmax_kernel takes from its list, with the tables still in LDS ...
+constexpr int IVF_FRONT_NT = 256;
+
+__global__ __launch_bounds__(IVF_FRONT_NT) void ivf_front_kernel(
+    const float *__restrict__ codebooks, int d, int m, const float *__restrict__ queries,
+    const float *__restrict__ coarse, const float *__restrict__ halves, const uint32_t *__restrict__ cell_ids,
+    int Kh, const int32_t *__restrict__ probes, int nprobe, float *__restrict__ luts,
+    const int64_t *__restrict__ list_off, const uint8_t *__restrict__ codes, int64_t n_total, int init,
+    long long unit, unsigned *__restrict__ qunits, unsigned *__restrict__ cand,
+    unsigned *__restrict__ mins, unsigned *__restrict__ nwalk_out)
+{
+    constexpr int NT = IVF_FRONT_NT;
+    extern __shared__ double yr[];  // [d]
+    __shared__ float lut_s[64 * 16];
+    __shared__ unsigned long long wsum[NT / WAVE];
+    __shared__ long long start_s[2], lo_s, total_s;
+    __shared__ unsigned units_s;
+    const int p = blockIdx.x, q = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int dsub = d / m;
+    const int entries = m * 16;
+    const int B = m / 2;
+
+    // geometry of the walk: list lengths one thread per probe, exclusive prefix sum
+    static_assert(IVF_MAX_NPROBE <= NT, "one thread per probe");
+    unsigned long long len = 0;
+    long long my_lo = 0;
+    if (tid == 0) units_s = 0;
+    __syncthreads();
+    if (tid < nprobe) {
+        const int c = probes[(size_t)q * nprobe + tid];
+        long long l = 0, h = 0;
+        if (c >= 0) { l = list_off[c]; h = list_off[c + 1]; }
+        if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: nothing is read
+        my_lo = l;
+        len = (unsigned long long)(h - l);
+        // units the scan kernel cuts this list into (the same expression as there)
+        if (h > l) atomicAdd(&units_s, (unsigned)((h - l / 16 * 16 + unit - 1) / unit));
+    }
+    // this cell's residual while those loads travel
+    const int cell = probes[(size_t)q * nprobe + p];
+    if (cell >= 0) {
+        if (coarse) {
+            for (int t = tid; t < d; t += NT)
+                yr[t] = (double)queries[(size_t)q * d + t] - (double)coarse[(size_t)cell * d + t];
+        } else {  // list `cell` of a multi-index: the centroid is a pair of half-centroids
+            const int dh = d >> 1;
+            const unsigned id = cell_ids[cell];
+            const float *h0 = halves + (size_t)(id / (unsigned)Kh) * dh;
+            const float *h1 = halves + ((size_t)Kh + id % (unsigned)Kh) * dh;
+            for (int t = tid; t < d; t += NT)
+                yr[t] = (double)queries[(size_t)q * d + t] - (double)(t < dh ? h0[t] : h1[t - dh]);
+        }
+    }
+    {
+        const int l = lane_id();
+        unsigned long long inc = len;
+#pragma unroll
+        for (int dd = 1; dd < WAVE; dd <<= 1) {
+            const unsigned long long up = __shfl_up(inc, dd);
+            if (l >= dd) inc += up;
+        }
+        if (l == WAVE - 1) wsum[tid / WAVE] = inc;
+        __syncthreads();  // (also: the residual is complete)
+        unsigned long long before = 0;
+        for (int wv = 0; wv < tid / WAVE; ++wv) before += wsum[wv];
+        if (tid == p) {
+            start_s[0] = (long long)(before + inc - len);
+            start_s[1] = (long long)(before + inc);
+            lo_s = my_lo;
+        }
+        if (tid == nprobe - 1) total_s = (long long)(before + inc);
+    }
+    // Tables, Eq. (1) on the residual: float64 differences and sums, one rounding
+    float *out = luts + ((size_t)q * nprobe + p) * entries;
+    for (int e = tid; e < entries; e += NT) {
+        float v = __builtin_inff();  // an unused probe slot: nothing of it is ever scanned
+        if (cell >= 0) {
+            const int j = e >> 4;
+            const float *c = codebooks + (size_t)e * dsub;
+            const double *y = yr + j * dsub;
+            double acc = 0.0;
+            for (int t = 0; t < dsub; ++t) {
+                const double df = y[t] - (double)c[t];
+                acc += df * df;
+            }
+            v = (float)acc;
+        }
+        out[e] = v;
+        lut_s[e] = v;
+    }
+    __syncthreads();
+    if (p == 0 && tid == 0) qunits[q] = units_s;
+    // minimum of each table, as its order-preserving image
+    if (tid < m) {
+        unsigned mn = 0xffffffffu;
+        for (int i = 0; i < 16; ++i) mn = min(mn, f2ord(lut_s[tid * 16 + i]));
+        mins[((size_t)q * nprobe + p) * m + tid] = mn;
+    }
+    // the walk's codes that lie in this list: float32 sums in increasing j (as ivf_qmax_kernel)
+    const long long total = total_s;
+    const int n_walk = (int)min((long long)init, total);
+    {
+        const long long s0 = start_s[0], s1 = min(start_s[1], (long long)n_walk);
+        for (long long i = s0 + tid; i < s1; i += NT) {
+            const unsigned *cw = reinterpret_cast<const unsigned *>(codes + (size_t)(lo_s + (i - s0)) * B);
+            float acc = 0.0f;
+            for (int k = 0; k < B / 4; ++k) {
+                const unsigned w = cw[k];
+                float e[8];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const unsigned comps = (w >> (8 * b)) & 0xffu;
+                    const int jb = 4 * k + b;
+                    e[2 * b] = lut_s[(2 * jb) * 16 + (comps & 15u)];
+                    e[2 * b + 1] = lut_s[(2 * jb + 1) * 16 + (comps >> 4)];
+                }
+#pragma unroll
+                for (int b = 0; b < 8; ++b) acc = acc + e[b];
+            }
+            cand[(size_t)q * QADC_MAX_INIT + i] = f2ord(acc);
+        }
+    }
+    if (p == 0 && tid == 0) nwalk_out[q] = (unsigned)n_walk;
+}
+
+// ... then one workgroup per query selects qmax among the sums, joins the minima of the tables into
+// the biases and derives delta: the arithmetic of quantize_luts_kernel.  (A launch of its own: the
+// kernel boundary makes the sums visible; a count of finished workgroups with memory fences, tried
+// first, made every workgroup of the launch before write the L2 back.)
+constexpr int IVF_FINISH_NT = 1024;
+
+__global__ __launch_bounds__(IVF_FINISH_NT) void ivf_finish_kernel(
+    const unsigned *__restrict__ cand, const unsigned *__restrict__ mins, const unsigned *__restrict__ nwalk,
+    int nprobe, int m, int R, int nbins, int qmin_mode, float *__restrict__ qmax_out,
+    float *__restrict__ qbias, float *__restrict__ qdelta)
+{
+    constexpr int NT = IVF_FINISH_NT;
+    __shared__ unsigned cand_s[QADC_MAX_INIT];
+    __shared__ float bias_s[64];
+    __shared__ unsigned bias_ord[64];
+    __shared__ SelectScratch sc;
+    const int q = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int n_walk = (int)nwalk[q];
+    for (int i = tid; i < n_walk; i += NT) cand_s[i] = cand[(size_t)q * QADC_MAX_INIT + i];
+    for (int e = tid; e < m; e += NT) bias_ord[e] = 0xffffffffu;
+    __syncthreads();
+    for (int e = tid; e < nprobe * m; e += NT)  // (m divides NT: a thread meets the same table every round)
+        atomicMin(&bias_ord[e % m], mins[(size_t)q * nprobe * m + e]);
+    __syncthreads();
+    if (tid < m) bias_s[tid] = ord2f(bias_ord[tid]);
+    __syncthreads();
+    float qmax = 0.0f;  // (no code in the probed lists)
+    if (n_walk > 0)     // uniform
+        qmax = ord2f(block_radix_select<unsigned, 4>(cand_s, (unsigned)n_walk, (unsigned)min(R, n_walk), &sc));
+    if (tid == 0) {
+        float qmin;
+        if (qmin_mode == QADC_QMIN_GLOBAL) {
+            qmin = bias_s[0];
+            for (int j = 1; j < m; ++j) qmin = fminf(qmin, bias_s[j]);
+            for (int j = 0; j < m; ++j) bias_s[j] = qmin;
+        } else {
+            qmin = 0.0f;
+            for (int j = 0; j < m; ++j) qmin = qmin + bias_s[j];
+        }
+        float delta = __fdiv_rn(qmax - qmin, (float)nbins);
+        if (!(delta > 0.0f)) delta = 1.0f;
+        qdelta[q] = delta;
+        qmax_out[q] = qmax;
+    }
+    __syncthreads();
+    if (tid < m) qbias[(size_t)q * m + tid] = bias_s[tid];
 }
 
 // ------------------------------------------------------------------- Seed
@@ -1236,8 +1427,11 @@ __global__ __launch_bounds__(NT) void ivf_scan_kernel(
 // query already names become unused slots (-1) -- a list is scanned once, so that keys stay
 // unique, and nothing outside list_off is read.
 __global__ void ivf_take_probes_kernel(const int32_t *__restrict__ in, int nprobe, int K, int64_t total,
-                                       int32_t *__restrict__ probes)
+                                       int32_t *__restrict__ probes, IvfClear clr, int nq)
 {
+    if (clr.scan_ws && (int)blockIdx.x < nq) {  // uniform: workgroup b also clears the control words of query b
+        ivf_clear_control(clr.scan_ws + (size_t)blockIdx.x * clr.ws_stride, clr.counts_off, clr.W, clr.countsA_off);
+    }
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const int64_t row = i / nprobe * nprobe;
@@ -1336,7 +1530,10 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     size_t o = 0;
     p->off_dist = o;   o += align_up((size_t)qd * kdist * 4, 256);
     p->off_bmin = o;   o += align_up((size_t)32 * ceil_div((int64_t)kdist, (int64_t)IVF_CT) * 4, 256);  // (calls of up to 32 queries)
-    p->off_front = o;  o += align_up((size_t)32 * (64 + 1) * 4, 256);  // quantizers of up to 32 queries (m <= 64)
+    // calls of up to 32 queries (ivf_front_kernel): biases [32][64], deltas, lengths of the walks, the sums of the init
+    // codes [32][QADC_MAX_INIT], the minima of the tables [32][nprobe][m]
+    p->off_front = o;
+    o += 32 * 64 * 4 + 256 + 256 + (size_t)32 * QADC_MAX_INIT * 4 + align_up((size_t)32 * nprobe * ix->m * 4, 256);
     p->off_probes = o; o += align_up((size_t)qb * nprobe * 4, 256);
     p->off_luts = o;   o += align_up((size_t)qb * nprobe * ix->m * 16 * 4, 256);
     p->off_qluts = o;  o += align_up((size_t)qb * nprobe * ix->m * 16, 256);
@@ -1415,11 +1612,23 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
     for (int q0 = 0; q0 < nq; q0 += p.qb) {
         const int nb = min(p.qb, nq - q0);
         const float *yq = queries + (size_t)q0 * d;
+        // A few queries: Tables and the sums of the qmax walk in one launch, the quantizer's parameters in a
+        // second (ivf_front_kernel, ivf_finish_kernel); the tables stay float and are quantized by the kernels that read them; the Index step's kernels
+        // clear the control words.
+        const bool front = nb <= 32 && !p.shared;
+        float *qbias = (float *)(ws + p.off_front);
+        float *qdelta = qbias + 32 * 64;
+        unsigned *nwalk = (unsigned *)(qdelta + 64);
+        unsigned *cand = nwalk + 64;
+        unsigned *tmins = cand + (size_t)32 * QADC_MAX_INIT;
+        IvfClear clr = {nullptr, 0, 0, 0, 0};
+        if (front) clr = IvfClear{scan_ws, p.stride, p.l.counts_off, p.countsA_off, p.W};
         // Index
         if (probes_in) {
             const int64_t np_total = (int64_t)nb * nprobe;
-            launch(QADC_PROF_IVF_INDEX, ivf_take_probes_kernel, dim3((unsigned)ceil_div(np_total, 256)), dim3(256),
-                   0, st, probes_in + (size_t)q0 * nprobe, nprobe, K, np_total, probes);
+            launch(QADC_PROF_IVF_INDEX, ivf_take_probes_kernel,
+                   dim3((unsigned)std::max<int64_t>(ceil_div(np_total, 256), front ? nb : 0)), dim3(256), 0, st,
+                   probes_in + (size_t)q0 * nprobe, nprobe, K, np_total, probes, clr, nb);
         } else {
             for (int i0 = 0; i0 < nb; i0 += p.qd) {
                 const int ni = min(p.qd, nb - i0);
@@ -1440,44 +1649,54 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
                            yi, ni, dist, bmin, nblk, vec4);
                 }
                 launch(QADC_PROF_IVF_INDEX, ivf_select_probes_kernel, dim3(ni), dim3(IVF_SEL_NT), 0, st, dist, K,
-                       nprobe, probes + (size_t)i0 * nprobe, (const unsigned *)bmin, (int)ceil_div(K, IVF_CT));
+                       nprobe, probes + (size_t)i0 * nprobe, (const unsigned *)bmin, (int)ceil_div(K, IVF_CT), clr);
             }
         }
-        // Tables
-        bool batch_tables = nb >= 64;
-        if (batch_tables) {
+        IvfQuantizer fq = {nullptr, nullptr, nullptr};
+        int rc = QADC_OK;
+        if (front) {
+            launch(QADC_PROF_IVF_TABLES, ivf_front_kernel, dim3(nprobe, nb), dim3(IVF_FRONT_NT),
+                   (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids,
+                   ix->Kh, probes, nprobe, luts, ix->list_off, ix->codes, ix->n, init, unit, qunits, cand, tmins,
+                   nwalk);
+            launch(QADC_PROF_IVF_TABLES, ivf_finish_kernel, dim3(nb), dim3(IVF_FINISH_NT), 0, st,
+                   (const unsigned *)cand, (const unsigned *)tmins, (const unsigned *)nwalk, nprobe, m, R, nbins,
+                   qmin_mode, qmax, qbias, qdelta);
+            fq = IvfQuantizer{luts, qbias, qdelta};
+            if (dbg_qluts)  // the 8-bit tables are wanted in memory after all
+                rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
+                                   nullptr, nullptr, st);
+        } else {
+            // Tables
+            bool batch_tables = nb >= 64;
+            if (batch_tables) {
 #define QADC_LUTS_CASE(D_)                                                                                       \
     case D_:                                                                                                    \
         launch(QADC_PROF_IVF_TABLES, ivf_build_luts_batch_kernel<D_>, dim3(nb), dim3(m * 16), 0, st, ix->codebooks, d, \
                m, yq, ix->coarse, ix->halves, ix->cell_ids, ix->Kh, probes, nprobe, luts);                      \
         break;
-            switch (d / m) {
-                QADC_LUTS_CASE(2)
-                QADC_LUTS_CASE(4)
-                QADC_LUTS_CASE(6)
-                QADC_LUTS_CASE(8)
-                QADC_LUTS_CASE(16)
-            default:
-                batch_tables = false;
-            }
+                switch (d / m) {
+                    QADC_LUTS_CASE(2)
+                    QADC_LUTS_CASE(4)
+                    QADC_LUTS_CASE(6)
+                    QADC_LUTS_CASE(8)
+                    QADC_LUTS_CASE(16)
+                default:
+                    batch_tables = false;
+                }
 #undef QADC_LUTS_CASE
+            }
+            if (!batch_tables)
+                launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
+                       (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids,
+                       ix->Kh, probes, nprobe, luts);
+            // (a few queries: a thread per init code, so that the walk is one round of loads)
+            launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(nb <= 32 ? 1024 : 256), 0, st, ix->list_off, ix->codes,
+                   m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n, scan_ws, p.stride, p.l.counts_off,
+                   p.W, p.countsA_off);
+            rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts, nullptr,
+                               nullptr, nullptr, st);
         }
-        if (!batch_tables)
-            launch(QADC_PROF_IVF_TABLES, ivf_build_luts_kernel, dim3(nprobe, nb), dim3(256),
-                   (size_t)d * sizeof(double), st, ix->codebooks, d, m, yq, ix->coarse, ix->halves, ix->cell_ids,
-                   ix->Kh, probes, nprobe, luts);
-        // (a few queries: a thread per init code, so that the walk is one round of loads)
-        launch(QADC_PROF_IVF_TABLES, ivf_qmax_kernel, dim3(nb), dim3(nb <= 32 ? 1024 : 256), 0, st, ix->list_off, ix->codes,
-               m, probes, nprobe, luts, init, R, qmax, unit, qunits, ix->n, scan_ws, p.stride, p.l.counts_off,
-               p.W, p.countsA_off);
-        // a few queries: the quantizer's parameters only, applied by the kernels that read the tables
-        const bool float_tables = nb <= 32 && !p.shared;
-        float *qbias = (float *)(ws + p.off_front);
-        float *qdelta = qbias + 32 * 64;
-        IvfQuantizer fq = {nullptr, nullptr, nullptr};
-        if (float_tables) fq = IvfQuantizer{luts, qbias, qdelta};
-        int rc = quantize_luts(16, luts, nb, nprobe, m, nullptr, 0, qmax, R, nbins, qmin_mode, qluts,
-                               float_tables ? qbias : nullptr, float_tables ? qdelta : nullptr, nullptr, st);
         if (rc != QADC_OK) return rc;
         // Scan: up to p.W workgroups per query, one per `upw` units of its lists (batches that fill
         // the GPU by their number alone), one per unit otherwise

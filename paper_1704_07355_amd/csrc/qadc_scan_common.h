@@ -255,7 +255,7 @@ constexpr int MERGE_NT = 1024;
 constexpr int MERGE_CAP = 6144;   // keys staged in LDS
 constexpr int MERGE_WG_PER_THREAD = 8;
 constexpr int MERGE_FLAT_G = 256;        // regions and ...
-constexpr int MERGE_FLAT_SLOTS = 16384;  // ... key slots up to which every slot is visited
+constexpr int MERGE_FLAT_SLOTS = 32768;  // ... key slots up to which every slot is visited
 
 // R best of the keys reported by the G workgroups of each query (64-bit keys
 // dist << 32 | index, at most R per workgroup), ordered; then everything the call wrote

@@ -346,3 +346,38 @@ def test_ivf_few_queries_both_workgroup_shapes(Q, O, m, wide_q, seed_kernel, mon
                                      probes=probes[iq].cpu().numpy(), qluts=qluts[iq].cpu().numpy())
         assert np.array_equal(idx_np(ids)[iq], rep["ids"]), iq
         assert np.array_equal(dist[iq].cpu().numpy(), rep["dist"]), iq
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_ivf_few_queries_path_equals_batch_path(Q, O, mode):
+    """Calls of up to 32 queries take kernels of their own (centroids staged in one round with the
+    minima of runs of 128 cells, Tables and the qmax walk in one launch, tables quantized where they
+    are read); a call of 70 takes the batch kernels.  Same cells, tables and neighbours either way, and
+    the oracle's on the cells and tables of the few-queries call.  d = 200 (two rounds of components),
+    K = 1300 (eleven runs of cells, the last one ragged), and queries that are not 16-byte aligned."""
+    import torch
+    K, d, m = 1300, 200, 8
+    coarse, cb, x, index = build_ivf(O, n=40_000, K=K, d=d, m=m, seed=77)
+    gix = gpu_index(Q, coarse, cb, index)
+    rng = np.random.default_rng(5)
+    nq, nprobe, R, init = 70, 4, 50, 200
+    queries = (x[rng.integers(0, len(x), size=nq)] + rng.normal(scale=6, size=(nq, d))).astype(np.float32)
+    flat = torch.zeros(nq * d + 1, dtype=torch.float32, device="cuda:0")
+    flat[1:] = to_gpu(queries).flatten()
+    gq_odd = flat[1:].view(nq, d)  # rows start 4 bytes past a 16-byte boundary
+    gq = to_gpu(queries)
+    ids, dist, probes, qluts = Q.qadc_ivf_search(gix, gq, nprobe, R, init, qmin_mode=mode, debug=True)
+    torch.cuda.synchronize()
+    for s, src in ((0, gq), (7, gq), (33, gq_odd), (64, gq_odd)):
+        n1 = 1 if s == 7 else 6
+        i2, d2, p2, q2 = Q.qadc_ivf_search(gix, src[s:s + n1], nprobe, R, init, qmin_mode=mode, debug=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(p2.cpu().numpy(), probes.cpu().numpy()[s:s + n1]), s
+        assert np.array_equal(q2.cpu().numpy(), qluts.cpu().numpy()[s:s + n1]), s
+        assert np.array_equal(idx_np(i2), idx_np(ids)[s:s + n1]), s
+        assert np.array_equal(d2.cpu().numpy(), dist.cpu().numpy()[s:s + n1]), s
+        for k in range(n1):
+            rep = O.ivf_quick_adc_search(index, coarse, cb, queries[s + k], nprobe, init, R, qmin_mode=mode,
+                                         probes=p2[k].cpu().numpy(), qluts=q2[k].cpu().numpy())
+            assert np.array_equal(idx_np(i2)[k], rep["ids"]), (s, k)
+            assert np.array_equal(d2[k].cpu().numpy(), rep["dist"]), (s, k)
