@@ -846,11 +846,10 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     __shared__ int len[IVF_MAX_NPROBE];
     __shared__ int more[IVF_MAX_NPROBE];  // codes sampled beyond per_list (long lists, long_shift > 0)
     __shared__ unsigned hist[256];
-    __shared__ unsigned last_s;
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
     // a few queries: the probed lists of a query are split over gridDim.y workgroups, which add
-    // their histograms into the query's control block; the last one to finish derives the bound
+    // their histograms into the query's control block
     const int parts = gridDim.y;
     // (nseed <= nprobe: only the lists of the nseed closest cells are sampled)
     const int per_part = (nseed + parts - 1) / parts;
@@ -924,22 +923,11 @@ __global__ __launch_bounds__(IVF_SEED_NT) void ivf_seed_kernel(
     __syncthreads();
     ScanHeader *hdr = reinterpret_cast<ScanHeader *>(ws + (size_t)q * ws_stride);
     if (parts > 1) {
-        // ghist[1][bin]: the query's histogram over all parts; ghist[0][1]: parts that have added theirs
+        // ghist[1][bin]: the query's histogram over all parts; every workgroup of the scan kernel derives
+        // the bound from it (the launch boundary orders the two; no count of finished parts, no fences)
         if (tid < 256 && hist[tid])
             __hip_atomic_fetch_add(&hdr->ghist[1][tid], hist[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned done = __hip_atomic_fetch_add(&hdr->ghist[0][1], 1u, __ATOMIC_ACQ_REL,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-            last_s = (done == (unsigned)parts - 1u) ? 1u : 0u;
-        }
-        __syncthreads();
-        if (!last_s) return;  // uniform
-        __threadfence();
-        if (tid < 256)
-            hist[tid] = __hip_atomic_load(&hdr->ghist[1][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
+        return;  // uniform
     }
     if (tid < WAVE) {
         unsigned h[4];
@@ -1057,7 +1045,7 @@ __global__ __launch_bounds__(NT) void ivf_scan_kernel(
     const int32_t *__restrict__ probes, int nprobe, const uint8_t *__restrict__ qluts, int cap_i,
     int R, int units_per_wg, int Wmax, const unsigned *__restrict__ wgmap, char *__restrict__ ws,
     size_t ws_stride, size_t counts_off, size_t lists_off, const int32_t *__restrict__ probes_alt,
-    const unsigned *__restrict__ flags, IvfQuantizer fq)
+    const unsigned *__restrict__ flags, IvfQuantizer fq, int hist_bound)
 {
     using C = ScanCfg<B, NT>;
     constexpr long long UNIT = (long long)IVF_UNIT_TILES * IVF_NT * C::CPT;  // the same codes whatever NT
@@ -1075,8 +1063,15 @@ __global__ __launch_bounds__(NT) void ivf_scan_kernel(
     const int q = (int)(me >> 12);
     const int g = (int)(me & 4095u);
     const unsigned cap = (unsigned)cap_i;
-    // bound + 1 left by the seed kernel (uniform load), 0 when there is none
-    const unsigned tau1 = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride)->ghist[0][0];
+    // bound + 1 left by the seed kernel (uniform load), 0 when there is none; hist_bound: the seed
+    // kernel's workgroups left the query's histogram instead, and the bound is derived below
+    const ScanHeader *hdr_in = reinterpret_cast<const ScanHeader *>(ws + (size_t)q * ws_stride);
+    unsigned tau1 = hist_bound ? 0u : hdr_in->ghist[0][0];
+    unsigned hb[4] = {0, 0, 0, 0};
+    if (hist_bound && tid < WAVE) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(&hdr_in->ghist[1][4 * tid]);
+        hb[0] = v.x; hb[1] = v.y; hb[2] = v.z; hb[3] = v.w;
+    }
 
     // Geometry of the probed lists, one thread per probe, then an exclusive prefix sum of the
     // unit counts.
@@ -1112,8 +1107,13 @@ __global__ __launch_bounds__(NT) void ivf_scan_kernel(
         if (tid == nprobe - 1) sh.ustart[nprobe] = (long long)(before + inc);
         if (tid == 0) { sh.tcnt[0] = 0; sh.fcnt = 0; }
     }
+    if (hist_bound && tid < WAVE) {  // the bin where the running count of the sample reaches R
+        const unsigned t = wave_threshold_bin<4>(hb, (unsigned)R);
+        if (tid == 0) sh.tau = (t < 256u) ? t + 1u : 0u;
+    }
     for (int e = tid; e < 256; e += NT) sh.sel.hist[e] = 0;
     __syncthreads();
+    if (hist_bound) tau1 = sh.tau;  // uniform
     const long long units = sh.ustart[nprobe];
     // Workgroups of this query: in proportion to its work (a query whose cell is one of the few
     // huge lists gets up to Wmax of them, a query of short lists a handful) -- the count the
@@ -1704,7 +1704,10 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         const int upw = nb >= 64 ? max(1, knob_or(knobs().ivf_units, 16)) : 1;
         // a few queries: their lists are sampled by several workgroups each
         const int seed_parts_env = knob_or(knobs().ivf_seed_parts, 0);
-        const int seed_parts = seed_parts_env > 0 ? min(seed_parts_env, nprobe) : nb >= 16 ? 1 : min(8, (nprobe + 7) / 8);
+        // (measured at N = 1e9: one query best with 16, 16 and 32 queries with 8, 64 with 4; the shared-list
+        // scan reads the bound itself and needs it in one piece)
+        const int parts_def = p.shared || nb >= 256 ? 1 : nb >= 64 ? 4 : nb >= 16 ? 8 : 16;
+        const int seed_parts = p.shared ? 1 : min(seed_parts_env > 0 ? seed_parts_env : parts_def, nprobe);
         // the bound is sampled from the lists of the closest cells only: they hold most of a query's best
         // codes, and the sample is most of the seed kernel's cost
         const int nseed = std::min(nprobe, std::max(1, knob_or(knobs().ivf_seed_probes, IVF_SEED_PROBES)));
@@ -1745,18 +1748,19 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
         if (mapped)
             launch(QADC_PROF_SEED, ivf_wgmap_kernel, dim3(1), dim3(IVF_MAP_NT), 0, st, qunits, nb, upw, p.W, wgmap,
                    (const unsigned *)qunits_light, (const unsigned *)flags);
+        const int hist_bound = (p.seed_per_list > 0 && seed_parts > 1) ? 1 : 0;
 #define QADC_IVF_CASE(B_)                                                                              \
     case B_:                                                                                          \
         if (wide_wgs)                                                                                  \
             launch(QADC_PROF_SCAN, ivf_scan_kernel<B_, 1024>, grid, dim3(1024), 0, st, ix->list_off, ix->codes, \
                    ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws, \
                    p.stride, p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light,              \
-                   (const unsigned *)flags, fq);                                                       \
+                   (const unsigned *)flags, fq, hist_bound);                                           \
         else                                                                                           \
             launch(QADC_PROF_SCAN, ivf_scan_kernel<B_, IVF_NT>, grid, dim3(IVF_NT), 0, st, ix->list_off, ix->codes, \
                    ix->n, probes, nprobe, qluts, nbins, R, upw, p.W, mapped ? wgmap : (unsigned *)nullptr, scan_ws, \
                    p.stride, p.l.counts_off, p.l.lists_off, (const int32_t *)probes_light,              \
-                   (const unsigned *)flags, fq);                                                       \
+                   (const unsigned *)flags, fq, hist_bound);                                           \
         break;
         switch (m / 2) {
             QADC_IVF_CASE(4)
