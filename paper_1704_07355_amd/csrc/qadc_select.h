@@ -9,10 +9,15 @@
 
 namespace qadc {
 
+constexpr int SELECT_SMALL = 64;  // keys left in the race that one wavefront ranks directly
+
 struct SelectScratch {
     unsigned hist[256];
     unsigned bin;
     unsigned need;
+    unsigned nsmall;
+    unsigned long long small[SELECT_SMALL];
+    unsigned long long result;
 };
 
 // Scan of a 256-bin histogram by the first wave: finds the bin holding the
@@ -68,9 +73,33 @@ __device__ K block_radix_select_each(Each each, unsigned need, SelectScratch *sc
         select_bin(sc, need);
         __syncthreads();
         need = sc->need;
+        const unsigned left = sc->hist[sc->bin];  // keys that share the prefix found so far
         prefix |= (K)sc->bin << shift;
         mask |= (K)255 << shift;
+        if (threadIdx.x == 0) sc->nsmall = 0;
         __syncthreads();
+        if (shift > 0 && need >= 1u && left >= need && left <= (unsigned)SELECT_SMALL) {  // uniform
+            // A handful of keys left (equal ones included): they are gathered and one wavefront finds
+            // the need-th smallest among them by counting, instead of a histogram pass per byte left.
+            each([&](K k) {
+                if ((k & mask) == prefix) sc->small[atomicAdd(&sc->nsmall, 1u)] = (unsigned long long)k;
+            });
+            __syncthreads();
+            if (threadIdx.x < WAVE) {
+                const unsigned n = sc->nsmall;
+                const unsigned l = threadIdx.x;
+                const unsigned long long mine = l < n ? sc->small[l] : ~0ull;
+                unsigned less = 0, leq = 0;
+                for (unsigned j = 0; j < n; ++j) {
+                    const unsigned long long o = sc->small[j];
+                    less += o < mine ? 1u : 0u;
+                    leq += o <= mine ? 1u : 0u;
+                }
+                if (l < n && less < need && need <= leq) sc->result = mine;  // (equal keys write the same value)
+            }
+            __syncthreads();
+            return (K)sc->result;
+        }
     }
     return prefix;
 }
