@@ -82,6 +82,8 @@ def parse():
                          "vectors are rotated before encoding and every query by qadc_rotate before qadc_search")
     ap.add_argument("--no-mi-full", action="store_true",
                     help="ivf workload: skip the multi-index of 2^14 x 2^14 cells over the same codes")
+    ap.add_argument("--no-small-calls", action="store_true",
+                    help="ivf: skip the timing of calls of 1, 4, 16 and 64 queries")
     ap.add_argument("--no-extras", action="store_true",
                     help="scan workload: skip the short runs of configs 3, 4 and 5 nested in the same line")
     ap.add_argument("--separate-calls", action="store_true",
@@ -545,6 +547,26 @@ def run_ivf(args):
                "sample": "%d queries of the last batch, NumPy oracle replay of the GPU's cells and tables "
                "(%d codes)" % (nqc, codes_done), "seconds": round(dt, 2), "gpu_sums_match_oracle": bool(same)}
 
+    # beside it: calls of a few queries (response time; the batch rate above is the headline)
+    small_calls = {}
+    for nsm in (1, 4, 16, 64):
+        if nsm > nb or getattr(args, "no_small_calls", False):
+            continue
+        sws = Q.qadc_workspace_init(torch.empty(Q.qadc_ivf_workspace_bytes(index, nsm, nprobe, R),
+                                                dtype=torch.uint8, device=dev))
+        reps = 200 if nsm <= 4 else 50
+        for i in range(5):
+            Q.qadc_ivf_search(index, queries[i * nsm:(i + 1) * nsm], nprobe, R, init, workspace=sws)
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        for i in range(reps):
+            j = i % (nq_total // nsm)
+            Q.qadc_ivf_search(index, queries[j * nsm:(j + 1) * nsm], nprobe, R, init, workspace=sws)
+        s1.record()
+        torch.cuda.synchronize()
+        small_calls[str(nsm)] = round(s0.elapsed_time(s1) / reps, 4)
+        del sws
+
     return ({
         "metric": "queries/s (IVF + Quick ADC, whole path per batch)",
         "value": round(nb / (ms_per_step * 1e-3), 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
@@ -555,7 +577,7 @@ def run_ivf(args):
                    "n": n, "K": K, "m": m, "nprobe": nprobe, "R": R, "init": init, "batch": nb},
         "gcodes_scanned_per_s": round(scanned / (ms_per_step * 1e-3) / 1e9, 2),
         "phase_ms_per_query": {k: round(v / nb, 5) for k, v in phase.items()},
-        "multi_index": multi_index,
+        "multi_index": multi_index, "ms_per_call_of_few_queries": small_calls,
         "roofline": roofline, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)})
 
 
