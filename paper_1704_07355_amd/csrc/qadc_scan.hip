@@ -26,6 +26,8 @@
 // on how the grid is cut or on the order waves run in.
 
 #include "qadc_scan_common.h"
+#include <algorithm>
+
 #include "qadc_scan_u8.h"
 #include "qadc_scan_tiled.h"
 
@@ -649,7 +651,10 @@ static int dispatch_seed_u8(const ScanPlan &p, const uint8_t *codes, int64_t n,
     // batches that the query-tiled kernels scan are sampled in the query-tiled way too
     if (p.tiled && nq >= TILED_MIN_Q && knob_or(knobs().tiled_seed, 1) != 0) {
         const int cpt = (p.B <= 16) ? SCAN_VEC * (16 / p.B) : 1;
-        return run_tiled_seed(p.t, codes, n, qluts, nq, cap, R, p.wide ? 1 : 0, (int64_t)p.seed_wgs * 1024 * cpt,
+        // (at most 512 sample tiles unless QADC_SEED_WGS says otherwise: N = 1e8, m = 32, 256 queries: 1024
+        // tiles 0.42 ms of sampling, 512 tiles 0.22 ms and 0.07 ms more in the scan, 256 tiles 0.12 and 0.21)
+        const int tiles = knobs().seed_wgs > 0 ? p.seed_wgs : std::min(p.seed_wgs, 512);
+        return run_tiled_seed(p.t, codes, n, qluts, nq, cap, R, p.wide ? 1 : 0, (int64_t)tiles * 1024 * cpt,
                               ws, p.stride, st);
     }
     // batches: several tiles per workgroup, so that building the pair tables pays
