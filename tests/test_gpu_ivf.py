@@ -381,3 +381,37 @@ def test_ivf_few_queries_path_equals_batch_path(Q, O, mode):
                                          probes=p2[k].cpu().numpy(), qluts=q2[k].cpu().numpy())
             assert np.array_equal(idx_np(i2)[k], rep["ids"]), (s, k)
             assert np.array_equal(d2[k].cpu().numpy(), rep["dist"]), (s, k)
+
+
+@pytest.mark.parametrize("K", [300_000, 530_000])
+def test_ivf_few_queries_many_cells(Q, O, K):
+    """Hundreds of thousands of cells, most of them empty, a few queries: with 2344 runs of 128 cells the
+    selection works from the runs' minima, with 4141 runs (more than fit its LDS list) it walks the
+    whole row; either way the oracle's cells (up to float32 ties) and, on those cells and tables, its
+    neighbours."""
+    import torch
+    d, m, n = 8, 8, 30_000
+    rng = np.random.default_rng(K)
+    coarse = rng.uniform(0, 255, size=(K, d)).astype(np.float32)
+    cells = np.sort(rng.integers(0, K, size=n))
+    list_off = np.zeros(K + 1, dtype=np.int64)
+    np.cumsum(np.bincount(cells, minlength=K), out=list_off[1:])
+    codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+    ids = rng.permutation(n).astype(np.uint32)
+    cb = rng.normal(scale=20, size=(m, 16, d // m)).astype(np.float32)
+    index = dict(list_off=list_off, codes=codes, ids=ids)
+    gix = gpu_index(Q, coarse, cb, index)
+    nq, nprobe, R, init = 3, 200, 20, 50
+    queries = rng.uniform(0, 255, size=(nq, d)).astype(np.float32)
+    gi, gd, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, R, init, debug=True)
+    torch.cuda.synchronize()
+    probes = probes.cpu().numpy()
+    for iq in range(nq):
+        want = O.ivf_probes(queries[iq], coarse, nprobe)
+        if not np.array_equal(probes[iq], want):
+            dq = O.sq_l2(queries[iq][None], coarse)[0]
+            np.testing.assert_allclose(dq[probes[iq]], dq[want], rtol=1e-5)
+        rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R,
+                                     probes=probes[iq], qluts=qluts[iq].cpu().numpy())
+        assert np.array_equal(idx_np(gi)[iq], rep["ids"]), iq
+        assert np.array_equal(gd[iq].cpu().numpy(), rep["dist"]), iq
