@@ -346,7 +346,7 @@ __global__ __launch_bounds__(1024) void prepare_u8_kernel(
 // radix select whenever it fills up -- so the result never depends on the bound being
 // good, only the speed does.
 template <int B, int NT>
-__global__ __launch_bounds__(NT) void scan_u8_kernel(
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(B >= SIXBIT ? 4 : 8))) void scan_u8_kernel(
     const uint8_t *__restrict__ codes, int64_t n, const uint8_t *__restrict__ qluts, int cap_i,
     int R, int mode, char *__restrict__ ws, size_t ws_stride, size_t counts_off,
     size_t lists_off, const unsigned *__restrict__ redo_flags)
