@@ -547,6 +547,31 @@ def run_ivf(args):
                "sample": "%d queries of the last batch, NumPy oracle replay of the GPU's cells and tables "
                "(%d codes)" % (nqc, codes_done), "seconds": round(dt, 2), "gpu_sums_match_oracle": bool(same)}
 
+    # beside it: batches alternating over two streams, each with a workspace of its own (the small kernels
+    # of one batch overlap the scans of the other)
+    two_streams = None
+    if args.streams > 1 and not getattr(args, "no_small_calls", False):
+        strs = [torch.cuda.Stream(device=dev) for _ in range(2)]
+        wss = [ws, Q.qadc_workspace_init(torch.empty(Q.qadc_ivf_workspace_bytes(index, nb, nprobe, R),
+                                                     dtype=torch.uint8, device=dev))]
+        nbat = nq_total // nb
+        torch.cuda.synchronize()
+
+        def alternate(reps):
+            for i in range(reps):
+                with torch.cuda.stream(strs[i % 2]):
+                    Q.qadc_ivf_search(index, queries[(i % nbat) * nb:(i % nbat + 1) * nb], nprobe, R, init,
+                                      workspace=wss[i % 2])
+        alternate(2)
+        torch.cuda.synchronize()
+        t2 = time.time()
+        alternate(2 * args.steps)
+        torch.cuda.synchronize()
+        dt2 = time.time() - t2
+        two_streams = {"ms_per_batch": round(dt2 / (2 * args.steps) * 1e3, 3),
+                       "queries_per_s": round(nb * 2 * args.steps / dt2, 1)}
+        del wss
+
     # beside it: calls of a few queries (response time; the batch rate above is the headline)
     small_calls = {}
     for nsm in (1, 4, 16, 64):
@@ -577,7 +602,7 @@ def run_ivf(args):
                    "n": n, "K": K, "m": m, "nprobe": nprobe, "R": R, "init": init, "batch": nb},
         "gcodes_scanned_per_s": round(scanned / (ms_per_step * 1e-3) / 1e9, 2),
         "phase_ms_per_query": {k: round(v / nb, 5) for k, v in phase.items()},
-        "multi_index": multi_index, "ms_per_call_of_few_queries": small_calls,
+        "multi_index": multi_index, "ms_per_call_of_few_queries": small_calls, "two_streams": two_streams,
         "roofline": roofline, "cpu_baseline": cpu, "database_build_s": round(t_build, 2)})
 
 
