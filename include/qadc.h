@@ -35,7 +35,8 @@
  *  - Environment variables named QADC_* (QADC_SCAN_WGS, QADC_SCAN_NT, QADC_TILED,
  *    QADC_SEED_MIN_TILES, QADC_SEED_WGS, QADC_SCAN_F32_WGS, QADC_IVF_WGS, QADC_IVF_UNITS,
  *    QADC_IVF_SEED, QADC_TILED_SEED, QADC_TILED_MFMA, QADC_MFMA_MIN_Q, QADC_MFMA_MIN_Q2, QADC_MFMA_MIN_Q4,
- *    QADC_MFMA_WAVES, QADC_IVF_SEED_PARTS)
+ *    QADC_MFMA_WAVES, QADC_IVF_SEED_PARTS, QADC_IVF_SEED_PROBES, QADC_IVF_SHARED, QADC_IVF_SHARED_WGS,
+ *    QADC_IVF_SHARED_MIN_PAIRS, QADC_IVF_WIDE_Q)
  *    change launch shapes, which of the equivalent kernels scans a batch and whether a
  *    sampled bound is used -- never a result.
  *    They are read once per call of an entry point and exist for tuning and for tests.
