@@ -88,7 +88,7 @@ constexpr int IVF_CK = 16;   // components per step
 template <int AQ>
 __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
     const float *__restrict__ coarse, int K, int d, const float *__restrict__ queries, int nq,
-    float *__restrict__ dist)
+    float *__restrict__ dist, unsigned *__restrict__ blockmin, int nblk)
 {
     constexpr int QT = 16 * AQ;
     __shared__ __attribute__((aligned(16))) float ys[IVF_CK][QT + 4];
@@ -161,16 +161,24 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
 #pragma unroll
     for (int a = 0; a < AQ; ++a) {
         const int q = q0 + AQ * ty + a;
-        if (q >= nq) continue;
+        unsigned mn = 0xffffffffu;  // smallest distance of this query over the workgroup's cells, as its image
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int c = c0 + 32 * k + 2 * tx;
+            if (c < K) mn = min(mn, f2ord(acc[a][2 * k]));
+            if (c + 1 < K) mn = min(mn, f2ord(acc[a][2 * k + 1]));
+            if (q >= nq) continue;
             if (c + 1 < K && (K & 1) == 0) {  // K even: the pair is 8-byte aligned
                 *reinterpret_cast<float2 *>(&dist[(size_t)q * K + c]) = make_float2(acc[a][2 * k], acc[a][2 * k + 1]);
             } else {
                 if (c < K) dist[(size_t)q * K + c] = acc[a][2 * k];
                 if (c + 1 < K) dist[(size_t)q * K + c + 1] = acc[a][2 * k + 1];
             }
+        }
+        if (blockmin) {  // uniform: the 16 lanes tx of a query are neighbours in the wavefront
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) mn = min(mn, (unsigned)__shfl_xor((int)mn, o));
+            if (tx == 0 && q < nq) blockmin[(size_t)q * nblk + blockIdx.x] = mn;
         }
     }
 }
@@ -1529,7 +1537,7 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->qd = (int)qd;
     size_t o = 0;
     p->off_dist = o;   o += align_up((size_t)qd * kdist * 4, 256);
-    p->off_bmin = o;   o += align_up((size_t)32 * ceil_div((int64_t)kdist, (int64_t)IVF_CT) * 4, 256);  // (calls of up to 32 queries)
+    p->off_bmin = o;   o += align_up((size_t)qd * ceil_div((int64_t)kdist, (int64_t)IVF_CT) * 4, 256);  // minima of the runs of cells
     // calls of up to 32 queries (ivf_front_kernel): biases [32][64], deltas, lengths of the walks, the sums of the init
     // codes [32][QADC_MAX_INIT], the minima of the tables [32][nprobe][m]
     p->off_front = o;
@@ -1633,16 +1641,16 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
             for (int i0 = 0; i0 < nb; i0 += p.qd) {
                 const int ni = min(p.qd, nb - i0);
                 const float *yi = yq + (size_t)i0 * d;
+                // the minima of the runs of IVF_CT cells go with the distances, and the selection reads
+                // only the runs that matter (when there are enough runs)
                 unsigned *bmin = nullptr;
+                const int nblk = (int)ceil_div(K, IVF_CT);
+                if (nblk >= 2 * nprobe && nblk <= IVF_SEL_MAXBLK) bmin = (unsigned *)(ws + p.off_bmin);
                 if (nb > 32) {
-                    dim3 grid((unsigned)ceil_div(K, IVF_CT), (unsigned)ceil_div(ni, 128));
+                    dim3 grid((unsigned)nblk, (unsigned)ceil_div(ni, 128));
                     launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_kernel<8>, grid, dim3(256), 0, st, ix->coarse, K, d,
-                           yi, ni, dist);
+                           yi, ni, dist, bmin, nblk);
                 } else {
-                    // a few queries: the minima of the runs of IVF_CT cells go with the distances, and
-                    // the selection reads only the runs that matter (when there are enough runs)
-                    const int nblk = (int)ceil_div(K, IVF_CT);
-                    if (nblk >= 2 * nprobe && nblk <= IVF_SEL_MAXBLK) bmin = (unsigned *)(ws + p.off_bmin);
                     const int vec4 = (d % 4 == 0 && ((uintptr_t)ix->coarse & 15) == 0 && ((uintptr_t)yi & 15) == 0) ? 1 : 0;
                     dim3 grid((unsigned)nblk, (unsigned)ceil_div(ni, IVF_FEW_Q));
                     launch(QADC_PROF_IVF_INDEX, ivf_coarse_dist_few_kernel, grid, dim3(256), 0, st, ix->coarse, K, d,
