@@ -80,12 +80,18 @@ __global__ __launch_bounds__(1024) void ivfs_offsets_kernel(const unsigned *__re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid < 3) carry[tid] = 0;
     __syncthreads();
+    // (the inputs of the next round are requested before this round's sums: a round is otherwise one
+    // memory latency long, and there are K / 1024 of them)
+    unsigned nP = 0;
+    long long nl = 0, nh = 0;
+    if (tid < K) { nP = pair_cnt[tid]; nl = list_off[tid]; nh = list_off[tid + 1]; }
     for (int c0 = 0; c0 < K; c0 += 1024) {
         const int c = c0 + tid;
+        const unsigned P = nP;
+        long long l = nl, h = nh;
+        if (c + 1024 < K) { nP = pair_cnt[c + 1024]; nl = list_off[c + 1024]; nh = list_off[c + 1024 + 1]; }
         unsigned v[3] = {0, 0, 0};
         if (c < K) {
-            const unsigned P = pair_cnt[c];
-            long long l = list_off[c], h = list_off[c + 1];
             if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: no work
             const long long n = h - l, s = ivfs_lead(n);
             const unsigned sets = P >= (unsigned)min_pairs ? (P + (unsigned)qw - 1u) / (unsigned)qw : 0u;
