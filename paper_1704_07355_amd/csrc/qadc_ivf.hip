@@ -1553,7 +1553,7 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     p->off_plight = p->off_ulight = 0;
     if (p->shared) {
         const size_t kk = align_up(((size_t)ix->K + 1) * 4, 256);
-        p->off_paircnt = o; o += kk;
+        p->off_paircnt = o; o += kk + 4096;  // (+ the totals of the 1024-cell blocks of the running sums)
         p->off_pairoff = o; o += kk;
         p->off_item0 = o;   o += kk;
         p->off_item1 = o;   o += kk;

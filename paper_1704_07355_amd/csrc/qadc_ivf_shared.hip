@@ -65,76 +65,99 @@ __global__ __launch_bounds__(256) void ivfs_count_kernel(const int32_t *__restri
     }
 }
 
-// One workgroup: exclusive running sums over the cells of (pairs, work items of the leading
-// parts, work items of the rest).  A cell with P >= min_pairs pairs and n codes is ceil(P / qw) sets
-// of pairs times ceil(len / IVFS_CHUNK) chunks of either part; a cell with fewer pairs is no work here.
-__global__ __launch_bounds__(1024) void ivfs_offsets_kernel(const unsigned *__restrict__ pair_cnt,
-                                                            const int64_t *__restrict__ list_off, int K,
-                                                            int64_t n_total, int qw, int min_pairs,
-                                                            unsigned *__restrict__ pair_off,
-                                                            unsigned *__restrict__ item_off0,
-                                                            unsigned *__restrict__ item_off1)
+// Exclusive running sums over the cells of (pairs, work items of the leading parts, work items of the
+// rest).  A cell with P >= min_pairs pairs and n codes is ceil(P / qw) sets of pairs times
+// ceil(len / IVFS_CHUNK) chunks of either part; a cell with fewer pairs is no work here.  Two launches:
+// every workgroup sums its 1024 cells and leaves its totals in blk[3][nblk]; then every workgroup adds
+// the totals of the workgroups before it (one workgroup walking all the cells took 64 rounds of
+// barriers and LDS chains for 65536 cells).
+constexpr int IVFS_OFF_NT = 1024;
+
+__global__ __launch_bounds__(IVFS_OFF_NT) void ivfs_offsets_kernel(const unsigned *__restrict__ pair_cnt,
+                                                                   const int64_t *__restrict__ list_off, int K,
+                                                                   int64_t n_total, int qw, int min_pairs,
+                                                                   unsigned *__restrict__ pair_off,
+                                                                   unsigned *__restrict__ item_off0,
+                                                                   unsigned *__restrict__ item_off1,
+                                                                   unsigned *__restrict__ blk)
 {
     __shared__ unsigned wsum[3][16];
-    __shared__ unsigned carry[3];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 3) carry[tid] = 0;
-    __syncthreads();
-    // (the inputs of the next round are requested before this round's sums: a round is otherwise one
-    // memory latency long, and there are K / 1024 of them)
-    unsigned nP = 0;
-    long long nl = 0, nh = 0;
-    if (tid < K) { nP = pair_cnt[tid]; nl = list_off[tid]; nh = list_off[tid + 1]; }
-    for (int c0 = 0; c0 < K; c0 += 1024) {
-        const int c = c0 + tid;
-        const unsigned P = nP;
-        long long l = nl, h = nh;
-        if (c + 1024 < K) { nP = pair_cnt[c + 1024]; nl = list_off[c + 1024]; nh = list_off[c + 1024 + 1]; }
-        unsigned v[3] = {0, 0, 0};
-        if (c < K) {
-            if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: no work
-            const long long n = h - l, s = ivfs_lead(n);
-            const unsigned sets = P >= (unsigned)min_pairs ? (P + (unsigned)qw - 1u) / (unsigned)qw : 0u;
-            v[0] = P;
-            v[1] = sets * (unsigned)((s + IVFS_CHUNK - 1) / IVFS_CHUNK);
-            v[2] = sets * (unsigned)((n - s + IVFS_CHUNK - 1) / IVFS_CHUNK);
-        }
-        unsigned inc[3] = {v[0], v[1], v[2]};
+    const int nblk = gridDim.x;
+    const int c = blockIdx.x * IVFS_OFF_NT + tid;
+    unsigned v[3] = {0, 0, 0};
+    if (c < K) {
+        const unsigned P = pair_cnt[c];
+        long long l = list_off[c], h = list_off[c + 1];
+        if (l < 0 || h > n_total || h < l) l = h = 0;  // offsets that are not a list: no work
+        const long long n = h - l, s = ivfs_lead(n);
+        const unsigned sets = P >= (unsigned)min_pairs ? (P + (unsigned)qw - 1u) / (unsigned)qw : 0u;
+        v[0] = P;
+        v[1] = sets * (unsigned)((s + IVFS_CHUNK - 1) / IVFS_CHUNK);
+        v[2] = sets * (unsigned)((n - s + IVFS_CHUNK - 1) / IVFS_CHUNK);
+    }
+    unsigned inc[3] = {v[0], v[1], v[2]};
 #pragma unroll
-        for (int s = 1; s < 64; s <<= 1) {
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                const unsigned o = __shfl_up(inc[k], s);
-                if (lane >= s) inc[k] += o;
-            }
-        }
-        if (lane == 63) {
-#pragma unroll
-            for (int k = 0; k < 3; ++k) wsum[k][wave] = inc[k];
-        }
-        __syncthreads();
-        unsigned before[3];
+    for (int s = 1; s < 64; s <<= 1) {
 #pragma unroll
         for (int k = 0; k < 3; ++k) {
-            before[k] = carry[k];
-            for (int w = 0; w < wave; ++w) before[k] += wsum[k][w];
+            const unsigned o = __shfl_up(inc[k], s);
+            if (lane >= s) inc[k] += o;
         }
-        if (c < K) {
-            pair_off[c] = before[0] + inc[0] - v[0];
-            item_off0[c] = before[1] + inc[1] - v[1];
-            item_off1[c] = before[2] + inc[2] - v[2];
-        }
-        __syncthreads();
-        if (tid == 1023) {
-#pragma unroll
-            for (int k = 0; k < 3; ++k) carry[k] = before[k] + inc[k];
-        }
-        __syncthreads();
     }
-    if (tid == 0) {
-        pair_off[K] = carry[0];
-        item_off0[K] = carry[1];
-        item_off1[K] = carry[2];
+    if (lane == 63) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) wsum[k][wave] = inc[k];
+    }
+    __syncthreads();
+    unsigned before[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        before[k] = 0;
+        for (int w = 0; w < wave; ++w) before[k] += wsum[k][w];
+    }
+    if (c < K) {
+        pair_off[c] = before[0] + inc[0] - v[0];
+        item_off0[c] = before[1] + inc[1] - v[1];
+        item_off1[c] = before[2] + inc[2] - v[2];
+    }
+    if (tid == IVFS_OFF_NT - 1) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) blk[k * nblk + blockIdx.x] = before[k] + inc[k];
+    }
+}
+
+__global__ __launch_bounds__(IVFS_OFF_NT) void ivfs_offsets_add_kernel(int K, const unsigned *__restrict__ blk,
+                                                                       unsigned *__restrict__ pair_off,
+                                                                       unsigned *__restrict__ item_off0,
+                                                                       unsigned *__restrict__ item_off1)
+{
+    __shared__ unsigned base_s[3], all_s[3];
+    const int tid = threadIdx.x;
+    const int nblk = gridDim.x;
+    if (tid < 3) { base_s[tid] = 0; all_s[tid] = 0; }
+    __syncthreads();
+    for (int b = tid; b < nblk; b += IVFS_OFF_NT) {  // at most 256 workgroups: one round
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const unsigned t = blk[k * nblk + b];
+            if (t) {
+                if (b < (int)blockIdx.x) atomicAdd(&base_s[k], t);
+                atomicAdd(&all_s[k], t);
+            }
+        }
+    }
+    __syncthreads();
+    const int c = blockIdx.x * IVFS_OFF_NT + tid;
+    if (c < K) {
+        pair_off[c] += base_s[0];
+        item_off0[c] += base_s[1];
+        item_off1[c] += base_s[2];
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        pair_off[K] = all_s[0];
+        item_off0[K] = all_s[1];
+        item_off1[K] = all_s[2];
     }
 }
 
@@ -426,8 +449,12 @@ int ivf_shared_scan(int B, const int64_t *list_off, const uint8_t *codes, int64_
     launch(QADC_PROF_SEED, ivfs_zero_kernel, dim3((unsigned)ceil_div(K, 256)), dim3(256), 0, st, pair_cnt, (int64_t)K);
     launch(QADC_PROF_SEED, ivfs_count_kernel, dim3(pgrid), dim3(256), 0, st, probes, nprobe, npairs, K,
            (const char *)scan_ws, ws_stride, pair_cnt, taus, flags);
-    launch(QADC_PROF_SEED, ivfs_offsets_kernel, dim3(1), dim3(1024), 0, st, (const unsigned *)pair_cnt, list_off, K,
-           n_total, 32, min_pairs, pair_off, item_off0, item_off1);
+    const unsigned ogrid = (unsigned)ceil_div(K, IVFS_OFF_NT);
+    unsigned *blk = pair_cnt + (size_t)K + 1;  // (the region of pair_cnt has room for 3 x 256 totals behind it)
+    launch(QADC_PROF_SEED, ivfs_offsets_kernel, dim3(ogrid), dim3(IVFS_OFF_NT), 0, st, (const unsigned *)pair_cnt,
+           list_off, K, n_total, 32, min_pairs, pair_off, item_off0, item_off1, blk);
+    launch(QADC_PROF_SEED, ivfs_offsets_add_kernel, dim3(ogrid), dim3(IVFS_OFF_NT), 0, st, K, (const unsigned *)blk,
+           pair_off, item_off0, item_off1);
     launch(QADC_PROF_SEED, ivfs_place_kernel, dim3(pgrid), dim3(256), 0, st, probes, npairs, K,
            (const unsigned *)pair_off, pair_cnt, pairs);
 #define QADC_IVFS_CASE(B_)                                                                                      \
