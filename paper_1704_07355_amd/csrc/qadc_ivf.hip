@@ -286,8 +286,10 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_few_kernel(
     // smallest image per query: inside the wavefront, then across the two wavefronts of a query
 #pragma unroll
     for (int a = 0; a < QH; ++a) {
+        if (a < nmine) {  // uniform in a wavefront
 #pragma unroll
-        for (int o = 1; o < WAVE; o <<= 1) mn[a] = min(mn[a], (unsigned)__shfl_xor((int)mn[a], o));
+            for (int o = 1; o < WAVE; o <<= 1) mn[a] = min(mn[a], (unsigned)__shfl_xor((int)mn[a], o));
+        }
         if (lane_id() == 0) wmin[tid / WAVE][a] = mn[a];
     }
     __syncthreads();
