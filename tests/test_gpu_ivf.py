@@ -415,3 +415,51 @@ def test_ivf_few_queries_many_cells(Q, O, K):
                                      probes=probes[iq], qluts=qluts[iq].cpu().numpy())
         assert np.array_equal(idx_np(gi)[iq], rep["ids"]), iq
         assert np.array_equal(gd[iq].cpu().numpy(), rep["dist"]), iq
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_ivf_random_shapes(Q, O, seed):
+    """Seeded random indexes and calls: m, d, K, list skew, empty databases, 1 to 650 queries (the kernels
+    of a few queries, of batches, and the shared-list route), nprobe up to 200, R up to 600, init from
+    1 to 2000, both qmin modes.  Every query: the oracle's neighbours on the GPU's cells and tables, and
+    tables within one step of the oracle's own."""
+    import torch
+    rng = np.random.default_rng(seed)
+    for trial in range(20):
+        m = int(rng.choice([8, 16, 32, 64]))
+        dsub = int(rng.choice([1, 2, 3, 4]))
+        d = m * dsub
+        K = int(rng.choice([5, 40, 130, 700, 3000]))
+        n = int(rng.choice([0, 50, 3000, 40000]))
+        nq = int(rng.choice([1, 2, 5, 13, 20, 33, 70, 200, 650]))
+        nprobe = int(min(K, rng.choice([1, 3, 8, 33, 64, 200])))
+        R = int(rng.choice([1, 10, 100, 600]))
+        init = int(rng.choice([1, 30, 300, 2000]))
+        mode = int(rng.integers(0, 2))
+        coarse = rng.uniform(0, 255, size=(K, d)).astype(np.float32)
+        spread = K if rng.random() < 0.7 else max(1, K // 8)   # or: everything in the first eighth of the cells
+        cells = np.sort(rng.integers(0, spread, size=n))
+        list_off = np.zeros(K + 1, dtype=np.int64)
+        np.cumsum(np.bincount(cells, minlength=K), out=list_off[1:])
+        codes = rng.integers(0, 256, size=(n, m // 2), dtype=np.uint8)
+        ids = rng.permutation(n).astype(np.uint32)
+        cb = rng.normal(scale=20, size=(m, 16, dsub)).astype(np.float32)
+        index = dict(list_off=list_off, codes=codes, ids=ids)
+        # (an empty database still needs allocations to point at)
+        g_codes = to_gpu(codes) if n else torch.zeros((1, m // 2), dtype=torch.uint8, device="cuda:0")
+        g_ids = to_gpu(ids.view(np.int32)) if n else torch.zeros((1,), dtype=torch.int32, device="cuda:0")
+        gix = Q.IvfIndex(to_gpu(coarse), to_gpu(list_off), g_codes, g_ids, to_gpu(cb))
+        gix.c.n = n
+        queries = (coarse[rng.integers(0, K, size=nq)] + rng.normal(scale=10, size=(nq, d))).astype(np.float32)
+        case = dict(trial=trial, m=m, d=d, K=K, n=n, nq=nq, nprobe=nprobe, R=R, init=init, mode=mode)
+        gi, gd, probes, qluts = Q.qadc_ivf_search(gix, to_gpu(queries), nprobe, R, init, qmin_mode=mode, debug=True)
+        torch.cuda.synchronize()
+        probes, qluts, gi, gd = probes.cpu().numpy(), qluts.cpu().numpy(), idx_np(gi), gd.cpu().numpy()
+        for iq in range(0, nq, max(1, nq // 12)):
+            rep = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R, qmin_mode=mode,
+                                         probes=probes[iq], qluts=qluts[iq])
+            assert np.array_equal(gi[iq], rep["ids"]), (case, iq)
+            assert np.array_equal(gd[iq], rep["dist"]), (case, iq)
+            own = O.ivf_quick_adc_search(index, coarse, cb, queries[iq], nprobe, init, R, qmin_mode=mode,
+                                         probes=probes[iq])
+            assert np.abs(own["qluts"].astype(int) - qluts[iq].astype(int)).max() <= 1, (case, iq)
