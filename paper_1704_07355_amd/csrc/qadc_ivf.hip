@@ -1473,7 +1473,7 @@ struct IvfPlan {
 };
 
 constexpr int IVF_SHARED_PITCH = MERGE_CAP;   // keys of a query's region: what the merge kernel holds in LDS
-constexpr int IVF_SHARED_MIN_Q = 640;         // smallest batch whose popular lists are scanned once for all (even at 512 on 65536 Zipf lists)
+constexpr int IVF_SHARED_MIN_Q = 384;         // smallest batch whose popular lists are scanned once for all (even at 360 on 65536 Zipf lists)
 constexpr int IVF_SHARED_MAX_R = 128;         // the region must hold a few dozen times R keys
 constexpr int IVF_SHARED_MAX_K = 1 << 18;     // one workgroup sums the per-cell counts
 
@@ -1582,9 +1582,9 @@ int ivf_search(const qadc_ivf_index *ix, const float *queries, int nq, int nprob
                size_t workspace_bytes, hipStream_t st)
 {
     IvfPlan p;
+    if (nq == 0) return QADC_OK;  // nothing asked for, whatever the pointers
     if (!ix || !queries || !out_ids || !out_dist)
         return fail(QADC_EINVAL, "qadc_ivf_search: null pointer");
-    if (nq == 0) return QADC_OK;
     if (!make_ivf_plan(ix, nq, nprobe, R, &p))
         return fail(QADC_EINVAL, "qadc_ivf_search: unsupported nq=%d nprobe=%d R=%d d=%d m=%d K=%d", nq,
                     nprobe, R, ix->d, ix->m, ix->K);

@@ -186,7 +186,7 @@ def test_cells_split_between_the_two_scans(Q, O, monkeypatch, min_pairs):
 
 @pytest.mark.parametrize("m,nprobe,R", [(16, 64, 128), (64, 100, 30)])
 def test_large_batch_takes_the_shared_route_by_itself(Q, O, m, nprobe, R):
-    """700 queries (no knob set: calls of 640 queries and more share lists), most cells probed by most
+    """700 queries (no knob set: calls of 384 queries and more share lists), most cells probed by most
     queries -- many sets of 32 pairs per cell -- with the largest R and nprobe beyond one table chunk of the
     seed kernel; against the oracle and against the same queries sent in calls of 100 (per-query scan)."""
     import torch
