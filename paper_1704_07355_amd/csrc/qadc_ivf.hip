@@ -1495,7 +1495,8 @@ static bool make_ivf_plan(const qadc_ivf_index *ix, int nq, int nprobe, int R, I
     // (13 to 63 queries: 256, measured 0.286 against 0.320 ms at 16 queries, 0.402 against 0.458 at 32)
     int w_def = 16384 / nq;
     if (w_def < 24) w_def = 24;
-    if (w_def > 128) w_def = (nq > IVF_WIDE_MAX_Q && nq < 64) ? 256 : 128;
+    // (up to 4 queries: 192, one query 0.0744 against 0.0780 ms)
+    if (w_def > 128) w_def = (nq > IVF_WIDE_MAX_Q && nq < 64) ? 256 : nq <= 4 ? 192 : 128;
     p->W = knob_or(knobs().ivf_wgs, w_def);
     if (p->W < 1) p->W = 1;
     if (p->W > 4096) p->W = 4096;
