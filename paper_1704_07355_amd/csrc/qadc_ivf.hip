@@ -193,6 +193,35 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_kernel(
 constexpr int IVF_FEW_DK = 128;  // components staged at a time
 constexpr int IVF_FEW_Q = 16;    // queries per workgroup
 
+// acc[a] += sum over the staged components of (y_a - c)^2 for the first NQ queries of a thread: c = the
+// thread's centroid row, ys = its first query's row (rows ld floats apart), four components at a time.
+// (A padded component is 0 - 0: the fused multiply-add leaves the sum as it is.)
+template <int NQ>
+__device__ __forceinline__ void few_walk(const float *c_row, const float *ys, int ld, int dk4, float (&acc)[8])
+{
+    float a[NQ];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) a[i] = acc[i];
+#pragma unroll 2
+    for (int kk = 0; kk < 4 * dk4; kk += 4) {
+        const float4 c = *reinterpret_cast<const float4 *>(c_row + kk);
+#pragma unroll
+        for (int i = 0; i < NQ; ++i) {
+            const float4 y = *reinterpret_cast<const float4 *>(ys + i * ld + kk);
+            float df = y.x - c.x;
+            a[i] = fmaf(df, df, a[i]);
+            df = y.y - c.y;
+            a[i] = fmaf(df, df, a[i]);
+            df = y.z - c.z;
+            a[i] = fmaf(df, df, a[i]);
+            df = y.w - c.w;
+            a[i] = fmaf(df, df, a[i]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) acc[i] = a[i];
+}
+
 __global__ __launch_bounds__(256) void ivf_coarse_dist_few_kernel(
     const float *__restrict__ coarse, int K, int d, const float *__restrict__ queries, int nq,
     float *__restrict__ dist, unsigned *__restrict__ blockmin, int nblk, int vec4)
@@ -252,24 +281,16 @@ __global__ __launch_bounds__(256) void ivf_coarse_dist_few_kernel(
         }
         __syncthreads();
         if (nmine <= 0) continue;  // uniform in a wavefront: no query for it
-        // (a padded component is 0 - 0: the fused multiply-add leaves the sum as it is)
-#pragma unroll 2
-        for (int kk = 0; kk < 4 * dk4; kk += 4) {
-            const float4 c = *reinterpret_cast<const float4 *>(&cs[cell][kk]);
-#pragma unroll
-            for (int a = 0; a < QH; ++a) {
-                if (a < nmine) {  // uniform
-                    const float4 y = *reinterpret_cast<const float4 *>(&ys[qh + a][kk]);
-                    float df = y.x - c.x;
-                    acc[a] = fmaf(df, df, acc[a]);
-                    df = y.y - c.y;
-                    acc[a] = fmaf(df, df, acc[a]);
-                    df = y.z - c.z;
-                    acc[a] = fmaf(df, df, acc[a]);
-                    df = y.w - c.w;
-                    acc[a] = fmaf(df, df, acc[a]);
-                }
-            }
+        // the walk, compiled for every number of queries a thread can have (no test per query inside)
+        switch (nmine) {
+        case 1: few_walk<1>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
+        case 2: few_walk<2>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
+        case 3: few_walk<3>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
+        case 4: few_walk<4>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
+        case 5: few_walk<5>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
+        case 6: few_walk<6>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
+        case 7: few_walk<7>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
+        default: few_walk<8>(&cs[cell][0], &ys[qh][0], IVF_FEW_DK + 4, dk4, acc); break;
         }
     }
     const int c = c0 + cell;
